@@ -1,0 +1,362 @@
+"""Pins for the float64 oracle: each test checks it against something other
+than itself -- hand-worked numbers, closed forms, library routines used in a
+different way, brute force on tiny sizes, or invariants the paper proves."""
+import os
+
+import numpy as np
+import pytest
+import scipy.optimize
+
+from oracle import squat_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            yield [p.strip() for p in line.split("|")]
+
+
+# ----------------------------------------------------------------- quantizer
+def test_rtn_hand_worked_cases():
+    """Section 2 formulas, worked by hand (tests/golden/rtn_worked.txt)."""
+    for bits, xs, dl, m, cs, dq in _rows("rtn_worked.txt"):
+        x = np.array([float(v) for v in xs.split()])
+        codes, scale, zero, xhat = O.rtn_group(x, int(bits))
+        assert float(scale[0]) == float(dl)
+        assert float(zero[0]) == float(m)
+        assert codes.tolist() == [int(v) for v in cs.split()]
+        assert xhat.tolist() == [float(v) for v in dq.split()]
+
+
+def test_packed_size_matches_paper_kv_size():
+    """Tables 1-2: the format's own share is the lower bound of the printed KV sizes."""
+    for bits, group, frac, printed in _rows("kv_size.txt"):
+        bits, group = int(bits), int(group)
+        d = 128
+        codes = np.zeros((1, d), dtype=np.uint8)
+        words = O.pack_codes(codes, bits)
+        nbytes = words.nbytes + 2 * 2 * (d // group)
+        assert nbytes / (2 * d) == float(frac)
+        assert float(frac) <= float(printed)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_rtn_properties(bits):
+    gen = np.random.default_rng(1)
+    x = gen.standard_normal((200, 32)) * gen.uniform(0.01, 50, size=(200, 1))
+    codes, scale, zero, xhat = O.rtn_group(x, bits, axis=1)
+    L = (1 << bits) - 1
+    assert codes.min() == 0 and codes.max() == L
+    s = scale.astype(np.float64)
+    # every element within half a step of its reconstruction, plus the slack the
+    # fp16 rounding of zero/scale can add at the clamped ends
+    slack = np.abs(zero.astype(np.float64)) * 2.0 ** -11 + L * s * 2.0 ** -11
+    assert np.all(np.abs(xhat - x) <= 0.5 * s + slack + 1e-12)
+    # min and max land on the extreme codes
+    assert np.all(codes[np.arange(200), x.argmin(1)] == 0)
+    assert np.all(codes[np.arange(200), x.argmax(1)] == L)
+
+
+@pytest.mark.parametrize("bits,G,g", [(2, 32, 32), (4, 32, 64), (2, 128, 32), (4, 64, 128), (2, 32, 128)])
+def test_r0_reduces_to_plain_rtn(bits, G, g):
+    """Section 3.3: lambda = 0 (or r = 0) is a compression-based quantizer, i.e.
+    independent per-group round-to-nearest of the ORIGINAL key."""
+    gen = np.random.default_rng(2)
+    K = gen.standard_normal((64, 128)) * 3
+    d = 128
+    for U in (None, np.zeros((d, d)), O.update_matrix_lowrank(gen.standard_normal((5, d)), 0.0, g)):
+        out = O.quantize_keys(K, U, bits, G, g)
+        c, s, z, xh = O.rtn_group(K.reshape(64, d // G, G), bits, axis=2)
+        assert np.array_equal(out["codes"], c.reshape(64, d))
+        assert np.array_equal(out["scale"], s.reshape(64, d // G))
+        assert np.array_equal(out["zero"], z.reshape(64, d // G))
+        assert np.array_equal(out["xhat"], xh.reshape(64, d))
+
+
+def test_channel_axis_r0_is_per_channel_rtn():
+    gen = np.random.default_rng(3)
+    K = gen.standard_normal((96, 64))
+    out = O.quantize_keys(K, None, 2, 32, 32, axis="channel")
+    for blk in range(3):
+        for ch in range(64):
+            c, s, z, xh = O.rtn_group(K[blk * 32:(blk + 1) * 32, ch], 2)
+            assert np.array_equal(out["codes"][blk * 32:(blk + 1) * 32, ch], c)
+            assert out["scale"][blk, ch] == s[0] and out["zero"][blk, ch] == z[0]
+
+
+def test_pack_unpack_roundtrip_and_layout():
+    gen = np.random.default_rng(4)
+    for bits in (2, 4):
+        codes = gen.integers(0, 1 << bits, size=(7, 128)).astype(np.uint8)
+        w = O.pack_codes(codes, bits)
+        assert w.shape == (7, 128 * bits // 32) and w.dtype == np.uint32
+        assert np.array_equal(O.unpack_codes(w, bits), codes)
+    one = np.zeros((1, 128), dtype=np.uint8)
+    one[0, 17] = 3
+    w = O.pack_codes(one, 2)
+    assert w[0, 1] == (3 << 2) and w.sum() == (3 << 2)
+    one[0, 17] = 0
+    one[0, 9] = 5
+    w = O.pack_codes(one, 4)
+    assert w[0, 1] == (5 << 4)
+
+
+def test_dequantize_is_the_definition():
+    gen = np.random.default_rng(5)
+    K = gen.standard_normal((16, 128))
+    Qh = gen.standard_normal((4, 128))
+    U = O.update_matrix_lowrank(Qh, 0.05, 32)
+    out = O.quantize_keys(K, U, 2, 32, 32)
+    back = O.dequantize_keys(out["codes"], out["scale"], out["zero"], 32)
+    assert np.array_equal(back, out["xhat"])
+    # element by element, written out
+    for i in (0, 7):
+        for c in (0, 31, 32, 127):
+            exp = float(out["codes"][i, c]) * float(out["scale"][i, c // 32]) + float(out["zero"][i, c // 32])
+            assert back[i, c] == exp
+
+
+# -------------------------------------------------------------- update matrix
+@pytest.mark.parametrize("d,g,r,lam", [(16, 4, 3, 0.7), (24, 8, 5, 0.01), (12, 1, 2, 2.0), (128, 32, 16, 1e-3), (128, 64, 40, 5e-4)])
+def test_three_routes_agree(d, g, r, lam):
+    gen = np.random.default_rng(10 + d)
+    Qh = gen.standard_normal((r, d)) * (30.0 if d == 128 else 1.0)
+    U1 = O.update_matrix_lemma(Qh, lam, g)
+    U2 = O.update_matrix_kkt(Qh, lam, g)
+    U3 = O.update_matrix_lowrank(Qh, lam, g)
+    sc = max(1.0, np.abs(U2).max())
+    assert np.abs(U1 - U2).max() <= 1e-9 * sc
+    assert np.abs(U3 - U2).max() <= 1e-9 * sc
+    # strictly block lower triangular
+    for t in range(d // g):
+        assert not U1[t * g:(t + 1) * g, t * g:].any()
+
+
+def test_update_matrix_is_the_constrained_minimiser_brute_force():
+    """Lemma 2 on tiny d: a generic least-squares routine and a generic
+    numerical optimiser both land on the same tail as B_t H_t d."""
+    d, g, r, lam = 8, 2, 3, 1.3
+    gen = np.random.default_rng(20)
+    Qh = gen.standard_normal((r, d))
+    U = O.update_matrix_lemma(Qh, lam, g)
+    Mst = np.vstack([np.eye(d), np.sqrt(lam) * Qh])     # ||M delta||^2 = delta^T P delta
+    for t in range(1, d // g):
+        dvec = gen.standard_normal(g)
+        b = np.zeros(t * g)
+        b[-g:] = dvec
+        tail_ls = np.linalg.lstsq(Mst[:, t * g:], -Mst[:, :t * g] @ b, rcond=None)[0]
+        mine = U[t * g:, (t - 1) * g:t * g] @ dvec
+        assert np.allclose(mine, tail_ls, atol=1e-11)
+
+        def obj(z):
+            dl = np.concatenate([b, z])
+            return dl @ dl + lam * np.sum((Qh @ dl) ** 2)
+        res = scipy.optimize.minimize(obj, np.zeros(d - t * g), method="BFGS", options={"gtol": 1e-10})
+        assert np.allclose(mine, res.x, atol=1e-5)
+        # no random perturbation does better
+        f0 = obj(mine)
+        for _ in range(50):
+            assert obj(mine + 1e-3 * gen.standard_normal(d - t * g)) >= f0 - 1e-13
+
+
+def test_g1_matches_one_coordinate_rule():
+    """Prop. 1 is Lemma 2 at g = 1; the same tail also follows from the classic
+    single-coordinate compensation on the trailing block of P (invert
+    P[t-1:, t-1:], take its first column over its first entry)."""
+    d, r, lam = 10, 3, 0.9
+    gen = np.random.default_rng(21)
+    Qh = gen.standard_normal((r, d))
+    P = np.eye(d) + lam * Qh.T @ Qh
+    P_inv = np.linalg.inv(P)
+    U = O.update_matrix_lemma(Qh, lam, 1)
+    for t in range(1, d):
+        # Prop. 1 literally: B_t h_t with A_t the leading t x t block of P_inv
+        A_t = P_inv[:t, :t]
+        h_t = np.linalg.inv(A_t)[:, -1]
+        B_t = P_inv[t:, :t]
+        assert np.allclose(U[t:, t - 1], B_t @ h_t, atol=1e-11)
+        # classic one-coordinate compensation on the trailing problem: pinning
+        # coordinate 0 to e moves the others by e * Hinv[1:, 0] / Hinv[0, 0]
+        Hinv = np.linalg.inv(P[t - 1:, t - 1:])
+        assert np.allclose(U[t:, t - 1], Hinv[1:, 0] / Hinv[0, 0], atol=1e-11)
+
+
+def test_lambda_zero_and_rank_zero_give_zero_matrix():
+    gen = np.random.default_rng(22)
+    Qh = gen.standard_normal((4, 32))
+    assert not O.update_matrix_lemma(Qh, 0.0, 8).any()
+    assert not O.update_matrix_lowrank(Qh, 0.0, 8).any()
+    assert not O.update_matrix_lowrank(np.zeros((0, 32)), 1.0, 8).any()
+    assert not O.update_matrix_lemma(np.zeros((3, 32)), 1.0, 8).any()
+
+
+def test_hard_constraint_is_the_large_lambda_limit():
+    d, g, r = 16, 4, 3
+    gen = np.random.default_rng(23)
+    Qh = gen.standard_normal((r, d))
+    Uh = O.update_matrix_lowrank(Qh, np.inf, g)
+    Ub = O.update_matrix_kkt(Qh, 1e9, g)
+    assert np.abs(Uh - Ub).max() < 1e-5
+    # each panel annihilates the subspace component of the frozen block's error
+    for t in range(1, d // g):
+        blk = slice((t - 1) * g, t * g)
+        assert np.allclose(Qh[:, blk] + Qh[:, t * g:] @ Uh[t * g:, blk], 0, atol=1e-12)
+
+
+# ------------------------------------------------------------- the iteration
+def _setup(d=128, r=8, n=48, seed=30, qscale=20.0):
+    gen = np.random.default_rng(seed)
+    Qh = gen.standard_normal((r, d)) * qscale
+    K = gen.standard_normal((n, d)) * 2
+    K[:, gen.choice(d, 4, replace=False)] *= 10
+    return Qh, K
+
+
+@pytest.mark.parametrize("bits,G,g,lam", [(2, 32, 32, 1e-3), (4, 32, 64, 5e-4), (2, 64, 32, 1e-2), (2, 32, 32, np.inf)])
+def test_each_step_is_lemma2_optimum_generic_solver(bits, G, g, lam):
+    """Re-run the iteration with (a) the scalar quantizer applied to the current
+    block and (b) the tail recomputed by a generic least-squares solve of
+    Lemma 2's problem, and compare with quantize_keys driven by U."""
+    d = 128
+    Qh, K = _setup(d=d, n=6)
+    U = O.update_matrix_lowrank(Qh, lam, g)
+    out = O.quantize_keys(K, U, bits, G, g, trace=True)
+    L = (1 << bits) - 1
+    if np.isinf(lam):
+        Mst = None
+    else:
+        Mst = np.vstack([np.eye(d), np.sqrt(lam) * Qh])
+    for i in range(K.shape[0]):
+        x = K[i].copy()
+        meta = {}
+        for t in range(d // g):
+            lo, hi = t * g, (t + 1) * g
+            if lo % G == 0:
+                for gi in range(lo // G, lo // G + max(1, g // G)):
+                    seg = x[gi * G:(gi + 1) * G]
+                    meta[gi] = (np.float64(np.float16((seg.max() - seg.min()) / L)), np.float64(np.float16(seg.min())))
+            xq = np.empty(g)
+            for j in range(lo, hi):
+                dl, m = meta[j // G]
+                c = 0.0 if dl == 0 else min(max(np.rint((x[j] - m) / dl), 0), L)
+                assert out["codes"][i, j] == c
+                xq[j - lo] = c * dl + m
+            dvec = xq - x[lo:hi]
+            x[lo:hi] = xq
+            if t < d // g - 1:
+                if Mst is not None:
+                    tail = np.linalg.lstsq(Mst[:, hi:], -Mst[:, lo:hi] @ dvec, rcond=None)[0]
+                else:
+                    # hard constraint: min ||tail|| s.t. Qh[:, hi:] tail = -Qh[:, blk] dvec
+                    tail = np.linalg.lstsq(Qh[:, hi:], -Qh[:, lo:hi] @ dvec, rcond=None)[0]
+                x[hi:] += tail
+            assert np.allclose(x, out["states"][t][i], atol=1e-9)
+        assert np.allclose(x, out["xhat"][i], atol=1e-9)
+
+
+@pytest.mark.parametrize("g", [32, 64])
+def test_soft_invariant_first_order_condition(g):
+    """After the update of step t the accumulated change delta = state - k
+    satisfies (P delta)[t g:] = 0 (stationarity of Lemma 2 accumulated)."""
+    Qh, K = _setup()
+    lam = 1e-3
+    U = O.update_matrix_lemma(Qh, lam, g)
+    out = O.quantize_keys(K, U, 2, 32, g, trace=True)
+    P = np.eye(128) + lam * Qh.T @ Qh
+    T = 128 // g
+    for t in range(T - 1):
+        delta = out["states"][t] - K
+        resid = (delta @ P)[:, (t + 1) * g:]
+        assert np.abs(resid).max() <= 1e-9 * np.abs(delta @ P).max()
+
+
+def test_hard_invariant_error_orthogonal_until_last_block():
+    """lambda = +inf: Qhat (state - k) = 0 after every step but the last, so the
+    final error's projection is exactly the last block's own rounding error."""
+    Qh, K = _setup(r=8)
+    g = 32
+    U = O.update_matrix_lowrank(Qh, np.inf, g)
+    out = O.quantize_keys(K, U, 2, 32, g, trace=True)
+    scale = np.abs(Qh).max() * np.abs(K).max()
+    for t in range(3):
+        assert np.abs((out["states"][t] - K) @ Qh.T).max() <= 1e-12 * scale
+    e_last = out["xhat"][:, 96:] - out["states"][2][:, 96:]
+    lhs = (out["xhat"] - K) @ Qh.T
+    rhs = e_last @ Qh[:, 96:].T
+    assert np.abs(lhs - rhs).max() <= 1e-12 * scale
+    # and SQuat's projected error beats plain RTN's on average (Figure 2's claim)
+    rtn = O.quantize_keys(K, None, 2, 32, g)
+    assert np.mean(lhs ** 2) < np.mean(((rtn["xhat"] - K) @ Qh.T) ** 2)
+
+
+def test_replay_classifier_accepts_itself_and_flags_a_planted_error():
+    Qh, K = _setup(n=32)
+    U = O.update_matrix_lowrank(Qh, 1e-3, 32)
+    out = O.quantize_keys(K, U, 2, 32, 32)
+    rep = O.replay_classify(K, U, 2, 32, 32, out["codes"], out["scale"], out["zero"])
+    assert rep["code_diff"] == 0 and rep["meta_diff"] == 0
+    bad = out["codes"].copy()
+    bad[3, 100] = (bad[3, 100] + 1) % 4          # last block: nothing downstream
+    rep = O.replay_classify(K, U, 2, 32, 32, bad, out["scale"], out["zero"])
+    assert rep["code_diff"] == 1 and rep["code_unexplained"] == 1
+    bad[3, 5] = (bad[3, 5] + 1) % 4              # first block: later codes no longer follow
+    rep = O.replay_classify(K, U, 2, 32, 32, bad, out["scale"], out["zero"])
+    assert rep["code_unexplained"] >= 2
+    # a sign error in the propagation is caught as unexplained disagreements
+    wrong = O.quantize_keys(K, -U, 2, 32, 32)
+    rep = O.replay_classify(K, U, 2, 32, 32, wrong["codes"], wrong["scale"], wrong["zero"])
+    assert rep["code_unexplained"] + rep["meta_unexplained"] > 0
+
+
+# ------------------------------------------------------------------ subspace
+def test_subspace_matches_library_svd():
+    gen = np.random.default_rng(40)
+    Q = gen.standard_normal((4, 300, 64)) * np.linspace(3, 0.2, 64)
+    A, ea = O.subspace(Q, 10)
+    B, eb = O.subspace_svd(Q, 10)
+    assert np.allclose(ea, eb, rtol=1e-10)
+    assert np.allclose(A, B, atol=1e-7 * np.abs(B).max())
+
+
+def test_subspace_planted_spectrum():
+    """Q = A diag(s) B^T with orthonormal B: Qhat^T Qhat must equal
+    B_r diag(s_r^2 * colnorm) B_r^T; with orthonormal A it is B_r diag(s_r^2) B_r^T."""
+    gen = np.random.default_rng(41)
+    n, d, r = 200, 32, 5
+    A, _ = np.linalg.qr(gen.standard_normal((n, d)))
+    B, _ = np.linalg.qr(gen.standard_normal((d, d)))
+    s = np.linspace(10, 1, d)
+    Q = (A * s) @ B.T
+    Qh, eig = O.subspace(Q, r)
+    assert np.allclose(eig, s[:r] ** 2, rtol=1e-10)
+    assert np.allclose(Qh.T @ Qh, (B[:, :r] * s[:r] ** 2) @ B[:, :r].T, atol=1e-9)
+    for i in range(r):
+        assert np.isclose(abs(Qh[i] @ B[:, i]), s[i], rtol=1e-10)
+
+
+def test_deviation_eckart_young():
+    """Definition 1 summed over the rows equals the tail of the spectrum."""
+    gen = np.random.default_rng(42)
+    Q = gen.standard_normal((150, 24)) * np.linspace(4, 0.5, 24)
+    r = 6
+    Qh, _ = O.subspace(Q, r)
+    dev = O.deviation_from_subspace(Q, Qh)
+    s = np.linalg.svd(Q, compute_uv=False)
+    assert np.isclose(np.sum(dev ** 2), np.sum(s[r:] ** 2), rtol=1e-10)
+
+
+def test_gqa_pooling_is_sum_of_grams():
+    gen = np.random.default_rng(43)
+    Q = gen.standard_normal((4, 50, 16))
+    assert np.allclose(O.gram(Q), sum(Q[h].T @ Q[h] for h in range(4)), atol=1e-10)
+    assert np.allclose(O.gram(Q), O.gram([Q[0], Q[1], Q[2], Q[3]]), atol=1e-10)
+
+
+def test_rank_deficient_queries_give_zero_rows():
+    gen = np.random.default_rng(44)
+    Q = gen.standard_normal((3, 16))
+    Qh, eig = O.subspace(Q, 6)
+    assert np.allclose(Qh[3:], 0, atol=1e-6) and np.all(eig[:3] > 0)
