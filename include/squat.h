@@ -1,0 +1,180 @@
+/*
+ * squat.h -- C ABI of the MI355X (gfx950) implementation of the SQuat
+ * key-quantization path (arxiv 2503.24358, "SQuat: Subspace-orthogonal KV
+ * Cache Quantization").
+ *
+ * Four calls cover the path, in the order Algorithm 1 uses them:
+ *
+ *   squat_build_subspace   prompt queries -> Qhat            (Section 3.2)
+ *   squat_prepare          Qhat, lambda, g -> update matrix  (Lemma 2, Lemma 3)
+ *   squat_quantize_keys    keys, update matrix -> codes      (Algorithm 1, Quant)
+ *   squat_dequantize_keys  codes -> keys                     (Section 2, deq)
+ *
+ * Conventions that hold for every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller, valid on the
+ *     device that is current when the call is made.  Only `ws` buffers are
+ *     scratch; everything else is either read-only input or fully overwritten
+ *     output.  Inputs and outputs must not alias.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  The calls never synchronise, never allocate or
+ *     free device memory and keep no state between calls, so they may be used
+ *     from several host threads on different streams.  Buffers must stay alive
+ *     until the stream has passed the enqueued work.
+ *   - Arguments are validated on the host BEFORE anything is launched.  The
+ *     return value is SQUAT_OK (0) or a negative squat_status; on error nothing
+ *     was enqueued.  squat_strerror() names a status.
+ *   - Row-major tensors; strides are given in ELEMENTS of the tensor's dtype.
+ *   - Head size d must be 128 in this version.  "Heads" are independent
+ *     problems: several layers may be stacked along the head axis in one call.
+ */
+#ifndef SQUAT_H
+#define SQUAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum squat_dtype {
+    SQUAT_F32 = 0,   /* IEEE binary32 */
+    SQUAT_F16 = 1,   /* IEEE binary16 */
+    SQUAT_BF16 = 2   /* bfloat16 */
+} squat_dtype;
+
+typedef enum squat_status {
+    SQUAT_OK = 0,
+    SQUAT_E_NULLPTR = -1,   /* a required pointer is NULL */
+    SQUAT_E_BADSHAPE = -2,  /* unsupported d, r, g, G, bits, negative sizes, bad strides */
+    SQUAT_E_BADDTYPE = -3,  /* dtype not one of squat_dtype / not allowed for this tensor */
+    SQUAT_E_ALIGN = -4,     /* pointer or stride breaks the stated alignment */
+    SQUAT_E_WORKSPACE = -5, /* ws is NULL or ws_bytes too small */
+    SQUAT_E_HIP = -6,       /* the HIP runtime refused a launch (hipGetLastError) */
+    SQUAT_E_BADVALUE = -7   /* lambda negative or NaN */
+} squat_status;
+
+typedef void* squat_stream; /* hipStream_t */
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int squat_version(void);
+
+/* Static, human-readable name of a status code (never NULL). */
+const char* squat_strerror(int status);
+
+/* ------------------------------------------------------------------------- *
+ * squat_build_subspace  (Section 3.2, last paragraph; Algorithm 1, the SVD
+ * line and the line defining Qhat; GQA pooling: appendix "Details of Our Main
+ * Algorithm").
+ *
+ * For every KV head j, pools the prompt queries of its q_per_kv query heads
+ * (query heads j*q_per_kv .. (j+1)*q_per_kv-1) row-wise, forms their Gram
+ * matrix Q^T Q, takes its r largest eigenpairs (eig_i, v_i) and writes
+ *     qhat[j, i, :] = sqrt(eig_i) * v_i,       i = 0..r-1, descending eig,
+ * i.e. the top-r right singular vectors of the pooled queries scaled by their
+ * singular values.  Each row's sign is fixed so that its largest-magnitude
+ * component is positive.  Eigenvalues that are zero (r > rank) give zero rows.
+ *
+ *   q       [n_kv_heads*q_per_kv, n_tokens, d] dtype q_dt, element (h,t,c) at
+ *           q[h*q_stride_head + t*q_stride_token + c]; base pointer 16-byte
+ *           aligned, both strides multiples of 8 elements.
+ *   qhat    out [n_kv_heads, r, d] float, dense.  May be NULL only if r == 0.
+ *   eig     out [n_kv_heads, r] float, eigenvalues of Q^T Q (squared singular
+ *           values), descending.  May be NULL.
+ *   gram    out [n_kv_heads, d, d] float, the pooled Gram matrix.  May be NULL.
+ *   ws      scratch of at least squat_build_subspace_workspace(...) bytes,
+ *           256-byte aligned.
+ *   0 <= r <= d.  n_tokens >= 1.  The Gram products are exact for bf16/f16
+ *   inputs and accumulate in fp32 within a slab of tokens, fp64 across slabs;
+ *   the eigen-solver (cyclic one-sided Jacobi) works in fp64.
+ * ------------------------------------------------------------------------- */
+size_t squat_build_subspace_workspace(int64_t n_tokens, int n_kv_heads, int q_per_kv, int d, int r);
+
+int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads,
+                         int q_per_kv, int d, int64_t q_stride_head, int64_t q_stride_token,
+                         int r, float* qhat, float* eig, float* gram,
+                         void* ws, size_t ws_bytes, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_prepare  (Lemma 2: the block update B_t H_t; Lemma 3 and its Remark:
+ * the A_t^{-1} chain; Prop. 1 is the g = 1 case).
+ *
+ * For every head writes the d x d matrix U, row-major, with
+ *     U[t*g : d, (t-1)*g : t*g] = B_t H_t          for t = 1 .. d/g - 1
+ * and zeros everywhere else, where P_inv = (I + lambda Qhat^T Qhat)^{-1},
+ * A_t is its leading (t g x t g) block, B_t the block below it and H_t the
+ * last g columns of A_t^{-1}.  The kernel evaluates the equivalent rank-r
+ * form  -Qr^T (I/lambda + Qr Qr^T)^{-1} Qb  (Qb, Qr: the columns of Qhat in
+ * and after block t) in fp64.  lambda = +INFINITY selects the limit
+ * -pinv(Qr) Qb (the equality constraint of Eq. (1)); lambda = 0 or r = 0
+ * gives U = 0 (plain round-to-nearest).
+ *
+ *   qhat    [n_heads, r, d] float, dense (NULL allowed only if r == 0).
+ *   update  out [n_heads, d, d] float, dense, 16-byte aligned.
+ *   g       32, 64 or 128 (g = 128 = d means a single block: U = 0).
+ *   ws      scratch of at least squat_prepare_workspace(...) bytes, 256-byte
+ *           aligned.
+ * ------------------------------------------------------------------------- */
+size_t squat_prepare_workspace(int n_heads, int d, int r, int g);
+
+int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, int g,
+                  float* update, void* ws, size_t ws_bytes, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_quantize_keys  (Section 2 "Quantization": qtz/deq; Algorithm 1,
+ * function Quant; Lemma 2, the update of the not-yet-quantized elements).
+ *
+ * For every key vector k (one token of one head of one batch entry) runs, on a
+ * working copy in fp32: for t = 1 .. d/g, quantize the g channels of block t
+ * from their CURRENT values with asymmetric min/max b-bit round-to-nearest
+ * (per token, over groups of `group` consecutive channels; scale and zero are
+ * rounded to fp16 before they are used, ties round to even, codes are clamped
+ * to [0, 2^b-1], a constant group has scale 0 and codes 0), freeze them at
+ * their dequantized values, and if t < d/g add  U[t g:, block] * (deq - current)
+ * to the remaining channels.  update == NULL is plain round-to-nearest.
+ * When group > g the statistics of a group are taken once, when its first
+ * block is reached.
+ *
+ *   k        [n_batch, n_heads, n_tokens, d] dtype k_dt; element (b,h,t,c) at
+ *            k[b*k_stride_batch + h*k_stride_head + t*k_stride_token + c];
+ *            base 16-byte aligned, strides multiples of 8 elements.  Not
+ *            modified.
+ *   update   [n_heads, d, d] float as written by squat_prepare (same g), or
+ *            NULL.  update_stride_batch (elements) is added per batch entry;
+ *            0 shares one matrix per head across the batch (the paper's
+ *            batch > 1 rule).
+ *   bits     2 or 4.   group  32, 64 or 128.   g  32, 64 or 128; group must
+ *            divide g or g must divide group.
+ *   codes    out [n_batch, n_heads, n_tokens, d*bits/32] uint32, dense,
+ *            16-byte aligned.  Channel c of a key is in word c / (32/bits) at
+ *            bit offset bits * (c mod 32/bits).
+ *   scale    out [n_batch, n_heads, n_tokens, d/group] fp16 bit patterns.
+ *   zero     out, same shape: the (real-valued) zero-point m.
+ *   n_tokens may be any value >= 0 (0: nothing is launched).
+ * ------------------------------------------------------------------------- */
+int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
+                        int64_t n_tokens, int d, int64_t k_stride_batch, int64_t k_stride_head,
+                        int64_t k_stride_token, const float* update, int64_t update_stride_batch,
+                        int bits, int group, int g, uint32_t* codes, uint16_t* scale,
+                        uint16_t* zero, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_dequantize_keys  (Section 2: deq(c) = c * Delta + m).
+ *
+ * Inverse of the storage format above: k_out[b,h,t,c] = code * scale + zero
+ * of the group of channel c, computed in fp32 (one fused multiply-add) and
+ * rounded once to out_dt.
+ *
+ *   codes, scale, zero   as written by squat_quantize_keys (dense).
+ *   k_out   [n_batch, n_heads, n_tokens, d] dtype out_dt with strides in
+ *           elements (multiples of 8, base 16-byte aligned).
+ * ------------------------------------------------------------------------- */
+int squat_dequantize_keys(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                          int64_t n_batch, int n_heads, int64_t n_tokens, int d, int bits,
+                          int group, void* k_out, squat_dtype out_dt, int64_t o_stride_batch,
+                          int64_t o_stride_head, int64_t o_stride_token, squat_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQUAT_H */

@@ -1,0 +1,156 @@
+// squat_dequantize_keys: deq(c) = c * Delta + m (Section 2 of the paper) over the
+// packed store written by squat_quantize_keys.  Pure streaming: one thread turns
+// 16 channels of one key (one or two packed words, one scale, one zero) into 16
+// output elements; a wavefront covers 8 consecutive keys, so code reads are one
+// contiguous 256/512-byte run and output writes one contiguous 2/4-KB run.
+#include "squat_internal.h"
+
+using namespace squat;
+
+namespace {
+
+struct DeqParams {
+    const uint32_t* codes;
+    const uint16_t* scale;
+    const uint16_t* zero;
+    unsigned char* out;
+    int64_t ob, oh, ot;      // output strides in BYTES
+    int64_t n_tokens;
+    int n_heads;
+};
+
+template <int DT>
+__device__ __forceinline__ void store16(unsigned char* dst, const float* v) {
+    if constexpr (DT == SQUAT_F32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<f32x4*>(dst + 16 * i) = f32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]};
+    } else {
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (DT == SQUAT_F16) {
+                half2v h;
+                h[0] = static_cast<_Float16>(v[2 * i]);
+                h[1] = static_cast<_Float16>(v[2 * i + 1]);
+                w[i] = __builtin_bit_cast(uint32_t, h);
+            } else {
+                // fp32 -> bf16, round to nearest even
+                uint32_t a = as_u32(v[2 * i]), b = as_u32(v[2 * i + 1]);
+                a = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
+                b = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+                w[i] = a | b;
+            }
+        }
+        *reinterpret_cast<u32x4*>(dst) = u32x4{w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<u32x4*>(dst + 16) = u32x4{w[4], w[5], w[6], w[7]};
+    }
+}
+
+// grid: x over (token, 16-channel chunk), y/z over (batch, head)
+template <int BITS, int GROUP, int DT>
+__global__ void __launch_bounds__(256) dequantize_kernel(const DeqParams p) {
+    constexpr int ES = (DT == SQUAT_F32) ? 4 : 2;
+    constexpr int WPK = kD * BITS / 32;       // words per key
+    constexpr int NG = kD / GROUP;            // groups per key
+    constexpr int WPC = BITS / 2;             // words per 16-channel chunk
+    const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
+    const int64_t flat = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t tok = flat >> 3;
+    const int chunk = static_cast<int>(flat & 7);
+    if (tok >= p.n_tokens) return;
+    const int64_t b = bh / p.n_heads;
+    const int64_t h = bh - b * p.n_heads;
+    const int64_t row = bh * p.n_tokens + tok;
+
+    uint32_t w[WPC];
+    if constexpr (WPC == 1) {
+        w[0] = p.codes[row * WPK + chunk];
+    } else {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(p.codes + row * WPK + 2 * chunk);
+        w[0] = v[0];
+        w[1] = v[1];
+    }
+    const int gi = chunk * 16 / GROUP;
+    const float sc = static_cast<float>(__builtin_bit_cast(_Float16, p.scale[row * NG + gi]));
+    const float zp = static_cast<float>(__builtin_bit_cast(_Float16, p.zero[row * NG + gi]));
+
+    float v[16];
+    constexpr int IPW = 32 / BITS;
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t c = (w[i / IPW] >> (BITS * (i % IPW))) & MASK;
+        v[i] = fmaf(static_cast<float>(c), sc, zp);
+    }
+    unsigned char* dst = p.out + b * p.ob + h * p.oh + tok * p.ot + chunk * 16 * ES;
+    store16<DT>(dst, v);
+}
+
+template <int BITS, int GROUP>
+int launch_dt(squat_dtype dt, const DeqParams& p, dim3 grid, hipStream_t s) {
+    switch (dt) {
+        case SQUAT_F32: hipLaunchKernelGGL((dequantize_kernel<BITS, GROUP, SQUAT_F32>), grid, dim3(256), 0, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL((dequantize_kernel<BITS, GROUP, SQUAT_F16>), grid, dim3(256), 0, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((dequantize_kernel<BITS, GROUP, SQUAT_BF16>), grid, dim3(256), 0, s, p); break;
+        default: return SQUAT_E_BADDTYPE;
+    }
+    return check_launch();
+}
+
+template <int BITS>
+int launch_group(int group, squat_dtype dt, const DeqParams& p, dim3 grid, hipStream_t s) {
+    switch (group) {
+        case 32: return launch_dt<BITS, 32>(dt, p, grid, s);
+        case 64: return launch_dt<BITS, 64>(dt, p, grid, s);
+        case 128: return launch_dt<BITS, 128>(dt, p, grid, s);
+    }
+    return SQUAT_E_BADSHAPE;
+}
+
+}  // namespace
+
+extern "C" int squat_dequantize_keys(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                     int64_t n_batch, int n_heads, int64_t n_tokens, int d, int bits,
+                                     int group, void* k_out, squat_dtype out_dt, int64_t o_stride_batch,
+                                     int64_t o_stride_head, int64_t o_stride_token, squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_heads < 0 || n_tokens < 0) return SQUAT_E_BADSHAPE;
+    if (out_dt != SQUAT_F32 && out_dt != SQUAT_F16 && out_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_batch == 0 || n_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!codes || !scale || !zero || !k_out) return SQUAT_E_NULLPTR;
+    if (o_stride_token < d || o_stride_batch < 0 || o_stride_head < 0) return SQUAT_E_BADSHAPE;
+    if ((o_stride_token % 8) || (o_stride_head % 8) || (o_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(k_out, 16) || !aligned(codes, 16) || !aligned(scale, 2) || !aligned(zero, 2)) return SQUAT_E_ALIGN;
+
+    const int es = elem_size(out_dt);
+    DeqParams p;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.out = static_cast<unsigned char*>(k_out);
+    p.ob = o_stride_batch * es;
+    p.oh = o_stride_head * es;
+    p.ot = o_stride_token * es;
+    p.n_tokens = n_tokens;
+    p.n_heads = n_heads;
+
+    const int64_t bh = n_batch * n_heads;
+    const int64_t gx = (n_tokens * 8 + 255) / 256;
+    int64_t gy = bh, gz = 1;
+    if (gy > 65535) {
+        gz = (bh + 65534) / 65535;
+        // need an exact factorisation so that every (y, z) is a real (batch, head)
+        gy = 0;
+        for (int64_t cand = 65535; cand >= 1; --cand)
+            if (bh % cand == 0) { gy = cand; break; }
+        gz = bh / gy;
+    }
+    if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? launch_group<2>(group, out_dt, p, grid, s)
+                     : launch_group<4>(group, out_dt, p, grid, s);
+}

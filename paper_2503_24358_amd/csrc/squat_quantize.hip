@@ -1,0 +1,478 @@
+// squat_quantize_keys: the iteration of Algorithm 1's `Quant` with the block
+// update of Lemma 2, for per-token groups of channels, on gfx950.
+//
+// One wavefront owns a tile of 32 tokens x 128 channels.  The working copy of
+// the keys lives in registers in the MFMA 32x32 accumulator layout with a token
+// as a COLUMN: lane (hh, n) holds, for token n, channels 16*hh .. 16*hh+15 of
+// each 32-channel tile.  In that layout
+//   - a group's min/max is an in-register reduction plus one exchange with
+//     lane ^ 32,
+//   - the normalised rounding error of a frozen tile is already the B operand
+//     of  W (channels x g) * E (g x tokens), so the update of Lemma 2 needs no
+//     data movement between lanes,
+//   - 16 two-bit codes of a lane are exactly one 32-bit word of the packed
+//     output.
+// The contraction runs on the fp16 matrix cores with both operands split into
+// a high and a low fp16 part (three products per tile), accumulating in fp32;
+// the error is kept in units of the group's scale so that its fp16 split has a
+// fixed range.  Workgroups are persistent and bound to one head: the head's
+// update panels are converted once into LDS, in MFMA A-operand order.
+#include "squat_internal.h"
+
+using namespace squat;
+
+namespace {
+
+constexpr int NT = kD / 32;          // 32-channel tiles per key
+constexpr int kWaves = 4;            // wavefronts per workgroup
+constexpr float kMagic = 12582912.0f;   // 1.5 * 2^23: adding it rounds to nearest-even integer
+constexpr uint32_t kMagicBits = 0x4B400000u;
+
+struct QuantParams {
+    const unsigned char* k;
+    int64_t sb, sh, st;              // key strides in BYTES
+    const float* update;
+    int64_t usb;                     // update stride per outer-batch entry, elements
+    uint32_t* codes;
+    uint16_t* scale;
+    uint16_t* zero;
+    int64_t n_tokens;
+    int64_t n_inner;                 // batch entries that share one update matrix
+    int n_heads;
+    int64_t tiles_per_seq;
+    int64_t units_per_prob;          // n_inner * tiles_per_seq
+    int wgs_per_prob;
+};
+
+// Tile pairs (jt, s) with a non-zero panel: block(jt) > block(s), BT tiles per block.
+__host__ __device__ constexpr int n_pairs(int BT) {
+    int c = 0;
+    for (int s = 0; s < NT; ++s)
+        for (int jt = (s / BT + 1) * BT; jt < NT; ++jt) ++c;
+    return c;
+}
+__host__ __device__ constexpr int pair_index(int BT, int jt, int s) {
+    int c = 0;
+    for (int ss = 0; ss < NT; ++ss)
+        for (int j = (ss / BT + 1) * BT; j < NT; ++j) {
+            if (ss == s && j == jt) return c;
+            ++c;
+        }
+    return -1;
+}
+
+__host__ __device__ constexpr uint32_t pack_const(int bits) {
+    uint32_t acc = 0;
+    const int items = 32 / bits;
+    for (int i = 0; i < items; ++i) acc = (acc << bits) + kMagicBits;
+    return acc;
+}
+
+template <int DT>
+struct Elem {
+    static constexpr int size = (DT == SQUAT_F32) ? 4 : 2;
+};
+
+// 16 consecutive channels (raw bytes in LDS) -> 16 floats.
+template <int DT>
+__device__ __forceinline__ void load16(const unsigned char* src, float* out) {
+    if constexpr (DT == SQUAT_F32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(src + 16 * i);
+            out[4 * i + 0] = v[0]; out[4 * i + 1] = v[1]; out[4 * i + 2] = v[2]; out[4 * i + 3] = v[3];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            u32x4 v = *reinterpret_cast<const u32x4*>(src + 16 * i);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                if constexpr (DT == SQUAT_BF16) {
+                    out[8 * i + 2 * w + 0] = as_f32(v[w] << 16);
+                    out[8 * i + 2 * w + 1] = as_f32(v[w] & 0xFFFF0000u);
+                } else {
+                    half2v h = __builtin_bit_cast(half2v, v[w]);
+                    out[8 * i + 2 * w + 0] = static_cast<float>(h[0]);
+                    out[8 * i + 2 * w + 1] = static_cast<float>(h[1]);
+                }
+            }
+        }
+    }
+}
+
+// min (or max) of a value with the same value in lane ^ 32.
+__device__ __forceinline__ float pair_min(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return fminf(as_f32(r[0]), as_f32(r[1]));
+}
+__device__ __forceinline__ float pair_max(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return fmaxf(as_f32(r[0]), as_f32(r[1]));
+}
+// After the call lanes 32..63 of `a` hold what lanes 0..31 of `b` held and vice versa.
+__device__ __forceinline__ void swap_halves(uint32_t& a, uint32_t& b) {
+    auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    a = r[0];
+    b = r[1];
+}
+
+// Split 8 floats into packed fp16 high and low parts (hi + lo ~ value to 2^-22).
+__device__ __forceinline__ void split8(const float* v, half8& hi, half8& lo) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        _Float16 h = static_cast<_Float16>(v[i]);
+        hi[i] = h;
+        lo[i] = static_cast<_Float16>(v[i] - static_cast<float>(h));
+    }
+}
+
+template <int BITS, int GT, int BT, int DT>
+__global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const QuantParams p) {
+    constexpr int ES = Elem<DT>::size;
+    constexpr int ROWB = kD * ES;                 // bytes of one key
+    constexpr int LROW = ROWB + 16;               // padded LDS row: conflict-free b128 column reads
+    constexpr int CPR = ROWB / 16;                // 16-byte chunks per key
+    constexpr int NLOAD = 32 * CPR / kWave;       // 16-byte loads per lane per tile
+    constexpr int NPAIRS = n_pairs(BT);
+    constexpr int NB = NT / BT;                   // blocks (iterations) per key
+    constexpr int NG = NT / GT;                   // groups per key
+    constexpr int WPT = BITS / 2;                 // packed words per lane per tile
+    constexpr int IPW = 32 / BITS;                // codes per word
+    constexpr float LV = static_cast<float>((1 << BITS) - 1);
+    constexpr uint32_t PCONST = pack_const(BITS);
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    half8* wlds = reinterpret_cast<half8*>(smem);           // [NPAIRS][2 kk][hi, lo][64 lanes]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int hh = lane >> 5;
+    const int n = lane & 31;
+    unsigned char* stage = smem + NPAIRS * 4096 + wave * (32 * LROW);
+
+    const int64_t prob = blockIdx.x / p.wgs_per_prob;
+    const int wg = blockIdx.x % p.wgs_per_prob;
+    const int head = static_cast<int>(prob % p.n_heads);
+    const int64_t bo = prob / p.n_heads;
+
+    if constexpr (NPAIRS > 0) {
+        // Convert this head's panels once: A operand of pair (jt, s), MFMA kk: lane (ha, m)
+        // holds U[32 jt + channel(m)][32 s + 16 ha + 8 kk + 0..7].
+        const float* U = p.update + bo * p.usb + static_cast<int64_t>(head) * kD * kD;
+        for (int idx = tid; idx < NPAIRS * 2 * 64; idx += kWaves * kWave) {
+            const int pr = idx >> 7;
+            const int kk = (idx >> 6) & 1;
+            const int l = idx & 63;
+            int jt = 0, s = 0;
+            {
+                int c = 0;
+                for (int ss = 0; ss < NT; ++ss)
+                    for (int j = (ss / BT + 1) * BT; j < NT; ++j) {
+                        if (c == pr) { jt = j; s = ss; }
+                        ++c;
+                    }
+            }
+            const int ha = l >> 5, m = l & 31;
+            const int row = 32 * jt + row_to_channel(m);
+            const int col = 32 * s + 16 * ha + 8 * kk;
+            const f32x4* src = reinterpret_cast<const f32x4*>(U + row * kD + col);
+            const f32x4 a = src[0], b = src[1];
+            const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+            half8 hi, lo;
+            split8(v, hi, lo);
+            wlds[((pr * 2 + kk) * 2 + 0) * 64 + l] = hi;
+            wlds[((pr * 2 + kk) * 2 + 1) * 64 + l] = lo;
+        }
+        __syncthreads();
+    }
+
+    const int64_t ustride = static_cast<int64_t>(p.wgs_per_prob) * kWaves;
+    int64_t unit = static_cast<int64_t>(wg) * kWaves + wave;
+
+    u32x4 pre[NLOAD];
+    auto issue_loads = [&](int64_t u) {
+        const int64_t bi = u / p.tiles_per_seq;
+        const int64_t tok0 = (u - bi * p.tiles_per_seq) * kTileTokens;
+        const unsigned char* base = p.k + (bo + bi) * p.sb + head * p.sh + tok0 * p.st;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int flat = i * kWave + lane;
+            const int row = flat / CPR, ch = flat % CPR;
+            if (tok0 + row < p.n_tokens)
+                pre[i] = *reinterpret_cast<const u32x4*>(base + row * p.st + ch * 16);
+            else
+                pre[i] = u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+
+    if (unit < p.units_per_prob) issue_loads(unit);
+
+    while (unit < p.units_per_prob) {
+        // ---- registers -> LDS (token-major rows), then read back channel-major per lane
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int flat = i * kWave + lane;
+            const int row = flat / CPR, ch = flat % CPR;
+            *reinterpret_cast<u32x4*>(stage + row * LROW + ch * 16) = pre[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        const int64_t cur = unit;
+        unit += ustride;
+
+        float x[NT][16];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            load16<DT>(stage + n * LROW + (32 * j + 16 * hh) * ES, x[j]);
+
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        if (unit < p.units_per_prob) issue_loads(unit);   // prefetch the next tile
+
+        uint32_t words[NT][WPT];
+        uint16_t sbits[NG], zbits[NG];
+        float g_scale[NG], g_inv[NG], g_zero[NG], g_top[NG];
+
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            // ---- statistics of the groups that start in this block (current values)
+#pragma unroll
+            for (int j = blk * BT; j < (blk + 1) * BT; ++j) {
+                if (j % GT == 0) {
+                    const int gi = j / GT;
+                    float mn = x[j][0], mx = x[j][0];
+#pragma unroll
+                    for (int jj = j; jj < j + GT; ++jj)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            mn = fminf(mn, x[jj][e]);
+                            mx = fmaxf(mx, x[jj][e]);
+                        }
+                    mn = pair_min(mn);
+                    mx = pair_max(mx);
+                    const float dl = (mx - mn) * (1.0f / LV);
+                    const float sh = round_f16(dl, sbits[gi]);
+                    g_zero[gi] = round_f16(mn, zbits[gi]);
+                    const bool live = sh > 0.0f;
+                    const float sp = live ? sh : 1.0f;
+                    float inv = __builtin_amdgcn_rcpf(sp);
+                    inv = fmaf(fmaf(-sp, inv, 1.0f), inv, inv);
+                    g_scale[gi] = sp;
+                    g_inv[gi] = inv;
+                    g_top[gi] = live ? LV : 0.0f;
+                }
+            }
+            // ---- quantize and freeze the block; keep its normalised error as MFMA B operands
+            half8 bhi[BT][2], blo[BT][2];
+#pragma unroll
+            for (int jj = 0; jj < BT; ++jj) {
+                const int j = blk * BT + jj;
+                const int gi = j / GT;
+                const float mh = g_zero[gi], inv = g_inv[gi], top = g_top[gi];
+                float et[16];
+#pragma unroll
+                for (int w = WPT - 1; w >= 0; --w) {
+                    uint32_t acc = 0;
+#pragma unroll
+                    for (int e = IPW - 1; e >= 0; --e) {
+                        const int c = w * IPW + e;
+                        const float u = (x[j][c] - mh) * inv;
+                        const float uc = __builtin_amdgcn_fmed3f(u, 0.0f, top);
+                        const float r = uc + kMagic;
+                        acc = (acc << BITS) + as_u32(r);
+                        et[c] = (r - kMagic) - u;
+                    }
+                    words[j][w] = acc - PCONST;
+                }
+                if (blk < NB - 1) {
+                    split8(et, bhi[jj][0], blo[jj][0]);
+                    split8(et + 8, bhi[jj][1], blo[jj][1]);
+                }
+            }
+            // ---- Lemma 2: remaining channels += U[rest, block] * error
+            if constexpr (NPAIRS > 0) {
+                if (blk < NB - 1) {
+#pragma unroll
+                    for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
+#pragma unroll
+                        for (int jj = 0; jj < BT; ++jj) {
+                            const int s = blk * BT + jj;
+                            const int pr = pair_index(BT, jt, s);
+                            f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                            for (int kk = 0; kk < 2; ++kk) {
+                                const half8 whi = wlds[((pr * 2 + kk) * 2 + 0) * 64 + lane];
+                                const half8 wlo = wlds[((pr * 2 + kk) * 2 + 1) * 64 + lane];
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, bhi[jj][kk], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, blo[jj][kk], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wlo, bhi[jj][kk], acc, 0, 0, 0);
+                            }
+                            const float sc = g_scale[s / GT];
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(sc, acc[e], x[jt][e]);
+                        }
+                    }
+                }
+            }
+        }
+
+        // ---- outputs
+        const int64_t bi = cur / p.tiles_per_seq;
+        const int64_t tok0 = (cur - bi * p.tiles_per_seq) * kTileTokens;
+        const bool valid = tok0 + n < p.n_tokens;
+        const int64_t rowid = ((bo + bi) * p.n_heads + head) * p.n_tokens + tok0 + n;
+
+        // lower half-wave collects the first half of a key's words, upper the second
+#pragma unroll
+        for (int w = 0; w < WPT; ++w) {
+            swap_halves(words[0][w], words[2][w]);
+            swap_halves(words[1][w], words[3][w]);
+        }
+        if (valid) {
+            uint32_t* dst = p.codes + rowid * (NT * 2 * WPT) + hh * (NT * WPT);
+            if constexpr (WPT == 1) {
+                *reinterpret_cast<u32x4*>(dst) = u32x4{words[0][0], words[2][0], words[1][0], words[3][0]};
+            } else {
+                *reinterpret_cast<u32x4*>(dst) = u32x4{words[0][0], words[0][1], words[2][0], words[2][1]};
+                *reinterpret_cast<u32x4*>(dst + 4) = u32x4{words[1][0], words[1][1], words[3][0], words[3][1]};
+            }
+            // lanes 0..31 write the scales, lanes 32..63 the zero-points
+            uint16_t* mdst = (hh ? p.zero : p.scale) + rowid * NG;
+            if constexpr (NG == 4) {
+                const uint32_t lo = hh ? (zbits[0] | (uint32_t(zbits[1]) << 16)) : (sbits[0] | (uint32_t(sbits[1]) << 16));
+                const uint32_t hi = hh ? (zbits[2] | (uint32_t(zbits[3]) << 16)) : (sbits[2] | (uint32_t(sbits[3]) << 16));
+                *reinterpret_cast<u32x2*>(mdst) = u32x2{lo, hi};
+            } else if constexpr (NG == 2) {
+                *reinterpret_cast<uint32_t*>(mdst) =
+                    hh ? (zbits[0] | (uint32_t(zbits[1]) << 16)) : (sbits[0] | (uint32_t(sbits[1]) << 16));
+            } else {
+                *mdst = hh ? zbits[0] : sbits[0];
+            }
+        }
+    }
+}
+
+template <int BITS, int GT, int BT, int DT>
+int launch(const QuantParams& p, int64_t n_prob, hipStream_t stream) {
+    constexpr int ES = Elem<DT>::size;
+    constexpr size_t lds = n_pairs(BT) * 4096 + kWaves * 32 * (kD * ES + 16);
+    auto kern = quantize_kernel<BITS, GT, BT, DT>;
+    static bool attr_done = false;      // idempotent; a race only repeats the call
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+            return SQUAT_E_HIP;
+        attr_done = true;
+    }
+    const dim3 grid(static_cast<unsigned>(n_prob * p.wgs_per_prob));
+    hipLaunchKernelGGL(kern, grid, dim3(kWaves * kWave), lds, stream, p);
+    return check_launch();
+}
+
+template <int BITS, int GT, int BT>
+int dispatch_dt(squat_dtype dt, const QuantParams& p, int64_t n_prob, hipStream_t s) {
+    switch (dt) {
+        case SQUAT_F32: return launch<BITS, GT, BT, SQUAT_F32>(p, n_prob, s);
+        case SQUAT_F16: return launch<BITS, GT, BT, SQUAT_F16>(p, n_prob, s);
+        case SQUAT_BF16: return launch<BITS, GT, BT, SQUAT_BF16>(p, n_prob, s);
+    }
+    return SQUAT_E_BADDTYPE;
+}
+template <int BITS, int GT>
+int dispatch_bt(int bt, squat_dtype dt, const QuantParams& p, int64_t n_prob, hipStream_t s) {
+    switch (bt) {
+        case 1: return dispatch_dt<BITS, GT, 1>(dt, p, n_prob, s);
+        case 2: return dispatch_dt<BITS, GT, 2>(dt, p, n_prob, s);
+        case 4: return dispatch_dt<BITS, GT, 4>(dt, p, n_prob, s);
+    }
+    return SQUAT_E_BADSHAPE;
+}
+template <int BITS>
+int dispatch_gt(int gt, int bt, squat_dtype dt, const QuantParams& p, int64_t n_prob, hipStream_t s) {
+    switch (gt) {
+        case 1: return dispatch_bt<BITS, 1>(bt, dt, p, n_prob, s);
+        case 2: return dispatch_bt<BITS, 2>(bt, dt, p, n_prob, s);
+        case 4: return dispatch_bt<BITS, 4>(bt, dt, p, n_prob, s);
+    }
+    return SQUAT_E_BADSHAPE;
+}
+
+int device_cu_count() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return 256;
+    return cus;
+}
+
+}  // namespace
+
+extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
+                                   int64_t n_tokens, int d, int64_t k_stride_batch,
+                                   int64_t k_stride_head, int64_t k_stride_token,
+                                   const float* update, int64_t update_stride_batch, int bits,
+                                   int group, int g, uint32_t* codes, uint16_t* scale,
+                                   uint16_t* zero, squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
+    if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_heads < 0 || n_tokens < 0) return SQUAT_E_BADSHAPE;
+    if (k_dt != SQUAT_F32 && k_dt != SQUAT_F16 && k_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_batch == 0 || n_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!k || !codes || !scale || !zero) return SQUAT_E_NULLPTR;
+    if (k_stride_token < d || k_stride_batch < 0 || k_stride_head < 0 || update_stride_batch < 0)
+        return SQUAT_E_BADSHAPE;
+    if ((k_stride_token % 8) || (k_stride_head % 8) || (k_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(k, 16) || !aligned(codes, 16) || !aligned(scale, 8) || !aligned(zero, 8)) return SQUAT_E_ALIGN;
+    if (update && (!aligned(update, 16) || (update_stride_batch % 4))) return SQUAT_E_ALIGN;
+    if (n_batch * n_heads > (int64_t(1) << 30)) return SQUAT_E_BADSHAPE;
+
+    const int es = elem_size(k_dt);
+    QuantParams p;
+    p.k = static_cast<const unsigned char*>(k);
+    p.sb = k_stride_batch * es;
+    p.sh = k_stride_head * es;
+    p.st = k_stride_token * es;
+    p.update = update;
+    p.usb = update_stride_batch;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.n_tokens = n_tokens;
+    p.n_heads = n_heads;
+    p.tiles_per_seq = (n_tokens + kTileTokens - 1) / kTileTokens;
+
+    // Workgroups are bound to one update matrix: per head when it is shared across the
+    // batch, per (batch, head) otherwise.
+    int64_t n_prob;
+    if (update && update_stride_batch != 0) {
+        n_prob = n_batch * n_heads;
+        p.n_inner = 1;
+    } else {
+        n_prob = n_heads;
+        p.n_inner = n_batch;
+    }
+    p.units_per_prob = p.n_inner * p.tiles_per_seq;
+
+    const int cus = device_cu_count();
+    const int64_t target = 2 * static_cast<int64_t>(cus);          // two resident workgroups per CU
+    int64_t per = (target + n_prob - 1) / n_prob;
+    const int64_t need = (p.units_per_prob + kWaves - 1) / kWaves;
+    if (per > need) per = need;
+    if (per < 1) per = 1;
+    p.wgs_per_prob = static_cast<int>(per);
+    if (n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
+
+    const int gt = group / 32;
+    const int bt = update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
+    if (!(gt % bt == 0 || bt % gt == 0)) return SQUAT_E_BADSHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? dispatch_gt<2>(gt, bt, k_dt, p, n_prob, s)
+                     : dispatch_gt<4>(gt, bt, k_dt, p, n_prob, s);
+}

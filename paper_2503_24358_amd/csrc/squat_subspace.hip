@@ -1,0 +1,422 @@
+// squat_build_subspace: Qhat = diag(Sigma[:r]) V[:r] of the pooled prompt queries
+// (Section 3.2 and Algorithm 1 of the paper; GQA pooling as in its appendix),
+// computed as the top-r eigenpairs of the Gram matrix Q^T Q.
+//
+//   gram_partial  MFMA kernel.  A wavefront streams 16-token chunks of one query
+//                 head; lane (hh, m) loads tokens 8*hh + 0..7, channels 4m..4m+3,
+//                 and regroups them in registers (v_perm) into four MFMA
+//                 operands X_a, a = 0..3, whose row m is channel 4m + a.  The
+//                 same registers serve as A and B operand of X_a^T X_b, so no
+//                 LDS transpose is needed; only the 10 tile products with
+//                 a <= b are formed (symmetry).  fp32 accumulation per
+//                 workgroup, partial tiles go to the workspace.
+//   gram_reduce   sums the workgroups' partials in fp64 in a fixed order
+//                 (deterministic), un-permutes channels and mirrors.
+//   eig_kernel    cyclic one-sided Jacobi in fp64 on the 128 x 128 Gram matrix in
+//                 LDS, one workgroup per KV head, then picks the r largest.
+#include "squat_internal.h"
+#include "squat_jacobi.h"
+
+using namespace squat;
+
+namespace {
+
+constexpr int kGramWaves = 4;
+constexpr int kTiles = 10;                     // (a, b) with a <= b, a, b in 0..3
+constexpr int kPartialFloats = kTiles * 1024;  // one workgroup's partial Gram
+
+struct GramParams {
+    const unsigned char* q;
+    int64_t sh, st;              // strides in BYTES
+    int64_t n_tokens;
+    int q_per_kv;
+    int wgs_per_head;
+    int64_t chunks_per_qhead;    // ceil(n_tokens / 16)
+    int64_t units_per_head;      // q_per_kv * chunks_per_qhead
+    float* partial;              // [n_kv_heads][wgs_per_head][10][1024]
+};
+
+__host__ __device__ constexpr int tile_index(int a, int b) {   // a <= b
+    int c = 0;
+    for (int i = 0; i < 4; ++i)
+        for (int j = i; j < 4; ++j) {
+            if (i == a && j == b) return c;
+            ++c;
+        }
+    return -1;
+}
+
+template <int DT>
+struct GramOps;
+
+// 16-bit inputs: operand of one MFMA = 8 tokens per lane, packed pairs.
+template <>
+struct GramOps<SQUAT_BF16> {
+    typedef bf16x8 op_t;
+    static __device__ __forceinline__ f32x16 mfma(op_t a, op_t b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <>
+struct GramOps<SQUAT_F16> {
+    typedef half8 op_t;
+    static __device__ __forceinline__ f32x16 mfma(op_t a, op_t b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
+
+// Accumulate one workgroup's share of Q^T Q.  16-bit element types.
+template <int DT>
+__global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const GramParams p) {
+    typedef typename GramOps<DT>::op_t op_t;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hh = lane >> 5, m = lane & 31;
+    const int kvh = blockIdx.x / p.wgs_per_head;
+    const int wg = blockIdx.x % p.wgs_per_head;
+
+    f32x16 acc[kTiles];
+#pragma unroll
+    for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+
+    const int64_t ustride = static_cast<int64_t>(p.wgs_per_head) * kGramWaves;
+    int64_t unit = static_cast<int64_t>(wg) * kGramWaves + wave;
+
+    u32x2 raw[8];
+    auto issue = [&](int64_t u) {
+        const int64_t qh = u / p.chunks_per_qhead;
+        const int64_t tok0 = (u - qh * p.chunks_per_qhead) * 16 + 8 * hh;
+        const unsigned char* base =
+            p.q + (static_cast<int64_t>(kvh) * p.q_per_kv + qh) * p.sh + tok0 * p.st + m * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (tok0 + j < p.n_tokens)
+                raw[j] = *reinterpret_cast<const u32x2*>(base + j * p.st);
+            else
+                raw[j] = u32x2{0u, 0u};
+        }
+    };
+    if (unit < p.units_per_head) issue(unit);
+
+    while (unit < p.units_per_head) {
+        // regroup: operand X_a holds, for channel 4m + a, the 8 tokens of this lane
+        uint32_t x[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[0][i] = __builtin_amdgcn_perm(raw[2 * i + 1][0], raw[2 * i][0], 0x05040100u);
+            x[1][i] = __builtin_amdgcn_perm(raw[2 * i + 1][0], raw[2 * i][0], 0x07060302u);
+            x[2][i] = __builtin_amdgcn_perm(raw[2 * i + 1][1], raw[2 * i][1], 0x05040100u);
+            x[3][i] = __builtin_amdgcn_perm(raw[2 * i + 1][1], raw[2 * i][1], 0x07060302u);
+        }
+        unit += ustride;
+        if (unit < p.units_per_head) issue(unit);
+
+        op_t ops[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+            ops[a] = __builtin_bit_cast(op_t, u32x4{x[a][0], x[a][1], x[a][2], x[a][3]});
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = a; b < 4; ++b)
+                acc[tile_index(a, b)] = GramOps<DT>::mfma(ops[a], ops[b], acc[tile_index(a, b)]);
+    }
+
+    // reduce the four wavefronts through LDS (two rounds), wave 0 writes the partial
+    float* red = reinterpret_cast<float*>(smem);        // [2][10][16][64]
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[((slot * kTiles + t) * 16 + e) * 64 + lane] = acc[t][e];
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][e] += red[((slot * kTiles + t) * 16 + e) * 64 + lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+        float* dst = p.partial + (static_cast<int64_t>(kvh) * p.wgs_per_head + wg) * kPartialFloats;
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) dst[(t * 16 + e) * 64 + lane] = acc[t][e];
+    }
+}
+
+// fp32 inputs: products on the fp32 matrix cores (32x32x2), two tokens per step.
+__global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_f32(const GramParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hh = lane >> 5, m = lane & 31;
+    const int kvh = blockIdx.x / p.wgs_per_head;
+    const int wg = blockIdx.x % p.wgs_per_head;
+
+    f32x16 acc[kTiles];
+#pragma unroll
+    for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+
+    const int64_t ustride = static_cast<int64_t>(p.wgs_per_head) * kGramWaves;
+    for (int64_t unit = static_cast<int64_t>(wg) * kGramWaves + wave; unit < p.units_per_head; unit += ustride) {
+        const int64_t qh = unit / p.chunks_per_qhead;
+        const int64_t tok0 = (unit - qh * p.chunks_per_qhead) * 16;
+        const unsigned char* base = p.q + (static_cast<int64_t>(kvh) * p.q_per_kv + qh) * p.sh + m * 16;
+        f32x4 raw[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t tok = tok0 + 2 * j + hh;
+            if (tok < p.n_tokens)
+                raw[j] = *reinterpret_cast<const f32x4*>(base + tok * p.st);
+            else
+                raw[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = a; b < 4; ++b)
+                    acc[tile_index(a, b)] =
+                        __builtin_amdgcn_mfma_f32_32x32x2f32(raw[j][a], raw[j][b], acc[tile_index(a, b)], 0, 0, 0);
+    }
+
+    float* red = reinterpret_cast<float*>(smem);
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[((slot * kTiles + t) * 16 + e) * 64 + lane] = acc[t][e];
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][e] += red[((slot * kTiles + t) * 16 + e) * 64 + lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+        float* dst = p.partial + (static_cast<int64_t>(kvh) * p.wgs_per_head + wg) * kPartialFloats;
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) dst[(t * 16 + e) * 64 + lane] = acc[t][e];
+    }
+}
+
+// partial[(t*16 + e)*64 + lane] is element (row mm, col nn) of tile t = (a, b) with
+// nn = lane & 31, mm = 8*(e>>2) + 4*(lane>>5) + (e&3), i.e. G[4*mm + a][4*nn + b].
+__global__ void __launch_bounds__(256) gram_reduce(const float* partial, int wgs_per_head,
+                                                   double* g64, float* gram_out) {
+    const int kvh = blockIdx.x;
+    const float* src = partial + static_cast<int64_t>(kvh) * wgs_per_head * kPartialFloats;
+    double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
+    float* go = gram_out ? gram_out + static_cast<int64_t>(kvh) * kD * kD : nullptr;
+    for (int idx = threadIdx.x; idx < kPartialFloats; idx += blockDim.x) {
+        double s = 0.0;
+        for (int w = 0; w < wgs_per_head; ++w) s += static_cast<double>(src[static_cast<int64_t>(w) * kPartialFloats + idx]);
+        const int t = idx >> 10, e = (idx >> 6) & 15, lane = idx & 63;
+        int a = 0, b = 0;
+        {
+            int c = 0;
+            for (int i = 0; i < 4; ++i)
+                for (int j = i; j < 4; ++j) {
+                    if (c == t) { a = i; b = j; }
+                    ++c;
+                }
+        }
+        const int nn = lane & 31;
+        const int mm = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const int row = 4 * mm + a, col = 4 * nn + b;
+        if (a == b) {
+            // diagonal tiles hold both (row, col) and (col, row); keep the upper one for an exactly symmetric result
+            if (row <= col) {
+                g[row * kD + col] = s;
+                g[col * kD + row] = s;
+                if (go) { go[row * kD + col] = static_cast<float>(s); go[col * kD + row] = static_cast<float>(s); }
+            }
+        } else {
+            g[row * kD + col] = s;
+            g[col * kD + row] = s;
+            if (go) { go[row * kD + col] = static_cast<float>(s); go[col * kD + row] = static_cast<float>(s); }
+        }
+    }
+}
+
+constexpr int kEigThreads = 1024;
+constexpr int kEigLd = kD;       // rows are read with unit stride by consecutive lanes
+
+__global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int r, float* qhat, float* eig,
+                                                          int* sweeps_out) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    double* A = reinterpret_cast<double*>(smem);                 // 128 x 128
+    double* nrm = A + kD * kEigLd;                               // 128
+    int* rank = reinterpret_cast<int*>(nrm + kD);                // 128
+    int* flag = rank + kD;
+    const int kvh = blockIdx.x;
+    const double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
+    for (int i = threadIdx.x; i < kD * kD; i += kEigThreads) A[i] = g[i];
+    __syncthreads();
+    const int sweeps = jacobi_rows<kEigThreads, 16>(A, kD, kEigLd, flag, 60, 1e-15);
+    if (sweeps_out && threadIdx.x == 0) sweeps_out[kvh] = sweeps;
+
+    // eigenvalue of row i = its norm
+    {
+        const int row = threadIdx.x >> 3, tl = threadIdx.x & 7;     // 8 lanes per row
+        double s = 0.0;
+        for (int c = tl; c < kD; c += 8) s += A[row * kEigLd + c] * A[row * kEigLd + c];
+        s = team_sum<8>(s);
+        if (tl == 0) nrm[row] = sqrt(s);
+    }
+    __syncthreads();
+    if (threadIdx.x < kD) {
+        const int i = threadIdx.x;
+        const double ni = nrm[i];
+        int rk = 0;
+        for (int j = 0; j < kD; ++j) {
+            const double nj = nrm[j];
+            rk += (nj > ni) || (nj == ni && j < i);
+        }
+        rank[i] = rk;
+    }
+    __syncthreads();
+    // row i with rank < r  ->  qhat[rank] = row / sqrt(norm), sign: largest |component| positive
+    {
+        const int row = threadIdx.x >> 3, tl = threadIdx.x & 7;
+        const int rk = rank[row];
+        if (rk < r) {
+            double best = -1.0, bestv = 0.0;
+            int besti = kD;
+            for (int c = tl; c < kD; c += 8) {
+                const double v = A[row * kEigLd + c];
+                if (fabs(v) > best) { best = fabs(v); bestv = v; besti = c; }
+            }
+#pragma unroll
+            for (int off = 4; off > 0; off >>= 1) {
+                const double ob = __shfl_xor(best, off, 8);
+                const double ov = __shfl_xor(bestv, off, 8);
+                const int oi = __shfl_xor(besti, off, 8);
+                if (ob > best || (ob == best && oi < besti)) { best = ob; bestv = ov; besti = oi; }
+            }
+            const double lam = nrm[row];
+            const double sc = lam > 0.0 ? (bestv < 0.0 ? -1.0 : 1.0) / sqrt(lam) : 0.0;
+            float* dst = qhat + (static_cast<int64_t>(kvh) * r + rk) * kD;
+            for (int c = tl; c < kD; c += 8) dst[c] = static_cast<float>(A[row * kEigLd + c] * sc);
+            if (eig && tl == 0) eig[static_cast<int64_t>(kvh) * r + rk] = static_cast<float>(lam);
+        }
+    }
+}
+
+struct SubspacePlan {
+    int wgs_per_head;
+    size_t off_partial, off_g64, total;
+};
+
+SubspacePlan plan(int64_t n_tokens, int n_kv_heads, int q_per_kv, int cus) {
+    SubspacePlan pl;
+    const int64_t units = q_per_kv * ((n_tokens + 15) / 16);
+    int64_t per = (cus + n_kv_heads - 1) / n_kv_heads;          // one workgroup per CU in total
+    const int64_t need = (units + kGramWaves * 8 - 1) / (kGramWaves * 8);   // at least 8 chunks per wavefront
+    if (per > need) per = need;
+    if (per < 1) per = 1;
+    pl.wgs_per_head = static_cast<int>(per);
+    pl.off_partial = 0;
+    size_t partial = static_cast<size_t>(n_kv_heads) * per * kPartialFloats * sizeof(float);
+    pl.off_g64 = (partial + 255) & ~size_t(255);
+    pl.total = pl.off_g64 + static_cast<size_t>(n_kv_heads) * kD * kD * sizeof(double);
+    return pl;
+}
+
+constexpr int kPlanCUs = 256;   // workspace size must not depend on the device: plan for MI355X's 256 CUs
+
+}  // namespace
+
+extern "C" size_t squat_build_subspace_workspace(int64_t n_tokens, int n_kv_heads, int q_per_kv, int d, int r) {
+    (void)r;
+    if (d != kD || n_tokens < 1 || n_kv_heads < 1 || q_per_kv < 1) return 0;
+    return plan(n_tokens, n_kv_heads, q_per_kv, kPlanCUs).total;
+}
+
+extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads,
+                                    int q_per_kv, int d, int64_t q_stride_head, int64_t q_stride_token,
+                                    int r, float* qhat, float* eig, float* gram, void* ws, size_t ws_bytes,
+                                    squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (n_tokens < 1 || n_kv_heads < 0 || q_per_kv < 1 || r < 0 || r > d) return SQUAT_E_BADSHAPE;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_kv_heads == 0) return SQUAT_OK;
+    if (!q || (r > 0 && !qhat)) return SQUAT_E_NULLPTR;
+    if (q_stride_token < d || q_stride_head < 0) return SQUAT_E_BADSHAPE;
+    if ((q_stride_token % 8) || (q_stride_head % 8) || !aligned(q, 16)) return SQUAT_E_ALIGN;
+    if (static_cast<int64_t>(n_kv_heads) * q_per_kv > (int64_t(1) << 24)) return SQUAT_E_BADSHAPE;
+    const SubspacePlan pl = plan(n_tokens, n_kv_heads, q_per_kv, kPlanCUs);
+    if (!ws || ws_bytes < pl.total) return SQUAT_E_WORKSPACE;
+    if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int es = elem_size(q_dt);
+    GramParams p;
+    p.q = static_cast<const unsigned char*>(q);
+    p.sh = q_stride_head * es;
+    p.st = q_stride_token * es;
+    p.n_tokens = n_tokens;
+    p.q_per_kv = q_per_kv;
+    p.wgs_per_head = pl.wgs_per_head;
+    p.chunks_per_qhead = (n_tokens + 15) / 16;
+    p.units_per_head = p.chunks_per_qhead * q_per_kv;
+    p.partial = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + pl.off_partial);
+    double* g64 = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_g64);
+
+    const size_t red_lds = 2 * kPartialFloats * sizeof(float);      // 80 KB
+    const dim3 grid(static_cast<unsigned>(n_kv_heads) * pl.wgs_per_head);
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gram_partial_16<SQUAT_BF16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(red_lds)) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(gram_partial_16<SQUAT_F16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(red_lds)) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(gram_partial_f32),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(red_lds)) != hipSuccess)
+            return SQUAT_E_HIP;
+    }
+    const size_t eig_lds = kD * kEigLd * sizeof(double) + kD * sizeof(double) + kD * sizeof(int) + 16;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(eig_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(eig_lds)) != hipSuccess)
+            return SQUAT_E_HIP;
+        attr_done = true;
+    }
+    switch (q_dt) {
+        case SQUAT_BF16: hipLaunchKernelGGL(gram_partial_16<SQUAT_BF16>, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL(gram_partial_16<SQUAT_F16>, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;
+        default: hipLaunchKernelGGL(gram_partial_f32, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;
+    }
+    int rc = check_launch();
+    if (rc) return rc;
+    hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(256), 0, s, p.partial, pl.wgs_per_head, g64, gram);
+    rc = check_launch();
+    if (rc) return rc;
+    if (r > 0) {
+        hipLaunchKernelGGL(eig_kernel, dim3(n_kv_heads), dim3(kEigThreads), eig_lds, s, g64, r, qhat, eig,
+                           static_cast<int*>(nullptr));
+        rc = check_launch();
+    }
+    return rc;
+}

@@ -1,0 +1,185 @@
+"""ctypes binding of libsquat.so -- same names and argument order as include/squat.h.
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch is used for device memory and the current stream.  There is
+no CPU fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+F32, F16, BF16 = 0, 1, 2
+_DT = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsquat.so")
+_lib = None
+
+SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
+           "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
+           "squat_quantize_keys", "squat_dequantize_keys")
+
+
+class SquatError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libsquat.so (built in-tree by paper_2503_24358_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("libsquat.so not found at %s: run `python -m paper_2503_24358_amd.build` "
+                           "(there is no fallback path)" % _LIB_PATH)
+    L = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp, sz, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+    L.squat_version.restype = i32
+    L.squat_version.argtypes = []
+    L.squat_strerror.restype = ctypes.c_char_p
+    L.squat_strerror.argtypes = [i32]
+    L.squat_build_subspace_workspace.restype = sz
+    L.squat_build_subspace_workspace.argtypes = [i64, i32, i32, i32, i32]
+    L.squat_build_subspace.restype = i32
+    L.squat_build_subspace.argtypes = [vp, i32, i64, i32, i32, i32, i64, i64, i32, vp, vp, vp, vp, sz, vp]
+    L.squat_prepare_workspace.restype = sz
+    L.squat_prepare_workspace.argtypes = [i32, i32, i32, i32]
+    L.squat_prepare.restype = i32
+    L.squat_prepare.argtypes = [vp, i32, i32, i32, f32, i32, vp, vp, sz, vp]
+    L.squat_quantize_keys.restype = i32
+    L.squat_quantize_keys.argtypes = [vp, i32, i64, i32, i64, i32, i64, i64, i64, vp, i64, i32, i32, i32,
+                                      vp, vp, vp, vp]
+    L.squat_dequantize_keys.restype = i32
+    L.squat_dequantize_keys.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i32, i64, i64, i64, vp]
+    _lib = L
+    return L
+
+
+def version() -> int:
+    return int(lib().squat_version())
+
+
+def strerror(status: int) -> str:
+    return lib().squat_strerror(int(status)).decode()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("libsquat takes device tensors only")
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def build_subspace_workspace(n_tokens: int, n_kv_heads: int, q_per_kv: int, d: int, r: int) -> int:
+    return int(lib().squat_build_subspace_workspace(n_tokens, n_kv_heads, q_per_kv, d, r))
+
+
+def build_subspace(q: torch.Tensor, q_per_kv: int, r: int, *, want_eig: bool = True, want_gram: bool = False,
+                   qhat=None, eig=None, gram=None, ws=None, stream=None):
+    """squat_build_subspace.  q: [n_kv_heads*q_per_kv, n_tokens, d] (last dim contiguous).
+    Returns (qhat [n_kv, r, d] f32, eig [n_kv, r] f32 or None, gram [n_kv, d, d] f32 or None)."""
+    _need_cuda(q)
+    hq, n, d = q.shape
+    if q.stride(2) != 1 or hq % q_per_kv:
+        raise ValueError("q must be [heads, tokens, d] with unit channel stride")
+    n_kv = hq // q_per_kv
+    dev = q.device
+    if qhat is None:
+        qhat = torch.empty((n_kv, r, d), dtype=torch.float32, device=dev)
+    if eig is None and want_eig:
+        eig = torch.empty((n_kv, r), dtype=torch.float32, device=dev)
+    if gram is None and want_gram:
+        gram = torch.empty((n_kv, d, d), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = _ws(build_subspace_workspace(n, n_kv, q_per_kv, d, r), dev)
+    rc = lib().squat_build_subspace(_ptr(q), _DT[q.dtype], n, n_kv, q_per_kv, d, q.stride(0), q.stride(1), r,
+                                    _ptr(qhat) if r > 0 else None, _ptr(eig), _ptr(gram), _ptr(ws), ws.numel(),
+                                    _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_build_subspace")
+    return qhat, eig, gram
+
+
+def prepare_workspace(n_heads: int, d: int, r: int, g: int) -> int:
+    return int(lib().squat_prepare_workspace(n_heads, d, r, g))
+
+
+def prepare(qhat: torch.Tensor, lam: float, g: int, *, update=None, ws=None, stream=None) -> torch.Tensor:
+    """squat_prepare.  qhat: [n_heads, r, d] f32 dense -> update [n_heads, d, d] f32."""
+    _need_cuda(qhat)
+    if qhat.dtype != torch.float32 or not qhat.is_contiguous():
+        raise ValueError("qhat must be dense float32")
+    h, r, d = qhat.shape
+    if update is None:
+        update = torch.empty((h, d, d), dtype=torch.float32, device=qhat.device)
+    if ws is None:
+        ws = _ws(prepare_workspace(h, d, r, g), qhat.device)
+    rc = lib().squat_prepare(_ptr(qhat) if r > 0 else None, h, d, r, float(lam), g, _ptr(update), _ptr(ws),
+                             ws.numel(), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_prepare")
+    return update
+
+
+def quantize_keys(k: torch.Tensor, update: Optional[torch.Tensor], bits: int, group: int, g: int, *,
+                  codes=None, scale=None, zero=None, stream=None):
+    """squat_quantize_keys.  k: [n_batch, n_heads, n_tokens, d]; update: [n_heads, d, d] f32 shared
+    across the batch, or [n_batch, n_heads, d, d], or None (plain round-to-nearest).
+    Returns (codes uint32 viewed as int32 [B,H,n,d*bits/32], scale f16 [B,H,n,d/group], zero f16)."""
+    _need_cuda(k, update)
+    b, h, n, d = k.shape
+    if k.stride(3) != 1:
+        raise ValueError("k must have unit channel stride")
+    dev = k.device
+    usb = 0
+    if update is not None:
+        if update.dtype != torch.float32 or not update.is_contiguous():
+            raise ValueError("update must be dense float32")
+        if update.dim() == 4:
+            usb = update.stride(0)
+    if codes is None:
+        codes = torch.empty((b, h, n, d * bits // 32), dtype=torch.int32, device=dev)
+    if scale is None:
+        scale = torch.empty((b, h, n, d // group), dtype=torch.float16, device=dev)
+    if zero is None:
+        zero = torch.empty((b, h, n, d // group), dtype=torch.float16, device=dev)
+    rc = lib().squat_quantize_keys(_ptr(k), _DT[k.dtype], b, h, n, d, k.stride(0), k.stride(1), k.stride(2),
+                                   _ptr(update), usb, bits, group, g, _ptr(codes), _ptr(scale), _ptr(zero),
+                                   _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_quantize_keys")
+    return codes, scale, zero
+
+
+def dequantize_keys(codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor, bits: int, group: int,
+                    out_dtype=torch.bfloat16, *, out=None, stream=None) -> torch.Tensor:
+    """squat_dequantize_keys.  Dense codes/scale/zero as written by quantize_keys -> k [B,H,n,d]."""
+    _need_cuda(codes, scale, zero)
+    b, h, n, w = codes.shape
+    d = w * 32 // bits
+    if not (codes.is_contiguous() and scale.is_contiguous() and zero.is_contiguous()):
+        raise ValueError("codes/scale/zero must be dense")
+    if out is None:
+        out = torch.empty((b, h, n, d), dtype=out_dtype, device=codes.device)
+    rc = lib().squat_dequantize_keys(_ptr(codes), _ptr(scale), _ptr(zero), b, h, n, d, bits, group, _ptr(out),
+                                     _DT[out.dtype], out.stride(0), out.stride(1), out.stride(2), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_dequantize_keys")
+    return out

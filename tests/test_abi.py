@@ -1,0 +1,93 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every
+symbol the header declares, and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_24358_amd import squat
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "squat.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(squat_[a-z_]+)\s*\(", header))
+    assert declared == set(squat.SYMBOLS)
+    L = squat.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_version_and_strerror():
+    assert squat.version() >= 100
+    assert squat.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert squat.strerror(code) not in ("ok", "unknown status")
+    assert squat.strerror(-99) == "unknown status"
+
+
+def test_workspace_queries():
+    assert squat.build_subspace_workspace(4096, 32, 1, 128, 16) >= 32 * 128 * 128 * 8
+    assert squat.build_subspace_workspace(4096, 32, 1, 64, 16) == 0      # d != 128
+    assert squat.prepare_workspace(8, 128, 16, 32) >= 8 * 3 * 16 * (32 + 128) * 8
+    assert squat.prepare_workspace(8, 128, 16, 48) == 0
+
+
+def test_argument_validation_happens_before_any_launch():
+    L = squat.lib()
+    fake = ctypes.c_void_p(0x1000)            # aligned, never dereferenced: every call below must fail first
+    odd = ctypes.c_void_p(0x1004)
+    q = lambda **kw: L.squat_quantize_keys(  # noqa: E731
+        kw.get("k", fake), kw.get("dt", 2), kw.get("b", 1), kw.get("h", 1), kw.get("n", 32), kw.get("d", 128),
+        kw.get("sb", 4096), kw.get("sh", 4096), kw.get("st", 128), kw.get("u", None), 0, kw.get("bits", 2),
+        kw.get("G", 32), kw.get("g", 32), kw.get("codes", fake), fake, fake, None)
+    assert q(d=64) == -2
+    assert q(bits=3) == -2
+    assert q(G=48) == -2
+    assert q(g=16) == -2
+    assert q(dt=7) == -3
+    assert q(k=None) == -1
+    assert q(codes=None) == -1
+    assert q(st=120) == -2          # rows would overlap
+    assert q(st=132) == -4          # not a multiple of 8 elements
+    assert q(k=odd) == -4
+    assert q(n=0) == 0              # empty input: nothing to do, nothing launched
+    assert q(n=-1) == -2
+
+    dq = lambda **kw: L.squat_dequantize_keys(  # noqa: E731
+        kw.get("codes", fake), fake, fake, 1, 1, kw.get("n", 32), kw.get("d", 128), kw.get("bits", 2),
+        kw.get("G", 32), kw.get("out", fake), kw.get("dt", 2), 4096, 4096, kw.get("st", 128), None)
+    assert dq(d=256) == -2
+    assert dq(bits=8) == -2
+    assert dq(out=None) == -1
+    assert dq(dt=5) == -3
+    assert dq(st=130) == -4
+    assert dq(n=0) == 0
+
+    bs = lambda **kw: L.squat_build_subspace(  # noqa: E731
+        kw.get("q", fake), kw.get("dt", 2), kw.get("n", 64), kw.get("h", 1), kw.get("qpk", 1), kw.get("d", 128),
+        8192, 128, kw.get("r", 8), kw.get("qhat", fake), None, None, kw.get("ws", fake), kw.get("wsb", 1 << 30), None)
+    assert bs(d=96) == -2
+    assert bs(r=129) == -2
+    assert bs(r=-1) == -2
+    assert bs(n=0) == -2
+    assert bs(q=None) == -1
+    assert bs(qhat=None) == -1
+    assert bs(ws=None) == -5
+    assert bs(wsb=16) == -5
+    assert bs(dt=9) == -3
+
+    pr = lambda **kw: L.squat_prepare(  # noqa: E731
+        kw.get("qhat", fake), 1, kw.get("d", 128), kw.get("r", 8), kw.get("lam", 1e-3), kw.get("g", 32),
+        kw.get("u", fake), kw.get("ws", fake), kw.get("wsb", 1 << 30), None)
+    assert pr(d=64) == -2
+    assert pr(g=24) == -2
+    assert pr(lam=-1.0) == -7
+    assert pr(lam=float("nan")) == -7
+    assert pr(u=None) == -1
+    assert pr(qhat=None) == -1
+    assert pr(ws=None) == -5
+    assert pr(wsb=8) == -5

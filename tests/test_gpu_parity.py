@@ -1,0 +1,360 @@
+"""GPU parity: the HIP path, called through the C ABI (ctypes binding), against
+the float64 oracle on the same seeded inputs, element by element.
+
+Tolerances (from the build's stated target):
+  * integer codes bit-exact, except where the float64 pre-rounding value lies
+    within 1e-5 (in units of the group scale) of a rounding boundary -- checked
+    with the oracle's teacher-forced replay; such cases, and all free-running
+    code differences, must stay <= 0.01 % of codes;
+  * dequantized keys / update matrices / subspace projectors: relative error
+    <= 1e-3 (observed far smaller; the asserts use tighter figures where the
+    arithmetic allows).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import squat_oracle as O
+from paper_2503_24358_amd import squat, synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+MISMATCH_BUDGET = 1e-4      # 0.01 % of codes
+
+
+def _keys(seed, heads, n, dtype, heavy=False, batch=None):
+    x32 = synth.keys(seed, heads, n, heavy_tail=heavy, batch=batch)
+    raw, val = synth.store(x32, dtype)
+    return util.to_device(raw, dtype), val
+
+
+def _oracle_U(seed, heads, r, lam, g, qscale=25.0):
+    gen = synth.rng(seed)
+    Qh = gen.standard_normal((heads, r, 128)) * qscale
+    U = np.stack([O.update_matrix_lowrank(Qh[h], lam, g) for h in range(heads)])
+    return Qh, U.astype(np.float32)
+
+
+def _unpack(codes_t, scale_t, zero_t, bits):
+    codes = O.unpack_codes(util.codes_to_host(codes_t), bits)
+    return codes, util.half_to_host(scale_t), util.half_to_host(zero_t)
+
+
+# ------------------------------------------------------------------ dequantize
+@pytest.mark.parametrize("bits,G", [(2, 32), (4, 32), (2, 128), (4, 64)])
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float16, torch.float32])
+def test_dequantize_matches_definition(bits, G, out_dtype):
+    gen = synth.rng(100 + bits + G)
+    B, H, n, d = 2, 3, 167, 128
+    codes = gen.integers(0, 1 << bits, size=(B, H, n, d)).astype(np.uint8)
+    scale = (gen.uniform(0.01, 3.0, size=(B, H, n, d // G))).astype(np.float16)
+    zero = (gen.standard_normal((B, H, n, d // G)) * 4).astype(np.float16)
+    words = O.pack_codes(codes, bits)
+    got = squat.dequantize_keys(torch.from_numpy(words.view(np.int32)).cuda(), torch.from_numpy(scale).cuda(),
+                                torch.from_numpy(zero).cuda(), bits, G, out_dtype)
+    torch.cuda.synchronize()
+    exact = O.dequantize_keys(codes, scale, zero, G)
+    want = util.round_to(exact, out_dtype)
+    g64 = util.out_to_f64(got)
+    # fp32 fma then one rounding to the output type: identical to rounding the exact value
+    # except for double-rounding ties
+    bad = g64 != want
+    assert bad.mean() <= 1e-4
+    assert np.linalg.norm(g64 - exact) <= 1e-3 * np.linalg.norm(exact)
+    if out_dtype == torch.float32:
+        assert np.abs(g64 - exact).max() <= 1e-6 * np.abs(exact).max()
+
+
+def test_dequantize_strided_output_and_empty():
+    gen = synth.rng(7)
+    B, H, n, d = 1, 2, 40, 128
+    codes = gen.integers(0, 4, size=(B, H, n, d)).astype(np.uint8)
+    scale = gen.uniform(0.1, 1.0, size=(B, H, n, 4)).astype(np.float16)
+    zero = gen.standard_normal((B, H, n, 4)).astype(np.float16)
+    words = torch.from_numpy(O.pack_codes(codes, 2).view(np.int32)).cuda()
+    big = torch.full((B, H, n, 256), -7.0, dtype=torch.bfloat16, device="cuda")
+    out = big[..., :128]
+    squat.dequantize_keys(words, torch.from_numpy(scale).cuda(), torch.from_numpy(zero).cuda(), 2, 32, out=out)
+    torch.cuda.synchronize()
+    want = util.round_to(O.dequantize_keys(codes, scale, zero, 32), torch.bfloat16)
+    assert np.array_equal(util.out_to_f64(out), want)
+    assert torch.all(big[..., 128:] == -7.0)
+    e = squat.dequantize_keys(words[:, :, :0], torch.from_numpy(scale).cuda()[:, :, :0].contiguous(),
+                              torch.from_numpy(zero).cuda()[:, :, :0].contiguous(), 2, 32)
+    assert e.shape == (1, 2, 0, 128)
+
+
+# ---------------------------------------------------------- quantize, r = 0
+@pytest.mark.parametrize("bits,G", [(2, 32), (4, 32), (2, 64), (4, 128), (2, 128)])
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16, synth.F32])
+def test_quantize_rtn_bit_exact(bits, G, dtype):
+    """update = NULL must be plain per-group round-to-nearest.  For 16-bit inputs
+    the statistics are exact in fp32, so only double-rounding of the scale can differ."""
+    B, H, n = 2, 3, 167
+    kt, kval = _keys(11 + bits + G, H, n, dtype, batch=B)
+    codes_t, scale_t, zero_t = squat.quantize_keys(kt, None, bits, G, 32)
+    torch.cuda.synchronize()
+    codes, scale, zero = _unpack(codes_t, scale_t, zero_t, bits)
+    tot = dict(code_diff=0, code_unexplained=0, meta_diff=0, meta_unexplained=0, n_codes=0)
+    for b in range(B):
+        for h in range(H):
+            ref = O.quantize_keys(kval[b, h], None, bits, G, 128)
+            assert np.array_equal(zero[b, h], ref["zero"])
+            rep = O.replay_classify(kval[b, h], None, bits, G, 128, codes[b, h], scale[b, h], zero[b, h])
+            for k in tot:
+                tot[k] += rep[k]
+            same = np.array_equal(scale[b, h], ref["scale"])
+            if same:
+                assert np.array_equal(codes[b, h], ref["codes"])
+    assert tot["code_unexplained"] == 0 and tot["meta_unexplained"] == 0
+    assert tot["code_diff"] <= MISMATCH_BUDGET * tot["n_codes"]
+    assert tot["meta_diff"] <= 2
+
+
+# ------------------------------------------------ quantize with propagation
+def _check_against_oracle(kt, kval, U_np, bits, G, g, *, per_batch_U=False, budget=MISMATCH_BUDGET):
+    """kt [B,H,n,128] on device, kval float64 same shape; U_np [H,128,128] (or [B,H,..]) float32."""
+    Ut = None if U_np is None else torch.from_numpy(U_np).cuda()
+    codes_t, scale_t, zero_t = squat.quantize_keys(kt, Ut, bits, G, g)
+    back_t = squat.dequantize_keys(codes_t, scale_t, zero_t, bits, G, torch.float32)
+    torch.cuda.synchronize()
+    codes, scale, zero = _unpack(codes_t, scale_t, zero_t, bits)
+    back = util.out_to_f64(back_t)
+    B, H = kval.shape[:2]
+    tot = dict(code_diff=0, code_unexplained=0, meta_diff=0, meta_unexplained=0, n_codes=0, n_meta=0)
+    free_diff = 0
+    worst_rel = 0.0
+    for b in range(B):
+        for h in range(H):
+            Uh = None if U_np is None else (U_np[b, h] if per_batch_U else U_np[h]).astype(np.float64)
+            ref = O.quantize_keys(kval[b, h], Uh, bits, G, g)
+            free_diff += int((ref["codes"] != codes[b, h]).sum())
+            rep = O.replay_classify(kval[b, h], Uh, bits, G, g, codes[b, h], scale[b, h], zero[b, h])
+            for k in tot:
+                tot[k] += rep[k]
+            # the GPU's own dequantize of the GPU's codes is exactly the definition
+            mine = O.dequantize_keys(codes[b, h], scale[b, h], zero[b, h], G)
+            assert np.abs(back[b, h] - mine).max() <= 1e-6 * max(1.0, np.abs(mine).max())
+            # dequantized keys agree with the oracle's wherever the discrete decisions agree (a
+            # flipped code or fp16 scale is a different, equally valid rounding, counted above)
+            same = (ref["codes"] == codes[b, h]).all(axis=1) & (ref["scale"] == scale[b, h]).all(axis=1) \
+                & (ref["zero"] == zero[b, h]).all(axis=1)
+            if same.any():
+                rel = np.linalg.norm(back[b, h][same] - ref["xhat"][same]) / max(np.linalg.norm(ref["xhat"][same]), 1e-30)
+                worst_rel = max(worst_rel, rel)
+    assert tot["code_unexplained"] == 0, tot
+    assert tot["meta_unexplained"] == 0, tot
+    assert tot["code_diff"] <= budget * tot["n_codes"], tot
+    assert free_diff <= budget * tot["n_codes"], (free_diff, tot)
+    assert worst_rel <= 1e-6, worst_rel
+    return tot, free_diff
+
+
+@pytest.mark.parametrize("bits,G,g", [(2, 32, 32), (4, 32, 32), (2, 32, 64), (4, 64, 64), (2, 128, 32), (2, 64, 32),
+                                      (4, 128, 64), (2, 32, 128)])
+def test_quantize_with_update_matches_oracle(bits, G, g):
+    B, H, n = 2, 4, 1031          # 32 full tiles and a ragged tail of 7
+    kt, kval = _keys(200 + bits + G + g, H, n, synth.BF16, batch=B)
+    _, U = _oracle_U(300 + g, H, 16, 1e-3, g)
+    _check_against_oracle(kt, kval, U, bits, G, g)
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.F16])
+def test_quantize_with_update_other_input_dtypes(dtype):
+    B, H, n = 1, 2, 523
+    kt, kval = _keys(400, H, n, dtype, batch=B)
+    _, U = _oracle_U(401, H, 8, 1e-3, 32)
+    _check_against_oracle(kt, kval, U, 2, 32, 32)
+
+
+def test_quantize_hard_constraint_and_heavy_tails():
+    B, H, n = 1, 3, 777
+    kt, kval = _keys(500, H, n, synth.BF16, heavy=True, batch=B)
+    Qh, U = _oracle_U(501, H, 16, np.inf, 32, qscale=1.0)
+    tot, _ = _check_against_oracle(kt, kval, U, 2, 32, 32)
+    # the invariant the hard constraint buys, on the GPU's own output: the projection of the error
+    # equals the projection of the last block's own rounding error (checked through the oracle replay
+    # being clean: identical codes imply identical states up to fp32), so just sanity-check SQuat < RTN
+    Ut = torch.from_numpy(U).cuda()
+    c, s, z = squat.quantize_keys(kt, Ut, 2, 32, 32)
+    c0, s0, z0 = squat.quantize_keys(kt, None, 2, 32, 32)
+    sq = util.out_to_f64(squat.dequantize_keys(c, s, z, 2, 32, torch.float32))
+    rt = util.out_to_f64(squat.dequantize_keys(c0, s0, z0, 2, 32, torch.float32))
+    for h in range(H):
+        e_sq = (sq[0, h] - kval[0, h]) @ Qh[h].T
+        e_rt = (rt[0, h] - kval[0, h]) @ Qh[h].T
+        assert np.mean(e_sq ** 2) < np.mean(e_rt ** 2)
+
+
+def test_quantize_per_batch_update_and_shared_update():
+    B, H, n = 3, 2, 96
+    kt, kval = _keys(600, H, n, synth.BF16, batch=B)
+    gen = synth.rng(601)
+    Qh = gen.standard_normal((B, H, 8, 128)) * 20
+    U = np.stack([[O.update_matrix_lowrank(Qh[b, h], 1e-3, 32) for h in range(H)] for b in range(B)]).astype(np.float32)
+    _check_against_oracle(kt, kval, U, 2, 32, 32, per_batch_U=True)
+    _check_against_oracle(kt, kval, U[0], 2, 32, 32)
+
+
+def test_quantize_strided_keys_and_tiny_token_counts():
+    H = 2
+    _, U = _oracle_U(700, H, 8, 1e-3, 32)
+    for n in (1, 31, 32, 33):
+        x32 = synth.keys(701 + n, H, n, batch=1)
+        raw, val = synth.store(x32, synth.BF16)
+        dense = util.to_device(raw, synth.BF16)
+        big = torch.zeros((1, H, n, 384), dtype=torch.bfloat16, device="cuda")
+        big[..., 128:256] = dense
+        view = big[..., 128:256]
+        tot, _ = _check_against_oracle(view, val, U, 2, 32, 32, budget=1.0)
+        assert tot["code_diff"] <= 1
+
+
+def test_quantize_degenerate_groups():
+    """Constant groups (scale 0), a constant that fp16 cannot hold, zeros, and huge offsets."""
+    H, n = 1, 64
+    x = synth.keys(800, H, n, batch=1, outliers=None)
+    x[0, 0, 0, :] = 0.0                       # all-zero key
+    x[0, 0, 1, :32] = 1e-6                    # constant group whose value fp16 cannot hold exactly
+    x[0, 0, 2, 32:64] = -3.0                  # constant group, exact
+    x[0, 0, 3, :] = 1000.0 + x[0, 0, 3, :]    # large offset, small range
+    x[0, 0, 4, 96:] = 5.5                     # constant last group
+    raw, val = synth.store(x, synth.BF16)
+    kt = util.to_device(raw, synth.BF16)
+    _, U = _oracle_U(801, H, 8, 1e-2, 32)
+    for bits in (2, 4):
+        tot, free = _check_against_oracle(kt, val, U, bits, 32, 32, budget=1.0)
+        assert tot["code_diff"] <= 2
+    x[0, 0, 1, :32] = 0.1                     # fp32 input: 0.1 is not an fp16 number
+    raw32, val32 = synth.store(x, synth.F32)
+    tot, free = _check_against_oracle(util.to_device(raw32, synth.F32), val32, U, 2, 32, 32, budget=1.0)
+    assert tot["code_diff"] <= 2
+    codes_t, scale_t, zero_t = squat.quantize_keys(kt, torch.from_numpy(U).cuda(), 2, 32, 32)
+    scale = util.half_to_host(scale_t)
+    assert scale[0, 0, 0, 0] == 0 and scale[0, 0, 1, 0] == 0 and scale[0, 0, 2, 1] == 0
+
+
+def test_quantize_is_deterministic():
+    kt, _ = _keys(900, 4, 640, synth.BF16, batch=2)
+    _, U = _oracle_U(901, 4, 16, 1e-3, 32)
+    Ut = torch.from_numpy(U).cuda()
+    a = squat.quantize_keys(kt, Ut, 2, 32, 32)
+    b = squat.quantize_keys(kt, Ut, 2, 32, 32)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_decode_flush_shape():
+    """Config 4 in miniature: many sequences x (layers*heads), one 32-token tile each, U shared across batch."""
+    B, H, n = 16, 24, 32
+    kt, kval = _keys(1000, H, n, synth.BF16, batch=B)
+    _, U = _oracle_U(1001, H, 16, 1e-3, 32)
+    _check_against_oracle(kt, kval, U, 2, 32, 32)
+
+
+# -------------------------------------------------------------------- subspace
+def _queries(seed, hq, n, dtype, planted=12):
+    x32 = synth.queries(seed, hq, n, planted_rank=planted)
+    raw, val = synth.store(x32, dtype)
+    return util.to_device(raw, dtype), val
+
+
+@pytest.mark.parametrize("dtype,hq,qpk,n", [(synth.BF16, 8, 4, 1000), (synth.F32, 2, 1, 512), (synth.F16, 4, 2, 333),
+                                            (synth.BF16, 3, 1, 17)])
+def test_gram_and_subspace_match_oracle(dtype, hq, qpk, n):
+    r = 8
+    qt, qval = _queries(1100 + n, hq, n, dtype)
+    qhat_t, eig_t, gram_t = squat.build_subspace(qt, qpk, r, want_gram=True)
+    torch.cuda.synchronize()
+    qhat, eig, gram = (t.cpu().numpy().astype(np.float64) for t in (qhat_t, eig_t, gram_t))
+    for j in range(hq // qpk):
+        Gm = O.gram(qval[j * qpk:(j + 1) * qpk])
+        assert np.linalg.norm(gram[j] - Gm) <= 2e-6 * np.linalg.norm(Gm)
+        assert np.array_equal(gram[j], gram[j].T)
+        Qh, ev = O.subspace(qval[j * qpk:(j + 1) * qpk], r)
+        k = min(r, qpk * n)
+        assert np.allclose(eig[j, :k], ev[:k], rtol=1e-5)
+        # compare what is unique: the projector-like matrix Qhat^T Qhat (eigenvector signs and the
+        # basis inside near-degenerate clusters are free), scaled by the gap below the r-th eigenvalue
+        full = np.linalg.eigvalsh(Gm)[::-1]
+        gap = (full[k - 1] - full[k]) / full[0] if k < 128 else 1.0
+        err = np.linalg.norm(qhat[j].T @ qhat[j] - Qh.T @ Qh) / np.linalg.norm(Qh.T @ Qh)
+        assert err <= 1e-3 and err <= 1e-5 / max(gap, 1e-3), (err, gap)
+        # rows are sigma_i v_i: check the eigen-equation directly
+        for i in range(k):
+            v = qhat[j, i] / np.sqrt(eig[j, i])
+            assert np.linalg.norm(Gm @ v - eig[j, i] * v) <= 1e-4 * eig[j, 0]
+            assert v[np.argmax(np.abs(v))] > 0
+        if k < r:
+            assert np.abs(qhat[j, k:]).max() <= 1e-3 * np.sqrt(ev[0])
+
+
+def test_subspace_rank_edge_cases():
+    qt, qval = _queries(1200, 2, 64, synth.BF16, planted=0)
+    q0, e0, _ = squat.build_subspace(qt, 1, 0)
+    assert q0.shape == (2, 0, 128)
+    qf, ef, _ = squat.build_subspace(qt, 1, 128)         # r = d, and rank(Q) = 64 < r
+    torch.cuda.synchronize()
+    qf = qf.cpu().numpy().astype(np.float64)
+    for h in range(2):
+        Gm = O.gram(qval[h])
+        assert np.linalg.norm(qf[h].T @ qf[h] - Gm) <= 1e-5 * np.linalg.norm(Gm)
+
+
+# --------------------------------------------------------------------- prepare
+@pytest.mark.parametrize("r,lam,g", [(16, 1e-3, 32), (5, 1e-3, 64), (40, 5e-4, 64), (32, 1e-3, 32), (7, 0.5, 32),
+                                     (16, np.inf, 32), (60, 5e-4, 32), (128, 1e-3, 32), (16, 1e-3, 128), (16, 0.0, 32),
+                                     (0, 1e-3, 32)])
+def test_prepare_matches_oracle(r, lam, g):
+    H = 3
+    gen = synth.rng(1300 + r)
+    Qh = (gen.standard_normal((H, r, 128)) * (np.linspace(60, 5, r)[None, :, None] if r else 1.0)).astype(np.float32)
+    Ut = squat.prepare(torch.from_numpy(Qh).cuda(), lam, g)
+    torch.cuda.synchronize()
+    U = Ut.cpu().numpy().astype(np.float64)
+    for h in range(H):
+        ref = O.update_matrix_lowrank(Qh[h].astype(np.float64), lam, g)
+        denom = max(np.linalg.norm(ref), 1e-30)
+        assert np.linalg.norm(U[h] - ref) <= 1e-5 * denom + 1e-12, (np.linalg.norm(U[h] - ref), denom)
+        for t in range(128 // g):
+            assert not U[h][t * g:(t + 1) * g, t * g:].any()
+
+
+def test_prepare_hard_rank_deficient_tail():
+    """lambda = +inf with r larger than the remaining channels of the last panel: pinv, not inverse."""
+    H, r, g = 2, 48, 32
+    gen = synth.rng(1400)
+    Qh = gen.standard_normal((H, r, 128)).astype(np.float32)
+    U = squat.prepare(torch.from_numpy(Qh).cuda(), float("inf"), g).cpu().numpy().astype(np.float64)
+    for h in range(H):
+        ref = O.update_matrix_lowrank(Qh[h].astype(np.float64), np.inf, g)
+        assert np.linalg.norm(U[h] - ref) <= 1e-5 * np.linalg.norm(ref)
+
+
+# ------------------------------------------------------------------ end to end
+def test_chained_path_end_to_end():
+    """build_subspace -> prepare -> quantize -> dequantize on the GPU, each stage also replayed by the
+    oracle from the GPU's previous output, so stage errors do not compound in the comparison."""
+    hq, qpk, n, r, lam, g = 8, 4, 2048, 16, 1e-3, 32
+    H = hq // qpk
+    qt, qval = _queries(1500, hq, n, synth.BF16)
+    kt, kval = _keys(1501, H, n, synth.BF16, batch=1)
+    qhat_t, eig_t, _ = squat.build_subspace(qt, qpk, r)
+    U_t = squat.prepare(qhat_t, lam, g)
+    codes_t, scale_t, zero_t = squat.quantize_keys(kt, U_t, 2, 32, g)
+    back_t = squat.dequantize_keys(codes_t, scale_t, zero_t, 2, 32, torch.bfloat16)
+    torch.cuda.synchronize()
+    qhat = qhat_t.cpu().numpy().astype(np.float64)
+    U = U_t.cpu().numpy()
+    for h in range(H):
+        ref_U = O.update_matrix_lemma(qhat[h], lam, g)
+        assert np.linalg.norm(U[h] - ref_U) <= 1e-5 * np.linalg.norm(ref_U)
+        Qh, _ = O.subspace(qval[h * qpk:(h + 1) * qpk], r)
+        assert np.linalg.norm(qhat[h].T @ qhat[h] - Qh.T @ Qh) <= 1e-3 * np.linalg.norm(Qh.T @ Qh)
+    _check_against_oracle(kt, kval, U, 2, 32, g)
+    codes, scale, zero = _unpack(codes_t, scale_t, zero_t, 2)
+    want = util.round_to(O.dequantize_keys(codes, scale, zero, 32), torch.bfloat16)
+    got = util.out_to_f64(back_t)
+    assert (got != want).mean() <= 1e-4
