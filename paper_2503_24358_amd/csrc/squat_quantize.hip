@@ -92,9 +92,11 @@ __device__ __forceinline__ void load16(const unsigned char* src, float* out) {
                     out[8 * i + 2 * w + 0] = as_f32(v[w] << 16);
                     out[8 * i + 2 * w + 1] = as_f32(v[w] & 0xFFFF0000u);
                 } else {
-                    half2v h = __builtin_bit_cast(half2v, v[w]);
-                    out[8 * i + 2 * w + 0] = static_cast<float>(h[0]);
-                    out[8 * i + 2 * w + 1] = static_cast<float>(h[1]);
+                    const uint32_t word = v[w];
+                    out[8 * i + 2 * w + 0] =
+                        static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(word & 0xFFFFu)));
+                    out[8 * i + 2 * w + 1] =
+                        static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(word >> 16)));
                 }
             }
         }
@@ -255,7 +257,9 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
                         }
                     mn = pair_min(mn);
                     mx = pair_max(mx);
-                    const float dl = (mx - mn) * (1.0f / LV);
+                    // IEEE division: an exact quotient (frequent with 16-bit inputs) must stay exact so
+                    // that a tie of the fp16 rounding below is broken to even, as the definition does
+                    const float dl = __fdiv_rn(mx - mn, LV);
                     const float sh = round_f16(dl, sbits[gi]);
                     g_zero[gi] = round_f16(mn, zbits[gi]);
                     const bool live = sh > 0.0f;
