@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="profiling aid: time only this stage (e.g. quantize_keys); "
+                                               "the other stages run once, untimed, to prepare its inputs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads/layers would shard without communication); "
@@ -89,16 +91,25 @@ def main():
 
     stages = ("build_subspace", "prepare", "quantize_keys", "dequantize_keys")
 
-    def step(ev=None):
+    only = args.only
+
+    def step(ev=None, everything=False):
+        run = lambda name: everything or not only or only == name  # noqa: E731
         if ev: ev[0].record()
-        squat.build_subspace(wl.q, wl.q_per_kv, wl.r, qhat=qhat, eig=eig, ws=ws_sub)
+        if run("build_subspace"):
+            squat.build_subspace(wl.q, wl.q_per_kv, wl.r, qhat=qhat, eig=eig, ws=ws_sub)
         if ev: ev[1].record()
-        squat.prepare(qhat, wl.lam, wl.g, update=update, ws=ws_prep)
+        if run("prepare"):
+            squat.prepare(qhat, wl.lam, wl.g, update=update, ws=ws_prep)
         if ev: ev[2].record()
-        squat.quantize_keys(wl.k, update, wl.bits, wl.group, wl.g, codes=codes, scale=scale, zero=zero)
+        if run("quantize_keys"):
+            squat.quantize_keys(wl.k, update, wl.bits, wl.group, wl.g, codes=codes, scale=scale, zero=zero)
         if ev: ev[3].record()
-        squat.dequantize_keys(codes, scale, zero, wl.bits, wl.group, out=back)
+        if run("dequantize_keys"):
+            squat.dequantize_keys(codes, scale, zero, wl.bits, wl.group, out=back)
         if ev: ev[4].record()
+
+    step(everything=True)
 
     for _ in range(args.warmup):
         step()
@@ -138,6 +149,7 @@ def main():
         "value": n_keys / (ms_per_step * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "only_stage": only or None,
         "config": {"workload": "long-context: %d layers x %d KV heads (x%d query heads), %d tokens/layer, d=128, "
                                "bf16 in, r=%d, lambda=%g, %d-bit, group %d, g=%d; layers stacked along the head axis, "
                                "one launch per stage" % (wl.layers, wl.kv_heads, wl.q_per_kv, n, wl.r, wl.lam,

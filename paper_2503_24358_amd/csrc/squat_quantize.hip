@@ -17,6 +17,8 @@
 // the error is kept in units of the group's scale so that its fp16 split has a
 // fixed range.  Workgroups are persistent and bound to one head: the head's
 // update panels are converted once into LDS, in MFMA A-operand order.
+#include <type_traits>
+
 #include "squat_internal.h"
 
 using namespace squat;
@@ -24,9 +26,10 @@ using namespace squat;
 namespace {
 
 constexpr int NT = kD / 32;          // 32-channel tiles per key
-constexpr int kWaves = 4;            // wavefronts per workgroup
-constexpr float kMagic = 12582912.0f;   // 1.5 * 2^23: adding it rounds to nearest-even integer
-constexpr uint32_t kMagicBits = 0x4B400000u;
+// Wavefronts per workgroup: one workgroup per CU, sized by LDS (update panels + one staging tile per
+// wavefront): 12 waves (3 per SIMD) for 16-bit keys, 6 for fp32 keys.
+__host__ __device__ constexpr int waves_for(int dt) { return dt == SQUAT_F32 ? 6 : 12; }
+constexpr int kWgsPerCU = 1;
 
 struct QuantParams {
     const unsigned char* k;
@@ -40,8 +43,10 @@ struct QuantParams {
     int64_t n_inner;                 // batch entries that share one update matrix
     int n_heads;
     int64_t tiles_per_seq;
-    int64_t units_per_prob;          // n_inner * tiles_per_seq
+    int64_t units_per_prob;          // n_inner * tiles_per_seq, < 2^31
     int wgs_per_prob;
+    uint32_t div_mul;                // unit / tiles_per_seq == (unit * div_mul) >> div_shift for unit < 2^31
+    uint32_t div_shift;
 };
 
 // Tile pairs (jt, s) with a non-zero panel: block(jt) > block(s), BT tiles per block.
@@ -59,13 +64,6 @@ __host__ __device__ constexpr int pair_index(int BT, int jt, int s) {
             ++c;
         }
     return -1;
-}
-
-__host__ __device__ constexpr uint32_t pack_const(int bits) {
-    uint32_t acc = 0;
-    const int items = 32 / bits;
-    for (int i = 0; i < items; ++i) acc = (acc << bits) + kMagicBits;
-    return acc;
 }
 
 template <int DT>
@@ -130,7 +128,8 @@ __device__ __forceinline__ void split8(const float* v, half8& hi, half8& lo) {
 }
 
 template <int BITS, int GT, int BT, int DT>
-__global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const QuantParams p) {
+__global__ void __launch_bounds__(waves_for(DT) * kWave, kWgsPerCU) quantize_kernel(const QuantParams p) {
+    constexpr int kWaves = waves_for(DT);
     constexpr int ES = Elem<DT>::size;
     constexpr int ROWB = kD * ES;                 // bytes of one key
     constexpr int LROW = ROWB + 16;               // padded LDS row: conflict-free b128 column reads
@@ -140,16 +139,15 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
     constexpr int NB = NT / BT;                   // blocks (iterations) per key
     constexpr int NG = NT / GT;                   // groups per key
     constexpr int WPT = BITS / 2;                 // packed words per lane per tile
-    constexpr int IPW = 32 / BITS;                // codes per word
+    constexpr int CPH = 16 / BITS;                // codes per 16-bit half-word
     constexpr float LV = static_cast<float>((1 << BITS) - 1);
-    constexpr uint32_t PCONST = pack_const(BITS);
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     half8* wlds = reinterpret_cast<half8*>(smem);           // [NPAIRS][2 kk][hi, lo][64 lanes]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hh = lane >> 5;
     const int n = lane & 31;
     unsigned char* stage = smem + NPAIRS * 4096 + wave * (32 * LROW);
@@ -159,7 +157,13 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
     const int head = static_cast<int>(prob % p.n_heads);
     const int64_t bo = prob / p.n_heads;
 
+    // Panels whose entries are all fp16 numbers (as squat_prepare writes them) have a zero low part:
+    // the third matrix product is skipped for the whole head.
+    bool need_lo = false;
+    int* lo_flag = reinterpret_cast<int*>(smem + NPAIRS * 4096 + kWaves * (32 * LROW));
     if constexpr (NPAIRS > 0) {
+        if (tid == 0) *lo_flag = 0;
+        __syncthreads();
         // Convert this head's panels once: A operand of pair (jt, s), MFMA kk: lane (ha, m)
         // holds U[32 jt + channel(m)][32 s + 16 ha + 8 kk + 0..7].
         const float* U = p.update + bo * p.usb + static_cast<int64_t>(head) * kD * kD;
@@ -186,32 +190,43 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
             split8(v, hi, lo);
             wlds[((pr * 2 + kk) * 2 + 0) * 64 + l] = hi;
             wlds[((pr * 2 + kk) * 2 + 1) * 64 + l] = lo;
+            const u32x4 lb = __builtin_bit_cast(u32x4, lo);
+            if (((lb[0] | lb[1] | lb[2] | lb[3]) & 0x7FFF7FFFu) != 0u) *lo_flag = 1;
         }
         __syncthreads();
+        need_lo = *lo_flag != 0;
     }
 
-    const int64_t ustride = static_cast<int64_t>(p.wgs_per_prob) * kWaves;
-    int64_t unit = static_cast<int64_t>(wg) * kWaves + wave;
-
+    const uint32_t st32 = static_cast<uint32_t>(p.st);
     u32x4 pre[NLOAD];
-    auto issue_loads = [&](int64_t u) {
-        const int64_t bi = u / p.tiles_per_seq;
-        const int64_t tok0 = (u - bi * p.tiles_per_seq) * kTileTokens;
+    // unit -> (batch entry, first token): exact multiply-shift division by tiles_per_seq (units < 2^31)
+    auto locate = [&](uint32_t u, uint32_t& bi, int64_t& tok0) {
+        bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
+        tok0 = static_cast<int64_t>(u - bi * static_cast<uint32_t>(p.tiles_per_seq)) * kTileTokens;
+    };
+    auto issue_loads = [&](uint32_t u) {
+        uint32_t bi;
+        int64_t tok0;
+        locate(u, bi, tok0);
         const unsigned char* base = p.k + (bo + bi) * p.sb + head * p.sh + tok0 * p.st;
+        const int64_t left = p.n_tokens - tok0;                 // >= 1 valid rows in this tile
+        const int last = left >= kTileTokens ? kTileTokens - 1 : static_cast<int>(left) - 1;
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
             const int flat = i * kWave + lane;
-            const int row = flat / CPR, ch = flat % CPR;
-            if (tok0 + row < p.n_tokens)
-                pre[i] = *reinterpret_cast<const u32x4*>(base + row * p.st + ch * 16);
-            else
-                pre[i] = u32x4{0u, 0u, 0u, 0u};
+            int row = flat / CPR;
+            const int ch = flat % CPR;
+            row = row < last ? row : last;      // rows past the end re-read the last valid key; their outputs are not stored
+            pre[i] = *reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16));
         }
     };
 
-    if (unit < p.units_per_prob) issue_loads(unit);
+    const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
+    const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
+    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
+    if (unit < nunits) issue_loads(unit);
 
-    while (unit < p.units_per_prob) {
+    while (unit < nunits) {
         // ---- registers -> LDS (token-major rows), then read back channel-major per lane
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
@@ -223,7 +238,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        const int64_t cur = unit;
+        const uint32_t cur = unit;
         unit += ustride;
 
         float x[NT][16];
@@ -234,11 +249,12 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 
-        if (unit < p.units_per_prob) issue_loads(unit);   // prefetch the next tile
+        if (unit < nunits) issue_loads(unit);   // prefetch the next tile
 
         uint32_t words[NT][WPT];
         uint16_t sbits[NG], zbits[NG];
         float g_scale[NG], g_inv[NG], g_zero[NG], g_top[NG];
+        bool g_risky[NG];
 
 #pragma unroll
         for (int blk = 0; blk < NB; ++blk) {
@@ -257,9 +273,14 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
                         }
                     mn = pair_min(mn);
                     mx = pair_max(mx);
-                    // IEEE division: an exact quotient (frequent with 16-bit inputs) must stay exact so
-                    // that a tie of the fp16 rounding below is broken to even, as the definition does
-                    const float dl = __fdiv_rn(mx - mn, LV);
+                    // Correctly rounded (max - min) / (2^b - 1) by one Newton step on the rounded
+                    // reciprocal of the constant divisor: an exact quotient (frequent with 16-bit
+                    // inputs) stays exact, so a tie of the fp16 rounding below breaks to even, as the
+                    // definition does.
+                    const float rng = mx - mn;
+                    constexpr float RL = 1.0f / LV;
+                    const float q0 = rng * RL;
+                    const float dl = fmaf(fmaf(-q0, LV, rng), RL, q0);
                     const float sh = round_f16(dl, sbits[gi]);
                     g_zero[gi] = round_f16(mn, zbits[gi]);
                     const bool live = sh > 0.0f;
@@ -269,35 +290,73 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
                     g_scale[gi] = sp;
                     g_inv[gi] = inv;
                     g_top[gi] = live ? LV : 0.0f;
+                    g_risky[gi] = !(sh >= 6.2e-5f) || fabsf(g_zero[gi]) * inv > 256.0f;
                 }
             }
             // ---- quantize and freeze the block; keep its normalised error as MFMA B operands
-            half8 bhi[BT][2], blo[BT][2];
+            // The clamp to [0, 2^b - 1] can only bite when the fp16 rounding of zero/scale moved the
+            // group's ends by more than half a step: scale not a normal fp16 number (incl. 0), or
+            // |zero| / scale > 256.  Otherwise the whole wavefront takes the path without it.
+            bool risky = false;
 #pragma unroll
             for (int jj = 0; jj < BT; ++jj) {
-                const int j = blk * BT + jj;
-                const int gi = j / GT;
-                const float mh = g_zero[gi], inv = g_inv[gi], top = g_top[gi];
-                float et[16];
-#pragma unroll
-                for (int w = WPT - 1; w >= 0; --w) {
-                    uint32_t acc = 0;
-#pragma unroll
-                    for (int e = IPW - 1; e >= 0; --e) {
-                        const int c = w * IPW + e;
-                        const float u = (x[j][c] - mh) * inv;
-                        const float uc = __builtin_amdgcn_fmed3f(u, 0.0f, top);
-                        const float r = uc + kMagic;
-                        acc = (acc << BITS) + as_u32(r);
-                        et[c] = (r - kMagic) - u;
-                    }
-                    words[j][w] = acc - PCONST;
-                }
-                if (blk < NB - 1) {
-                    split8(et, bhi[jj][0], blo[jj][0]);
-                    split8(et + 8, bhi[jj][1], blo[jj][1]);
-                }
+                const int gi = (blk * BT + jj) / GT;
+                risky = risky || g_risky[gi];
             }
+            // A group that spans several blocks (G > g) has its later blocks updated after its statistics
+            // were taken: those can leave the range, so there the clamp is part of the definition.
+            const bool clamp = (GT > BT && (blk * BT) % GT != 0) || __builtin_amdgcn_ballot_w64(risky) != 0ull;
+            u32x4 bhi[BT][2], blo[BT][2];
+            auto quant_block = [&](auto clamp_tag) {
+                constexpr bool CLAMP = decltype(clamp_tag)::value;
+#pragma unroll
+                for (int jj = 0; jj < BT; ++jj) {
+                    const int j = blk * BT + jj;
+                    const int gi = j / GT;
+                    const float mh = g_zero[gi], inv = g_inv[gi], top = g_top[gi];
+                    // codes are collected per half-word as exact small floats (Horner), then converted once
+                    uint32_t hw[16 / CPH];
+                    float eh[16], el[16];
+#pragma unroll
+                    for (int q = 16 / CPH - 1; q >= 0; --q) {
+                        float accf = 0.0f;
+#pragma unroll
+                        for (int e = CPH - 1; e >= 0; --e) {
+                            const int c = q * CPH + e;
+                            const float dd = x[j][c] - mh;
+                            float u = dd * inv;
+                            if constexpr (CLAMP) u = __builtin_amdgcn_fmed3f(u, 0.0f, top);
+                            const float code = __builtin_rintf(u);
+                            accf = fmaf(accf, static_cast<float>(1 << BITS), code);
+                            if (blk < NB - 1) {
+                                // normalised error  code - (x - m)/Delta  split into a part with 11
+                                // significant bits (exact in fp16) and the exact remainder
+                                const float et = fmaf(-inv, dd, code);
+                                eh[c] = as_f32(as_u32(et) & 0xFFFFE000u);
+                                el[c] = et - eh[c];
+                            }
+                        }
+                        hw[q] = static_cast<uint32_t>(accf);
+                    }
+#pragma unroll
+                    for (int w = 0; w < WPT; ++w) words[j][w] = hw[2 * w] | (hw[2 * w + 1] << 16);
+                    if (blk < NB - 1) {
+#pragma unroll
+                        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                bhi[jj][kk][i] = __builtin_bit_cast(
+                                    uint32_t, __builtin_amdgcn_cvt_pkrtz(eh[8 * kk + 2 * i], eh[8 * kk + 2 * i + 1]));
+                                blo[jj][kk][i] = __builtin_bit_cast(
+                                    uint32_t, __builtin_amdgcn_cvt_pkrtz(el[8 * kk + 2 * i], el[8 * kk + 2 * i + 1]));
+                            }
+                    }
+                }
+            };
+            if (clamp)
+                quant_block(std::true_type{});
+            else
+                quant_block(std::false_type{});
             // ---- Lemma 2: remaining channels += U[rest, block] * error
             if constexpr (NPAIRS > 0) {
                 if (blk < NB - 1) {
@@ -311,10 +370,12 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
 #pragma unroll
                             for (int kk = 0; kk < 2; ++kk) {
                                 const half8 whi = wlds[((pr * 2 + kk) * 2 + 0) * 64 + lane];
-                                const half8 wlo = wlds[((pr * 2 + kk) * 2 + 1) * 64 + lane];
-                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, bhi[jj][kk], acc, 0, 0, 0);
-                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, blo[jj][kk], acc, 0, 0, 0);
-                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wlo, bhi[jj][kk], acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, blo[jj][kk]), acc, 0, 0, 0);
+                                if (need_lo) {
+                                    const half8 wlo = wlds[((pr * 2 + kk) * 2 + 1) * 64 + lane];
+                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wlo, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
+                                }
                             }
                             const float sc = g_scale[s / GT];
 #pragma unroll
@@ -326,10 +387,11 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
         }
 
         // ---- outputs
-        const int64_t bi = cur / p.tiles_per_seq;
-        const int64_t tok0 = (cur - bi * p.tiles_per_seq) * kTileTokens;
+        uint32_t bi;
+        int64_t tok0;
+        locate(cur, bi, tok0);
         const bool valid = tok0 + n < p.n_tokens;
-        const int64_t rowid = ((bo + bi) * p.n_heads + head) * p.n_tokens + tok0 + n;
+        const int64_t row0 = ((bo + bi) * p.n_heads + head) * p.n_tokens + tok0;     // wave-uniform
 
         // lower half-wave collects the first half of a key's words, upper the second
 #pragma unroll
@@ -338,7 +400,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
             swap_halves(words[1][w], words[3][w]);
         }
         if (valid) {
-            uint32_t* dst = p.codes + rowid * (NT * 2 * WPT) + hh * (NT * WPT);
+            uint32_t* dst = p.codes + row0 * (NT * 2 * WPT) + (n * (NT * 2 * WPT) + hh * (NT * WPT));
             if constexpr (WPT == 1) {
                 *reinterpret_cast<u32x4*>(dst) = u32x4{words[0][0], words[2][0], words[1][0], words[3][0]};
             } else {
@@ -346,7 +408,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
                 *reinterpret_cast<u32x4*>(dst + 4) = u32x4{words[1][0], words[1][1], words[3][0], words[3][1]};
             }
             // lanes 0..31 write the scales, lanes 32..63 the zero-points
-            uint16_t* mdst = (hh ? p.zero : p.scale) + rowid * NG;
+            uint16_t* mdst = (hh ? p.zero : p.scale) + row0 * NG + n * NG;
             if constexpr (NG == 4) {
                 const uint32_t lo = hh ? (zbits[0] | (uint32_t(zbits[1]) << 16)) : (sbits[0] | (uint32_t(sbits[1]) << 16));
                 const uint32_t hi = hh ? (zbits[2] | (uint32_t(zbits[3]) << 16)) : (sbits[2] | (uint32_t(sbits[3]) << 16));
@@ -364,7 +426,8 @@ __global__ void __launch_bounds__(kWaves * kWave, 2) quantize_kernel(const Quant
 template <int BITS, int GT, int BT, int DT>
 int launch(const QuantParams& p, int64_t n_prob, hipStream_t stream) {
     constexpr int ES = Elem<DT>::size;
-    constexpr size_t lds = n_pairs(BT) * 4096 + kWaves * 32 * (kD * ES + 16);
+    constexpr int kWaves = waves_for(DT);
+    constexpr size_t lds = n_pairs(BT) * 4096 + kWaves * 32 * (kD * ES + 16) + 16;
     auto kern = quantize_kernel<BITS, GT, BT, DT>;
     static bool attr_done = false;      // idempotent; a race only repeats the call
     if (!attr_done) {
@@ -463,11 +526,22 @@ extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_ba
         p.n_inner = n_batch;
     }
     p.units_per_prob = p.n_inner * p.tiles_per_seq;
+    if (p.units_per_prob >= (int64_t(1) << 31) || p.tiles_per_seq >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    if (k_stride_token * es >= (int64_t(1) << 26)) return SQUAT_E_BADSHAPE;
+    {
+        // floor(u / d) for u < 2^31: shift = 31 + ceil(log2 d), mul = floor(2^shift / d) + 1
+        const uint64_t dv = static_cast<uint64_t>(p.tiles_per_seq);
+        uint32_t l = 0;
+        while ((uint64_t(1) << l) < dv) ++l;
+        p.div_shift = 31 + l;
+        p.div_mul = static_cast<uint32_t>(((uint64_t(1) << p.div_shift) / dv) + 1);
+    }
 
     const int cus = device_cu_count();
-    const int64_t target = 2 * static_cast<int64_t>(cus);          // two resident workgroups per CU
+    const int64_t target = kWgsPerCU * static_cast<int64_t>(cus);   // fill every CU once
     int64_t per = (target + n_prob - 1) / n_prob;
-    const int64_t need = (p.units_per_prob + kWaves - 1) / kWaves;
+    const int kw = waves_for(k_dt);
+    const int64_t need = (p.units_per_prob + kw - 1) / kw;
     if (per > need) per = need;
     if (per < 1) per = 1;
     p.wgs_per_prob = static_cast<int>(per);
