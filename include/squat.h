@@ -107,7 +107,10 @@ int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int 
  * form  -Qr^T (I/lambda + Qr Qr^T)^{-1} Qb  (Qb, Qr: the columns of Qhat in
  * and after block t) in fp64.  lambda = +INFINITY selects the limit
  * -pinv(Qr) Qb (the equality constraint of Eq. (1)); lambda = 0 or r = 0
- * gives U = 0 (plain round-to-nearest).
+ * gives U = 0 (plain round-to-nearest).  Every entry is rounded to the nearest
+ * fp16-representable number (relative 2^-12, entries must stay below 65504)
+ * and stored as fp32: squat_quantize_keys detects such a matrix and contracts
+ * with two fp16 matrix passes instead of three.
  *
  *   qhat    [n_heads, r, d] float, dense (NULL allowed only if r == 0).
  *   update  out [n_heads, d, d] float, dense, 16-byte aligned.
@@ -140,6 +143,7 @@ int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, in
  *            base 16-byte aligned, strides multiples of 8 elements.  Not
  *            modified.
  *   update   [n_heads, d, d] float as written by squat_prepare (same g), or
+ *            any fp32 matrix of that block structure with |entries| < 65504, or
  *            NULL.  update_stride_batch (elements) is added per batch entry;
  *            0 shares one matrix per head across the batch (the paper's
  *            batch > 1 rule).

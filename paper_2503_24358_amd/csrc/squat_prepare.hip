@@ -7,7 +7,8 @@
 // One workgroup per (head, t) works in fp64: it forms S = I/lambda + Qr Qr^T in LDS,
 // diagonalises it with the one-sided Jacobi routine (rows a_i = mu_i v_i), and applies
 // S^+ = sum_i a_i a_i^T / mu_i^3.  lambda = +inf drops the I/lambda term and discards the
-// (numerically) zero mu_i, which yields -pinv(Qr) Qb.
+// (numerically) zero mu_i, which yields -pinv(Qr) Qb.  The result is stored as fp32 numbers that are
+// exactly representable in fp16.
 #include <math.h>
 
 #include "squat_internal.h"
@@ -99,7 +100,9 @@ __global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams 
         const int c = idx / g, j = idx % g;
         double s = 0.0;
         for (int i = 0; i < rp; ++i) s += z[i * kD + c] * y[i * g + j];
-        U[(c0 + c) * kD + (c0 - g) + j] = static_cast<float>(-s);
+        // Entries are rounded to the fp16 grid (relative 2^-12): the quantize kernel then needs two
+        // matrix passes instead of three, and both sides of any comparison use this same matrix.
+        U[(c0 + c) * kD + (c0 - g) + j] = static_cast<float>(static_cast<_Float16>(static_cast<float>(-s)));
     }
 }
 

@@ -8,7 +8,8 @@ Tolerances (from the build's stated target):
     code differences, must stay <= 0.01 % of codes;
   * dequantized keys / update matrices / subspace projectors: relative error
     <= 1e-3 (observed far smaller; the asserts use tighter figures where the
-    arithmetic allows).
+    arithmetic allows; the update matrix is stored on the fp16 grid, so its
+    bound is one fp16 rounding, 2^-11 per entry).
 """
 import numpy as np
 import pytest
@@ -304,6 +305,16 @@ def test_subspace_rank_edge_cases():
 
 
 # --------------------------------------------------------------------- prepare
+def _assert_update_matches(U, ref):
+    """squat_prepare computes in fp64 and stores the nearest fp16-representable number: compare with the
+    oracle's matrix rounded the same way (entries may differ by one fp16 step only at rounding midpoints)."""
+    want = ref.astype(np.float16).astype(np.float64)
+    assert np.array_equal(U.astype(np.float16).astype(np.float64), U), "entries must be fp16 numbers"
+    assert (U != want).mean() <= 1e-3
+    assert np.all(np.abs(U - ref) <= 2.0 ** -11 * np.abs(ref) + 2.0 ** -24)
+    assert np.linalg.norm(U - ref) <= 3e-4 * max(np.linalg.norm(ref), 1e-30) + 1e-12
+
+
 @pytest.mark.parametrize("r,lam,g", [(16, 1e-3, 32), (5, 1e-3, 64), (40, 5e-4, 64), (32, 1e-3, 32), (7, 0.5, 32),
                                      (16, np.inf, 32), (60, 5e-4, 32), (128, 1e-3, 32), (16, 1e-3, 128), (16, 0.0, 32),
                                      (0, 1e-3, 32)])
@@ -316,8 +327,7 @@ def test_prepare_matches_oracle(r, lam, g):
     U = Ut.cpu().numpy().astype(np.float64)
     for h in range(H):
         ref = O.update_matrix_lowrank(Qh[h].astype(np.float64), lam, g)
-        denom = max(np.linalg.norm(ref), 1e-30)
-        assert np.linalg.norm(U[h] - ref) <= 1e-5 * denom + 1e-12, (np.linalg.norm(U[h] - ref), denom)
+        _assert_update_matches(U[h], ref)
         for t in range(128 // g):
             assert not U[h][t * g:(t + 1) * g, t * g:].any()
 
@@ -330,7 +340,7 @@ def test_prepare_hard_rank_deficient_tail():
     U = squat.prepare(torch.from_numpy(Qh).cuda(), float("inf"), g).cpu().numpy().astype(np.float64)
     for h in range(H):
         ref = O.update_matrix_lowrank(Qh[h].astype(np.float64), np.inf, g)
-        assert np.linalg.norm(U[h] - ref) <= 1e-5 * np.linalg.norm(ref)
+        _assert_update_matches(U[h], ref)
 
 
 # ------------------------------------------------------------------ end to end
@@ -350,7 +360,7 @@ def test_chained_path_end_to_end():
     U = U_t.cpu().numpy()
     for h in range(H):
         ref_U = O.update_matrix_lemma(qhat[h], lam, g)
-        assert np.linalg.norm(U[h] - ref_U) <= 1e-5 * np.linalg.norm(ref_U)
+        _assert_update_matches(U[h].astype(np.float64), ref_U)
         Qh, _ = O.subspace(qval[h * qpk:(h + 1) * qpk], r)
         assert np.linalg.norm(qhat[h].T @ qhat[h] - Qh.T @ Qh) <= 1e-3 * np.linalg.norm(Qh.T @ Qh)
     _check_against_oracle(kt, kval, U, 2, 32, g)
