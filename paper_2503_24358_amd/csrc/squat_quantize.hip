@@ -217,7 +217,9 @@ __global__ void __launch_bounds__(waves_for(DT) * kWave, kWgsPerCU) quantize_ker
             int row = flat / CPR;
             const int ch = flat % CPR;
             row = row < last ? row : last;      // rows past the end re-read the last valid key; their outputs are not stored
-            pre[i] = *reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16));
+            // streamed once: non-temporal, so the tile does not displace the update panels in L2
+            pre[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16)));
         }
     };
 
@@ -402,20 +404,24 @@ __global__ void __launch_bounds__(waves_for(DT) * kWave, kWgsPerCU) quantize_ker
         if (valid) {
             uint32_t* dst = p.codes + row0 * (NT * 2 * WPT) + (n * (NT * 2 * WPT) + hh * (NT * WPT));
             if constexpr (WPT == 1) {
-                *reinterpret_cast<u32x4*>(dst) = u32x4{words[0][0], words[2][0], words[1][0], words[3][0]};
+                __builtin_nontemporal_store(u32x4{words[0][0], words[2][0], words[1][0], words[3][0]},
+                                            reinterpret_cast<u32x4*>(dst));
             } else {
-                *reinterpret_cast<u32x4*>(dst) = u32x4{words[0][0], words[0][1], words[2][0], words[2][1]};
-                *reinterpret_cast<u32x4*>(dst + 4) = u32x4{words[1][0], words[1][1], words[3][0], words[3][1]};
+                __builtin_nontemporal_store(u32x4{words[0][0], words[0][1], words[2][0], words[2][1]},
+                                            reinterpret_cast<u32x4*>(dst));
+                __builtin_nontemporal_store(u32x4{words[1][0], words[1][1], words[3][0], words[3][1]},
+                                            reinterpret_cast<u32x4*>(dst + 4));
             }
             // lanes 0..31 write the scales, lanes 32..63 the zero-points
             uint16_t* mdst = (hh ? p.zero : p.scale) + row0 * NG + n * NG;
             if constexpr (NG == 4) {
                 const uint32_t lo = hh ? (zbits[0] | (uint32_t(zbits[1]) << 16)) : (sbits[0] | (uint32_t(sbits[1]) << 16));
                 const uint32_t hi = hh ? (zbits[2] | (uint32_t(zbits[3]) << 16)) : (sbits[2] | (uint32_t(sbits[3]) << 16));
-                *reinterpret_cast<u32x2*>(mdst) = u32x2{lo, hi};
+                __builtin_nontemporal_store(u32x2{lo, hi}, reinterpret_cast<u32x2*>(mdst));
             } else if constexpr (NG == 2) {
-                *reinterpret_cast<uint32_t*>(mdst) =
-                    hh ? (zbits[0] | (uint32_t(zbits[1]) << 16)) : (sbits[0] | (uint32_t(sbits[1]) << 16));
+                __builtin_nontemporal_store(
+                    hh ? (zbits[0] | (uint32_t(zbits[1]) << 16)) : (sbits[0] | (uint32_t(sbits[1]) << 16)),
+                    reinterpret_cast<uint32_t*>(mdst));
             } else {
                 *mdst = hh ? zbits[0] : sbits[0];
             }

@@ -93,7 +93,7 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const G
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (tok0 + j < p.n_tokens)
-                raw[j] = *reinterpret_cast<const u32x2*>(base + j * p.st);
+                raw[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + j * p.st));
             else
                 raw[j] = u32x2{0u, 0u};
         }
