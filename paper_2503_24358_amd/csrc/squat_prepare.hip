@@ -61,7 +61,8 @@ __global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams 
         S[idx] = s;
     }
     __syncthreads();
-    jacobi_rows<kPrepThreads, TS>(S, rp, rp, flag, 60, 1e-15);
+    jacobi_rows<kPrepThreads, TS>(S, rp, rp, mu, flag, 60, 1e-15);
+    __syncthreads();
 
     if (tid < rp) {
         double s = 0.0;

@@ -274,7 +274,8 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
     const double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     for (int i = threadIdx.x; i < kD * kD; i += kEigThreads) A[i] = g[i];
     __syncthreads();
-    const int sweeps = jacobi_rows<kEigThreads, 16>(A, kD, kEigLd, flag, 60, 1e-15);
+    const int sweeps = jacobi_rows<kEigThreads, 16>(A, kD, kEigLd, nrm, flag, 60, 1e-15);
+    __syncthreads();
     if (sweeps_out && threadIdx.x == 0) sweeps_out[kvh] = sweeps;
 
     // eigenvalue of row i = its norm
