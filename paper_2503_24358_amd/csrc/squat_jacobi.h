@@ -9,13 +9,18 @@
 // separate eigenvector matrix is kept.  Pairs follow a round-robin tournament
 // (n - 1 rounds of n / 2 disjoint pairs), one team of lanes per pair.
 //
-// Cost per round is kept low in three ways: squared row norms are cached and
-// updated algebraically (one dot product per pair instead of three, refreshed
-// from scratch every sweep); the rotation angle is computed in fp32 (any angle
-// gives an exactly orthogonal rotation; its accuracy only sets how completely
-// one rotation annihilates the pair, and later sweeps finish the job), while
-// cos/sin are normalised in fp64 by Newton steps; team reductions use DPP
-// moves instead of LDS permutes.
+// The per-round instruction count is what bounds this routine, so: squared row
+// norms are cached and updated algebraically (one dot product per pair instead
+// of three, refreshed from scratch every sweep); each lane keeps its slice of
+// both rows in registers between the dot product and the update (16-byte LDS
+// accesses); the rotation angle is computed in fp32 with hardware reciprocal /
+// square-root approximations (ANY angle gives an exactly orthogonal rotation;
+// its accuracy only sets how completely one rotation annihilates the pair, and
+// later sweeps finish the job) while cos/sin are normalised in fp64 by Newton
+// steps; team reductions use DPP moves instead of LDS permutes; the sweep that
+// would only confirm convergence is skipped when the largest relative
+// off-diagonal seen in a sweep is already below sqrt(tol) (Jacobi converges
+// quadratically).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -57,17 +62,20 @@ __device__ __forceinline__ double team_sum(double v) {
     return v;
 }
 
-// A: n x n row-major with leading dimension ld (doubles) in LDS; n even, n/2 * TS <= THREADS.
-// nrm2: n doubles in LDS (scratch for the squared row norms).  `flag` is one int in LDS.
+// A: n x n row-major with leading dimension ld (doubles, even; A 16-byte aligned) in LDS; n even,
+// n/2 * TS <= THREADS, n <= MAXE * TS.  FULL promises n == MAXE * TS (no column predicates).
+// nrm2: n doubles in LDS (scratch for the squared row norms).  `flag`: two ints in LDS.
 // Returns the number of sweeps done.  All threads of the block must call it.
-template <int THREADS, int TS>
+template <int THREADS, int TS, int MAXE, bool FULL>
 __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, int max_sweeps, double tol) {
+    constexpr int MAXP = (MAXE + 1) / 2;     // column pairs per lane
     const int tid = threadIdx.x;
     const int team = tid / TS;
     const int tl = tid % TS;
     const int pairs = n >> 1;
     const int m = n - 1;
-    const double tol2 = tol * tol;
+    const float tol2 = static_cast<float>(tol * tol);
+    const float early2 = static_cast<float>(tol);           // (sqrt(tol))^2
     int sweep = 0;
     for (; sweep < max_sweeps; ++sweep) {
         // refresh the cached squared norms (one team per row, several passes if needed)
@@ -80,7 +88,10 @@ __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, in
             s = team_sum<TS>(s);
             if (tl == 0) nrm2[row] = s;
         }
-        if (tid == 0) *flag = 0;
+        if (tid == 0) {
+            flag[0] = 0;      // any rotation in this sweep
+            flag[1] = 0;      // any pair whose relative off-diagonal exceeded sqrt(tol)
+        }
         __syncthreads();
         for (int round = 0; round < m; ++round) {
             if (team < pairs) {
@@ -89,53 +100,84 @@ __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, in
                     p = m;
                     q = round;
                 } else {
-                    p = (round + team) % m;
-                    q = (round - team + m) % m;
+                    p = round + team;
+                    p = p >= m ? p - m : p;
+                    q = round - team;
+                    q = q < 0 ? q + m : q;
                 }
                 double* x = A + p * ld;
                 double* y = A + q * ld;
-                double ga = 0.0;
-                for (int c = tl; c < n; c += TS) ga += x[c] * y[c];
-                ga = team_sum<TS>(ga);
+                double2 xv[MAXP], yv[MAXP];
+                double g0 = 0.0, g1 = 0.0;
+#pragma unroll
+                for (int e = 0; e < MAXP; ++e) {
+                    const int c = 2 * (tl + e * TS);
+                    if (FULL || c < n) {
+                        xv[e] = *reinterpret_cast<const double2*>(x + c);
+                        yv[e] = *reinterpret_cast<const double2*>(y + c);
+                    } else {
+                        xv[e] = double2{0.0, 0.0};
+                        yv[e] = double2{0.0, 0.0};
+                    }
+                    g0 = fma(xv[e].x, yv[e].x, g0);
+                    g1 = fma(xv[e].y, yv[e].y, g1);
+                }
+                const double ga = team_sum<TS>(g0 + g1);
                 const double al = nrm2[p], be = nrm2[q];
-                if (ga * ga > tol2 * al * be && ga != 0.0) {
-                    // tan of the rotation angle in fp32, cos/sin normalised in fp64
-                    const float gf = static_cast<float>(ga), df = static_cast<float>(be - al);
-                    float zf;
-                    if (fabsf(gf) > 1e-30f && fabsf(df) < 1e30f)
-                        zf = df / (2.0f * gf);
-                    else   // outside fp32's comfortable range: take the ratio in fp64 (rare)
-                        zf = static_cast<float>((be - al) / (2.0 * ga));
-                    float tf;
-                    if (fabsf(zf) < 1e15f)
-                        tf = copysignf(1.0f, zf) / (fabsf(zf) + sqrtf(1.0f + zf * zf));
-                    else
-                        tf = 0.5f / zf;
+                // the decision and the angle only need fp32 (the range guard sends the rare pair whose
+                // magnitudes leave fp32's range through fp64)
+                float gf = static_cast<float>(ga), af = static_cast<float>(al), bf = static_cast<float>(be);
+                float df = static_cast<float>(be - al);
+                const float big = fmaxf(af, bf);
+                if (!(big < 1e18f && big > 1e-18f)) {
+                    // rescale by a power of two: the ratios below are scale-free
+                    int ex;
+                    (void)frexp(fmax(al, be), &ex);
+                    gf = static_cast<float>(ldexp(ga, -ex));
+                    af = static_cast<float>(ldexp(al, -ex));
+                    bf = static_cast<float>(ldexp(be, -ex));
+                    df = static_cast<float>(ldexp(be - al, -ex));
+                }
+                const float g2 = gf * gf, ab = af * bf;
+                if (g2 > tol2 * ab && gf != 0.0f) {
+                    const float zf = df * __builtin_amdgcn_rcpf(2.0f * gf);
+                    const float az = fabsf(zf);
+                    // tan = sign(z) / (|z| + sqrt(1 + z^2));   |z| huge: 1 / (2 z)
+                    const float den = az < 1e18f ? az + __builtin_amdgcn_sqrtf(fmaf(zf, zf, 1.0f)) : 2.0f * az;
+                    const float tf = copysignf(__builtin_amdgcn_rcpf(den), zf);
                     const double t = static_cast<double>(tf);
-                    const double a = 1.0 + t * t;
-                    double cs = static_cast<double>(rsqrtf(static_cast<float>(a)));
-                    cs = cs * (1.5 - 0.5 * a * cs * cs);
-                    cs = cs * (1.5 - 0.5 * a * cs * cs);
+                    const double a = fma(t, t, 1.0);
+                    double cs = static_cast<double>(__builtin_amdgcn_rsqf(static_cast<float>(a)));
+                    cs = cs * fma(-0.5 * a, cs * cs, 1.5);
+                    cs = cs * fma(-0.5 * a, cs * cs, 1.5);
                     const double sn = cs * t;
-                    for (int c = tl; c < n; c += TS) {
-                        const double xv = x[c], yv = y[c];
-                        x[c] = cs * xv - sn * yv;
-                        y[c] = sn * xv + cs * yv;
+#pragma unroll
+                    for (int e = 0; e < MAXP; ++e) {
+                        const int c = 2 * (tl + e * TS);
+                        if (FULL || c < n) {
+                            *reinterpret_cast<double2*>(x + c) =
+                                double2{fma(cs, xv[e].x, -sn * yv[e].x), fma(cs, xv[e].y, -sn * yv[e].y)};
+                            *reinterpret_cast<double2*>(y + c) =
+                                double2{fma(sn, xv[e].x, cs * yv[e].x), fma(sn, xv[e].y, cs * yv[e].y)};
+                        }
                     }
                     if (tl == 0) {
-                        // exact for the exact angle; the fp32 angle leaves an O(1e-7) relative drift that
-                        // the per-sweep refresh removes
-                        nrm2[p] = cs * cs * al - 2.0 * cs * sn * ga + sn * sn * be;
-                        nrm2[q] = sn * sn * al + 2.0 * cs * sn * ga + cs * cs * be;
-                        *flag = 1;
+                        // exact for ANY rotation angle; rounding drift is removed by the per-sweep refresh
+                        const double cc = cs * cs, ss = sn * sn, x2 = 2.0 * cs * sn * ga;
+                        nrm2[p] = cc * al - x2 + ss * be;
+                        nrm2[q] = ss * al + x2 + cc * be;
+                        flag[0] = 1;
+                        if (g2 > early2 * ab) flag[1] = 1;
                     }
                 }
             }
             __syncthreads();
         }
-        const int any = *flag;
+        const int any = flag[0], coarse = flag[1];
         __syncthreads();
-        if (!any) {
+        if (!any || !coarse) {
+            // no rotation at all, or every off-diagonal of this sweep was already below sqrt(tol)
+            // before its rotation: quadratic convergence puts the next sweep below tol
             ++sweep;
             break;
         }

@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams 
         S[idx] = s;
     }
     __syncthreads();
-    jacobi_rows<kPrepThreads, TS>(S, rp, rp, mu, flag, 60, 1e-15);
+    jacobi_rows<kPrepThreads, TS, (kD + TS - 1) / TS, false>(S, rp, rp, mu, flag, 60, 1e-13);
     __syncthreads();
 
     if (tid < rp) {

@@ -84,35 +84,42 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const G
     const int64_t ustride = static_cast<int64_t>(p.wgs_per_head) * kGramWaves;
     int64_t unit = static_cast<int64_t>(wg) * kGramWaves + wave;
 
-    u32x2 raw[8];
-    auto issue = [&](int64_t u) {
+    // kDepth chunks of 16 tokens are in flight per wavefront (4 KB each).  Loads are unconditional:
+    // units past the end re-read the last unit, rows past the end of a query head re-read its last
+    // row; both are discarded below by wave-uniform tests, so the load stream stays straight-line.
+    constexpr int kDepth = 4;
+    u32x2 raw[kDepth][8];
+    const int64_t last_unit = p.units_per_head - 1;
+    auto issue = [&](int64_t u, u32x2* dst) {
+        u = u < last_unit ? u : last_unit;
         const int64_t qh = u / p.chunks_per_qhead;
         const int64_t tok0 = (u - qh * p.chunks_per_qhead) * 16 + 8 * hh;
-        const unsigned char* base =
-            p.q + (static_cast<int64_t>(kvh) * p.q_per_kv + qh) * p.sh + tok0 * p.st + m * 8;
+        const unsigned char* base = p.q + (static_cast<int64_t>(kvh) * p.q_per_kv + qh) * p.sh + m * 8;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (tok0 + j < p.n_tokens)
-                raw[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + j * p.st));
-            else
-                raw[j] = u32x2{0u, 0u};
+            int64_t tok = tok0 + j;
+            tok = tok < p.n_tokens ? tok : p.n_tokens - 1;
+            dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + tok * p.st));
         }
     };
-    if (unit < p.units_per_head) issue(unit);
-
-    while (unit < p.units_per_head) {
+    auto consume = [&](int64_t u, u32x2* src) {
+        if (u > last_unit) return;                       // wave-uniform
+        const int64_t qh = u / p.chunks_per_qhead;
+        const int64_t tokc = (u - qh * p.chunks_per_qhead) * 16;
+        if (tokc + 16 > p.n_tokens) {                    // ragged last chunk of a query head (wave-uniform)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (tokc + 8 * hh + j >= p.n_tokens) src[j] = u32x2{0u, 0u};
+        }
         // regroup: operand X_a holds, for channel 4m + a, the 8 tokens of this lane
         uint32_t x[4][4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            x[0][i] = __builtin_amdgcn_perm(raw[2 * i + 1][0], raw[2 * i][0], 0x05040100u);
-            x[1][i] = __builtin_amdgcn_perm(raw[2 * i + 1][0], raw[2 * i][0], 0x07060302u);
-            x[2][i] = __builtin_amdgcn_perm(raw[2 * i + 1][1], raw[2 * i][1], 0x05040100u);
-            x[3][i] = __builtin_amdgcn_perm(raw[2 * i + 1][1], raw[2 * i][1], 0x07060302u);
+            x[0][i] = __builtin_amdgcn_perm(src[2 * i + 1][0], src[2 * i][0], 0x05040100u);
+            x[1][i] = __builtin_amdgcn_perm(src[2 * i + 1][0], src[2 * i][0], 0x07060302u);
+            x[2][i] = __builtin_amdgcn_perm(src[2 * i + 1][1], src[2 * i][1], 0x05040100u);
+            x[3][i] = __builtin_amdgcn_perm(src[2 * i + 1][1], src[2 * i][1], 0x07060302u);
         }
-        unit += ustride;
-        if (unit < p.units_per_head) issue(unit);
-
         op_t ops[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a)
@@ -122,6 +129,19 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const G
 #pragma unroll
             for (int b = a; b < 4; ++b)
                 acc[tile_index(a, b)] = GramOps<DT>::mfma(ops[a], ops[b], acc[tile_index(a, b)]);
+    };
+
+    if (unit <= last_unit) {
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i) issue(unit + i * ustride, raw[i]);
+        while (unit <= last_unit) {
+#pragma unroll
+            for (int i = 0; i < kDepth; ++i) {
+                consume(unit + i * ustride, raw[i]);
+                issue(unit + (i + kDepth) * ustride, raw[i]);
+            }
+            unit += kDepth * ustride;
+        }
     }
 
     // reduce the four wavefronts through LDS (two rounds), wave 0 writes the partial
@@ -274,7 +294,7 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
     const double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     for (int i = threadIdx.x; i < kD * kD; i += kEigThreads) A[i] = g[i];
     __syncthreads();
-    const int sweeps = jacobi_rows<kEigThreads, 16>(A, kD, kEigLd, nrm, flag, 60, 1e-15);
+    const int sweeps = jacobi_rows<kEigThreads, 16, kD / 16, true>(A, kD, kEigLd, nrm, flag, 60, 1e-13);
     __syncthreads();
     if (sweeps_out && threadIdx.x == 0) sweeps_out[kvh] = sweeps;
 
