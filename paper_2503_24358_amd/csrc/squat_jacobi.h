@@ -66,10 +66,23 @@ __device__ __forceinline__ double team_sum(double v) {
 // n/2 * TS <= THREADS, n <= MAXE * TS.  FULL promises n == MAXE * TS (no column predicates).
 // nrm2: n doubles in LDS (scratch for the squared row norms).  `flag`: two ints in LDS.
 // Returns the number of sweeps done.  All threads of the block must call it.
+// THREADS == 64 runs the whole problem inside one wavefront (tid = lane): the synchronisation points
+// are then wave-level fences instead of workgroup barriers, so several problems can share a workgroup.
+template <int THREADS>
+__device__ __forceinline__ void team_sync() {
+    if constexpr (THREADS == 64) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        __syncthreads();
+    }
+}
+
 template <int THREADS, int TS, int MAXE, bool FULL>
 __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, int max_sweeps, double tol) {
     constexpr int MAXP = (MAXE + 1) / 2;     // column pairs per lane
-    const int tid = threadIdx.x;
+    const int tid = THREADS == 64 ? (threadIdx.x & 63) : threadIdx.x;
     const int team = tid / TS;
     const int tl = tid % TS;
     const int pairs = n >> 1;
@@ -92,7 +105,7 @@ __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, in
             flag[0] = 0;      // any rotation in this sweep
             flag[1] = 0;      // any pair whose relative off-diagonal exceeded sqrt(tol)
         }
-        __syncthreads();
+        team_sync<THREADS>();
         for (int round = 0; round < m; ++round) {
             if (team < pairs) {
                 int p, q;
@@ -171,10 +184,10 @@ __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, in
                     }
                 }
             }
-            __syncthreads();
+            team_sync<THREADS>();
         }
         const int any = flag[0], coarse = flag[1];
-        __syncthreads();
+        team_sync<THREADS>();
         if (!any || !coarse) {
             // no rotation at all, or every off-diagonal of this sweep was already below sqrt(tol)
             // before its rotation: quadratic convergence puts the next sweep below tol

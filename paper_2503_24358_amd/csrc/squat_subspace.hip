@@ -280,7 +280,11 @@ __global__ void __launch_bounds__(256) gram_reduce(const float* partial, int wgs
     }
 }
 
-constexpr int kEigThreads = 1024;
+#ifndef SQUAT_EIG_TS
+#define SQUAT_EIG_TS 16
+#endif
+constexpr int kEigTeam = SQUAT_EIG_TS;          // lanes per row pair
+constexpr int kEigThreads = 64 * kEigTeam;
 constexpr int kEigLd = kD;       // rows are read with unit stride by consecutive lanes
 
 __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int r, float* qhat, float* eig,
@@ -294,13 +298,13 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
     const double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     for (int i = threadIdx.x; i < kD * kD; i += kEigThreads) A[i] = g[i];
     __syncthreads();
-    const int sweeps = jacobi_rows<kEigThreads, 16, kD / 16, true>(A, kD, kEigLd, nrm, flag, 60, 1e-13);
+    const int sweeps = jacobi_rows<kEigThreads, kEigTeam, kD / kEigTeam, true>(A, kD, kEigLd, nrm, flag, 60, 1e-13);
     __syncthreads();
     if (sweeps_out && threadIdx.x == 0) sweeps_out[kvh] = sweeps;
 
     // eigenvalue of row i = its norm
-    {
-        const int row = threadIdx.x >> 3, tl = threadIdx.x & 7;     // 8 lanes per row
+    for (int row = threadIdx.x >> 3; row < kD; row += kEigThreads / 8) {     // 8 lanes per row
+        const int tl = threadIdx.x & 7;
         double s = 0.0;
         for (int c = tl; c < kD; c += 8) s += A[row * kEigLd + c] * A[row * kEigLd + c];
         s = team_sum<8>(s);
@@ -319,8 +323,8 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
     }
     __syncthreads();
     // row i with rank < r  ->  qhat[rank] = row / sqrt(norm), sign: largest |component| positive
-    {
-        const int row = threadIdx.x >> 3, tl = threadIdx.x & 7;
+    for (int row = threadIdx.x >> 3; row < kD; row += kEigThreads / 8) {
+        const int tl = threadIdx.x & 7;
         const int rk = rank[row];
         if (rk < r) {
             double best = -1.0, bestv = 0.0;
