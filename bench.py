@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="profiling aid: also run one plain device copy of the key tensor (known size) per step, "
+                         "to calibrate the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--only", default="", help="profiling aid: time only this stage (e.g. quantize_keys); "
                                                "the other stages run once, untimed, to prepare its inputs")
     args = ap.parse_args()
@@ -108,6 +111,8 @@ def main():
         if run("dequantize_keys"):
             squat.dequantize_keys(codes, scale, zero, wl.bits, wl.group, out=back)
         if ev: ev[4].record()
+        if args.with_copy:
+            back.copy_(wl.k)          # 2 x keys x 256 B through a plain elementwise copy kernel
 
     step(everything=True)
 
@@ -132,16 +137,22 @@ def main():
     q_bytes = n_keys * wl.key_bytes()
     achieved = q_bytes / (q_ms * 1e-3) / 1e9
     roofline = {"kernel": "quantize_kernel<2-bit,G32,g32,bf16>", "bound": "hbm", "achieved": achieved,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                # FETCH_SIZE + WRITE_SIZE of this kernel from rocprofv3 --pmc, scaled by a plain copy of known
+                # size (profiles/quantize_kernel_long_context_hbm_traffic.txt); measured at the default workload
+                "traffic": 2.5629e9 if (args.layers == 32 and args.tokens == 32768) else None,
                 "bytes_per_launch": q_bytes, "ms_per_launch": q_ms,
-                "mfma_tflops": n_keys * 12288 * 3 / (q_ms * 1e-3) / 1e12}
+                # embedded contraction: 12288 flop per key at g = 32, two fp16 passes (update matrix on the fp16 grid)
+                "mfma_tflops": n_keys * 12288 * 2 / (q_ms * 1e-3) / 1e12,
+                "mfma_frac_of_fp16_peak": n_keys * 12288 * 2 / (q_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     d_ms = stage_ms["dequantize_keys"]
     gram_bytes = wl.q.numel() * 2
     other = {
         "dequantize_keys": {"bound": "hbm", "achieved": q_bytes / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                             "unit": "GB/s", "frac": q_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "build_subspace": {"ms": stage_ms["build_subspace"], "gram_input_GB": gram_bytes / 1e9,
-                           "note": "gram (HBM-bound MFMA) + fp64 Jacobi eigen-solver (latency-bound)"},
+                           "note": "gram (HBM-bound bf16 MFMA, see profiles/) + fp64 Jacobi eigen-solver "
+                                   "(instruction-issue-bound, one workgroup per head)"},
         "prepare": {"ms": stage_ms["prepare"]},
     }
     out = {
