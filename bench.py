@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the quantize and dequantize kernels for the other bit widths / group sizes "
+                         "of the long-context configuration (adds a \"variants\" list to the JSON line)")
     ap.add_argument("--with-copy", action="store_true",
                     help="profiling aid: also run one plain device copy of the key tensor (known size) per step, "
                          "to calibrate the FETCH_SIZE / WRITE_SIZE counters")
@@ -171,6 +174,32 @@ def main():
         "roofline": roofline,
         "other_kernels": other,
     }
+    if args.variants:
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            evs[0].record()
+            for i in range(reps):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps
+        out["variants"] = []
+        for bits, G, g, use_update in [(2, 32, 32, True), (2, 32, 64, True), (4, 32, 32, True), (4, 32, 64, True),
+                                       (2, 128, 32, True), (4, 128, 32, True), (2, 128, 64, True),
+                                       (2, 32, 128, False), (2, 128, 128, False), (4, 128, 128, False)]:
+            upd = squat.prepare(qhat, wl.lam, g) if use_update else None
+            c = torch.empty((1, H, n, d * bits // 32), dtype=torch.int32, device=dev)
+            sc = torch.empty((1, H, n, d // G), dtype=torch.float16, device=dev)
+            ze = torch.empty_like(sc)
+            tq = timed(lambda: squat.quantize_keys(wl.k, upd, bits, G, g, codes=c, scale=sc, zero=ze))
+            td = timed(lambda: squat.dequantize_keys(c, sc, ze, bits, G, out=back))
+            nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // G))
+            out["variants"].append({"bits": bits, "group": G, "g": g, "update": use_update,
+                                    "bytes_per_key": nbytes // n_keys,
+                                    "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                    "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(dict(n_tokens=n, r=wl.r, lam=wl.lam, bits=wl.bits, group=wl.group,
                                                 g=wl.g, q_per_kv=wl.q_per_kv))

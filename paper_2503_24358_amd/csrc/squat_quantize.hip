@@ -27,8 +27,12 @@ namespace {
 
 constexpr int NT = kD / 32;          // 32-channel tiles per key
 // Wavefronts per workgroup: one workgroup per CU, sized by LDS (update panels + one staging tile per
-// wavefront): 12 waves (3 per SIMD) for 16-bit keys, 6 for fp32 keys.
-__host__ __device__ constexpr int waves_for(int dt) { return dt == SQUAT_F32 ? 6 : 12; }
+// wavefront) and registers: 12 waves (3 per SIMD) for 16-bit keys, 6 for fp32 keys.
+// Variants that keep more live state (two tiles per block, or statistics over four tiles) get 8 waves so
+// that each may use 256 registers instead of spilling at 168.
+__host__ __device__ constexpr int waves_for(int dt, int gt, int bt) {
+    return dt == SQUAT_F32 ? 6 : ((bt == 2 || (gt == 4 && bt == 1)) ? 8 : 12);
+}
 constexpr int kWgsPerCU = 1;
 
 struct QuantParams {
@@ -128,8 +132,8 @@ __device__ __forceinline__ void split8(const float* v, half8& hi, half8& lo) {
 }
 
 template <int BITS, int GT, int BT, int DT>
-__global__ void __launch_bounds__(waves_for(DT) * kWave, kWgsPerCU) quantize_kernel(const QuantParams p) {
-    constexpr int kWaves = waves_for(DT);
+__global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quantize_kernel(const QuantParams p) {
+    constexpr int kWaves = waves_for(DT, GT, BT);
     constexpr int ES = Elem<DT>::size;
     constexpr int ROWB = kD * ES;                 // bytes of one key
     constexpr int LROW = ROWB + 16;               // padded LDS row: conflict-free b128 column reads
@@ -432,7 +436,7 @@ __global__ void __launch_bounds__(waves_for(DT) * kWave, kWgsPerCU) quantize_ker
 template <int BITS, int GT, int BT, int DT>
 int launch(const QuantParams& p, int64_t n_prob, hipStream_t stream) {
     constexpr int ES = Elem<DT>::size;
-    constexpr int kWaves = waves_for(DT);
+    constexpr int kWaves = waves_for(DT, GT, BT);
     constexpr size_t lds = n_pairs(BT) * 4096 + kWaves * 32 * (kD * ES + 16) + 16;
     auto kern = quantize_kernel<BITS, GT, BT, DT>;
     static bool attr_done = false;      // idempotent; a race only repeats the call
@@ -546,15 +550,15 @@ extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_ba
     const int cus = device_cu_count();
     const int64_t target = kWgsPerCU * static_cast<int64_t>(cus);   // fill every CU once
     int64_t per = (target + n_prob - 1) / n_prob;
-    const int kw = waves_for(k_dt);
+    const int gt = group / 32;
+    const int bt = update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
+    const int kw = waves_for(k_dt, gt, bt);
     const int64_t need = (p.units_per_prob + kw - 1) / kw;
     if (per > need) per = need;
     if (per < 1) per = 1;
     p.wgs_per_prob = static_cast<int>(per);
     if (n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
 
-    const int gt = group / 32;
-    const int bt = update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
     if (!(gt % bt == 0 || bt % gt == 0)) return SQUAT_E_BADSHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? dispatch_gt<2>(gt, bt, k_dt, p, n_prob, s)
