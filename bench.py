@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--variants", action="store_true",
                     help="also time the quantize and dequantize kernels for the other bit widths / group sizes "
                          "of the long-context configuration (adds a \"variants\" list to the JSON line)")
+    ap.add_argument("--decode", action="store_true",
+                    help="also time the decode-time flush shape (64 sequences, 32 buffered tokens per head): one "
+                         "layer (8 heads) per launch and all 32 layers (256 heads) per launch (adds \"decode_flush\")")
     ap.add_argument("--with-copy", action="store_true",
                     help="profiling aid: also run one plain device copy of the key tensor (known size) per step, "
                          "to calibrate the FETCH_SIZE / WRITE_SIZE counters")
@@ -200,6 +203,27 @@ def main():
                                     "bytes_per_key": nbytes // n_keys,
                                     "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                     "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    if args.decode:
+        def timed_us(fn, reps=50):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+        out["decode_flush"] = []
+        for heads in (wl.kv_heads, H):
+            kb = torch.randn((64, heads, 32, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+            c = torch.empty((64, heads, 32, d * wl.bits // 32), dtype=torch.int32, device=dev)
+            sc = torch.empty((64, heads, 32, d // wl.group), dtype=torch.float16, device=dev)
+            ze = torch.empty_like(sc)
+            us = timed_us(lambda: squat.quantize_keys(kb, update[:heads], wl.bits, wl.group, wl.g, codes=c, scale=sc, zero=ze))
+            nk = 64 * heads * 32
+            out["decode_flush"].append({"sequences": 64, "heads_per_launch": heads, "keys_per_flush": nk,
+                                        "us_per_flush_back_to_back": us, "keys_per_s": nk / (us * 1e-6)})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(dict(n_tokens=n, r=wl.r, lam=wl.lam, bits=wl.bits, group=wl.group,
                                                 g=wl.g, q_per_kv=wl.q_per_kv))
