@@ -20,8 +20,9 @@ Parity status of each function:
                                 g=1 against the one-coordinate rule of Prop. 1)
   rtn_group, quantize_keys      pinned (hand-worked fixture, r=0 fixed point,
                                 per-step optimality against a generic solver,
-                                soft and hard invariants)
-  dequantize_keys, pack/unpack  pinned (definition of deq; pack o unpack = id)
+                                soft and hard invariants), both grouping axes
+  dequantize_keys, pack/unpack  pinned (definition of deq; pack o unpack = id,
+                                single-code layout checks), both layouts
   exact integer codes for a concrete key under lambda>0: parity unpinned by the
   paper (it prints no worked numeric example); pinned only through the
   invariants above.
@@ -34,7 +35,8 @@ __all__ = [
     "gram", "subspace", "subspace_svd", "deviation_from_subspace",
     "update_matrix_lemma", "update_matrix_kkt", "update_matrix_lowrank",
     "rtn_group", "quantize_keys", "dequantize_keys",
-    "pack_codes", "unpack_codes", "replay_classify",
+    "pack_codes", "unpack_codes", "pack_codes_tokens", "unpack_codes_tokens",
+    "replay_classify",
 ]
 
 
@@ -395,6 +397,41 @@ def unpack_codes(words: np.ndarray, bits: int) -> np.ndarray:
     return out.reshape(words.shape[:-1] + (words.shape[-1] * per,)).astype(np.uint8)
 
 
+def pack_codes_tokens(codes: np.ndarray, bits: int) -> np.ndarray:
+    """Packed layout of the per-channel mode (ours to define): tokens are cut
+    into tiles of 32; within a tile every channel owns `bits` consecutive 32-bit
+    words that hold its 32 codes little-endian ALONG TOKENS: token j of the
+    tile sits in word j // (32/bits) at bit offset bits * (j mod 32/bits).
+
+    codes (..., n, d) -> words (..., n/32, d, bits) uint32; n a multiple of 32.
+    """
+    codes = np.asarray(codes, dtype=np.uint32)
+    n, d = codes.shape[-2:]
+    if n % 32:
+        raise ValueError("token count must be a multiple of 32")
+    per = 32 // bits
+    lead = codes.shape[:-2]
+    # (..., tile, word, token-in-word, channel) -> (..., tile, channel, word, token-in-word)
+    grp = codes.reshape(lead + (n // 32, bits, per, d))
+    grp = np.moveaxis(grp, -1, -3)
+    shifts = (np.arange(per, dtype=np.uint32) * np.uint32(bits))
+    return np.bitwise_or.reduce(grp << shifts, axis=-1).astype(np.uint32)
+
+
+def unpack_codes_tokens(words: np.ndarray, bits: int) -> np.ndarray:
+    """Inverse of pack_codes_tokens: words (..., n/32, d, bits) -> codes (..., n, d) uint8."""
+    words = np.asarray(words, dtype=np.uint32)
+    per = 32 // bits
+    tiles, d, nw = words.shape[-3:]
+    if nw != bits:
+        raise ValueError("last axis must hold `bits` words per channel")
+    shifts = (np.arange(per, dtype=np.uint32) * np.uint32(bits))
+    mask = np.uint32((1 << bits) - 1)
+    out = (words[..., None] >> shifts) & mask                # (..., tile, d, word, token-in-word)
+    out = np.moveaxis(out, -3, -1)                           # (..., tile, word, token-in-word, d)
+    return out.reshape(words.shape[:-3] + (tiles * 32, d)).astype(np.uint8)
+
+
 # --------------------------------------------------------------------------- #
 # Teacher-forced replay: classify the disagreements of another implementation
 # --------------------------------------------------------------------------- #
@@ -413,8 +450,8 @@ def _fp16_neighbours_mid(v: np.ndarray):
 
 def replay_classify(K: np.ndarray, U, bits: int, G: int, g: int,
                     codes_other: np.ndarray, scale_other: np.ndarray,
-                    zero_other: np.ndarray, tol: float = 1e-5):
-    """Replay `quantize_keys` (axis="token") in float64 while FORCING the other
+                    zero_other: np.ndarray, tol: float = 1e-5, axis: str = "token"):
+    """Replay `quantize_keys` in float64 while FORCING the other
     implementation's codes and fp16 metadata for all earlier decisions, and
     classify every decision where float64 would have chosen differently.
 
@@ -424,6 +461,9 @@ def replay_classify(K: np.ndarray, U, bits: int, G: int, g: int,
     value is the adjacent fp16 number and the float64 value lies within
     tol * Delta of the fp16 rounding midpoint.  Anything else is `unexplained`.
     Forcing removes downstream cascades, so each root cause is counted once.
+
+    `axis` as in quantize_keys; scale_other/zero_other are (n, d/G) for "token"
+    and (n/G, d) for "channel".
 
     Returns dict with counts: n_codes, code_diff, code_unexplained,
     n_meta, meta_diff, meta_unexplained, and worst distances seen.
@@ -436,33 +476,46 @@ def replay_classify(K: np.ndarray, U, bits: int, G: int, g: int,
     so = np.asarray(scale_other).astype(np.float16)
     zo = np.asarray(zero_other).astype(np.float16)
     Ud = None if U is None else np.asarray(U, dtype=np.float64)
+    if axis not in ("token", "channel"):
+        raise ValueError(axis)
+    if axis == "channel" and n % G:
+        raise ValueError("token count must be a multiple of G")
+    n_meta = 2 * n * (d // G) if axis == "token" else 2 * (n // G) * d
     out = dict(n_codes=n * d, code_diff=0, code_unexplained=0,
-               n_meta=2 * n * (d // G), meta_diff=0, meta_unexplained=0,
+               n_meta=n_meta, meta_diff=0, meta_unexplained=0,
                worst_code_dist=0.0, worst_meta_dist=0.0)
+
+    def check_meta(m, M, s_other, z_other):
+        dl = (M - m) / levels
+        for v, other in ((dl, s_other), (m, z_other)):
+            mine, dist, neigh = _fp16_neighbours_mid(v)
+            diff = mine != other
+            if diff.any():
+                o64 = other.astype(np.float64)
+                adjacent = o64 == neigh
+                ok = adjacent & (dist <= tol * np.maximum(dl, 1e-300))
+                out["meta_diff"] += int(diff.sum())
+                out["meta_unexplained"] += int((diff & ~ok).sum())
+                rel = dist[diff] / np.maximum(dl[diff], 1e-300)
+                out["worst_meta_dist"] = max(out["worst_meta_dist"], float(rel.max()))
+
     for t in range(T):
         lo, hi = t * g, (t + 1) * g
-        if lo % G == 0:
-            n_new = max(1, g // G)
-            first = lo // G
-            for gi in range(first, first + n_new):
-                seg = x[:, gi * G:(gi + 1) * G]
-                m = seg.min(axis=1)
-                M = seg.max(axis=1)
-                dl = (M - m) / levels
-                for v, other in ((dl, so[:, gi]), (m, zo[:, gi])):
-                    mine, dist, neigh = _fp16_neighbours_mid(v)
-                    diff = mine != other
-                    if diff.any():
-                        o64 = other.astype(np.float64)
-                        adjacent = o64 == neigh
-                        ok = adjacent & (dist <= tol * np.maximum(dl, 1e-300))
-                        out["meta_diff"] += int(diff.sum())
-                        out["meta_unexplained"] += int((diff & ~ok).sum())
-                        rel = dist[diff] / np.maximum(dl[diff], 1e-300)
-                        out["worst_meta_dist"] = max(out["worst_meta_dist"], float(rel.max()))
-        gidx = np.arange(lo, hi) // G
-        s64 = so[:, gidx].astype(np.float64)
-        z64 = zo[:, gidx].astype(np.float64)
+        if axis == "token":
+            if lo % G == 0:
+                n_new = max(1, g // G)
+                first = lo // G
+                for gi in range(first, first + n_new):
+                    seg = x[:, gi * G:(gi + 1) * G]
+                    check_meta(seg.min(axis=1), seg.max(axis=1), so[:, gi], zo[:, gi])
+            gidx = np.arange(lo, hi) // G
+            s64 = so[:, gidx].astype(np.float64)
+            z64 = zo[:, gidx].astype(np.float64)
+        else:
+            blk = x[:, lo:hi].reshape(n // G, G, g)
+            check_meta(blk.min(axis=1), blk.max(axis=1), so[:, lo:hi], zo[:, lo:hi])
+            s64 = np.repeat(so[:, lo:hi].astype(np.float64), G, axis=0)
+            z64 = np.repeat(zo[:, lo:hi].astype(np.float64), G, axis=0)
         xb = x[:, lo:hi]
         safe = np.where(s64 > 0, s64, 1.0)
         u = (xb - z64) / safe

@@ -311,6 +311,104 @@ def test_replay_classifier_accepts_itself_and_flags_a_planted_error():
     assert rep["code_unexplained"] + rep["meta_unexplained"] > 0
 
 
+# ------------------------------------------- per-channel mode (the paper's own layout)
+@pytest.mark.parametrize("bits,g,lam", [(2, 32, 1e-3), (4, 64, 5e-4), (2, 32, np.inf)])
+def test_channel_axis_each_step_generic_solver(bits, g, lam):
+    """Algorithm 1's `Quant` with statistics per channel over G = 32 tokens: every
+    channel of the block is quantized by the scalar quantizer applied to its 32
+    current values, and every token's tail is recomputed by a generic
+    least-squares solve of Lemma 2's problem."""
+    d, G = 128, 32
+    Qh, K = _setup(d=d, n=64)
+    U = O.update_matrix_lowrank(Qh, lam, g)
+    out = O.quantize_keys(K, U, bits, G, g, axis="channel", trace=True)
+    Mst = None if np.isinf(lam) else np.vstack([np.eye(d), np.sqrt(lam) * Qh])
+    for grp in range(2):
+        x = K[grp * G:(grp + 1) * G].copy()
+        for t in range(d // g):
+            lo, hi = t * g, (t + 1) * g
+            xq = np.empty((G, g))
+            for j in range(lo, hi):
+                c, s, z, xh = O.rtn_group(x[:, j], bits)
+                assert np.array_equal(out["codes"][grp * G:(grp + 1) * G, j], c)
+                assert out["scale"][grp, j] == s[0] and out["zero"][grp, j] == z[0]
+                xq[:, j - lo] = xh
+            dvec = xq - x[:, lo:hi]
+            x[:, lo:hi] = xq
+            if t < d // g - 1:
+                for i in range(G):
+                    if Mst is not None:
+                        tail = np.linalg.lstsq(Mst[:, hi:], -Mst[:, lo:hi] @ dvec[i], rcond=None)[0]
+                    else:
+                        tail = np.linalg.lstsq(Qh[:, hi:], -Qh[:, lo:hi] @ dvec[i], rcond=None)[0]
+                    x[i, hi:] += tail
+            assert np.allclose(x, out["states"][t][grp * G:(grp + 1) * G], atol=1e-9)
+        assert np.allclose(x, out["xhat"][grp * G:(grp + 1) * G], atol=1e-9)
+
+
+def test_channel_axis_invariants():
+    """The invariants do not depend on which scalar quantizer froze the block: soft
+    first-order condition for finite lambda, exact orthogonality for lambda = +inf."""
+    Qh, K = _setup(n=96)
+    lam, g = 1e-3, 32
+    P = np.eye(128) + lam * Qh.T @ Qh
+    out = O.quantize_keys(K, O.update_matrix_lemma(Qh, lam, g), 2, 32, g, axis="channel", trace=True)
+    for t in range(3):
+        delta = out["states"][t] - K
+        assert np.abs((delta @ P)[:, (t + 1) * g:]).max() <= 1e-9 * np.abs(delta @ P).max()
+    out = O.quantize_keys(K, O.update_matrix_lowrank(Qh, np.inf, g), 2, 32, g, axis="channel", trace=True)
+    scale = np.abs(Qh).max() * np.abs(K).max()
+    for t in range(3):
+        assert np.abs((out["states"][t] - K) @ Qh.T).max() <= 1e-12 * scale
+    lhs = (out["xhat"] - K) @ Qh.T
+    rtn = O.quantize_keys(K, None, 2, 32, g, axis="channel")
+    assert np.mean(lhs ** 2) < np.mean(((rtn["xhat"] - K) @ Qh.T) ** 2)
+    # read-back is the definition, element by element
+    back = O.dequantize_keys(out["codes"], out["scale"], out["zero"], 32, axis="channel")
+    assert np.array_equal(back, out["xhat"])
+    for i, c in ((0, 0), (31, 5), (32, 5), (95, 127)):
+        assert back[i, c] == float(out["codes"][i, c]) * float(out["scale"][i // 32, c]) + float(out["zero"][i // 32, c])
+
+
+def test_token_axis_packing_layout_and_roundtrip():
+    gen = np.random.default_rng(6)
+    for bits in (2, 4):
+        codes = gen.integers(0, 1 << bits, size=(3, 96, 128)).astype(np.uint8)
+        w = O.pack_codes_tokens(codes, bits)
+        assert w.shape == (3, 3, 128, bits) and w.dtype == np.uint32
+        assert np.array_equal(O.unpack_codes_tokens(w, bits), codes)
+    one = np.zeros((64, 128), dtype=np.uint8)
+    one[32 + 17, 9] = 3                      # tile 1, token 17 of the tile, channel 9
+    w = O.pack_codes_tokens(one, 2)
+    assert w[1, 9, 1] == (3 << 2) and w.sum() == (3 << 2)
+    one[32 + 17, 9] = 0
+    one[9, 100] = 5                          # tile 0, token 9: 4-bit word 1, nibble 1
+    w = O.pack_codes_tokens(one, 4)
+    assert w[0, 100, 1] == (5 << 4) and w.sum() == (5 << 4)
+    # same share of the 16-bit size as the per-token layout (Tables 1-2's KV size column)
+    assert O.pack_codes_tokens(np.zeros((32, 128), np.uint8), 2).nbytes == O.pack_codes(np.zeros((32, 128), np.uint8), 2).nbytes
+
+
+def test_replay_classifier_channel_axis():
+    Qh, K = _setup(n=64)
+    U = O.update_matrix_lowrank(Qh, 1e-3, 32)
+    out = O.quantize_keys(K, U, 2, 32, 32, axis="channel")
+    rep = O.replay_classify(K, U, 2, 32, 32, out["codes"], out["scale"], out["zero"], axis="channel")
+    assert rep["code_diff"] == 0 and rep["meta_diff"] == 0 and rep["n_meta"] == 2 * 2 * 128
+    bad = out["codes"].copy()
+    bad[40, 100] = (bad[40, 100] + 1) % 4
+    rep = O.replay_classify(K, U, 2, 32, 32, bad, out["scale"], out["zero"], axis="channel")
+    assert rep["code_diff"] == 1 and rep["code_unexplained"] == 1
+    # the per-token result is a different quantization: the channel-axis replay must reject it
+    tok = O.quantize_keys(K, U, 2, 32, 32)
+    rep = O.replay_classify(K, U, 2, 32, 32, tok["codes"], out["scale"], out["zero"], axis="channel")
+    assert rep["code_unexplained"] > 0
+    badz = out["zero"].copy()
+    badz[1, 7] = np.nextafter(np.nextafter(badz[1, 7], np.float16(np.inf)), np.float16(np.inf))
+    rep = O.replay_classify(K, U, 2, 32, 32, out["codes"], out["scale"], badz, axis="channel")
+    assert rep["meta_unexplained"] >= 1
+
+
 # ------------------------------------------------------------------ subspace
 def test_subspace_matches_library_svd():
     gen = np.random.default_rng(40)
