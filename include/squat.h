@@ -10,6 +10,11 @@
  *   squat_quantize_keys    keys, update matrix -> codes      (Algorithm 1, Quant)
  *   squat_dequantize_keys  codes -> keys                     (Section 2, deq)
  *
+ * squat_quantize_keys groups every key's channels (statistics per token); the
+ * pair squat_quantize_keys_per_channel / squat_dequantize_keys_per_channel is
+ * the paper's own grouping (statistics per channel over 32 tokens), with the
+ * same Qhat and update matrix.
+ *
  * Conventions that hold for every call
  *   - Every data pointer is a DEVICE pointer owned by the caller, valid on the
  *     device that is current when the call is made.  Only `ws` buffers are
@@ -177,6 +182,62 @@ int squat_dequantize_keys(const uint32_t* codes, const uint16_t* scale, const ui
                           int64_t n_batch, int n_heads, int64_t n_tokens, int d, int bits,
                           int group, void* k_out, squat_dtype out_dt, int64_t o_stride_batch,
                           int64_t o_stride_head, int64_t o_stride_token, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_quantize_keys_per_channel  (Algorithm 1, function Quant, as printed:
+ * "per-channel" quantization of each key block; Section 2 "Quantization";
+ * Section 4 "Hyper-parameters": group size 32 = residual length 32; Lemma 2
+ * for the update).
+ *
+ * Tokens are taken in groups of `group` = 32 consecutive tokens of one head
+ * (what the decode phase flushes from the residual buffer, or 32-token slices
+ * of the prompt).  For one such group, on a working copy in fp32: for
+ * t = 1 .. d/g, every channel of block t is quantized on its own over the 32
+ * tokens, from their CURRENT values, with asymmetric min/max b-bit
+ * round-to-nearest (scale and zero rounded to fp16 before use, ties to even,
+ * codes clamped to [0, 2^b-1], a constant channel has scale 0 and codes 0);
+ * the block is frozen at its dequantized values and, if t < d/g, every token's
+ * remaining channels receive  U[t g:, block] * (deq - current)  of that token.
+ * update == NULL is plain per-channel round-to-nearest (KIVI's key format).
+ *
+ *   k, update, update_stride_batch, bits, g    as for squat_quantize_keys.
+ *   group    must be 32.   n_tokens must be a multiple of 32 (the caller keeps
+ *            the remainder in its 16-bit residual buffer, as Algorithm 1 does).
+ *   codes    out [n_batch, n_heads, n_tokens/32, d, bits] uint32, dense,
+ *            16-byte aligned: the 32 codes of channel c in token group T are
+ *            `bits` consecutive words; token j of the group is in word
+ *            j / (32/bits) at bit offset bits * (j mod 32/bits).
+ *   scale    out [n_batch, n_heads, n_tokens/32, d] fp16 bit patterns,
+ *            4-byte aligned.
+ *   zero     out, same shape: the (real-valued) zero-point m.
+ *   Keys must be finite: a NaN or Inf spoils the whole group of 32 tokens.
+ * ------------------------------------------------------------------------- */
+int squat_quantize_keys_per_channel(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
+                                    int64_t n_tokens, int d, int64_t k_stride_batch,
+                                    int64_t k_stride_head, int64_t k_stride_token,
+                                    const float* update, int64_t update_stride_batch, int bits,
+                                    int group, int g, uint32_t* codes, uint16_t* scale,
+                                    uint16_t* zero, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_dequantize_keys_per_channel  (Section 2: deq(c) = c * Delta + m, on
+ * the per-channel store).
+ *
+ * k_out[b,h,t,c] = code * scale + zero of (token group t / 32, channel c), one
+ * fused multiply-add in fp32, rounded once to out_dt.
+ *
+ *   codes, scale, zero   as written by squat_quantize_keys_per_channel (dense;
+ *           all three 16-byte aligned).
+ *   group   must be 32; n_tokens a multiple of 32.
+ *   k_out   [n_batch, n_heads, n_tokens, d] dtype out_dt with strides in
+ *           elements (multiples of 8, base 16-byte aligned).
+ * ------------------------------------------------------------------------- */
+int squat_dequantize_keys_per_channel(const uint32_t* codes, const uint16_t* scale,
+                                      const uint16_t* zero, int64_t n_batch, int n_heads,
+                                      int64_t n_tokens, int d, int bits, int group, void* k_out,
+                                      squat_dtype out_dt, int64_t o_stride_batch,
+                                      int64_t o_stride_head, int64_t o_stride_token,
+                                      squat_stream stream);
 
 #ifdef __cplusplus
 }

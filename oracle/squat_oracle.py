@@ -413,9 +413,9 @@ def pack_codes_tokens(codes: np.ndarray, bits: int) -> np.ndarray:
     lead = codes.shape[:-2]
     # (..., tile, word, token-in-word, channel) -> (..., tile, channel, word, token-in-word)
     grp = codes.reshape(lead + (n // 32, bits, per, d))
-    grp = np.moveaxis(grp, -1, -3)
+    grp = np.ascontiguousarray(np.moveaxis(grp, -1, -3))
     shifts = (np.arange(per, dtype=np.uint32) * np.uint32(bits))
-    return np.bitwise_or.reduce(grp << shifts, axis=-1).astype(np.uint32)
+    return np.ascontiguousarray(np.bitwise_or.reduce(grp << shifts, axis=-1).astype(np.uint32))
 
 
 def unpack_codes_tokens(words: np.ndarray, bits: int) -> np.ndarray:

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libsquat.so")
 
-SOURCES = ["squat_api.cpp", "squat_quantize.hip", "squat_dequantize.hip",
+SOURCES = ["squat_api.cpp", "squat_quantize.hip", "squat_quantize_pc.hip", "squat_dequantize.hip",
            "squat_subspace.hip", "squat_prepare.hip"]
 
 # Packed-fp32 VALU ops are switched off on purpose (build flags).

@@ -3,6 +3,11 @@
 // 16 channels of one key (one or two packed words, one scale, one zero) into 16
 // output elements; a wavefront covers 8 consecutive keys, so code reads are one
 // contiguous 256/512-byte run and output writes one contiguous 2/4-KB run.
+//
+// squat_dequantize_keys_per_channel reads the token-major store of the
+// per-channel mode: one wavefront rebuilds one tile of 32 tokens; a lane owns 8
+// consecutive channels (one 16-byte piece of an output row) of 8 tokens, so it
+// needs 8 packed words, 8 scales and 8 zero-points, and writes whole rows.
 #include "squat_internal.h"
 
 using namespace squat;
@@ -87,6 +92,95 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const DeqParams p) {
     store16<DT>(dst, v);
 }
 
+// One wavefront per tile of 32 tokens.  Lane (s = lane >> 4, pc = lane & 15): channels 8 pc .. 8 pc + 7,
+// tokens 8 s .. 8 s + 7 of the tile.  Token j of the tile sits in word j / (32 / BITS) of its channel
+// at bit BITS * (j mod 32 / BITS), so the lane's 8 tokens are BITS consecutive bytes of one word.
+template <int BITS, int DT>
+__global__ void __launch_bounds__(256) dequantize_pc_kernel(const DeqParams p, const int64_t tiles_per_seq) {
+    constexpr int ES = (DT == SQUAT_F32) ? 4 : 2;
+    const int lane = threadIdx.x & 63;
+    const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (tile >= tiles_per_seq) return;
+    const int64_t b = bh / p.n_heads;
+    const int64_t h = bh - b * p.n_heads;
+    const int64_t gt = bh * tiles_per_seq + tile;
+    const int s = lane >> 4, pc = lane & 15;
+
+    const int widx = 8 * s * BITS / 32;               // word of the channel that holds tokens 8 s .. 8 s + 7
+    const int shift0 = (8 * s * BITS) % 32;
+    const uint32_t* cw = p.codes + gt * (kD * BITS) + (8 * pc) * BITS + widx;
+    uint32_t w[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) w[c] = cw[c * BITS] >> shift0;
+    const u32x4 sraw = *reinterpret_cast<const u32x4*>(p.scale + gt * kD + 8 * pc);
+    const u32x4 zraw = *reinterpret_cast<const u32x4*>(p.zero + gt * kD + 8 * pc);
+    float sc[8], zp[8];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        sc[2 * c] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(sraw[c] & 0xFFFFu)));
+        sc[2 * c + 1] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(sraw[c] >> 16)));
+        zp[2 * c] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(zraw[c] & 0xFFFFu)));
+        zp[2 * c + 1] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(zraw[c] >> 16)));
+    }
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    unsigned char* dst = p.out + b * p.ob + h * p.oh + (tile * kTileTokens + 8 * s) * p.ot + pc * 8 * ES;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float v[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            v[c] = fmaf(static_cast<float>((w[c] >> (BITS * i)) & MASK), sc[c], zp[c]);
+        unsigned char* o = dst + i * p.ot;
+        if constexpr (DT == SQUAT_F32) {
+            *reinterpret_cast<f32x4*>(o) = f32x4{v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f32x4*>(o + 16) = f32x4{v[4], v[5], v[6], v[7]};
+        } else {
+            uint32_t pk[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if constexpr (DT == SQUAT_F16) {
+                    half2v hv;
+                    hv[0] = static_cast<_Float16>(v[2 * c]);
+                    hv[1] = static_cast<_Float16>(v[2 * c + 1]);
+                    pk[c] = __builtin_bit_cast(uint32_t, hv);
+                } else {
+                    // fp32 -> bf16, round to nearest even
+                    uint32_t a = as_u32(v[2 * c]), bb = as_u32(v[2 * c + 1]);
+                    a = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
+                    bb = (bb + 0x7FFFu + ((bb >> 16) & 1u)) & 0xFFFF0000u;
+                    pk[c] = a | bb;
+                }
+            }
+            *reinterpret_cast<u32x4*>(o) = u32x4{pk[0], pk[1], pk[2], pk[3]};
+        }
+    }
+}
+
+template <int BITS>
+int launch_pc(squat_dtype dt, const DeqParams& p, int64_t tiles, dim3 grid, hipStream_t s) {
+    switch (dt) {
+        case SQUAT_F32: hipLaunchKernelGGL((dequantize_pc_kernel<BITS, SQUAT_F32>), grid, dim3(256), 0, s, p, tiles); break;
+        case SQUAT_F16: hipLaunchKernelGGL((dequantize_pc_kernel<BITS, SQUAT_F16>), grid, dim3(256), 0, s, p, tiles); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((dequantize_pc_kernel<BITS, SQUAT_BF16>), grid, dim3(256), 0, s, p, tiles); break;
+        default: return SQUAT_E_BADDTYPE;
+    }
+    return check_launch();
+}
+
+// (batch, head) pairs over grid y / z: an exact factorisation so that every (y, z) is a real pair.
+bool split_bh(int64_t bh, int64_t& gy, int64_t& gz) {
+    gy = bh;
+    gz = 1;
+    if (gy > 65535) {
+        gy = 0;
+        for (int64_t cand = 65535; cand >= 1; --cand)
+            if (bh % cand == 0) { gy = cand; break; }
+        gz = bh / gy;
+    }
+    return gz <= 65535;
+}
+
 template <int BITS, int GROUP>
 int launch_dt(squat_dtype dt, const DeqParams& p, dim3 grid, hipStream_t s) {
     switch (dt) {
@@ -137,20 +231,49 @@ extern "C" int squat_dequantize_keys(const uint32_t* codes, const uint16_t* scal
     p.n_tokens = n_tokens;
     p.n_heads = n_heads;
 
-    const int64_t bh = n_batch * n_heads;
     const int64_t gx = (n_tokens * 8 + 255) / 256;
-    int64_t gy = bh, gz = 1;
-    if (gy > 65535) {
-        gz = (bh + 65534) / 65535;
-        // need an exact factorisation so that every (y, z) is a real (batch, head)
-        gy = 0;
-        for (int64_t cand = 65535; cand >= 1; --cand)
-            if (bh % cand == 0) { gy = cand; break; }
-        gz = bh / gy;
-    }
-    if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
+    int64_t gy, gz;
+    if (!split_bh(n_batch * n_heads, gy, gz) || gx > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? launch_group<2>(group, out_dt, p, grid, s)
                      : launch_group<4>(group, out_dt, p, grid, s);
+}
+
+extern "C" int squat_dequantize_keys_per_channel(const uint32_t* codes, const uint16_t* scale,
+                                                 const uint16_t* zero, int64_t n_batch, int n_heads,
+                                                 int64_t n_tokens, int d, int bits, int group, void* k_out,
+                                                 squat_dtype out_dt, int64_t o_stride_batch,
+                                                 int64_t o_stride_head, int64_t o_stride_token,
+                                                 squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != kTileTokens) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_heads < 0 || n_tokens < 0 || n_tokens % group) return SQUAT_E_BADSHAPE;
+    if (out_dt != SQUAT_F32 && out_dt != SQUAT_F16 && out_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_batch == 0 || n_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!codes || !scale || !zero || !k_out) return SQUAT_E_NULLPTR;
+    if (o_stride_token < d || o_stride_batch < 0 || o_stride_head < 0) return SQUAT_E_BADSHAPE;
+    if ((o_stride_token % 8) || (o_stride_head % 8) || (o_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(k_out, 16) || !aligned(codes, 16) || !aligned(scale, 16) || !aligned(zero, 16)) return SQUAT_E_ALIGN;
+
+    const int es = elem_size(out_dt);
+    DeqParams p;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.out = static_cast<unsigned char*>(k_out);
+    p.ob = o_stride_batch * es;
+    p.oh = o_stride_head * es;
+    p.ot = o_stride_token * es;
+    p.n_tokens = n_tokens;
+    p.n_heads = n_heads;
+
+    const int64_t tiles = n_tokens / kTileTokens;
+    const int64_t gx = (tiles + 3) / 4;
+    int64_t gy, gz;
+    if (!split_bh(n_batch * n_heads, gy, gz) || gx > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? launch_pc<2>(out_dt, p, tiles, grid, s) : launch_pc<4>(out_dt, p, tiles, grid, s);
 }

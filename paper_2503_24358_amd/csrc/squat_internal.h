@@ -55,4 +55,41 @@ __host__ __device__ __forceinline__ int row_to_channel(int m) {
     return 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
 }
 
+// Tile pairs (jt, s) of 32-channel tiles with a non-zero update panel: block(jt) > block(s), BT tiles
+// per block, kD / 32 tiles per key.  Enumerated in the order the panels are laid out in LDS.
+__host__ __device__ constexpr int n_pairs(int BT) {
+    int c = 0;
+    for (int s = 0; s < kD / 32; ++s)
+        for (int jt = (s / BT + 1) * BT; jt < kD / 32; ++jt) ++c;
+    return c;
+}
+__host__ __device__ constexpr int pair_index(int BT, int jt, int s) {
+    int c = 0;
+    for (int ss = 0; ss < kD / 32; ++ss)
+        for (int j = (ss / BT + 1) * BT; j < kD / 32; ++j) {
+            if (ss == s && j == jt) return c;
+            ++c;
+        }
+    return -1;
+}
+
+// min (or max) of a value with the same value in lane ^ 32.
+__device__ __forceinline__ float pair_min(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return fminf(as_f32(r[0]), as_f32(r[1]));
+}
+__device__ __forceinline__ float pair_max(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
+    return fmaxf(as_f32(r[0]), as_f32(r[1]));
+}
+
+// Number of compute units of the current device (256 if the query fails).
+inline int device_cu_count() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return 256;
+    return cus;
+}
+
 }  // namespace squat

@@ -53,23 +53,6 @@ struct QuantParams {
     uint32_t div_shift;
 };
 
-// Tile pairs (jt, s) with a non-zero panel: block(jt) > block(s), BT tiles per block.
-__host__ __device__ constexpr int n_pairs(int BT) {
-    int c = 0;
-    for (int s = 0; s < NT; ++s)
-        for (int jt = (s / BT + 1) * BT; jt < NT; ++jt) ++c;
-    return c;
-}
-__host__ __device__ constexpr int pair_index(int BT, int jt, int s) {
-    int c = 0;
-    for (int ss = 0; ss < NT; ++ss)
-        for (int j = (ss / BT + 1) * BT; j < NT; ++j) {
-            if (ss == s && j == jt) return c;
-            ++c;
-        }
-    return -1;
-}
-
 template <int DT>
 struct Elem {
     static constexpr int size = (DT == SQUAT_F32) ? 4 : 2;
@@ -105,15 +88,6 @@ __device__ __forceinline__ void load16(const unsigned char* src, float* out) {
     }
 }
 
-// min (or max) of a value with the same value in lane ^ 32.
-__device__ __forceinline__ float pair_min(float v) {
-    auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
-    return fminf(as_f32(r[0]), as_f32(r[1]));
-}
-__device__ __forceinline__ float pair_max(float v) {
-    auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
-    return fmaxf(as_f32(r[0]), as_f32(r[1]));
-}
 // After the call lanes 32..63 of `a` hold what lanes 0..31 of `b` held and vice versa.
 __device__ __forceinline__ void swap_halves(uint32_t& a, uint32_t& b) {
     auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
@@ -477,14 +451,6 @@ int dispatch_gt(int gt, int bt, squat_dtype dt, const QuantParams& p, int64_t n_
         case 4: return dispatch_bt<BITS, 4>(bt, dt, p, n_prob, s);
     }
     return SQUAT_E_BADSHAPE;
-}
-
-int device_cu_count() {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        return 256;
-    return cus;
 }
 
 }  // namespace

@@ -1,0 +1,496 @@
+// squat_quantize_keys_per_channel: the iteration of Algorithm 1's `Quant` with
+// the block update of Lemma 2 in the paper's own grouping: every channel of a
+// key block is quantized over a group of 32 consecutive TOKENS (KIVI's layout
+// for keys, Section 2 / Algorithm 1), on gfx950.
+//
+// One wavefront owns a tile of 32 tokens x 128 channels = one quantization
+// group of every channel.  The working copy lives in registers in the MFMA
+// 32x32 accumulator layout with a CHANNEL as a column: lane (hh, n) holds, for
+// channel n of each 32-channel tile, tokens 16*hh .. 16*hh+15.  In that layout
+//   - a channel's min/max over the group is an in-register reduction plus one
+//     exchange with lane ^ 32,
+//   - 16 two-bit codes of a lane are one 32-bit word of the token-major packed
+//     output.
+// The update of Lemma 2 is  X[:, rest] += E (tokens x g) * W^T (g x rest):  the
+// error tile is the A operand, which wants a token per lane, so it takes one
+// trip through LDS (4-byte writes, 16-byte reads).  Each error is split into an
+// fp16 high and low part which sit side by side along the MFMA K dimension
+// (K = channel x {high, low}); the matching B operand simply holds every
+// update-matrix entry twice.  Errors of a block are normalised by one common
+// scale per (tile, block), the largest step size among the block's channels, so
+// that the split has a fixed range although every channel has its own step.
+#include <type_traits>
+
+#include "squat_internal.h"
+
+using namespace squat;
+
+namespace {
+
+constexpr int NT = kD / 32;          // 32-channel tiles per key
+constexpr float kErrGain = 256.0f;   // errors enter the fp16 split as multiples of (common scale / 256)
+
+// Wavefronts per workgroup (one workgroup per CU): bounded by LDS (update panels + one staging tile
+// per wavefront) and by registers.
+__host__ __device__ constexpr int pc_waves_for(int dt, int bt) {
+    return dt == SQUAT_F32 ? 6 : (bt == 2 ? 8 : 12);
+}
+
+struct PcParams {
+    const unsigned char* k;
+    int64_t sb, sh, st;              // key strides in BYTES
+    const float* update;
+    int64_t usb;                     // update stride per outer-batch entry, elements
+    uint32_t* codes;
+    uint16_t* scale;
+    uint16_t* zero;
+    int64_t n_inner;                 // batch entries that share one update matrix
+    int n_heads;
+    int64_t tiles_per_seq;
+    int64_t units_per_prob;          // n_inner * tiles_per_seq, < 2^31
+    int wgs_per_prob;
+    uint32_t div_mul;                // unit / tiles_per_seq == (unit * div_mul) >> div_shift for unit < 2^31
+    uint32_t div_shift;
+};
+
+template <int DT>
+__device__ __forceinline__ float load_elem(const unsigned char* src) {
+    if constexpr (DT == SQUAT_F32) {
+        return *reinterpret_cast<const float*>(src);
+    } else if constexpr (DT == SQUAT_BF16) {
+        return as_f32(static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(src)) << 16);
+    } else {
+        return static_cast<float>(__builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t*>(src)));
+    }
+}
+
+__device__ __forceinline__ float dpp_f32(float v, int sel) {
+    int r;
+    switch (sel) {
+        case 0: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0xB1, 0xF, 0xF, true); break;    // quad_perm [1,0,3,2]
+        case 1: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0x4E, 0xF, 0xF, true); break;    // quad_perm [2,3,0,1]
+        case 2: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0x141, 0xF, 0xF, true); break;   // row_half_mirror
+        default: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0x140, 0xF, 0xF, true); break;  // row_mirror
+    }
+    return as_f32(static_cast<uint32_t>(r));
+}
+
+// Maximum over lanes 0..31 of a value that lanes n and n + 32 hold alike; wave-uniform result.
+__device__ __forceinline__ float half_wave_max(float v) {
+    v = fmaxf(v, dpp_f32(v, 0));
+    v = fmaxf(v, dpp_f32(v, 1));
+    v = fmaxf(v, dpp_f32(v, 2));
+    v = fmaxf(v, dpp_f32(v, 3));
+    const float a = as_f32(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(as_u32(v)), 0)));
+    const float b = as_f32(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(as_u32(v)), 16)));
+    return fmaxf(a, b);
+}
+
+template <int BITS, int BT, int DT>
+__global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_kernel(const PcParams p) {
+    constexpr int kWaves = pc_waves_for(DT, BT);
+    constexpr int ES = (DT == SQUAT_F32) ? 4 : 2;
+    constexpr int ROWB = kD * ES;                 // bytes of one key
+    constexpr int LROW = ROWB + 16;               // padded LDS row of the staging tile
+    constexpr int CPR = ROWB / 16;                // 16-byte chunks per key
+    constexpr int NLOAD = 32 * CPR / kWave;       // 16-byte loads per lane per tile
+    constexpr int NPAIRS = n_pairs(BT);
+    constexpr int NB = NT / BT;                   // blocks (iterations) per key
+    constexpr int WPT = BITS / 2;                 // packed words per lane per tile
+    constexpr int CPH = 16 / BITS;                // codes per 16-bit half-word
+    constexpr int EROW = 32 * BT + 4;             // dwords per row of the error tile in LDS (padded)
+    constexpr int NCH = 4 * BT;                   // MFMA K-chunks per block: 8 channels x {high, low} each
+    constexpr float LV = static_cast<float>((1 << BITS) - 1);
+    static_assert(NPAIRS == 0 || 32 * EROW * 4 <= 32 * LROW, "the error tile reuses the staging tile's LDS");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    half8* wlds = reinterpret_cast<half8*>(smem);           // [NPAIRS][4 chunks][hi, lo][64 lanes]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hh = lane >> 5;
+    const int n = lane & 31;
+    unsigned char* stage = smem + NPAIRS * 8192 + wave * (32 * LROW);
+    uint32_t* ebuf = reinterpret_cast<uint32_t*>(stage);
+
+    const int64_t prob = blockIdx.x / p.wgs_per_prob;
+    const int wg = blockIdx.x % p.wgs_per_prob;
+    const int head = static_cast<int>(prob % p.n_heads);
+    const int64_t bo = prob / p.n_heads;
+
+    // Panels whose entries are all fp16 numbers (as squat_prepare writes them) have a zero low part:
+    // the product with it is skipped for the whole head.
+    bool need_lo = false;
+    int* lo_flag = reinterpret_cast<int*>(smem + NPAIRS * 8192 + kWaves * (32 * LROW));
+    if constexpr (NPAIRS > 0) {
+        if (tid == 0) *lo_flag = 0;
+        __syncthreads();
+        // B operand of pair (jt, s), chunk c: lane (hb, m) holds, for output channel 32 jt + m, the
+        // entries U[32 jt + m][32 s + 8 c + 4 hb + i], i = 0..3, each one twice (K = 2 i and 2 i + 1).
+        const float* U = p.update + bo * p.usb + static_cast<int64_t>(head) * kD * kD;
+        for (int idx = tid; idx < NPAIRS * 4 * 64; idx += kWaves * kWave) {
+            const int pr = idx >> 8;
+            const int c = (idx >> 6) & 3;
+            const int l = idx & 63;
+            int jt = 0, s = 0;
+            {
+                int cnt = 0;
+                for (int ss = 0; ss < NT; ++ss)
+                    for (int j = (ss / BT + 1) * BT; j < NT; ++j) {
+                        if (cnt == pr) { jt = j; s = ss; }
+                        ++cnt;
+                    }
+            }
+            const int hb = l >> 5, m = l & 31;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(U + (32 * jt + m) * kD + 32 * s + 8 * c + 4 * hb);
+            half8 hi, lo;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const _Float16 h = static_cast<_Float16>(v[i]);
+                const _Float16 r = static_cast<_Float16>(v[i] - static_cast<float>(h));
+                hi[2 * i] = h; hi[2 * i + 1] = h;
+                lo[2 * i] = r; lo[2 * i + 1] = r;
+            }
+            wlds[((pr * 4 + c) * 2 + 0) * 64 + l] = hi;
+            wlds[((pr * 4 + c) * 2 + 1) * 64 + l] = lo;
+            const u32x4 lb = __builtin_bit_cast(u32x4, lo);
+            if (((lb[0] | lb[1] | lb[2] | lb[3]) & 0x7FFF7FFFu) != 0u) *lo_flag = 1;
+        }
+        __syncthreads();
+        need_lo = *lo_flag != 0;
+    }
+
+    const uint32_t st32 = static_cast<uint32_t>(p.st);
+    u32x4 pre[NLOAD];
+    // unit -> (batch entry, tile): exact multiply-shift division by tiles_per_seq (units < 2^31)
+    auto locate = [&](uint32_t u, uint32_t& bi, uint32_t& tile) {
+        bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
+        tile = u - bi * static_cast<uint32_t>(p.tiles_per_seq);
+    };
+    auto issue_loads = [&](uint32_t u) {
+        uint32_t bi, tile;
+        locate(u, bi, tile);
+        const unsigned char* base = p.k + (bo + bi) * p.sb + head * p.sh + static_cast<int64_t>(tile) * kTileTokens * p.st;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int flat = i * kWave + lane;
+            const int row = flat / CPR;
+            const int ch = flat % CPR;
+            // streamed once: non-temporal, so the tile does not displace the update panels in L2
+            pre[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16)));
+        }
+    };
+
+    const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
+    const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
+    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
+    if (unit < nunits) issue_loads(unit);
+
+    while (unit < nunits) {
+        // ---- registers -> LDS (token-major rows), then read back one channel per lane
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int flat = i * kWave + lane;
+            const int row = flat / CPR, ch = flat % CPR;
+            *reinterpret_cast<u32x4*>(stage + row * LROW + ch * 16) = pre[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        const uint32_t cur = unit;
+        unit += ustride;
+
+        // x[j][e]: token 16 hh + e of the tile, channel 32 j + n
+        float x[NT][16];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                x[j][e] = load_elem<DT>(stage + (16 * hh + e) * LROW + (32 * j + n) * ES);
+
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        if (unit < nunits) issue_loads(unit);   // prefetch the next tile
+
+        uint32_t words[NT][WPT];
+        uint16_t sbits[NT], zbits[NT];
+
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            // ---- statistics of this block's channels over the 32 tokens (current values)
+            float b_zero[BT], b_inv[BT], b_top[BT], b_step[BT];
+            bool b_live[BT];
+            bool risky = false;
+            float contrib = 0.0f;
+#pragma unroll
+            for (int jj = 0; jj < BT; ++jj) {
+                const int j = blk * BT + jj;
+                float mn = x[j][0], mx = x[j][0];
+#pragma unroll
+                for (int e = 1; e < 16; ++e) {
+                    mn = fminf(mn, x[j][e]);
+                    mx = fmaxf(mx, x[j][e]);
+                }
+                mn = pair_min(mn);
+                mx = pair_max(mx);
+                // Correctly rounded (max - min) / (2^b - 1) by one Newton step on the rounded reciprocal
+                // of the constant divisor: an exact quotient stays exact, so a tie of the fp16 rounding
+                // below breaks to even, as the definition does.
+                const float rng = mx - mn;
+                constexpr float RL = 1.0f / LV;
+                const float q0 = rng * RL;
+                const float dl = fmaf(fmaf(-q0, LV, rng), RL, q0);
+                const float sh = round_f16(dl, sbits[j]);
+                const float zh = round_f16(mn, zbits[j]);
+                const bool live = sh > 0.0f;
+                const float sp = live ? sh : 1.0f;
+                float inv = __builtin_amdgcn_rcpf(sp);
+                inv = fmaf(fmaf(-sp, inv, 1.0f), inv, inv);
+                b_zero[jj] = zh;
+                b_inv[jj] = inv;
+                b_top[jj] = live ? LV : 0.0f;
+                b_step[jj] = sp;
+                b_live[jj] = live;
+                risky = risky || !(sh >= 6.2e-5f) || fabsf(zh) * inv > 256.0f;
+                // what this channel's error can reach: half a step, or for a constant channel (scale 0,
+                // every code 0) the distance from the fp16 zero-point to the values themselves
+                const float reach = live ? sh : 2.0f * (fabsf(zh - mn) + rng);
+                contrib = fmaxf(contrib, reach);
+            }
+            // common scale of this block's errors (wave-uniform, never zero)
+            float kappa = 1.0f, rk = kErrGain;
+            if (blk < NB - 1) {
+                kappa = fmaxf(half_wave_max(contrib), 1e-30f);
+                rk = kErrGain / kappa;
+            }
+            // The clamp to [0, 2^b - 1] can only bite when the fp16 rounding of zero/scale moved the
+            // group's ends by more than half a step: scale not a normal fp16 number (incl. 0), or
+            // |zero| / scale > 256.  Otherwise the whole wavefront takes the path without it.
+            const bool clamp = __builtin_amdgcn_ballot_w64(risky) != 0ull;
+            auto quant_block = [&](auto clamp_tag) {
+                constexpr bool CLAMP = decltype(clamp_tag)::value;
+#pragma unroll
+                for (int jj = 0; jj < BT; ++jj) {
+                    const int j = blk * BT + jj;
+                    const float mh = b_zero[jj], inv = b_inv[jj], top = b_top[jj];
+                    const float ratio = b_live[jj] ? b_step[jj] * rk : rk;
+                    // codes are collected per half-word as exact small floats (Horner), then converted once
+                    uint32_t hw[16 / CPH];
+#pragma unroll
+                    for (int q = 16 / CPH - 1; q >= 0; --q) {
+                        float accf = 0.0f;
+#pragma unroll
+                        for (int e = CPH - 1; e >= 0; --e) {
+                            const int c = q * CPH + e;
+                            const float dd = x[j][c] - mh;
+                            float u = dd * inv;
+                            if constexpr (CLAMP) u = __builtin_amdgcn_fmed3f(u, 0.0f, top);
+                            const float code = __builtin_rintf(u);
+                            accf = fmaf(accf, static_cast<float>(1 << BITS), code);
+                            if (blk < NB - 1) {
+                                // error  code - (x - m)/Delta  in units of the common scale / 256, split into
+                                // a part with 11 significant bits (exact in fp16) and the remainder
+                                float et = fmaf(-inv, dd, code) * ratio;
+                                if constexpr (CLAMP) et = __builtin_amdgcn_fmed3f(et, -60000.0f, 60000.0f);
+                                const float eh = as_f32(as_u32(et) & 0xFFFFE000u);
+                                const float el = et - eh;
+                                // row of the MFMA A operand that stands for token 16 hh + c
+                                const int mrow = 8 * (c >> 2) + 4 * hh + (c & 3);
+                                if constexpr (NPAIRS > 0)
+                                    ebuf[mrow * EROW + 32 * jj + n] =
+                                        __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(eh, el));
+                            }
+                        }
+                        hw[q] = static_cast<uint32_t>(accf);
+                    }
+#pragma unroll
+                    for (int w = 0; w < WPT; ++w) words[j][w] = hw[2 * w] | (hw[2 * w + 1] << 16);
+                }
+            };
+            if (clamp)
+                quant_block(std::true_type{});
+            else
+                quant_block(std::false_type{});
+            // ---- Lemma 2: remaining channels += error * U[rest, block]^T
+            if constexpr (NPAIRS > 0) {
+                if (blk < NB - 1) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    // A operand, chunk c: lane (ha, m) holds row m, K = 8 ha .. 8 ha + 7, i.e. channels
+                    // 8 c + 4 ha .. + 3 of the block, each as (high, low)
+                    half8 aop[NCH];
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c)
+                        aop[c] = __builtin_bit_cast(
+                            half8, *reinterpret_cast<const u32x4*>(ebuf + n * EROW + 8 * c + 4 * hh));
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const float ks = kappa * (1.0f / kErrGain);
+#pragma unroll
+                    for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
+                        f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                        for (int jj = 0; jj < BT; ++jj) {
+                            const int pr = pair_index(BT, jt, blk * BT + jj);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const half8 whi = wlds[((pr * 4 + c) * 2 + 0) * 64 + lane];
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], whi, acc, 0, 0, 0);
+                                if (need_lo) {
+                                    const half8 wlo = wlds[((pr * 4 + c) * 2 + 1) * 64 + lane];
+                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], wlo, acc, 0, 0, 0);
+                                }
+                            }
+                        }
+                        // accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3), i.e. token 16 hh + e
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(ks, acc[e], x[jt][e]);
+                    }
+                }
+            }
+        }
+
+        // ---- outputs
+        uint32_t bi, tile;
+        locate(cur, bi, tile);
+        const int64_t gt = ((bo + bi) * p.n_heads + head) * p.tiles_per_seq + tile;     // wave-uniform
+        // codes[tile][channel][BITS words]: this lane's 16 tokens are words hh * WPT .. of its channel
+        uint32_t* cdst = p.codes + gt * (kD * BITS) + n * BITS + hh * WPT;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            if constexpr (WPT == 1)
+                __builtin_nontemporal_store(words[j][0], cdst + 32 * j * BITS);
+            else
+                __builtin_nontemporal_store(u32x2{words[j][0], words[j][1]},
+                                            reinterpret_cast<u32x2*>(cdst + 32 * j * BITS));
+        }
+        // lanes 0..31 write the scales, lanes 32..63 the zero-points; even lanes store their
+        // neighbour's value with their own (two channels per 32-bit word)
+        uint16_t* mbase = (hh ? p.zero : p.scale) + gt * kD + n;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const uint32_t mine = hh ? zbits[j] : sbits[j];
+            const uint32_t other = static_cast<uint32_t>(
+                __builtin_amdgcn_mov_dpp(static_cast<int>(mine), 0xB1, 0xF, 0xF, true));
+            if ((n & 1) == 0)
+                __builtin_nontemporal_store(mine | (other << 16), reinterpret_cast<uint32_t*>(mbase + 32 * j));
+        }
+    }
+}
+
+template <int BITS, int BT, int DT>
+int launch(const PcParams& p, int64_t n_prob, hipStream_t stream) {
+    constexpr int ES = (DT == SQUAT_F32) ? 4 : 2;
+    constexpr int kWaves = pc_waves_for(DT, BT);
+    constexpr size_t lds = n_pairs(BT) * 8192 + kWaves * 32 * (kD * ES + 16) + 16;
+    auto kern = quantize_pc_kernel<BITS, BT, DT>;
+    static bool attr_done = false;      // idempotent; a race only repeats the call
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+            return SQUAT_E_HIP;
+        attr_done = true;
+    }
+    const dim3 grid(static_cast<unsigned>(n_prob * p.wgs_per_prob));
+    hipLaunchKernelGGL(kern, grid, dim3(kWaves * kWave), lds, stream, p);
+    return check_launch();
+}
+
+template <int BITS, int BT>
+int dispatch_dt(squat_dtype dt, const PcParams& p, int64_t n_prob, hipStream_t s) {
+    switch (dt) {
+        case SQUAT_F32: return launch<BITS, BT, SQUAT_F32>(p, n_prob, s);
+        case SQUAT_F16: return launch<BITS, BT, SQUAT_F16>(p, n_prob, s);
+        case SQUAT_BF16: return launch<BITS, BT, SQUAT_BF16>(p, n_prob, s);
+    }
+    return SQUAT_E_BADDTYPE;
+}
+template <int BITS>
+int dispatch_bt(int bt, squat_dtype dt, const PcParams& p, int64_t n_prob, hipStream_t s) {
+    switch (bt) {
+        case 1: return dispatch_dt<BITS, 1>(dt, p, n_prob, s);
+        case 2: return dispatch_dt<BITS, 2>(dt, p, n_prob, s);
+        case 4: return dispatch_dt<BITS, 4>(dt, p, n_prob, s);
+    }
+    return SQUAT_E_BADSHAPE;
+}
+
+}  // namespace
+
+extern "C" int squat_quantize_keys_per_channel(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
+                                               int64_t n_tokens, int d, int64_t k_stride_batch,
+                                               int64_t k_stride_head, int64_t k_stride_token,
+                                               const float* update, int64_t update_stride_batch, int bits,
+                                               int group, int g, uint32_t* codes, uint16_t* scale,
+                                               uint16_t* zero, squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != kTileTokens) return SQUAT_E_BADSHAPE;
+    if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_heads < 0 || n_tokens < 0) return SQUAT_E_BADSHAPE;
+    if (n_tokens % group) return SQUAT_E_BADSHAPE;
+    if (k_dt != SQUAT_F32 && k_dt != SQUAT_F16 && k_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_batch == 0 || n_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!k || !codes || !scale || !zero) return SQUAT_E_NULLPTR;
+    if (k_stride_token < d || k_stride_batch < 0 || k_stride_head < 0 || update_stride_batch < 0)
+        return SQUAT_E_BADSHAPE;
+    if ((k_stride_token % 8) || (k_stride_head % 8) || (k_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(k, 16) || !aligned(codes, 16) || !aligned(scale, 4) || !aligned(zero, 4)) return SQUAT_E_ALIGN;
+    if (update && (!aligned(update, 16) || (update_stride_batch % 4))) return SQUAT_E_ALIGN;
+    if (n_batch * n_heads > (int64_t(1) << 30)) return SQUAT_E_BADSHAPE;
+
+    const int es = elem_size(k_dt);
+    PcParams p;
+    p.k = static_cast<const unsigned char*>(k);
+    p.sb = k_stride_batch * es;
+    p.sh = k_stride_head * es;
+    p.st = k_stride_token * es;
+    p.update = update;
+    p.usb = update_stride_batch;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.n_heads = n_heads;
+    p.tiles_per_seq = n_tokens / kTileTokens;
+
+    // Workgroups are bound to one update matrix: per head when it is shared across the
+    // batch, per (batch, head) otherwise.
+    int64_t n_prob;
+    if (update && update_stride_batch != 0) {
+        n_prob = n_batch * n_heads;
+        p.n_inner = 1;
+    } else {
+        n_prob = n_heads;
+        p.n_inner = n_batch;
+    }
+    p.units_per_prob = p.n_inner * p.tiles_per_seq;
+    if (p.units_per_prob >= (int64_t(1) << 31) || p.tiles_per_seq >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    if (k_stride_token * es >= (int64_t(1) << 26)) return SQUAT_E_BADSHAPE;
+    {
+        // floor(u / dv) for u < 2^31: shift = 31 + ceil(log2 dv), mul = floor(2^shift / dv) + 1
+        const uint64_t dv = static_cast<uint64_t>(p.tiles_per_seq);
+        uint32_t l = 0;
+        while ((uint64_t(1) << l) < dv) ++l;
+        p.div_shift = 31 + l;
+        p.div_mul = static_cast<uint32_t>(((uint64_t(1) << p.div_shift) / dv) + 1);
+    }
+
+    const int bt = update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
+    const int kw = pc_waves_for(k_dt, bt);
+    int64_t per = (static_cast<int64_t>(device_cu_count()) + n_prob - 1) / n_prob;     // fill every CU once
+    const int64_t need = (p.units_per_prob + kw - 1) / kw;
+    if (per > need) per = need;
+    if (per < 1) per = 1;
+    p.wgs_per_prob = static_cast<int>(per);
+    if (n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? dispatch_bt<2>(bt, k_dt, p, n_prob, s) : dispatch_bt<4>(bt, k_dt, p, n_prob, s);
+}

@@ -19,7 +19,8 @@ _lib = None
 
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
-           "squat_quantize_keys", "squat_dequantize_keys")
+           "squat_quantize_keys", "squat_dequantize_keys",
+           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel")
 
 
 class SquatError(RuntimeError):
@@ -55,6 +56,10 @@ def lib() -> ctypes.CDLL:
                                       vp, vp, vp, vp]
     L.squat_dequantize_keys.restype = i32
     L.squat_dequantize_keys.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i32, i64, i64, i64, vp]
+    L.squat_quantize_keys_per_channel.restype = i32
+    L.squat_quantize_keys_per_channel.argtypes = L.squat_quantize_keys.argtypes
+    L.squat_dequantize_keys_per_channel.restype = i32
+    L.squat_dequantize_keys_per_channel.argtypes = L.squat_dequantize_keys.argtypes
     _lib = L
     return L
 
@@ -182,4 +187,57 @@ def dequantize_keys(codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor
                                      _DT[out.dtype], out.stride(0), out.stride(1), out.stride(2), _stream(stream))
     if rc:
         raise SquatError(rc, "squat_dequantize_keys")
+    return out
+
+
+def quantize_keys_per_channel(k: torch.Tensor, update: Optional[torch.Tensor], bits: int, group: int, g: int, *,
+                              codes=None, scale=None, zero=None, stream=None):
+    """squat_quantize_keys_per_channel.  k: [n_batch, n_heads, n_tokens, d], n_tokens a multiple of
+    group (= 32); update as for quantize_keys.
+    Returns (codes uint32 viewed as int32 [B,H,n/32,d,bits], scale f16 [B,H,n/32,d], zero f16)."""
+    _need_cuda(k, update)
+    b, h, n, d = k.shape
+    if k.stride(3) != 1:
+        raise ValueError("k must have unit channel stride")
+    if group <= 0 or n % group:
+        raise ValueError("n_tokens must be a multiple of group")
+    dev = k.device
+    usb = 0
+    if update is not None:
+        if update.dtype != torch.float32 or not update.is_contiguous():
+            raise ValueError("update must be dense float32")
+        if update.dim() == 4:
+            usb = update.stride(0)
+    if codes is None:
+        codes = torch.empty((b, h, n // 32, d, bits), dtype=torch.int32, device=dev)
+    if scale is None:
+        scale = torch.empty((b, h, n // group, d), dtype=torch.float16, device=dev)
+    if zero is None:
+        zero = torch.empty((b, h, n // group, d), dtype=torch.float16, device=dev)
+    rc = lib().squat_quantize_keys_per_channel(_ptr(k), _DT[k.dtype], b, h, n, d, k.stride(0), k.stride(1),
+                                               k.stride(2), _ptr(update), usb, bits, group, g, _ptr(codes),
+                                               _ptr(scale), _ptr(zero), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_quantize_keys_per_channel")
+    return codes, scale, zero
+
+
+def dequantize_keys_per_channel(codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor, bits: int,
+                                group: int, out_dtype=torch.bfloat16, *, out=None, stream=None) -> torch.Tensor:
+    """squat_dequantize_keys_per_channel.  Dense codes [B,H,n/32,d,bits], scale/zero [B,H,n/group,d]
+    as written by quantize_keys_per_channel -> k [B,H,n,d]."""
+    _need_cuda(codes, scale, zero)
+    b, h, tiles, d, w = codes.shape
+    if w != bits:
+        raise ValueError("codes must be [B, H, n/32, d, bits]")
+    if not (codes.is_contiguous() and scale.is_contiguous() and zero.is_contiguous()):
+        raise ValueError("codes/scale/zero must be dense")
+    n = tiles * 32
+    if out is None:
+        out = torch.empty((b, h, n, d), dtype=out_dtype, device=codes.device)
+    rc = lib().squat_dequantize_keys_per_channel(_ptr(codes), _ptr(scale), _ptr(zero), b, h, n, d, bits, group,
+                                                 _ptr(out), _DT[out.dtype], out.stride(0), out.stride(1),
+                                                 out.stride(2), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_dequantize_keys_per_channel")
     return out

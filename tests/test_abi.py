@@ -91,3 +91,40 @@ def test_argument_validation_happens_before_any_launch():
     assert pr(qhat=None) == -1
     assert pr(ws=None) == -5
     assert pr(wsb=8) == -5
+
+
+def test_per_channel_argument_validation_happens_before_any_launch():
+    L = squat.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    q = lambda **kw: L.squat_quantize_keys_per_channel(  # noqa: E731
+        kw.get("k", fake), kw.get("dt", 2), kw.get("b", 1), kw.get("h", 1), kw.get("n", 64), kw.get("d", 128),
+        kw.get("sb", 8192), kw.get("sh", 8192), kw.get("st", 128), kw.get("u", None), 0, kw.get("bits", 2),
+        kw.get("G", 32), kw.get("g", 32), kw.get("codes", fake), fake, fake, None)
+    assert q(d=64) == -2
+    assert q(bits=3) == -2
+    assert q(G=64) == -2            # token groups are 32 tokens
+    assert q(G=16) == -2
+    assert q(g=16) == -2
+    assert q(n=40) == -2            # not a multiple of the group
+    assert q(dt=7) == -3
+    assert q(k=None) == -1
+    assert q(codes=None) == -1
+    assert q(st=120) == -2
+    assert q(st=132) == -4
+    assert q(k=odd) == -4
+    assert q(n=0) == 0
+    assert q(n=-32) == -2
+
+    dq = lambda **kw: L.squat_dequantize_keys_per_channel(  # noqa: E731
+        kw.get("codes", fake), fake, fake, 1, 1, kw.get("n", 64), kw.get("d", 128), kw.get("bits", 2),
+        kw.get("G", 32), kw.get("out", fake), kw.get("dt", 2), 8192, 8192, kw.get("st", 128), None)
+    assert dq(d=256) == -2
+    assert dq(bits=8) == -2
+    assert dq(G=128) == -2
+    assert dq(n=33) == -2
+    assert dq(out=None) == -1
+    assert dq(dt=5) == -3
+    assert dq(st=130) == -4
+    assert dq(codes=odd) == -4
+    assert dq(n=0) == 0
