@@ -28,12 +28,21 @@ using namespace squat;
 namespace {
 
 constexpr int NT = kD / 32;          // 32-channel tiles per key
+#ifndef SQUAT_PC_DIAG
+#define SQUAT_PC_DIAG 0
+#endif
 constexpr float kErrGain = 256.0f;   // errors enter the fp16 split as multiples of (common scale / 256)
 
 // Wavefronts per workgroup (one workgroup per CU): bounded by LDS (update panels + one staging tile
 // per wavefront) and by registers.
 __host__ __device__ constexpr int pc_waves_for(int dt, int bt) {
-    return dt == SQUAT_F32 ? 6 : (bt == 2 ? 8 : 12);
+#ifndef SQUAT_PC_W1
+#define SQUAT_PC_W1 12
+#endif
+#ifndef SQUAT_PC_W2
+#define SQUAT_PC_W2 8
+#endif
+    return dt == SQUAT_F32 ? 6 : (bt == 2 ? SQUAT_PC_W2 : (bt == 1 ? SQUAT_PC_W1 : 12));
 }
 
 struct PcParams {
@@ -168,18 +177,23 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
         bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
         tile = u - bi * static_cast<uint32_t>(p.tiles_per_seq);
     };
+    // lane part of a load address: 16-byte chunk (lane % CPR) of row (lane / CPR); load i adds 64 / CPR rows
+    const uint32_t lane_off = static_cast<uint32_t>(lane / CPR) * st32 + static_cast<uint32_t>(lane % CPR) * 16;
     auto issue_loads = [&](uint32_t u) {
         uint32_t bi, tile;
         locate(u, bi, tile);
-        const unsigned char* base = p.k + (bo + bi) * p.sb + head * p.sh + static_cast<int64_t>(tile) * kTileTokens * p.st;
+        // wave-uniform by construction; say so, so that the loads take a scalar base and one lane offset
+        // (the builtin returns a signed int: widen both halves as unsigned)
+        const uint64_t voff = static_cast<uint64_t>((bo + bi) * p.sb + head * p.sh +
+                                                    static_cast<int64_t>(tile) * kTileTokens * p.st);
+        const uint32_t off_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(voff >> 32)));
+        const uint32_t off_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(voff & 0xFFFFFFFFull)));
+        const unsigned char* base = p.k + ((static_cast<uint64_t>(off_hi) << 32) | static_cast<uint64_t>(off_lo));
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            const int flat = i * kWave + lane;
-            const int row = flat / CPR;
-            const int ch = flat % CPR;
             // streamed once: non-temporal, so the tile does not displace the update panels in L2
             pre[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16)));
+                reinterpret_cast<const u32x4*>(base + static_cast<int64_t>(i * (kWave / CPR)) * p.st + lane_off));
         }
     };
 
@@ -209,13 +223,21 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
         for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                x[j][e] = load_elem<DT>(stage + (16 * hh + e) * LROW + (32 * j + n) * ES);
+                x[j][e] = (SQUAT_PC_DIAG & 4) ? as_f32(pre[(j * 16 + e) & (NLOAD - 1)][e & 3] & 0x3FFFFFFFu)
+                                              : load_elem<DT>(stage + (16 * hh + e) * LROW + (32 * j + n) * ES);
 
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        if (unit < nunits) issue_loads(unit);   // prefetch the next tile
+        // The next tile is prefetched into registers; with several blocks the loads are issued only once
+        // the first half of the blocks is frozen, so that they reuse the registers of those tiles.
+#ifndef SQUAT_PC_PF
+#define SQUAT_PC_PF (NB / 2 - 1)
+#endif
+        constexpr int PF_BLK = NB >= 2 ? SQUAT_PC_PF : -1;
+        if constexpr (PF_BLK < 0)
+            if (unit < nunits) issue_loads(unit);
 
         uint32_t words[NT][WPT];
         uint16_t sbits[NT], zbits[NT];
@@ -301,7 +323,7 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                                 const float el = et - eh;
                                 // row of the MFMA A operand that stands for token 16 hh + c
                                 const int mrow = 8 * (c >> 2) + 4 * hh + (c & 3);
-                                if constexpr (NPAIRS > 0)
+                                if constexpr (NPAIRS > 0 && !(SQUAT_PC_DIAG & 2))
                                     ebuf[mrow * EROW + 32 * jj + n] =
                                         __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(eh, el));
                             }
@@ -329,30 +351,51 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                     for (int c = 0; c < NCH; ++c)
                         aop[c] = __builtin_bit_cast(
                             half8, *reinterpret_cast<const u32x4*>(ebuf + n * EROW + 8 * c + 4 * hh));
+                    const float ks = kappa * (1.0f / kErrGain);
+                    // two straight-line versions (with and without the low parts of the panels), so that
+                    // the operand reads of a whole chain can be issued ahead of its matrix products
+                    auto propagate = [&](auto lo_tag) {
+                        constexpr bool LO = decltype(lo_tag)::value;
+#pragma unroll
+                        for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
+                            f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                            for (int jj = 0; jj < BT; ++jj) {
+                                const int pr = pair_index(BT, jt, blk * BT + jj);
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) {
+                                    const half8 whi = wlds[((pr * 4 + c) * 2 + 0) * 64 + lane];
+                                    if constexpr (!(SQUAT_PC_DIAG & 1))
+                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], whi, acc, 0, 0, 0);
+                                    if constexpr (LO) {
+                                        const half8 wlo = wlds[((pr * 4 + c) * 2 + 1) * 64 + lane];
+                                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], wlo, acc, 0, 0, 0);
+                                    }
+                                }
+                            }
+                            // accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3), i.e. token 16 hh + e
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(ks, acc[e], x[jt][e]);
+                        }
+                    };
+                    if (need_lo)
+                        propagate(std::true_type{});
+                    else
+                        propagate(std::false_type{});
+                    // the next block's error tile must not overtake this block's operand reads
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    const float ks = kappa * (1.0f / kErrGain);
+                }
+            }
+            if (blk == PF_BLK) {
+                if (unit < nunits) {
+                    issue_loads(unit);
+                } else {
+                    // the loop ends after this tile: say that the old contents are dead, or they would be
+                    // kept in registers up to this point
 #pragma unroll
-                    for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
-                        f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                        for (int jj = 0; jj < BT; ++jj) {
-                            const int pr = pair_index(BT, jt, blk * BT + jj);
-#pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                const half8 whi = wlds[((pr * 4 + c) * 2 + 0) * 64 + lane];
-                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], whi, acc, 0, 0, 0);
-                                if (need_lo) {
-                                    const half8 wlo = wlds[((pr * 4 + c) * 2 + 1) * 64 + lane];
-                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], wlo, acc, 0, 0, 0);
-                                }
-                            }
-                        }
-                        // accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3), i.e. token 16 hh + e
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(ks, acc[e], x[jt][e]);
-                    }
+                    for (int i = 0; i < NLOAD; ++i) pre[i] = __builtin_nondeterministic_value(pre[i]);
                 }
             }
         }
