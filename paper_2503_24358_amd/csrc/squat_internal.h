@@ -73,14 +73,27 @@ __host__ __device__ constexpr int pair_index(int BT, int jt, int s) {
     return -1;
 }
 
+// min / max as the single machine instruction (the C library functions add one instruction per
+// operand that only matters for signalling NaNs when the operands come out of a lane exchange).
+__device__ __forceinline__ float raw_min(float a, float b) {
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float raw_max(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // min (or max) of a value with the same value in lane ^ 32.
 __device__ __forceinline__ float pair_min(float v) {
     auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
-    return fminf(as_f32(r[0]), as_f32(r[1]));
+    return raw_min(as_f32(r[0]), as_f32(r[1]));
 }
 __device__ __forceinline__ float pair_max(float v) {
     auto r = __builtin_amdgcn_permlane32_swap(as_u32(v), as_u32(v), false, false);
-    return fmaxf(as_f32(r[0]), as_f32(r[1]));
+    return raw_max(as_f32(r[0]), as_f32(r[1]));
 }
 
 // Number of compute units of the current device (256 if the query fails).

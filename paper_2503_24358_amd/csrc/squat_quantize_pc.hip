@@ -13,12 +13,18 @@
 //     output.
 // The update of Lemma 2 is  X[:, rest] += E (tokens x g) * W^T (g x rest):  the
 // error tile is the A operand, which wants a token per lane, so it takes one
-// trip through LDS (4-byte writes, 16-byte reads).  Each error is split into an
-// fp16 high and low part which sit side by side along the MFMA K dimension
-// (K = channel x {high, low}); the matching B operand simply holds every
-// update-matrix entry twice.  Errors of a block are normalised by one common
-// scale per (tile, block), the largest step size among the block's channels, so
-// that the split has a fixed range although every channel has its own step.
+// trip through LDS (4-byte writes, 16-byte reads), and the working copy itself
+// is the accumulator of the matrix product.  Each error (in the keys' own
+// units) is split into an fp16 high part and a low part scaled by 2^11, which
+// sit side by side along the MFMA K dimension (K = channel x {high, low}); the
+// matching B operand holds every update-matrix entry twice, the second copy
+// scaled by 2^-11.  The scaling keeps the low part a normal fp16 number
+// whenever the high part is one, so the pair carries the error to 2^-21
+// relative (or 2^-35 absolute) for every step size fp16 can hold.
+// 16-bit keys reach the accumulator layout through the matrix cores as well:
+// the raw key rows (16-byte pieces, the A operand as it lies in memory) times a
+// 0/1 selection matrix is an exact conversion to fp32 and a transposition in
+// one step.
 #include <type_traits>
 
 #include "squat_internal.h"
@@ -28,21 +34,16 @@ using namespace squat;
 namespace {
 
 constexpr int NT = kD / 32;          // 32-channel tiles per key
-#ifndef SQUAT_PC_DIAG
-#define SQUAT_PC_DIAG 0
-#endif
-constexpr float kErrGain = 256.0f;   // errors enter the fp16 split as multiples of (common scale / 256)
+
+constexpr float kLoGain = 2048.0f;   // the low part of an error enters the matrix product times 2^11
+constexpr float kFastOffset = 32.0f; // largest |zero| / scale for which the one-multiply-add path is used
+constexpr float kFastStep = 0.015625f;  // smallest step size for which the cheap error split is used (see below)
 
 // Wavefronts per workgroup (one workgroup per CU): bounded by LDS (update panels + one staging tile
-// per wavefront) and by registers.
+// per wavefront) and by registers (168 per lane at 12 wavefronts).
 __host__ __device__ constexpr int pc_waves_for(int dt, int bt) {
-#ifndef SQUAT_PC_W1
-#define SQUAT_PC_W1 12
-#endif
-#ifndef SQUAT_PC_W2
-#define SQUAT_PC_W2 8
-#endif
-    return dt == SQUAT_F32 ? 6 : (bt == 2 ? SQUAT_PC_W2 : (bt == 1 ? SQUAT_PC_W1 : 12));
+    (void)bt;
+    return dt == SQUAT_F32 ? 6 : 12;
 }
 
 struct PcParams {
@@ -73,28 +74,6 @@ __device__ __forceinline__ float load_elem(const unsigned char* src) {
     }
 }
 
-__device__ __forceinline__ float dpp_f32(float v, int sel) {
-    int r;
-    switch (sel) {
-        case 0: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0xB1, 0xF, 0xF, true); break;    // quad_perm [1,0,3,2]
-        case 1: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0x4E, 0xF, 0xF, true); break;    // quad_perm [2,3,0,1]
-        case 2: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0x141, 0xF, 0xF, true); break;   // row_half_mirror
-        default: r = __builtin_amdgcn_mov_dpp(static_cast<int>(as_u32(v)), 0x140, 0xF, 0xF, true); break;  // row_mirror
-    }
-    return as_f32(static_cast<uint32_t>(r));
-}
-
-// Maximum over lanes 0..31 of a value that lanes n and n + 32 hold alike; wave-uniform result.
-__device__ __forceinline__ float half_wave_max(float v) {
-    v = fmaxf(v, dpp_f32(v, 0));
-    v = fmaxf(v, dpp_f32(v, 1));
-    v = fmaxf(v, dpp_f32(v, 2));
-    v = fmaxf(v, dpp_f32(v, 3));
-    const float a = as_f32(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(as_u32(v)), 0)));
-    const float b = as_f32(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(as_u32(v)), 16)));
-    return fmaxf(a, b);
-}
-
 template <int BITS, int BT, int DT>
 __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_kernel(const PcParams p) {
     constexpr int kWaves = pc_waves_for(DT, BT);
@@ -110,6 +89,7 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
     constexpr int EROW = 32 * BT + 4;             // dwords per row of the error tile in LDS (padded)
     constexpr int NCH = 4 * BT;                   // MFMA K-chunks per block: 8 channels x {high, low} each
     constexpr float LV = static_cast<float>((1 << BITS) - 1);
+    constexpr bool XL = DT != SQUAT_F32;          // load through the matrix cores (16-bit keys)
     static_assert(NPAIRS == 0 || 32 * EROW * 4 <= 32 * LROW, "the error tile reuses the staging tile's LDS");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -132,11 +112,28 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
     // the product with it is skipped for the whole head.
     bool need_lo = false;
     int* lo_flag = reinterpret_cast<int*>(smem + NPAIRS * 8192 + kWaves * (32 * LROW));
+    // Selection matrices for the load: B operand of chunk c (16 channels of a 32-channel tile): lane (hb, m)
+    // holds B[k = 8 hb + i][m] = 1 if m == 16 c + 8 hb + i, in the keys' own 16-bit format.
+    u32x4* sel_lds = reinterpret_cast<u32x4*>(smem + NPAIRS * 8192 + kWaves * (32 * LROW) + 16);
+    if constexpr (XL) {
+        constexpr uint32_t ONE = DT == SQUAT_BF16 ? 0x3F80u : 0x3C00u;
+        for (int idx = tid; idx < 2 * 64; idx += kWaves * kWave) {
+            const int c = idx >> 6, l = idx & 63;
+            const int i1 = (l & 31) - 16 * c - 8 * (l >> 5);        // the i with a one, if in 0..7
+            u32x4 v;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                v[w] = (i1 == 2 * w ? ONE : 0u) | (i1 == 2 * w + 1 ? ONE << 16 : 0u);
+            sel_lds[idx] = v;
+        }
+        if constexpr (NPAIRS == 0) __syncthreads();
+    }
     if constexpr (NPAIRS > 0) {
         if (tid == 0) *lo_flag = 0;
         __syncthreads();
         // B operand of pair (jt, s), chunk c: lane (hb, m) holds, for output channel 32 jt + m, the
-        // entries U[32 jt + m][32 s + 8 c + 4 hb + i], i = 0..3, each one twice (K = 2 i and 2 i + 1).
+        // entries U[32 jt + m][32 s + 8 c + 4 hb + i], i = 0..3, each one twice: K = 2 i meets the high
+        // part of the error, K = 2 i + 1 its low part times 2^11, so that copy is scaled by 2^-11.
         const float* U = p.update + bo * p.usb + static_cast<int64_t>(head) * kD * kD;
         for (int idx = tid; idx < NPAIRS * 4 * 64; idx += kWaves * kWave) {
             const int pr = idx >> 8;
@@ -158,8 +155,8 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
             for (int i = 0; i < 4; ++i) {
                 const _Float16 h = static_cast<_Float16>(v[i]);
                 const _Float16 r = static_cast<_Float16>(v[i] - static_cast<float>(h));
-                hi[2 * i] = h; hi[2 * i + 1] = h;
-                lo[2 * i] = r; lo[2 * i + 1] = r;
+                hi[2 * i] = h; hi[2 * i + 1] = static_cast<_Float16>(static_cast<float>(h) * (1.0f / kLoGain));
+                lo[2 * i] = r; lo[2 * i + 1] = static_cast<_Float16>(static_cast<float>(r) * (1.0f / kLoGain));
             }
             wlds[((pr * 4 + c) * 2 + 0) * 64 + l] = hi;
             wlds[((pr * 4 + c) * 2 + 1) * 64 + l] = lo;
@@ -207,7 +204,10 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
             const int flat = i * kWave + lane;
-            const int row = flat / CPR, ch = flat % CPR;
+            const int tok = flat / CPR, ch = flat % CPR;
+            // token 16 a + 4 b + c goes to row 8 b + 4 a + c: the row of the MFMA accumulator whose
+            // register 4 b + c in lane half a stands for it
+            const int row = 8 * ((tok >> 2) & 3) + 4 * (tok >> 4) + (tok & 3);
             *reinterpret_cast<u32x4*>(stage + row * LROW + ch * 16) = pre[i];
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -218,13 +218,35 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
         unit += ustride;
 
         // x[j][e]: token 16 hh + e of the tile, channel 32 j + n
-        float x[NT][16];
+        f32x16 x[NT];
+        if constexpr (XL) {
+            const u32x4 sel0 = sel_lds[lane], sel1 = sel_lds[64 + lane];
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+            for (int j = 0; j < NT; ++j) {
+                // A operand: lane (hh, n) holds row n, K = 8 hh .. 8 hh + 7 of each 16-channel chunk
+                const u32x4 a0 = *reinterpret_cast<const u32x4*>(stage + n * LROW + (32 * j + 8 * hh) * ES);
+                const u32x4 a1 = *reinterpret_cast<const u32x4*>(stage + n * LROW + (32 * j + 16 + 8 * hh) * ES);
+                f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                if constexpr (DT == SQUAT_BF16) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0),
+                                                                  __builtin_bit_cast(bf16x8, sel0), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1),
+                                                                  __builtin_bit_cast(bf16x8, sel1), acc, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a0),
+                                                                 __builtin_bit_cast(half8, sel0), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a1),
+                                                                 __builtin_bit_cast(half8, sel1), acc, 0, 0, 0);
+                }
+                x[j] = acc;
+            }
+        } else {
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                x[j][e] = (SQUAT_PC_DIAG & 4) ? as_f32(pre[(j * 16 + e) & (NLOAD - 1)][e & 3] & 0x3FFFFFFFu)
-                                              : load_elem<DT>(stage + (16 * hh + e) * LROW + (32 * j + n) * ES);
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    x[j][e] = load_elem<DT>(stage + (8 * (e >> 2) + 4 * hh + (e & 3)) * LROW + (32 * j + n) * ES);
+        }
 
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -232,10 +254,7 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
 
         // The next tile is prefetched into registers; with several blocks the loads are issued only once
         // the first half of the blocks is frozen, so that they reuse the registers of those tiles.
-#ifndef SQUAT_PC_PF
-#define SQUAT_PC_PF (NB / 2 - 1)
-#endif
-        constexpr int PF_BLK = NB >= 2 ? SQUAT_PC_PF : -1;
+        constexpr int PF_BLK = NB >= 2 ? NB / 2 - 1 : -1;
         if constexpr (PF_BLK < 0)
             if (unit < nunits) issue_loads(unit);
 
@@ -246,9 +265,7 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
         for (int blk = 0; blk < NB; ++blk) {
             // ---- statistics of this block's channels over the 32 tokens (current values)
             float b_zero[BT], b_inv[BT], b_top[BT], b_step[BT];
-            bool b_live[BT];
             bool risky = false;
-            float contrib = 0.0f;
 #pragma unroll
             for (int jj = 0; jj < BT; ++jj) {
                 const int j = blk * BT + jj;
@@ -277,22 +294,17 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                 b_inv[jj] = inv;
                 b_top[jj] = live ? LV : 0.0f;
                 b_step[jj] = sp;
-                b_live[jj] = live;
-                risky = risky || !(sh >= 6.2e-5f) || fabsf(zh) * inv > 256.0f;
-                // what this channel's error can reach: half a step, or for a constant channel (scale 0,
-                // every code 0) the distance from the fp16 zero-point to the values themselves
-                const float reach = live ? sh : 2.0f * (fabsf(zh - mn) + rng);
-                contrib = fmaxf(contrib, reach);
+                risky = risky || !(sh >= kFastStep) || fabsf(zh) * inv > kFastOffset;
             }
-            // common scale of this block's errors (wave-uniform, never zero)
-            float kappa = 1.0f, rk = kErrGain;
-            if (blk < NB - 1) {
-                kappa = fmaxf(half_wave_max(contrib), 1e-30f);
-                rk = kErrGain / kappa;
-            }
-            // The clamp to [0, 2^b - 1] can only bite when the fp16 rounding of zero/scale moved the
-            // group's ends by more than half a step: scale not a normal fp16 number (incl. 0), or
-            // |zero| / scale > 256.  Otherwise the whole wavefront takes the path without it.
+            // Two versions of the block.  The careful one clamps to [0, 2^b - 1] (which can only bite when
+            // the fp16 rounding of zero/scale moved the group's ends by more than half a step: scale not a
+            // normal fp16 number, incl. 0, or |zero| / scale > 256), computes (x - m) / Delta as written
+            // and takes the high part of the error from a real conversion to fp16, exact for any size.
+            // The cheap one folds the zero-point into one multiply-add, x * (1/Delta) - m/Delta, whose
+            // rounding error grows with |m| / Delta, and masks the high part in fp32, which loses up to
+            // 2^-24 (absolute) when the error is below fp16's normal range.  The whole wavefront takes it
+            // only while |m| / Delta <= 32 and Delta >= 2^-6 in every channel of the block (both errors
+            // then stay below 5e-6 steps).
             const bool clamp = __builtin_amdgcn_ballot_w64(risky) != 0ull;
             auto quant_block = [&](auto clamp_tag) {
                 constexpr bool CLAMP = decltype(clamp_tag)::value;
@@ -300,7 +312,8 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                 for (int jj = 0; jj < BT; ++jj) {
                     const int j = blk * BT + jj;
                     const float mh = b_zero[jj], inv = b_inv[jj], top = b_top[jj];
-                    const float ratio = b_live[jj] ? b_step[jj] * rk : rk;
+                    const float sp = b_step[jj];       // step size (1 for a constant channel: the error is m - x)
+                    const float nmi = -mh * inv;
                     // codes are collected per half-word as exact small floats (Horner), then converted once
                     uint32_t hw[16 / CPH];
 #pragma unroll
@@ -309,21 +322,31 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
 #pragma unroll
                         for (int e = CPH - 1; e >= 0; --e) {
                             const int c = q * CPH + e;
-                            const float dd = x[j][c] - mh;
-                            float u = dd * inv;
-                            if constexpr (CLAMP) u = __builtin_amdgcn_fmed3f(u, 0.0f, top);
-                            const float code = __builtin_rintf(u);
+                            float u, code, et = 0.0f;
+                            if constexpr (CLAMP) {
+                                const float dd = x[j][c] - mh;
+                                u = __builtin_amdgcn_fmed3f(dd * inv, 0.0f, top);
+                                code = __builtin_rintf(u);
+                                if (blk < NB - 1)
+                                    et = __builtin_amdgcn_fmed3f(fmaf(-inv, dd, code) * sp, -60000.0f, 60000.0f);
+                            } else {
+                                u = fmaf(x[j][c], inv, nmi);
+                                code = __builtin_rintf(u);
+                                if (blk < NB - 1) et = (code - u) * sp;
+                            }
                             accf = fmaf(accf, static_cast<float>(1 << BITS), code);
                             if (blk < NB - 1) {
-                                // error  code - (x - m)/Delta  in units of the common scale / 256, split into
-                                // a part with 11 significant bits (exact in fp16) and the remainder
-                                float et = fmaf(-inv, dd, code) * ratio;
-                                if constexpr (CLAMP) et = __builtin_amdgcn_fmed3f(et, -60000.0f, 60000.0f);
-                                const float eh = as_f32(as_u32(et) & 0xFFFFE000u);
-                                const float el = et - eh;
+                                // error  deq - x  split into a part with 11 significant bits (exact in
+                                // fp16) and the remainder times 2^11
+                                float eh;
+                                if constexpr (CLAMP)
+                                    eh = static_cast<float>(static_cast<_Float16>(et));
+                                else
+                                    eh = as_f32(as_u32(et) & 0xFFFFE000u);
+                                const float el = (et - eh) * kLoGain;
                                 // row of the MFMA A operand that stands for token 16 hh + c
                                 const int mrow = 8 * (c >> 2) + 4 * hh + (c & 3);
-                                if constexpr (NPAIRS > 0 && !(SQUAT_PC_DIAG & 2))
+                                if constexpr (NPAIRS > 0)
                                     ebuf[mrow * EROW + 32 * jj + n] =
                                         __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(eh, el));
                             }
@@ -351,32 +374,28 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                     for (int c = 0; c < NCH; ++c)
                         aop[c] = __builtin_bit_cast(
                             half8, *reinterpret_cast<const u32x4*>(ebuf + n * EROW + 8 * c + 4 * hh));
-                    const float ks = kappa * (1.0f / kErrGain);
                     // two straight-line versions (with and without the low parts of the panels), so that
                     // the operand reads of a whole chain can be issued ahead of its matrix products
                     auto propagate = [&](auto lo_tag) {
                         constexpr bool LO = decltype(lo_tag)::value;
+                        // The working copy is the accumulator.  The chains of the remaining tiles are
+                        // interleaved (K-chunk outermost), so that no matrix product waits for the one
+                        // issued just before it.  Accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3),
+                        // i.e. token 16 hh + e.
 #pragma unroll
-                        for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
-                            f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        for (int jj = 0; jj < BT; ++jj)
 #pragma unroll
-                            for (int jj = 0; jj < BT; ++jj) {
-                                const int pr = pair_index(BT, jt, blk * BT + jj);
+                            for (int c = 0; c < 4; ++c)
 #pragma unroll
-                                for (int c = 0; c < 4; ++c) {
+                                for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
+                                    const int pr = pair_index(BT, jt, blk * BT + jj);
                                     const half8 whi = wlds[((pr * 4 + c) * 2 + 0) * 64 + lane];
-                                    if constexpr (!(SQUAT_PC_DIAG & 1))
-                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], whi, acc, 0, 0, 0);
+                                    x[jt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], whi, x[jt], 0, 0, 0);
                                     if constexpr (LO) {
                                         const half8 wlo = wlds[((pr * 4 + c) * 2 + 1) * 64 + lane];
-                                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], wlo, acc, 0, 0, 0);
+                                        x[jt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], wlo, x[jt], 0, 0, 0);
                                     }
                                 }
-                            }
-                            // accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3), i.e. token 16 hh + e
-#pragma unroll
-                            for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(ks, acc[e], x[jt][e]);
-                        }
                     };
                     if (need_lo)
                         propagate(std::true_type{});
@@ -432,7 +451,7 @@ template <int BITS, int BT, int DT>
 int launch(const PcParams& p, int64_t n_prob, hipStream_t stream) {
     constexpr int ES = (DT == SQUAT_F32) ? 4 : 2;
     constexpr int kWaves = pc_waves_for(DT, BT);
-    constexpr size_t lds = n_pairs(BT) * 8192 + kWaves * 32 * (kD * ES + 16) + 16;
+    constexpr size_t lds = n_pairs(BT) * 8192 + kWaves * 32 * (kD * ES + 16) + 16 + 2 * 64 * 16;
     auto kern = quantize_pc_kernel<BITS, BT, DT>;
     static bool attr_done = false;      // idempotent; a race only repeats the call
     if (!attr_done) {

@@ -214,6 +214,24 @@ def test_per_channel_degenerate_groups():
     assert scale[0, 0, 0, 0] == 0 and scale[0, 0, 0, 1] == 0 and not scale[0, 0, 1, :32].any()
 
 
+def test_per_channel_tiny_keys_keep_their_subnormal_values():
+    """fp16 keys in and below the subnormal range of fp16 (and bf16 keys far below fp16's range): the load
+    path must not flush them; scales then are subnormal fp16 numbers or zero."""
+    H, n = 2, 64
+    _, U = _oracle_U(2851, H, 8, 1e-2, 32)
+    x = synth.keys(2850, H, n, batch=1, outliers=None) * np.float32(2e-5)
+    raw, val = synth.store(x, synth.F16)
+    assert (np.abs(val) < 6.1e-5).mean() > 0.9 and (val != 0).mean() > 0.9
+    tot, _ = _check(util.to_device(raw, synth.F16), val, U, 2, 32, budget=1.0)
+    assert tot["code_diff"] + tot["meta_diff"] <= 4
+    codes_t, scale_t, _ = squat.quantize_keys_per_channel(util.to_device(raw, synth.F16), None, 2, 32, 32)
+    assert (O.unpack_codes_tokens(util.codes_to_host(codes_t), 2) != 0).mean() > 0.5      # not flushed to one value
+    xb = synth.keys(2852, H, n, batch=1, outliers=None) * np.float32(1e-9)
+    rawb, valb = synth.store(xb, synth.BF16)
+    tot, _ = _check(util.to_device(rawb, synth.BF16), valb, U, 2, 32, budget=1.0)
+    assert tot["code_diff"] + tot["meta_diff"] <= 4
+
+
 def test_per_channel_deterministic_and_input_untouched():
     kt, _ = _keys(2900, 4, 640, synth.BF16, batch=2)
     _, U = _oracle_U(2901, 4, 16, 1e-3, 32)
