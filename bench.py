@@ -177,17 +177,37 @@ def main():
         "roofline": roofline,
         "other_kernels": other,
     }
-    if args.variants:
-        def timed(fn, reps=5):
+    def timed(fn, reps=5):
+        fn()
+        fn()
+        torch.cuda.synchronize()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        evs[0].record()
+        for i in range(reps):
             fn()
-            torch.cuda.synchronize()
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-            evs[0].record()
-            for i in range(reps):
-                fn()
-                evs[i + 1].record()
-            torch.cuda.synchronize()
-            return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps
+
+    # The paper's own grouping (statistics per channel over 32 tokens): same keys, same update matrix, the
+    # per-channel entry points; the headline variant always, the others with --variants.
+    pc_list = [(2, 32, True)]
+    if args.variants:
+        pc_list += [(2, 64, True), (4, 32, True), (4, 64, True), (2, 128, False)]
+    out["per_channel"] = []
+    for bits, g, use_update in pc_list:
+        upd = (update if g == wl.g else squat.prepare(qhat, wl.lam, g)) if use_update else None
+        c = torch.empty((1, H, n // 32, d, bits), dtype=torch.int32, device=dev)
+        sc = torch.empty((1, H, n // 32, d), dtype=torch.float16, device=dev)
+        ze = torch.empty_like(sc)
+        tq = timed(lambda: squat.quantize_keys_per_channel(wl.k, upd, bits, 32, g, codes=c, scale=sc, zero=ze))
+        td = timed(lambda: squat.dequantize_keys_per_channel(c, sc, ze, bits, 32, out=back))
+        nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // 32))
+        out["per_channel"].append({"bits": bits, "token_group": 32, "g": g, "update": use_update,
+                                   "bytes_per_key": nbytes // n_keys,
+                                   "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    if args.variants:
         out["variants"] = []
         for bits, G, g, use_update in [(2, 32, 32, True), (2, 32, 64, True), (4, 32, 32, True), (4, 32, 64, True),
                                        (2, 128, 32, True), (4, 128, 32, True), (2, 128, 64, True),

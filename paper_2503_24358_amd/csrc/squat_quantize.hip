@@ -34,6 +34,7 @@ __host__ __device__ constexpr int waves_for(int dt, int gt, int bt) {
     return dt == SQUAT_F32 ? 6 : ((bt == 2 || (gt == 4 && bt == 1)) ? 8 : 12);
 }
 constexpr int kWgsPerCU = 1;
+constexpr float kFastOffset = 32.0f;   // largest |zero| / scale for which the one-multiply-add path is used
 
 struct QuantParams {
     const unsigned char* k;
@@ -270,13 +271,16 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
                     g_scale[gi] = sp;
                     g_inv[gi] = inv;
                     g_top[gi] = live ? LV : 0.0f;
-                    g_risky[gi] = !(sh >= 6.2e-5f) || fabsf(g_zero[gi]) * inv > 256.0f;
+                    g_risky[gi] = !(sh >= 6.2e-5f) || fabsf(g_zero[gi]) * inv > kFastOffset;
                 }
             }
             // ---- quantize and freeze the block; keep its normalised error as MFMA B operands
-            // The clamp to [0, 2^b - 1] can only bite when the fp16 rounding of zero/scale moved the
-            // group's ends by more than half a step: scale not a normal fp16 number (incl. 0), or
-            // |zero| / scale > 256.  Otherwise the whole wavefront takes the path without it.
+            // Two versions of the block.  The careful one clamps to [0, 2^b - 1] (which can only bite when
+            // the fp16 rounding of zero/scale moved the group's ends by more than half a step: scale not a
+            // normal fp16 number, incl. 0, or |zero| / scale > 256) and computes (x - m) / Delta as
+            // written.  The cheap one folds the zero-point into one multiply-add, x * (1/Delta) - m/Delta,
+            // whose rounding error grows with |m| / Delta: the whole wavefront takes it only while that
+            // ratio stays below 32 in every group of the block (error < 5e-6 steps).
             bool risky = false;
 #pragma unroll
             for (int jj = 0; jj < BT; ++jj) {
@@ -294,6 +298,7 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
                     const int j = blk * BT + jj;
                     const int gi = j / GT;
                     const float mh = g_zero[gi], inv = g_inv[gi], top = g_top[gi];
+                    const float nmi = -mh * inv;
                     // codes are collected per half-word as exact small floats (Horner), then converted once
                     uint32_t hw[16 / CPH];
                     float eh[16], el[16];
@@ -303,15 +308,21 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
 #pragma unroll
                         for (int e = CPH - 1; e >= 0; --e) {
                             const int c = q * CPH + e;
-                            const float dd = x[j][c] - mh;
-                            float u = dd * inv;
-                            if constexpr (CLAMP) u = __builtin_amdgcn_fmed3f(u, 0.0f, top);
-                            const float code = __builtin_rintf(u);
+                            float code, et;
+                            if constexpr (CLAMP) {
+                                const float dd = x[j][c] - mh;
+                                const float u = __builtin_amdgcn_fmed3f(dd * inv, 0.0f, top);
+                                code = __builtin_rintf(u);
+                                et = fmaf(-inv, dd, code);
+                            } else {
+                                const float u = fmaf(x[j][c], inv, nmi);
+                                code = __builtin_rintf(u);
+                                et = code - u;
+                            }
                             accf = fmaf(accf, static_cast<float>(1 << BITS), code);
                             if (blk < NB - 1) {
                                 // normalised error  code - (x - m)/Delta  split into a part with 11
                                 // significant bits (exact in fp16) and the exact remainder
-                                const float et = fmaf(-inv, dd, code);
                                 eh[c] = as_f32(as_u32(et) & 0xFFFFE000u);
                                 el[c] = et - eh[c];
                             }
@@ -340,28 +351,37 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
             // ---- Lemma 2: remaining channels += U[rest, block] * error
             if constexpr (NPAIRS > 0) {
                 if (blk < NB - 1) {
+                    // two straight-line versions (with and without the low parts of the panels), so that
+                    // the operand reads of a chain can be issued ahead of its matrix products
+                    auto propagate = [&](auto lo_tag) {
+                        constexpr bool LO = decltype(lo_tag)::value;
 #pragma unroll
-                    for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
+                        for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
 #pragma unroll
-                        for (int jj = 0; jj < BT; ++jj) {
-                            const int s = blk * BT + jj;
-                            const int pr = pair_index(BT, jt, s);
-                            f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                            for (int jj = 0; jj < BT; ++jj) {
+                                const int s = blk * BT + jj;
+                                const int pr = pair_index(BT, jt, s);
+                                f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                            for (int kk = 0; kk < 2; ++kk) {
-                                const half8 whi = wlds[((pr * 2 + kk) * 2 + 0) * 64 + lane];
-                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
-                                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, blo[jj][kk]), acc, 0, 0, 0);
-                                if (need_lo) {
-                                    const half8 wlo = wlds[((pr * 2 + kk) * 2 + 1) * 64 + lane];
-                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wlo, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
+                                for (int kk = 0; kk < 2; ++kk) {
+                                    const half8 whi = wlds[((pr * 2 + kk) * 2 + 0) * 64 + lane];
+                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
+                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, blo[jj][kk]), acc, 0, 0, 0);
+                                    if constexpr (LO) {
+                                        const half8 wlo = wlds[((pr * 2 + kk) * 2 + 1) * 64 + lane];
+                                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wlo, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
+                                    }
                                 }
-                            }
-                            const float sc = g_scale[s / GT];
+                                const float sc = g_scale[s / GT];
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(sc, acc[e], x[jt][e]);
+                                for (int e = 0; e < 16; ++e) x[jt][e] = fmaf(sc, acc[e], x[jt][e]);
+                            }
                         }
-                    }
+                    };
+                    if (need_lo)
+                        propagate(std::true_type{});
+                    else
+                        propagate(std::false_type{});
                 }
             }
         }

@@ -103,3 +103,38 @@ def test_fullsize_outputs_are_valid_everywhere(run):
     torch.cuda.synchronize()
     assert torch.equal(c2, run["codes"]) and torch.equal(s2, run["scale"]) and torch.equal(z2, run["zero"])
     assert torch.equal(before, run["wl"].k[0, 7, :64])
+
+
+def test_fullsize_per_channel_mode_on_sampled_token_groups(run):
+    """The per-channel grouping at the benchmark's size and launch configuration: whole 32-token groups
+    (the unit the oracle can recompute on its own) sampled from sampled heads."""
+    wl = run["wl"]
+    codes_t, scale_t, zero_t = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
+    back_t = squat.dequantize_keys_per_channel(codes_t, scale_t, zero_t, wl.bits, 32, torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.isfinite(scale_t).all() and torch.isfinite(zero_t).all() and (scale_t >= 0).all()
+    gen = np.random.default_rng(19)
+    heads = np.concatenate([[0, 255], gen.integers(0, wl.heads, size=14)])
+    n_groups = wl.n_tokens // 32
+    tot = dict(code_diff=0, code_unexplained=0, meta_diff=0, meta_unexplained=0, n_codes=0, worst_code_dist=0.0)
+    for h in heads:
+        groups = np.unique(np.concatenate([[0, n_groups - 1], gen.integers(0, n_groups, size=10)]))
+        U = run["update"][h].cpu().numpy().astype(np.float64)
+        for gi in groups:
+            k = _bf16_to_f64(wl.k[0, h, gi * 32:(gi + 1) * 32])
+            codes = O.unpack_codes_tokens(codes_t[0, h, gi:gi + 1].cpu().numpy().view(np.uint32), wl.bits)
+            scale = scale_t[0, h, gi:gi + 1].cpu().numpy()
+            zero = zero_t[0, h, gi:gi + 1].cpu().numpy()
+            rep = O.replay_classify(k, U, wl.bits, 32, wl.g, codes, scale, zero, axis="channel")
+            for key in tot:
+                tot[key] = max(tot[key], rep[key]) if key.startswith("worst") else tot[key] + rep[key]
+            want = O.dequantize_keys(codes, scale, zero, 32, axis="channel")
+            got = _bf16_to_f64(back_t[0, h, gi * 32:(gi + 1) * 32])
+            m, e = np.frexp(want)
+            assert (got != np.ldexp(np.rint(m * 256.0) / 256.0, e)).mean() <= 1e-4
+    assert tot["code_unexplained"] == 0 and tot["meta_unexplained"] == 0, tot
+    assert tot["code_diff"] + tot["meta_diff"] <= max(1, 1e-4 * tot["n_codes"]), tot
+    assert tot["worst_code_dist"] <= 1e-5
+    c2, s2, z2 = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
+    torch.cuda.synchronize()
+    assert torch.equal(c2, codes_t) and torch.equal(s2, scale_t) and torch.equal(z2, zero_t)
