@@ -21,6 +21,8 @@ Parity status of each function:
   rtn_group, quantize_keys      pinned (hand-worked fixture, r=0 fixed point,
                                 per-step optimality against a generic solver,
                                 soft and hard invariants), both grouping axes
+  key_scores                    pinned (element loops, one-hot queries, closed
+                                form for constant codes)
   dequantize_keys, pack/unpack  pinned (definition of deq; pack o unpack = id,
                                 single-code layout checks), both layouts
   exact integer codes for a concrete key under lambda>0: parity unpinned by the
@@ -36,7 +38,7 @@ __all__ = [
     "update_matrix_lemma", "update_matrix_kkt", "update_matrix_lowrank",
     "rtn_group", "quantize_keys", "dequantize_keys",
     "pack_codes", "unpack_codes", "pack_codes_tokens", "unpack_codes_tokens",
-    "replay_classify",
+    "replay_classify", "key_scores",
 ]
 
 
@@ -369,6 +371,21 @@ def dequantize_keys(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray,
         s = np.repeat(s64, G, axis=-2)
         z = np.repeat(z64, G, axis=-2)
     return codes.astype(np.float64) * s + z
+
+
+def key_scores(q: np.ndarray, codes: np.ndarray, scale: np.ndarray, zero: np.ndarray,
+               G: int, out_scale: float = 1.0, axis: str = "token") -> np.ndarray:
+    """Attention logits of decode-time queries against the QUANTIZED keys:
+    out_scale * q . deq(code)^T, with deq as in Section 2.  This is what the
+    decoding phase of Algorithm 1 feeds to the softmax for the tokens that have
+    left the residual buffer (the full-precision tail is an ordinary q . k^T).
+
+    q (n_q, d) float; codes (n, d) unpacked; scale/zero as for dequantize_keys.
+    Returns (n_q, n) float64: the definition written out, dequantize then a
+    library matrix product.
+    """
+    khat = dequantize_keys(codes, scale, zero, G, axis=axis)
+    return float(out_scale) * (np.asarray(q, dtype=np.float64) @ khat.T)
 
 
 # --------------------------------------------------------------------------- #

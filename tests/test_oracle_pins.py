@@ -311,6 +311,40 @@ def test_replay_classifier_accepts_itself_and_flags_a_planted_error():
     assert rep["code_unexplained"] + rep["meta_unexplained"] > 0
 
 
+def test_key_scores_are_the_definition():
+    """q . deq(code)^T: explicit loops on a small case, one-hot queries read single dequantized
+    channels, and all-equal codes give the closed form c * sum(q*scale) + sum(q*zero)."""
+    gen = np.random.default_rng(7)
+    n, d, G = 5, 128, 32
+    codes = gen.integers(0, 4, size=(n, d)).astype(np.uint8)
+    scale = gen.uniform(0.1, 2.0, size=(n, d // G)).astype(np.float16)
+    zero = gen.standard_normal((n, d // G)).astype(np.float16)
+    q = gen.standard_normal((3, d))
+    got = O.key_scores(q, codes, scale, zero, G, out_scale=0.25)
+    for i in range(3):
+        for t in range(n):
+            acc = 0.0
+            for c in range(d):
+                acc += q[i, c] * (float(codes[t, c]) * float(scale[t, c // G]) + float(zero[t, c // G]))
+            assert abs(got[i, t] - 0.25 * acc) <= 1e-12 * max(1.0, abs(acc))
+    eye = np.eye(d)[[0, 31, 32, 127]]
+    back = O.dequantize_keys(codes, scale, zero, G)
+    assert np.array_equal(O.key_scores(eye, codes, scale, zero, G), back[:, [0, 31, 32, 127]].T)
+    const = np.full((n, d), 3, dtype=np.uint8)
+    s64, z64 = scale.astype(np.float64), zero.astype(np.float64)
+    qg = q.reshape(3, d // G, G).sum(axis=2)
+    want = 3.0 * qg @ s64.T + qg @ z64.T
+    assert np.allclose(O.key_scores(q, const, scale, zero, G), want, rtol=1e-12, atol=1e-12)
+    # per-channel store: scale/zero indexed by (token group, channel)
+    sc = gen.uniform(0.1, 2.0, size=(2, d)).astype(np.float16)
+    zc = gen.standard_normal((2, d)).astype(np.float16)
+    cc = gen.integers(0, 4, size=(64, d)).astype(np.uint8)
+    got = O.key_scores(q, cc, sc, zc, 32, axis="channel")
+    t, i = 40, 1
+    acc = sum(q[i, c] * (float(cc[t, c]) * float(sc[1, c]) + float(zc[1, c])) for c in range(d))
+    assert abs(got[i, t] - acc) <= 1e-12 * max(1.0, abs(acc))
+
+
 # ------------------------------------------- per-channel mode (the paper's own layout)
 @pytest.mark.parametrize("bits,g,lam", [(2, 32, 1e-3), (4, 64, 5e-4), (2, 32, np.inf)])
 def test_channel_axis_each_step_generic_solver(bits, g, lam):
