@@ -10,6 +10,9 @@
  *   squat_quantize_keys    keys, update matrix -> codes      (Algorithm 1, Quant)
  *   squat_dequantize_keys  codes -> keys                     (Section 2, deq)
  *
+ * squat_key_scores is the decode-side consumer of that store (attention
+ * logits straight from the codes).
+ *
  * squat_quantize_keys groups every key's channels (statistics per token); the
  * pair squat_quantize_keys_per_channel / squat_dequantize_keys_per_channel is
  * the paper's own grouping (statistics per channel over 32 tokens), with the
@@ -238,6 +241,35 @@ int squat_dequantize_keys_per_channel(const uint32_t* codes, const uint16_t* sca
                                       squat_dtype out_dt, int64_t o_stride_batch,
                                       int64_t o_stride_head, int64_t o_stride_token,
                                       squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_key_scores  (decoding phase of Algorithm 1: attention over the keys
+ * that have left the residual buffer, which exist only in quantized form;
+ * Section 2: deq(c) = c * Delta + m).
+ *
+ * scores[b, hq, t] = out_scale * sum_c q[b, hq, c] * (code[b, h, t, c] * scale + zero)
+ * for the KV head h = hq / q_per_kv, read straight from the packed store of
+ * squat_quantize_keys (per-token groups) without materialising the keys.  The
+ * caller computes the logits of its full-precision residual tokens itself and
+ * places them behind these (hence the output strides).
+ *
+ *   codes, scale, zero   as written by squat_quantize_keys: [n_batch,
+ *            n_kv_heads, n_tokens, ...], dense; codes 16-byte, scale/zero
+ *            8-byte aligned.
+ *   q        [n_batch, n_kv_heads*q_per_kv, d] dtype q_dt, element (b,hq,c) at
+ *            q[b*q_stride_batch + hq*q_stride_head + c]; |q| < 1000.
+ *   q_per_kv 1 .. 8 query heads per KV head.
+ *   out_scale  e.g. 1/sqrt(d); must not be NaN.
+ *   scores   out, float: element (b,hq,t) at scores[b*s_stride_batch +
+ *            hq*s_stride_head + t]; s_stride_head >= n_tokens.
+ *   Products of queries and codes are exact (fp16 high/low query parts times
+ *   integer codes on the matrix cores), sums are fp32.
+ * ------------------------------------------------------------------------- */
+int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                     int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
+                     const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                     int64_t q_stride_head, float out_scale, float* scores,
+                     int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
 
 #ifdef __cplusplus
 }

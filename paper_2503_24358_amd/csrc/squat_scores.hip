@@ -1,0 +1,280 @@
+// squat_key_scores: attention logits of decode-time queries against the packed
+// key store, out_scale * q . deq(code)^T, without materialising the keys
+// (Section 2: deq(c) = c * Delta + m; decoding phase of Algorithm 1: the tokens
+// that have left the residual buffer are only available quantized).
+//
+// Per token and group of channels,  q . deq = Delta * sum_c q_c code_c + m * sum_c q_c.
+// The first sum is a small dense contraction and runs on the matrix cores
+// (v_mfma_f32_16x16x32_f16: 16 query rows x 16 tokens x 32 channels = one
+// quantization group of 32 channels per instruction):
+//   - A operand (constant per wavefront): the queries of the KV head's query
+//     heads, each split into an fp16 high and low row, so rows = (query head,
+//     part); products with the integer codes are then exact.
+//   - B operand: the codes themselves.  A packed word is rotated and masked in
+//     place: a code at bit position s of a 16-bit half IS the fp16 subnormal
+//     number code * 2^(s-24), so two codes become one operand register with a
+//     rotate and an and; the power of two is undone in the A operand.  Codes are
+//     only taken from bits 6..9 of a half: the matrix cores align products by
+//     their exponent FIELDS, and a subnormal with many leading zeros would push
+//     its product's low bits out of the adder (measured: 2^-14 relative with
+//     codes at bits 0..1, fp32-exact with codes at bits 6..9).
+//   - the second sum is one more matrix product per 16 tokens: zero-points (fp16
+//     as stored) times the per-group sums of the queries.
+// The accumulator puts a token in a lane (column) and the (query head, part)
+// rows in its registers, so Delta of the lane's own token scales the four group
+// results, high and low rows add inside the lane, and consecutive lanes store
+// consecutive tokens of one query head.
+#include "squat_internal.h"
+
+using namespace squat;
+
+namespace {
+
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+constexpr int kUnitTokens = 16;        // tokens per matrix product (MFMA N)
+constexpr int kUnitsPerWave = 32;      // 16-token units a wavefront handles (amortises its operand set-up)
+constexpr int kScoreWaves = 4;
+
+struct ScoreParams {
+    const uint32_t* codes;
+    const uint16_t* scale;
+    const uint16_t* zero;
+    const unsigned char* q;
+    int q_dt;
+    int64_t qsb, qsh;                // query strides in ELEMENTS
+    float* scores;
+    int64_t ssb, ssh;                // score strides in elements
+    int64_t n_tokens;
+    int n_kv_heads;
+    int qpk;
+    float out_scale;
+};
+
+__device__ __forceinline__ float load_q(const unsigned char* q, int dt, int64_t idx) {
+    if (dt == SQUAT_F32) return reinterpret_cast<const float*>(q)[idx];
+    const uint16_t raw = reinterpret_cast<const uint16_t*>(q)[idx];
+    if (dt == SQUAT_BF16) return as_f32(static_cast<uint32_t>(raw) << 16);
+    return static_cast<float>(__builtin_bit_cast(_Float16, raw));
+}
+
+__device__ __forceinline__ uint32_t pack_halves(_Float16 lo, _Float16 hi) {
+    return static_cast<uint32_t>(__builtin_bit_cast(uint16_t, lo)) |
+           (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
+}
+
+// grid: x over slabs of kScoreWaves * kUnitsPerWave units, y / z over (batch, KV head)
+template <int BITS, int NG>
+__global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const ScoreParams p) {
+    constexpr int WPK = kD * BITS / 32;                   // packed words per key
+    constexpr int CPG = 4 / NG;                           // 32-channel chunks per group
+    // A code at bit s of a half-word is the fp16 number code * 2^(s - 24); the query side carries
+    // 2^(TOP - s), so every product is code * q * 2^(TOP - 24).  2-bit codes are read at s = 6 and 8,
+    // 4-bit codes at s = 6.
+    constexpr int TOP = BITS == 2 ? 8 : 6;
+    constexpr float DESCALE = static_cast<float>(1 << (24 - TOP));
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int kb = lane >> 4;                             // K block of an operand / row block of the result
+    const int col = lane & 15;                            // operand row (A) or token (B, result)
+    const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
+    const int64_t b = bh / p.n_kv_heads;
+    const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
+
+    // ---- A operands: row `col` = (query head col / 2, part col % 2); K = 8 kb + 2 j + pp
+    const int qh = col >> 1, part = col & 1;
+    const bool row_live = qh < p.qpk;
+    const int64_t qbase = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + (row_live ? qh : 0)) * p.qsh;
+    u32x4 aop[4];
+    float csum[4];                                        // this lane's share of each chunk's sum of q
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        csum[g] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            _Float16 h[2];
+#pragma unroll
+            for (int pp = 0; pp < 2; ++pp) {
+                int ch, sh;
+                if constexpr (BITS == 2) {
+                    ch = 32 * g + 16 * (kb >> 1) + 4 * (kb & 1) + j + 8 * pp;
+                    sh = TOP - (6 + 2 * (j & 1));
+                } else {
+                    ch = 32 * g + 8 * kb + j + 4 * pp;
+                    sh = 0;
+                }
+                const float v = row_live ? load_q(p.q, p.q_dt, qbase + ch) : 0.0f;
+                csum[g] += v;
+                const float vs = v * static_cast<float>(1 << sh);
+                const _Float16 hi = static_cast<_Float16>(vs);
+                h[pp] = part == 0 ? hi : static_cast<_Float16>(vs - static_cast<float>(hi));
+            }
+            aop[g][j] = pack_halves(h[0], h[1]);
+        }
+    }
+    // group sums of q (all K blocks of the row: lanes col, col + 16, col + 32, col + 48), as an fp16
+    // high/low pair in K = 2 g + {0, 1} of the rows of part 0; every other entry of this operand is zero
+    u32x4 azp = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CPG; ++c) s += csum[g * CPG + c];
+        s += __shfl_xor(s, 16, 64);
+        s += __shfl_xor(s, 32, 64);
+        const _Float16 hi = static_cast<_Float16>(s);
+        const _Float16 lo = static_cast<_Float16>(s - static_cast<float>(hi));
+        azp[g] = (kb == 0 && part == 0) ? pack_halves(hi, lo) : 0u;
+    }
+
+    // ---- stream the 16-token units of this wavefront
+    const int64_t n_units = (p.n_tokens + kUnitTokens - 1) / kUnitTokens;
+    const int64_t u0 = (static_cast<int64_t>(blockIdx.x) * kScoreWaves + wave) * kUnitsPerWave;
+    const int64_t u1 = u0 + kUnitsPerWave < n_units ? u0 + kUnitsPerWave : n_units;
+    const int64_t row0 = bh * p.n_tokens;
+    const int widx0 = BITS == 2 ? (kb >> 1) : kb;          // word of chunk 0 this lane unpacks
+    // right-rotations that bring this lane's codes to bits 6..9 of both halves: 2-bit, codes c0, c0 + 1
+    // (c0 = 4 (kb & 1), at bits 2 c0) then c0 + 2, c0 + 3; a rotation by 32 - k is a left shift by k
+    const uint32_t rot_a = (kb & 1) ? 2u : 26u, rot_b = (kb & 1) ? 6u : 30u;
+    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
+    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    const float fin = p.out_scale;
+
+#pragma unroll 2
+    for (int64_t u = u0; u < u1; ++u) {
+        const int64_t tok = u * kUnitTokens + col;
+        const int64_t tc = tok < p.n_tokens ? tok : p.n_tokens - 1;     // rows past the end re-read the last key
+        const uint32_t* cw = p.codes + (row0 + tc) * WPK + widx0;
+        uint32_t w[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) w[g] = __builtin_nontemporal_load(cw + g * (WPK / 4));
+        uint32_t sraw[2] = {0u, 0u}, zraw[2] = {0u, 0u};
+        if constexpr (NG == 4) {
+            const u32x2 sv = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p.scale + (row0 + tc) * 4));
+            const u32x2 zv = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p.zero + (row0 + tc) * 4));
+            sraw[0] = sv[0]; sraw[1] = sv[1];
+            zraw[0] = zv[0]; zraw[1] = zv[1];
+        } else if constexpr (NG == 2) {
+            sraw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p.scale + (row0 + tc) * 2));
+            zraw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p.zero + (row0 + tc) * 2));
+        } else {
+            sraw[0] = __builtin_nontemporal_load(p.scale + (row0 + tc));
+            zraw[0] = __builtin_nontemporal_load(p.zero + (row0 + tc));
+        }
+
+        f32x4v acc[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            u32x4 bop;
+            if constexpr (BITS == 2) {
+                const uint32_t wa = __builtin_amdgcn_alignbit(w[g], w[g], rot_a);
+                const uint32_t wb = __builtin_amdgcn_alignbit(w[g], w[g], rot_b);
+                bop = u32x4{wa & 0x00C000C0u, wa & 0x03000300u, wb & 0x00C000C0u, wb & 0x03000300u};
+            } else {
+                // code j (and j + 4 in the upper half) sits at bit 4 j: rotate it to bit 6
+                bop = u32x4{__builtin_amdgcn_alignbit(w[g], w[g], 26u) & 0x03C003C0u,
+                            __builtin_amdgcn_alignbit(w[g], w[g], 30u) & 0x03C003C0u,
+                            __builtin_amdgcn_alignbit(w[g], w[g], 2u) & 0x03C003C0u,
+                            __builtin_amdgcn_alignbit(w[g], w[g], 6u) & 0x03C003C0u};
+            }
+            acc[g / CPG] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]),
+                                                                  __builtin_bit_cast(half8, bop), acc[g / CPG], 0, 0, 0);
+        }
+        // zero-points: K = 2 g + {0, 1} both hold m_g (the other K blocks meet zero rows of the A operand)
+        u32x4 zop = {0u, 0u, 0u, 0u};
+        zop[0] = __builtin_amdgcn_perm(zraw[0], zraw[0], 0x01000100u);
+        if constexpr (NG >= 2) zop[1] = __builtin_amdgcn_perm(zraw[0], zraw[0], 0x03020302u);
+        if constexpr (NG == 4) {
+            zop[2] = __builtin_amdgcn_perm(zraw[1], zraw[1], 0x01000100u);
+            zop[3] = __builtin_amdgcn_perm(zraw[1], zraw[1], 0x03020302u);
+        }
+        f32x4v zacc = {0.0f, 0.0f, 0.0f, 0.0f};
+        zacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, azp), __builtin_bit_cast(half8, zop),
+                                                      zacc, 0, 0, 0);
+        // Delta of this lane's token scales each group's result
+        f32x4v r = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const uint32_t word = sraw[g >> 1];
+            const float sc = static_cast<float>(
+                __builtin_bit_cast(_Float16, static_cast<uint16_t>((g & 1) ? (word >> 16) : (word & 0xFFFFu))));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = fmaf(sc, acc[g][i], r[i]);
+        }
+        // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
+        const float s0 = fin * (fmaf(DESCALE, r[0] + r[1], zacc[0] + zacc[1]));
+        const float s1 = fin * (fmaf(DESCALE, r[2] + r[3], zacc[2] + zacc[3]));
+        if (tok < p.n_tokens) {
+            if (st0) __builtin_nontemporal_store(s0, out0 + tok);
+            if (st1) __builtin_nontemporal_store(s1, out0 + p.ssh + tok);
+        }
+    }
+}
+
+template <int BITS>
+int launch_ng(int ng, const ScoreParams& p, dim3 grid, hipStream_t s) {
+    switch (ng) {
+        case 4: hipLaunchKernelGGL((key_scores_kernel<BITS, 4>), grid, dim3(kScoreWaves * kWave), 0, s, p); break;
+        case 2: hipLaunchKernelGGL((key_scores_kernel<BITS, 2>), grid, dim3(kScoreWaves * kWave), 0, s, p); break;
+        case 1: hipLaunchKernelGGL((key_scores_kernel<BITS, 1>), grid, dim3(kScoreWaves * kWave), 0, s, p); break;
+        default: return SQUAT_E_BADSHAPE;
+    }
+    return check_launch();
+}
+
+}  // namespace
+
+extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
+                                const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                                int64_t q_stride_head, float out_scale, float* scores,
+                                int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
+    if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0) return SQUAT_E_BADSHAPE;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (!(out_scale == out_scale)) return SQUAT_E_BADVALUE;
+    if (n_batch == 0 || n_kv_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!codes || !scale || !zero || !q || !scores) return SQUAT_E_NULLPTR;
+    if (q_stride_head < d || q_stride_batch < 0 || s_stride_head < n_tokens || s_stride_batch < 0) return SQUAT_E_BADSHAPE;
+    if (!aligned(codes, 16) || !aligned(scale, 8) || !aligned(zero, 8) || !aligned(scores, 4) ||
+        !aligned(q, static_cast<size_t>(elem_size(q_dt))))
+        return SQUAT_E_ALIGN;
+
+    ScoreParams p;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.q = static_cast<const unsigned char*>(q);
+    p.q_dt = static_cast<int>(q_dt);
+    p.qsb = q_stride_batch;
+    p.qsh = q_stride_head;
+    p.scores = scores;
+    p.ssb = s_stride_batch;
+    p.ssh = s_stride_head;
+    p.n_tokens = n_tokens;
+    p.n_kv_heads = n_kv_heads;
+    p.qpk = q_per_kv;
+    p.out_scale = out_scale;
+
+    const int64_t n_units = (n_tokens + kUnitTokens - 1) / kUnitTokens;
+    const int64_t per_wg = static_cast<int64_t>(kScoreWaves) * kUnitsPerWave;
+    const int64_t gx = (n_units + per_wg - 1) / per_wg;
+    const int64_t bh = n_batch * n_kv_heads;
+    int64_t gy = bh, gz = 1;
+    if (gy > 65535) {
+        gy = 0;
+        for (int64_t cand = 65535; cand >= 1; --cand)
+            if (bh % cand == 0) { gy = cand; break; }
+        gz = bh / gy;
+    }
+    if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? launch_ng<2>(128 / group, p, grid, s) : launch_ng<4>(128 / group, p, grid, s);
+}

@@ -20,7 +20,7 @@ _lib = None
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
            "squat_quantize_keys", "squat_dequantize_keys",
-           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel")
+           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores")
 
 
 class SquatError(RuntimeError):
@@ -60,6 +60,9 @@ def lib() -> ctypes.CDLL:
     L.squat_quantize_keys_per_channel.argtypes = L.squat_quantize_keys.argtypes
     L.squat_dequantize_keys_per_channel.restype = i32
     L.squat_dequantize_keys_per_channel.argtypes = L.squat_dequantize_keys.argtypes
+    L.squat_key_scores.restype = i32
+    L.squat_key_scores.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i32, i32, i64, i64, f32, vp,
+                                   i64, i64, vp]
     _lib = L
     return L
 
@@ -240,4 +243,28 @@ def dequantize_keys_per_channel(codes: torch.Tensor, scale: torch.Tensor, zero: 
                                                  out.stride(2), _stream(stream))
     if rc:
         raise SquatError(rc, "squat_dequantize_keys_per_channel")
+    return out
+
+
+def key_scores(q: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor, bits: int,
+               group: int, q_per_kv: int, out_scale: float = 1.0, *, out=None, stream=None) -> torch.Tensor:
+    """squat_key_scores.  q: [B, n_kv_heads*q_per_kv, d]; codes/scale/zero as written by quantize_keys
+    ([B, n_kv_heads, n, ...], dense) -> scores float32 [B, n_kv_heads*q_per_kv, n] (or into `out`, whose
+    last dimension may be longer than n: the logits land in its first n columns)."""
+    _need_cuda(q, codes, scale, zero)
+    b, h, n, w = codes.shape
+    d = w * 32 // bits
+    if q.dim() != 3 or q.shape[0] != b or q.shape[1] != h * q_per_kv or q.shape[2] != d or q.stride(2) != 1:
+        raise ValueError("q must be [B, n_kv_heads*q_per_kv, d] with unit channel stride")
+    if not (codes.is_contiguous() and scale.is_contiguous() and zero.is_contiguous()):
+        raise ValueError("codes/scale/zero must be dense")
+    if out is None:
+        out = torch.empty((b, h * q_per_kv, n), dtype=torch.float32, device=codes.device)
+    if out.dtype != torch.float32 or out.stride(2) != 1 or out.shape[0] != b or out.shape[1] != h * q_per_kv:
+        raise ValueError("out must be float32 [B, n_q_heads, >= n] with unit token stride")
+    rc = lib().squat_key_scores(_ptr(codes), _ptr(scale), _ptr(zero), b, h, n, d, bits, group, _ptr(q), _DT[q.dtype],
+                                q_per_kv, q.stride(0), q.stride(1), float(out_scale), _ptr(out), out.stride(0),
+                                out.stride(1), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_key_scores")
     return out

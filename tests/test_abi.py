@@ -128,3 +128,27 @@ def test_per_channel_argument_validation_happens_before_any_launch():
     assert dq(st=130) == -4
     assert dq(codes=odd) == -4
     assert dq(n=0) == 0
+
+
+def test_key_scores_argument_validation_happens_before_any_launch():
+    L = squat.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    ks = lambda **kw: L.squat_key_scores(  # noqa: E731
+        kw.get("codes", fake), fake, fake, 1, 2, kw.get("n", 64), kw.get("d", 128), kw.get("bits", 2),
+        kw.get("G", 32), kw.get("q", fake), kw.get("dt", 2), kw.get("qpk", 4), 1024, kw.get("qsh", 128),
+        kw.get("os", 1.0), kw.get("out", fake), 8 * 64, kw.get("ssh", 64), None)
+    assert ks(d=64) == -2
+    assert ks(bits=3) == -2
+    assert ks(G=16) == -2
+    assert ks(qpk=0) == -2
+    assert ks(qpk=9) == -2
+    assert ks(dt=4) == -3
+    assert ks(os=float("nan")) == -7
+    assert ks(q=None) == -1
+    assert ks(out=None) == -1
+    assert ks(qsh=64) == -2         # query rows would overlap
+    assert ks(ssh=32) == -2         # score rows would overlap
+    assert ks(codes=odd) == -4
+    assert ks(n=0) == 0
+    assert ks(n=-1) == -2

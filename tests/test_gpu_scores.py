@@ -1,0 +1,138 @@
+"""GPU parity of squat_key_scores (attention logits straight from the packed key store) against
+the float64 oracle: out_scale * q . deq(code)^T.  Products of the fp16 high/low query parts with
+the integer codes are exact on the matrix cores, so the only error is fp32 summation: about 130
+terms per logit, summed as  scale * sum(q code) + zero * sum(q)  (two parts that partly cancel), with
+the matrix cores' own accumulation order.  Worst case n * 2^-23 * (cancellation ~2) ~ 3e-5 relative
+to sum_c |q_c| |deq_c|; the test allows 4e-5 (observed worst: 1.1e-5), 25 times inside the 1e-3
+relative tolerance the build states for projections."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import squat_oracle as O
+from paper_2503_24358_amd import squat, synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+def _store(seed, B, H, n, bits, G, heavy=False):
+    """A packed store produced by the oracle's quantizer (plain round-to-nearest is enough here: the
+    scores call only reads the format)."""
+    gen = synth.rng(seed)
+    x = synth.keys(seed + 1, H, n, heavy_tail=heavy, batch=B)
+    codes = np.empty((B, H, n, 128), dtype=np.uint8)
+    scale = np.empty((B, H, n, 128 // G), dtype=np.float16)
+    zero = np.empty_like(scale)
+    for b in range(B):
+        for h in range(H):
+            out = O.quantize_keys(x[b, h].astype(np.float64), None, bits, G, 128)
+            codes[b, h], scale[b, h], zero[b, h] = out["codes"], out["scale"], out["zero"]
+    return gen, codes, scale, zero
+
+
+def _dev(codes, scale, zero, bits):
+    words = O.pack_codes(codes, bits)
+    return (torch.from_numpy(words.view(np.int32)).cuda(), torch.from_numpy(scale).cuda(), torch.from_numpy(zero).cuda())
+
+
+def _check(q_t, qval, codes, scale, zero, bits, G, qpk, out_scale, got):
+    B, Hq = qval.shape[:2]
+    got = got.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // qpk
+            want = O.key_scores(qval[b, hq][None], codes[b, h], scale[b, h], zero[b, h], G, out_scale)[0]
+            khat = np.abs(O.dequantize_keys(codes[b, h], scale[b, h], zero[b, h], G))
+            bound = abs(out_scale) * (np.abs(qval[b, hq])[None] * khat).sum(axis=1)
+            err = np.abs(got[b, hq] - want)
+            assert np.all(err <= 4e-5 * bound + 1e-30), (b, hq, float((err / (bound + 1e-30)).max()))
+            worst = max(worst, float((err / (bound + 1e-30)).max()))
+    return worst
+
+
+@pytest.mark.parametrize("bits,G", [(2, 32), (4, 32), (2, 64), (4, 128), (2, 128), (4, 64)])
+@pytest.mark.parametrize("qdt", [synth.BF16, synth.F16, synth.F32])
+def test_scores_match_definition(bits, G, qdt):
+    B, H, n, qpk = 2, 3, 1000, 4          # 62 full units and a ragged one of 8 tokens
+    gen, codes, scale, zero = _store(3100 + bits + G, B, H, n, bits, G)
+    q32 = (gen.standard_normal((B, H * qpk, 128)) * 3).astype(np.float32)
+    qraw, qval = synth.store(q32, qdt)
+    ct, st, zt = _dev(codes, scale, zero, bits)
+    got = squat.key_scores(util.to_device(qraw, qdt), ct, st, zt, bits, G, qpk, out_scale=128 ** -0.5)
+    torch.cuda.synchronize()
+    assert got.shape == (B, H * qpk, n)
+    _check(None, qval, codes, scale, zero, bits, G, qpk, 128 ** -0.5, got)
+
+
+@pytest.mark.parametrize("qpk", [1, 2, 3, 8])
+def test_scores_query_heads_per_kv_head(qpk):
+    B, H, n = 1, 2, 130
+    gen, codes, scale, zero = _store(3200 + qpk, B, H, n, 2, 32, heavy=True)
+    q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.BF16)
+    ct, st, zt = _dev(codes, scale, zero, 2)
+    got = squat.key_scores(util.to_device(qraw, synth.BF16), ct, st, zt, 2, 32, qpk)
+    torch.cuda.synchronize()
+    _check(None, qval, codes, scale, zero, 2, 32, qpk, 1.0, got)
+
+
+def test_scores_strided_output_tiny_and_empty_inputs():
+    B, H, qpk = 2, 2, 4
+    for n in (1, 15, 16, 17):
+        gen, codes, scale, zero = _store(3300 + n, B, H, n, 2, 32)
+        q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+        qraw, qval = synth.store(q32, synth.F16)
+        ct, st, zt = _dev(codes, scale, zero, 2)
+        big = torch.full((B, H * qpk, n + 40), -7.0, dtype=torch.float32, device="cuda")   # room for residual logits
+        squat.key_scores(util.to_device(qraw, synth.F16), ct, st, zt, 2, 32, qpk, out=big)
+        torch.cuda.synchronize()
+        _check(None, qval, codes, scale, zero, 2, 32, qpk, 1.0, big[..., :n])
+        assert torch.all(big[..., n:] == -7.0)
+    e = squat.key_scores(torch.zeros((B, H * qpk, 128), dtype=torch.bfloat16, device="cuda"), ct[:, :, :0].contiguous(),
+                         st[:, :, :0].contiguous(), zt[:, :, :0].contiguous(), 2, 32, qpk)
+    assert e.shape == (B, H * qpk, 0)
+
+
+def test_scores_special_queries_and_constant_groups():
+    """One-hot queries read single dequantized channels exactly; constant groups (scale 0) contribute
+    zero * sum(q); a zero query gives exact zeros."""
+    B, H, n, qpk = 1, 1, 64, 4
+    gen, codes, scale, zero = _store(3400, B, H, n, 2, 32)
+    scale[0, 0, 5, 1] = 0
+    codes[0, 0, 5, 32:64] = 0
+    q = np.zeros((B, H * qpk, 128), dtype=np.float32)
+    q[0, 0, 0] = 1.0
+    q[0, 1, 37] = -2.0
+    q[0, 2, 127] = 0.5
+    qraw, qval = synth.store(q, synth.F32)
+    ct, st, zt = _dev(codes, scale, zero, 2)
+    got = squat.key_scores(util.to_device(qraw, synth.F32), ct, st, zt, 2, 32, qpk).cpu().numpy().astype(np.float64)
+    back = O.dequantize_keys(codes[0, 0], scale[0, 0], zero[0, 0], 32)
+    assert np.array_equal(got[0, 0], back[:, 0].astype(np.float32).astype(np.float64))
+    assert np.allclose(got[0, 1], -2.0 * back[:, 37], rtol=1e-6, atol=0)
+    assert np.allclose(got[0, 2], 0.5 * back[:, 127], rtol=1e-6, atol=0)
+    assert not got[0, 3].any()
+
+
+def test_scores_on_the_quantize_kernels_own_output():
+    """End to end on the GPU: quantize with an update matrix, then logits from the store, against the
+    oracle applied to the GPU's own codes and metadata."""
+    B, H, n, qpk = 2, 4, 640, 4
+    x32 = synth.keys(3500, H, n, batch=B)
+    kraw, kval = synth.store(x32, synth.BF16)
+    gen = synth.rng(3501)
+    Qh = gen.standard_normal((H, 16, 128)) * 25
+    U = np.stack([O.update_matrix_lowrank(Qh[h], 1e-3, 32) for h in range(H)]).astype(np.float32)
+    ct, st, zt = squat.quantize_keys(util.to_device(kraw, synth.BF16), torch.from_numpy(U).cuda(), 2, 32, 32)
+    q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.BF16)
+    got = squat.key_scores(util.to_device(qraw, synth.BF16), ct, st, zt, 2, 32, qpk, out_scale=0.1)
+    torch.cuda.synchronize()
+    codes = O.unpack_codes(util.codes_to_host(ct), 2)
+    _check(None, qval, codes, util.half_to_host(st), util.half_to_host(zt), 2, 32, qpk, 0.1, got)
+    # and they approximate the logits against the original keys (what the method is for)
+    exact = np.einsum("bqc,bqtc->bqt", qval, np.repeat(kval, qpk, axis=1)) * 0.1
+    g = got.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(g - exact) <= 0.8 * np.linalg.norm(exact)      # 2-bit: error ~ half a key std per channel
