@@ -255,9 +255,10 @@ int squat_dequantize_keys_per_channel(const uint32_t* codes, const uint16_t* sca
  *
  *   codes, scale, zero   as written by squat_quantize_keys: [n_batch,
  *            n_kv_heads, n_tokens, ...], dense; codes 16-byte, scale/zero
- *            8-byte aligned.
+ *            8-byte aligned.  n_tokens < 2^25.
  *   q        [n_batch, n_kv_heads*q_per_kv, d] dtype q_dt, element (b,hq,c) at
- *            q[b*q_stride_batch + hq*q_stride_head + c]; |q| < 1000.
+ *            q[b*q_stride_batch + hq*q_stride_head + c]; base 16-byte aligned,
+ *            strides multiples of 8 elements; |q| < 16000.
  *   q_per_kv 1 .. 8 query heads per KV head.
  *   out_scale  e.g. 1/sqrt(d); must not be NaN.
  *   scores   out, float: element (b,hq,t) at scores[b*s_stride_batch +

@@ -30,10 +30,23 @@ using namespace squat;
 
 namespace {
 
+#ifndef SQUAT_SC_NT
+#define SQUAT_SC_NT 1
+#endif
+#ifndef SQUAT_SC_DEPTH
+#define SQUAT_SC_DEPTH 4
+#endif
+#if SQUAT_SC_NT
+#define SC_LOAD(p) __builtin_nontemporal_load(p)
+#else
+#define SC_LOAD(p) (*(p))
+#endif
+
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int kUnitTokens = 16;        // tokens per matrix product (MFMA N)
-constexpr int kUnitsPerWave = 32;      // 16-token units a wavefront handles (amortises its operand set-up)
+constexpr int kMaxUnitsPerWave = 32;   // 16-token units a wavefront handles (amortises its operand set-up) ...
+constexpr int kMinUnitsPerWave = 4;    // ... unless the sequence is short: then all four wavefronts share it
 constexpr int kScoreWaves = 4;
 
 struct ScoreParams {
@@ -49,22 +62,16 @@ struct ScoreParams {
     int n_kv_heads;
     int qpk;
     float out_scale;
+    int units_per_wave;
 };
-
-__device__ __forceinline__ float load_q(const unsigned char* q, int dt, int64_t idx) {
-    if (dt == SQUAT_F32) return reinterpret_cast<const float*>(q)[idx];
-    const uint16_t raw = reinterpret_cast<const uint16_t*>(q)[idx];
-    if (dt == SQUAT_BF16) return as_f32(static_cast<uint32_t>(raw) << 16);
-    return static_cast<float>(__builtin_bit_cast(_Float16, raw));
-}
 
 __device__ __forceinline__ uint32_t pack_halves(_Float16 lo, _Float16 hi) {
     return static_cast<uint32_t>(__builtin_bit_cast(uint16_t, lo)) |
            (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
 }
 
-// grid: x over slabs of kScoreWaves * kUnitsPerWave units, y / z over (batch, KV head)
-template <int BITS, int NG>
+// grid: x over slabs of kScoreWaves * units_per_wave units, y / z over (batch, KV head)
+template <int BITS, int NG, int QDT>
 __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const ScoreParams p) {
     constexpr int WPK = kD * BITS / 32;                   // packed words per key
     constexpr int CPG = 4 / NG;                           // 32-channel chunks per group
@@ -82,10 +89,37 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     const int64_t b = bh / p.n_kv_heads;
     const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
 
+    // ---- the KV head's queries -> LDS as fp32 (one wide load per thread instead of 32 two-byte loads per
+    // lane: vector-memory instructions are what this kernel runs out of first)
+    constexpr int QLD = kD + 1;                           // row stride in floats (odd: spreads the banks)
+    __shared__ float qlds[8 * QLD];
+    {
+        const int e0 = 4 * static_cast<int>(threadIdx.x);            // 4 consecutive channels of one query head
+        const int qrow = e0 / kD, qch = e0 % kD;
+        if (qrow < p.qpk) {
+            const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
+            float v[4];
+            if constexpr (QDT == SQUAT_F32) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
+                v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+            } else {
+                const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
+                    v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
+                                             : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) qlds[qrow * QLD + qch + i] = v[i];
+        }
+    }
+    __syncthreads();
+
     // ---- A operands: row `col` = (query head col / 2, part col % 2); K = 8 kb + 2 j + pp
     const int qh = col >> 1, part = col & 1;
     const bool row_live = qh < p.qpk;
-    const int64_t qbase = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + (row_live ? qh : 0)) * p.qsh;
     u32x4 aop[4];
     float csum[4];                                        // this lane's share of each chunk's sum of q
 #pragma unroll
@@ -104,7 +138,7 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
                     ch = 32 * g + 8 * kb + j + 4 * pp;
                     sh = 0;
                 }
-                const float v = row_live ? load_q(p.q, p.q_dt, qbase + ch) : 0.0f;
+                const float v = row_live ? qlds[qh * QLD + ch] : 0.0f;
                 csum[g] += v;
                 const float vs = v * static_cast<float>(1 << sh);
                 const _Float16 hi = static_cast<_Float16>(vs);
@@ -129,9 +163,9 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     }
 
     // ---- stream the 16-token units of this wavefront
-    const int64_t n_units = (p.n_tokens + kUnitTokens - 1) / kUnitTokens;
-    const int64_t u0 = (static_cast<int64_t>(blockIdx.x) * kScoreWaves + wave) * kUnitsPerWave;
-    const int64_t u1 = u0 + kUnitsPerWave < n_units ? u0 + kUnitsPerWave : n_units;
+    const int n_units = static_cast<int>((p.n_tokens + kUnitTokens - 1) / kUnitTokens);
+    const int u0 = (static_cast<int>(blockIdx.x) * kScoreWaves + wave) * p.units_per_wave;
+    const int u1 = min(u0 + p.units_per_wave, n_units);
     const int64_t row0 = bh * p.n_tokens;
     const int widx0 = BITS == 2 ? (kb >> 1) : kb;          // word of chunk 0 this lane unpacks
     // right-rotations that bring this lane's codes to bits 6..9 of both halves: 2-bit, codes c0, c0 + 1
@@ -141,28 +175,78 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
     const float fin = p.out_scale;
 
-#pragma unroll 2
-    for (int64_t u = u0; u < u1; ++u) {
-        const int64_t tok = u * kUnitTokens + col;
-        const int64_t tc = tok < p.n_tokens ? tok : p.n_tokens - 1;     // rows past the end re-read the last key
-        const uint32_t* cw = p.codes + (row0 + tc) * WPK + widx0;
-        uint32_t w[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) w[g] = __builtin_nontemporal_load(cw + g * (WPK / 4));
-        uint32_t sraw[2] = {0u, 0u}, zraw[2] = {0u, 0u};
-        if constexpr (NG == 4) {
-            const u32x2 sv = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p.scale + (row0 + tc) * 4));
-            const u32x2 zv = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p.zero + (row0 + tc) * 4));
-            sraw[0] = sv[0]; sraw[1] = sv[1];
-            zraw[0] = zv[0]; zraw[1] = zv[1];
-        } else if constexpr (NG == 2) {
-            sraw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p.scale + (row0 + tc) * 2));
-            zraw[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p.zero + (row0 + tc) * 2));
-        } else {
-            sraw[0] = __builtin_nontemporal_load(p.scale + (row0 + tc));
-            zraw[0] = __builtin_nontemporal_load(p.zero + (row0 + tc));
+    // Loads: as few vector-memory instructions as possible (they, not bytes or arithmetic, bound this
+    // kernel when every lane fetches its own 4-byte words): per unit ONE 16-byte load by the lanes that
+    // cover the unit's codes (contiguous in memory) and ONE load of the scales and zero-points, landed
+    // in a small per-wavefront LDS tile from which every lane then picks the words of its K block.
+    constexpr int PPT = WPK / 4;                          // 16-byte pieces of codes per token
+    constexpr int CL = kUnitTokens * PPT;                 // lanes that load codes (32 or 64)
+    constexpr int CS = WPK * 4 + 16;                      // LDS bytes per token of codes (padded)
+    constexpr int META0 = kUnitTokens * CS;               // scales at META0 + 8 t, zero-points 128 bytes later
+    constexpr int TILE = META0 + 256;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[kScoreWaves * TILE];
+    unsigned char* lds = lds_all + wave * TILE;
+    struct Raw {
+        u32x4 c;
+        u32x2 m;
+    };
+    // 32-bit token indices inside this (batch, KV head): the host rejects sequences of 2^25 tokens or more
+    const int n_tok = static_cast<int>(p.n_tokens);
+    const int ml = BITS == 2 ? lane - 32 : lane;          // index among the lanes that load metadata
+    const bool is_c = lane < CL, is_m = ml >= 0 && ml < 32;
+    const int c_tok = lane / PPT, c_piece = lane % PPT;
+    const int m_tok = ml & 15;
+    const uint32_t* c_base = p.codes + row0 * WPK + c_piece * 4;
+    const uint16_t* m_base = ((ml & 16) ? p.zero : p.scale) + row0 * NG;
+    // units past the end of this wavefront's range re-read its last unit (never used); rows past the end
+    // of the keys re-read the last key
+    auto fetch = [&](int u, Raw& r) {
+        r.c = u32x4{0u, 0u, 0u, 0u};
+        r.m = u32x2{0u, 0u};
+        if (is_c) {
+            const int t = min(u * kUnitTokens + c_tok, n_tok - 1);
+            r.c = SC_LOAD(reinterpret_cast<const u32x4*>(c_base + static_cast<uint32_t>(t) * WPK));
         }
-
+        if (is_m) {
+            const int t = min(u * kUnitTokens + m_tok, n_tok - 1);
+            if constexpr (NG == 4) {
+                r.m = SC_LOAD(reinterpret_cast<const u32x2*>(m_base + static_cast<uint32_t>(t) * 4));
+            } else if constexpr (NG == 2) {
+                r.m[0] = SC_LOAD(reinterpret_cast<const uint32_t*>(m_base + static_cast<uint32_t>(t) * 2));
+            } else {
+                r.m[0] = SC_LOAD(m_base + static_cast<uint32_t>(t));
+            }
+        }
+    };
+    struct Words {
+        uint32_t w[4];
+        uint32_t sraw[2], zraw[2];
+    };
+    // registers -> LDS tile -> the words of this lane's K block, the scales and zero-points of its token
+    auto redistribute = [&](const Raw& r, Words& o) {
+        if (is_c) *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) = r.c;
+        if (is_m) *reinterpret_cast<u32x2*>(lds + META0 + (ml & 16) * 8 + m_tok * 8) = r.m;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            o.w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4);
+        const u32x2 sv = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
+        const u32x2 zv = *reinterpret_cast<const u32x2*>(lds + META0 + 128 + col * 8);
+        o.sraw[0] = sv[0]; o.sraw[1] = sv[1];
+        o.zraw[0] = zv[0]; o.zraw[1] = zv[1];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto compute = [&](int u, const Raw& raw) {
+        const int tok = u * kUnitTokens + col;
+        Words wd;
+        redistribute(raw, wd);
+        const uint32_t* w = wd.w;
+        const uint32_t* sraw = wd.sraw;
+        const uint32_t* zraw = wd.zraw;
         f32x4v acc[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) acc[g] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
@@ -207,22 +291,47 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
         const float s0 = fin * (fmaf(DESCALE, r[0] + r[1], zacc[0] + zacc[1]));
         const float s1 = fin * (fmaf(DESCALE, r[2] + r[3], zacc[2] + zacc[3]));
-        if (tok < p.n_tokens) {
+        if (tok < n_tok) {
             if (st0) __builtin_nontemporal_store(s0, out0 + tok);
             if (st1) __builtin_nontemporal_store(s1, out0 + p.ssh + tok);
         }
+    };
+
+    // software pipeline: the loads of SQUAT_SC_DEPTH units are in flight while one is being computed
+    if (u0 >= u1) return;
+    Raw ring[SQUAT_SC_DEPTH];
+#pragma unroll
+    for (int i = 0; i < SQUAT_SC_DEPTH; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
+    for (int u = u0; u < u1; u += SQUAT_SC_DEPTH) {
+#pragma unroll
+        for (int i = 0; i < SQUAT_SC_DEPTH; ++i) {
+            const Raw cur = ring[i];
+            fetch(min(u + i + SQUAT_SC_DEPTH, u1 - 1), ring[i]);
+            if (u + i < u1) compute(u + i, cur);
+        }
     }
+}
+
+template <int BITS, int NG>
+int launch_dt(const ScoreParams& p, dim3 grid, hipStream_t s) {
+    const dim3 block(kScoreWaves * kWave);
+    switch (p.q_dt) {
+        case SQUAT_F32: hipLaunchKernelGGL((key_scores_kernel<BITS, NG, SQUAT_F32>), grid, block, 0, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL((key_scores_kernel<BITS, NG, SQUAT_F16>), grid, block, 0, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_kernel<BITS, NG, SQUAT_BF16>), grid, block, 0, s, p); break;
+        default: return SQUAT_E_BADDTYPE;
+    }
+    return check_launch();
 }
 
 template <int BITS>
 int launch_ng(int ng, const ScoreParams& p, dim3 grid, hipStream_t s) {
     switch (ng) {
-        case 4: hipLaunchKernelGGL((key_scores_kernel<BITS, 4>), grid, dim3(kScoreWaves * kWave), 0, s, p); break;
-        case 2: hipLaunchKernelGGL((key_scores_kernel<BITS, 2>), grid, dim3(kScoreWaves * kWave), 0, s, p); break;
-        case 1: hipLaunchKernelGGL((key_scores_kernel<BITS, 1>), grid, dim3(kScoreWaves * kWave), 0, s, p); break;
-        default: return SQUAT_E_BADSHAPE;
+        case 4: return launch_dt<BITS, 4>(p, grid, s);
+        case 2: return launch_dt<BITS, 2>(p, grid, s);
+        case 1: return launch_dt<BITS, 1>(p, grid, s);
     }
-    return check_launch();
+    return SQUAT_E_BADSHAPE;
 }
 
 }  // namespace
@@ -236,14 +345,14 @@ extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, co
     if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
     if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
     if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
-    if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0 || n_tokens >= (int64_t(1) << 25)) return SQUAT_E_BADSHAPE;
     if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
     if (!(out_scale == out_scale)) return SQUAT_E_BADVALUE;
     if (n_batch == 0 || n_kv_heads == 0 || n_tokens == 0) return SQUAT_OK;
     if (!codes || !scale || !zero || !q || !scores) return SQUAT_E_NULLPTR;
     if (q_stride_head < d || q_stride_batch < 0 || s_stride_head < n_tokens || s_stride_batch < 0) return SQUAT_E_BADSHAPE;
-    if (!aligned(codes, 16) || !aligned(scale, 8) || !aligned(zero, 8) || !aligned(scores, 4) ||
-        !aligned(q, static_cast<size_t>(elem_size(q_dt))))
+    if ((q_stride_head % 8) || (q_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(codes, 16) || !aligned(scale, 8) || !aligned(zero, 8) || !aligned(scores, 4) || !aligned(q, 16))
         return SQUAT_E_ALIGN;
 
     ScoreParams p;
@@ -263,7 +372,10 @@ extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, co
     p.out_scale = out_scale;
 
     const int64_t n_units = (n_tokens + kUnitTokens - 1) / kUnitTokens;
-    const int64_t per_wg = static_cast<int64_t>(kScoreWaves) * kUnitsPerWave;
+    int64_t upw = (n_units + kScoreWaves - 1) / kScoreWaves;
+    upw = upw > kMaxUnitsPerWave ? kMaxUnitsPerWave : (upw < kMinUnitsPerWave ? kMinUnitsPerWave : upw);
+    p.units_per_wave = static_cast<int>(upw);
+    const int64_t per_wg = static_cast<int64_t>(kScoreWaves) * upw;
     const int64_t gx = (n_units + per_wg - 1) / per_wg;
     const int64_t bh = n_batch * n_kv_heads;
     int64_t gy = bh, gz = 1;
