@@ -207,6 +207,15 @@ def main():
                                    "bytes_per_key": nbytes // n_keys,
                                    "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                    "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    # Decode-side consumer: attention logits of one query token per query head straight from the packed
+    # store just written (48 B of codes and metadata in, 4 B per query head out, per key).
+    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()                      # [1, q_heads, d]: the last prompt token's queries
+    logits = torch.empty((1, H * wl.q_per_kv, n), dtype=torch.float32, device=dev)
+    ts = timed(lambda: squat.key_scores(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
+    sbytes = n_keys * (d * wl.bits // 8 + 4 * (d // wl.group) + 4 * wl.q_per_kv)
+    out["key_scores"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bytes_per_key": sbytes // n_keys,
+                         "us": ts * 1e3, "keys_per_s": n_keys / (ts * 1e-3),
+                         "frac_of_hbm_peak": sbytes / (ts * 1e-3) / 1e9 / HBM_PEAK_GBS}
     if args.variants:
         out["variants"] = []
         for bits, G, g, use_update in [(2, 32, 32, True), (2, 32, 64, True), (4, 32, 32, True), (4, 32, 64, True),
@@ -244,6 +253,18 @@ def main():
             nk = 64 * heads * 32
             out["decode_flush"].append({"sequences": 64, "heads_per_launch": heads, "keys_per_flush": nk,
                                         "us_per_flush_back_to_back": us, "keys_per_s": nk / (us * 1e-6)})
+        # logits of 64 sequences x all (layer, KV head) slots over 2048 quantized tokens each
+        nd = 2048
+        cd = torch.randint(-2 ** 31, 2 ** 31 - 1, (64, H, nd, d * wl.bits // 32), dtype=torch.int32, device=dev)
+        sd = torch.rand((64, H, nd, d // wl.group), device=dev).half()
+        zd = torch.randn((64, H, nd, d // wl.group), device=dev).half()
+        qd = torch.randn((64, H * wl.q_per_kv, d), device=dev, dtype=torch.bfloat16)
+        ld = torch.empty((64, H * wl.q_per_kv, nd), dtype=torch.float32, device=dev)
+        us = timed_us(lambda: squat.key_scores(qd, cd, sd, zd, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=ld), reps=10)
+        nk = 64 * H * nd
+        nb = nk * (d * wl.bits // 8 + 4 * (d // wl.group) + 4 * wl.q_per_kv)
+        out["decode_scores"] = {"sequences": 64, "heads": H, "quantized_tokens": nd, "q_per_kv": wl.q_per_kv, "us": us,
+                                "keys_per_s": nk / (us * 1e-6), "frac_of_hbm_peak": nb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(dict(n_tokens=n, r=wl.r, lam=wl.lam, bits=wl.bits, group=wl.group,
                                                 g=wl.g, q_per_kv=wl.q_per_kv))

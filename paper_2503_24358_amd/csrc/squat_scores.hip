@@ -120,11 +120,14 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     // ---- A operands: row `col` = (query head col / 2, part col % 2); K = 8 kb + 2 j + pp
     const int qh = col >> 1, part = col & 1;
     const bool row_live = qh < p.qpk;
-    u32x4 aop[4];
-    float csum[4];                                        // this lane's share of each chunk's sum of q
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        csum[g] = 0.0f;
+    // Wavefront w builds the operand of chunk w (and that chunk's sum of q per row); the four share them
+    // through LDS.
+    __shared__ __attribute__((aligned(16))) u32x4 aop_lds[4 * kWave];
+    __shared__ float csum_lds[4 * kWave];
+    {
+        const int g = wave;
+        float cs = 0.0f;
+        u32x4 a;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             _Float16 h[2];
@@ -139,24 +142,35 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
                     sh = 0;
                 }
                 const float v = row_live ? qlds[qh * QLD + ch] : 0.0f;
-                csum[g] += v;
+                cs += v;
                 const float vs = v * static_cast<float>(1 << sh);
                 const _Float16 hi = static_cast<_Float16>(vs);
                 h[pp] = part == 0 ? hi : static_cast<_Float16>(vs - static_cast<float>(hi));
             }
-            aop[g][j] = pack_halves(h[0], h[1]);
+            a[j] = pack_halves(h[0], h[1]);
         }
+        // all K blocks of the row: lanes col, col + 16, col + 32, col + 48
+        cs += __shfl_xor(cs, 16, 64);
+        cs += __shfl_xor(cs, 32, 64);
+        aop_lds[g * kWave + lane] = a;
+        csum_lds[g * kWave + lane] = cs;
     }
-    // group sums of q (all K blocks of the row: lanes col, col + 16, col + 32, col + 48), as an fp16
-    // high/low pair in K = 2 g + {0, 1} of the rows of part 0; every other entry of this operand is zero
+    __syncthreads();
+    u32x4 aop[4];
+    float csum[4];                                        // sum of q over each chunk, for this lane's row
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        aop[g] = aop_lds[g * kWave + lane];
+        csum[g] = csum_lds[g * kWave + lane];
+    }
+    // group sums of q as an fp16 high/low pair in K = 2 g + {0, 1} of the rows of part 0; every other
+    // entry of this operand is zero
     u32x4 azp = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         float s = 0.0f;
 #pragma unroll
         for (int c = 0; c < CPG; ++c) s += csum[g * CPG + c];
-        s += __shfl_xor(s, 16, 64);
-        s += __shfl_xor(s, 32, 64);
         const _Float16 hi = static_cast<_Float16>(s);
         const _Float16 lo = static_cast<_Float16>(s - static_cast<float>(hi));
         azp[g] = (kb == 0 && part == 0) ? pack_halves(hi, lo) : 0u;
