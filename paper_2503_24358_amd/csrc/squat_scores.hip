@@ -30,17 +30,8 @@ using namespace squat;
 
 namespace {
 
-#ifndef SQUAT_SC_NT
-#define SQUAT_SC_NT 1
-#endif
-#ifndef SQUAT_SC_DEPTH
-#define SQUAT_SC_DEPTH 4
-#endif
-#if SQUAT_SC_NT
-#define SC_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define SC_LOAD(p) (*(p))
-#endif
+constexpr int kDepth = 4;              // units whose loads are in flight per wavefront (software pipeline)
+#define SC_LOAD(p) __builtin_nontemporal_load(p)       // the store is streamed once
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
@@ -311,16 +302,16 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         }
     };
 
-    // software pipeline: the loads of SQUAT_SC_DEPTH units are in flight while one is being computed
+    // software pipeline: the loads of kDepth units are in flight while one is being computed
     if (u0 >= u1) return;
-    Raw ring[SQUAT_SC_DEPTH];
+    Raw ring[kDepth];
 #pragma unroll
-    for (int i = 0; i < SQUAT_SC_DEPTH; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
-    for (int u = u0; u < u1; u += SQUAT_SC_DEPTH) {
+    for (int i = 0; i < kDepth; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
+    for (int u = u0; u < u1; u += kDepth) {
 #pragma unroll
-        for (int i = 0; i < SQUAT_SC_DEPTH; ++i) {
+        for (int i = 0; i < kDepth; ++i) {
             const Raw cur = ring[i];
-            fetch(min(u + i + SQUAT_SC_DEPTH, u1 - 1), ring[i]);
+            fetch(min(u + i + kDepth, u1 - 1), ring[i]);
             if (u + i < u1) compute(u + i, cur);
         }
     }
