@@ -198,4 +198,125 @@ __device__ int jacobi_rows(double* A, int n, int ld, double* nrm2, int* flag, in
     return sweep;
 }
 
+
+// The same sweep for the full-size problem (n = MAXE * TS rows, n / 2 teams of TS lanes, all threads
+// busy), re-ordered so that half of the row traffic stays in registers.  LDS bandwidth, not
+// arithmetic, bounds the routine above at this size: every round each team reads two rows and writes
+// two rows.  Here the pairs of one sweep are visited level by level: at the level with span S the teams
+// form blocks of S teams over 2 S consecutive rows; team j of a block keeps row (base + j) in REGISTERS
+// for the S rounds of the level and meets rows base + S + ((j + round) mod S), which alone travel
+// through LDS.  Spans n/2, n/4, ..., 1 give n - 1 rounds in which every pair of rows meets exactly
+// once (pairs across the two halves of a block at this level, pairs inside a half at the deeper
+// levels), i.e. a cyclic ordering like the tournament above, with half its LDS traffic.
+template <int THREADS, int TS, int MAXE>
+__device__ int jacobi_rows_resident(double* A, int ld, double* nrm2, int* flag, int max_sweeps, double tol) {
+    constexpr int N = MAXE * TS;
+    constexpr int MAXP = MAXE / 2;           // column pairs per lane
+    static_assert(THREADS == (N / 2) * TS && MAXE % 2 == 0, "one team of TS lanes per row pair");
+    const int tid = threadIdx.x;
+    const int team = tid / TS;
+    const int tl = tid % TS;
+    const float tol2 = static_cast<float>(tol * tol);
+    const float early2 = static_cast<float>(tol);           // (sqrt(tol))^2
+    int sweep = 0;
+    for (; sweep < max_sweeps; ++sweep) {
+        // refresh the cached squared norms (one team per row, two passes)
+        for (int row = team; row < N; row += THREADS / TS) {
+            double s = 0.0;
+            for (int c = tl; c < N; c += TS) {
+                const double v = A[row * ld + c];
+                s += v * v;
+            }
+            s = team_sum<TS>(s);
+            if (tl == 0) nrm2[row] = s;
+        }
+        if (tid == 0) {
+            flag[0] = 0;      // any rotation in this sweep
+            flag[1] = 0;      // any pair whose relative off-diagonal exceeded sqrt(tol)
+        }
+        __syncthreads();
+        for (int span = N / 2; span >= 1; span >>= 1) {
+            const int base = (team / span) * (2 * span);
+            const int j = team % span;
+            const int p = base + j;
+            double* x = A + p * ld;
+            double2 xv[MAXP];
+#pragma unroll
+            for (int e = 0; e < MAXP; ++e) xv[e] = *reinterpret_cast<const double2*>(x + 2 * (tl + e * TS));
+            double al = nrm2[p];
+            for (int round = 0; round < span; ++round) {
+                int jq = j + round;
+                jq = jq >= span ? jq - span : jq;
+                const int q = base + span + jq;
+                double* y = A + q * ld;
+                double2 yv[MAXP];
+                double g0 = 0.0, g1 = 0.0;
+#pragma unroll
+                for (int e = 0; e < MAXP; ++e) {
+                    yv[e] = *reinterpret_cast<const double2*>(y + 2 * (tl + e * TS));
+                    g0 = fma(xv[e].x, yv[e].x, g0);
+                    g1 = fma(xv[e].y, yv[e].y, g1);
+                }
+                const double ga = team_sum<TS>(g0 + g1);
+                const double be = nrm2[q];
+                // the decision and the angle only need fp32 (the range guard sends the rare pair whose
+                // magnitudes leave fp32's range through fp64)
+                float gf = static_cast<float>(ga), af = static_cast<float>(al), bf = static_cast<float>(be);
+                float df = static_cast<float>(be - al);
+                const float big = fmaxf(af, bf);
+                if (!(big < 1e18f && big > 1e-18f)) {
+                    int ex;
+                    (void)frexp(fmax(al, be), &ex);
+                    gf = static_cast<float>(ldexp(ga, -ex));
+                    af = static_cast<float>(ldexp(al, -ex));
+                    bf = static_cast<float>(ldexp(be, -ex));
+                    df = static_cast<float>(ldexp(be - al, -ex));
+                }
+                const float g2 = gf * gf, ab = af * bf;
+                if (g2 > tol2 * ab && gf != 0.0f) {
+                    const float zf = df * __builtin_amdgcn_rcpf(2.0f * gf);
+                    const float az = fabsf(zf);
+                    // tan = sign(z) / (|z| + sqrt(1 + z^2));   |z| huge: 1 / (2 z)
+                    const float den = az < 1e18f ? az + __builtin_amdgcn_sqrtf(fmaf(zf, zf, 1.0f)) : 2.0f * az;
+                    const float tf = copysignf(__builtin_amdgcn_rcpf(den), zf);
+                    const double t = static_cast<double>(tf);
+                    const double a = fma(t, t, 1.0);
+                    double cs = static_cast<double>(__builtin_amdgcn_rsqf(static_cast<float>(a)));
+                    cs = cs * fma(-0.5 * a, cs * cs, 1.5);
+                    cs = cs * fma(-0.5 * a, cs * cs, 1.5);
+                    const double sn = cs * t;
+#pragma unroll
+                    for (int e = 0; e < MAXP; ++e) {
+                        const double2 xo = xv[e];
+                        xv[e] = double2{fma(cs, xo.x, -sn * yv[e].x), fma(cs, xo.y, -sn * yv[e].y)};
+                        *reinterpret_cast<double2*>(y + 2 * (tl + e * TS)) =
+                            double2{fma(sn, xo.x, cs * yv[e].x), fma(sn, xo.y, cs * yv[e].y)};
+                    }
+                    // exact for ANY rotation angle; rounding drift is removed by the per-sweep refresh
+                    const double cc = cs * cs, ss = sn * sn, x2 = 2.0 * cs * sn * ga;
+                    if (tl == 0) {
+                        nrm2[q] = ss * al + x2 + cc * be;
+                        flag[0] = 1;
+                        if (g2 > early2 * ab) flag[1] = 1;
+                    }
+                    al = cc * al - x2 + ss * be;
+                }
+                __syncthreads();
+            }
+            // the level is over: the resident row goes back for the next level's pairing
+#pragma unroll
+            for (int e = 0; e < MAXP; ++e) *reinterpret_cast<double2*>(x + 2 * (tl + e * TS)) = xv[e];
+            if (tl == 0) nrm2[p] = al;
+            __syncthreads();
+        }
+        const int any = flag[0], coarse = flag[1];
+        __syncthreads();
+        if (!any || !coarse) {
+            ++sweep;
+            break;
+        }
+    }
+    return sweep;
+}
+
 }  // namespace squat

@@ -280,6 +280,9 @@ __global__ void __launch_bounds__(256) gram_reduce(const float* partial, int wgs
     }
 }
 
+#ifndef SQUAT_EIG_RESIDENT
+#define SQUAT_EIG_RESIDENT 1
+#endif
 #ifndef SQUAT_EIG_TS
 #define SQUAT_EIG_TS 16
 #endif
@@ -298,7 +301,11 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
     const double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     for (int i = threadIdx.x; i < kD * kD; i += kEigThreads) A[i] = g[i];
     __syncthreads();
+#if SQUAT_EIG_RESIDENT
+    const int sweeps = jacobi_rows_resident<kEigThreads, kEigTeam, kD / kEigTeam>(A, kEigLd, nrm, flag, 60, 1e-13);
+#else
     const int sweeps = jacobi_rows<kEigThreads, kEigTeam, kD / kEigTeam, true>(A, kD, kEigLd, nrm, flag, 60, 1e-13);
+#endif
     __syncthreads();
     if (sweeps_out && threadIdx.x == 0) sweeps_out[kvh] = sweeps;
 
