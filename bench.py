@@ -263,6 +263,32 @@ def main():
         us = timed_us(lambda: squat.key_scores(qd, cd, sd, zd, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=ld), reps=10)
         nk = 64 * H * nd
         nb = nk * (d * wl.bits // 8 + 4 * (d // wl.group) + 4 * wl.q_per_kv)
+        # the same shape through the cache object: 64 decode steps (append one token per sequence, then
+        # logits over everything cached); two of the 64 appends flush a full residual buffer
+        kp = torch.randn((64, H, nd, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        cache = squat.Cache(64, H, wl.q_per_kv, wl.bits, wl.group, wl.g, 32, nd + 64, kv_dtype=torch.bfloat16, update=update)
+        cache.prefill(kp)
+        del kp
+        knew = torch.randn((64, H, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        lc = torch.empty((64, H * wl.q_per_kv, nd + 64), dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t_app = t_sc = 0.0
+        for _ in range(64):
+            e[0].record()
+            cache.append(knew)
+            e[1].record()
+            cache.key_scores(qd, d ** -0.5, out=lc)
+            e[2].record()
+            torch.cuda.synchronize()
+            t_app += e[0].elapsed_time(e[1])
+            t_sc += e[1].elapsed_time(e[2])
+        cnt = cache.counts()
+        out["decode_cache"] = {"sequences": 64, "heads": H, "tokens_cached": int(cnt.n_tokens), "residual": 32,
+                               "us_per_append_mean_of_64": t_app / 64 * 1e3, "us_per_logits_mean_of_64": t_sc / 64 * 1e3,
+                               "note": "append = copy into the residual buffer, plus every 32nd step one quantize "
+                                       "launch over 64 x %d x 32 keys" % H}
+        del cache
         out["decode_scores"] = {"sequences": 64, "heads": H, "quantized_tokens": nd, "q_per_kv": wl.q_per_kv, "us": us,
                                 "keys_per_s": nk / (us * 1e-6), "frac_of_hbm_peak": nb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:

@@ -272,6 +272,92 @@ int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_
                      int64_t q_stride_head, float out_scale, float* scores,
                      int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
 
+/* ------------------------------------------------------------------------- *
+ * squat_cache_*  (Algorithm 1: the prefill split "r = l mod R", the residual
+ * buffer K^full and its flush in the decoding phase; appendix "Details of Our
+ * Main Algorithm": values follow KIVI, per-token groups, the most recent R
+ * tokens in full precision, the oldest one quantized when token R + 1 arrives).
+ *
+ * A small STATEFUL object on top of the stateless calls: it owns no device
+ * memory (everything lives in one caller-provided arena) and holds only
+ * counters and pointers on the host.  All sequences of the batch advance
+ * together.  Calls enqueue on the given stream and update the counters when
+ * they are made: use one stream and one host thread per cache.
+ *
+ *   keys    quantized with squat_quantize_keys (per-token groups, the update
+ *           matrix given at creation, shared by the batch) in groups of
+ *           `residual` tokens; the rest waits in the residual buffer.
+ *   values  (optional) quantized with plain round-to-nearest one token at a
+ *           time once they are older than `residual` tokens.
+ *   logits  squat_cache_key_scores = squat_key_scores over the quantized keys
+ *           followed by plain dot products over the residual keys:
+ *           scores[b, hq, 0 .. keys_quantized + keys_residual).
+ * ------------------------------------------------------------------------- */
+typedef struct squat_cache squat_cache;
+
+typedef struct squat_cache_config {
+    int64_t n_batch;
+    int n_kv_heads;       /* layers may be stacked along this axis */
+    int q_per_kv;         /* 1 .. 8 */
+    int d;                /* 128 */
+    int bits;             /* 2 or 4 */
+    int group;            /* channels per quantization group: 32, 64 or 128 */
+    int g;                /* channels frozen per iteration: 32, 64 or 128 (as given to squat_prepare) */
+    int residual;         /* R: full-precision tokens kept; 1 .. 1024 (32 in the paper) */
+    int64_t max_tokens;   /* capacity of the quantized stores per sequence; multiple of residual, < 2^25 */
+    squat_dtype kv_dtype; /* dtype of incoming keys / values and of the residual buffers */
+    int quantize_values;  /* 0: keys only */
+} squat_cache_config;
+
+typedef struct squat_cache_buffers {   /* device pointers inside the arena */
+    uint32_t* key_codes;      /* [n_batch, n_kv_heads, max_tokens, d*bits/32] */
+    uint16_t* key_scale;      /* [n_batch, n_kv_heads, max_tokens, d/group]   */
+    uint16_t* key_zero;
+    void* key_residual;       /* [n_batch, n_kv_heads, residual, d] kv_dtype; slots 0 .. keys_residual-1 in use */
+    uint32_t* value_codes;    /* same shapes; NULL without values */
+    uint16_t* value_scale;
+    uint16_t* value_zero;
+    void* value_residual;     /* ring: oldest token in slot value_ring_head */
+} squat_cache_buffers;
+
+typedef struct squat_cache_counts {
+    int64_t n_tokens;         /* tokens seen per sequence */
+    int64_t keys_quantized;
+    int keys_residual;
+    int64_t values_quantized;
+    int values_residual;
+    int value_ring_head;
+} squat_cache_counts;
+
+/* Bytes of device memory the cache needs (0 if the configuration is not supported). */
+size_t squat_cache_arena_bytes(const squat_cache_config* cfg);
+
+/* arena: device memory, 256-byte aligned, at least squat_cache_arena_bytes(cfg); update: [n_kv_heads, d, d]
+ * float as written by squat_prepare with the same g (NULL: plain round-to-nearest); both must outlive the
+ * cache.  *out receives the object (host memory; release it with squat_cache_destroy). */
+int squat_cache_create(const squat_cache_config* cfg, void* arena, size_t arena_bytes, const float* update,
+                       squat_cache** out);
+void squat_cache_destroy(squat_cache* cache);
+int squat_cache_reset(squat_cache* cache);          /* forget all tokens (no device work) */
+int squat_cache_state(const squat_cache* cache, squat_cache_counts* out);
+int squat_cache_get_buffers(const squat_cache* cache, squat_cache_buffers* out);
+
+/* Prompt keys (and values, if configured): [n_batch, n_kv_heads, n_tokens, d] kv_dtype with element strides
+ * (multiples of 8, base 16-byte aligned; values use the same strides).  Only on an empty cache.  Keys
+ * 0 .. n_tokens - (n_tokens mod residual) - 1 are quantized, the rest goes to the residual buffer. */
+int squat_cache_prefill(squat_cache* cache, const void* k, const void* v, int64_t n_tokens,
+                        int64_t stride_batch, int64_t stride_head, int64_t stride_token, squat_stream stream);
+
+/* One decoded token per sequence: k, v [n_batch, n_kv_heads, d].  SQUAT_E_BADSHAPE when a store is full. */
+int squat_cache_append(squat_cache* cache, const void* k, const void* v, int64_t stride_batch,
+                       int64_t stride_head, squat_stream stream);
+
+/* Logits of q [n_batch, n_kv_heads*q_per_kv, d] against every cached key, quantized ones first; arguments
+ * as for squat_key_scores; s_stride_head >= keys_quantized + keys_residual. */
+int squat_cache_key_scores(const squat_cache* cache, const void* q, squat_dtype q_dt, int64_t q_stride_batch,
+                           int64_t q_stride_head, float out_scale, float* scores, int64_t s_stride_batch,
+                           int64_t s_stride_head, squat_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

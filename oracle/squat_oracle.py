@@ -21,6 +21,8 @@ Parity status of each function:
   rtn_group, quantize_keys      pinned (hand-worked fixture, r=0 fixed point,
                                 per-step optimality against a generic solver,
                                 soft and hard invariants), both grouping axes
+  CacheOracle                   pinned (counts against l mod R by hand, stores
+                                against one-shot quantization of the prefix)
   key_scores                    pinned (element loops, one-hot queries, closed
                                 form for constant codes)
   dequantize_keys, pack/unpack  pinned (definition of deq; pack o unpack = id,
@@ -38,7 +40,7 @@ __all__ = [
     "update_matrix_lemma", "update_matrix_kkt", "update_matrix_lowrank",
     "rtn_group", "quantize_keys", "dequantize_keys",
     "pack_codes", "unpack_codes", "pack_codes_tokens", "unpack_codes_tokens",
-    "replay_classify", "key_scores",
+    "replay_classify", "key_scores", "CacheOracle",
 ]
 
 
@@ -386,6 +388,77 @@ def key_scores(q: np.ndarray, codes: np.ndarray, scale: np.ndarray, zero: np.nda
     """
     khat = dequantize_keys(codes, scale, zero, G, axis=axis)
     return float(out_scale) * (np.asarray(q, dtype=np.float64) @ khat.T)
+
+
+class CacheOracle:
+    """Residual-buffer bookkeeping of Algorithm 1 for ONE head of ONE sequence,
+    written out with Python lists (prefill: "r = l mod R", K_full = the last r
+    keys; decoding: append, and when the buffer holds R keys quantize all of them
+    and empty it), plus the value rule of the appendix "Details of Our Main
+    Algorithm" (values per token, the most recent R in full precision, the oldest
+    one quantized when token R + 1 arrives).  Keys use per-token groups (this
+    build's contract), so a flush of R keys is R independent runs of
+    `quantize_keys`.
+    """
+
+    def __init__(self, U, bits: int, G: int, g: int, R: int, values: bool = False):
+        self.U, self.bits, self.G, self.g, self.R, self.values = U, bits, G, g, R, values
+        self.k_codes, self.k_scale, self.k_zero = [], [], []      # one entry per quantized key
+        self.k_full = []                                           # residual keys, oldest first
+        self.v_codes, self.v_scale, self.v_zero = [], [], []
+        self.v_full = []                                           # residual values, oldest first
+        self.n_tokens = 0
+
+    def _quant_keys(self, rows):
+        out = quantize_keys(np.asarray(rows, dtype=np.float64), self.U, self.bits, self.G, self.g)
+        for i in range(len(rows)):
+            self.k_codes.append(out["codes"][i])
+            self.k_scale.append(out["scale"][i])
+            self.k_zero.append(out["zero"][i])
+
+    def _quant_value(self, row):
+        out = quantize_keys(np.asarray(row, dtype=np.float64)[None], None, self.bits, self.G, len(row))
+        self.v_codes.append(out["codes"][0])
+        self.v_scale.append(out["scale"][0])
+        self.v_zero.append(out["zero"][0])
+
+    def prefill(self, K, V=None):
+        K = np.asarray(K, dtype=np.float64)
+        l = K.shape[0]
+        r = l % self.R
+        if l - r > 0:
+            self._quant_keys(K[: l - r])
+        self.k_full = [K[i] for i in range(l - r, l)]
+        if self.values:
+            V = np.asarray(V, dtype=np.float64)
+            for i in range(l):
+                self._push_value(V[i])
+        self.n_tokens = l
+
+    def _push_value(self, v):
+        self.v_full.append(np.asarray(v, dtype=np.float64))
+        if len(self.v_full) == self.R + 1:
+            self._quant_value(self.v_full.pop(0))
+
+    def append(self, k, v=None):
+        self.k_full.append(np.asarray(k, dtype=np.float64))
+        if len(self.k_full) == self.R:
+            self._quant_keys(self.k_full)
+            self.k_full = []
+        if self.values:
+            self._push_value(v)
+        self.n_tokens += 1
+
+    def scores(self, q, out_scale: float = 1.0):
+        """Logits of q (n_q, d) against all cached keys: quantized ones first, then the residual ones."""
+        q = np.asarray(q, dtype=np.float64)
+        parts = []
+        if self.k_codes:
+            parts.append(key_scores(q, np.stack(self.k_codes), np.stack(self.k_scale), np.stack(self.k_zero),
+                                    self.G, out_scale))
+        if self.k_full:
+            parts.append(float(out_scale) * (q @ np.stack(self.k_full).T))
+        return np.concatenate(parts, axis=1) if parts else np.zeros((q.shape[0], 0))
 
 
 # --------------------------------------------------------------------------- #

@@ -13,7 +13,7 @@ OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libsquat.so")
 
 SOURCES = ["squat_api.cpp", "squat_quantize.hip", "squat_quantize_pc.hip", "squat_dequantize.hip",
-           "squat_subspace.hip", "squat_prepare.hip", "squat_scores.hip"]
+           "squat_subspace.hip", "squat_prepare.hip", "squat_scores.hip", "squat_cache.hip"]
 
 # Packed-fp32 VALU ops are switched off on purpose (build flags).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

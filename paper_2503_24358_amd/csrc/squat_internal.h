@@ -96,6 +96,17 @@ __device__ __forceinline__ float pair_max(float v) {
     return raw_max(as_f32(r[0]), as_f32(r[1]));
 }
 
+// Entry points with an explicit output / input placement inside a larger store (used by the cache).
+int quantize_keys_into(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens, int d,
+                       int64_t k_stride_batch, int64_t k_stride_head, int64_t k_stride_token, const float* update,
+                       int64_t update_stride_batch, int bits, int group, int g, uint32_t* codes, uint16_t* scale,
+                       uint16_t* zero, int64_t out_stride, int64_t out_offset, squat_stream stream);
+int key_scores_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                    int n_kv_heads, int64_t n_tokens, int64_t store_stride, int d, int bits, int group,
+                    const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head,
+                    float out_scale, float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                    squat_stream stream);
+
 // Number of compute units of the current device (256 if the query fails).
 inline int device_cu_count() {
     int dev = 0, cus = 0;

@@ -45,6 +45,8 @@ struct QuantParams {
     uint16_t* scale;
     uint16_t* zero;
     int64_t n_tokens;
+    int64_t out_stride;              // tokens per (batch, head) in the output store (>= n_tokens)
+    int64_t out_offset;              // first output token
     int64_t n_inner;                 // batch entries that share one update matrix
     int n_heads;
     int64_t tiles_per_seq;
@@ -391,7 +393,7 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
         int64_t tok0;
         locate(cur, bi, tok0);
         const bool valid = tok0 + n < p.n_tokens;
-        const int64_t row0 = ((bo + bi) * p.n_heads + head) * p.n_tokens + tok0;     // wave-uniform
+        const int64_t row0 = ((bo + bi) * p.n_heads + head) * p.out_stride + p.out_offset + tok0;     // wave-uniform
 
         // lower half-wave collects the first half of a key's words, upper the second
 #pragma unroll
@@ -475,17 +477,19 @@ int dispatch_gt(int gt, int bt, squat_dtype dt, const QuantParams& p, int64_t n_
 
 }  // namespace
 
-extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
-                                   int64_t n_tokens, int d, int64_t k_stride_batch,
-                                   int64_t k_stride_head, int64_t k_stride_token,
-                                   const float* update, int64_t update_stride_batch, int bits,
-                                   int group, int g, uint32_t* codes, uint16_t* scale,
-                                   uint16_t* zero, squat_stream stream) {
+// squat_quantize_keys with the outputs placed at tokens out_offset .. of a store that holds out_stride
+// tokens per (batch, head): what a cache appends with.
+int squat::quantize_keys_into(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens,
+                              int d, int64_t k_stride_batch, int64_t k_stride_head, int64_t k_stride_token,
+                              const float* update, int64_t update_stride_batch, int bits, int group, int g,
+                              uint32_t* codes, uint16_t* scale, uint16_t* zero, int64_t out_stride,
+                              int64_t out_offset, squat_stream stream) {
     if (d != kD) return SQUAT_E_BADSHAPE;
     if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
     if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
     if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
     if (n_batch < 0 || n_heads < 0 || n_tokens < 0) return SQUAT_E_BADSHAPE;
+    if (out_offset < 0 || out_stride < out_offset + n_tokens) return SQUAT_E_BADSHAPE;
     if (k_dt != SQUAT_F32 && k_dt != SQUAT_F16 && k_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
     if (n_batch == 0 || n_heads == 0 || n_tokens == 0) return SQUAT_OK;
     if (!k || !codes || !scale || !zero) return SQUAT_E_NULLPTR;
@@ -493,6 +497,8 @@ extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_ba
         return SQUAT_E_BADSHAPE;
     if ((k_stride_token % 8) || (k_stride_head % 8) || (k_stride_batch % 8)) return SQUAT_E_ALIGN;
     if (!aligned(k, 16) || !aligned(codes, 16) || !aligned(scale, 8) || !aligned(zero, 8)) return SQUAT_E_ALIGN;
+    // the kernel stores 16-byte pieces of codes and 8-byte pieces of metadata per key
+    if ((out_stride * (d * bits / 8)) % 16 || (out_offset * (d * bits / 8)) % 16) return SQUAT_E_ALIGN;
     if (update && (!aligned(update, 16) || (update_stride_batch % 4))) return SQUAT_E_ALIGN;
     if (n_batch * n_heads > (int64_t(1) << 30)) return SQUAT_E_BADSHAPE;
 
@@ -508,6 +514,8 @@ extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_ba
     p.scale = scale;
     p.zero = zero;
     p.n_tokens = n_tokens;
+    p.out_stride = out_stride;
+    p.out_offset = out_offset;
     p.n_heads = n_heads;
     p.tiles_per_seq = (n_tokens + kTileTokens - 1) / kTileTokens;
 
@@ -549,4 +557,15 @@ extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_ba
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? dispatch_gt<2>(gt, bt, k_dt, p, n_prob, s)
                      : dispatch_gt<4>(gt, bt, k_dt, p, n_prob, s);
+}
+
+extern "C" int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
+                                   int64_t n_tokens, int d, int64_t k_stride_batch,
+                                   int64_t k_stride_head, int64_t k_stride_token,
+                                   const float* update, int64_t update_stride_batch, int bits,
+                                   int group, int g, uint32_t* codes, uint16_t* scale,
+                                   uint16_t* zero, squat_stream stream) {
+    return squat::quantize_keys_into(k, k_dt, n_batch, n_heads, n_tokens, d, k_stride_batch, k_stride_head,
+                                     k_stride_token, update, update_stride_batch, bits, group, g, codes, scale,
+                                     zero, n_tokens, 0, stream);
 }

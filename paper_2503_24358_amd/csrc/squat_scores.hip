@@ -36,7 +36,7 @@ constexpr int kDepth = 4;              // units whose loads are in flight per wa
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int kUnitTokens = 16;        // tokens per matrix product (MFMA N)
-constexpr int kMaxUnitsPerWave = 32;   // 16-token units a wavefront handles (amortises its operand set-up) ...
+constexpr int kMaxUnitsPerWave = 32;   // 16-token units a wavefront aims at (amortises its operand set-up; up to 1.5x) ...
 constexpr int kMinUnitsPerWave = 4;    // ... unless the sequence is short: then all four wavefronts share it
 constexpr int kScoreWaves = 4;
 
@@ -50,6 +50,7 @@ struct ScoreParams {
     float* scores;
     int64_t ssb, ssh;                // score strides in elements
     int64_t n_tokens;
+    int64_t store_stride;            // tokens per (batch, KV head) in the store (>= n_tokens)
     int n_kv_heads;
     int qpk;
     float out_scale;
@@ -171,7 +172,7 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     const int n_units = static_cast<int>((p.n_tokens + kUnitTokens - 1) / kUnitTokens);
     const int u0 = (static_cast<int>(blockIdx.x) * kScoreWaves + wave) * p.units_per_wave;
     const int u1 = min(u0 + p.units_per_wave, n_units);
-    const int64_t row0 = bh * p.n_tokens;
+    const int64_t row0 = bh * p.store_stride;
     const int widx0 = BITS == 2 ? (kb >> 1) : kb;          // word of chunk 0 this lane unpacks
     // right-rotations that bring this lane's codes to bits 6..9 of both halves: 2-bit, codes c0, c0 + 1
     // (c0 = 4 (kb & 1), at bits 2 c0) then c0 + 2, c0 + 3; a rotation by 32 - k is a left shift by k
@@ -341,16 +342,19 @@ int launch_ng(int ng, const ScoreParams& p, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
-extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
-                                int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
-                                const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
-                                int64_t q_stride_head, float out_scale, float* scores,
-                                int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream) {
+// squat_key_scores over the first n_tokens tokens of a store that holds store_stride tokens per
+// (batch, KV head).
+int squat::key_scores_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                           int n_kv_heads, int64_t n_tokens, int64_t store_stride, int d, int bits, int group,
+                           const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                           int64_t q_stride_head, float out_scale, float* scores, int64_t s_stride_batch,
+                           int64_t s_stride_head, squat_stream stream) {
     if (d != kD) return SQUAT_E_BADSHAPE;
     if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
     if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
     if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
     if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0 || n_tokens >= (int64_t(1) << 25)) return SQUAT_E_BADSHAPE;
+    if (store_stride < n_tokens) return SQUAT_E_BADSHAPE;
     if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
     if (!(out_scale == out_scale)) return SQUAT_E_BADVALUE;
     if (n_batch == 0 || n_kv_heads == 0 || n_tokens == 0) return SQUAT_OK;
@@ -372,16 +376,22 @@ extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, co
     p.ssb = s_stride_batch;
     p.ssh = s_stride_head;
     p.n_tokens = n_tokens;
+    p.store_stride = store_stride;
     p.n_kv_heads = n_kv_heads;
     p.qpk = q_per_kv;
     p.out_scale = out_scale;
 
     const int64_t n_units = (n_tokens + kUnitTokens - 1) / kUnitTokens;
-    int64_t upw = (n_units + kScoreWaves - 1) / kScoreWaves;
-    upw = upw > kMaxUnitsPerWave ? kMaxUnitsPerWave : (upw < kMinUnitsPerWave ? kMinUnitsPerWave : upw);
+    // Workgroups along the sequence: about kScoreWaves * kMaxUnitsPerWave units each, the count rounded to
+    // nearest and the units then spread evenly, so that no workgroup pays the operand set-up for a sliver
+    // (2080 tokens = 130 units used to run as 128 + 2 and took 60 % longer than 2048 tokens).
+    const int64_t slab = static_cast<int64_t>(kScoreWaves) * kMaxUnitsPerWave;
+    int64_t gx = (n_units + slab / 2) / slab;
+    if (gx < 1) gx = 1;
+    int64_t upw = (n_units + kScoreWaves * gx - 1) / (kScoreWaves * gx);
+    if (upw < kMinUnitsPerWave) upw = kMinUnitsPerWave;
     p.units_per_wave = static_cast<int>(upw);
-    const int64_t per_wg = static_cast<int64_t>(kScoreWaves) * upw;
-    const int64_t gx = (n_units + per_wg - 1) / per_wg;
+    gx = (n_units + kScoreWaves * upw - 1) / (kScoreWaves * upw);
     const int64_t bh = n_batch * n_kv_heads;
     int64_t gy = bh, gz = 1;
     if (gy > 65535) {
@@ -394,4 +404,14 @@ extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, co
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? launch_ng<2>(128 / group, p, grid, s) : launch_ng<4>(128 / group, p, grid, s);
+}
+
+extern "C" int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
+                                const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                                int64_t q_stride_head, float out_scale, float* scores,
+                                int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream) {
+    return squat::key_scores_from(codes, scale, zero, n_batch, n_kv_heads, n_tokens, n_tokens, d, bits, group, q,
+                                  q_dt, q_per_kv, q_stride_batch, q_stride_head, out_scale, scores,
+                                  s_stride_batch, s_stride_head, stream);
 }

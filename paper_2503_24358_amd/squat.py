@@ -20,7 +20,30 @@ _lib = None
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
            "squat_quantize_keys", "squat_dequantize_keys",
-           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores")
+           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores",
+           "squat_cache_arena_bytes", "squat_cache_create", "squat_cache_destroy", "squat_cache_reset",
+           "squat_cache_state", "squat_cache_get_buffers", "squat_cache_prefill", "squat_cache_append",
+           "squat_cache_key_scores")
+
+
+class CacheConfig(ctypes.Structure):
+    _fields_ = [("n_batch", ctypes.c_int64), ("n_kv_heads", ctypes.c_int), ("q_per_kv", ctypes.c_int),
+                ("d", ctypes.c_int), ("bits", ctypes.c_int), ("group", ctypes.c_int), ("g", ctypes.c_int),
+                ("residual", ctypes.c_int), ("max_tokens", ctypes.c_int64), ("kv_dtype", ctypes.c_int),
+                ("quantize_values", ctypes.c_int)]
+
+
+class CacheBuffers(ctypes.Structure):
+    _fields_ = [("key_codes", ctypes.c_void_p), ("key_scale", ctypes.c_void_p), ("key_zero", ctypes.c_void_p),
+                ("key_residual", ctypes.c_void_p), ("value_codes", ctypes.c_void_p),
+                ("value_scale", ctypes.c_void_p), ("value_zero", ctypes.c_void_p),
+                ("value_residual", ctypes.c_void_p)]
+
+
+class CacheCounts(ctypes.Structure):
+    _fields_ = [("n_tokens", ctypes.c_int64), ("keys_quantized", ctypes.c_int64), ("keys_residual", ctypes.c_int),
+                ("values_quantized", ctypes.c_int64), ("values_residual", ctypes.c_int),
+                ("value_ring_head", ctypes.c_int)]
 
 
 class SquatError(RuntimeError):
@@ -63,6 +86,25 @@ def lib() -> ctypes.CDLL:
     L.squat_key_scores.restype = i32
     L.squat_key_scores.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i32, i32, i64, i64, f32, vp,
                                    i64, i64, vp]
+    cfgp = ctypes.POINTER(CacheConfig)
+    L.squat_cache_arena_bytes.restype = sz
+    L.squat_cache_arena_bytes.argtypes = [cfgp]
+    L.squat_cache_create.restype = i32
+    L.squat_cache_create.argtypes = [cfgp, vp, sz, vp, ctypes.POINTER(vp)]
+    L.squat_cache_destroy.restype = None
+    L.squat_cache_destroy.argtypes = [vp]
+    L.squat_cache_reset.restype = i32
+    L.squat_cache_reset.argtypes = [vp]
+    L.squat_cache_state.restype = i32
+    L.squat_cache_state.argtypes = [vp, ctypes.POINTER(CacheCounts)]
+    L.squat_cache_get_buffers.restype = i32
+    L.squat_cache_get_buffers.argtypes = [vp, ctypes.POINTER(CacheBuffers)]
+    L.squat_cache_prefill.restype = i32
+    L.squat_cache_prefill.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp]
+    L.squat_cache_append.restype = i32
+    L.squat_cache_append.argtypes = [vp, vp, vp, i64, i64, vp]
+    L.squat_cache_key_scores.restype = i32
+    L.squat_cache_key_scores.argtypes = [vp, vp, i32, i64, i64, f32, vp, i64, i64, vp]
     _lib = L
     return L
 
@@ -268,3 +310,104 @@ def key_scores(q: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, zero: 
     if rc:
         raise SquatError(rc, "squat_key_scores")
     return out
+
+
+class Cache:
+    """squat_cache_*: the residual-buffer bookkeeping around the stateless calls.  The arena (one uint8
+    device tensor) and the update matrix are kept alive by this object; the store tensors returned by
+    `stores()` are views into the arena."""
+
+    def __init__(self, n_batch: int, n_kv_heads: int, q_per_kv: int, bits: int, group: int, g: int, residual: int,
+                 max_tokens: int, kv_dtype=torch.bfloat16, update: Optional[torch.Tensor] = None,
+                 quantize_values: bool = False, device="cuda", d: int = 128):
+        self.cfg = CacheConfig(n_batch, n_kv_heads, q_per_kv, d, bits, group, g, residual, max_tokens,
+                               _DT[kv_dtype], int(quantize_values))
+        self.kv_dtype = kv_dtype
+        nbytes = int(lib().squat_cache_arena_bytes(ctypes.byref(self.cfg)))
+        if nbytes == 0:
+            raise SquatError(-2, "squat_cache_arena_bytes")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        if update is not None and (update.dtype != torch.float32 or not update.is_contiguous()):
+            raise ValueError("update must be dense float32")
+        self.update = update
+        handle = ctypes.c_void_p()
+        rc = lib().squat_cache_create(ctypes.byref(self.cfg), _ptr(self.arena), nbytes, _ptr(update), ctypes.byref(handle))
+        if rc:
+            raise SquatError(rc, "squat_cache_create")
+        self._h = handle
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h:
+            lib().squat_cache_destroy(h)
+            self._h = None
+
+    def counts(self) -> CacheCounts:
+        out = CacheCounts()
+        rc = lib().squat_cache_state(self._h, ctypes.byref(out))
+        if rc:
+            raise SquatError(rc, "squat_cache_state")
+        return out
+
+    def reset(self):
+        lib().squat_cache_reset(self._h)
+
+    def _view(self, ptr, shape, dtype):
+        off = ptr - self.arena.data_ptr()
+        n = 1
+        for x in shape:
+            n *= x
+        nb = n * torch.empty((), dtype=dtype).element_size()
+        return self.arena[off:off + nb].view(dtype).view(shape)
+
+    def stores(self) -> dict:
+        """Views of the arena: codes int32 [B,H,max,d*bits/32], scale/zero f16 [B,H,max,d/group], residual
+        buffers [B,H,R,d] in the kv dtype (values only when configured)."""
+        b = CacheBuffers()
+        rc = lib().squat_cache_get_buffers(self._h, ctypes.byref(b))
+        if rc:
+            raise SquatError(rc, "squat_cache_get_buffers")
+        c = self.cfg
+        B, H, M, R, d = c.n_batch, c.n_kv_heads, c.max_tokens, c.residual, c.d
+        out = {"key_codes": self._view(b.key_codes, (B, H, M, d * c.bits // 32), torch.int32),
+               "key_scale": self._view(b.key_scale, (B, H, M, d // c.group), torch.float16),
+               "key_zero": self._view(b.key_zero, (B, H, M, d // c.group), torch.float16),
+               "key_residual": self._view(b.key_residual, (B, H, R, d), self.kv_dtype)}
+        if c.quantize_values:
+            out.update({"value_codes": self._view(b.value_codes, (B, H, M, d * c.bits // 32), torch.int32),
+                        "value_scale": self._view(b.value_scale, (B, H, M, d // c.group), torch.float16),
+                        "value_zero": self._view(b.value_zero, (B, H, M, d // c.group), torch.float16),
+                        "value_residual": self._view(b.value_residual, (B, H, R, d), self.kv_dtype)})
+        return out
+
+    def prefill(self, k: torch.Tensor, v: Optional[torch.Tensor] = None, stream=None):
+        """k, v: [B, H, n, d] in the kv dtype (same strides)."""
+        _need_cuda(k, v)
+        if v is not None and v.stride() != k.stride():
+            raise ValueError("k and v must share their strides")
+        rc = lib().squat_cache_prefill(self._h, _ptr(k), _ptr(v), k.shape[2], k.stride(0), k.stride(1), k.stride(2),
+                                       _stream(stream))
+        if rc:
+            raise SquatError(rc, "squat_cache_prefill")
+
+    def append(self, k: torch.Tensor, v: Optional[torch.Tensor] = None, stream=None):
+        """k, v: [B, H, d], one decoded token per sequence."""
+        _need_cuda(k, v)
+        if v is not None and v.stride() != k.stride():
+            raise ValueError("k and v must share their strides")
+        rc = lib().squat_cache_append(self._h, _ptr(k), _ptr(v), k.stride(0), k.stride(1), _stream(stream))
+        if rc:
+            raise SquatError(rc, "squat_cache_append")
+
+    def key_scores(self, q: torch.Tensor, out_scale: float = 1.0, out=None, stream=None) -> torch.Tensor:
+        """q: [B, H*q_per_kv, d] -> logits float32 [B, H*q_per_kv, keys cached] (quantized keys first)."""
+        _need_cuda(q)
+        cnt = self.counts()
+        n = cnt.keys_quantized + cnt.keys_residual
+        if out is None:
+            out = torch.empty((q.shape[0], q.shape[1], n), dtype=torch.float32, device=q.device)
+        rc = lib().squat_cache_key_scores(self._h, _ptr(q), _DT[q.dtype], q.stride(0), q.stride(1), float(out_scale),
+                                          _ptr(out), out.stride(0), out.stride(1), _stream(stream))
+        if rc:
+            raise SquatError(rc, "squat_cache_key_scores")
+        return out

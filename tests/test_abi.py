@@ -152,3 +152,42 @@ def test_key_scores_argument_validation_happens_before_any_launch():
     assert ks(codes=odd) == -4
     assert ks(n=0) == 0
     assert ks(n=-1) == -2
+
+
+def test_cache_configuration_and_creation_are_validated_on_the_host():
+    L = squat.lib()
+    ok = squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4096, 2, 1)
+    need = L.squat_cache_arena_bytes(ctypes.byref(ok))
+    per = 2 * 8 * 4096 * (32 + 8 + 8) + 2 * 8 * 32 * 256            # codes + scale + zero + residual, per tensor kind
+    assert need >= 2 * per and need % 256 == 0
+    keys_only = squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4096, 2, 0)
+    assert per <= L.squat_cache_arena_bytes(ctypes.byref(keys_only)) < need
+    for bad in (squat.CacheConfig(2, 8, 4, 64, 2, 32, 32, 32, 4096, 2, 0),      # d
+                squat.CacheConfig(2, 8, 4, 128, 3, 32, 32, 32, 4096, 2, 0),     # bits
+                squat.CacheConfig(2, 8, 4, 128, 2, 48, 32, 32, 4096, 2, 0),     # group
+                squat.CacheConfig(2, 8, 0, 128, 2, 32, 32, 32, 4096, 2, 0),     # q_per_kv
+                squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4100, 2, 0),     # capacity not a multiple of R
+                squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 0, 4096, 2, 0),      # R
+                squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4096, 5, 0)):    # dtype
+        assert L.squat_cache_arena_bytes(ctypes.byref(bad)) == 0
+        h = ctypes.c_void_p()
+        assert L.squat_cache_create(ctypes.byref(bad), ctypes.c_void_p(0x1000), 1 << 40, None, ctypes.byref(h)) == -2
+    h = ctypes.c_void_p()
+    assert L.squat_cache_create(ctypes.byref(ok), None, need, None, ctypes.byref(h)) == -5
+    assert L.squat_cache_create(ctypes.byref(ok), ctypes.c_void_p(0x1000), need - 1, None, ctypes.byref(h)) == -5
+    assert L.squat_cache_create(ctypes.byref(ok), ctypes.c_void_p(0x1010), need, None, ctypes.byref(h)) == -4
+    assert L.squat_cache_create(ctypes.byref(ok), ctypes.c_void_p(0x1000), need, None, None) == -1
+    # a cache over a fake arena: bookkeeping calls that never touch the device
+    assert L.squat_cache_create(ctypes.byref(ok), ctypes.c_void_p(0x100000), need, None, ctypes.byref(h)) == 0
+    cnt = squat.CacheCounts()
+    assert L.squat_cache_state(h, ctypes.byref(cnt)) == 0 and cnt.n_tokens == 0 and cnt.keys_residual == 0
+    buf = squat.CacheBuffers()
+    assert L.squat_cache_get_buffers(h, ctypes.byref(buf)) == 0 and buf.key_codes == 0x100000
+    assert L.squat_cache_prefill(h, None, None, 64, 0, 0, 128, None) == -1            # NULL keys
+    assert L.squat_cache_prefill(h, ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1000), 64, 0, 0, 100, None) == -4
+    assert L.squat_cache_prefill(h, ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1000), -1, 0, 0, 128, None) == -2
+    assert L.squat_cache_prefill(h, None, None, 0, 0, 0, 128, None) == 0               # nothing to do
+    assert L.squat_cache_append(h, None, None, 0, 0, None) == -1
+    assert L.squat_cache_reset(h) == 0
+    L.squat_cache_destroy(h)
+    assert L.squat_cache_state(None, ctypes.byref(cnt)) == -1

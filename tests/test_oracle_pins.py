@@ -345,6 +345,40 @@ def test_key_scores_are_the_definition():
     assert abs(got[i, t] - acc) <= 1e-12 * max(1.0, abs(acc))
 
 
+def test_cache_bookkeeping_follows_algorithm_1():
+    """Prefill split r = l mod R, flush every R decoded keys, values lag R tokens behind.  Per-token
+    groups make every key independent, so whatever the order of the flushes the quantized store must
+    equal one-shot quantization of the same prefix."""
+    Qh, K = _setup(n=150)
+    gen = np.random.default_rng(31)
+    V = gen.standard_normal((150, 128))
+    U = O.update_matrix_lowrank(Qh, 1e-3, 32)
+    R = 32
+    c = O.CacheOracle(U, 2, 32, 32, R, values=True)
+    c.prefill(K[:70], V[:70])
+    assert len(c.k_codes) == 64 and len(c.k_full) == 6            # 70 = 2 * 32 + 6
+    assert len(c.v_codes) == 70 - R and len(c.v_full) == R
+    for t in range(70, 150):
+        c.append(K[t], V[t])
+        n = t + 1
+        assert len(c.k_full) == n % R and len(c.k_codes) == n - n % R
+        assert len(c.v_codes) == n - R and len(c.v_full) == R
+    ref = O.quantize_keys(K[:128], U, 2, 32, 32)
+    assert np.array_equal(np.stack(c.k_codes), ref["codes"]) and np.array_equal(np.stack(c.k_scale), ref["scale"])
+    assert np.array_equal(np.stack(c.k_full), K[128:150])
+    vref = O.rtn_group(V[:118].reshape(118, 4, 32), 2, axis=2)
+    assert np.array_equal(np.stack(c.v_codes), vref[0].reshape(118, 128))
+    assert np.array_equal(np.stack(c.v_full), V[118:150])
+    q = gen.standard_normal((3, 128))
+    s = c.scores(q, 0.5)
+    assert s.shape == (3, 150)
+    assert np.allclose(s[:, 128:], 0.5 * q @ K[128:150].T, rtol=1e-13)
+    assert np.allclose(s[:, :128], 0.5 * q @ ref["xhat"].T, rtol=1e-12, atol=1e-12)
+    short = O.CacheOracle(U, 2, 32, 32, R, values=True)
+    short.prefill(K[:5], V[:5])                                   # shorter than the buffer: nothing quantized
+    assert not short.k_codes and len(short.k_full) == 5 and not short.v_codes and len(short.v_full) == 5
+
+
 # ------------------------------------------- per-channel mode (the paper's own layout)
 @pytest.mark.parametrize("bits,g,lam", [(2, 32, 1e-3), (4, 64, 5e-4), (2, 32, np.inf)])
 def test_channel_axis_each_step_generic_solver(bits, g, lam):
