@@ -273,6 +273,33 @@ int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_
                      int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
+ * squat_key_scores_per_channel  (decoding phase of Algorithm 1 with the
+ * grouping its Quant function prints; Section 2: deq(c) = c * Delta + m).
+ *
+ * scores[b, hq, t] = out_scale * sum_c q[b, hq, c] * (code * scale + zero) with
+ * the scale and zero-point of (token group t / 32, channel c), read straight
+ * from the packed store of squat_quantize_keys_per_channel.
+ *
+ *   codes, scale, zero   as written by squat_quantize_keys_per_channel, dense,
+ *            all three 16-byte aligned.  group must be 32, n_tokens a multiple
+ *            of 32 and < 2^25.
+ *   q, q_per_kv, out_scale, scores and their strides   as for squat_key_scores;
+ *            |q| is not restricted (the kernel normalises by the exponent of
+ *            the largest |q| of a KV head, and per token group by the exponent
+ *            of its largest scale).
+ *   Each product q_c * scale_c is carried as an fp16 high/low pair: relative
+ *   error below 2^-21 per term, and an absolute floor of 2^-24 times (largest
+ *   |q| of the KV head) x (largest scale of the token group) per term; products
+ *   with the integer codes are exact, sums are fp32.
+ * ------------------------------------------------------------------------- */
+int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                 int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits,
+                                 int group, const void* q, squat_dtype q_dt, int q_per_kv,
+                                 int64_t q_stride_batch, int64_t q_stride_head, float out_scale,
+                                 float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                                 squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
  * squat_cache_*  (Algorithm 1: the prefill split "r = l mod R", the residual
  * buffer K^full and its flush in the decoding phase; appendix "Details of Our
  * Main Algorithm": values follow KIVI, per-token groups, the most recent R

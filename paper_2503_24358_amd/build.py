@@ -13,7 +13,7 @@ OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libsquat.so")
 
 SOURCES = ["squat_api.cpp", "squat_quantize.hip", "squat_quantize_pc.hip", "squat_dequantize.hip",
-           "squat_subspace.hip", "squat_prepare.hip", "squat_scores.hip", "squat_cache.hip"]
+           "squat_subspace.hip", "squat_prepare.hip", "squat_scores.hip", "squat_scores_pc.hip", "squat_cache.hip"]
 
 # Packed-fp32 VALU ops are switched off on purpose (build flags).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -28,10 +28,11 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-# Per-file extras.  The scores kernel reads every matrix-product result right away with ordinary vector
+# Per-file extras.  The scores kernels read every matrix-product result right away with ordinary vector
 # instructions: keep those results in the ordinary register file instead of the accumulation registers
 # (saves one copy per result register).
-EXTRA = {"squat_scores.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA = {"squat_scores.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "squat_scores_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src: str) -> str:

@@ -106,6 +106,11 @@ int key_scores_from(const uint32_t* codes, const uint16_t* scale, const uint16_t
                     const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head,
                     float out_scale, float* scores, int64_t s_stride_batch, int64_t s_stride_head,
                     squat_stream stream);
+int key_scores_pc_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                       int n_kv_heads, int64_t n_tokens, int64_t store_tokens, int d, int bits, int group,
+                       const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head,
+                       float out_scale, float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                       squat_stream stream);
 
 // Number of compute units of the current device (256 if the query fails).
 inline int device_cu_count() {

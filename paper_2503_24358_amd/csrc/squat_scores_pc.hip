@@ -1,0 +1,371 @@
+// squat_key_scores_per_channel: attention logits of decode-time queries against
+// the PER-CHANNEL packed key store (the grouping Algorithm 1's Quant prints:
+// one scale / zero-point per channel and group of 32 tokens), out_scale * q .
+// deq(code)^T without materialising the keys (Section 2: deq(c) = c * Delta + m).
+//
+// For token t of token group T,
+//     q . deq = sum_c (q_c Delta_{T,c}) code_{c,t}  +  sum_c q_c m_{T,c}.
+// The scales sit INSIDE the contraction here, so the query-side operand is
+// rebuilt for every token group: a_c = q_c Delta_c as an fp16 high / low pair
+// (rows = (query head, part), as in the per-token kernel), formed with packed
+// fp16 arithmetic from the fp16 parts of q and the fp16 Delta as stored:
+//     hi = rn(q_hi Delta),  lo = fma(q_hi, Delta, -hi) [exact] (+ q_lo Delta).
+// Two wave-uniform powers of two keep that inside fp16's range whatever the data:
+// q is normalised by the exponent of max |q| of the KV head, Delta by the
+// exponent of the largest Delta of the token group (both undone in fp32 at the
+// end).  The codes are the other operand, as raw bits: a code at bit s of a
+// 16-bit half IS the fp16 subnormal code * 2^(s-24), and codes are only read at
+// bits 6..9 (the matrix cores align products by exponent fields; lower positions
+// lose bits).  A packed word holds 16 (2-bit) or 8 (4-bit) TOKENS of one channel
+// while a matrix operand wants consecutive CHANNELS of one token in a lane, so
+// the group's words go through a small per-wavefront LDS tile; a lane then takes
+// the low (high) 16-bit halves of two channels' words with one v_perm, and one
+// rotate + mask puts its token's two codes into an operand register: 1.5
+// instructions per code.  The zero-point term is one more matrix product per
+// chunk with the zero-points as stored as the other operand (every column gets
+// the same sum, so each lane finds it next to its own token's result).
+#include "squat_internal.h"
+
+using namespace squat;
+
+namespace {
+
+constexpr int kPcDepth = 3;            // token groups whose loads are in flight per wavefront
+constexpr int kPcWaves = 4;
+constexpr int kPcTilesPerWave = 16;    // token groups a wavefront aims at (amortises its set-up) ...
+constexpr int kPcMinTilesPerWave = 2;  // ... unless the sequence is short
+#define PC_LOAD(p) __builtin_nontemporal_load(p)
+
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+struct ScorePcParams {
+    const uint32_t* codes;
+    const uint16_t* scale;
+    const uint16_t* zero;
+    const unsigned char* q;
+    int q_dt;
+    int64_t qsb, qsh;                // query strides in ELEMENTS
+    float* scores;
+    int64_t ssb, ssh;                // score strides in elements
+    int n_tiles;                     // token groups per (batch, KV head) to read
+    int64_t store_tiles;             // token groups per (batch, KV head) in the store (>= n_tiles)
+    int n_kv_heads;
+    int qpk;
+    float out_scale;
+    int tiles_per_wave;
+};
+
+__device__ __forceinline__ uint32_t pack2(_Float16 lo, _Float16 hi) {
+    return static_cast<uint32_t>(__builtin_bit_cast(uint16_t, lo)) |
+           (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
+    const uint32_t o = static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+    return v > o ? v : o;
+}
+
+// grid: x over slabs of kPcWaves * tiles_per_wave token groups, y / z over (batch, KV head)
+template <int BITS, int QDT>
+__global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const ScorePcParams p) {
+    constexpr int W = BITS;                               // packed words per channel and token group
+    constexpr int TH = 16 / BITS;                         // tokens per 16-bit half of a word: 8 or 4
+    constexpr uint32_t MASK = BITS == 2 ? 0x00C000C0u : 0x03C003C0u;   // a code at bits 6.. of both halves
+    // LDS tile of one wavefront: region k = word k of every channel (128 words; 32 spare bytes shift the
+    // banks of consecutive regions), then the scales and the zero-points as stored
+    constexpr int RSTRIDE = 512 + 32;
+    constexpr int SOFF = W * RSTRIDE, ZOFF = SOFF + 256, TILE = ZOFF + 256;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int kb = lane >> 4;                             // K block of an operand / row block of the result
+    const int col = lane & 15;                            // operand row (A) or column (B, result)
+    const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
+    const int64_t b = bh / p.n_kv_heads;
+    const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
+
+    // ---- the KV head's queries -> LDS as fp32, rows past q_per_kv zero
+    constexpr int QLD = kD + 1;
+    __shared__ float qlds[8 * QLD];
+    {
+        const int e0 = 4 * static_cast<int>(threadIdx.x);
+        const int qrow = e0 / kD, qch = e0 % kD;
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (qrow < p.qpk) {
+            const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
+            if constexpr (QDT == SQUAT_F32) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
+                v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+            } else {
+                const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
+                    v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
+                                             : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qlds[qrow * QLD + qch + i] = v[i];
+    }
+    __syncthreads();
+
+    // ---- power of two that brings max |q| of this KV head into [1, 2)
+    float qmax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int e = lane + 64 * i;
+        qmax = fmaxf(qmax, fabsf(qlds[(e / kD) * QLD + (e % kD)]));
+    }
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) qmax = fmaxf(qmax, __shfl_xor(qmax, s, 64));
+    uint32_t eb = as_u32(qmax) >> 23;
+    eb = eb < 1u ? 1u : (eb > 253u ? 253u : eb);
+    const float inv_q = as_f32((254u - eb) << 23);        // 2^-(eb - 127)
+    const float fin = p.out_scale * as_f32(eb << 23);     // out_scale * 2^(eb - 127)
+
+    // ---- constant query-side registers: row `col` = (query head col / 2, part col % 2); register r of
+    // chunk g holds K = 8 kb + 2 r + {0, 1}  <->  channels 32 g + 8 kb + 2 r + {0, 1}
+    const int qh = col >> 1, part = col & 1;
+    // The operand register of a row is  fma(q_hi, Delta, -sub)  with sub = rn(q_sub Delta): high rows keep
+    // q_sub = 0 (the result is rn(q_hi Delta)), low rows q_sub = q_hi (the result is the exact remainder),
+    // so both kinds of row run the same two instructions.
+    half2v qhi[4][4];
+    half2v qsub[4][4];
+    half2v qlo[4][4];                                     // fp32 queries only: low part (low rows), else 0
+    uint32_t azp[4][4];                                   // operand of the zero-point product
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int c = 32 * g + 8 * kb + 2 * r;
+            const float v0 = qlds[qh * QLD + c] * inv_q, v1 = qlds[qh * QLD + c + 1] * inv_q;
+            const _Float16 h0 = static_cast<_Float16>(v0), h1 = static_cast<_Float16>(v1);
+            const _Float16 l0 = static_cast<_Float16>(v0 - static_cast<float>(h0));
+            const _Float16 l1 = static_cast<_Float16>(v1 - static_cast<float>(h1));
+            const _Float16 zh = static_cast<_Float16>(0.0f);
+            qhi[g][r] = half2v{h0, h1};
+            qsub[g][r] = part == 0 ? half2v{zh, zh} : half2v{h0, h1};
+            qlo[g][r] = part == 0 ? half2v{zh, zh} : half2v{l0, l1};
+            azp[g][r] = part == 0 ? pack2(h0, h1) : pack2(l0, l1);
+        }
+
+    // ---- this wavefront's token groups
+    const int t0 = (static_cast<int>(blockIdx.x) * kPcWaves + wave) * p.tiles_per_wave;
+    const int t1 = min(t0 + p.tiles_per_wave, p.n_tiles);
+    if (t0 >= t1) return;                                 // after the last workgroup barrier
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[kPcWaves * TILE];
+    unsigned char* lds = lds_all + wave * TILE;
+    const int64_t tile0 = bh * p.store_tiles;
+    // loads: lane L fetches the words of channels 2 L and 2 L + 1 (16 or 32 contiguous bytes) and four
+    // scales (lanes 0..31) or zero-points (lanes 32..63) of the token group
+    const uint32_t* c_base = p.codes + tile0 * (kD * W) + lane * (2 * W);
+    const uint16_t* m_base = (lane < 32 ? p.scale : p.zero) + tile0 * kD + 4 * (lane & 31);
+    struct Raw {
+        u32x4 c[BITS / 2];
+        u32x2 m;
+    };
+    auto fetch = [&](int t, Raw& r) {
+        const uint32_t tt = static_cast<uint32_t>(t);
+#pragma unroll
+        for (int i = 0; i < BITS / 2; ++i)
+            r.c[i] = PC_LOAD(reinterpret_cast<const u32x4*>(c_base + tt * (kD * W) + 4 * i));
+        r.m = PC_LOAD(reinterpret_cast<const u32x2*>(m_base + tt * kD));
+    };
+
+    const int wsel = col / TH, j = col % TH;              // this lane's word and token position in a half
+    const uint32_t rot = static_cast<uint32_t>(BITS * j - 6) & 31u;      // right-rotation: code -> bits 6..
+    const int tokA = (32 / W) * wsel + j;                 // token of the first product's column, second: + TH
+    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
+    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    const unsigned char* rd_codes = lds + wsel * RSTRIDE + 32 * kb;
+    const unsigned char* rd_meta = lds + SOFF + 16 * kb;
+
+    auto compute = [&](int t, const Raw& raw) {
+        // registers -> LDS tile
+        if constexpr (BITS == 2) {
+            *reinterpret_cast<u32x2*>(lds + 8 * lane) = u32x2{raw.c[0][0], raw.c[0][2]};
+            *reinterpret_cast<u32x2*>(lds + RSTRIDE + 8 * lane) = u32x2{raw.c[0][1], raw.c[0][3]};
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<u32x2*>(lds + k * RSTRIDE + 8 * lane) = u32x2{raw.c[0][k], raw.c[BITS / 2 - 1][k]};
+        }
+        *reinterpret_cast<u32x2*>(lds + SOFF + 8 * lane) = raw.m;          // lanes 32..63 land at ZOFF
+        // largest Delta of the token group (fp16 patterns of non-negative numbers order like integers)
+        uint32_t mx = 0u;
+        if (lane < 32) {
+            const uint32_t a = raw.m[0] & 0x7FFF7FFFu, c = raw.m[1] & 0x7FFF7FFFu;
+            const uint32_t ma = max(a & 0xFFFFu, a >> 16), mc = max(c & 0xFFFFu, c >> 16);
+            mx = max(ma, mc);
+        }
+        mx = dpp_max<0xB1>(mx);                           // quad_perm [1,0,3,2]
+        mx = dpp_max<0x4E>(mx);                           // quad_perm [2,3,0,1]
+        mx = dpp_max<0x141>(mx);                          // row_half_mirror
+        mx = dpp_max<0x140>(mx);                          // row_mirror
+        const uint32_t m0 = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(mx), 0));
+        const uint32_t m1 = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(mx), 16));
+        const int eD = static_cast<int>(max(m0, m1) >> 10);                // exponent field 0 .. 31
+        int field = 30 - eD;                              // Delta * 2^(field - 15) < 2 (< 4 if eD = 30)
+        field = field < 1 ? 1 : field;
+        const uint32_t sp = static_cast<uint32_t>(field) << 10;
+        const half2v spack = __builtin_bit_cast(half2v, sp | (sp << 16));
+        const float descale = as_f32(static_cast<uint32_t>(127 + 33 - field) << 23);   // 2^18 * 2^(15 - field)
+
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        f32x4v accA = {0.0f, 0.0f, 0.0f, 0.0f}, accB = accA, zacc = accA;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const u32x4 sc = *reinterpret_cast<const u32x4*>(rd_meta + 64 * g);
+            const u32x4 zm = *reinterpret_cast<const u32x4*>(rd_meta + 256 + 64 * g);
+            const u32x4 wlo = *reinterpret_cast<const u32x4*>(rd_codes + 128 * g);
+            const u32x4 whi = *reinterpret_cast<const u32x4*>(rd_codes + 128 * g + 16);
+            const uint32_t w[8] = {wlo[0], wlo[1], wlo[2], wlo[3], whi[0], whi[1], whi[2], whi[3]};
+            u32x4 aop, bopA, bopB;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // (bit-casting the vector ELEMENT expression directly makes this compiler read element 0)
+                const uint32_t sraw = sc[r];
+                const half2v dl = __builtin_bit_cast(half2v, sraw) * spack;
+                const half2v sub = qsub[g][r] * dl;
+                half2v a = __builtin_elementwise_fma(qhi[g][r], dl, -sub);
+                if constexpr (QDT == SQUAT_F32) a = __builtin_elementwise_fma(qlo[g][r], dl, a);
+                aop[r] = __builtin_bit_cast(uint32_t, a);
+                // low / high halves of the words of channels 2 r, 2 r + 1: tokens j / TH + j of the word
+                const uint32_t pl = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x05040100u);
+                const uint32_t ph = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x07060302u);
+                bopA[r] = __builtin_amdgcn_alignbit(pl, pl, rot) & MASK;
+                bopB[r] = __builtin_amdgcn_alignbit(ph, ph, rot) & MASK;
+            }
+            accA = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop), __builtin_bit_cast(half8, bopA),
+                                                          accA, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop), __builtin_bit_cast(half8, bopB),
+                                                          accB, 0, 0, 0);
+            const u32x4 az = {azp[g][0], azp[g][1], azp[g][2], azp[g][3]};
+            zacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, az), __builtin_bit_cast(half8, zm),
+                                                          zacc, 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
+        const float z0 = zacc[0] + zacc[1], z1 = zacc[2] + zacc[3];
+        const int64_t tok = static_cast<int64_t>(t) * 32 + tokA;
+        if (st0) {
+            __builtin_nontemporal_store(fin * fmaf(descale, accA[0] + accA[1], z0), out0 + tok);
+            __builtin_nontemporal_store(fin * fmaf(descale, accB[0] + accB[1], z0), out0 + tok + TH);
+        }
+        if (st1) {
+            __builtin_nontemporal_store(fin * fmaf(descale, accA[2] + accA[3], z1), out0 + p.ssh + tok);
+            __builtin_nontemporal_store(fin * fmaf(descale, accB[2] + accB[3], z1), out0 + p.ssh + tok + TH);
+        }
+    };
+
+    // software pipeline: the loads of kPcDepth token groups are in flight while one is being computed
+    Raw ring[kPcDepth];
+#pragma unroll
+    for (int i = 0; i < kPcDepth; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
+    for (int t = t0; t < t1; t += kPcDepth) {
+#pragma unroll
+        for (int i = 0; i < kPcDepth; ++i) {
+            const Raw cur = ring[i];
+            fetch(min(t + i + kPcDepth, t1 - 1), ring[i]);
+            if (t + i < t1) compute(t + i, cur);
+        }
+    }
+}
+
+template <int BITS>
+int launch_dt(const ScorePcParams& p, dim3 grid, hipStream_t s) {
+    const dim3 block(kPcWaves * kWave);
+    switch (p.q_dt) {
+        case SQUAT_F32: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_F32>), grid, block, 0, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_F16>), grid, block, 0, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_BF16>), grid, block, 0, s, p); break;
+        default: return SQUAT_E_BADDTYPE;
+    }
+    return check_launch();
+}
+
+}  // namespace
+
+// squat_key_scores_per_channel over the first n_tokens tokens of a store that holds store_tokens tokens
+// (a multiple of 32) per (batch, KV head).
+int squat::key_scores_pc_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                              int n_kv_heads, int64_t n_tokens, int64_t store_tokens, int d, int bits, int group,
+                              const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                              int64_t q_stride_head, float out_scale, float* scores, int64_t s_stride_batch,
+                              int64_t s_stride_head, squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != 32) return SQUAT_E_BADSHAPE;
+    if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0 || n_tokens >= (int64_t(1) << 25)) return SQUAT_E_BADSHAPE;
+    if ((n_tokens % 32) || (store_tokens % 32) || store_tokens < n_tokens) return SQUAT_E_BADSHAPE;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (!(out_scale == out_scale)) return SQUAT_E_BADVALUE;
+    if (n_batch == 0 || n_kv_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!codes || !scale || !zero || !q || !scores) return SQUAT_E_NULLPTR;
+    if (q_stride_head < d || q_stride_batch < 0 || s_stride_head < n_tokens || s_stride_batch < 0) return SQUAT_E_BADSHAPE;
+    if ((q_stride_head % 8) || (q_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(codes, 16) || !aligned(scale, 16) || !aligned(zero, 16) || !aligned(scores, 4) || !aligned(q, 16))
+        return SQUAT_E_ALIGN;
+
+    ScorePcParams p;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.q = static_cast<const unsigned char*>(q);
+    p.q_dt = static_cast<int>(q_dt);
+    p.qsb = q_stride_batch;
+    p.qsh = q_stride_head;
+    p.scores = scores;
+    p.ssb = s_stride_batch;
+    p.ssh = s_stride_head;
+    p.n_tiles = static_cast<int>(n_tokens / 32);
+    p.store_tiles = store_tokens / 32;
+    p.n_kv_heads = n_kv_heads;
+    p.qpk = q_per_kv;
+    p.out_scale = out_scale;
+
+    // workgroups along the sequence: about kPcWaves * kPcTilesPerWave token groups each, spread evenly
+    const int64_t n_tiles = p.n_tiles;
+    const int64_t slab = static_cast<int64_t>(kPcWaves) * kPcTilesPerWave;
+    int64_t gx = (n_tiles + slab / 2) / slab;
+    if (gx < 1) gx = 1;
+    int64_t tpw = (n_tiles + kPcWaves * gx - 1) / (kPcWaves * gx);
+    if (tpw < kPcMinTilesPerWave) tpw = kPcMinTilesPerWave;
+    p.tiles_per_wave = static_cast<int>(tpw);
+    gx = (n_tiles + kPcWaves * tpw - 1) / (kPcWaves * tpw);
+    const int64_t bh = n_batch * n_kv_heads;
+    int64_t gy = bh, gz = 1;
+    if (gy > 65535) {
+        gy = 0;
+        for (int64_t cand = 65535; cand >= 1; --cand)
+            if (bh % cand == 0) { gy = cand; break; }
+        gz = bh / gy;
+    }
+    if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? launch_dt<2>(p, grid, s) : launch_dt<4>(p, grid, s);
+}
+
+extern "C" int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                            int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits,
+                                            int group, const void* q, squat_dtype q_dt, int q_per_kv,
+                                            int64_t q_stride_batch, int64_t q_stride_head, float out_scale,
+                                            float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                                            squat_stream stream) {
+    return squat::key_scores_pc_from(codes, scale, zero, n_batch, n_kv_heads, n_tokens, n_tokens, d, bits, group, q,
+                                     q_dt, q_per_kv, q_stride_batch, q_stride_head, out_scale, scores,
+                                     s_stride_batch, s_stride_head, stream);
+}

@@ -20,7 +20,7 @@ _lib = None
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
            "squat_quantize_keys", "squat_dequantize_keys",
-           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores",
+           "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel",
            "squat_cache_arena_bytes", "squat_cache_create", "squat_cache_destroy", "squat_cache_reset",
            "squat_cache_state", "squat_cache_get_buffers", "squat_cache_prefill", "squat_cache_append",
            "squat_cache_key_scores")
@@ -103,6 +103,8 @@ def lib() -> ctypes.CDLL:
     L.squat_cache_prefill.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp]
     L.squat_cache_append.restype = i32
     L.squat_cache_append.argtypes = [vp, vp, vp, i64, i64, vp]
+    L.squat_key_scores_per_channel.restype = i32
+    L.squat_key_scores_per_channel.argtypes = list(L.squat_key_scores.argtypes)
     L.squat_cache_key_scores.restype = i32
     L.squat_cache_key_scores.argtypes = [vp, vp, i32, i64, i64, f32, vp, i64, i64, vp]
     _lib = L
@@ -309,6 +311,31 @@ def key_scores(q: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, zero: 
                                 out.stride(1), _stream(stream))
     if rc:
         raise SquatError(rc, "squat_key_scores")
+    return out
+
+
+def key_scores_per_channel(q: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor, bits: int,
+                           q_per_kv: int, out_scale: float = 1.0, out=None, stream=None) -> torch.Tensor:
+    """squat_key_scores_per_channel.  q: [B, n_kv_heads*q_per_kv, d]; codes [B, H, n/32, d, bits] int32,
+    scale/zero [B, H, n/32, d] float16 as written by quantize_keys_per_channel.  Returns float32
+    [B, n_kv_heads*q_per_kv, n] (or fills `out`)."""
+    b, h, tiles, d, nw = codes.shape
+    n = tiles * 32
+    if nw != bits or scale.shape != (b, h, tiles, d) or zero.shape != scale.shape:
+        raise ValueError("codes [B,H,n/32,d,bits], scale/zero [B,H,n/32,d] expected")
+    if q.dim() != 3 or q.shape[0] != b or q.shape[1] != h * q_per_kv or q.shape[2] != d or q.stride(2) != 1:
+        raise ValueError("q must be [B, n_kv_heads*q_per_kv, d] with unit channel stride")
+    if not (codes.is_contiguous() and scale.is_contiguous() and zero.is_contiguous()):
+        raise ValueError("codes/scale/zero must be dense")
+    if out is None:
+        out = torch.empty((b, h * q_per_kv, n), dtype=torch.float32, device=codes.device)
+    if out.dtype != torch.float32 or out.stride(2) != 1 or out.shape[0] != b or out.shape[1] != h * q_per_kv:
+        raise ValueError("out must be float32 [B, n_q_heads, >= n] with unit token stride")
+    rc = lib().squat_key_scores_per_channel(_ptr(codes), _ptr(scale), _ptr(zero), b, h, n, d, bits, 32, _ptr(q),
+                                            _DT[q.dtype], q_per_kv, q.stride(0), q.stride(1), float(out_scale),
+                                            _ptr(out), out.stride(0), out.stride(1), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_key_scores_per_channel")
     return out
 
 
