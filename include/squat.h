@@ -334,11 +334,18 @@ typedef struct squat_cache_config {
     int64_t max_tokens;   /* capacity of the quantized stores per sequence; multiple of residual, < 2^25 */
     squat_dtype kv_dtype; /* dtype of incoming keys / values and of the residual buffers */
     int quantize_values;  /* 0: keys only */
+    int key_per_channel;  /* 0: keys grouped per token (squat_quantize_keys, `group` channels per group);
+                             1: keys grouped per channel over 32 tokens as Algorithm 1 prints it
+                             (squat_quantize_keys_per_channel; residual must be a multiple of 32, the
+                             key stores then have the per-channel layout and `group` applies to the
+                             values only) */
 } squat_cache_config;
 
 typedef struct squat_cache_buffers {   /* device pointers inside the arena */
-    uint32_t* key_codes;      /* [n_batch, n_kv_heads, max_tokens, d*bits/32] */
-    uint16_t* key_scale;      /* [n_batch, n_kv_heads, max_tokens, d/group]   */
+    uint32_t* key_codes;      /* [n_batch, n_kv_heads, max_tokens, d*bits/32]; per-channel keys:
+                                 [n_batch, n_kv_heads, max_tokens/32, d, bits] */
+    uint16_t* key_scale;      /* [n_batch, n_kv_heads, max_tokens, d/group]; per-channel keys:
+                                 [n_batch, n_kv_heads, max_tokens/32, d] */
     uint16_t* key_zero;
     void* key_residual;       /* [n_batch, n_kv_heads, residual, d] kv_dtype; slots 0 .. keys_residual-1 in use */
     uint32_t* value_codes;    /* same shapes; NULL without values */

@@ -396,23 +396,37 @@ class CacheOracle:
     keys; decoding: append, and when the buffer holds R keys quantize all of them
     and empty it), plus the value rule of the appendix "Details of Our Main
     Algorithm" (values per token, the most recent R in full precision, the oldest
-    one quantized when token R + 1 arrives).  Keys use per-token groups (this
-    build's contract), so a flush of R keys is R independent runs of
-    `quantize_keys`.
+    one quantized when token R + 1 arrives).  key_axis="token": keys use
+    per-token groups of G channels (this build's contract), so a flush of R keys
+    is R independent runs of `quantize_keys`; key_axis="channel": the grouping
+    Algorithm 1 prints, a flush is R / 32 groups of 32 tokens quantized per
+    channel (G then applies to the values only).
     """
 
-    def __init__(self, U, bits: int, G: int, g: int, R: int, values: bool = False):
+    def __init__(self, U, bits: int, G: int, g: int, R: int, values: bool = False, key_axis: str = "token"):
         self.U, self.bits, self.G, self.g, self.R, self.values = U, bits, G, g, R, values
-        self.k_codes, self.k_scale, self.k_zero = [], [], []      # one entry per quantized key
+        self.key_axis = key_axis
+        if key_axis == "channel" and R % 32:
+            raise ValueError("per-channel keys are flushed in whole groups of 32 tokens")
+        # codes: one entry per quantized key; scale / zero: one entry per key (token axis) or per group
+        # of 32 keys (channel axis)
+        self.k_codes, self.k_scale, self.k_zero = [], [], []
         self.k_full = []                                           # residual keys, oldest first
         self.v_codes, self.v_scale, self.v_zero = [], [], []
         self.v_full = []                                           # residual values, oldest first
         self.n_tokens = 0
 
     def _quant_keys(self, rows):
-        out = quantize_keys(np.asarray(rows, dtype=np.float64), self.U, self.bits, self.G, self.g)
+        rows = np.asarray(rows, dtype=np.float64)
+        if self.key_axis == "channel":
+            out = quantize_keys(rows, self.U, self.bits, 32, self.g, axis="channel")
+            n_meta = len(rows) // 32
+        else:
+            out = quantize_keys(rows, self.U, self.bits, self.G, self.g)
+            n_meta = len(rows)
         for i in range(len(rows)):
             self.k_codes.append(out["codes"][i])
+        for i in range(n_meta):
             self.k_scale.append(out["scale"][i])
             self.k_zero.append(out["zero"][i])
 
@@ -455,7 +469,7 @@ class CacheOracle:
         parts = []
         if self.k_codes:
             parts.append(key_scores(q, np.stack(self.k_codes), np.stack(self.k_scale), np.stack(self.k_zero),
-                                    self.G, out_scale))
+                                    32 if self.key_axis == "channel" else self.G, out_scale, axis=self.key_axis))
         if self.k_full:
             parts.append(float(out_scale) * (q @ np.stack(self.k_full).T))
         return np.concatenate(parts, axis=1) if parts else np.zeros((q.shape[0], 0))

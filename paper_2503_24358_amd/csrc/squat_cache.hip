@@ -11,6 +11,11 @@
 // quantized.  Logits: squat_key_scores over the quantized tokens plus plain dot
 // products over the residual ones.
 //
+// key_per_channel selects the grouping Algorithm 1 prints for the keys: every
+// flush of R = 32 tokens is one token group quantized per channel
+// (squat_quantize_keys_per_channel / squat_key_scores_per_channel); otherwise
+// keys are grouped per token (squat_quantize_keys / squat_key_scores).
+//
 // The object itself is host memory (counters and pointers); every device byte
 // lives in one arena the caller provides.  Calls enqueue work on the given
 // stream and update the counters at enqueue time: one stream, one host thread
@@ -47,11 +52,12 @@ bool config_ok(const squat_cache_config* c) {
     if (c->residual < 1 || c->residual > 1024) return false;
     if (c->max_tokens < c->residual || c->max_tokens % c->residual || c->max_tokens >= (int64_t(1) << 25)) return false;
     if (c->kv_dtype != SQUAT_F32 && c->kv_dtype != SQUAT_F16 && c->kv_dtype != SQUAT_BF16) return false;
+    if (c->key_per_channel && (c->residual % kTileTokens)) return false;      // whole token groups per flush
     return true;
 }
 
 struct Layout {
-    size_t codes, meta, res, total;
+    size_t codes, meta, kmeta, res, total;
     size_t off_kc, off_ks, off_kz, off_kr, off_vc, off_vs, off_vz, off_vr;
 };
 
@@ -60,11 +66,13 @@ Layout layout(const squat_cache_config& c) {
     const size_t bh = static_cast<size_t>(c.n_batch) * c.n_kv_heads;
     l.codes = align_up(bh * c.max_tokens * (c.d * c.bits / 8));
     l.meta = align_up(bh * c.max_tokens * (c.d / c.group) * 2);
+    // per-channel keys: d scales per group of 32 tokens = 4 per token
+    l.kmeta = c.key_per_channel ? align_up(bh * c.max_tokens * (c.d / kTileTokens) * 2) : l.meta;
     l.res = align_up(bh * c.residual * c.d * elem_size(c.kv_dtype));
     size_t o = 0;
     l.off_kc = o; o += l.codes;
-    l.off_ks = o; o += l.meta;
-    l.off_kz = o; o += l.meta;
+    l.off_ks = o; o += l.kmeta;
+    l.off_kz = o; o += l.kmeta;
     l.off_kr = o; o += l.res;
     l.off_vc = l.off_vs = l.off_vz = l.off_vr = 0;
     if (c.quantize_values) {
@@ -259,9 +267,13 @@ extern "C" int squat_cache_prefill(squat_cache* c, const void* k, const void* v,
     const int64_t vq = n_tokens - vres;
     if (kq > f.max_tokens || vq > f.max_tokens) return SQUAT_E_BADSHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc = quantize_keys_into(k, f.kv_dtype, f.n_batch, f.n_kv_heads, kq, f.d, stride_batch, stride_head,
-                                stride_token, c->update, 0, f.bits, f.group, f.g, c->buf.key_codes,
-                                c->buf.key_scale, c->buf.key_zero, f.max_tokens, 0, stream);
+    int rc = f.key_per_channel
+                 ? quantize_keys_pc_into(k, f.kv_dtype, f.n_batch, f.n_kv_heads, kq, f.d, stride_batch, stride_head,
+                                         stride_token, c->update, 0, f.bits, kTileTokens, f.g, c->buf.key_codes,
+                                         c->buf.key_scale, c->buf.key_zero, f.max_tokens, 0, stream)
+                 : quantize_keys_into(k, f.kv_dtype, f.n_batch, f.n_kv_heads, kq, f.d, stride_batch, stride_head,
+                                      stride_token, c->update, 0, f.bits, f.group, f.g, c->buf.key_codes,
+                                      c->buf.key_scale, c->buf.key_zero, f.max_tokens, 0, stream);
     if (rc) return rc;
     rc = copy_tokens(c, k, stride_batch, stride_head, stride_token, kq, c->buf.key_residual, 0, kres, s);
     if (rc) return rc;
@@ -300,10 +312,14 @@ extern "C" int squat_cache_append(squat_cache* c, const void* k, const void* v, 
     int rc = copy_tokens(c, k, stride_batch, stride_head, f.d, 0, c->buf.key_residual, c->n_kres, 1, s);
     if (rc) return rc;
     if (flush) {
-        rc = quantize_keys_into(c->buf.key_residual, f.kv_dtype, f.n_batch, f.n_kv_heads, R, f.d,
-                                static_cast<int64_t>(f.n_kv_heads) * R * f.d, static_cast<int64_t>(R) * f.d, f.d,
-                                c->update, 0, f.bits, f.group, f.g, c->buf.key_codes, c->buf.key_scale,
-                                c->buf.key_zero, f.max_tokens, c->n_kq, stream);
+        const int64_t rsb = static_cast<int64_t>(f.n_kv_heads) * R * f.d, rsh = static_cast<int64_t>(R) * f.d;
+        rc = f.key_per_channel
+                 ? quantize_keys_pc_into(c->buf.key_residual, f.kv_dtype, f.n_batch, f.n_kv_heads, R, f.d, rsb, rsh,
+                                         f.d, c->update, 0, f.bits, kTileTokens, f.g, c->buf.key_codes,
+                                         c->buf.key_scale, c->buf.key_zero, f.max_tokens, c->n_kq, stream)
+                 : quantize_keys_into(c->buf.key_residual, f.kv_dtype, f.n_batch, f.n_kv_heads, R, f.d, rsb, rsh, f.d,
+                                      c->update, 0, f.bits, f.group, f.g, c->buf.key_codes, c->buf.key_scale,
+                                      c->buf.key_zero, f.max_tokens, c->n_kq, stream);
         if (rc) return rc;
     }
     if (f.quantize_values) {
@@ -348,9 +364,14 @@ extern "C" int squat_cache_key_scores(const squat_cache* c, const void* q, squat
     if (s_stride_head < c->n_kq + c->n_kres || s_stride_batch < 0 || q_stride_head < f.d || q_stride_batch < 0)
         return SQUAT_E_BADSHAPE;
     if ((q_stride_head % 8) || (q_stride_batch % 8) || !aligned(q, 16) || !aligned(scores, 4)) return SQUAT_E_ALIGN;
-    int rc = key_scores_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch, f.n_kv_heads, c->n_kq,
-                             f.max_tokens, f.d, f.bits, f.group, q, q_dt, f.q_per_kv, q_stride_batch, q_stride_head,
-                             out_scale, scores, s_stride_batch, s_stride_head, stream);
+    int rc = f.key_per_channel
+                 ? key_scores_pc_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch, f.n_kv_heads,
+                                      c->n_kq, f.max_tokens, f.d, f.bits, kTileTokens, q, q_dt, f.q_per_kv,
+                                      q_stride_batch, q_stride_head, out_scale, scores, s_stride_batch,
+                                      s_stride_head, stream)
+                 : key_scores_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch, f.n_kv_heads,
+                                   c->n_kq, f.max_tokens, f.d, f.bits, f.group, q, q_dt, f.q_per_kv, q_stride_batch,
+                                   q_stride_head, out_scale, scores, s_stride_batch, s_stride_head, stream);
     if (rc) return rc;
     if (c->n_kres == 0) return SQUAT_OK;
     const int64_t total = f.n_batch * f.n_kv_heads * static_cast<int64_t>(f.q_per_kv) * c->n_kres;

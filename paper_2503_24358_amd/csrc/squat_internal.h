@@ -101,6 +101,10 @@ int quantize_keys_into(const void* k, squat_dtype k_dt, int64_t n_batch, int n_h
                        int64_t k_stride_batch, int64_t k_stride_head, int64_t k_stride_token, const float* update,
                        int64_t update_stride_batch, int bits, int group, int g, uint32_t* codes, uint16_t* scale,
                        uint16_t* zero, int64_t out_stride, int64_t out_offset, squat_stream stream);
+int quantize_keys_pc_into(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens, int d,
+                          int64_t k_stride_batch, int64_t k_stride_head, int64_t k_stride_token, const float* update,
+                          int64_t update_stride_batch, int bits, int group, int g, uint32_t* codes, uint16_t* scale,
+                          uint16_t* zero, int64_t out_stride, int64_t out_offset, squat_stream stream);
 int key_scores_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
                     int n_kv_heads, int64_t n_tokens, int64_t store_stride, int d, int bits, int group,
                     const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head,

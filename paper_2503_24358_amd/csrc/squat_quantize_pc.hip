@@ -57,6 +57,7 @@ struct PcParams {
     int64_t n_inner;                 // batch entries that share one update matrix
     int n_heads;
     int64_t tiles_per_seq;
+    int64_t out_tiles, out_tile0;    // token groups per (batch, head) in the output store, first one written
     int64_t units_per_prob;          // n_inner * tiles_per_seq, < 2^31
     int wgs_per_prob;
     uint32_t div_mul;                // unit / tiles_per_seq == (unit * div_mul) >> div_shift for unit < 2^31
@@ -422,7 +423,7 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
         // ---- outputs
         uint32_t bi, tile;
         locate(cur, bi, tile);
-        const int64_t gt = ((bo + bi) * p.n_heads + head) * p.tiles_per_seq + tile;     // wave-uniform
+        const int64_t gt = ((bo + bi) * p.n_heads + head) * p.out_tiles + p.out_tile0 + tile;     // wave-uniform
         // codes[tile][channel][BITS words]: this lane's 16 tokens are words hh * WPT .. of its channel
         uint32_t* cdst = p.codes + gt * (kD * BITS) + n * BITS + hh * WPT;
 #pragma unroll
@@ -486,13 +487,16 @@ int dispatch_bt(int bt, squat_dtype dt, const PcParams& p, int64_t n_prob, hipSt
 
 }  // namespace
 
-extern "C" int squat_quantize_keys_per_channel(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
-                                               int64_t n_tokens, int d, int64_t k_stride_batch,
-                                               int64_t k_stride_head, int64_t k_stride_token,
-                                               const float* update, int64_t update_stride_batch, int bits,
-                                               int group, int g, uint32_t* codes, uint16_t* scale,
-                                               uint16_t* zero, squat_stream stream) {
+// squat_quantize_keys_per_channel into a store that holds out_stride tokens per (batch, head), starting at
+// token out_offset (both multiples of 32).
+int squat::quantize_keys_pc_into(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens,
+                                 int d, int64_t k_stride_batch, int64_t k_stride_head, int64_t k_stride_token,
+                                 const float* update, int64_t update_stride_batch, int bits, int group, int g,
+                                 uint32_t* codes, uint16_t* scale, uint16_t* zero, int64_t out_stride,
+                                 int64_t out_offset, squat_stream stream) {
     if (d != kD) return SQUAT_E_BADSHAPE;
+    if (out_stride % kTileTokens || out_offset % kTileTokens || out_offset < 0 || out_offset + n_tokens > out_stride)
+        return SQUAT_E_BADSHAPE;
     if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
     if (group != kTileTokens) return SQUAT_E_BADSHAPE;
     if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
@@ -521,6 +525,8 @@ extern "C" int squat_quantize_keys_per_channel(const void* k, squat_dtype k_dt, 
     p.zero = zero;
     p.n_heads = n_heads;
     p.tiles_per_seq = n_tokens / kTileTokens;
+    p.out_tiles = out_stride / kTileTokens;
+    p.out_tile0 = out_offset / kTileTokens;
 
     // Workgroups are bound to one update matrix: per head when it is shared across the
     // batch, per (batch, head) otherwise.
@@ -555,4 +561,15 @@ extern "C" int squat_quantize_keys_per_channel(const void* k, squat_dtype k_dt, 
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? dispatch_bt<2>(bt, k_dt, p, n_prob, s) : dispatch_bt<4>(bt, k_dt, p, n_prob, s);
+}
+
+extern "C" int squat_quantize_keys_per_channel(const void* k, squat_dtype k_dt, int64_t n_batch, int n_heads,
+                                               int64_t n_tokens, int d, int64_t k_stride_batch,
+                                               int64_t k_stride_head, int64_t k_stride_token,
+                                               const float* update, int64_t update_stride_batch, int bits,
+                                               int group, int g, uint32_t* codes, uint16_t* scale,
+                                               uint16_t* zero, squat_stream stream) {
+    return squat::quantize_keys_pc_into(k, k_dt, n_batch, n_heads, n_tokens, d, k_stride_batch, k_stride_head,
+                                        k_stride_token, update, update_stride_batch, bits, group, g, codes, scale,
+                                        zero, n_tokens < 0 ? 0 : n_tokens, 0, stream);
 }

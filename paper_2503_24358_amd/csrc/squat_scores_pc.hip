@@ -30,7 +30,7 @@ using namespace squat;
 
 namespace {
 
-constexpr int kPcDepth = 3;            // token groups whose loads are in flight per wavefront
+constexpr int kPcDepth = 2;            // token groups whose loads are in flight per wavefront
 constexpr int kPcWaves = 4;
 constexpr int kPcTilesPerWave = 16;    // token groups a wavefront aims at (amortises its set-up) ...
 constexpr int kPcMinTilesPerWave = 2;  // ... unless the sequence is short
@@ -67,16 +67,21 @@ __device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
     return v > o ? v : o;
 }
 
-// grid: x over slabs of kPcWaves * tiles_per_wave token groups, y / z over (batch, KV head)
-template <int BITS, int QDT>
+// grid: x over slabs of kPcWaves * tiles_per_wave token groups, y / z over (batch, KV head).
+// NT = token groups per step.  With at most four query heads per KV head only 8 of the 16 operand rows
+// are in use, so NT = 2 gives rows 0..7 to one token group and rows 8..15 to the next one (same queries,
+// the other group's scales): the instructions that build the query-side operand then serve two groups,
+// and lanes of K blocks 0, 1 find the first group's results in their registers, K blocks 2, 3 the second's.
+template <int BITS, int QDT, int NT>
 __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const ScorePcParams p) {
     constexpr int W = BITS;                               // packed words per channel and token group
     constexpr int TH = 16 / BITS;                         // tokens per 16-bit half of a word: 8 or 4
     constexpr uint32_t MASK = BITS == 2 ? 0x00C000C0u : 0x03C003C0u;   // a code at bits 6.. of both halves
-    // LDS tile of one wavefront: region k = word k of every channel (128 words; 32 spare bytes shift the
-    // banks of consecutive regions), then the scales and the zero-points as stored
+    // LDS tile of one wavefront: region (i, k) = word k of every channel of group i (128 words; 32 spare
+    // bytes shift the banks of consecutive regions), then scales of group 0 (, 1), zero-points of group 0 (, 1)
     constexpr int RSTRIDE = 512 + 32;
-    constexpr int SOFF = W * RSTRIDE, ZOFF = SOFF + 256, TILE = ZOFF + 256;
+    constexpr int META = NT * W * RSTRIDE, ZOFF = NT * 256, TILE = META + 2 * NT * 256;
+    constexpr int ML = 2 * NT;                            // metadata dwords a lane loads
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -127,16 +132,17 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     const float inv_q = as_f32((254u - eb) << 23);        // 2^-(eb - 127)
     const float fin = p.out_scale * as_f32(eb << 23);     // out_scale * 2^(eb - 127)
 
-    // ---- constant query-side registers: row `col` = (query head col / 2, part col % 2); register r of
-    // chunk g holds K = 8 kb + 2 r + {0, 1}  <->  channels 32 g + 8 kb + 2 r + {0, 1}
-    const int qh = col >> 1, part = col & 1;
+    // ---- constant query-side registers: row `col` = (token group col / 8 if NT = 2, query head, part);
+    // register r of chunk g holds K = 8 kb + 2 r + {0, 1}  <->  channels 32 g + 8 kb + 2 r + {0, 1}.
     // The operand register of a row is  fma(q_hi, Delta, -sub)  with sub = rn(q_sub Delta): high rows keep
     // q_sub = 0 (the result is rn(q_hi Delta)), low rows q_sub = q_hi (the result is the exact remainder),
     // so both kinds of row run the same two instructions.
+    const int arow = NT == 2 ? (col & 7) : col;
+    const int ahalf = NT == 2 ? (col >> 3) : 0;           // token group whose scales this lane's row uses
+    const int qh = arow >> 1, part = arow & 1;
     half2v qhi[4][4];
     half2v qsub[4][4];
     half2v qlo[4][4];                                     // fp32 queries only: low part (low rows), else 0
-    uint32_t azp[4][4];                                   // operand of the zero-point product
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -150,10 +156,9 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
             qhi[g][r] = half2v{h0, h1};
             qsub[g][r] = part == 0 ? half2v{zh, zh} : half2v{h0, h1};
             qlo[g][r] = part == 0 ? half2v{zh, zh} : half2v{l0, l1};
-            azp[g][r] = part == 0 ? pack2(h0, h1) : pack2(l0, l1);
         }
 
-    // ---- this wavefront's token groups
+    // ---- this wavefront's token groups (tiles_per_wave is a multiple of NT)
     const int t0 = (static_cast<int>(blockIdx.x) * kPcWaves + wave) * p.tiles_per_wave;
     const int t1 = min(t0 + p.tiles_per_wave, p.n_tiles);
     if (t0 >= t1) return;                                 // after the last workgroup barrier
@@ -161,47 +166,68 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[kPcWaves * TILE];
     unsigned char* lds = lds_all + wave * TILE;
     const int64_t tile0 = bh * p.store_tiles;
-    // loads: lane L fetches the words of channels 2 L and 2 L + 1 (16 or 32 contiguous bytes) and four
-    // scales (lanes 0..31) or zero-points (lanes 32..63) of the token group
+    // loads per token group: lane L fetches the words of channels 2 L and 2 L + 1 (16 or 32 contiguous
+    // bytes); metadata per step: 2 NT arrays of 128 halves (scales of group 0 (, 1), zero-points of group
+    // 0 (, 1)), 4 NT halves per lane
     const uint32_t* c_base = p.codes + tile0 * (kD * W) + lane * (2 * W);
-    const uint16_t* m_base = (lane < 32 ? p.scale : p.zero) + tile0 * kD + 4 * (lane & 31);
+    constexpr int LPA = 32 / NT;                          // lanes per metadata array
+    const int m_arr = lane / LPA;                         // which array this lane loads from
+    const int m_tile = m_arr % NT;
+    const uint16_t* m_base = (m_arr < NT ? p.scale : p.zero) + tile0 * kD + (lane % LPA) * (4 * NT);
+    typedef uint32_t mvec __attribute__((ext_vector_type(ML)));
     struct Raw {
-        u32x4 c[BITS / 2];
-        u32x2 m;
+        u32x4 c[NT][BITS / 2];
+        mvec m;
     };
+    // a group past the end of this wavefront's range re-reads its last group (never used)
     auto fetch = [&](int t, Raw& r) {
-        const uint32_t tt = static_cast<uint32_t>(t);
 #pragma unroll
-        for (int i = 0; i < BITS / 2; ++i)
-            r.c[i] = PC_LOAD(reinterpret_cast<const u32x4*>(c_base + tt * (kD * W) + 4 * i));
-        r.m = PC_LOAD(reinterpret_cast<const u32x2*>(m_base + tt * kD));
+        for (int i = 0; i < NT; ++i) {
+            const uint32_t tt = static_cast<uint32_t>(min(t + i, t1 - 1));
+#pragma unroll
+            for (int k = 0; k < BITS / 2; ++k)
+                r.c[i][k] = PC_LOAD(reinterpret_cast<const u32x4*>(c_base + tt * (kD * W) + 4 * k));
+        }
+        const uint32_t tm = static_cast<uint32_t>(min(t + m_tile, t1 - 1));
+        r.m = PC_LOAD(reinterpret_cast<const mvec*>(m_base + tm * kD));
     };
 
     const int wsel = col / TH, j = col % TH;              // this lane's word and token position in a half
     const uint32_t rot = static_cast<uint32_t>(BITS * j - 6) & 31u;      // right-rotation: code -> bits 6..
     const int tokA = (32 / W) * wsel + j;                 // token of the first product's column, second: + TH
-    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
-    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    const int kbh = NT == 2 ? (kb & 1) : kb;              // pair of query heads in this lane's result rows
+    const int rhalf = NT == 2 ? (kb >> 1) : 0;            // token group of this lane's result rows
+    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kbh) * p.ssh;
+    const bool st0 = 2 * kbh < p.qpk, st1 = 2 * kbh + 1 < p.qpk;
     const unsigned char* rd_codes = lds + wsel * RSTRIDE + 32 * kb;
-    const unsigned char* rd_meta = lds + SOFF + 16 * kb;
+    const unsigned char* rd_scale = lds + META + ahalf * 256 + 16 * kb;
+    // zero-points: the group of the COLUMN (every K block of a column must see the same group)
+    const unsigned char* rd_zero = lds + META + ZOFF + (NT == 2 ? (col >> 3) * 256 : 0) + 16 * kb;
+    const bool z_mine = NT == 1 || (col >> 3) == rhalf;
 
     auto compute = [&](int t, const Raw& raw) {
         // registers -> LDS tile
-        if constexpr (BITS == 2) {
-            *reinterpret_cast<u32x2*>(lds + 8 * lane) = u32x2{raw.c[0][0], raw.c[0][2]};
-            *reinterpret_cast<u32x2*>(lds + RSTRIDE + 8 * lane) = u32x2{raw.c[0][1], raw.c[0][3]};
-        } else {
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                *reinterpret_cast<u32x2*>(lds + k * RSTRIDE + 8 * lane) = u32x2{raw.c[0][k], raw.c[BITS / 2 - 1][k]};
+        for (int i = 0; i < NT; ++i) {
+            unsigned char* reg = lds + i * W * RSTRIDE + 8 * lane;
+            if constexpr (BITS == 2) {
+                *reinterpret_cast<u32x2*>(reg) = u32x2{raw.c[i][0][0], raw.c[i][0][2]};
+                *reinterpret_cast<u32x2*>(reg + RSTRIDE) = u32x2{raw.c[i][0][1], raw.c[i][0][3]};
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    *reinterpret_cast<u32x2*>(reg + k * RSTRIDE) = u32x2{raw.c[i][0][k], raw.c[i][BITS / 2 - 1][k]};
+            }
         }
-        *reinterpret_cast<u32x2*>(lds + SOFF + 8 * lane) = raw.m;          // lanes 32..63 land at ZOFF
-        // largest Delta of the token group (fp16 patterns of non-negative numbers order like integers)
+        *reinterpret_cast<mvec*>(lds + META + 4 * ML * lane) = raw.m;
+        // largest Delta of each token group: fp16 patterns of non-negative numbers order like integers;
+        // lanes 0..15 (row 0) hold scales of group 0, lanes 16..31 (row 1) of group NT - 1; the rows of
+        // the zero-points are reduced too and never read
         uint32_t mx = 0u;
-        if (lane < 32) {
-            const uint32_t a = raw.m[0] & 0x7FFF7FFFu, c = raw.m[1] & 0x7FFF7FFFu;
-            const uint32_t ma = max(a & 0xFFFFu, a >> 16), mc = max(c & 0xFFFFu, c >> 16);
-            mx = max(ma, mc);
+#pragma unroll
+        for (int i = 0; i < ML; ++i) {
+            const uint32_t v = raw.m[i];
+            mx = max(mx, max(v & 0xFFFFu, v >> 16));
         }
         mx = dpp_max<0xB1>(mx);                           // quad_perm [1,0,3,2]
         mx = dpp_max<0x4E>(mx);                           // quad_perm [2,3,0,1]
@@ -209,26 +235,32 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
         mx = dpp_max<0x140>(mx);                          // row_mirror
         const uint32_t m0 = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(mx), 0));
         const uint32_t m1 = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(mx), 16));
-        const int eD = static_cast<int>(max(m0, m1) >> 10);                // exponent field 0 .. 31
-        int field = 30 - eD;                              // Delta * 2^(field - 15) < 2 (< 4 if eD = 30)
-        field = field < 1 ? 1 : field;
-        const uint32_t sp = static_cast<uint32_t>(field) << 10;
+        // Delta * 2^(field - 15) < 2 (< 4 at the top of fp16's range); a negative or NaN "scale" only
+        // ends up at the clamp
+        int field[2];
+        field[0] = 30 - static_cast<int>((NT == 2 ? m0 : max(m0, m1)) >> 10);
+        field[1] = 30 - static_cast<int>(m1 >> 10);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) field[i] = field[i] < 1 ? 1 : field[i];
+        const int fa = NT == 2 && ahalf ? field[1] : field[0];
+        const int fr = NT == 2 && rhalf ? field[1] : field[0];
+        const uint32_t sp = static_cast<uint32_t>(fa) << 10;
         const half2v spack = __builtin_bit_cast(half2v, sp | (sp << 16));
-        const float descale = as_f32(static_cast<uint32_t>(127 + 33 - field) << 23);   // 2^18 * 2^(15 - field)
+        const float descale = as_f32(static_cast<uint32_t>(127 + 33 - fr) << 23);     // 2^18 * 2^(15 - field)
 
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        f32x4v accA = {0.0f, 0.0f, 0.0f, 0.0f}, accB = accA, zacc = accA;
+        f32x4v acc[NT][2];
+#pragma unroll
+        for (int i = 0; i < NT; ++i) acc[i][0] = acc[i][1] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4v zacc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const u32x4 sc = *reinterpret_cast<const u32x4*>(rd_meta + 64 * g);
-            const u32x4 zm = *reinterpret_cast<const u32x4*>(rd_meta + 256 + 64 * g);
-            const u32x4 wlo = *reinterpret_cast<const u32x4*>(rd_codes + 128 * g);
-            const u32x4 whi = *reinterpret_cast<const u32x4*>(rd_codes + 128 * g + 16);
-            const uint32_t w[8] = {wlo[0], wlo[1], wlo[2], wlo[3], whi[0], whi[1], whi[2], whi[3]};
-            u32x4 aop, bopA, bopB;
+            const u32x4 sc = *reinterpret_cast<const u32x4*>(rd_scale + 64 * g);
+            const u32x4 zm = *reinterpret_cast<const u32x4*>(rd_zero + 64 * g);
+            u32x4 aop;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // (bit-casting the vector ELEMENT expression directly makes this compiler read element 0)
@@ -238,17 +270,34 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
                 half2v a = __builtin_elementwise_fma(qhi[g][r], dl, -sub);
                 if constexpr (QDT == SQUAT_F32) a = __builtin_elementwise_fma(qlo[g][r], dl, a);
                 aop[r] = __builtin_bit_cast(uint32_t, a);
-                // low / high halves of the words of channels 2 r, 2 r + 1: tokens j / TH + j of the word
-                const uint32_t pl = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x05040100u);
-                const uint32_t ph = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x07060302u);
-                bopA[r] = __builtin_amdgcn_alignbit(pl, pl, rot) & MASK;
-                bopB[r] = __builtin_amdgcn_alignbit(ph, ph, rot) & MASK;
             }
-            accA = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop), __builtin_bit_cast(half8, bopA),
-                                                          accA, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop), __builtin_bit_cast(half8, bopB),
-                                                          accB, 0, 0, 0);
-            const u32x4 az = {azp[g][0], azp[g][1], azp[g][2], azp[g][3]};
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {
+                const unsigned char* src = rd_codes + i * W * RSTRIDE + 128 * g;
+                const u32x4 wlo = *reinterpret_cast<const u32x4*>(src);
+                const u32x4 whi = *reinterpret_cast<const u32x4*>(src + 16);
+                const uint32_t w[8] = {wlo[0], wlo[1], wlo[2], wlo[3], whi[0], whi[1], whi[2], whi[3]};
+                u32x4 bopA, bopB;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    // low / high halves of the words of channels 2 r, 2 r + 1: tokens j / TH + j of the word
+                    const uint32_t pl = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x05040100u);
+                    const uint32_t ph = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x07060302u);
+                    bopA[r] = __builtin_amdgcn_alignbit(pl, pl, rot) & MASK;
+                    bopB[r] = __builtin_amdgcn_alignbit(ph, ph, rot) & MASK;
+                }
+                acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop),
+                                                                   __builtin_bit_cast(half8, bopA), acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop),
+                                                                   __builtin_bit_cast(half8, bopB), acc[i][1], 0, 0, 0);
+            }
+            u32x4 az;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // high rows: q_hi (q_sub = 0), low rows: q_lo (q_sub = q_hi); rebuilt to save 16 registers
+                az[r] = __builtin_bit_cast(uint32_t, qhi[g][r]) ^ __builtin_bit_cast(uint32_t, qsub[g][r]);
+                if constexpr (QDT == SQUAT_F32) az[r] |= __builtin_bit_cast(uint32_t, qlo[g][r]);
+            }
             zacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, az), __builtin_bit_cast(half8, zm),
                                                           zacc, 0, 0, 0);
         }
@@ -256,40 +305,61 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
-        const float z0 = zacc[0] + zacc[1], z1 = zacc[2] + zacc[3];
-        const int64_t tok = static_cast<int64_t>(t) * 32 + tokA;
-        if (st0) {
-            __builtin_nontemporal_store(fin * fmaf(descale, accA[0] + accA[1], z0), out0 + tok);
-            __builtin_nontemporal_store(fin * fmaf(descale, accB[0] + accB[1], z0), out0 + tok + TH);
+        // rows 4 kb + {0, 1}: high and low part of the first query head of the lane, rows + {2, 3}: the second
+        float z0 = zacc[0] + zacc[1], z1 = zacc[2] + zacc[3];
+        if constexpr (NT == 2) {
+            // the zero-point sums of this lane's group sit 8 columns away when the column is the other group's
+            const float y0 = as_f32(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(as_u32(z0)), 0x128, 0xF, 0xF, false)));
+            const float y1 = as_f32(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(as_u32(z1)), 0x128, 0xF, 0xF, false)));
+            z0 = z_mine ? z0 : y0;
+            z1 = z_mine ? z1 : y1;
         }
-        if (st1) {
-            __builtin_nontemporal_store(fin * fmaf(descale, accA[2] + accA[3], z1), out0 + p.ssh + tok);
-            __builtin_nontemporal_store(fin * fmaf(descale, accB[2] + accB[3], z1), out0 + p.ssh + tok + TH);
+        float r0[2], r1[2];
+#pragma unroll
+        for (int sgn = 0; sgn < 2; ++sgn) {
+            f32x4v v = acc[0][sgn];
+            if constexpr (NT == 2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = rhalf ? acc[NT - 1][sgn][e] : v[e];
+            }
+            r0[sgn] = fin * fmaf(descale, v[0] + v[1], z0);
+            r1[sgn] = fin * fmaf(descale, v[2] + v[3], z1);
+        }
+        const int tr = t + rhalf;
+        if (tr < t1) {
+            const int64_t tok = static_cast<int64_t>(tr) * 32 + tokA;
+            if (st0) {
+                __builtin_nontemporal_store(r0[0], out0 + tok);
+                __builtin_nontemporal_store(r0[1], out0 + tok + TH);
+            }
+            if (st1) {
+                __builtin_nontemporal_store(r1[0], out0 + p.ssh + tok);
+                __builtin_nontemporal_store(r1[1], out0 + p.ssh + tok + TH);
+            }
         }
     };
 
-    // software pipeline: the loads of kPcDepth token groups are in flight while one is being computed
+    // software pipeline: the loads of kPcDepth steps are in flight while one is being computed
     Raw ring[kPcDepth];
 #pragma unroll
-    for (int i = 0; i < kPcDepth; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
-    for (int t = t0; t < t1; t += kPcDepth) {
+    for (int i = 0; i < kPcDepth; ++i) fetch(t0 + NT * i, ring[i]);
+    for (int t = t0; t < t1; t += NT * kPcDepth) {
 #pragma unroll
         for (int i = 0; i < kPcDepth; ++i) {
             const Raw cur = ring[i];
-            fetch(min(t + i + kPcDepth, t1 - 1), ring[i]);
-            if (t + i < t1) compute(t + i, cur);
+            fetch(t + NT * (i + kPcDepth), ring[i]);
+            if (t + NT * i < t1) compute(t + NT * i, cur);
         }
     }
 }
 
-template <int BITS>
+template <int BITS, int NT>
 int launch_dt(const ScorePcParams& p, dim3 grid, hipStream_t s) {
     const dim3 block(kPcWaves * kWave);
     switch (p.q_dt) {
-        case SQUAT_F32: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_F32>), grid, block, 0, s, p); break;
-        case SQUAT_F16: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_F16>), grid, block, 0, s, p); break;
-        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_BF16>), grid, block, 0, s, p); break;
+        case SQUAT_F32: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_F32, NT>), grid, block, 0, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_F16, NT>), grid, block, 0, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_pc_kernel<BITS, SQUAT_BF16, NT>), grid, block, 0, s, p); break;
         default: return SQUAT_E_BADDTYPE;
     }
     return check_launch();
@@ -343,6 +413,8 @@ int squat::key_scores_pc_from(const uint32_t* codes, const uint16_t* scale, cons
     if (gx < 1) gx = 1;
     int64_t tpw = (n_tiles + kPcWaves * gx - 1) / (kPcWaves * gx);
     if (tpw < kPcMinTilesPerWave) tpw = kPcMinTilesPerWave;
+    const bool two = q_per_kv <= 4;                       // two token groups per step (see the kernel)
+    if (two) tpw += tpw & 1;
     p.tiles_per_wave = static_cast<int>(tpw);
     gx = (n_tiles + kPcWaves * tpw - 1) / (kPcWaves * tpw);
     const int64_t bh = n_batch * n_kv_heads;
@@ -356,7 +428,8 @@ int squat::key_scores_pc_from(const uint32_t* codes, const uint16_t* scale, cons
     if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return bits == 2 ? launch_dt<2>(p, grid, s) : launch_dt<4>(p, grid, s);
+    if (two) return bits == 2 ? launch_dt<2, 2>(p, grid, s) : launch_dt<4, 2>(p, grid, s);
+    return bits == 2 ? launch_dt<2, 1>(p, grid, s) : launch_dt<4, 1>(p, grid, s);
 }
 
 extern "C" int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,

@@ -30,7 +30,7 @@ class CacheConfig(ctypes.Structure):
     _fields_ = [("n_batch", ctypes.c_int64), ("n_kv_heads", ctypes.c_int), ("q_per_kv", ctypes.c_int),
                 ("d", ctypes.c_int), ("bits", ctypes.c_int), ("group", ctypes.c_int), ("g", ctypes.c_int),
                 ("residual", ctypes.c_int), ("max_tokens", ctypes.c_int64), ("kv_dtype", ctypes.c_int),
-                ("quantize_values", ctypes.c_int)]
+                ("quantize_values", ctypes.c_int), ("key_per_channel", ctypes.c_int)]
 
 
 class CacheBuffers(ctypes.Structure):
@@ -346,9 +346,9 @@ class Cache:
 
     def __init__(self, n_batch: int, n_kv_heads: int, q_per_kv: int, bits: int, group: int, g: int, residual: int,
                  max_tokens: int, kv_dtype=torch.bfloat16, update: Optional[torch.Tensor] = None,
-                 quantize_values: bool = False, device="cuda", d: int = 128):
+                 quantize_values: bool = False, device="cuda", d: int = 128, key_per_channel: bool = False):
         self.cfg = CacheConfig(n_batch, n_kv_heads, q_per_kv, d, bits, group, g, residual, max_tokens,
-                               _DT[kv_dtype], int(quantize_values))
+                               _DT[kv_dtype], int(quantize_values), int(key_per_channel))
         self.kv_dtype = kv_dtype
         nbytes = int(lib().squat_cache_arena_bytes(ctypes.byref(self.cfg)))
         if nbytes == 0:
@@ -388,7 +388,8 @@ class Cache:
         return self.arena[off:off + nb].view(dtype).view(shape)
 
     def stores(self) -> dict:
-        """Views of the arena: codes int32 [B,H,max,d*bits/32], scale/zero f16 [B,H,max,d/group], residual
+        """Views of the arena: codes int32 [B,H,max,d*bits/32], scale/zero f16 [B,H,max,d/group] (per-channel
+        keys: [B,H,max/32,d,bits] and [B,H,max/32,d]), residual
         buffers [B,H,R,d] in the kv dtype (values only when configured)."""
         b = CacheBuffers()
         rc = lib().squat_cache_get_buffers(self._h, ctypes.byref(b))
@@ -396,9 +397,12 @@ class Cache:
             raise SquatError(rc, "squat_cache_get_buffers")
         c = self.cfg
         B, H, M, R, d = c.n_batch, c.n_kv_heads, c.max_tokens, c.residual, c.d
-        out = {"key_codes": self._view(b.key_codes, (B, H, M, d * c.bits // 32), torch.int32),
-               "key_scale": self._view(b.key_scale, (B, H, M, d // c.group), torch.float16),
-               "key_zero": self._view(b.key_zero, (B, H, M, d // c.group), torch.float16),
+        kc, km = (B, H, M, d * c.bits // 32), (B, H, M, d // c.group)
+        if c.key_per_channel:
+            kc, km = (B, H, M // 32, d, c.bits), (B, H, M // 32, d)
+        out = {"key_codes": self._view(b.key_codes, kc, torch.int32),
+               "key_scale": self._view(b.key_scale, km, torch.float16),
+               "key_zero": self._view(b.key_zero, km, torch.float16),
                "key_residual": self._view(b.key_residual, (B, H, R, d), self.kv_dtype)}
         if c.quantize_values:
             out.update({"value_codes": self._view(b.value_codes, (B, H, M, d * c.bits // 32), torch.int32),

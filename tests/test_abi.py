@@ -152,6 +152,22 @@ def test_key_scores_argument_validation_happens_before_any_launch():
     assert ks(codes=odd) == -4
     assert ks(n=0) == 0
     assert ks(n=-1) == -2
+    kp = lambda **kw: L.squat_key_scores_per_channel(  # noqa: E731
+        kw.get("codes", fake), kw.get("scale", fake), fake, 1, 2, kw.get("n", 64), kw.get("d", 128),
+        kw.get("bits", 2), kw.get("G", 32), kw.get("q", fake), kw.get("dt", 2), kw.get("qpk", 4), 1024,
+        kw.get("qsh", 128), kw.get("os", 1.0), kw.get("out", fake), 8 * 64, kw.get("ssh", 64), None)
+    assert kp(d=64) == -2
+    assert kp(bits=3) == -2
+    assert kp(G=64) == -2           # token groups of 32 only
+    assert kp(n=48) == -2           # whole token groups only
+    assert kp(qpk=9) == -2
+    assert kp(dt=4) == -3
+    assert kp(os=float("nan")) == -7
+    assert kp(q=None) == -1
+    assert kp(ssh=32) == -2
+    assert kp(codes=odd) == -4
+    assert kp(scale=odd) == -4
+    assert kp(n=0) == 0
 
 
 def test_cache_configuration_and_creation_are_validated_on_the_host():
@@ -168,10 +184,13 @@ def test_cache_configuration_and_creation_are_validated_on_the_host():
                 squat.CacheConfig(2, 8, 0, 128, 2, 32, 32, 32, 4096, 2, 0),     # q_per_kv
                 squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4100, 2, 0),     # capacity not a multiple of R
                 squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 0, 4096, 2, 0),      # R
-                squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4096, 5, 0)):    # dtype
+                squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 32, 4096, 5, 0),     # dtype
+                squat.CacheConfig(2, 8, 4, 128, 2, 32, 32, 16, 4096, 2, 0, 1)): # per-channel keys: R not a multiple of 32
         assert L.squat_cache_arena_bytes(ctypes.byref(bad)) == 0
         h = ctypes.c_void_p()
         assert L.squat_cache_create(ctypes.byref(bad), ctypes.c_void_p(0x1000), 1 << 40, None, ctypes.byref(h)) == -2
+    pc = squat.CacheConfig(2, 8, 4, 128, 2, 64, 32, 32, 4096, 2, 0, 1)          # per-channel keys: 4 scales per token
+    assert L.squat_cache_arena_bytes(ctypes.byref(pc)) == L.squat_cache_arena_bytes(ctypes.byref(keys_only))
     h = ctypes.c_void_p()
     assert L.squat_cache_create(ctypes.byref(ok), None, need, None, ctypes.byref(h)) == -5
     assert L.squat_cache_create(ctypes.byref(ok), ctypes.c_void_p(0x1000), need - 1, None, ctypes.byref(h)) == -5

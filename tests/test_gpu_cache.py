@@ -13,7 +13,7 @@ from tests import util
 pytestmark = pytest.mark.gpu
 
 
-def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed):
+def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed, per_channel=False):
     gen = synth.rng(seed)
     n_all = n_prompt + n_decode
     kraw, kval = synth.store(synth.keys(seed + 1, H, n_all, batch=B), dtype)
@@ -23,8 +23,19 @@ def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed):
     U = np.stack([O.update_matrix_lowrank(Qh[h], 1e-3, g) for h in range(H)]).astype(np.float16).astype(np.float32)
     Ut = torch.from_numpy(U).cuda()
     max_tokens = ((n_all + R - 1) // R) * R
-    cache = squat.Cache(B, H, qpk, bits, G, g, R, max_tokens, kv_dtype=kt.dtype, update=Ut, quantize_values=values)
-    refs = [[O.CacheOracle(U[h].astype(np.float64), bits, G, g, R, values=values) for h in range(H)] for _ in range(B)]
+    cache = squat.Cache(B, H, qpk, bits, G, g, R, max_tokens, kv_dtype=kt.dtype, update=Ut, quantize_values=values,
+                        key_per_channel=per_channel)
+    axis = "channel" if per_channel else "token"
+    KG = 32 if per_channel else G                                  # key group: 32 tokens or G channels
+    refs = [[O.CacheOracle(U[h].astype(np.float64), bits, G, g, R, values=values, key_axis=axis) for h in range(H)]
+            for _ in range(B)]
+
+    def key_store(st, nq):
+        if per_channel:
+            return (O.unpack_codes_tokens(util.codes_to_host(st["key_codes"][:, :, :nq // 32]), bits),
+                    util.half_to_host(st["key_scale"][:, :, :nq // 32]), util.half_to_host(st["key_zero"][:, :, :nq // 32]))
+        return (O.unpack_codes(util.codes_to_host(st["key_codes"][:, :, :nq]), bits),
+                util.half_to_host(st["key_scale"][:, :, :nq]), util.half_to_host(st["key_zero"][:, :, :nq]))
 
     def check_counts():
         cnt = cache.counts()
@@ -53,8 +64,7 @@ def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed):
             torch.cuda.synchronize()
             st = cache.stores()
             nq, nr = cnt.keys_quantized, cnt.keys_residual
-            codes = O.unpack_codes(util.codes_to_host(st["key_codes"][:, :, :nq]), bits)
-            sc, ze = util.half_to_host(st["key_scale"][:, :, :nq]), util.half_to_host(st["key_zero"][:, :, :nq])
+            codes, sc, ze = key_store(st, nq)
             g64 = got.cpu().numpy().astype(np.float64)
             assert g64.shape == (B, H * qpk, nq + nr)
             for b in range(B):
@@ -64,22 +74,26 @@ def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed):
                     bound_res = 0.25 * np.abs(qval[b, hq]) @ np.abs(kval[b, h, t + 1 - nr:t + 1]).T if nr else np.zeros(0)
                     assert np.all(np.abs(g64[b, hq, nq:] - want_res) <= 1e-5 * bound_res + 1e-30)
                     if nq:
-                        want = O.key_scores(qval[b, hq][None], codes[b, h], sc[b, h], ze[b, h], G, 0.25)[0]
-                        khat = np.abs(O.dequantize_keys(codes[b, h], sc[b, h], ze[b, h], G))
+                        want = O.key_scores(qval[b, hq][None], codes[b, h], sc[b, h], ze[b, h], KG, 0.25, axis=axis)[0]
+                        khat = np.abs(O.dequantize_keys(codes[b, h], sc[b, h], ze[b, h], KG, axis=axis))
                         bound = 0.25 * (np.abs(qval[b, hq])[None] * khat).sum(axis=1)
-                        assert np.all(np.abs(g64[b, hq, :nq] - want) <= 4e-5 * bound + 1e-30)
+                        floor = 0.0
+                        if per_channel:      # fp16 high/low pair of q * Delta: see test_gpu_scores_pc
+                            qmax = np.abs(qval[b, h * qpk:(h + 1) * qpk]).max()
+                            floor = 0.25 * 128 * (2 ** bits - 1) * 2.0 ** -24 * qmax * np.repeat(sc[b, h].astype(np.float64).max(axis=1), 32)
+                        assert np.all(np.abs(g64[b, hq, :nq] - want) <= 4e-5 * bound + floor + 1e-30)
     torch.cuda.synchronize()
     cnt = cache.counts()
     st = cache.stores()
     nq, nr = cnt.keys_quantized, cnt.keys_residual
-    codes = O.unpack_codes(util.codes_to_host(st["key_codes"][:, :, :nq]), bits)
-    sc, ze = util.half_to_host(st["key_scale"][:, :, :nq]), util.half_to_host(st["key_zero"][:, :, :nq])
+    codes, sc, ze = key_store(st, nq)
     res = util.out_to_f64(st["key_residual"][:, :, :nr])
     tot = dict(code_diff=0, code_unexplained=0, meta_diff=0, meta_unexplained=0, n_codes=0)
     for b in range(B):
         for h in range(H):
             assert np.array_equal(res[b, h], kval[b, h, n_all - nr:n_all])
-            rep = O.replay_classify(kval[b, h, :nq], U[h].astype(np.float64), bits, G, g, codes[b, h], sc[b, h], ze[b, h])
+            rep = O.replay_classify(kval[b, h, :nq], U[h].astype(np.float64), bits, KG, g, codes[b, h], sc[b, h], ze[b, h],
+                                    axis=axis)
             for k in tot:
                 tot[k] += rep[k]
     assert tot["code_unexplained"] == 0 and tot["meta_unexplained"] == 0, tot
@@ -108,6 +122,15 @@ def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed):
 @pytest.mark.parametrize("values", [False, True])
 def test_cache_prefill_then_decode(values):
     _run(B=2, H=3, qpk=4, bits=2, G=32, g=32, R=32, n_prompt=70, n_decode=75, dtype=synth.BF16, values=values, seed=4100)
+
+
+def test_cache_per_channel_keys():
+    """The paper's own configuration: keys per channel over groups of 32 tokens = the residual length,
+    values per token (here in groups of 64 channels)."""
+    _run(B=2, H=2, qpk=4, bits=2, G=64, g=32, R=32, n_prompt=70, n_decode=75, dtype=synth.BF16, values=True, seed=4150,
+         per_channel=True)
+    _run(B=1, H=2, qpk=8, bits=4, G=32, g=64, R=64, n_prompt=200, n_decode=70, dtype=synth.F16, values=False, seed=4160,
+         per_channel=True)
 
 
 def test_cache_short_prompt_other_parameters():

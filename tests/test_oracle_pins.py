@@ -377,6 +377,20 @@ def test_cache_bookkeeping_follows_algorithm_1():
     short = O.CacheOracle(U, 2, 32, 32, R, values=True)
     short.prefill(K[:5], V[:5])                                   # shorter than the buffer: nothing quantized
     assert not short.k_codes and len(short.k_full) == 5 and not short.v_codes and len(short.v_full) == 5
+    # the grouping Algorithm 1 prints: every flush is one group of 32 tokens quantized per channel, and
+    # groups are independent, so the store again equals one-shot quantization of the prefix
+    pc = O.CacheOracle(U, 2, 64, 32, R, key_axis="channel")
+    pc.prefill(K[:70])
+    for t in range(70, 150):
+        pc.append(K[t])
+    refc = O.quantize_keys(K[:128], U, 2, 32, 32, axis="channel")
+    assert np.array_equal(np.stack(pc.k_codes), refc["codes"]) and np.array_equal(np.stack(pc.k_scale), refc["scale"])
+    assert np.array_equal(np.stack(pc.k_zero), refc["zero"]) and len(pc.k_scale) == 4
+    assert np.array_equal(np.stack(pc.k_full), K[128:150])
+    sp = pc.scores(q, 0.5)
+    assert np.allclose(sp[:, :128], 0.5 * q @ refc["xhat"].T, rtol=1e-12, atol=1e-12)
+    assert np.allclose(sp[:, 128:], 0.5 * q @ K[128:150].T, rtol=1e-13)
+    assert not np.array_equal(refc["codes"], ref["codes"])        # the two groupings are different quantizers
 
 
 # ------------------------------------------- per-channel mode (the paper's own layout)
