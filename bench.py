@@ -195,6 +195,8 @@ def main():
     if args.variants:
         pc_list += [(2, 64, True), (4, 32, True), (4, 64, True), (2, 128, False)]
     out["per_channel"] = []
+    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()                      # [1, q_heads, d]: the last prompt token's queries
+    logits = torch.empty((1, H * wl.q_per_kv, n), dtype=torch.float32, device=dev)
     for bits, g, use_update in pc_list:
         upd = (update if g == wl.g else squat.prepare(qhat, wl.lam, g)) if use_update else None
         c = torch.empty((1, H, n // 32, d, bits), dtype=torch.int32, device=dev)
@@ -202,15 +204,17 @@ def main():
         ze = torch.empty_like(sc)
         tq = timed(lambda: squat.quantize_keys_per_channel(wl.k, upd, bits, 32, g, codes=c, scale=sc, zero=ze))
         td = timed(lambda: squat.dequantize_keys_per_channel(c, sc, ze, bits, 32, out=back))
+        tsc = timed(lambda: squat.key_scores_per_channel(qdec, c, sc, ze, bits, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
         nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // 32))
+        sb = n_keys * (d * bits // 8 + 4 * (d // 32) + 4 * wl.q_per_kv)
         out["per_channel"].append({"bits": bits, "token_group": 32, "g": g, "update": use_update,
                                    "bytes_per_key": nbytes // n_keys,
                                    "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                   "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                                   "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "key_scores_us": tsc * 1e3, "key_scores_bytes_per_key": sb // n_keys,
+                                   "key_scores_frac_of_hbm_peak": sb / (tsc * 1e-3) / 1e9 / HBM_PEAK_GBS})
     # Decode-side consumer: attention logits of one query token per query head straight from the packed
     # store just written (48 B of codes and metadata in, 4 B per query head out, per key).
-    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()                      # [1, q_heads, d]: the last prompt token's queries
-    logits = torch.empty((1, H * wl.q_per_kv, n), dtype=torch.float32, device=dev)
     ts = timed(lambda: squat.key_scores(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
     sbytes = n_keys * (d * wl.bits // 8 + 4 * (d // wl.group) + 4 * wl.q_per_kv)
     out["key_scores"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bytes_per_key": sbytes // n_keys,
@@ -264,31 +268,34 @@ def main():
         nk = 64 * H * nd
         nb = nk * (d * wl.bits // 8 + 4 * (d // wl.group) + 4 * wl.q_per_kv)
         # the same shape through the cache object: 64 decode steps (append one token per sequence, then
-        # logits over everything cached); two of the 64 appends flush a full residual buffer
+        # logits over everything cached); two of the 64 appends flush a full residual buffer.  Once with
+        # keys grouped per token, once per channel over the 32 flushed tokens (the paper's grouping).
         kp = torch.randn((64, H, nd, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
-        cache = squat.Cache(64, H, wl.q_per_kv, wl.bits, wl.group, wl.g, 32, nd + 64, kv_dtype=torch.bfloat16, update=update)
-        cache.prefill(kp)
-        del kp
         knew = torch.randn((64, H, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
         lc = torch.empty((64, H * wl.q_per_kv, nd + 64), dtype=torch.float32, device=dev)
-        torch.cuda.synchronize()
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        t_app = t_sc = 0.0
-        for _ in range(64):
-            e[0].record()
-            cache.append(knew)
-            e[1].record()
-            cache.key_scores(qd, d ** -0.5, out=lc)
-            e[2].record()
+        for name, per_channel in (("decode_cache", False), ("decode_cache_per_channel", True)):
+            cache = squat.Cache(64, H, wl.q_per_kv, wl.bits, wl.group, wl.g, 32, nd + 64, kv_dtype=torch.bfloat16,
+                                update=update, key_per_channel=per_channel)
+            cache.prefill(kp)
             torch.cuda.synchronize()
-            t_app += e[0].elapsed_time(e[1])
-            t_sc += e[1].elapsed_time(e[2])
-        cnt = cache.counts()
-        out["decode_cache"] = {"sequences": 64, "heads": H, "tokens_cached": int(cnt.n_tokens), "residual": 32,
-                               "us_per_append_mean_of_64": t_app / 64 * 1e3, "us_per_logits_mean_of_64": t_sc / 64 * 1e3,
-                               "note": "append = copy into the residual buffer, plus every 32nd step one quantize "
-                                       "launch over 64 x %d x 32 keys" % H}
-        del cache
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            t_app = t_sc = 0.0
+            for _ in range(64):
+                e[0].record()
+                cache.append(knew)
+                e[1].record()
+                cache.key_scores(qd, d ** -0.5, out=lc)
+                e[2].record()
+                torch.cuda.synchronize()
+                t_app += e[0].elapsed_time(e[1])
+                t_sc += e[1].elapsed_time(e[2])
+            cnt = cache.counts()
+            out[name] = {"sequences": 64, "heads": H, "tokens_cached": int(cnt.n_tokens), "residual": 32,
+                         "us_per_append_mean_of_64": t_app / 64 * 1e3, "us_per_logits_mean_of_64": t_sc / 64 * 1e3,
+                         "note": "append = copy into the residual buffer, plus every 32nd step one quantize "
+                                 "launch over 64 x %d x 32 keys" % H}
+            del cache
+        del kp
         out["decode_scores"] = {"sequences": 64, "heads": H, "quantized_tokens": nd, "q_per_kv": wl.q_per_kv, "us": us,
                                 "keys_per_s": nk / (us * 1e-6), "frac_of_hbm_peak": nb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:

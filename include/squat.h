@@ -11,7 +11,8 @@
  *   squat_dequantize_keys  codes -> keys                     (Section 2, deq)
  *
  * squat_key_scores is the decode-side consumer of that store (attention
- * logits straight from the codes).
+ * logits straight from the codes); squat_key_scores_per_channel is the same
+ * for the per-channel store.
  *
  * squat_quantize_keys groups every key's channels (statistics per token); the
  * pair squat_quantize_keys_per_channel / squat_dequantize_keys_per_channel is
@@ -316,7 +317,9 @@ int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, c
  *           `residual` tokens; the rest waits in the residual buffer.
  *   values  (optional) quantized with plain round-to-nearest one token at a
  *           time once they are older than `residual` tokens.
- *   logits  squat_cache_key_scores = squat_key_scores over the quantized keys
+ *   keys    with key_per_channel: quantized with squat_quantize_keys_per_channel
+ *           instead (groups of 32 tokens per channel, the paper's grouping).
+ *   logits  squat_cache_key_scores = squat_key_scores (or _per_channel) over the quantized keys
  *           followed by plain dot products over the residual keys:
  *           scores[b, hq, 0 .. keys_quantized + keys_residual).
  * ------------------------------------------------------------------------- */
