@@ -138,3 +138,46 @@ def test_fullsize_per_channel_mode_on_sampled_token_groups(run):
     c2, s2, z2 = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
     torch.cuda.synchronize()
     assert torch.equal(c2, codes_t) and torch.equal(s2, scale_t) and torch.equal(z2, zero_t)
+
+
+def test_fullsize_logits_from_both_stores_on_sampled_tokens(run):
+    """squat_key_scores and squat_key_scores_per_channel as bench.py launches them (one decode query per
+    query head over all 32768 quantized tokens of every head): sampled (query head, token) logits against
+    the oracle applied to the GPU's own stores; every logit finite; second run bit-identical."""
+    wl = run["wl"]
+    n, d, qpk = wl.n_tokens, wl.d, wl.q_per_kv
+    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()
+    out_scale = d ** -0.5
+    tok = squat.key_scores(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, out_scale)
+    pc, ps, pz = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
+    chan = squat.key_scores_per_channel(qdec, pc, ps, pz, wl.bits, qpk, out_scale)
+    torch.cuda.synchronize()
+    assert tok.shape == chan.shape == (1, wl.heads * qpk, n)
+    assert torch.isfinite(tok).all() and torch.isfinite(chan).all()
+    gen = np.random.default_rng(23)
+    for hq in np.concatenate([[0, wl.heads * qpk - 1], gen.integers(0, wl.heads * qpk, size=10)]):
+        h = int(hq) // qpk
+        q = _bf16_to_f64(qdec[0, hq])
+        # per-token store: sampled tokens, including the first and last of the sequence
+        ts = np.unique(np.concatenate([[0, 15, 16, n - 1], gen.integers(0, n, size=40)]))
+        codes = O.unpack_codes(run["codes"][0, h, ts].cpu().numpy().view(np.uint32), wl.bits)
+        sc, ze = run["scale"][0, h, ts].cpu().numpy(), run["zero"][0, h, ts].cpu().numpy()
+        want = O.key_scores(q[None], codes, sc, ze, wl.group, out_scale)[0]
+        bound = out_scale * (np.abs(q)[None] * np.abs(O.dequantize_keys(codes, sc, ze, wl.group))).sum(axis=1)
+        got = tok[0, hq, ts].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - want) <= 4e-5 * bound)
+        # per-channel store: whole sampled token groups
+        qmax = np.abs(_bf16_to_f64(qdec[0, h * qpk:(h + 1) * qpk])).max()
+        for gi in np.unique(np.concatenate([[0, n // 32 - 1], gen.integers(0, n // 32, size=6)])):
+            codes = O.unpack_codes_tokens(pc[0, h, gi:gi + 1].cpu().numpy().view(np.uint32), wl.bits)
+            sc, ze = ps[0, h, gi:gi + 1].cpu().numpy(), pz[0, h, gi:gi + 1].cpu().numpy()
+            want = O.key_scores(q[None], codes, sc, ze, 32, out_scale, axis="channel")[0]
+            khat = np.abs(O.dequantize_keys(codes, sc, ze, 32, axis="channel"))
+            bound = out_scale * (np.abs(q)[None] * khat).sum(axis=1)
+            floor = out_scale * 128 * (2 ** wl.bits - 1) * 2.0 ** -24 * qmax * float(sc.astype(np.float64).max())
+            got = chan[0, hq, gi * 32:(gi + 1) * 32].cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(got - want) <= 4e-5 * bound + floor)
+    tok2 = squat.key_scores(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, out_scale)
+    chan2 = squat.key_scores_per_channel(qdec, pc, ps, pz, wl.bits, qpk, out_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(tok, tok2) and torch.equal(chan, chan2)
