@@ -12,10 +12,16 @@
 //                 workgroup, partial tiles go to the workspace.
 //   gram_reduce   sums the workgroups' partials in fp64 in a fixed order
 //                 (deterministic), un-permutes channels and mirrors.
+//   eig_tridiag_kernel  r <= 32: Householder tridiagonalisation, Sturm-count search
+//                 for the r largest eigenvalues, inverse iteration, back-transformation
+//                 (squat_tridiag.h), one workgroup per KV head; flags a head whose result
+//                 fails its own residual checks.
 //   eig_kernel    cyclic one-sided Jacobi in fp64 on the 128 x 128 Gram matrix in
-//                 LDS, one workgroup per KV head, then picks the r largest.
+//                 LDS, one workgroup per KV head, then picks the r largest: r > 32, and
+//                 the heads the kernel above flagged.
 #include "squat_internal.h"
 #include "squat_jacobi.h"
+#include "squat_tridiag.h"
 
 using namespace squat;
 
@@ -290,9 +296,20 @@ constexpr int kEigTeam = SQUAT_EIG_TS;          // lanes per row pair
 constexpr int kEigThreads = 64 * kEigTeam;
 constexpr int kEigLd = kD;       // rows are read with unit stride by consecutive lanes
 
-__global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int r, float* qhat, float* eig,
-                                                          int* sweeps_out) {
+__global__ void __launch_bounds__(kTriThreads) eig_tridiag_kernel(const double* g64, double* vws, int r, float* qhat,
+                                                                  float* eig, int* need) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int64_t kvh = blockIdx.x;
+    const bool ok = tridiag_top_eigs(g64 + kvh * kD * kD, vws + kvh * kD * kD, r, qhat + kvh * r * kD,
+                                     eig ? eig + kvh * r : nullptr, reinterpret_cast<double*>(smem));
+    if (threadIdx.x == 0) need[kvh] = ok ? 0 : 1;
+}
+
+// need: NULL = every head; else only the heads with need[head] != 0
+__global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int r, float* qhat, float* eig,
+                                                          int* sweeps_out, const int* need) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    if (need && need[blockIdx.x] == 0) return;
     double* A = reinterpret_cast<double*>(smem);                 // 128 x 128
     double* nrm = A + kD * kEigLd;                               // 128
     int* rank = reinterpret_cast<int*>(nrm + kD);                // 128
@@ -358,7 +375,7 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
 
 struct SubspacePlan {
     int wgs_per_head;
-    size_t off_partial, off_g64, total;
+    size_t off_partial, off_g64, off_v, off_need, total;
 };
 
 SubspacePlan plan(int64_t n_tokens, int n_kv_heads, int q_per_kv, int cus) {
@@ -372,7 +389,10 @@ SubspacePlan plan(int64_t n_tokens, int n_kv_heads, int q_per_kv, int cus) {
     pl.off_partial = 0;
     size_t partial = static_cast<size_t>(n_kv_heads) * per * kPartialFloats * sizeof(float);
     pl.off_g64 = (partial + 255) & ~size_t(255);
-    pl.total = pl.off_g64 + static_cast<size_t>(n_kv_heads) * kD * kD * sizeof(double);
+    const size_t mat = static_cast<size_t>(n_kv_heads) * kD * kD * sizeof(double);
+    pl.off_v = pl.off_g64 + mat;                               // Householder reflectors of every head
+    pl.off_need = pl.off_v + mat;                              // per head: 1 = the Jacobi kernel must redo it
+    pl.total = pl.off_need + ((static_cast<size_t>(n_kv_heads) * sizeof(int) + 255) & ~size_t(255));
     return pl;
 }
 
@@ -433,6 +453,9 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(eig_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(eig_lds)) != hipSuccess)
             return SQUAT_E_HIP;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(eig_tridiag_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kTriLdsBytes)) != hipSuccess)
+            return SQUAT_E_HIP;
         attr_done = true;
     }
     switch (q_dt) {
@@ -446,8 +469,17 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
     rc = check_launch();
     if (rc) return rc;
     if (r > 0) {
+        int* need = nullptr;
+        if (r <= kTriMaxR) {
+            need = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) + pl.off_need);
+            double* vws = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_v);
+            hipLaunchKernelGGL(eig_tridiag_kernel, dim3(n_kv_heads), dim3(kTriThreads), kTriLdsBytes, s, g64, vws, r, qhat,
+                               eig, need);
+            rc = check_launch();
+            if (rc) return rc;
+        }
         hipLaunchKernelGGL(eig_kernel, dim3(n_kv_heads), dim3(kEigThreads), eig_lds, s, g64, r, qhat, eig,
-                           static_cast<int*>(nullptr));
+                           static_cast<int*>(nullptr), static_cast<const int*>(need));
         rc = check_launch();
     }
     return rc;

@@ -1,0 +1,611 @@
+// Top-r eigenpairs of a symmetric positive semi-definite 128 x 128 matrix by the
+// classical dense route, one 1024-thread workgroup per matrix (Section 3.2: the
+// right singular vectors and singular values of the query matrix are the
+// eigenpairs of its Gram matrix):
+//
+//   1. Householder reduction to tridiagonal form T.  The matrix lives in
+//      REGISTERS: thread (row i, lane l of the row's team of 8) holds columns
+//      16 l .. 16 l + 15 of row i; per step only the column being eliminated, the
+//      product A v and two scalars travel through LDS (two barriers per step).
+//   2. The r largest eigenvalues of T by 9-section on Sturm counts (8 trial
+//      shifts per eigenvalue and round, 18 rounds from [-3, 3] ||T||): the count
+//      is the number of sign changes of the three-term recurrence of the leading
+//      principal minors, division-free, rescaled by a power of two every 8 terms.
+//   3. Eigenvectors of T by inverse iteration with those shifts (made distinct by
+//      a few ulps where eigenvalues coincide): two solves per vector by Gaussian
+//      elimination with partial pivoting, one lane per vector; then the Gram
+//      matrix of the vectors decides whether they are orthonormal to 1e-10
+//      already (separated eigenvalues), need one symmetric correction step (close
+//      eigenvalues) or go through Cholesky-QR (coincident ones).
+//   4. Rayleigh quotients = eigenvalues; residuals ||T x - lambda x|| checked.
+//   5. Back-transformation by the stored reflectors (kept in LDS during step 1,
+//      parked in global memory while steps 2-4 use that LDS block).
+//
+// A matrix whose result fails the checks of step 4 (never seen with fp64, kept as
+// a safety net) is flagged and handed to the Jacobi kernel.  About 40 times fewer
+// floating-point operations than cyclic Jacobi on the full matrix.
+#pragma once
+
+#include "squat_internal.h"
+#include "squat_jacobi.h"
+
+namespace squat {
+
+constexpr int kTriN = 128;
+constexpr int kTriThreads = 1024;
+constexpr int kTriMaxR = 32;            // vectors the LDS plan holds
+constexpr int kTriPts = 8;              // trial shifts per eigenvalue and round
+constexpr int kTriRounds = 18;          // 9^18 > 6 * 2^53
+constexpr double kTriAccept = 1e-9;     // ||T x - lambda x|| / ||T|| and |x_i . x_j| allowed before the fallback
+
+// LDS plan, in doubles
+constexpr int kTriXs = 0;               // [2][128] column being eliminated (double-buffered)
+constexpr int kTriPs = 256;             // [2][128] beta * A v
+constexpr int kTriDd = 512;             // [128] diagonal of T (then normalised)
+constexpr int kTriEe = 640;             // [128] sub-diagonal (then normalised)
+constexpr int kTriBet = 768;            // [128] beta of every reflector
+constexpr int kTriDe = 896;             // [128][2] (d_i, e_{i-1}^2) normalised, for the Sturm recurrence
+constexpr int kTriLam = 1152;           // [32] eigenvalues, [32] shifts, [32] Rayleigh quotients, [32] scratch
+constexpr int kTriMisc = 1280;          // [64] reductions and flags
+constexpr int kTriX = 1344;             // [128][32] vectors, element-major
+constexpr int kTriU0 = kTriX + 4096;    // [128][32] reciprocal pivots
+constexpr int kTriU1 = kTriU0 + 4096;
+constexpr int kTriU2 = kTriU1 + 4096;
+constexpr int kTriS = kTriU2 + 4096;    // [32][33] Gram matrix / Cholesky factor
+constexpr int kTriLdsDoubles = kTriS + 32 * 33;
+constexpr size_t kTriLdsBytes = static_cast<size_t>(kTriLdsDoubles) * sizeof(double);
+static_assert(kTriLdsBytes <= 160 * 1024, "LDS plan exceeds a compute unit");
+static_assert(kTriX + 16384 == kTriS, "vectors and factors form one 128 KB block (reused for the reflectors)");
+
+__device__ __forceinline__ double tri_block_max(double v, double* scratch, int tid) {
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) v = fmax(v, __shfl_xor(v, s, 64));
+    __syncthreads();                                      // scratch may still be read from an earlier use
+    if ((tid & 63) == 0) scratch[tid >> 6] = v;
+    __syncthreads();
+    double m = scratch[0];
+#pragma unroll
+    for (int w = 1; w < kTriThreads / 64; ++w) m = fmax(m, scratch[w]);
+    return m;
+}
+
+__device__ __forceinline__ double tri_pow2(int e) {       // 2^e, -1022 <= e <= 1023
+    return __hiloint2double((e + 1023) << 20, 0);
+}
+
+// Workgroup barrier that orders LDS traffic only (the Householder loop touches nothing else; the full
+// barrier would also wait for the vector-memory counter).
+__device__ __forceinline__ void tri_lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ double tri_readlane(double v, int src) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the wavefront, the same value (bit for bit) in every lane and in every wavefront that
+// sums the same numbers: four 16-lane sums by lane permutes, combined as scalars.
+__device__ __forceinline__ double tri_wave_sum(double v) {
+    v = team_sum<16>(v);
+    return (tri_readlane(v, 0) + tri_readlane(v, 16)) + (tri_readlane(v, 32) + tri_readlane(v, 48));
+}
+
+// Sum over an aligned team of 32 lanes (two rows of 16): row sums by lane permutes, then the two rows
+// trade their sums with the row-swap instruction (no trip through the LDS crossbar).
+__device__ __forceinline__ double tri_sum32(double v) {
+    v = team_sum<16>(v);
+    const uint32_t lo = static_cast<uint32_t>(__double2loint(v)), hi = static_cast<uint32_t>(__double2hiint(v));
+    const auto sl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto sh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __hiloint2double(static_cast<int>(sh[0]), static_cast<int>(sl[0])) +
+           __hiloint2double(static_cast<int>(sh[1]), static_cast<int>(sl[1]));
+}
+
+// 1 / sqrt(x) and 1 / x from the hardware approximations and Newton steps (short dependent chains: the
+// library routines would sit on the critical path of every Householder step)
+__device__ __forceinline__ double tri_rsqrt(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+#pragma unroll
+    for (int it = 0; it < 3; ++it) {
+        const double e = fma(-x * y, y, 1.0);
+        y = fma(0.5 * y, e, y);
+    }
+    return y;
+}
+__device__ __forceinline__ double tri_rcp(double x) {
+    double y = __builtin_amdgcn_rcp(x);
+#pragma unroll
+    for (int it = 0; it < 3; ++it) y = fma(y, fma(-x, y, 1.0), y);
+    return y;
+}
+
+// One Householder step, column k = 16 KK + CC (CC is a compile-time register index).  The kernel is
+// bound by instruction issue (four wavefronts per SIMD, all running the same step), so the step is
+// written for few instructions: the eliminated column goes to LDS with zeros above the diagonal (no
+// masks afterwards), and the rank-two update v w' + w v' is applied as two multiply-adds per element.
+template <int CC>
+__device__ __forceinline__ void tri_step(double (&a)[16], int kk, int i, int l, int tid, double* L) {
+    const int k = 16 * kk + CC;
+    if (k > kTriN - 3) return;                            // uniform
+    constexpr int CN = (CC + 1) & 15;                     // register of column k + 1 ...
+    const int own = CC == 15 ? kk + 1 : kk;               // ... in this lane of the row team
+    const int lane = tid & 63, wave = tid >> 6;
+    double* xs = L + kTriXs + (k & 1) * kTriN;
+    double* ps = L + kTriPs + (k & 1) * kTriN;
+    if (l == kk) {
+        xs[i] = i > k ? a[CC] : 0.0;
+        if (i == k) L[kTriDd + k] = a[CC];
+    }
+    tri_lds_barrier();
+    const bool rows_live = 8 * wave + 7 > k;              // this wavefront still owns rows of the trailing block
+    double alpha = 0.0, beta = 0.0, p_i = 0.0, v_i = 0.0;
+    double vj[16];
+    bool live = false;
+    if (rows_live || wave == 0) {
+        const double xa = xs[lane], xb = xs[lane + 64];
+        const double x0 = xs[k + 1];
+        // sigma = |x|^2 without its first element
+        double r2 = fma(xb, xb, xa * xa);
+        r2 = tri_wave_sum(r2) - x0 * x0;
+        // (cancellation in the line above only matters when the rest is ~1e-16 |x0|^2: then the reflector is
+        // the identity to working precision either way; a tiny negative result takes the identity branch)
+        live = r2 > 0.0;
+        alpha = x0;
+        if (live) {
+            const double sigma = fma(x0, x0, r2);
+            const double sq = sigma * tri_rsqrt(sigma);
+            alpha = x0 >= 0.0 ? -sq : sq;
+            beta = tri_rcp(fma(fabs(x0), sq, sigma));     // 2 / v'v with v = x - alpha e_1
+            if (rows_live) {
+                double q4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int c = 0; c < 16; ++c) vj[c] = xs[16 * l + c];
+                if (l == own) vj[CN] -= alpha;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) q4[c & 3] = fma(a[c], vj[c], q4[c & 3]);
+                const double q = team_sum<8>((q4[0] + q4[1]) + (q4[2] + q4[3]));
+                v_i = xs[i];
+                if (i == k + 1) v_i -= alpha;
+                p_i = i > k ? beta * q : 0.0;
+            }
+        }
+    }
+    // rows that are done contribute zeros; every row writes so that nothing stale is read
+    if (l == 0) {
+        ps[i] = p_i;
+        L[kTriX + k * kTriN + i] = v_i;                    // reflector k (the block of the later phases is free now)
+    }
+    if (tid == 0) {
+        L[kTriEe + k] = alpha;
+        L[kTriBet + k] = beta;
+    }
+    tri_lds_barrier();
+    if (live && rows_live) {
+        // K = beta/2 p'v ; w = p - K v ; A -= v w' + w v'
+        double s;
+        {
+            double va = xs[lane], vb = xs[lane + 64];
+            if (lane == k + 1) va -= alpha;
+            if (lane + 64 == k + 1) vb -= alpha;
+            s = fma(ps[lane], va, ps[lane + 64] * vb);
+        }
+        const double K = 0.5 * beta * tri_wave_sum(s);
+        const double nw_i = fma(K, v_i, -p_i), nv_i = -v_i;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const double w = fma(-K, vj[c], ps[16 * l + c]);
+            a[c] = fma(nv_i, w, fma(nw_i, vj[c], a[c]));
+        }
+    }
+}
+
+// g: the matrix (row-major doubles, symmetric positive semi-definite); vws: 128 x 128 doubles of
+// scratch in global memory; qhat: r rows of 128 floats = sqrt(lambda_j) v_j, eigenvalues descending;
+// eig: r floats or NULL.  Returns (to every thread) whether the result was accepted; if not, nothing
+// was written.  All 1024 threads of the block must call it; L: kTriLdsBytes of LDS, 16-byte aligned.
+__device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, int r, float* qhat, float* eig,
+                                                 double* L) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = tid >> 3, l = tid & 7;
+    double* misc = L + kTriMisc;
+
+    // ---- load, scale by a power of two so that the largest entry is in [1, 2)
+    double a[16];
+    {
+        const double* src = g + i * kTriN + 16 * l;
+#pragma unroll
+        for (int c = 0; c < 16; c += 2) {
+            const double2 t = *reinterpret_cast<const double2*>(src + c);
+            a[c] = t.x;
+            a[c + 1] = t.y;
+        }
+    }
+    double amax = 0.0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) amax = fmax(amax, fabs(a[c]));
+    amax = tri_block_max(amax, misc, tid);
+    if (!(amax > 0.0) || !(amax < 1e300)) {
+        // zero matrix: zero eigenvalues, zero rows (also taken for NaN / Inf input: nothing sensible exists)
+        for (int e = tid; e < r * kTriN; e += kTriThreads) qhat[e] = 0.0f;
+        if (eig)
+            for (int e = tid; e < r; e += kTriThreads) eig[e] = 0.0f;
+        return true;
+    }
+    const int aexp = ((__double2hiint(amax) >> 20) & 0x7FF) - 1023;
+    const int sexp = aexp < -1000 ? -1000 : (aexp > 1000 ? 1000 : aexp);
+    const double down = tri_pow2(-sexp), up = tri_pow2(sexp);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) a[c] *= down;
+
+    // ---- 1. Householder reduction
+    if (tid < 4 * kTriN) L[tid] = 0.0;                   // column and product buffers: never read uninitialised
+    __syncthreads();
+    for (int kk = 0; kk < 8; ++kk) {
+        tri_step<0>(a, kk, i, l, tid, L);
+        tri_step<1>(a, kk, i, l, tid, L);
+        tri_step<2>(a, kk, i, l, tid, L);
+        tri_step<3>(a, kk, i, l, tid, L);
+        tri_step<4>(a, kk, i, l, tid, L);
+        tri_step<5>(a, kk, i, l, tid, L);
+        tri_step<6>(a, kk, i, l, tid, L);
+        tri_step<7>(a, kk, i, l, tid, L);
+        tri_step<8>(a, kk, i, l, tid, L);
+        tri_step<9>(a, kk, i, l, tid, L);
+        tri_step<10>(a, kk, i, l, tid, L);
+        tri_step<11>(a, kk, i, l, tid, L);
+        tri_step<12>(a, kk, i, l, tid, L);
+        tri_step<13>(a, kk, i, l, tid, L);
+        tri_step<14>(a, kk, i, l, tid, L);
+        tri_step<15>(a, kk, i, l, tid, L);
+    }
+    if (l == 7) {
+        if (i == kTriN - 2) L[kTriDd + kTriN - 2] = a[14];
+        if (i == kTriN - 1) {
+            L[kTriDd + kTriN - 1] = a[15];
+            L[kTriEe + kTriN - 2] = a[14];
+            L[kTriEe + kTriN - 1] = 0.0;
+            L[kTriBet + kTriN - 2] = 0.0;
+            L[kTriBet + kTriN - 1] = 0.0;
+        }
+    }
+    __syncthreads();
+    // the reflectors leave LDS (their block is needed for the vectors and factors) and come back for step 5
+    for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
+        *reinterpret_cast<double2*>(vws + e) = *reinterpret_cast<const double2*>(L + kTriX + e);
+
+    // ---- normalise T to max |entry| = 1
+    double tmax = 0.0;
+    if (tid < kTriN) tmax = fmax(fabs(L[kTriDd + tid]), fabs(L[kTriEe + tid]));
+    tmax = tri_block_max(tmax, misc, tid);                // > 0: the trace is preserved
+    const double tinv = 1.0 / tmax;
+    __syncthreads();
+    if (tid < kTriN) {
+        const double dn = L[kTriDd + tid] * tinv, en = L[kTriEe + tid] * tinv;
+        L[kTriDd + tid] = dn;
+        L[kTriEe + tid] = en;
+        L[kTriDe + 2 * tid] = dn;
+        if (tid + 1 < kTriN) L[kTriDe + 2 * (tid + 1) + 1] = en * en;
+        if (tid == 0) L[kTriDe + 1] = 0.0;
+    }
+    __syncthreads();
+
+    // ---- 2. the r largest eigenvalues by 9-section on Sturm counts
+    if (tid < kTriPts * r) {
+        const int j = tid / kTriPts, pt = tid % kTriPts;
+        const int below_target = kTriN - 1 - j;           // eigenvalue j (descending) has this many below it
+        double lo = -3.0001, hi = 3.0001;
+        const double* de = L + kTriDe;
+        for (int round = 0; round < kTriRounds; ++round) {
+            asm volatile("" ::: "memory");                // keep the 128 LDS reads inside the round (not hoisted into registers)
+            const double step = (hi - lo) * (1.0 / (kTriPts + 1));
+            const double x = fma(step, static_cast<double>(pt + 1), lo);
+            double p0 = 1.0, p1 = de[0] - x;
+            int cnt = static_cast<unsigned>(__double2hiint(p1)) >> 31;
+            for (int b = 1; b < kTriN; b += 8) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int ii = b + u;
+                    if (ii < kTriN) {
+                        const double2 t = *reinterpret_cast<const double2*>(de + 2 * ii);
+                        const double p2 = fma(t.x - x, p1, -(t.y * p0));
+                        cnt += static_cast<unsigned>(__double2hiint(p2) ^ __double2hiint(p1)) >> 31;
+                        p0 = p1;
+                        p1 = p2;
+                    }
+                }
+                // rescale the pair by a power of two (the larger one to [1, 2))
+                const double m = fmax(fabs(p0), fabs(p1));
+                const int ex = ((__double2hiint(m) >> 20) & 0x7FF) - 1023;
+                if (ex > -1000 && ex < 1000) {
+                    const double f = tri_pow2(-ex);
+                    p0 *= f;
+                    p1 *= f;
+                }
+            }
+            // the team's points are ascending: those with count <= target are a prefix
+            const unsigned long long mask = __ballot(cnt <= below_target);
+            const int nb = __popc(static_cast<unsigned>((mask >> (lane & ~(kTriPts - 1))) & ((1u << kTriPts) - 1u)));
+            const double nlo = nb == 0 ? lo : fma(step, static_cast<double>(nb), lo);
+            const double nhi = nb == kTriPts ? hi : fma(step, static_cast<double>(nb + 1), lo);
+            lo = nlo;
+            hi = nhi;
+        }
+        if (pt == 0) L[kTriLam + j] = 0.5 * (lo + hi);
+    }
+    __syncthreads();
+
+    // ---- 3. inverse iteration, one lane per vector
+    if (tid == 0) {
+        const double sep = 10.0 * 2.220446049250313e-16;  // coincident eigenvalues get shifts a few ulps apart
+        double prev = L[kTriLam];
+        L[kTriLam + 32] = prev;
+        for (int j = 1; j < r; ++j) {
+            double s = L[kTriLam + j];
+            s = s > prev - sep ? prev - sep : s;
+            L[kTriLam + 32 + j] = s;
+            prev = s;
+        }
+    }
+    // columns r .. 31 are padding (unit vectors, never used)
+    for (int e = tid; e < kTriN * 32; e += kTriThreads) {
+        const int row = e >> 5, colj = e & 31;
+        // start vectors: a fixed pseudo-random pattern in (-1, 1)
+        uint32_t h = static_cast<uint32_t>(row) * 2654435761u + static_cast<uint32_t>(colj) * 40503u + 12345u;
+        h ^= h >> 15;
+        h *= 2246822519u;
+        h ^= h >> 13;
+        const double rnd = (static_cast<double>(h >> 8) + 0.5) * (2.0 / 16777216.0) - 1.0;
+        L[kTriX + e] = colj < r ? rnd : (row == colj ? 1.0 : 0.0);
+    }
+    __syncthreads();
+    if (tid < r) {
+        const int j = tid;
+        const double shift = L[kTriLam + 32 + j];
+        const double pivmin = 2.0e-19;
+        const double* dn = L + kTriDd;
+        const double* en = L + kTriEe;
+        double* X = L + kTriX + j;
+        double* U0 = L + kTriU0 + j;
+        double* U1 = L + kTriU1 + j;
+        double* U2 = L + kTriU2 + j;
+        double scale = 1.0;
+        for (int it = 0; it < 2; ++it) {
+            // forward elimination with row interchanges, applied to the right-hand side on the fly
+            double ca = dn[0] - shift, cc = en[0], cf = 0.0, cb = X[0] * scale;
+            for (int row = 0; row < kTriN - 1; ++row) {
+                const double na = en[row], nc = dn[row + 1] - shift, nf = row + 1 < kTriN - 1 ? en[row + 1] : 0.0;
+                const double nb = X[32 * (row + 1)] * scale;
+                const bool keep = fabs(ca) >= fabs(na);
+                double pa = keep ? ca : na, pc = keep ? cc : nc, pf = keep ? cf : nf, pb = keep ? cb : nb;
+                const double oa = keep ? na : ca, oc = keep ? nc : cc, of = keep ? nf : cf, ob = keep ? nb : cb;
+                if (fabs(pa) < pivmin) pa = pa < 0.0 ? -pivmin : pivmin;
+                const double inv = tri_rcp(pa);
+                const double mlt = oa * inv;
+                U0[32 * row] = inv;
+                U1[32 * row] = pc;
+                U2[32 * row] = pf;
+                X[32 * row] = pb;
+                ca = fma(-mlt, pc, oc);
+                cc = fma(-mlt, pf, of);
+                cf = 0.0;
+                cb = fma(-mlt, pb, ob);
+            }
+            if (fabs(ca) < pivmin) ca = ca < 0.0 ? -pivmin : pivmin;
+            // back substitution
+            double x2 = 0.0, x1 = cb * tri_rcp(ca), big = fabs(x1);
+            X[32 * (kTriN - 1)] = x1;
+            for (int row = kTriN - 2; row >= 0; --row) {
+                const double x = (X[32 * row] - U1[32 * row] * x1 - U2[32 * row] * x2) * U0[32 * row];
+                X[32 * row] = x;
+                big = fmax(big, fabs(x));
+                x2 = x1;
+                x1 = x;
+            }
+            scale = big > 0.0 && big < 1e300 ? 1.0 / big : 1.0;
+        }
+        // unit 2-norm
+        double s2 = 0.0;
+        for (int row = 0; row < kTriN; ++row) {
+            const double x = X[32 * row] * scale;
+            s2 = fma(x, x, s2);
+        }
+        const double nrm = scale * (s2 > 0.0 ? 1.0 / sqrt(s2) : 0.0);
+        for (int row = 0; row < kTriN; ++row) X[32 * row] *= nrm;
+    }
+    __syncthreads();
+
+    // ---- orthonormality: Gram matrix of the 32 columns; Cholesky-QR (twice) only if it is not the identity
+    double* S = L + kTriS;
+    bool ok = true;
+    for (int pass = 0; pass < 3; ++pass) {
+        double dev = 0.0;
+        if (tid < 256) {
+            const int a2 = tid >> 4, b2 = tid & 15;
+            double s00 = 0.0, s01 = 0.0, s10 = 0.0, s11 = 0.0;
+            for (int row = 0; row < kTriN; ++row) {
+                const double2 xa = *reinterpret_cast<const double2*>(L + kTriX + 32 * row + 2 * a2);
+                const double2 xb = *reinterpret_cast<const double2*>(L + kTriX + 32 * row + 2 * b2);
+                s00 = fma(xa.x, xb.x, s00);
+                s01 = fma(xa.x, xb.y, s01);
+                s10 = fma(xa.y, xb.x, s10);
+                s11 = fma(xa.y, xb.y, s11);
+            }
+            S[(2 * a2) * 33 + 2 * b2] = s00;
+            S[(2 * a2) * 33 + 2 * b2 + 1] = s01;
+            S[(2 * a2 + 1) * 33 + 2 * b2] = s10;
+            S[(2 * a2 + 1) * 33 + 2 * b2 + 1] = s11;
+            // only the r real columns count (the padding columns are never used)
+            const double i00 = a2 == b2 ? 1.0 : 0.0;
+            const bool ra0 = 2 * a2 < r, ra1 = 2 * a2 + 1 < r, rb0 = 2 * b2 < r, rb1 = 2 * b2 + 1 < r;
+            dev = fmax(fmax(ra0 && rb0 ? fabs(s00 - i00) : 0.0, ra1 && rb1 ? fabs(s11 - i00) : 0.0),
+                       fmax(ra0 && rb1 ? fabs(s01) : 0.0, ra1 && rb0 ? fabs(s10) : 0.0));
+        }
+        dev = tri_block_max(dev, misc, tid);
+        if (!(dev == dev)) ok = false;
+        if (dev <= 1e-10 || !ok) break;
+        if (pass == 2) {
+            ok = dev <= kTriAccept;
+            break;
+        }
+        if (dev <= 1e-5) {
+            // nearly orthonormal (close eigenvalues, not coincident ones): one symmetric step
+            // X <- X (3/2 I - 1/2 S) squares the deviation
+            const int row = tid >> 3, j0 = 4 * (tid & 7);
+            const double* xr = L + kTriX + 32 * row;
+            double out[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = 0.0;
+            for (int k2 = 0; k2 < r; ++k2) {
+                const double xk = xr[k2];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) out[c] = fma(xk, S[k2 * 33 + j0 + c], out[c]);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = fma(-0.5, out[c], 1.5 * xr[j0 + c]);
+            __syncthreads();
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (j0 + c < r) L[kTriX + 32 * row + j0 + c] = out[c];
+            __syncthreads();
+            continue;
+        }
+        // Cholesky S = C C' in place (lower triangle), one wavefront, lane = row
+        if (wave == 0) {
+            int bad = 0;
+            for (int j = 0; j < r; ++j) {
+                double acc = 0.0;
+                if (lane < r && lane >= j) {
+                    acc = S[lane * 33 + j];
+                    for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[lane * 33 + k2], S[j * 33 + k2], acc);
+                }
+                const double piv = __shfl(acc, j, 64);
+                if (!(piv > 1e-280)) bad = 1;
+                const double rs = bad ? 0.0 : 1.0 / sqrt(piv);
+                if (lane < r && lane >= j) S[lane * 33 + j] = lane == j ? rs : acc * rs;      // diagonal: 1 / C_jj
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+            if (lane == 0) misc[32] = bad ? 1.0 : 0.0;
+        }
+        __syncthreads();
+        if (misc[32] != 0.0) {
+            ok = false;
+            break;
+        }
+        // X <- X C^-T : row by row, y_j = (x_j - sum_{k<j} C_jk y_k) / C_jj
+        if (tid < kTriN) {
+            double* xr = L + kTriX + 32 * tid;
+            double y[32];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                if (j < r) {                              // uniform
+                    double acc = xr[j];
+#pragma unroll
+                    for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[j * 33 + k2], y[k2], acc);
+                    y[j] = acc * S[j * 33 + j];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 32; ++j)
+                if (j < r) xr[j] = y[j];
+        }
+        __syncthreads();
+    }
+
+    // ---- 4. Rayleigh quotients and residuals: team of 32 lanes per vector, 4 elements per lane
+    const int vj = tid >> 5, sub = tid & 31;
+    double xv[4];
+    {
+        double num = 0.0, den = 0.0;
+        double yv[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int row = sub + 32 * m;
+            const double x = L[kTriX + 32 * row + vj];
+            const double xm = row > 0 ? L[kTriX + 32 * (row - 1) + vj] : 0.0;
+            const double xp = row < kTriN - 1 ? L[kTriX + 32 * (row + 1) + vj] : 0.0;
+            const double em = row > 0 ? L[kTriEe + row - 1] : 0.0;
+            const double y = fma(L[kTriDd + row], x, fma(em, xm, L[kTriEe + row] * xp));
+            xv[m] = x;
+            yv[m] = y;
+            num = fma(x, y, num);
+            den = fma(x, x, den);
+        }
+        num = tri_sum32(num);
+        den = tri_sum32(den);
+        const double rq = den > 0.0 ? num / den : 0.0;
+        double res = 0.0;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const double t = yv[m] - rq * xv[m];
+            res = fma(t, t, res);
+        }
+        res = tri_sum32(res);
+        if (sub == 0) L[kTriLam + 64 + vj] = rq;
+        double worst = vj < r ? sqrt(res) : 0.0;
+        if (!(worst == worst)) worst = 1e300;
+        worst = tri_block_max(worst, misc, tid);
+        if (!(worst <= kTriAccept)) ok = false;
+    }
+    if (!ok) return false;                                // uniform: every thread saw the same flags
+
+    // ---- 5. back-transformation; the reflectors come back from global memory into the vectors' and
+    // factors' LDS block (the vectors are in registers now)
+    __syncthreads();
+    __threadfence_block();
+    {
+        double* V = L + kTriX;
+        for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
+            *reinterpret_cast<double2*>(V + e) = *reinterpret_cast<const double2*>(vws + e);
+        __syncthreads();
+        for (int k = kTriN - 3; k >= 0; --k) {
+            const double beta = L[kTriBet + k];
+            if (beta == 0.0) continue;                    // uniform
+            double v[4], s = 0.0;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                v[m] = V[k * kTriN + sub + 32 * m];
+                s = fma(v[m], xv[m], s);
+            }
+            s = tri_sum32(s) * beta;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) xv[m] = fma(-s, v[m], xv[m]);
+        }
+    }
+
+    // ---- output: rank by eigenvalue, sign so that the largest component is positive, rows sqrt(lambda) v
+    if (vj < r) {
+        const double lam = L[kTriLam + 64 + vj];
+        int rank = 0;
+        for (int o = 0; o < r; ++o) {
+            const double lo = L[kTriLam + 64 + o];
+            rank += (lo > lam) || (lo == lam && o < vj);
+        }
+        double best = -1.0, bestv = 0.0;
+        int besti = kTriN;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const double av = fabs(xv[m]);
+            if (av > best) { best = av; bestv = xv[m]; besti = sub + 32 * m; }
+        }
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) {
+            const double ob = __shfl_xor(best, off, 64);
+            const double ov = __shfl_xor(bestv, off, 64);
+            const int oi = __shfl_xor(besti, off, 64);
+            if (ob > best || (ob == best && oi < besti)) { best = ob; bestv = ov; besti = oi; }
+        }
+        const double lam_true = fmax(lam, 0.0) * tmax * up;
+        const double sc = (bestv < 0.0 ? -1.0 : 1.0) * sqrt(lam_true);
+        float* dst = qhat + rank * kTriN;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) dst[sub + 32 * m] = static_cast<float>(xv[m] * sc);
+        if (eig && sub == 0) eig[rank] = static_cast<float>(lam_true);
+    }
+    return true;
+}
+
+}  // namespace squat

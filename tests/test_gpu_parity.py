@@ -294,6 +294,76 @@ def test_gram_and_subspace_match_oracle(dtype, hq, qpk, n):
             assert np.abs(qhat[j, k:]).max() <= 1e-3 * np.sqrt(ev[0])
 
 
+def _subspace_checks(q_np, r, qpk=1, scale_tol=1.0):
+    """Run squat_build_subspace on float32 queries [heads, n, 128] and check what is unique against the
+    oracle: eigenvalues, orthonormality of the rows / sqrt(eigenvalue), the eigen-equation, and the
+    projector-like matrix where the r-th gap defines it.  Returns the number of heads that the
+    tridiagonal route handed to the Jacobi kernel (the library keeps one int per head for that in the
+    last 256-byte-aligned block of its workspace)."""
+    qt = torch.from_numpy(q_np.astype(np.float32)).cuda()
+    n_kv = q_np.shape[0] // qpk
+    nbytes = squat.build_subspace_workspace(q_np.shape[1], n_kv, qpk, 128, r)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    qhat_t, eig_t, gram_t = squat.build_subspace(qt, qpk, r, want_gram=True, ws=ws)
+    torch.cuda.synchronize()
+    redone = int(ws[nbytes - ((4 * n_kv + 255) // 256) * 256:].view(torch.int32)[:n_kv].sum().item())
+    qhat, eig = qhat_t.cpu().numpy().astype(np.float64), eig_t.cpu().numpy().astype(np.float64)
+    for j in range(q_np.shape[0] // qpk):
+        Gm = O.gram(q_np[j * qpk:(j + 1) * qpk].astype(np.float64))
+        Qh, ev = O.subspace(q_np[j * qpk:(j + 1) * qpk].astype(np.float64), r)
+        top = max(ev[0], 1e-300)
+        assert np.all(np.abs(eig[j] - ev) <= 1e-5 * scale_tol * top), (j, np.abs(eig[j] - ev).max() / top)
+        assert np.all(np.diff(eig[j]) <= 0)
+        live = ev > 1e-6 * top
+        if live.any():
+            V = qhat[j][live] / np.sqrt(eig[j][live])[:, None]
+            assert np.abs(V @ V.T - np.eye(V.shape[0])).max() <= 1e-5
+            assert np.abs(Gm @ V.T - V.T * eig[j][live][None]).max() <= 2e-5 * scale_tol * top
+        assert np.abs(qhat[j][~live]).max(initial=0.0) <= 2e-3 * np.sqrt(top)
+        full = np.linalg.eigvalsh(Gm)[::-1]
+        gap = (full[r - 1] - full[r]) / top if r < 128 else 1.0
+        if gap > 1e-4:
+            err = np.linalg.norm(qhat[j].T @ qhat[j] - Qh.T @ Qh) / max(np.linalg.norm(Qh.T @ Qh), 1e-300)
+            assert err <= 1e-5 / gap, (j, err, gap)
+    return redone
+
+
+def test_subspace_special_spectra():
+    """Spectra that stress the eigen-solver for r <= 32 (tridiagonal reduction, Sturm-count search,
+    inverse iteration): decaying, flat, rank-deficient, coincident eigenvalues, a single direction,
+    zero, and wildly different magnitudes across heads."""
+    gen = synth.rng(1250)
+    d = 128
+    B, _ = np.linalg.qr(gen.standard_normal((d, d)))
+    heads = []
+    heads.append((B * (0.8 ** np.arange(d) * 30)) @ B.T)                      # decaying
+    heads.append(gen.standard_normal((d, d)))                                 # flat-ish, full rank
+    low = np.zeros((d, d)); low[:20] = gen.standard_normal((20, d))          # rank 20 < r
+    heads.append(low)
+    heads.append(np.sqrt(5.0) * B)                                            # Gram = 5 I: all eigenvalues coincide
+    rep = B * np.where(np.arange(d) < 10, 3.0, 1.0)                           # ten eigenvalues 9, the rest 1
+    heads.append(rep @ B.T)
+    one = np.zeros((d, d)); one[0] = gen.standard_normal(d)                   # a single direction
+    heads.append(one)
+    heads.append(np.zeros((d, d)))                                            # nothing
+    heads.append(1e-6 * gen.standard_normal((d, d)))                          # tiny
+    heads.append(3e4 * gen.standard_normal((d, d)))                           # huge
+    dg = np.zeros((d, d)); dg[np.arange(d), np.arange(d)] = np.arange(d, 0, -1.0)   # already diagonal
+    heads.append(dg)
+    q = np.stack(heads)
+    for r in (32, 16, 1):
+        assert _subspace_checks(q, r) == 0       # even these are accepted by the fast route (33 forces Jacobi)
+    _subspace_checks(q, 33)
+
+
+def test_subspace_many_random_heads_r32():
+    """64 heads of near-isotropic queries (close eigenvalues everywhere, the regime of the benchmark)."""
+    q = synth.queries(1260, 64, 700, planted_rank=0)
+    assert _subspace_checks(q, 32) == 0          # the fast route's own residual checks accepted every head
+    q = synth.queries(1261, 16, 300, planted_rank=0)
+    assert _subspace_checks(q, 32, qpk=4) == 0
+
+
 def test_subspace_rank_edge_cases():
     qt, qval = _queries(1200, 2, 64, synth.BF16, planted=0)
     q0, e0, _ = squat.build_subspace(qt, 1, 0)
