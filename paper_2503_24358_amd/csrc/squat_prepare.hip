@@ -115,8 +115,9 @@ __global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams 
 // Jacobi then needs no workgroup barrier (it is bound by synchronisation latency, not arithmetic), the
 // head's Qhat is staged once in LDS as fp32, and all intermediates stay in LDS:
 //   X = S^+ Qb = sum_i a_i (a_i . Qb) / mu_i^3   (rp x g),      W = -Qr^T X.
-__global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p) {
+__global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p, const int* need) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    if (need && need[blockIdx.x] == 0) return;             // done by the Cholesky kernel
     const int r = p.r, rp = p.rp, g = p.g;
     constexpr int QLD = kD + 1;       // odd row stride: column reads across rows hit distinct LDS banks
     const int ld = rp + 2;            // padded row: teams of 4 lanes read different rows at the same column
@@ -182,6 +183,162 @@ __global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p) {
     }
 }
 
+// r <= 32 and finite lambda: S = I/lambda + Qr Qr^T is positive definite with smallest eigenvalue
+// >= 1/lambda, so X = S^-1 Qb comes from a Cholesky factorisation instead of an eigen-decomposition.
+// One 512-thread workgroup per head does all panels, arranged so that no thread runs a long chain of
+// dependent LDS reads:
+//   - S: thread (i, k) accumulates the three 32-channel pieces of Q_i . Q_k side by side and sums them
+//     from the back (S_t needs the channels from t g on);
+//   - Cholesky: one wavefront per panel, lane = row, the row in REGISTERS, right-looking (the column
+//     being eliminated is broadcast with v_readlane);
+//   - triangular solves: every wavefront takes a few columns of Qb, lane = row again: the unknown just
+//     found is broadcast and every later row subtracts its multiple at once;
+//   - W = -Qr^T X with four accumulators per entry.
+// A panel whose pivots span more than 1e9 (lambda times the largest eigenvalue of Qr Qr^T that large)
+// sets the head's flag: the eigen-route kernel, launched afterwards, redoes exactly the flagged heads.
+constexpr int kCholThreads = 512;           // 256 registers per thread: the Cholesky keeps a 32-double row in them
+constexpr int kCholLd = 33;
+constexpr int kCholCols = 12;          // columns of Qb per wavefront in the solves (8 wavefronts x 12 = 96)
+
+__device__ __forceinline__ double chol_readlane(double v, int src) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
+}
+
+__global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepParams p, int* need) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int r = p.r, g = p.g, nsteps = p.nsteps;
+    constexpr int QLD = kD + 1;
+    const int head = blockIdx.x, tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    float* Qf = reinterpret_cast<float*>(smem);                                   // [32][129]
+    double* Sall = reinterpret_cast<double*>(smem + ((32 * QLD * sizeof(float) + 15) & ~size_t(15)));   // [nsteps][32][33]
+    double* Xall = Sall + nsteps * 32 * kCholLd;                                  // [nsteps][32][g]
+    int* bad = reinterpret_cast<int*>(Xall + nsteps * 32 * g);
+    const float* Q = p.qhat + static_cast<int64_t>(head) * r * kD;
+    for (int idx = tid; idx < 32 * kD; idx += kCholThreads)
+        Qf[(idx >> 7) * QLD + (idx & 127)] = idx < r * kD ? Q[idx] : 0.0f;
+    if (tid == 0) bad[0] = 0;
+    __syncthreads();
+
+    // S_t[i][k] = [i == k] / lambda + sum_{c >= (t+1) g} Q[i][c] Q[k][c]   (rows / columns >= r: identity)
+    for (int e = tid; e < 1024; e += kCholThreads) {
+        const int i = e >> 5, k = e & 31;
+        const float* qi = Qf + i * QLD;
+        const float* qk = Qf + k * QLD;
+        double piece[3] = {0.0, 0.0, 0.0};                // channels 32..63, 64..95, 96..127
+#pragma unroll 8
+        for (int c = 0; c < 32; ++c) {
+#pragma unroll
+            for (int b = 0; b < 3; ++b)
+                piece[b] = fma(static_cast<double>(qi[32 * (b + 1) + c]), static_cast<double>(qk[32 * (b + 1) + c]), piece[b]);
+        }
+        const double diag = i == k ? (i < r ? p.inv_lambda : 1.0) : 0.0;
+        for (int t = 0; t < nsteps; ++t) {
+            double s = diag;
+            for (int b = (t + 1) * (g / 32) - 1; b < 3; ++b) s += piece[b];
+            Sall[(t * 32 + i) * kCholLd + k] = s;
+        }
+    }
+    __syncthreads();
+
+    // Cholesky S = C C^T, one wavefront per panel; C goes back to LDS with 1 / C_jj on the diagonal
+    if (wave < nsteps) {
+        double* S = Sall + wave * 32 * kCholLd;
+        const int row = lane & 31;                        // lanes 32..63 mirror lanes 0..31 (and do not store)
+        double a[32];
+#pragma unroll
+        for (int c = 0; c < 32; ++c) a[c] = S[row * kCholLd + c];
+        double pmin = 1e300, pmax = 0.0;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const double piv = chol_readlane(a[j], j);
+            if (j < r) {
+                pmin = fmin(pmin, piv);
+                pmax = fmax(pmax, piv);
+            }
+            const double rs = piv > 0.0 ? 1.0 / sqrt(piv) : 0.0;
+            const double lj = a[j] * rs;                  // column j of C (rows > j), garbage above the diagonal
+            a[j] = row == j ? rs : lj;
+#pragma unroll
+            for (int k2 = j + 1; k2 < 32; ++k2) a[k2] = fma(-lj, chol_readlane(lj, k2), a[k2]);
+        }
+        if (lane < 32) {
+#pragma unroll
+            for (int c = 0; c < 32; ++c) S[row * kCholLd + c] = a[c];
+        }
+        if (lane == 0 && !(pmin > 1e-9 * pmax)) atomicOr(bad, 1);       // also catches NaN
+    }
+    __syncthreads();
+    if (bad[0]) {                                          // uniform: leave this head to the eigen route
+        if (tid == 0) need[head] = 1;
+        return;
+    }
+    if (tid == 0) need[head] = 0;
+
+    // X = S^-1 Qb: kCholCols columns per wavefront, lane = row
+    {
+        const int ncols = nsteps * g;
+        const int col0 = wave * kCholCols;
+        if (col0 < ncols) {
+            // (a wavefront's columns may straddle two panels: every column carries its own panel index)
+            const int row = lane & 31;
+            double bcol[kCholCols];
+            int tt[kCholCols], jj[kCholCols];
+#pragma unroll
+            for (int q = 0; q < kCholCols; ++q) {
+                const int col = min(col0 + q, ncols - 1);
+                tt[q] = col / g;
+                jj[q] = col % g;
+                bcol[q] = static_cast<double>(Qf[row * QLD + tt[q] * g + jj[q]]);
+            }
+            // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
+            for (int k = 0; k < 32; ++k) {
+#pragma unroll
+                for (int q = 0; q < kCholCols; ++q) {
+                    const double* S = Sall + tt[q] * 32 * kCholLd;
+                    const double cik = S[row * kCholLd + k];                  // row == k: 1 / C_kk
+                    const double yk = chol_readlane(bcol[q] * cik, k);        // lane k holds b_k / C_kk
+                    bcol[q] = row == k ? yk : (row > k ? fma(-cik, yk, bcol[q]) : bcol[q]);
+                }
+            }
+            // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k
+            for (int k = 31; k >= 0; --k) {
+#pragma unroll
+                for (int q = 0; q < kCholCols; ++q) {
+                    const double* S = Sall + tt[q] * 32 * kCholLd;
+                    const double cki = S[k * kCholLd + row];                  // row == k: 1 / C_kk
+                    const double xk = chol_readlane(bcol[q] * cki, k);
+                    bcol[q] = row == k ? xk : (row < k ? fma(-cki, xk, bcol[q]) : bcol[q]);
+                }
+            }
+            if (lane < 32) {
+#pragma unroll
+                for (int q = 0; q < kCholCols; ++q)
+                    if (col0 + q < ncols) Xall[(tt[q] * 32 + row) * g + jj[q]] = bcol[q];
+            }
+        }
+    }
+    __syncthreads();
+
+    // W_t[c][j] = -sum_k Q[k][(t+1) g + c] X_t[k][j], rounded to the fp16 grid as in the other kernels
+    float* U = p.update + static_cast<int64_t>(head) * kD * kD;
+    for (int t = 0; t < nsteps; ++t) {
+        const int c0 = (t + 1) * g, nrest = kD - c0;
+        const double* X = Xall + t * 32 * g;
+        for (int idx = tid; idx < nrest * g; idx += kCholThreads) {
+            const int c = idx / g, j = idx % g;
+            double s4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int k = 0; k < 32; ++k)
+                s4[k & 3] = fma(static_cast<double>(Qf[k * QLD + c0 + c]), X[k * g + j], s4[k & 3]);
+            const double sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+            U[(c0 + c) * kD + (c0 - g) + j] = static_cast<float>(static_cast<_Float16>(static_cast<float>(-sum)));
+        }
+    }
+}
+
 int team_size(int rp) {
     int ts = 64;
     while (ts > 1 && (rp / 2) * ts > kPrepThreads) ts >>= 1;
@@ -195,7 +352,8 @@ extern "C" size_t squat_prepare_workspace(int n_heads, int d, int r, int g) {
     const int nsteps = d / g - 1;
     const int rp = (r + 1) & ~1;
     const size_t per = static_cast<size_t>(rp) * (g + kD) * sizeof(double);
-    const size_t total = static_cast<size_t>(n_heads) * nsteps * per;
+    const size_t total = ((static_cast<size_t>(n_heads) * nsteps * per + 255) & ~size_t(255)) +
+                         ((static_cast<size_t>(n_heads) * sizeof(int) + 255) & ~size_t(255));   // + one flag per head
     return total < 256 ? 256 : total;
 }
 
@@ -242,7 +400,25 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
                 return SQUAT_E_HIP;
             done = true;
         }
-        hipLaunchKernelGGL(prepare_wave_kernel, dim3(n_heads), dim3(64 * nsteps), lds, s, p);
+        const int* need = nullptr;
+        if (!p.hard) {
+            int* flags = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) +
+                                                ((static_cast<size_t>(n_heads) * nsteps * p.rp * (g + kD) * sizeof(double) + 255) & ~size_t(255)));
+            const size_t clds = ((32 * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
+                                static_cast<size_t>(nsteps) * 32 * (kCholLd + g) * sizeof(double) + 16;
+            static bool cdone = false;
+            if (!cdone) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(prepare_chol_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
+                    return SQUAT_E_HIP;
+                cdone = true;
+            }
+            hipLaunchKernelGGL(prepare_chol_kernel, dim3(n_heads), dim3(kCholThreads), clds, s, p, flags);
+            rc = check_launch();
+            if (rc) return rc;
+            need = flags;
+        }
+        hipLaunchKernelGGL(prepare_wave_kernel, dim3(n_heads), dim3(64 * nsteps), lds, s, p, need);
         return check_launch();
     }
     const size_t lds = (static_cast<size_t>(p.rp) * p.rp + p.rp) * sizeof(double) + 16;
