@@ -404,6 +404,30 @@ def test_prepare_matches_oracle(r, lam, g):
             assert not U[h][t * g:(t + 1) * g, t * g:].any()
 
 
+def test_prepare_mixed_conditioning_picks_the_route_per_head():
+    """r <= 32, finite lambda: heads whose S = I / lambda + Qr Qr^T is well conditioned take the Cholesky
+    route (large rows of full rank, or zero rows at ordinary scale); a head with zero rows AND lambda *
+    sigma^2 ~ 1e12 (eigenvalues 1 / lambda next to sigma^2) is flagged and redone by the eigen route.  All
+    must match the oracle; the flags live in the last 256-byte-aligned block of the workspace."""
+    H, r, g, lam = 4, 20, 32, 50.0
+    gen = synth.rng(1450)
+    Qh = gen.standard_normal((H, r, 128)).astype(np.float32)
+    Qh[0] *= 3e4                              # large but of full row rank
+    Qh[1] *= 3e4                              # lambda sigma^2 ~ 50 * 9e8 * 100 ...
+    Qh[1, 8:] = 0.0                           # ... next to 1 / lambda
+    Qh[2, 8:] = 0.0                           # rank 8
+    Qh[3] *= 1e-3
+    qt = torch.from_numpy(Qh).cuda()
+    nbytes = squat.prepare_workspace(H, 128, r, g)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    U = squat.prepare(qt, lam, g, ws=ws).cpu().numpy().astype(np.float64)
+    flags = ws[nbytes - 256:].view(torch.int32)[:H].cpu().numpy()
+    assert list(flags) == [0, 1, 0, 0]
+    for h in range(H):
+        ref = O.update_matrix_lowrank(Qh[h].astype(np.float64), lam, g)
+        _assert_update_matches(U[h], ref)
+
+
 def test_prepare_hard_rank_deficient_tail():
     """lambda = +inf with r larger than the remaining channels of the last panel: pinv, not inverse."""
     H, r, g = 2, 48, 32
