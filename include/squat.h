@@ -95,7 +95,9 @@ const char* squat_strerror(int status);
  *           256-byte aligned.
  *   0 <= r <= d.  n_tokens >= 1.  The Gram products are exact for bf16/f16
  *   inputs and accumulate in fp32 within a slab of tokens, fp64 across slabs;
- *   the eigen-solver (cyclic one-sided Jacobi) works in fp64.
+ *   the eigen-solver works in fp64 (r <= 32: Householder tridiagonalisation,
+ *   Sturm-count search, inverse iteration; otherwise, or if that route's own
+ *   residual checks fail for a head, cyclic one-sided Jacobi).
  * ------------------------------------------------------------------------- */
 size_t squat_build_subspace_workspace(int64_t n_tokens, int n_kv_heads, int q_per_kv, int d, int r);
 
@@ -114,7 +116,9 @@ int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int 
  * A_t is its leading (t g x t g) block, B_t the block below it and H_t the
  * last g columns of A_t^{-1}.  The kernel evaluates the equivalent rank-r
  * form  -Qr^T (I/lambda + Qr Qr^T)^{-1} Qb  (Qb, Qr: the columns of Qhat in
- * and after block t) in fp64.  lambda = +INFINITY selects the limit
+ * and after block t) in fp64 (r <= 32 and finite lambda: by a Cholesky
+ * factorisation, heads that turn out ill-conditioned and all other cases by an
+ * eigen-decomposition).  lambda = +INFINITY selects the limit
  * -pinv(Qr) Qb (the equality constraint of Eq. (1)); lambda = 0 or r = 0
  * gives U = 0 (plain round-to-nearest).  Every entry is rounded to the nearest
  * fp16-representable number (relative 2^-12, entries must stay below 65504)

@@ -286,13 +286,7 @@ __global__ void __launch_bounds__(256) gram_reduce(const float* partial, int wgs
     }
 }
 
-#ifndef SQUAT_EIG_RESIDENT
-#define SQUAT_EIG_RESIDENT 1
-#endif
-#ifndef SQUAT_EIG_TS
-#define SQUAT_EIG_TS 16
-#endif
-constexpr int kEigTeam = SQUAT_EIG_TS;          // lanes per row pair
+constexpr int kEigTeam = 16;                    // lanes per row pair
 constexpr int kEigThreads = 64 * kEigTeam;
 constexpr int kEigLd = kD;       // rows are read with unit stride by consecutive lanes
 
@@ -318,11 +312,7 @@ __global__ void __launch_bounds__(kEigThreads) eig_kernel(const double* g64, int
     const double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     for (int i = threadIdx.x; i < kD * kD; i += kEigThreads) A[i] = g[i];
     __syncthreads();
-#if SQUAT_EIG_RESIDENT
     const int sweeps = jacobi_rows_resident<kEigThreads, kEigTeam, kD / kEigTeam>(A, kEigLd, nrm, flag, 60, 1e-13);
-#else
-    const int sweeps = jacobi_rows<kEigThreads, kEigTeam, kD / kEigTeam, true>(A, kD, kEigLd, nrm, flag, 60, 1e-13);
-#endif
     __syncthreads();
     if (sweeps_out && threadIdx.x == 0) sweeps_out[kvh] = sweeps;
 
