@@ -23,6 +23,8 @@ Parity status of each function:
                                 soft and hard invariants), both grouping axes
   CacheOracle                   pinned (counts against l mod R by hand, stores
                                 against one-shot quantization of the prefix)
+  key_scores_rope, rope_rotate  pinned (norm preservation, relative-position identity, explicit
+                                2x2 rotations, zero angle = key_scores)
   key_scores                    pinned (element loops, one-hot queries, closed
                                 form for constant codes)
   dequantize_keys, pack/unpack  pinned (definition of deq; pack o unpack = id,
@@ -40,7 +42,7 @@ __all__ = [
     "update_matrix_lemma", "update_matrix_kkt", "update_matrix_lowrank",
     "rtn_group", "quantize_keys", "dequantize_keys",
     "pack_codes", "unpack_codes", "pack_codes_tokens", "unpack_codes_tokens",
-    "replay_classify", "key_scores", "CacheOracle",
+    "replay_classify", "key_scores", "key_scores_rope", "rope_rotate", "CacheOracle",
 ]
 
 
@@ -388,6 +390,31 @@ def key_scores(q: np.ndarray, codes: np.ndarray, scale: np.ndarray, zero: np.nda
     """
     khat = dequantize_keys(codes, scale, zero, G, axis=axis)
     return float(out_scale) * (np.asarray(q, dtype=np.float64) @ khat.T)
+
+
+def rope_rotate(x: np.ndarray, positions: np.ndarray, inv_freq: np.ndarray) -> np.ndarray:
+    """Rotary position embedding of rows x (n, d) at integer positions (n,): channel pairs (c, c + d/2),
+    c < d/2, are rotated by the angle positions * inv_freq[c]:
+        x'_c       = x_c cos - x_{c+d/2} sin
+        x'_{c+d/2} = x_{c+d/2} cos + x_c sin
+    (the "rotate half" convention of the Llama models the paper evaluates).  float64."""
+    x = np.asarray(x, dtype=np.float64)
+    half = x.shape[-1] // 2
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * np.asarray(inv_freq, dtype=np.float64)[None, :]
+    c, s_ = np.cos(ang), np.sin(ang)
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * c - b * s_, b * c + a * s_], axis=-1)
+
+
+def key_scores_rope(q: np.ndarray, codes: np.ndarray, scale: np.ndarray, zero: np.ndarray, G: int,
+                    inv_freq: np.ndarray, pos0: int = 0, out_scale: float = 1.0) -> np.ndarray:
+    """Logits against keys that were quantized BEFORE the rotary embedding (the SQuat-pre variant of
+    Section 4: the cache holds pre-RoPE keys and positions are applied on the fly after
+    dequantization): out_scale * q . RoPE_{pos0 + t}(deq(code_t)).  q is taken as given (the caller
+    has already rotated it to its own position).  Per-token groups.  Returns (n_q, n) float64."""
+    khat = dequantize_keys(codes, scale, zero, G)
+    rot = rope_rotate(khat, pos0 + np.arange(khat.shape[0]), inv_freq)
+    return float(out_scale) * (np.asarray(q, dtype=np.float64) @ rot.T)
 
 
 class CacheOracle:

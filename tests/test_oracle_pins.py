@@ -345,6 +345,43 @@ def test_key_scores_are_the_definition():
     assert abs(got[i, t] - acc) <= 1e-12 * max(1.0, abs(acc))
 
 
+def test_rope_logits_are_rotations_applied_after_dequantization():
+    """rope_rotate is a position-dependent rotation of the channel pairs (c, c + 64): it preserves
+    norms, composes additively in the position (so logits depend on relative positions only), equals
+    explicit 2 x 2 rotations, and at angle zero key_scores_rope is key_scores."""
+    gen = np.random.default_rng(11)
+    n, d, G = 6, 128, 32
+    inv_freq = 10000.0 ** (-np.arange(64) / 64.0)
+    x = gen.standard_normal((n, d))
+    pos = np.array([0, 1, 7, 100, 4095, 131071])
+    y = O.rope_rotate(x, pos, inv_freq)
+    assert np.allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-13)
+    assert np.array_equal(y[0], x[0])                                   # position 0: identity
+    for t in (2, 4):
+        for c in (0, 5, 63):
+            ang = pos[t] * inv_freq[c]
+            R = np.array([[np.cos(ang), -np.sin(ang)], [np.sin(ang), np.cos(ang)]])
+            assert np.allclose(R @ np.array([x[t, c], x[t, c + 64]]), [y[t, c], y[t, c + 64]], rtol=1e-12, atol=1e-12)
+    # composition: rotating by p then by m equals rotating by p + m
+    z = O.rope_rotate(O.rope_rotate(x, pos, inv_freq), np.full(n, 17), inv_freq)
+    assert np.allclose(z, O.rope_rotate(x, pos + 17, inv_freq), rtol=1e-9, atol=1e-9)
+    # relative positions: (R_m q) . (R_p k) = q . (R_{p-m} k)
+    q = gen.standard_normal((2, d))
+    m = 50
+    lhs = O.rope_rotate(q, np.full(2, m), inv_freq) @ O.rope_rotate(x, pos + m, inv_freq).T
+    assert np.allclose(lhs, q @ O.rope_rotate(x, pos, inv_freq).T, rtol=1e-9, atol=1e-9)
+    codes = gen.integers(0, 4, size=(n, d)).astype(np.uint8)
+    scale = gen.uniform(0.1, 2.0, size=(n, d // G)).astype(np.float16)
+    zero = gen.standard_normal((n, d // G)).astype(np.float16)
+    assert np.array_equal(O.key_scores_rope(q, codes, scale, zero, G, np.zeros(64), 9, 0.5),
+                          O.key_scores(q, codes, scale, zero, G, 0.5))
+    got = O.key_scores_rope(q, codes, scale, zero, G, inv_freq, pos0=3, out_scale=0.5)
+    back = O.dequantize_keys(codes, scale, zero, G)
+    for t in range(n):
+        want = 0.5 * q @ O.rope_rotate(back[t:t + 1], np.array([3 + t]), inv_freq)[0]
+        assert np.allclose(got[:, t], want, rtol=1e-12, atol=1e-12)
+
+
 def test_cache_bookkeeping_follows_algorithm_1():
     """Prefill split r = l mod R, flush every R decoded keys, values lag R tokens behind.  Per-token
     groups make every key independent, so whatever the order of the flushes the quantized store must
