@@ -220,6 +220,19 @@ def main():
     out["key_scores"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bytes_per_key": sbytes // n_keys,
                          "us": ts * 1e3, "keys_per_s": n_keys / (ts * 1e-3),
                          "frac_of_hbm_peak": sbytes / (ts * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # the pre-RoPE variant of the same consumer: keys dequantized, rotated to their positions and rounded to
+    # fp16 in registers before the contraction (bound by vector arithmetic, not by HBM)
+    inv_freq = (10000.0 ** (-torch.arange(64, dtype=torch.float64, device=dev) / 64.0)).float()
+    tr = timed(lambda: squat.key_scores_rope(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, inv_freq, 0,
+                                             d ** -0.5, out=logits), reps=10)
+    out["key_scores_rope"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bound": "alu", "us": tr * 1e3,
+                              "keys_per_s": n_keys / (tr * 1e-3), "frac_of_hbm_peak": sbytes / (tr * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "valu_instructions_per_16_keys": 270,
+                              # 270 wave64 instructions per 16 keys = 1080 lane-operations per key; peak: 256 CUs x 4 SIMDs
+                              # x 16 lanes x 2.4 GHz (packed fp32 is switched off in this build)
+                              "alu_lane_ops_per_s": n_keys / (tr * 1e-3) * 1080,
+                              "alu_peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
+                              "alu_frac": n_keys / (tr * 1e-3) * 1080 / (256 * 4 * 16 * 2.4e9)}
     if args.variants:
         out["variants"] = []
         for bits, G, g, use_update in [(2, 32, 32, True), (2, 32, 64, True), (4, 32, 32, True), (4, 32, 64, True),

@@ -12,7 +12,8 @@
  *
  * squat_key_scores is the decode-side consumer of that store (attention
  * logits straight from the codes); squat_key_scores_per_channel is the same
- * for the per-channel store.
+ * for the per-channel store, squat_key_scores_rope for keys stored before the
+ * rotary position embedding.
  *
  * squat_quantize_keys groups every key's channels (statistics per token); the
  * pair squat_quantize_keys_per_channel / squat_dequantize_keys_per_channel is
@@ -276,6 +277,32 @@ int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_
                      const void* q, squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
                      int64_t q_stride_head, float out_scale, float* scores,
                      int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
+ * squat_key_scores_rope  (Section 4: the pre-RoPE variant, which quantizes and
+ * stores keys before the rotary position embedding and applies positions on
+ * the fly after dequantization; Section 2: deq).
+ *
+ * scores[b, hq, t] = out_scale * sum_c q[b, hq, c] * RoPE_{pos0 + t}(deq(code[b, h, t, :]))[c]
+ * for the KV head h = hq / q_per_kv, where RoPE_p rotates every channel pair
+ * (c, c + 64), c < 64, by the angle p * inv_freq[c]:
+ *     x'_c = x_c cos - x_{c+64} sin,    x'_{c+64} = x_{c+64} cos + x_c sin.
+ * The queries are taken as given (already rotated to their own position).
+ *
+ *   codes, scale, zero, q, q_per_kv, out_scale, scores and the strides   as for
+ *            squat_key_scores (per-token store).
+ *   inv_freq [64] float, device memory: the rotary frequencies (theta^(-c/64),
+ *            or any scaled variant).
+ *   pos0     position of token 0 of the store, 0 <= pos0 < 2^40.
+ *   Accuracy: the rotated key is rounded to fp16 before the contraction
+ *   (relative 2^-11 per channel); angles are exact to ~1e-5 rad.
+ * ------------------------------------------------------------------------- */
+int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                          int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
+                          const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt,
+                          int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head, float out_scale,
+                          float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                          squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
  * squat_key_scores_per_channel  (decoding phase of Algorithm 1 with the

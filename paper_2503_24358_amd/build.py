@@ -13,7 +13,8 @@ OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libsquat.so")
 
 SOURCES = ["squat_api.cpp", "squat_quantize.hip", "squat_quantize_pc.hip", "squat_dequantize.hip",
-           "squat_subspace.hip", "squat_prepare.hip", "squat_scores.hip", "squat_scores_pc.hip", "squat_cache.hip"]
+           "squat_subspace.hip", "squat_prepare.hip", "squat_scores.hip", "squat_scores_pc.hip", "squat_scores_rope.hip",
+           "squat_cache.hip"]
 
 # Packed-fp32 VALU ops are switched off on purpose (build flags).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -32,7 +33,8 @@ def _hipcc() -> str:
 # instructions: keep those results in the ordinary register file instead of the accumulation registers
 # (saves one copy per result register).
 EXTRA = {"squat_scores.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-         "squat_scores_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+         "squat_scores_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "squat_scores_rope.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src: str) -> str:

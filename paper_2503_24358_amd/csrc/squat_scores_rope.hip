@@ -1,0 +1,362 @@
+// squat_key_scores_rope: attention logits against keys that were quantized BEFORE
+// the rotary position embedding (the pre-RoPE variant of Section 4: the cache
+// stores pre-RoPE keys and applies positions on the fly after dequantization),
+//     scores[b, hq, t] = out_scale * q . RoPE_{pos0 + t}(deq(code_t)),
+// channel pairs (c, c + 64) rotated by (pos0 + t) * inv_freq[c]; per-token store.
+//
+// The rotation sits between the codes and the contraction, so the codes cannot
+// go to the matrix cores raw as in squat_key_scores: every key is dequantized in
+// registers (code * Delta + m, fp32), rotated, rounded to fp16 and only then
+// multiplied with the fp16 high/low rows of the queries
+// (v_mfma_f32_16x16x32_f16, token = column, (query head, part) = row).  This
+// kernel is bound by vector arithmetic (270 instructions per 16 tokens against
+// about 60 in the unrotated kernel), which is the price of that variant; it
+// still never writes a key to memory.
+//
+// A lane owns, for its token, channels 32 g + 8 kb + i (g < 4, i < 8): both
+// members of every rotary pair (chunks g and g + 2), so the rotation needs no
+// lane exchange.  cos / sin of the lane's 16 angles are carried in registers
+// and advanced by 16 positions per unit with the addition theorems; they are
+// seeded per wavefront from fp64 range reduction (position * inv_freq reduced to
+// a fraction of a turn before the fp32 sincospi), so the recurrence runs for at
+// most ~48 steps (error ~ 1e-5 of a radian, far below the fp16 rounding of the
+// rotated key, 2^-11 relative, which sets the accuracy of this call).
+#include "squat_internal.h"
+
+using namespace squat;
+
+namespace {
+
+constexpr int kRopeDepth = 3;          // units whose loads are in flight per wavefront
+#define RP_LOAD(p) __builtin_nontemporal_load(p)
+
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+constexpr int kRopeUnit = 16;          // tokens per matrix product (MFMA N)
+constexpr int kRopeMaxUnitsPerWave = 32;
+constexpr int kRopeMinUnitsPerWave = 4;
+constexpr int kRopeWaves = 4;
+
+struct RopeParams {
+    const uint32_t* codes;
+    const uint16_t* scale;
+    const uint16_t* zero;
+    const unsigned char* q;
+    const float* inv_freq;           // [64]
+    int64_t pos0;
+    int q_dt;
+    int64_t qsb, qsh;                // query strides in ELEMENTS
+    float* scores;
+    int64_t ssb, ssh;
+    int64_t n_tokens;
+    int n_kv_heads;
+    int qpk;
+    float out_scale;
+    int units_per_wave;
+};
+
+__device__ __forceinline__ uint32_t pack_h2(_Float16 lo, _Float16 hi) {
+    return static_cast<uint32_t>(__builtin_bit_cast(uint16_t, lo)) |
+           (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
+}
+
+// cos and sin of position * freq: the product is reduced to a fraction of a turn in fp64 first
+__device__ __forceinline__ void turn_sincos(double position, float freq, float& c, float& s) {
+    const double turns = position * static_cast<double>(freq) * 0.15915494309189535;   // / (2 pi)
+    const double frac = turns - rint(turns);                                           // [-0.5, 0.5]
+    sincospif(static_cast<float>(2.0 * frac), &s, &c);
+}
+
+template <int BITS, int NG, int QDT>
+__global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(const RopeParams p) {
+    constexpr int WPK = kD * BITS / 32;                   // packed words per key
+    constexpr int CPG = 4 / NG;                           // 32-channel chunks per group
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int kb = lane >> 4;                             // K block of an operand / row block of the result
+    const int col = lane & 15;                            // operand row (A) or token (B, result)
+    const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
+    const int64_t b = bh / p.n_kv_heads;
+    const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
+
+    // ---- the KV head's queries -> LDS as fp32 (rows past q_per_kv zero); rotation of 16 positions per
+    // frequency -> LDS
+    constexpr int QLD = kD + 1;
+    __shared__ float qlds[8 * QLD];
+    __shared__ float step_cs[2 * 64];
+    {
+        const int e0 = 4 * static_cast<int>(threadIdx.x);
+        const int qrow = e0 / kD, qch = e0 % kD;
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (qrow < p.qpk) {
+            const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
+            if constexpr (QDT == SQUAT_F32) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
+                v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+            } else {
+                const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
+                    v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
+                                             : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qlds[qrow * QLD + qch + i] = v[i];
+        if (threadIdx.x < 64) {
+            float c, s;
+            turn_sincos(static_cast<double>(kRopeUnit), p.inv_freq[threadIdx.x], c, s);
+            step_cs[2 * threadIdx.x] = c;
+            step_cs[2 * threadIdx.x + 1] = s;
+        }
+    }
+    __syncthreads();
+
+    // ---- A operands: row `col` = (query head col / 2, fp16 high / low part col % 2);
+    // register r of chunk g holds K = 8 kb + 2 r + {0, 1}  <->  channels 32 g + 8 kb + 2 r + {0, 1}
+    const int qh = col >> 1, part = col & 1;
+    u32x4 aop[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            _Float16 h[2];
+#pragma unroll
+            for (int pp = 0; pp < 2; ++pp) {
+                const float v = qlds[qh * QLD + 32 * g + 8 * kb + 2 * r + pp];
+                const _Float16 hi = static_cast<_Float16>(v);
+                h[pp] = part == 0 ? hi : static_cast<_Float16>(v - static_cast<float>(hi));
+            }
+            aop[g][r] = pack_h2(h[0], h[1]);
+        }
+
+    // ---- this wavefront's 16-token units
+    const int n_units = static_cast<int>((p.n_tokens + kRopeUnit - 1) / kRopeUnit);
+    const int u0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
+    const int u1 = min(u0 + p.units_per_wave, n_units);
+    if (u0 >= u1) return;                                 // after the last workgroup barrier
+
+    // rotary state of this lane: frequency index 8 g' + i  <->  channel pair (32 g' + 8 kb + i, + 64)
+    float cs[16], sn[16], dc[16], ds[16];
+    {
+        const double position = static_cast<double>(p.pos0 + static_cast<int64_t>(u0) * kRopeUnit + col);
+#pragma unroll
+        for (int f = 0; f < 16; ++f) {
+            const int ch = 32 * (f >> 3) + 8 * kb + (f & 7);
+            turn_sincos(position, p.inv_freq[ch], cs[f], sn[f]);
+            dc[f] = step_cs[2 * ch];
+            ds[f] = step_cs[2 * ch + 1];
+        }
+    }
+
+    const int64_t row0 = bh * p.n_tokens;
+    const int widx0 = BITS == 2 ? (kb >> 1) : kb;         // word of chunk 0 this lane unpacks
+    const uint32_t wshift = BITS == 2 ? 16u * (kb & 1) : 0u;
+    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
+    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    const float fin = p.out_scale;
+
+    // loads: per unit ONE 16-byte load by the lanes that cover the unit's codes and ONE load of the
+    // scales and zero-points, through a small per-wavefront LDS tile (as in the unrotated kernel)
+    constexpr int PPT = WPK / 4;
+    constexpr int CL = kRopeUnit * PPT;
+    constexpr int CS = WPK * 4 + 16;
+    constexpr int META0 = kRopeUnit * CS;
+    constexpr int TILE = META0 + 256;
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[kRopeWaves * TILE];
+    unsigned char* lds = lds_all + wave * TILE;
+    struct Raw {
+        u32x4 c;
+        u32x2 m;
+    };
+    const int n_tok = static_cast<int>(p.n_tokens);
+    const int ml = BITS == 2 ? lane - 32 : lane;
+    const bool is_c = lane < CL, is_m = ml >= 0 && ml < 32;
+    const int c_tok = lane / PPT, c_piece = lane % PPT;
+    const int m_tok = ml & 15;
+    const uint32_t* c_base = p.codes + row0 * WPK + c_piece * 4;
+    const uint16_t* m_base = ((ml & 16) ? p.zero : p.scale) + row0 * NG;
+    auto fetch = [&](int u, Raw& r) {
+        r.c = u32x4{0u, 0u, 0u, 0u};
+        r.m = u32x2{0u, 0u};
+        if (is_c) {
+            const int t = min(u * kRopeUnit + c_tok, n_tok - 1);
+            r.c = RP_LOAD(reinterpret_cast<const u32x4*>(c_base + static_cast<uint32_t>(t) * WPK));
+        }
+        if (is_m) {
+            const int t = min(u * kRopeUnit + m_tok, n_tok - 1);
+            if constexpr (NG == 4) {
+                r.m = RP_LOAD(reinterpret_cast<const u32x2*>(m_base + static_cast<uint32_t>(t) * 4));
+            } else if constexpr (NG == 2) {
+                r.m[0] = RP_LOAD(reinterpret_cast<const uint32_t*>(m_base + static_cast<uint32_t>(t) * 2));
+            } else {
+                r.m[0] = RP_LOAD(m_base + static_cast<uint32_t>(t));
+            }
+        }
+    };
+
+    auto compute = [&](int u, const Raw& raw) {
+        // registers -> LDS tile -> the words of this lane's K block, the metadata of its token
+        if (is_c) *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) = raw.c;
+        if (is_m) *reinterpret_cast<u32x2*>(lds + META0 + (ml & 16) * 8 + m_tok * 8) = raw.m;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t w[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4) >> wshift;
+        const u32x2 sv = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
+        const u32x2 zv = *reinterpret_cast<const u32x2*>(lds + META0 + 128 + col * 8);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        float sc[NG], zp[NG];
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            const uint32_t sw = gi < 2 ? sv[0] : sv[1], zw = gi < 2 ? zv[0] : zv[1];
+            sc[gi] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>((gi & 1) ? (sw >> 16) : (sw & 0xFFFFu))));
+            zp[gi] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>((gi & 1) ? (zw >> 16) : (zw & 0xFFFFu))));
+        }
+        // dequantize this lane's 32 channels (Section 2: code * Delta + m)
+        float k[4][8];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t code = (w[g] >> (BITS * i)) & ((1u << BITS) - 1u);
+                k[g][i] = fmaf(static_cast<float>(code), sc[g / CPG], zp[g / CPG]);
+            }
+        // rotate the pairs (chunk g', chunk g' + 2), then move the angles on by 16 positions
+#pragma unroll
+        for (int f = 0; f < 16; ++f) {
+            const int g = f >> 3, i = f & 7;
+            const float a = k[g][i], bb = k[g + 2][i];
+            k[g][i] = fmaf(a, cs[f], -(bb * sn[f]));
+            k[g + 2][i] = fmaf(bb, cs[f], a * sn[f]);
+            const float c2 = fmaf(cs[f], dc[f], -(sn[f] * ds[f]));
+            sn[f] = fmaf(sn[f], dc[f], cs[f] * ds[f]);
+            cs[f] = c2;
+        }
+        f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            u32x4 bop;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                bop[r] = pack_h2(static_cast<_Float16>(k[g][2 * r]), static_cast<_Float16>(k[g][2 * r + 1]));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]), __builtin_bit_cast(half8, bop),
+                                                         acc, 0, 0, 0);
+        }
+        // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
+        const int tok = u * kRopeUnit + col;
+        if (tok < n_tok) {
+            if (st0) __builtin_nontemporal_store(fin * (acc[0] + acc[1]), out0 + tok);
+            if (st1) __builtin_nontemporal_store(fin * (acc[2] + acc[3]), out0 + p.ssh + tok);
+        }
+    };
+
+    // software pipeline; every unit of the range is computed in order (the angles advance with it)
+    Raw ring[kRopeDepth];
+#pragma unroll
+    for (int i = 0; i < kRopeDepth; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
+    for (int u = u0; u < u1; u += kRopeDepth) {
+#pragma unroll
+        for (int i = 0; i < kRopeDepth; ++i) {
+            const Raw cur = ring[i];
+            fetch(min(u + i + kRopeDepth, u1 - 1), ring[i]);
+            if (u + i < u1) compute(u + i, cur);
+        }
+    }
+}
+
+template <int BITS, int NG>
+int launch_dt(const RopeParams& p, dim3 grid, hipStream_t s) {
+    const dim3 block(kRopeWaves * kWave);
+    switch (p.q_dt) {
+        case SQUAT_F32: hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, SQUAT_F32>), grid, block, 0, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, SQUAT_F16>), grid, block, 0, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, SQUAT_BF16>), grid, block, 0, s, p); break;
+        default: return SQUAT_E_BADDTYPE;
+    }
+    return check_launch();
+}
+
+template <int BITS>
+int launch_ng(int ng, const RopeParams& p, dim3 grid, hipStream_t s) {
+    switch (ng) {
+        case 4: return launch_dt<BITS, 4>(p, grid, s);
+        case 2: return launch_dt<BITS, 2>(p, grid, s);
+        case 1: return launch_dt<BITS, 1>(p, grid, s);
+    }
+    return SQUAT_E_BADSHAPE;
+}
+
+}  // namespace
+
+extern "C" int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                     int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
+                                     const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt,
+                                     int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head, float out_scale,
+                                     float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                                     squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
+    if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0 || n_tokens >= (int64_t(1) << 25)) return SQUAT_E_BADSHAPE;
+    if (pos0 < 0 || pos0 >= (int64_t(1) << 40)) return SQUAT_E_BADSHAPE;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (!(out_scale == out_scale)) return SQUAT_E_BADVALUE;
+    if (n_batch == 0 || n_kv_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!codes || !scale || !zero || !q || !scores || !inv_freq) return SQUAT_E_NULLPTR;
+    if (q_stride_head < d || q_stride_batch < 0 || s_stride_head < n_tokens || s_stride_batch < 0) return SQUAT_E_BADSHAPE;
+    if ((q_stride_head % 8) || (q_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(codes, 16) || !aligned(scale, 8) || !aligned(zero, 8) || !aligned(scores, 4) || !aligned(q, 16) ||
+        !aligned(inv_freq, 4))
+        return SQUAT_E_ALIGN;
+
+    RopeParams p;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.q = static_cast<const unsigned char*>(q);
+    p.inv_freq = inv_freq;
+    p.pos0 = pos0;
+    p.q_dt = static_cast<int>(q_dt);
+    p.qsb = q_stride_batch;
+    p.qsh = q_stride_head;
+    p.scores = scores;
+    p.ssb = s_stride_batch;
+    p.ssh = s_stride_head;
+    p.n_tokens = n_tokens;
+    p.n_kv_heads = n_kv_heads;
+    p.qpk = q_per_kv;
+    p.out_scale = out_scale;
+
+    // workgroups along the sequence: about kRopeWaves * kRopeMaxUnitsPerWave units each, spread evenly
+    const int64_t n_units = (n_tokens + kRopeUnit - 1) / kRopeUnit;
+    const int64_t slab = static_cast<int64_t>(kRopeWaves) * kRopeMaxUnitsPerWave;
+    int64_t gx = (n_units + slab / 2) / slab;
+    if (gx < 1) gx = 1;
+    int64_t upw = (n_units + kRopeWaves * gx - 1) / (kRopeWaves * gx);
+    if (upw < kRopeMinUnitsPerWave) upw = kRopeMinUnitsPerWave;
+    p.units_per_wave = static_cast<int>(upw);
+    gx = (n_units + kRopeWaves * upw - 1) / (kRopeWaves * upw);
+    const int64_t bh = n_batch * n_kv_heads;
+    int64_t gy = bh, gz = 1;
+    if (gy > 65535) {
+        gy = 0;
+        for (int64_t cand = 65535; cand >= 1; --cand)
+            if (bh % cand == 0) { gy = cand; break; }
+        gz = bh / gy;
+    }
+    if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? launch_ng<2>(128 / group, p, grid, s) : launch_ng<4>(128 / group, p, grid, s);
+}

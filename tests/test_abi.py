@@ -168,6 +168,23 @@ def test_key_scores_argument_validation_happens_before_any_launch():
     assert kp(codes=odd) == -4
     assert kp(scale=odd) == -4
     assert kp(n=0) == 0
+    kr = lambda **kw: L.squat_key_scores_rope(  # noqa: E731
+        kw.get("codes", fake), fake, fake, 1, 2, kw.get("n", 64), kw.get("d", 128), kw.get("bits", 2),
+        kw.get("G", 32), kw.get("freq", fake), kw.get("pos0", 0), kw.get("q", fake), kw.get("dt", 2),
+        kw.get("qpk", 4), 1024, kw.get("qsh", 128), kw.get("os", 1.0), kw.get("out", fake), 8 * 64,
+        kw.get("ssh", 64), None)
+    assert kr(d=64) == -2
+    assert kr(bits=3) == -2
+    assert kr(G=16) == -2
+    assert kr(qpk=9) == -2
+    assert kr(pos0=-1) == -2
+    assert kr(dt=4) == -3
+    assert kr(os=float("nan")) == -7
+    assert kr(freq=None) == -1
+    assert kr(q=None) == -1
+    assert kr(ssh=32) == -2
+    assert kr(codes=odd) == -4
+    assert kr(n=0) == 0
 
 
 def test_cache_configuration_and_creation_are_validated_on_the_host():

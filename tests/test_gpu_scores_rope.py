@@ -1,0 +1,119 @@
+"""GPU parity of squat_key_scores_rope (logits against keys stored BEFORE the rotary embedding: the
+key is dequantized, rotated to its position, and only then contracted with the query) against the
+float64 oracle.  The rotated key reaches the matrix cores rounded to fp16 (relative 2^-11 per channel),
+the queries as exact fp16 high/low pairs, the angles are good to ~1e-5 rad: worst case 2^-11 * sum_c
+|q_c| |k_rot_c| = 4.9e-4; the test allows 6e-4 (observed ~1e-4: the roundings do not line up), inside
+the 1e-3 relative tolerance the build states for projections."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import squat_oracle as O
+from paper_2503_24358_amd import squat, synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+INV_FREQ = (10000.0 ** (-np.arange(64) / 64.0)).astype(np.float32)
+
+
+def _store(seed, B, H, n, bits, G):
+    gen = synth.rng(seed)
+    x = synth.keys(seed + 1, H, n, batch=B)
+    codes = np.empty((B, H, n, 128), dtype=np.uint8)
+    scale = np.empty((B, H, n, 128 // G), dtype=np.float16)
+    zero = np.empty_like(scale)
+    for b in range(B):
+        for h in range(H):
+            out = O.quantize_keys(x[b, h].astype(np.float64), None, bits, G, 128)
+            codes[b, h], scale[b, h], zero[b, h] = out["codes"], out["scale"], out["zero"]
+    return gen, codes, scale, zero
+
+
+def _dev(codes, scale, zero, bits):
+    words = O.pack_codes(codes, bits)
+    return (torch.from_numpy(words.view(np.int32)).cuda(), torch.from_numpy(scale).cuda(), torch.from_numpy(zero).cuda())
+
+
+def _check(qval, codes, scale, zero, G, qpk, inv_freq, pos0, out_scale, got):
+    B, Hq = qval.shape[:2]
+    got = got.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // qpk
+            want = O.key_scores_rope(qval[b, hq][None], codes[b, h], scale[b, h], zero[b, h], G, inv_freq, pos0, out_scale)[0]
+            khat = O.dequantize_keys(codes[b, h], scale[b, h], zero[b, h], G)
+            rot = np.abs(O.rope_rotate(khat, pos0 + np.arange(khat.shape[0]), inv_freq))
+            bound = abs(out_scale) * (np.abs(qval[b, hq])[None] * rot).sum(axis=1)
+            err = np.abs(got[b, hq] - want)
+            assert np.all(err <= 6e-4 * bound + 1e-30), (b, hq, float((err / (bound + 1e-30)).max()))
+            worst = max(worst, float((err / (bound + 1e-30)).max()))
+    return worst
+
+
+@pytest.mark.parametrize("bits,G", [(2, 32), (4, 32), (2, 64), (4, 128), (2, 128)])
+@pytest.mark.parametrize("qdt", [synth.BF16, synth.F16, synth.F32])
+def test_rope_scores_match_definition(bits, G, qdt):
+    B, H, n, qpk = 2, 3, 1000, 4          # 62 full units and a ragged one of 8 tokens
+    gen, codes, scale, zero = _store(5100 + bits + G, B, H, n, bits, G)
+    q32 = (gen.standard_normal((B, H * qpk, 128)) * 3).astype(np.float32)
+    qraw, qval = synth.store(q32, qdt)
+    ct, st, zt = _dev(codes, scale, zero, bits)
+    got = squat.key_scores_rope(util.to_device(qraw, qdt), ct, st, zt, bits, G, qpk, torch.from_numpy(INV_FREQ).cuda(),
+                                pos0=0, out_scale=128 ** -0.5)
+    torch.cuda.synchronize()
+    assert got.shape == (B, H * qpk, n)
+    _check(qval, codes, scale, zero, G, qpk, INV_FREQ, 0, 128 ** -0.5, got)
+
+
+@pytest.mark.parametrize("pos0", [1, 4097, 131000, 2 ** 33 + 5])
+def test_rope_scores_at_large_positions_and_long_ranges(pos0):
+    """Angles of many thousands of radians (range reduction in fp64) and wavefront ranges of the maximum
+    length (the cos / sin recurrence runs ~48 units before it is re-seeded)."""
+    B, H, n, qpk = 1, 2, 16 * 190, 2      # 190 units: one workgroup, 48 units per wavefront
+    gen, codes, scale, zero = _store(5200, B, H, n, 2, 32)
+    q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.BF16)
+    ct, st, zt = _dev(codes, scale, zero, 2)
+    got = squat.key_scores_rope(util.to_device(qraw, synth.BF16), ct, st, zt, 2, 32, qpk, torch.from_numpy(INV_FREQ).cuda(), pos0=pos0)
+    torch.cuda.synchronize()
+    _check(qval, codes, scale, zero, 32, qpk, INV_FREQ, pos0, 1.0, got)
+
+
+def test_rope_scores_reduce_to_plain_scores_and_respect_relative_positions():
+    B, H, n, qpk = 1, 2, 200, 4
+    gen, codes, scale, zero = _store(5300, B, H, n, 2, 32)
+    q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.F32)
+    ct, st, zt = _dev(codes, scale, zero, 2)
+    qt = util.to_device(qraw, synth.F32)
+    zero_freq = torch.zeros(64, dtype=torch.float32, device="cuda")
+    plain = squat.key_scores(qt, ct, st, zt, 2, 32, qpk).cpu().numpy().astype(np.float64)
+    flat = squat.key_scores_rope(qt, ct, st, zt, 2, 32, qpk, zero_freq, pos0=77).cpu().numpy().astype(np.float64)
+    _check(qval, codes, scale, zero, 32, qpk, np.zeros(64), 77, 1.0, torch.from_numpy(flat))
+    assert np.abs(flat - plain).max() <= 6e-4 * np.abs(plain).max() + 1e-6
+    # shifting the keys' positions by m and rotating the query by m leaves the logits unchanged
+    m = 333
+    inv = torch.from_numpy(INV_FREQ).cuda()
+    base = squat.key_scores_rope(qt, ct, st, zt, 2, 32, qpk, inv, pos0=10).cpu().numpy().astype(np.float64)
+    qrot = O.rope_rotate(qval.reshape(-1, 128), np.full(H * qpk, m), INV_FREQ).reshape(qval.shape).astype(np.float32)
+    moved = squat.key_scores_rope(torch.from_numpy(qrot).cuda(), ct, st, zt, 2, 32, qpk, inv, pos0=10 + m)
+    moved = moved.cpu().numpy().astype(np.float64)
+    scale_ref = np.abs(base).max()
+    assert np.abs(moved - base).max() <= 2e-3 * scale_ref
+
+
+def test_rope_scores_query_heads_strides_and_tiny_inputs():
+    for qpk, n in ((1, 1), (3, 17), (8, 130)):
+        B, H = 2, 2
+        gen, codes, scale, zero = _store(5400 + n, B, H, n, 4, 64)
+        q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+        qraw, qval = synth.store(q32, synth.F16)
+        ct, st, zt = _dev(codes, scale, zero, 4)
+        big = torch.full((B, H * qpk, n + 24), -7.0, dtype=torch.float32, device="cuda")
+        squat.key_scores_rope(util.to_device(qraw, synth.F16), ct, st, zt, 4, 64, qpk, torch.from_numpy(INV_FREQ).cuda(),
+                              pos0=5, out_scale=0.3, out=big)
+        torch.cuda.synchronize()
+        _check(qval, codes, scale, zero, 64, qpk, INV_FREQ, 5, 0.3, big[..., :n])
+        assert torch.all(big[..., n:] == -7.0)
