@@ -1,11 +1,11 @@
 // Top-r eigenpairs of a symmetric positive semi-definite 128 x 128 matrix by the
-// classical dense route, one 1024-thread workgroup per matrix (Section 3.2: the
+// classical dense route, one 512-thread workgroup per matrix (Section 3.2: the
 // right singular vectors and singular values of the query matrix are the
 // eigenpairs of its Gram matrix):
 //
 //   1. Householder reduction to tridiagonal form T.  The matrix lives in
-//      REGISTERS: thread (row i, lane l of the row's team of 8) holds columns
-//      16 l .. 16 l + 15 of row i; per step only the column being eliminated, the
+//      REGISTERS: thread (row pair, lane l of the pair's team of 8) holds columns
+//      16 l .. 16 l + 15 of two rows; per step only the column being eliminated, the
 //      product A v and two scalars travel through LDS (two barriers per step).
 //   2. The r largest eigenvalues of T by 9-section on Sturm counts (8 trial
 //      shifts per eigenvalue and round, 18 rounds from [-3, 3] ||T||): the count
@@ -32,7 +32,8 @@
 namespace squat {
 
 constexpr int kTriN = 128;
-constexpr int kTriThreads = 1024;
+constexpr int kTriRows = 2;              // matrix rows per thread
+constexpr int kTriThreads = kTriN / kTriRows * 8;   // 512: a row's 128 columns are spread over 8 lanes
 constexpr int kTriMaxR = 32;            // vectors the LDS plan holds
 constexpr int kTriPts = 8;              // trial shifts per eigenvalue and round
 constexpr int kTriRounds = 18;          // 9^18 > 6 * 2^53
@@ -122,11 +123,13 @@ __device__ __forceinline__ double tri_rcp(double x) {
 }
 
 // One Householder step, column k = 16 KK + CC (CC is a compile-time register index).  The kernel is
-// bound by instruction issue (four wavefronts per SIMD, all running the same step), so the step is
-// written for few instructions: the eliminated column goes to LDS with zeros above the diagonal (no
-// masks afterwards), and the rank-two update v w' + w v' is applied as two multiply-adds per element.
+// bound by instruction issue: per step every wavefront recomputes sigma, alpha, beta and K and re-reads v
+// and p from LDS, so fewer, fatter wavefronts do less in total.  A thread therefore holds kTriRows rows
+// (x 16 columns): v and p are read once for both rows.  The eliminated column goes to LDS with zeros
+// above the diagonal (no masks afterwards), and the rank-two update v w' + w v' is applied as two
+// multiply-adds per element.
 template <int CC>
-__device__ __forceinline__ void tri_step(double (&a)[16], int kk, int i, int l, int tid, double* L) {
+__device__ __forceinline__ void tri_step(double (&a)[kTriRows][16], int kk, int i0, int l, int tid, double* L) {
     const int k = 16 * kk + CC;
     if (k > kTriN - 3) return;                            // uniform
     constexpr int CN = (CC + 1) & 15;                     // register of column k + 1 ...
@@ -135,12 +138,18 @@ __device__ __forceinline__ void tri_step(double (&a)[16], int kk, int i, int l, 
     double* xs = L + kTriXs + (k & 1) * kTriN;
     double* ps = L + kTriPs + (k & 1) * kTriN;
     if (l == kk) {
-        xs[i] = i > k ? a[CC] : 0.0;
-        if (i == k) L[kTriDd + k] = a[CC];
+#pragma unroll
+        for (int r = 0; r < kTriRows; ++r) {
+            xs[i0 + r] = i0 + r > k ? a[r][CC] : 0.0;
+            if (i0 + r == k) L[kTriDd + k] = a[r][CC];
+        }
     }
     tri_lds_barrier();
-    const bool rows_live = 8 * wave + 7 > k;              // this wavefront still owns rows of the trailing block
-    double alpha = 0.0, beta = 0.0, p_i = 0.0, v_i = 0.0;
+    const bool rows_live = 8 * kTriRows * (wave + 1) - 1 > k;   // this wavefront still owns rows of the trailing block
+    double alpha = 0.0, beta = 0.0;
+    double p_i[kTriRows], v_i[kTriRows];
+#pragma unroll
+    for (int r = 0; r < kTriRows; ++r) p_i[r] = v_i[r] = 0.0;
     double vj[16];
     bool live = false;
     if (rows_live || wave == 0) {
@@ -159,23 +168,29 @@ __device__ __forceinline__ void tri_step(double (&a)[16], int kk, int i, int l, 
             alpha = x0 >= 0.0 ? -sq : sq;
             beta = tri_rcp(fma(fabs(x0), sq, sigma));     // 2 / v'v with v = x - alpha e_1
             if (rows_live) {
-                double q4[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                 for (int c = 0; c < 16; ++c) vj[c] = xs[16 * l + c];
                 if (l == own) vj[CN] -= alpha;
 #pragma unroll
-                for (int c = 0; c < 16; ++c) q4[c & 3] = fma(a[c], vj[c], q4[c & 3]);
-                const double q = team_sum<8>((q4[0] + q4[1]) + (q4[2] + q4[3]));
-                v_i = xs[i];
-                if (i == k + 1) v_i -= alpha;
-                p_i = i > k ? beta * q : 0.0;
+                for (int r = 0; r < kTriRows; ++r) {
+                    double q4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                    for (int c = 0; c < 16; ++c) q4[c & 3] = fma(a[r][c], vj[c], q4[c & 3]);
+                    const double q = team_sum<8>((q4[0] + q4[1]) + (q4[2] + q4[3]));
+                    v_i[r] = xs[i0 + r];
+                    if (i0 + r == k + 1) v_i[r] -= alpha;
+                    p_i[r] = i0 + r > k ? beta * q : 0.0;
+                }
             }
         }
     }
     // rows that are done contribute zeros; every row writes so that nothing stale is read
     if (l == 0) {
-        ps[i] = p_i;
-        L[kTriX + k * kTriN + i] = v_i;                    // reflector k (the block of the later phases is free now)
+#pragma unroll
+        for (int r = 0; r < kTriRows; ++r) {
+            ps[i0 + r] = p_i[r];
+            L[kTriX + k * kTriN + i0 + r] = v_i[r];        // reflector k (the block of the later phases is free now)
+        }
     }
     if (tid == 0) {
         L[kTriEe + k] = alpha;
@@ -192,11 +207,17 @@ __device__ __forceinline__ void tri_step(double (&a)[16], int kk, int i, int l, 
             s = fma(ps[lane], va, ps[lane + 64] * vb);
         }
         const double K = 0.5 * beta * tri_wave_sum(s);
-        const double nw_i = fma(K, v_i, -p_i), nv_i = -v_i;
+        double nw_i[kTriRows], nv_i[kTriRows];
+#pragma unroll
+        for (int r = 0; r < kTriRows; ++r) {
+            nw_i[r] = fma(K, v_i[r], -p_i[r]);
+            nv_i[r] = -v_i[r];
+        }
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
             const double w = fma(-K, vj[c], ps[16 * l + c]);
-            a[c] = fma(nv_i, w, fma(nw_i, vj[c], a[c]));
+#pragma unroll
+            for (int r = 0; r < kTriRows; ++r) a[r][c] = fma(nv_i[r], w, fma(nw_i[r], vj[c], a[r][c]));
         }
     }
 }
@@ -204,27 +225,30 @@ __device__ __forceinline__ void tri_step(double (&a)[16], int kk, int i, int l, 
 // g: the matrix (row-major doubles, symmetric positive semi-definite); vws: 128 x 128 doubles of
 // scratch in global memory; qhat: r rows of 128 floats = sqrt(lambda_j) v_j, eigenvalues descending;
 // eig: r floats or NULL.  Returns (to every thread) whether the result was accepted; if not, nothing
-// was written.  All 1024 threads of the block must call it; L: kTriLdsBytes of LDS, 16-byte aligned.
+// was written.  All kTriThreads threads of the block must call it; L: kTriLdsBytes of LDS, 16-byte aligned.
 __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, int r, float* qhat, float* eig,
                                                  double* L) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i = tid >> 3, l = tid & 7;
+    const int i0 = kTriRows * (tid >> 3), l = tid & 7;    // this thread's rows i0 .. and columns 16 l ..
     double* misc = L + kTriMisc;
 
     // ---- load, scale by a power of two so that the largest entry is in [1, 2)
-    double a[16];
-    {
-        const double* src = g + i * kTriN + 16 * l;
+    double a[kTriRows][16];
+#pragma unroll
+    for (int r = 0; r < kTriRows; ++r) {
+        const double* src = g + (i0 + r) * kTriN + 16 * l;
 #pragma unroll
         for (int c = 0; c < 16; c += 2) {
             const double2 t = *reinterpret_cast<const double2*>(src + c);
-            a[c] = t.x;
-            a[c + 1] = t.y;
+            a[r][c] = t.x;
+            a[r][c + 1] = t.y;
         }
     }
     double amax = 0.0;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) amax = fmax(amax, fabs(a[c]));
+    for (int r = 0; r < kTriRows; ++r)
+#pragma unroll
+        for (int c = 0; c < 16; ++c) amax = fmax(amax, fabs(a[r][c]));
     amax = tri_block_max(amax, misc, tid);
     if (!(amax > 0.0) || !(amax < 1e300)) {
         // zero matrix: zero eigenvalues, zero rows (also taken for NaN / Inf input: nothing sensible exists)
@@ -237,34 +261,37 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     const int sexp = aexp < -1000 ? -1000 : (aexp > 1000 ? 1000 : aexp);
     const double down = tri_pow2(-sexp), up = tri_pow2(sexp);
 #pragma unroll
-    for (int c = 0; c < 16; ++c) a[c] *= down;
+    for (int r = 0; r < kTriRows; ++r)
+#pragma unroll
+        for (int c = 0; c < 16; ++c) a[r][c] *= down;
 
     // ---- 1. Householder reduction
-    if (tid < 4 * kTriN) L[tid] = 0.0;                   // column and product buffers: never read uninitialised
+    for (int e = tid; e < 4 * kTriN; e += kTriThreads) L[e] = 0.0;      // column and product buffers: never read uninitialised
     __syncthreads();
     for (int kk = 0; kk < 8; ++kk) {
-        tri_step<0>(a, kk, i, l, tid, L);
-        tri_step<1>(a, kk, i, l, tid, L);
-        tri_step<2>(a, kk, i, l, tid, L);
-        tri_step<3>(a, kk, i, l, tid, L);
-        tri_step<4>(a, kk, i, l, tid, L);
-        tri_step<5>(a, kk, i, l, tid, L);
-        tri_step<6>(a, kk, i, l, tid, L);
-        tri_step<7>(a, kk, i, l, tid, L);
-        tri_step<8>(a, kk, i, l, tid, L);
-        tri_step<9>(a, kk, i, l, tid, L);
-        tri_step<10>(a, kk, i, l, tid, L);
-        tri_step<11>(a, kk, i, l, tid, L);
-        tri_step<12>(a, kk, i, l, tid, L);
-        tri_step<13>(a, kk, i, l, tid, L);
-        tri_step<14>(a, kk, i, l, tid, L);
-        tri_step<15>(a, kk, i, l, tid, L);
+        tri_step<0>(a, kk, i0, l, tid, L);
+        tri_step<1>(a, kk, i0, l, tid, L);
+        tri_step<2>(a, kk, i0, l, tid, L);
+        tri_step<3>(a, kk, i0, l, tid, L);
+        tri_step<4>(a, kk, i0, l, tid, L);
+        tri_step<5>(a, kk, i0, l, tid, L);
+        tri_step<6>(a, kk, i0, l, tid, L);
+        tri_step<7>(a, kk, i0, l, tid, L);
+        tri_step<8>(a, kk, i0, l, tid, L);
+        tri_step<9>(a, kk, i0, l, tid, L);
+        tri_step<10>(a, kk, i0, l, tid, L);
+        tri_step<11>(a, kk, i0, l, tid, L);
+        tri_step<12>(a, kk, i0, l, tid, L);
+        tri_step<13>(a, kk, i0, l, tid, L);
+        tri_step<14>(a, kk, i0, l, tid, L);
+        tri_step<15>(a, kk, i0, l, tid, L);
     }
-    if (l == 7) {
-        if (i == kTriN - 2) L[kTriDd + kTriN - 2] = a[14];
-        if (i == kTriN - 1) {
-            L[kTriDd + kTriN - 1] = a[15];
-            L[kTriEe + kTriN - 2] = a[14];
+    static_assert(kTriRows >= 2, "the last two rows are taken from one thread");
+    if (l == 7 && i0 == kTriN - kTriRows) {
+        L[kTriDd + kTriN - 2] = a[kTriRows - 2][14];
+        {
+            L[kTriDd + kTriN - 1] = a[kTriRows - 1][15];
+            L[kTriEe + kTriN - 2] = a[kTriRows - 1][14];
             L[kTriEe + kTriN - 1] = 0.0;
             L[kTriBet + kTriN - 2] = 0.0;
             L[kTriBet + kTriN - 1] = 0.0;
@@ -452,22 +479,28 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         if (dev <= 1e-5) {
             // nearly orthonormal (close eigenvalues, not coincident ones): one symmetric step
             // X <- X (3/2 I - 1/2 S) squares the deviation
-            const int row = tid >> 3, j0 = 4 * (tid & 7);
-            const double* xr = L + kTriX + 32 * row;
-            double out[4];
+            constexpr int NP = kTriN * 8 / kTriThreads;    // row passes per thread
+            const int j0 = 4 * (tid & 7);
+            double out[NP][4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) out[c] = 0.0;
-            for (int k2 = 0; k2 < r; ++k2) {
-                const double xk = xr[k2];
+            for (int ps2 = 0; ps2 < NP; ++ps2) {
+                const double* xr = L + kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8));
 #pragma unroll
-                for (int c = 0; c < 4; ++c) out[c] = fma(xk, S[k2 * 33 + j0 + c], out[c]);
+                for (int c = 0; c < 4; ++c) out[ps2][c] = 0.0;
+                for (int k2 = 0; k2 < r; ++k2) {
+                    const double xk = xr[k2];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) out[ps2][c] = fma(xk, S[k2 * 33 + j0 + c], out[ps2][c]);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) out[ps2][c] = fma(-0.5, out[ps2][c], 1.5 * xr[j0 + c]);
             }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) out[c] = fma(-0.5, out[c], 1.5 * xr[j0 + c]);
             __syncthreads();
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (j0 + c < r) L[kTriX + 32 * row + j0 + c] = out[c];
+            for (int ps2 = 0; ps2 < NP; ++ps2)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j0 + c < r) L[kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8)) + j0 + c] = out[ps2][c];
             __syncthreads();
             continue;
         }
@@ -515,38 +548,46 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         __syncthreads();
     }
 
-    // ---- 4. Rayleigh quotients and residuals: team of 32 lanes per vector, 4 elements per lane
-    const int vj = tid >> 5, sub = tid & 31;
-    double xv[4];
+    // ---- 4. Rayleigh quotients and residuals: team of 32 lanes per vector, 4 elements per lane, NV
+    // vectors per thread
+    constexpr int NV = 32 * 32 / kTriThreads;
+    const int sub = tid & 31;
+    double xv[NV][4];
     {
-        double num = 0.0, den = 0.0;
-        double yv[4];
+        double worst = 0.0;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const int row = sub + 32 * m;
-            const double x = L[kTriX + 32 * row + vj];
-            const double xm = row > 0 ? L[kTriX + 32 * (row - 1) + vj] : 0.0;
-            const double xp = row < kTriN - 1 ? L[kTriX + 32 * (row + 1) + vj] : 0.0;
-            const double em = row > 0 ? L[kTriEe + row - 1] : 0.0;
-            const double y = fma(L[kTriDd + row], x, fma(em, xm, L[kTriEe + row] * xp));
-            xv[m] = x;
-            yv[m] = y;
-            num = fma(x, y, num);
-            den = fma(x, x, den);
-        }
-        num = tri_sum32(num);
-        den = tri_sum32(den);
-        const double rq = den > 0.0 ? num / den : 0.0;
-        double res = 0.0;
+        for (int q = 0; q < NV; ++q) {
+            const int vj = (tid >> 5) + q * (kTriThreads / 32);
+            double num = 0.0, den = 0.0;
+            double yv[4];
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const double t = yv[m] - rq * xv[m];
-            res = fma(t, t, res);
+            for (int m = 0; m < 4; ++m) {
+                const int row = sub + 32 * m;
+                const double x = L[kTriX + 32 * row + vj];
+                const double xm = row > 0 ? L[kTriX + 32 * (row - 1) + vj] : 0.0;
+                const double xp = row < kTriN - 1 ? L[kTriX + 32 * (row + 1) + vj] : 0.0;
+                const double em = row > 0 ? L[kTriEe + row - 1] : 0.0;
+                const double y = fma(L[kTriDd + row], x, fma(em, xm, L[kTriEe + row] * xp));
+                xv[q][m] = x;
+                yv[m] = y;
+                num = fma(x, y, num);
+                den = fma(x, x, den);
+            }
+            num = tri_sum32(num);
+            den = tri_sum32(den);
+            const double rq = den > 0.0 ? num / den : 0.0;
+            double res = 0.0;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const double t = yv[m] - rq * xv[q][m];
+                res = fma(t, t, res);
+            }
+            res = tri_sum32(res);
+            if (sub == 0) L[kTriLam + 64 + vj] = rq;
+            double w = vj < r ? sqrt(res) : 0.0;
+            if (!(w == w)) w = 1e300;
+            worst = fmax(worst, w);
         }
-        res = tri_sum32(res);
-        if (sub == 0) L[kTriLam + 64 + vj] = rq;
-        double worst = vj < r ? sqrt(res) : 0.0;
-        if (!(worst == worst)) worst = 1e300;
         worst = tri_block_max(worst, misc, tid);
         if (!(worst <= kTriAccept)) ok = false;
     }
@@ -564,20 +605,30 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         for (int k = kTriN - 3; k >= 0; --k) {
             const double beta = L[kTriBet + k];
             if (beta == 0.0) continue;                    // uniform
-            double v[4], s = 0.0;
+            double v[4];
 #pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                v[m] = V[k * kTriN + sub + 32 * m];
-                s = fma(v[m], xv[m], s);
+            for (int m = 0; m < 4; ++m) v[m] = V[k * kTriN + sub + 32 * m];
+            double s[NV];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                s[q] = 0.0;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) s[q] = fma(v[m], xv[q][m], s[q]);
             }
-            s = tri_sum32(s) * beta;
 #pragma unroll
-            for (int m = 0; m < 4; ++m) xv[m] = fma(-s, v[m], xv[m]);
+            for (int q = 0; q < NV; ++q) s[q] = tri_sum32(s[q]) * beta;
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int m = 0; m < 4; ++m) xv[q][m] = fma(-s[q], v[m], xv[q][m]);
         }
     }
 
     // ---- output: rank by eigenvalue, sign so that the largest component is positive, rows sqrt(lambda) v
-    if (vj < r) {
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        const int vj = (tid >> 5) + q * (kTriThreads / 32);
+        if (vj >= r) continue;                            // uniform per team of 32 lanes
         const double lam = L[kTriLam + 64 + vj];
         int rank = 0;
         for (int o = 0; o < r; ++o) {
@@ -588,8 +639,8 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         int besti = kTriN;
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
-            const double av = fabs(xv[m]);
-            if (av > best) { best = av; bestv = xv[m]; besti = sub + 32 * m; }
+            const double av = fabs(xv[q][m]);
+            if (av > best) { best = av; bestv = xv[q][m]; besti = sub + 32 * m; }
         }
 #pragma unroll
         for (int off = 16; off > 0; off >>= 1) {
@@ -602,7 +653,7 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         const double sc = (bestv < 0.0 ? -1.0 : 1.0) * sqrt(lam_true);
         float* dst = qhat + rank * kTriN;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) dst[sub + 32 * m] = static_cast<float>(xv[m] * sc);
+        for (int m = 0; m < 4; ++m) dst[sub + 32 * m] = static_cast<float>(xv[q][m] * sc);
         if (eig && sub == 0) eig[rank] = static_cast<float>(lam_true);
     }
     return true;
