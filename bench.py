@@ -133,8 +133,12 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     stage_ms = {}
+    stage_ms_median, stage_ms_min = {}, {}
     for s, name in enumerate(stages):
-        stage_ms[name] = sum(ev[s].elapsed_time(ev[s + 1]) for ev in events) / args.steps
+        ts = sorted(ev[s].elapsed_time(ev[s + 1]) for ev in events)
+        stage_ms[name] = sum(ts) / args.steps
+        stage_ms_median[name] = ts[len(ts) // 2]
+        stage_ms_min[name] = ts[0]
 
     n_keys = wl.n_keys
     # roofline of the dominant bandwidth kernel, the quantize pass: algorithmic bytes = keys x (256 B in +
@@ -157,8 +161,8 @@ def main():
         "dequantize_keys": {"bound": "hbm", "achieved": q_bytes / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                             "unit": "GB/s", "frac": q_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "build_subspace": {"ms": stage_ms["build_subspace"], "gram_input_GB": gram_bytes / 1e9,
-                           "note": "gram (HBM-bound bf16 MFMA, see profiles/) + fp64 Jacobi eigen-solver "
-                                   "(instruction-issue-bound, one workgroup per head)"},
+                           "note": "gram (HBM-bound bf16 MFMA, see profiles/) + fp64 eigen-solver, one workgroup per "
+                                   "head (Householder tridiagonalisation, bisection, inverse iteration; latency-bound)"},
         "prepare": {"ms": stage_ms["prepare"]},
     }
     out = {
@@ -172,7 +176,7 @@ def main():
                                "one launch per stage" % (wl.layers, wl.kv_heads, wl.q_per_kv, n, wl.r, wl.lam,
                                                          wl.bits, wl.group, wl.g),
                    "keys_per_step": n_keys},
-        "stage_ms": stage_ms,
+        "stage_ms": stage_ms, "stage_ms_median": stage_ms_median, "stage_ms_min": stage_ms_min,
         "quantize_keys_per_s": n_keys / (q_ms * 1e-3),
         "roofline": roofline,
         "other_kernels": other,
@@ -188,6 +192,16 @@ def main():
             evs[i + 1].record()
         torch.cuda.synchronize()
         return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps
+
+    # The machine, and a practical ceiling measured beside the vendor peak: a plain elementwise device copy
+    # of the key tensor (reads and writes keys x 256 B each).
+    props = torch.cuda.get_device_properties(0)
+    t_copy = timed(lambda: back.copy_(wl.k.view_as(back)))
+    out["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
+                     "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
+                     "hbm_GiB": props.total_memory / 2 ** 30,
+                     "device_copy_GBps": 2 * n_keys * d * 2 / (t_copy * 1e-3) / 1e9}
+    roofline["frac_of_device_copy"] = achieved / out["device"]["device_copy_GBps"]
 
     # The paper's own grouping (statistics per channel over 32 tokens): same keys, same update matrix, the
     # per-channel entry points; the headline variant always, the others with --variants.
