@@ -76,7 +76,7 @@ template <int DT>
 __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const GramParams p) {
     typedef typename GramOps<DT>::op_t op_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hh = lane >> 5, m = lane & 31;
     const int kvh = blockIdx.x / p.wgs_per_head;
     const int wg = blockIdx.x % p.wgs_per_head;
@@ -88,30 +88,62 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const G
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
 
     const int64_t ustride = static_cast<int64_t>(p.wgs_per_head) * kGramWaves;
-    int64_t unit = static_cast<int64_t>(wg) * kGramWaves + wave;
+    const int64_t cpq = p.chunks_per_qhead;
+    const int64_t last_unit = p.units_per_head - 1;
+
+    // Position of a unit (chunk of 16 tokens of one query head), kept in scalar registers and advanced
+    // without a division: units of a wavefront are `ustride` apart.
+    struct Cursor {
+        int64_t u, qh, c;        // unit, its query head, its chunk inside the query head
+    };
+    auto advance = [&](Cursor& k) {
+        k.u += ustride;
+        k.c += ustride;
+        while (k.c >= cpq) {     // wave-uniform
+            k.c -= cpq;
+            ++k.qh;
+        }
+    };
+    Cursor ci;                   // next unit to load
+    ci.u = static_cast<int64_t>(wg) * kGramWaves + wave;
+    ci.qh = ci.u / cpq;
+    ci.c = ci.u - ci.qh * cpq;
+    Cursor cc = ci;              // next unit to multiply
+
+    // Lane (hh, m) loads bytes 8 m .. 8 m + 7 of rows 8 hh + j, j = 0..7, of a chunk: one 32-bit offset per
+    // row from the chunk's (scalar) base address.
+    const uint32_t st32 = static_cast<uint32_t>(p.st);
+    uint32_t voff[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) voff[j] = static_cast<uint32_t>(8 * hh + j) * st32 + static_cast<uint32_t>(m) * 8u;
 
     // kDepth chunks of 16 tokens are in flight per wavefront (4 KB each).  Loads are unconditional:
     // units past the end re-read the last unit, rows past the end of a query head re-read its last
     // row; both are discarded below by wave-uniform tests, so the load stream stays straight-line.
     constexpr int kDepth = 4;
     u32x2 raw[kDepth][8];
-    const int64_t last_unit = p.units_per_head - 1;
-    auto issue = [&](int64_t u, u32x2* dst) {
-        u = u < last_unit ? u : last_unit;
-        const int64_t qh = u / p.chunks_per_qhead;
-        const int64_t tok0 = (u - qh * p.chunks_per_qhead) * 16 + 8 * hh;
-        const unsigned char* base = p.q + (static_cast<int64_t>(kvh) * p.q_per_kv + qh) * p.sh + m * 8;
+    auto issue = [&](const Cursor& k, u32x2* dst) {
+        const bool past = k.u > last_unit;
+        const int64_t qh = past ? p.q_per_kv - 1 : k.qh;
+        const int64_t tokc = (past ? cpq - 1 : k.c) * 16;
+        const unsigned char* head = p.q + (static_cast<int64_t>(kvh) * p.q_per_kv + qh) * p.sh;
+        if (tokc + 16 <= p.n_tokens) {                   // whole chunk (wave-uniform)
+            const unsigned char* base = head + tokc * p.st;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            int64_t tok = tok0 + j;
-            tok = tok < p.n_tokens ? tok : p.n_tokens - 1;
-            dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + tok * p.st));
+            for (int j = 0; j < 8; ++j)
+                dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + voff[j]));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                int64_t tok = tokc + 8 * hh + j;
+                tok = tok < p.n_tokens ? tok : p.n_tokens - 1;
+                dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(head + tok * p.st + m * 8));
+            }
         }
     };
-    auto consume = [&](int64_t u, u32x2* src) {
-        if (u > last_unit) return;                       // wave-uniform
-        const int64_t qh = u / p.chunks_per_qhead;
-        const int64_t tokc = (u - qh * p.chunks_per_qhead) * 16;
+    auto consume = [&](const Cursor& k, u32x2* src) {
+        if (k.u > last_unit) return;                     // wave-uniform
+        const int64_t tokc = k.c * 16;
         if (tokc + 16 > p.n_tokens) {                    // ragged last chunk of a query head (wave-uniform)
 #pragma unroll
             for (int j = 0; j < 8; ++j)
@@ -137,16 +169,20 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_16(const G
                 acc[tile_index(a, b)] = GramOps<DT>::mfma(ops[a], ops[b], acc[tile_index(a, b)]);
     };
 
-    if (unit <= last_unit) {
+    if (cc.u <= last_unit) {
 #pragma unroll
-        for (int i = 0; i < kDepth; ++i) issue(unit + i * ustride, raw[i]);
-        while (unit <= last_unit) {
+        for (int i = 0; i < kDepth; ++i) {
+            issue(ci, raw[i]);
+            advance(ci);
+        }
+        while (cc.u <= last_unit) {
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
-                consume(unit + i * ustride, raw[i]);
-                issue(unit + (i + kDepth) * ustride, raw[i]);
+                consume(cc, raw[i]);
+                advance(cc);
+                issue(ci, raw[i]);
+                advance(ci);
             }
-            unit += kDepth * ustride;
         }
     }
 
@@ -408,6 +444,8 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
     if (q_stride_token < d || q_stride_head < 0) return SQUAT_E_BADSHAPE;
     if ((q_stride_token % 8) || (q_stride_head % 8) || !aligned(q, 16)) return SQUAT_E_ALIGN;
     if (static_cast<int64_t>(n_kv_heads) * q_per_kv > (int64_t(1) << 24)) return SQUAT_E_BADSHAPE;
+    // a chunk's 16 rows are addressed by 32-bit byte offsets from its first row
+    if (q_stride_token * elem_size(q_dt) >= (int64_t(1) << 27)) return SQUAT_E_BADSHAPE;
     const SubspacePlan pl = plan(n_tokens, n_kv_heads, q_per_kv, kPlanCUs);
     if (!ws || ws_bytes < pl.total) return SQUAT_E_WORKSPACE;
     if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
