@@ -24,6 +24,13 @@ struct DeqParams {
     int n_heads;
 };
 
+// Two floats -> two bf16 (round to nearest even, NaN stays NaN) in one word: the hardware conversion.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+
 template <int DT>
 __device__ __forceinline__ void store16(unsigned char* dst, const float* v) {
     if constexpr (DT == SQUAT_F32) {
@@ -40,11 +47,7 @@ __device__ __forceinline__ void store16(unsigned char* dst, const float* v) {
                 h[1] = static_cast<_Float16>(v[2 * i + 1]);
                 w[i] = __builtin_bit_cast(uint32_t, h);
             } else {
-                // fp32 -> bf16, round to nearest even
-                uint32_t a = as_u32(v[2 * i]), b = as_u32(v[2 * i + 1]);
-                a = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
-                b = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
-                w[i] = a | b;
+                w[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
             }
         }
         *reinterpret_cast<u32x4*>(dst) = u32x4{w[0], w[1], w[2], w[3]};
@@ -77,8 +80,10 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const DeqParams p) {
         w[1] = v[1];
     }
     const int gi = chunk * 16 / GROUP;
-    const float sc = static_cast<float>(__builtin_bit_cast(_Float16, p.scale[row * NG + gi]));
-    const float zp = static_cast<float>(__builtin_bit_cast(_Float16, p.zero[row * NG + gi]));
+    float sc = static_cast<float>(__builtin_bit_cast(_Float16, p.scale[row * NG + gi]));
+    float zp = static_cast<float>(__builtin_bit_cast(_Float16, p.zero[row * NG + gi]));
+    // converted once: folded into the 16 multiply-adds as mixed-precision operands they would issue at half rate
+    asm volatile("" : "+v"(sc), "+v"(zp));
 
     float v[16];
     constexpr int IPW = 32 / BITS;
@@ -145,11 +150,7 @@ __global__ void __launch_bounds__(256) dequantize_pc_kernel(const DeqParams p, c
                     hv[1] = static_cast<_Float16>(v[2 * c + 1]);
                     pk[c] = __builtin_bit_cast(uint32_t, hv);
                 } else {
-                    // fp32 -> bf16, round to nearest even
-                    uint32_t a = as_u32(v[2 * c]), bb = as_u32(v[2 * c + 1]);
-                    a = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
-                    bb = (bb + 0x7FFFu + ((bb >> 16) & 1u)) & 0xFFFF0000u;
-                    pk[c] = a | bb;
+                    pk[c] = pack_bf16(v[2 * c], v[2 * c + 1]);
                 }
             }
             *reinterpret_cast<u32x4*>(o) = u32x4{pk[0], pk[1], pk[2], pk[3]};
