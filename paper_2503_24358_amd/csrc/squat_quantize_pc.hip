@@ -375,14 +375,15 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                     for (int c = 0; c < NCH; ++c)
                         aop[c] = __builtin_bit_cast(
                             half8, *reinterpret_cast<const u32x4*>(ebuf + n * EROW + 8 * c + 4 * hh));
-                    // two straight-line versions (with and without the low parts of the panels), so that
-                    // the operand reads of a whole chain can be issued ahead of its matrix products
-                    auto propagate = [&](auto lo_tag) {
-                        constexpr bool LO = decltype(lo_tag)::value;
-                        // The working copy is the accumulator.  The chains of the remaining tiles are
-                        // interleaved (K-chunk outermost), so that no matrix product waits for the one
-                        // issued just before it.  Accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3),
-                        // i.e. token 16 hh + e.
+                    // The working copy is the accumulator.  The chains of the remaining tiles are
+                    // interleaved (K-chunk outermost), so that no matrix product waits for the one
+                    // issued just before it.  Accumulator register e is row 8 (e >> 2) + 4 hh + (e & 3),
+                    // i.e. token 16 hh + e.  The products with the low parts of the panels follow as a
+                    // second, conditional pass over the same accumulators (straight-line code in both
+                    // passes, operand reads issued ahead; one pass with the choice inside would make the
+                    // two versions hand the working copy over in different registers).
+                    auto pass = [&](auto part_tag) {
+                        constexpr int PART = decltype(part_tag)::value;
 #pragma unroll
                         for (int jj = 0; jj < BT; ++jj)
 #pragma unroll
@@ -390,18 +391,12 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
 #pragma unroll
                                 for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
                                     const int pr = pair_index(BT, jt, blk * BT + jj);
-                                    const half8 whi = wlds[((pr * 4 + c) * 2 + 0) * 64 + lane];
-                                    x[jt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], whi, x[jt], 0, 0, 0);
-                                    if constexpr (LO) {
-                                        const half8 wlo = wlds[((pr * 4 + c) * 2 + 1) * 64 + lane];
-                                        x[jt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], wlo, x[jt], 0, 0, 0);
-                                    }
+                                    const half8 w = wlds[((pr * 4 + c) * 2 + PART) * 64 + lane];
+                                    x[jt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[4 * jj + c], w, x[jt], 0, 0, 0);
                                 }
                     };
-                    if (need_lo)
-                        propagate(std::true_type{});
-                    else
-                        propagate(std::false_type{});
+                    pass(std::integral_constant<int, 0>{});
+                    if (need_lo) pass(std::integral_constant<int, 1>{});
                     // the next block's error tile must not overtake this block's operand reads
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
@@ -414,8 +409,16 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
                 } else {
                     // the loop ends after this tile: say that the old contents are dead, or they would be
                     // kept in registers up to this point
+                    // (an empty statement that "writes" them: no instruction, unlike a frozen undefined value,
+                    // which is materialised as zeros)
 #pragma unroll
-                    for (int i = 0; i < NLOAD; ++i) pre[i] = __builtin_nondeterministic_value(pre[i]);
+                    for (int i = 0; i < NLOAD; ++i)
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            uint32_t dead;
+                            asm volatile("" : "=v"(dead));
+                            pre[i][w] = dead;
+                        }
                 }
             }
         }
