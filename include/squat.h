@@ -87,7 +87,8 @@ const char* squat_strerror(int status);
  *
  *   q       [n_kv_heads*q_per_kv, n_tokens, d] dtype q_dt, element (h,t,c) at
  *           q[h*q_stride_head + t*q_stride_token + c]; base pointer 16-byte
- *           aligned, both strides multiples of 8 elements.
+ *           aligned, both strides multiples of 8 elements; a token stride of
+ *           2^27 bytes or more is SQUAT_E_BADSHAPE.
  *   qhat    out [n_kv_heads, r, d] float, dense.  May be NULL only if r == 0.
  *   eig     out [n_kv_heads, r] float, eigenvalues of Q^T Q (squared singular
  *           values), descending.  May be NULL.
@@ -154,8 +155,8 @@ int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, in
  *
  *   k        [n_batch, n_heads, n_tokens, d] dtype k_dt; element (b,h,t,c) at
  *            k[b*k_stride_batch + h*k_stride_head + t*k_stride_token + c];
- *            base 16-byte aligned, strides multiples of 8 elements.  Not
- *            modified.
+ *            base 16-byte aligned, strides multiples of 8 elements (a token
+ *            stride of 2^26 bytes or more is SQUAT_E_BADSHAPE).  Not modified.
  *   update   [n_heads, d, d] float as written by squat_prepare (same g), or
  *            any fp32 matrix of that block structure with |entries| < 65504, or
  *            NULL.  update_stride_batch (elements) is added per batch entry;
