@@ -56,6 +56,7 @@ def test_argument_validation_happens_before_any_launch():
     assert q(k=odd) == -4
     assert q(n=0) == 0              # empty input: nothing to do, nothing launched
     assert q(n=-1) == -2
+    assert q(st=1 << 25) == -2      # bf16: a token stride of 2^26 bytes, same reason
 
     dq = lambda **kw: L.squat_dequantize_keys(  # noqa: E731
         kw.get("codes", fake), fake, fake, 1, 1, kw.get("n", 32), kw.get("d", 128), kw.get("bits", 2),
@@ -69,7 +70,8 @@ def test_argument_validation_happens_before_any_launch():
 
     bs = lambda **kw: L.squat_build_subspace(  # noqa: E731
         kw.get("q", fake), kw.get("dt", 2), kw.get("n", 64), kw.get("h", 1), kw.get("qpk", 1), kw.get("d", 128),
-        8192, 128, kw.get("r", 8), kw.get("qhat", fake), None, None, kw.get("ws", fake), kw.get("wsb", 1 << 30), None)
+        8192, kw.get("st", 128), kw.get("r", 8), kw.get("qhat", fake), None, None, kw.get("ws", fake),
+        kw.get("wsb", 1 << 30), None)
     assert bs(d=96) == -2
     assert bs(r=129) == -2
     assert bs(r=-1) == -2
@@ -79,6 +81,7 @@ def test_argument_validation_happens_before_any_launch():
     assert bs(ws=None) == -5
     assert bs(wsb=16) == -5
     assert bs(dt=9) == -3
+    assert bs(st=1 << 26) == -2     # bf16: a token stride of 2^27 bytes is beyond the kernel's 32-bit row offsets
 
     pr = lambda **kw: L.squat_prepare(  # noqa: E731
         kw.get("qhat", fake), 1, kw.get("d", 128), kw.get("r", 8), kw.get("lam", 1e-3), kw.get("g", 32),
