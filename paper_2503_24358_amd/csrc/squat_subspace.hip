@@ -285,13 +285,21 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_f32(const 
 
 // partial[(t*16 + e)*64 + lane] is element (row mm, col nn) of tile t = (a, b) with
 // nn = lane & 31, mm = 8*(e>>2) + 4*(lane>>5) + (e&3), i.e. G[4*mm + a][4*nn + b].
-__global__ void __launch_bounds__(256) gram_reduce(const float* partial, int wgs_per_head,
-                                                   double* g64, float* gram_out) {
+constexpr int kRedLd = kD + 1;          // padded row of the LDS copy: the mirrored writes spread over the banks
+constexpr int kRedThreads = 512;
+constexpr size_t kRedLdsBytes = static_cast<size_t>(kD) * kRedLd * sizeof(double);
+
+// The tile layout is scattered over the matrix, so the sums are placed (both triangles) in an LDS copy of the
+// matrix first and written out row by row.
+__global__ void __launch_bounds__(kRedThreads) gram_reduce(const float* partial, int wgs_per_head,
+                                                           double* g64, float* gram_out) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    double* L = reinterpret_cast<double*>(smem);
     const int kvh = blockIdx.x;
     const float* src = partial + static_cast<int64_t>(kvh) * wgs_per_head * kPartialFloats;
     double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     float* go = gram_out ? gram_out + static_cast<int64_t>(kvh) * kD * kD : nullptr;
-    for (int idx = threadIdx.x; idx < kPartialFloats; idx += blockDim.x) {
+    for (int idx = threadIdx.x; idx < kPartialFloats; idx += kRedThreads) {
         double s = 0.0;
         for (int w = 0; w < wgs_per_head; ++w) s += static_cast<double>(src[static_cast<int64_t>(w) * kPartialFloats + idx]);
         const int t = idx >> 10, e = (idx >> 6) & 15, lane = idx & 63;
@@ -307,18 +315,17 @@ __global__ void __launch_bounds__(256) gram_reduce(const float* partial, int wgs
         const int nn = lane & 31;
         const int mm = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
         const int row = 4 * mm + a, col = 4 * nn + b;
-        if (a == b) {
-            // diagonal tiles hold both (row, col) and (col, row); keep the upper one for an exactly symmetric result
-            if (row <= col) {
-                g[row * kD + col] = s;
-                g[col * kD + row] = s;
-                if (go) { go[row * kD + col] = static_cast<float>(s); go[col * kD + row] = static_cast<float>(s); }
-            }
-        } else {
-            g[row * kD + col] = s;
-            g[col * kD + row] = s;
-            if (go) { go[row * kD + col] = static_cast<float>(s); go[col * kD + row] = static_cast<float>(s); }
+        // diagonal tiles hold both (row, col) and (col, row); keep the upper one for an exactly symmetric result
+        if (a != b || row <= col) {
+            L[row * kRedLd + col] = s;
+            L[col * kRedLd + row] = s;
         }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kD * kD; idx += kRedThreads) {
+        const double v = L[(idx >> 7) * kRedLd + (idx & (kD - 1))];
+        g[idx] = v;
+        if (go) go[idx] = static_cast<float>(v);
     }
 }
 
@@ -484,6 +491,9 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(eig_tridiag_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kTriLdsBytes)) != hipSuccess)
             return SQUAT_E_HIP;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gram_reduce),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kRedLdsBytes)) != hipSuccess)
+            return SQUAT_E_HIP;
         attr_done = true;
     }
     switch (q_dt) {
@@ -493,7 +503,7 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
     }
     int rc = check_launch();
     if (rc) return rc;
-    hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(256), 0, s, p.partial, pl.wgs_per_head, g64, gram);
+    hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(kRedThreads), kRedLdsBytes, s, p.partial, pl.wgs_per_head, g64, gram);
     rc = check_launch();
     if (rc) return rc;
     if (r > 0) {
