@@ -265,7 +265,9 @@ def _queries(seed, hq, n, dtype, planted=12):
 
 
 @pytest.mark.parametrize("dtype,hq,qpk,n", [(synth.BF16, 8, 4, 1000), (synth.F32, 2, 1, 512), (synth.F16, 4, 2, 333),
-                                            (synth.BF16, 3, 1, 17)])
+                                            (synth.BF16, 3, 1, 17),
+                                            (synth.BF16, 16, 8, 40),       # a wavefront's units skip whole query heads
+                                            (synth.BF16, 1, 1, 20011)])    # many workgroups on one head, ragged tail
 def test_gram_and_subspace_match_oracle(dtype, hq, qpk, n):
     r = 8
     qt, qval = _queries(1100 + n, hq, n, dtype)
