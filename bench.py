@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--decode", action="store_true",
                     help="also time the decode-time flush shape (64 sequences, 32 buffered tokens per head): one "
                          "layer (8 heads) per launch and all 32 layers (256 heads) per launch (adds \"decode_flush\")")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="also run the whole path with one launch per stage and LAYER (8 KV heads per launch instead of "
+                         "all 256 stacked), launched eagerly and replayed from a HIP graph (adds \"per_layer\")")
     ap.add_argument("--with-copy", action="store_true",
                     help="profiling aid: also run one plain device copy of the key tensor (known size) per step, "
                          "to calibrate the FETCH_SIZE / WRITE_SIZE counters")
@@ -325,6 +328,71 @@ def main():
         del kp
         out["decode_scores"] = {"sequences": 64, "heads": H, "quantized_tokens": nd, "q_per_kv": wl.q_per_kv, "us": us,
                                 "keys_per_s": nk / (us * 1e-6), "frac_of_hbm_peak": nb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    if args.per_layer:
+        # The same work as `step`, issued layer by layer: 4 launches-groups x 32 layers.  Eager launches are
+        # bound by the host (ctypes marshalling per call); the graph replays the identical launches back to back.
+        kvh, qhs = wl.kv_heads, wl.kv_heads * wl.q_per_kv
+        ws_l = torch.empty(squat.build_subspace_workspace(n, kvh, wl.q_per_kv, d, wl.r), dtype=torch.uint8, device=dev)
+        wp_l = torch.empty(max(256, squat.prepare_workspace(kvh, d, wl.r, wl.g)), dtype=torch.uint8, device=dev)
+        codes_b = codes.clone()
+
+        def layer_step():
+            for l in range(wl.layers):
+                hs = slice(l * kvh, (l + 1) * kvh)
+                squat.build_subspace(wl.q[l * qhs:(l + 1) * qhs], wl.q_per_kv, wl.r, qhat=qhat[hs], eig=eig[hs], ws=ws_l)
+                squat.prepare(qhat[hs], wl.lam, wl.g, update=update[hs], ws=wp_l)
+                squat.quantize_keys(wl.k[:, hs], update[hs], wl.bits, wl.group, wl.g, codes=codes[:, hs],
+                                    scale=scale[:, hs], zero=zero[:, hs])
+                squat.dequantize_keys(codes[:, hs], scale[:, hs], zero[:, hs], wl.bits, wl.group, out=back[:, hs])
+
+        t_eager = timed(layer_step, reps=5)
+        codes_e = codes.clone()
+
+        # the same launches spread over 8 streams (layer l on stream l mod 8, each stream with its own workspaces)
+        NS = 8
+        streams = [torch.cuda.Stream() for _ in range(NS)]
+        ws_s = [torch.empty_like(ws_l) for _ in range(NS)]
+        wp_s = [torch.empty_like(wp_l) for _ in range(NS)]
+
+        def streams_step():
+            main = torch.cuda.current_stream()
+            start = torch.cuda.Event()
+            start.record(main)
+            for i, st in enumerate(streams):
+                st.wait_event(start)
+            for l in range(wl.layers):
+                i = l % NS
+                hs = slice(l * kvh, (l + 1) * kvh)
+                with torch.cuda.stream(streams[i]):
+                    squat.build_subspace(wl.q[l * qhs:(l + 1) * qhs], wl.q_per_kv, wl.r, qhat=qhat[hs], eig=eig[hs], ws=ws_s[i])
+                    squat.prepare(qhat[hs], wl.lam, wl.g, update=update[hs], ws=wp_s[i])
+                    squat.quantize_keys(wl.k[:, hs], update[hs], wl.bits, wl.group, wl.g, codes=codes[:, hs],
+                                        scale=scale[:, hs], zero=zero[:, hs])
+                    squat.dequantize_keys(codes[:, hs], scale[:, hs], zero[:, hs], wl.bits, wl.group, out=back[:, hs])
+            for st in streams:
+                done = torch.cuda.Event()
+                done.record(st)
+                main.wait_event(done)
+
+        codes.zero_()
+        t_streams = timed(streams_step, reps=5)
+        streams_equal = bool(torch.equal(codes, codes_e))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            layer_step()
+        codes.zero_()
+        t_graph = timed(graph.replay, reps=10)
+        out["per_layer"] = {"launch_groups": wl.layers, "heads_per_launch": kvh, "ms_per_step_eager": t_eager,
+                            "ms_per_step_graph": t_graph, "keys_per_s_graph": n_keys / (t_graph * 1e-3),
+                            "ms_per_step_8_streams": t_streams, "keys_per_s_8_streams": n_keys / (t_streams * 1e-3),
+                            "streams_codes_equal_eager": streams_equal,
+                            "graph_codes_equal_eager": bool(torch.equal(codes, codes_e)),
+                            # the Gram sums are grouped differently (32 workgroups per head instead of 1)
+                            "packed_words_differing_from_stacked": float((codes_e != codes_b).float().mean()),
+                            "note": "the per-head solvers (eigen-solver 0.44 ms, prepare 0.09 ms per launch whatever the "
+                                    "number of heads) run on 8 of 256 CUs here and are serial over the layers: stack the "
+                                    "layers, as the headline step does, or give each layer its own stream"}
+        del graph
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(dict(n_tokens=n, r=wl.r, lam=wl.lam, bits=wl.bits, group=wl.group,
                                                 g=wl.g, q_per_kv=wl.q_per_kv))
