@@ -125,7 +125,9 @@ __device__ __forceinline__ void load8(const unsigned char* p, float* out) {
 }
 
 // scores[b, hq, t0 + t] = out_scale * q[b, hq, :] . res[b, hq / qpk, t, :]   for t < count.  Eight lanes per
-// output (16 channels each, two 8-element loads), summed by three lane exchanges inside the group.
+// (batch, KV head, token): each loads its 16 channels of the key once and meets the same channels of the
+// KV head's query heads one after the other (the buffer is read once, not once per query head); a dot
+// product is summed by three lane exchanges inside the group.  total = batch x KV heads x count.
 template <int QDT, int KDT>
 __global__ void __launch_bounds__(256) residual_scores_kernel(const unsigned char* q, int64_t qsb, int64_t qsh,
                                                              const unsigned char* res, int slots, int count,
@@ -139,25 +141,27 @@ __global__ void __launch_bounds__(256) residual_scores_kernel(const unsigned cha
     if (!live) i = total - 1;                      // keep the whole wavefront in the shuffles below
     const int t = static_cast<int>(i % count);
     const int64_t r = i / count;
-    const int n_q = n_kv_heads * qpk;
-    const int hq = static_cast<int>(r % n_q);
-    const int64_t b = r / n_q;
-    const unsigned char* qrow = q + (b * qsb + hq * qsh) * QES + part * 16 * QES;
+    const int kvh = static_cast<int>(r % n_kv_heads);
+    const int64_t b = r / n_kv_heads;
     const unsigned char* krow =
-        res + ((b * n_kv_heads + hq / qpk) * slots + t) * static_cast<int64_t>(kD) * KES + part * 16 * KES;
-    float acc = 0.0f;
+        res + ((b * n_kv_heads + kvh) * slots + t) * static_cast<int64_t>(kD) * KES + part * 16 * KES;
+    float ka[16];
+    load8<KDT>(krow, ka);
+    load8<KDT>(krow + 8 * KES, ka + 8);
+    for (int h = 0; h < qpk; ++h) {
+        const int hq = kvh * qpk + h;
+        const unsigned char* qrow = q + (b * qsb + hq * qsh) * QES + part * 16 * QES;
+        float qa[16];
+        load8<QDT>(qrow, qa);
+        load8<QDT>(qrow + 8 * QES, qa + 8);
+        float acc = 0.0f;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        float qa[8], ka[8];
-        load8<QDT>(qrow + c * 8 * QES, qa);
-        load8<KDT>(krow + c * 8 * KES, ka);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc = fmaf(qa[e], ka[e], acc);
+        for (int e = 0; e < 16; ++e) acc = fmaf(qa[e], ka[e], acc);
+        acc += __shfl_xor(acc, 1, 64);
+        acc += __shfl_xor(acc, 2, 64);
+        acc += __shfl_xor(acc, 4, 64);
+        if (live && part == 0) scores[b * ssb + hq * ssh + t0 + t] = out_scale * acc;
     }
-    acc += __shfl_xor(acc, 1, 64);
-    acc += __shfl_xor(acc, 2, 64);
-    acc += __shfl_xor(acc, 4, 64);
-    if (live && part == 0) scores[b * ssb + hq * ssh + t0 + t] = out_scale * acc;
 }
 
 template <int QDT>
@@ -374,8 +378,8 @@ extern "C" int squat_cache_key_scores(const squat_cache* c, const void* q, squat
                                    q_stride_head, out_scale, scores, s_stride_batch, s_stride_head, stream);
     if (rc) return rc;
     if (c->n_kres == 0) return SQUAT_OK;
-    const int64_t total = f.n_batch * f.n_kv_heads * static_cast<int64_t>(f.q_per_kv) * c->n_kres;
-    const int64_t blocks = (total * 8 + 255) / 256;          // eight lanes per logit
+    const int64_t total = f.n_batch * f.n_kv_heads * static_cast<int64_t>(c->n_kres);
+    const int64_t blocks = (total * 8 + 255) / 256;          // eight lanes per buffered key
     if (blocks > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
     const dim3 grid(static_cast<unsigned>(blocks));
     hipStream_t s = static_cast<hipStream_t>(stream);
