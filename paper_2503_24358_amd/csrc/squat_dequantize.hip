@@ -22,6 +22,7 @@ struct DeqParams {
     int64_t ob, oh, ot;      // output strides in BYTES
     int64_t n_tokens;
     int n_heads;
+    uint32_t div_mul, div_shift;    // bh / n_heads == (bh * div_mul) >> div_shift for bh < 2^31
 };
 
 // Two floats -> two bf16 (round to nearest even, NaN stays NaN) in one word: the hardware conversion.
@@ -67,7 +68,9 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const DeqParams p) {
     const int64_t tok = flat >> 3;
     const int chunk = static_cast<int>(flat & 7);
     if (tok >= p.n_tokens) return;
-    const int64_t b = bh / p.n_heads;
+    // exact multiply-shift division (a 64-bit division is ~60 scalar instructions in front of every
+    // wavefront's first load, and the wavefronts of this kernel are short)
+    const int64_t b = static_cast<int64_t>((static_cast<uint64_t>(bh) * p.div_mul) >> p.div_shift);
     const int64_t h = bh - b * p.n_heads;
     const int64_t row = bh * p.n_tokens + tok;
 
@@ -107,7 +110,9 @@ __global__ void __launch_bounds__(256) dequantize_pc_kernel(const DeqParams p, c
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
     const int64_t tile = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
     if (tile >= tiles_per_seq) return;
-    const int64_t b = bh / p.n_heads;
+    // exact multiply-shift division (a 64-bit division is ~60 scalar instructions in front of every
+    // wavefront's first load, and the wavefronts of this kernel are short)
+    const int64_t b = static_cast<int64_t>((static_cast<uint64_t>(bh) * p.div_mul) >> p.div_shift);
     const int64_t h = bh - b * p.n_heads;
     const int64_t gt = bh * tiles_per_seq + tile;
     const int s = lane >> 4, pc = lane & 15;
@@ -231,6 +236,15 @@ extern "C" int squat_dequantize_keys(const uint32_t* codes, const uint16_t* scal
     p.ot = o_stride_token * es;
     p.n_tokens = n_tokens;
     p.n_heads = n_heads;
+    if (n_batch * n_heads >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    {
+        // floor(u / d) for u < 2^31: shift = 31 + ceil(log2 d), mul = floor(2^shift / d) + 1
+        const uint64_t dv = static_cast<uint64_t>(n_heads);
+        uint32_t l = 0;
+        while ((uint64_t(1) << l) < dv) ++l;
+        p.div_shift = 31 + l;
+        p.div_mul = static_cast<uint32_t>(((uint64_t(1) << p.div_shift) / dv) + 1);
+    }
 
     const int64_t gx = (n_tokens * 8 + 255) / 256;
     int64_t gy, gz;
@@ -269,6 +283,15 @@ extern "C" int squat_dequantize_keys_per_channel(const uint32_t* codes, const ui
     p.ot = o_stride_token * es;
     p.n_tokens = n_tokens;
     p.n_heads = n_heads;
+    if (n_batch * n_heads >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    {
+        // floor(u / d) for u < 2^31: shift = 31 + ceil(log2 d), mul = floor(2^shift / d) + 1
+        const uint64_t dv = static_cast<uint64_t>(n_heads);
+        uint32_t l = 0;
+        while ((uint64_t(1) << l) < dv) ++l;
+        p.div_shift = 31 + l;
+        p.div_mul = static_cast<uint32_t>(((uint64_t(1) << p.div_shift) / dv) + 1);
+    }
 
     const int64_t tiles = n_tokens / kTileTokens;
     const int64_t gx = (tiles + 3) / 4;
