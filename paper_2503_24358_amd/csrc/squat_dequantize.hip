@@ -119,10 +119,30 @@ __global__ void __launch_bounds__(256) dequantize_pc_kernel(const DeqParams p, c
 
     const int widx = 8 * s * BITS / 32;               // word of the channel that holds tokens 8 s .. 8 s + 7
     const int shift0 = (8 * s * BITS) % 32;
-    const uint32_t* cw = p.codes + gt * (kD * BITS) + (8 * pc) * BITS + widx;
+    // The tile's packed words come in with one (two for 4 bits) 16-byte load per lane, contiguous over the
+    // wavefront, and go through a wavefront-private LDS tile to the lanes that unpack them (a lane's own 8
+    // words are 4 BITS bytes apart in memory: fetched directly, every load instruction touched 16 to 32
+    // sectors for 256 bytes).  Every 16 words of the tile are followed by 4 words of padding, which spreads
+    // the 16 lanes of a token group over the banks.
+    constexpr int TW = kD * BITS;                     // words per tile
+    __shared__ __attribute__((aligned(16))) uint32_t tile_lds[4][TW + TW / 4];
+    uint32_t* tl = tile_lds[threadIdx.x >> 6];
+    const uint32_t* ct = p.codes + gt * TW;
+#pragma unroll
+    for (int i = 0; i < TW / 256; ++i) {
+        const int idx = (i * 64 + lane) * 4;
+        *reinterpret_cast<u32x4*>(tl + idx + (idx >> 4) * 4) =
+            __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ct + idx));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     uint32_t w[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) w[c] = cw[c * BITS] >> shift0;
+    for (int c = 0; c < 8; ++c) {
+        const int idx = (8 * pc + c) * BITS + widx;
+        w[c] = tl[idx + (idx >> 4) * 4] >> shift0;
+    }
     const u32x4 sraw = *reinterpret_cast<const u32x4*>(p.scale + gt * kD + 8 * pc);
     const u32x4 zraw = *reinterpret_cast<const u32x4*>(p.zero + gt * kD + 8 * pc);
     float sc[8], zp[8];
