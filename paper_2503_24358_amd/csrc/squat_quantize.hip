@@ -353,9 +353,12 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
             // ---- Lemma 2: remaining channels += U[rest, block] * error
             if constexpr (NPAIRS > 0) {
                 if (blk < NB - 1) {
-                    // two straight-line versions (with and without the low parts of the panels), so that
-                    // the operand reads of a chain can be issued ahead of its matrix products
-                    auto propagate = [&](auto lo_tag) {
+                    // Straight-line code, so that the operand reads of a chain can be issued ahead of its
+                    // matrix products.  The products with the low parts of the panels, needed only when some
+                    // panel entry is not an fp16 number, are a second, conditional pass (one pass with the
+                    // choice inside makes its two versions hand the working copy over in different registers:
+                    // a register move per value where they join).
+                    auto pass = [&](auto lo_tag) {
                         constexpr bool LO = decltype(lo_tag)::value;
 #pragma unroll
                         for (int jt = (blk + 1) * BT; jt < NT; ++jt) {
@@ -366,13 +369,10 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
                                 f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
                                 for (int kk = 0; kk < 2; ++kk) {
-                                    const half8 whi = wlds[((pr * 2 + kk) * 2 + 0) * 64 + lane];
-                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
-                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(whi, __builtin_bit_cast(half8, blo[jj][kk]), acc, 0, 0, 0);
-                                    if constexpr (LO) {
-                                        const half8 wlo = wlds[((pr * 2 + kk) * 2 + 1) * 64 + lane];
-                                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wlo, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
-                                    }
+                                    const half8 w = wlds[((pr * 2 + kk) * 2 + (LO ? 1 : 0)) * 64 + lane];
+                                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, __builtin_bit_cast(half8, bhi[jj][kk]), acc, 0, 0, 0);
+                                    if constexpr (!LO)
+                                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, __builtin_bit_cast(half8, blo[jj][kk]), acc, 0, 0, 0);
                                 }
                                 const float sc = g_scale[s / GT];
 #pragma unroll
@@ -380,10 +380,8 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
                             }
                         }
                     };
-                    if (need_lo)
-                        propagate(std::true_type{});
-                    else
-                        propagate(std::false_type{});
+                    pass(std::false_type{});
+                    if (need_lo) pass(std::true_type{});
                 }
             }
         }
