@@ -191,14 +191,13 @@ __global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p, c
 //     from the back (S_t needs the channels from t g on);
 //   - Cholesky: one wavefront per panel, lane = row, the row in REGISTERS, right-looking (the column
 //     being eliminated is broadcast with v_readlane);
-//   - triangular solves: every wavefront takes a few columns of Qb, lane = row again: the unknown just
-//     found is broadcast and every later row subtracts its multiple at once;
+//   - triangular solves: every wavefront takes a few pairs of columns of Qb, lane = row of one column of the
+//     pair: the unknown just found is broadcast and every later row subtracts its multiple at once;
 //   - W = -Qr^T X with four accumulators per entry.
 // A panel whose pivots span more than 1e9 (lambda times the largest eigenvalue of Qr Qr^T that large)
 // sets the head's flag: the eigen-route kernel, launched afterwards, redoes exactly the flagged heads.
 constexpr int kCholThreads = 512;           // 256 registers per thread: the Cholesky keeps a 32-double row in them
 constexpr int kCholLd = 33;
-constexpr int kCholCols = 12;          // columns of Qb per wavefront in the solves (8 wavefronts x 12 = 96)
 
 __device__ __forceinline__ double chol_readlane(double v, int src) {
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
@@ -264,9 +263,10 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
 #pragma unroll
             for (int k2 = j + 1; k2 < 32; ++k2) a[k2] = fma(-lj, chol_readlane(lj, k2), a[k2]);
         }
+        // stored with zeros above the diagonal: the solves below then need no row tests for them
         if (lane < 32) {
 #pragma unroll
-            for (int c = 0; c < 32; ++c) S[row * kCholLd + c] = a[c];
+            for (int c = 0; c < 32; ++c) S[row * kCholLd + c] = c > row ? 0.0 : a[c];
         }
         if (lane == 0 && !(pmin > 1e-9 * pmax)) atomicOr(bad, 1);       // also catches NaN
     }
@@ -277,48 +277,59 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     }
     if (tid == 0) need[head] = 0;
 
-    // X = S^-1 Qb: kCholCols columns per wavefront, lane = row
+    // X = S^-1 Qb.  A wavefront holds TWO columns of Qb per register (lanes 0..31 the rows of one, lanes 32..63
+    // the rows of the other, both of the same panel) and nsteps g / 16 such pairs (6 at g = 32, 4 at g = 64).  The
+    // unknown of a step is broadcast inside each half by a lane permutation through the LDS crossbar (two
+    // v_readlane per column, which is what a broadcast to all 64 lanes costs, made this phase 44 of the
+    // kernel's 70 us).
     {
-        const int ncols = nsteps * g;
-        const int col0 = wave * kCholCols;
-        if (col0 < ncols) {
-            // (a wavefront's columns may straddle two panels: every column carries its own panel index)
-            const int row = lane & 31;
-            double bcol[kCholCols];
-            int tt[kCholCols], jj[kCholCols];
+        const int pairs_per_panel = g / 2;
+        const int ppw = nsteps * pairs_per_panel / 8;     // pairs per wavefront: 6 or 4
+        const int row = lane & 31, half = lane >> 5;
+        double bcol[6];
+        int so[6];                                        // offset of the pair's panel in Sall (an index, so that the reads stay LDS reads)
+        int tq[6], jq[6];
 #pragma unroll
-            for (int q = 0; q < kCholCols; ++q) {
-                const int col = min(col0 + q, ncols - 1);
-                tt[q] = col / g;
-                jj[q] = col % g;
-                bcol[q] = static_cast<double>(Qf[row * QLD + tt[q] * g + jj[q]]);
-            }
-            // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
-            for (int k = 0; k < 32; ++k) {
+        for (int q = 0; q < 6; ++q) {
+            const int pr = min(wave + 8 * q, nsteps * pairs_per_panel - 1);
+            tq[q] = pr / pairs_per_panel;
+            jq[q] = 2 * (pr % pairs_per_panel) + half;
+            so[q] = tq[q] * 32 * kCholLd;
+            bcol[q] = static_cast<double>(Qf[row * QLD + tq[q] * g + jq[q]]);
+        }
+        const int src_base = 4 * (lane & 32);             // byte address of lane 0 of this half
+        auto half_bcast = [&](double v, int k) {
+            const int lo = __builtin_amdgcn_ds_bpermute(src_base + 4 * k, __double2loint(v));
+            const int hi = __builtin_amdgcn_ds_bpermute(src_base + 4 * k, __double2hiint(v));
+            return __hiloint2double(hi, lo);
+        };
+        // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k (C_ik = 0 for i < k as stored)
+        for (int k = 0; k < 32; ++k) {
+            const bool own = row == k;
 #pragma unroll
-                for (int q = 0; q < kCholCols; ++q) {
-                    const double* S = Sall + tt[q] * 32 * kCholLd;
-                    const double cik = S[row * kCholLd + k];                  // row == k: 1 / C_kk
-                    const double yk = chol_readlane(bcol[q] * cik, k);        // lane k holds b_k / C_kk
-                    bcol[q] = row == k ? yk : (row > k ? fma(-cik, yk, bcol[q]) : bcol[q]);
-                }
-            }
-            // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k
-            for (int k = 31; k >= 0; --k) {
-#pragma unroll
-                for (int q = 0; q < kCholCols; ++q) {
-                    const double* S = Sall + tt[q] * 32 * kCholLd;
-                    const double cki = S[k * kCholLd + row];                  // row == k: 1 / C_kk
-                    const double xk = chol_readlane(bcol[q] * cki, k);
-                    bcol[q] = row == k ? xk : (row < k ? fma(-cki, xk, bcol[q]) : bcol[q]);
-                }
-            }
-            if (lane < 32) {
-#pragma unroll
-                for (int q = 0; q < kCholCols; ++q)
-                    if (col0 + q < ncols) Xall[(tt[q] * 32 + row) * g + jj[q]] = bcol[q];
+            for (int q = 0; q < 6; ++q) {
+                // (no test on q here: pairs past ppw repeat the last one, so that the six chains stay one
+                // straight-line block and overlap their LDS round trips)
+                const double cik = Sall[so[q] + row * kCholLd + k];              // row == k: 1 / C_kk
+                const double tk = bcol[q] * cik;
+                const double yk = half_bcast(tk, k);
+                bcol[q] = own ? tk : fma(-cik, yk, bcol[q]);
             }
         }
+        // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k (C_ki = 0 for i > k as stored)
+        for (int k = 31; k >= 0; --k) {
+            const bool own = row == k;
+#pragma unroll
+            for (int q = 0; q < 6; ++q) {
+                const double cki = Sall[so[q] + k * kCholLd + row];
+                const double tk = bcol[q] * cki;
+                const double xk = half_bcast(tk, k);
+                bcol[q] = own ? tk : fma(-cki, xk, bcol[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+            if (q < ppw) Xall[(tq[q] * 32 + row) * g + jq[q]] = bcol[q];
     }
     __syncthreads();
 
