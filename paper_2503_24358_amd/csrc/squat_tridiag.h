@@ -599,6 +599,9 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     __threadfence_block();
     {
         double* V = L + kTriX;
+        // (unrolled, so that the loads of several trips are in flight together: one trip at a time, each of the 16
+        // trips waits out a whole global-memory round trip)
+#pragma unroll 8
         for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
             *reinterpret_cast<double2*>(V + e) = *reinterpret_cast<const double2*>(vws + e);
         __syncthreads();
