@@ -7,8 +7,8 @@
 //      REGISTERS: thread (row pair, lane l of the pair's team of 8) holds columns
 //      16 l .. 16 l + 15 of two rows; per step only the column being eliminated, the
 //      product A v and two scalars travel through LDS (two barriers per step).
-//   2. The r largest eigenvalues of T by 9-section on Sturm counts (8 trial
-//      shifts per eigenvalue and round, 18 rounds from [-3, 3] ||T||): the count
+//   2. The r largest eigenvalues of T by 17-section on Sturm counts (16 trial
+//      shifts per eigenvalue and round, 14 rounds from [-3, 3] ||T||): the count
 //      is the number of sign changes of the three-term recurrence of the leading
 //      principal minors, division-free, rescaled by a power of two every 8 terms.
 //   3. Eigenvectors of T by inverse iteration with those shifts (made distinct by
@@ -35,8 +35,8 @@ constexpr int kTriN = 128;
 constexpr int kTriRows = 2;              // matrix rows per thread
 constexpr int kTriThreads = kTriN / kTriRows * 8;   // 512: a row's 128 columns are spread over 8 lanes
 constexpr int kTriMaxR = 32;            // vectors the LDS plan holds
-constexpr int kTriPts = 8;              // trial shifts per eigenvalue and round
-constexpr int kTriRounds = 18;          // 9^18 > 6 * 2^53
+constexpr int kTriPts = 16;             // trial shifts per eigenvalue and round (32 eigenvalues x 16 = every thread of the block)
+constexpr int kTriRounds = 14;          // 17^14 > 6 * 2^53
 constexpr double kTriAccept = 1e-9;     // ||T x - lambda x|| / ||T|| and |x_i . x_j| allowed before the fallback
 
 // LDS plan, in doubles
@@ -56,6 +56,7 @@ constexpr int kTriS = kTriU2 + 4096;    // [32][33] Gram matrix / Cholesky facto
 constexpr int kTriLdsDoubles = kTriS + 32 * 33;
 constexpr size_t kTriLdsBytes = static_cast<size_t>(kTriLdsDoubles) * sizeof(double);
 static_assert(kTriLdsBytes <= 160 * 1024, "LDS plan exceeds a compute unit");
+static_assert(kTriPts * kTriMaxR <= kTriThreads && (kTriPts & (kTriPts - 1)) == 0 && kTriPts <= 32, "one thread per (eigenvalue, trial shift); a team's points are one aligned run of lanes");
 static_assert(kTriX + 16384 == kTriS, "vectors and factors form one 128 KB block (reused for the reflectors)");
 
 __device__ __forceinline__ double tri_block_max(double v, double* scratch, int tid) {
@@ -318,7 +319,7 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     }
     __syncthreads();
 
-    // ---- 2. the r largest eigenvalues by 9-section on Sturm counts
+    // ---- 2. the r largest eigenvalues by 17-section on Sturm counts
     if (tid < kTriPts * r) {
         const int j = tid / kTriPts, pt = tid % kTriPts;
         const int below_target = kTriN - 1 - j;           // eigenvalue j (descending) has this many below it
@@ -329,19 +330,22 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
             const double step = (hi - lo) * (1.0 / (kTriPts + 1));
             const double x = fma(step, static_cast<double>(pt + 1), lo);
             double p0 = 1.0, p1 = de[0] - x;
-            int cnt = static_cast<unsigned>(__double2hiint(p1)) >> 31;
-            for (int b = 1; b < kTriN; b += 8) {
+            // The signs of the minors are shifted into a register, newest at bit 0 (one instruction per term);
+            // a block's sign changes are then the ones of (signs ^ signs >> 1) over its terms.  The sign of
+            // p_0 = 1 is 0, so the first minor's own sign is a change.
+            uint32_t signs = static_cast<uint32_t>(__double2hiint(p1)) >> 31;
+            int cnt = static_cast<int>(signs);
+            auto block = [&](int b, auto nt_tag) {
+                constexpr int NTERMS = decltype(nt_tag)::value;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int ii = b + u;
-                    if (ii < kTriN) {
-                        const double2 t = *reinterpret_cast<const double2*>(de + 2 * ii);
-                        const double p2 = fma(t.x - x, p1, -(t.y * p0));
-                        cnt += static_cast<unsigned>(__double2hiint(p2) ^ __double2hiint(p1)) >> 31;
-                        p0 = p1;
-                        p1 = p2;
-                    }
+                for (int u = 0; u < NTERMS; ++u) {
+                    const double2 t = *reinterpret_cast<const double2*>(de + 2 * (b + u));
+                    const double p2 = fma(t.x - x, p1, -(t.y * p0));
+                    signs = __builtin_amdgcn_alignbit(signs, static_cast<uint32_t>(__double2hiint(p2)), 31);
+                    p0 = p1;
+                    p1 = p2;
                 }
+                cnt += __popc((signs ^ (signs >> 1)) & ((1u << NTERMS) - 1u));
                 // rescale the pair by a power of two (the larger one to [1, 2))
                 const double m = fmax(fabs(p0), fabs(p1));
                 const int ex = ((__double2hiint(m) >> 20) & 0x7FF) - 1023;
@@ -350,7 +354,10 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
                     p0 *= f;
                     p1 *= f;
                 }
-            }
+            };
+            static_assert((kTriN - 1) % 8 == 7, "15 blocks of 8 terms and one of 7");
+            for (int b = 1; b + 8 <= kTriN; b += 8) block(b, std::integral_constant<int, 8>{});
+            block(kTriN - 7, std::integral_constant<int, 7>{});
             // the team's points are ascending: those with count <= target are a prefix
             const unsigned long long mask = __ballot(cnt <= below_target);
             const int nb = __popc(static_cast<unsigned>((mask >> (lane & ~(kTriPts - 1))) & ((1u << kTriPts) - 1u)));
