@@ -106,11 +106,14 @@ __device__ __forceinline__ double tri_sum32(double v) {
 }
 
 // 1 / sqrt(x) and 1 / x from the hardware approximations and Newton steps (short dependent chains: the
-// library routines would sit on the critical path of every Householder step)
+// library routines would sit on the critical path of every Householder step).  The approximations are good
+// to 5e-8 relative (measured over 2^22 arguments across 120 binades), so two steps reach the last bit: the
+// largest relative error after one step is 4e-15, after two 2.6e-16 (reciprocal: 0 against the library's
+// division), and a third changes nothing.
 __device__ __forceinline__ double tri_rsqrt(double x) {
     double y = __builtin_amdgcn_rsq(x);
 #pragma unroll
-    for (int it = 0; it < 3; ++it) {
+    for (int it = 0; it < 2; ++it) {
         const double e = fma(-x * y, y, 1.0);
         y = fma(0.5 * y, e, y);
     }
@@ -119,7 +122,7 @@ __device__ __forceinline__ double tri_rsqrt(double x) {
 __device__ __forceinline__ double tri_rcp(double x) {
     double y = __builtin_amdgcn_rcp(x);
 #pragma unroll
-    for (int it = 0; it < 3; ++it) y = fma(y, fma(-x, y, 1.0), y);
+    for (int it = 0; it < 2; ++it) y = fma(y, fma(-x, y, 1.0), y);
     return y;
 }
 
