@@ -389,7 +389,7 @@ def main():
                             "graph_codes_equal_eager": bool(torch.equal(codes, codes_e)),
                             # the Gram sums are grouped differently (32 workgroups per head instead of 1)
                             "packed_words_differing_from_stacked": float((codes_e != codes_b).float().mean()),
-                            "note": "the per-head solvers (eigen-solver 0.44 ms, prepare 0.09 ms per launch whatever the "
+                            "note": "the per-head solvers (eigen-solver 0.37 ms, prepare 0.07 ms per launch whatever the "
                                     "number of heads) run on 8 of 256 CUs here and are serial over the layers: stack the "
                                     "layers, as the headline step does, or give each layer its own stream"}
         del graph
