@@ -199,9 +199,20 @@ def main():
     # The machine, and a practical ceiling measured beside the vendor peak: a plain elementwise device copy
     # of the key tensor (reads and writes keys x 256 B each).
     props = torch.cuda.get_device_properties(0)
+
+    def max_clock_mhz():
+        # rocminfo's "Max Clock Freq. (MHz)" of the first GPU agent (the torch properties do not carry it)
+        try:
+            import subprocess
+            txt = subprocess.run(["/opt/rocm/bin/rocminfo"], capture_output=True, text=True, timeout=20).stdout
+            gpu = txt[txt.index("Device Type:             GPU"):]
+            line = [ln for ln in gpu.splitlines() if "Max Clock Freq. (MHz)" in ln][0]
+            return int(line.split(":")[1])
+        except Exception:
+            return None
     t_copy = timed(lambda: back.copy_(wl.k.view_as(back)))
     out["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
-                     "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
+                     "max_clock_mhz": max_clock_mhz(),
                      "hbm_GiB": props.total_memory / 2 ** 30,
                      "device_copy_GBps": 2 * n_keys * d * 2 / (t_copy * 1e-3) / 1e9}
     roofline["frac_of_device_copy"] = achieved / out["device"]["device_copy_GBps"]
