@@ -45,9 +45,33 @@ def cpu_baseline(wl_args: dict, heads: int = 4, repeats: int = 8):
             out = O.quantize_keys(kval[h], U, bits, G, g)
             O.dequantize_keys(out["codes"], out["scale"], out["zero"], G)
     dt = time.perf_counter() - t0
+
+    def one_pass():
+        for h in range(heads):
+            Qh, _ = O.subspace(qval[h * qpk:(h + 1) * qpk], r)
+            U = O.update_matrix_lemma(Qh, lam, g)
+            out = O.quantize_keys(kval[h], U, bits, G, g)
+            O.dequantize_keys(out["codes"], out["scale"], out["zero"], G)
+
+    single = None
+    try:                                            # the same oracle with the BLAS / OpenMP pools held to one thread
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            t1 = time.perf_counter()
+            one_pass()
+            single = heads * n / (time.perf_counter() - t1)
+    except Exception:
+        pass
+    model = None
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = [ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")][0]
+    except Exception:
+        pass
     return {"value": repeats * heads * n / dt, "unit": "keys/s", "cores": int(threads), "kind": "oracle",
             "sample": "%d KV heads x %d tokens (pooled queries of %d query heads each), whole path, "
-                      "%d passes, %.1f s" % (heads, n, qpk, repeats, dt)}
+                      "%d passes, %.1f s" % (heads, n, qpk, repeats, dt),
+            "value_one_thread": single, "cpu_model": model, "cpu_count": os.cpu_count()}
 
 
 def main():
