@@ -355,7 +355,12 @@ def main():
                 t_app += e[0].elapsed_time(e[1])
                 t_sc += e[1].elapsed_time(e[2])
             cnt = cache.counts()
+            rope_us = None
+            if not per_channel:
+                # the same cache read as a store of pre-RoPE keys (rotation after dequantization), at its final state
+                rope_us = timed_us(lambda: cache.key_scores_rope(qd, inv_freq, 0, d ** -0.5, out=lc), reps=5)
             out[name] = {"sequences": 64, "heads": H, "tokens_cached": int(cnt.n_tokens), "residual": 32,
+                         "us_per_rope_logits_at_end": rope_us,
                          "us_per_append_mean_of_64": t_app / 64 * 1e3, "us_per_logits_mean_of_64": t_sc / 64 * 1e3,
                          "note": "append = copy into the residual buffer, plus every 32nd step one quantize "
                                  "launch over 64 x %d x 32 keys" % H}

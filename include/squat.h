@@ -351,7 +351,8 @@ int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, c
  *           time once they are older than `residual` tokens.
  *   keys    with key_per_channel: quantized with squat_quantize_keys_per_channel
  *           instead (groups of 32 tokens per channel, the paper's grouping).
- *   logits  squat_cache_key_scores = squat_key_scores (or _per_channel) over the quantized keys
+ *   logits  squat_cache_key_scores (squat_cache_key_scores_rope for keys stored before the rotary embedding)
+ *           = squat_key_scores (or _per_channel; or _rope) over the quantized keys
  *           followed by plain dot products over the residual keys:
  *           scores[b, hq, 0 .. keys_quantized + keys_residual).
  * ------------------------------------------------------------------------- */
@@ -426,6 +427,16 @@ int squat_cache_append(squat_cache* cache, const void* k, const void* v, int64_t
 int squat_cache_key_scores(const squat_cache* cache, const void* q, squat_dtype q_dt, int64_t q_stride_batch,
                            int64_t q_stride_head, float out_scale, float* scores, int64_t s_stride_batch,
                            int64_t s_stride_head, squat_stream stream);
+
+/* The same for a cache that holds the keys as they are BEFORE the rotary embedding (the paper's SQuat-pre
+ * variant, Section 4: rotation after dequantization): cache token t is rotated to position pos0 + t before it
+ * meets q (squat_key_scores_rope over the quantized keys; the buffered keys are rotated the same way, pairs of
+ * channels (c, c + d/2), angle position * inv_freq[c]).  inv_freq: [d/2] float, device.  q is taken as given
+ * (already rotated to its own position).  0 <= pos0 < 2^40.  Caches with key_per_channel = 1 are
+ * SQUAT_E_BADSHAPE (the rotating kernel reads the per-token store only). */
+int squat_cache_key_scores_rope(const squat_cache* cache, const void* q, squat_dtype q_dt, int64_t q_stride_batch,
+                                int64_t q_stride_head, const float* inv_freq, int64_t pos0, float out_scale,
+                                float* scores, int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
 
 #ifdef __cplusplus
 }

@@ -501,6 +501,23 @@ class CacheOracle:
             parts.append(float(out_scale) * (q @ np.stack(self.k_full).T))
         return np.concatenate(parts, axis=1) if parts else np.zeros((q.shape[0], 0))
 
+    def scores_rope(self, q, inv_freq, pos0: int = 0, out_scale: float = 1.0):
+        """The same for a cache that holds keys as they are before the rotary embedding (SQuat-pre,
+        Section 4): cached token t is rotated to position pos0 + t after dequantization (quantized
+        keys) or as it is (residual keys), then meets q.  Per-token key groups only."""
+        if self.key_axis != "token":
+            raise ValueError("rotation after dequantization is defined here for per-token key groups")
+        q = np.asarray(q, dtype=np.float64)
+        parts = []
+        nq = len(self.k_codes)
+        if nq:
+            parts.append(key_scores_rope(q, np.stack(self.k_codes), np.stack(self.k_scale), np.stack(self.k_zero),
+                                         self.G, inv_freq, pos0, out_scale))
+        if self.k_full:
+            rot = rope_rotate(np.stack(self.k_full), pos0 + nq + np.arange(len(self.k_full)), inv_freq)
+            parts.append(float(out_scale) * (q @ rot.T))
+        return np.concatenate(parts, axis=1) if parts else np.zeros((q.shape[0], 0))
+
 
 # --------------------------------------------------------------------------- #
 # Packed layout (ours to define; the paper does not fix one)

@@ -164,6 +164,76 @@ __global__ void __launch_bounds__(256) residual_scores_kernel(const unsigned cha
     }
 }
 
+// The same for keys stored before the rotary embedding: the buffered key of cache token t is rotated to position
+// pos0 + t first (pairs of channels (c, c + 64), angle position * inv_freq[c]; the partner channels sit in the
+// lane four to the side).  The angles depend on the token only, so a thread keeps its 16 (cos, sin) pairs and
+// goes over kRopeRes (batch, KV head) pairs with them.  total = ceil(batch x KV heads / kRopeRes) x count.
+constexpr int kRopeRes = 8;
+
+template <int QDT, int KDT>
+__global__ void __launch_bounds__(256) residual_scores_rope_kernel(const unsigned char* q, int64_t qsb, int64_t qsh,
+                                                                  const unsigned char* res, int slots, int count,
+                                                                  int64_t n_bh, int n_kv_heads, int qpk,
+                                                                  const float* inv_freq, int64_t pos_first,
+                                                                  float out_scale, float* scores, int64_t ssb,
+                                                                  int64_t ssh, int64_t t0, int64_t total) {
+    constexpr int QES = QDT == SQUAT_F32 ? 4 : 2, KES = KDT == SQUAT_F32 ? 4 : 2;
+    const int64_t gi = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int part = static_cast<int>(gi & 7);
+    int64_t i = gi >> 3;
+    const bool live = i < total;
+    if (!live) i = total - 1;                      // keep the whole wavefront in the shuffles below
+    const int t = static_cast<int>(i % count);
+    const int64_t rg = i / count;
+    float cs[16], sn[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        turn_sincos(static_cast<double>(pos_first + t), inv_freq[16 * (part & 3) + e], cs[e], sn[e]);
+    const float sgn = part < 4 ? -1.0f : 1.0f;     // x'_c = x_c cos - x_{c+64} sin,  x'_{c+64} = x_{c+64} cos + x_c sin
+    for (int j = 0; j < kRopeRes; ++j) {
+        const int64_t r = rg * kRopeRes + j;
+        if (r >= n_bh) break;                      // the same for the eight lanes of a group
+        const int kvh = static_cast<int>(r % n_kv_heads);
+        const int64_t b = r / n_kv_heads;
+        const unsigned char* krow = res + (r * slots + t) * static_cast<int64_t>(kD) * KES + part * 16 * KES;
+        float ka[16];
+        load8<KDT>(krow, ka);
+        load8<KDT>(krow + 8 * KES, ka + 8);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float other = __shfl_xor(ka[e], 4, 64);
+            ka[e] = fmaf(sgn * other, sn[e], ka[e] * cs[e]);
+        }
+        for (int h = 0; h < qpk; ++h) {
+            const int hq = kvh * qpk + h;
+            const unsigned char* qrow = q + (b * qsb + hq * qsh) * QES + part * 16 * QES;
+            float qa[16];
+            load8<QDT>(qrow, qa);
+            load8<QDT>(qrow + 8 * QES, qa + 8);
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc = fmaf(qa[e], ka[e], acc);
+            acc += __shfl_xor(acc, 1, 64);
+            acc += __shfl_xor(acc, 2, 64);
+            acc += __shfl_xor(acc, 4, 64);
+            if (live && part == 0) scores[b * ssb + hq * ssh + t0 + t] = out_scale * acc;
+        }
+    }
+}
+
+template <int QDT>
+int launch_residual_rope(squat_dtype kdt, dim3 grid, hipStream_t s, const unsigned char* q, int64_t qsb, int64_t qsh,
+                         const unsigned char* res, int slots, int count, int64_t n_bh, int n_kv_heads, int qpk,
+                         const float* inv_freq, int64_t pos_first, float out_scale, float* scores, int64_t ssb,
+                         int64_t ssh, int64_t t0, int64_t total) {
+    switch (kdt) {
+        case SQUAT_F32: hipLaunchKernelGGL((residual_scores_rope_kernel<QDT, SQUAT_F32>), grid, dim3(256), 0, s, q, qsb, qsh, res, slots, count, n_bh, n_kv_heads, qpk, inv_freq, pos_first, out_scale, scores, ssb, ssh, t0, total); break;
+        case SQUAT_F16: hipLaunchKernelGGL((residual_scores_rope_kernel<QDT, SQUAT_F16>), grid, dim3(256), 0, s, q, qsb, qsh, res, slots, count, n_bh, n_kv_heads, qpk, inv_freq, pos_first, out_scale, scores, ssb, ssh, t0, total); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((residual_scores_rope_kernel<QDT, SQUAT_BF16>), grid, dim3(256), 0, s, q, qsb, qsh, res, slots, count, n_bh, n_kv_heads, qpk, inv_freq, pos_first, out_scale, scores, ssb, ssh, t0, total); break;
+    }
+    return check_launch();
+}
+
 template <int QDT>
 int launch_residual(squat_dtype kdt, dim3 grid, hipStream_t s, const unsigned char* q, int64_t qsb, int64_t qsh,
                     const unsigned char* res, int slots, int count, int n_kv_heads, int qpk, float out_scale,
@@ -389,6 +459,43 @@ extern "C" int squat_cache_key_scores(const squat_cache* c, const void* q, squat
         case SQUAT_F32: return launch_residual<SQUAT_F32>(f.kv_dtype, grid, s, qp, q_stride_batch, q_stride_head, res, f.residual, c->n_kres, f.n_kv_heads, f.q_per_kv, out_scale, scores, s_stride_batch, s_stride_head, c->n_kq, total);
         case SQUAT_F16: return launch_residual<SQUAT_F16>(f.kv_dtype, grid, s, qp, q_stride_batch, q_stride_head, res, f.residual, c->n_kres, f.n_kv_heads, f.q_per_kv, out_scale, scores, s_stride_batch, s_stride_head, c->n_kq, total);
         case SQUAT_BF16: return launch_residual<SQUAT_BF16>(f.kv_dtype, grid, s, qp, q_stride_batch, q_stride_head, res, f.residual, c->n_kres, f.n_kv_heads, f.q_per_kv, out_scale, scores, s_stride_batch, s_stride_head, c->n_kq, total);
+    }
+    return SQUAT_E_BADDTYPE;
+}
+
+extern "C" int squat_cache_key_scores_rope(const squat_cache* c, const void* q, squat_dtype q_dt,
+                                           int64_t q_stride_batch, int64_t q_stride_head, const float* inv_freq,
+                                           int64_t pos0, float out_scale, float* scores, int64_t s_stride_batch,
+                                           int64_t s_stride_head, squat_stream stream) {
+    if (!c) return SQUAT_E_NULLPTR;
+    const squat_cache_config& f = c->cfg;
+    if (f.key_per_channel) return SQUAT_E_BADSHAPE;         // the rotating kernel reads the per-token store only
+    if (!q || !scores || !inv_freq) return SQUAT_E_NULLPTR;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (pos0 < 0 || pos0 >= (int64_t(1) << 40)) return SQUAT_E_BADSHAPE;
+    if (s_stride_head < c->n_kq + c->n_kres || s_stride_batch < 0 || q_stride_head < f.d || q_stride_batch < 0)
+        return SQUAT_E_BADSHAPE;
+    if ((q_stride_head % 8) || (q_stride_batch % 8) || !aligned(q, 16) || !aligned(scores, 4) || !aligned(inv_freq, 4))
+        return SQUAT_E_ALIGN;
+    int rc = key_scores_rope_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch, f.n_kv_heads,
+                                  c->n_kq, f.max_tokens, f.d, f.bits, f.group, inv_freq, pos0, q, q_dt, f.q_per_kv,
+                                  q_stride_batch, q_stride_head, out_scale, scores, s_stride_batch, s_stride_head,
+                                  stream);
+    if (rc) return rc;
+    if (c->n_kres == 0) return SQUAT_OK;
+    const int64_t n_bh = f.n_batch * f.n_kv_heads;
+    const int64_t total = ((n_bh + kRopeRes - 1) / kRopeRes) * static_cast<int64_t>(c->n_kres);
+    const int64_t blocks = (total * 8 + 255) / 256;          // eight lanes per (group of pairs, buffered token)
+    if (blocks > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(blocks));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned char* qp = static_cast<const unsigned char*>(q);
+    const unsigned char* res = static_cast<const unsigned char*>(c->buf.key_residual);
+    const int64_t pos_first = pos0 + c->n_kq;                // position of the oldest buffered key
+    switch (q_dt) {
+        case SQUAT_F32: return launch_residual_rope<SQUAT_F32>(f.kv_dtype, grid, s, qp, q_stride_batch, q_stride_head, res, f.residual, c->n_kres, n_bh, f.n_kv_heads, f.q_per_kv, inv_freq, pos_first, out_scale, scores, s_stride_batch, s_stride_head, c->n_kq, total);
+        case SQUAT_F16: return launch_residual_rope<SQUAT_F16>(f.kv_dtype, grid, s, qp, q_stride_batch, q_stride_head, res, f.residual, c->n_kres, n_bh, f.n_kv_heads, f.q_per_kv, inv_freq, pos_first, out_scale, scores, s_stride_batch, s_stride_head, c->n_kq, total);
+        case SQUAT_BF16: return launch_residual_rope<SQUAT_BF16>(f.kv_dtype, grid, s, qp, q_stride_batch, q_stride_head, res, f.residual, c->n_kres, n_bh, f.n_kv_heads, f.q_per_kv, inv_freq, pos_first, out_scale, scores, s_stride_batch, s_stride_head, c->n_kq, total);
     }
     return SQUAT_E_BADDTYPE;
 }

@@ -49,6 +49,7 @@ struct RopeParams {
     float* scores;
     int64_t ssb, ssh;
     int64_t n_tokens;
+    int64_t store_stride;            // tokens per (batch, KV head) in the store (>= n_tokens)
     int n_kv_heads;
     int qpk;
     float out_scale;
@@ -58,13 +59,6 @@ struct RopeParams {
 __device__ __forceinline__ uint32_t pack_h2(_Float16 lo, _Float16 hi) {
     return static_cast<uint32_t>(__builtin_bit_cast(uint16_t, lo)) |
            (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
-}
-
-// cos and sin of position * freq: the product is reduced to a fraction of a turn in fp64 first
-__device__ __forceinline__ void turn_sincos(double position, float freq, float& c, float& s) {
-    const double turns = position * static_cast<double>(freq) * 0.15915494309189535;   // / (2 pi)
-    const double frac = turns - rint(turns);                                           // [-0.5, 0.5]
-    sincospif(static_cast<float>(2.0 * frac), &s, &c);
 }
 
 template <int BITS, int NG, int QDT>
@@ -152,7 +146,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
         }
     }
 
-    const int64_t row0 = bh * p.n_tokens;
+    const int64_t row0 = bh * p.store_stride;
     const int widx0 = BITS == 2 ? (kb >> 1) : kb;         // word of chunk 0 this lane unpacks
     const uint32_t wshift = BITS == 2 ? 16u * (kb & 1) : 0u;
     float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
@@ -298,13 +292,15 @@ int launch_ng(int ng, const RopeParams& p, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
-extern "C" int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
-                                     int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
-                                     const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt,
-                                     int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head, float out_scale,
-                                     float* scores, int64_t s_stride_batch, int64_t s_stride_head,
-                                     squat_stream stream) {
+// squat_key_scores_rope over the first n_tokens tokens of a store that holds store_stride tokens per (batch, KV
+// head): what a cache reads with.
+int squat::key_scores_rope_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                                int n_kv_heads, int64_t n_tokens, int64_t store_stride, int d, int bits, int group,
+                                const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt, int q_per_kv,
+                                int64_t q_stride_batch, int64_t q_stride_head, float out_scale, float* scores,
+                                int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream) {
     if (d != kD) return SQUAT_E_BADSHAPE;
+    if (store_stride < n_tokens) return SQUAT_E_BADSHAPE;
     if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
     if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
     if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
@@ -334,6 +330,7 @@ extern "C" int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scal
     p.ssb = s_stride_batch;
     p.ssh = s_stride_head;
     p.n_tokens = n_tokens;
+    p.store_stride = store_stride;
     p.n_kv_heads = n_kv_heads;
     p.qpk = q_per_kv;
     p.out_scale = out_scale;
@@ -359,4 +356,15 @@ extern "C" int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scal
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? launch_ng<2>(128 / group, p, grid, s) : launch_ng<4>(128 / group, p, grid, s);
+}
+
+extern "C" int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                     int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
+                                     const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt,
+                                     int q_per_kv, int64_t q_stride_batch, int64_t q_stride_head, float out_scale,
+                                     float* scores, int64_t s_stride_batch, int64_t s_stride_head,
+                                     squat_stream stream) {
+    return squat::key_scores_rope_from(codes, scale, zero, n_batch, n_kv_heads, n_tokens, n_tokens, d, bits, group,
+                                       inv_freq, pos0, q, q_dt, q_per_kv, q_stride_batch, q_stride_head, out_scale,
+                                       scores, s_stride_batch, s_stride_head, stream);
 }

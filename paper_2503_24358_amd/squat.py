@@ -23,7 +23,7 @@ SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel", "squat_key_scores_rope",
            "squat_cache_arena_bytes", "squat_cache_create", "squat_cache_destroy", "squat_cache_reset",
            "squat_cache_state", "squat_cache_get_buffers", "squat_cache_prefill", "squat_cache_append",
-           "squat_cache_key_scores")
+           "squat_cache_key_scores", "squat_cache_key_scores_rope")
 
 
 class CacheConfig(ctypes.Structure):
@@ -110,6 +110,8 @@ def lib() -> ctypes.CDLL:
     L.squat_key_scores_per_channel.argtypes = list(L.squat_key_scores.argtypes)
     L.squat_cache_key_scores.restype = i32
     L.squat_cache_key_scores.argtypes = [vp, vp, i32, i64, i64, f32, vp, i64, i64, vp]
+    L.squat_cache_key_scores_rope.restype = i32
+    L.squat_cache_key_scores_rope.argtypes = [vp, vp, i32, i64, i64, vp, i64, f32, vp, i64, i64, vp]
     _lib = L
     return L
 
@@ -470,4 +472,22 @@ class Cache:
                                           _ptr(out), out.stride(0), out.stride(1), _stream(stream))
         if rc:
             raise SquatError(rc, "squat_cache_key_scores")
+        return out
+
+    def key_scores_rope(self, q: torch.Tensor, inv_freq: torch.Tensor, pos0: int = 0, out_scale: float = 1.0, out=None,
+                        stream=None) -> torch.Tensor:
+        """Logits against a cache of pre-RoPE keys: cache token t is rotated to position pos0 + t first.
+        inv_freq: [d/2] float32 on the device."""
+        _need_cuda(q, inv_freq)
+        if inv_freq.dtype != torch.float32 or not inv_freq.is_contiguous():
+            raise ValueError("inv_freq must be dense float32")
+        cnt = self.counts()
+        n = cnt.keys_quantized + cnt.keys_residual
+        if out is None:
+            out = torch.empty((q.shape[0], q.shape[1], n), dtype=torch.float32, device=q.device)
+        rc = lib().squat_cache_key_scores_rope(self._h, _ptr(q), _DT[q.dtype], q.stride(0), q.stride(1),
+                                               _ptr(inv_freq), int(pos0), float(out_scale), _ptr(out),
+                                               out.stride(0), out.stride(1), _stream(stream))
+        if rc:
+            raise SquatError(rc, "squat_cache_key_scores_rope")
         return out

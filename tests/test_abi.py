@@ -227,6 +227,18 @@ def test_cache_configuration_and_creation_are_validated_on_the_host():
     assert L.squat_cache_prefill(h, ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1000), -1, 0, 0, 128, None) == -2
     assert L.squat_cache_prefill(h, None, None, 0, 0, 0, 128, None) == 0               # nothing to do
     assert L.squat_cache_append(h, None, None, 0, 0, None) == -1
+    fake = ctypes.c_void_p(0x1000)
+    rope = lambda **kw: L.squat_cache_key_scores_rope(  # noqa: E731
+        kw.get("c", h), kw.get("q", fake), kw.get("dt", 2), 4096, 128, kw.get("f", fake), kw.get("pos0", 0), 1.0,
+        kw.get("s", fake), 1 << 20, 4096, None)
+    assert rope(f=None) == -1 and rope(q=None) == -1 and rope(s=None) == -1 and rope(c=None) == -1
+    assert rope(dt=6) == -3
+    assert rope(pos0=-1) == -2 and rope(pos0=1 << 40) == -2
+    assert rope() == 0                                                                 # empty cache: nothing launched
+    hp = ctypes.c_void_p()
+    assert L.squat_cache_create(ctypes.byref(pc), ctypes.c_void_p(0x100000), need, None, ctypes.byref(hp)) == 0
+    assert rope(c=hp) == -2                                                            # per-channel key store
+    L.squat_cache_destroy(hp)
     assert L.squat_cache_reset(h) == 0
     L.squat_cache_destroy(h)
     assert L.squat_cache_state(None, ctypes.byref(cnt)) == -1

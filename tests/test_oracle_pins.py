@@ -382,6 +382,33 @@ def test_rope_logits_are_rotations_applied_after_dequantization():
         assert np.allclose(got[:, t], want, rtol=1e-12, atol=1e-12)
 
 
+def test_cache_rope_logits_are_the_plain_ones_of_rotated_keys():
+    """CacheOracle.scores_rope: with zero frequencies it is `scores`; otherwise column t equals the plain
+    logit of the cached key t (dequantized or buffered) rotated by hand to position pos0 + t, and shifting
+    pos0 together with the query's position changes nothing (relative positions)."""
+    gen = np.random.default_rng(12)
+    d, G, R = 128, 32, 8
+    inv_freq = 10000.0 ** (-np.arange(64) / 64.0)
+    K = gen.standard_normal((21, d))
+    q = gen.standard_normal((3, d))
+    c = O.CacheOracle(None, 2, G, 128, R)
+    c.prefill(K[:13])                                  # 8 quantized, 5 buffered
+    for t in range(13, 21):
+        c.append(K[t])                                 # ends with 16 quantized, 5 buffered
+    assert len(c.k_codes) == 16 and len(c.k_full) == 5
+    assert np.array_equal(c.scores_rope(q, np.zeros(64), 7, 0.25), c.scores(q, 0.25))
+    got = c.scores_rope(q, inv_freq, pos0=5, out_scale=0.25)
+    deq = O.dequantize_keys(np.stack(c.k_codes), np.stack(c.k_scale), np.stack(c.k_zero), G)
+    cached = np.concatenate([deq, np.stack(c.k_full)])
+    for t in range(21):
+        ang = (5 + t) * inv_freq
+        a, b = cached[t, :64], cached[t, 64:]
+        rot = np.concatenate([a * np.cos(ang) - b * np.sin(ang), b * np.cos(ang) + a * np.sin(ang)])
+        assert np.allclose(got[:, t], 0.25 * q @ rot, rtol=1e-12, atol=1e-12)
+    qm = O.rope_rotate(q, np.full(3, 40), inv_freq)
+    assert np.allclose(c.scores_rope(qm, inv_freq, pos0=40), c.scores_rope(q, inv_freq, pos0=0), rtol=1e-9, atol=1e-9)
+
+
 def test_cache_bookkeeping_follows_algorithm_1():
     """Prefill split r = l mod R, flush every R decoded keys, values lag R tokens behind.  Per-token
     groups make every key independent, so whatever the order of the flushes the quantized store must
