@@ -22,7 +22,8 @@ Parity status of each function:
                                 per-step optimality against a generic solver,
                                 soft and hard invariants), both grouping axes
   CacheOracle                   pinned (counts against l mod R by hand, stores
-                                against one-shot quantization of the prefix)
+                                against one-shot quantization of the prefix; scores_rope:
+                                zero frequencies = scores, hand-rotated cached keys)
   key_scores_rope, rope_rotate  pinned (norm preservation, relative-position identity, explicit
                                 2x2 rotations, zero angle = key_scores)
   key_scores                    pinned (element loops, one-hot queries, closed
