@@ -249,6 +249,7 @@ def main():
     out["per_channel"] = []
     qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()                      # [1, q_heads, d]: the last prompt token's queries
     logits = torch.empty((1, H * wl.q_per_kv, n), dtype=torch.float32, device=dev)
+    inv_freq = (10000.0 ** (-torch.arange(64, dtype=torch.float64, device=dev) / 64.0)).float()
     for bits, g, use_update in pc_list:
         upd = (update if g == wl.g else squat.prepare(qhat, wl.lam, g)) if use_update else None
         c = torch.empty((1, H, n // 32, d, bits), dtype=torch.int32, device=dev)
@@ -257,6 +258,9 @@ def main():
         tq = timed(lambda: squat.quantize_keys_per_channel(wl.k, upd, bits, 32, g, codes=c, scale=sc, zero=ze))
         td = timed(lambda: squat.dequantize_keys_per_channel(c, sc, ze, bits, 32, out=back))
         tsc = timed(lambda: squat.key_scores_per_channel(qdec, c, sc, ze, bits, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
+        # the same store read as pre-RoPE keys (rotation after dequantization: the paper's SQuat-pre on its own grouping)
+        tsr = timed(lambda: squat.key_scores_rope_per_channel(qdec, c, sc, ze, bits, wl.q_per_kv, inv_freq, 0, d ** -0.5,
+                                                              out=logits), reps=10)
         nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // 32))
         sb = n_keys * (d * bits // 8 + 4 * (d // 32) + 4 * wl.q_per_kv)
         out["per_channel"].append({"bits": bits, "token_group": 32, "g": g, "update": use_update,
@@ -264,7 +268,9 @@ def main():
                                    "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                    "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                    "key_scores_us": tsc * 1e3, "key_scores_bytes_per_key": sb // n_keys,
-                                   "key_scores_frac_of_hbm_peak": sb / (tsc * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                                   "key_scores_frac_of_hbm_peak": sb / (tsc * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "key_scores_rope_us": tsr * 1e3,
+                                   "key_scores_rope_frac_of_hbm_peak": sb / (tsr * 1e-3) / 1e9 / HBM_PEAK_GBS})
     # Decode-side consumer: attention logits of one query token per query head straight from the packed
     # store just written (48 B of codes and metadata in, 4 B per query head out, per key).
     ts = timed(lambda: squat.key_scores(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
@@ -274,7 +280,6 @@ def main():
                          "frac_of_hbm_peak": sbytes / (ts * 1e-3) / 1e9 / HBM_PEAK_GBS}
     # the pre-RoPE variant of the same consumer: keys dequantized, rotated to their positions and rounded to
     # fp16 in registers before the contraction (bound by vector arithmetic, not by HBM)
-    inv_freq = (10000.0 ** (-torch.arange(64, dtype=torch.float64, device=dev) / 64.0)).float()
     tr = timed(lambda: squat.key_scores_rope(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, inv_freq, 0,
                                              d ** -0.5, out=logits), reps=10)
     out["key_scores_rope"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bound": "alu", "us": tr * 1e3,
@@ -355,10 +360,8 @@ def main():
                 t_app += e[0].elapsed_time(e[1])
                 t_sc += e[1].elapsed_time(e[2])
             cnt = cache.counts()
-            rope_us = None
-            if not per_channel:
-                # the same cache read as a store of pre-RoPE keys (rotation after dequantization), at its final state
-                rope_us = timed_us(lambda: cache.key_scores_rope(qd, inv_freq, 0, d ** -0.5, out=lc), reps=5)
+            # the same cache read as a store of pre-RoPE keys (rotation after dequantization), at its final state
+            rope_us = timed_us(lambda: cache.key_scores_rope(qd, inv_freq, 0, d ** -0.5, out=lc), reps=5)
             out[name] = {"sequences": 64, "heads": H, "tokens_cached": int(cnt.n_tokens), "residual": 32,
                          "us_per_rope_logits_at_end": rope_us,
                          "us_per_append_mean_of_64": t_app / 64 * 1e3, "us_per_logits_mean_of_64": t_sc / 64 * 1e3,

@@ -333,6 +333,30 @@ int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, c
                                  squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
+ * squat_key_scores_rope_per_channel  (Section 4: the pre-RoPE variant, rotation
+ * after dequantization, on the grouping Algorithm 1's Quant function prints:
+ * the combination the paper's main tables report as SQuat-pre).
+ *
+ * scores[b, hq, t] = out_scale * sum_c q[b, hq, c] * RoPE_{pos0 + t}(deq(t, :))[c]
+ * with deq(t, c) = code * scale + zero of (token group t / 32, channel c) and
+ * RoPE as for squat_key_scores_rope.
+ *
+ *   codes, scale, zero   as written by squat_quantize_keys_per_channel, dense,
+ *            all three 16-byte aligned.  group must be 32, n_tokens a multiple
+ *            of 32 and < 2^25.
+ *   inv_freq, pos0   as for squat_key_scores_rope.
+ *   q, q_per_kv, out_scale, scores and their strides   as for squat_key_scores
+ *            (|q| below the fp16 range, 65504).
+ *   Accuracy: as squat_key_scores_rope (rotated key rounded to fp16).
+ * ------------------------------------------------------------------------- */
+int squat_key_scores_rope_per_channel(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                      int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits,
+                                      int group, const float* inv_freq, int64_t pos0, const void* q,
+                                      squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                                      int64_t q_stride_head, float out_scale, float* scores,
+                                      int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
  * squat_cache_*  (Algorithm 1: the prefill split "r = l mod R", the residual
  * buffer K^full and its flush in the decoding phase; appendix "Details of Our
  * Main Algorithm": values follow KIVI, per-token groups, the most recent R
@@ -430,10 +454,10 @@ int squat_cache_key_scores(const squat_cache* cache, const void* q, squat_dtype 
 
 /* The same for a cache that holds the keys as they are BEFORE the rotary embedding (the paper's SQuat-pre
  * variant, Section 4: rotation after dequantization): cache token t is rotated to position pos0 + t before it
- * meets q (squat_key_scores_rope over the quantized keys; the buffered keys are rotated the same way, pairs of
- * channels (c, c + d/2), angle position * inv_freq[c]).  inv_freq: [d/2] float, device.  q is taken as given
- * (already rotated to its own position).  0 <= pos0 < 2^40.  Caches with key_per_channel = 1 are
- * SQUAT_E_BADSHAPE (the rotating kernel reads the per-token store only). */
+ * meets q (squat_key_scores_rope, or squat_key_scores_rope_per_channel for caches with key_per_channel = 1,
+ * over the quantized keys; the buffered keys are rotated the same way, pairs of channels (c, c + d/2), angle
+ * position * inv_freq[c]).  inv_freq: [d/2] float, device.  q is taken as given (already rotated to its own
+ * position).  0 <= pos0 < 2^40. */
 int squat_cache_key_scores_rope(const squat_cache* cache, const void* q, squat_dtype q_dt, int64_t q_stride_batch,
                                 int64_t q_stride_head, const float* inv_freq, int64_t pos0, float out_scale,
                                 float* scores, int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);

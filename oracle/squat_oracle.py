@@ -408,12 +408,14 @@ def rope_rotate(x: np.ndarray, positions: np.ndarray, inv_freq: np.ndarray) -> n
 
 
 def key_scores_rope(q: np.ndarray, codes: np.ndarray, scale: np.ndarray, zero: np.ndarray, G: int,
-                    inv_freq: np.ndarray, pos0: int = 0, out_scale: float = 1.0) -> np.ndarray:
+                    inv_freq: np.ndarray, pos0: int = 0, out_scale: float = 1.0,
+                    axis: str = "token") -> np.ndarray:
     """Logits against keys that were quantized BEFORE the rotary embedding (the SQuat-pre variant of
     Section 4: the cache holds pre-RoPE keys and positions are applied on the fly after
     dequantization): out_scale * q . RoPE_{pos0 + t}(deq(code_t)).  q is taken as given (the caller
-    has already rotated it to its own position).  Per-token groups.  Returns (n_q, n) float64."""
-    khat = dequantize_keys(codes, scale, zero, G)
+    has already rotated it to its own position).  `axis` as in dequantize_keys ("channel": the
+    grouping Algorithm 1 prints, statistics per channel over G tokens).  Returns (n_q, n) float64."""
+    khat = dequantize_keys(codes, scale, zero, G, axis=axis)
     rot = rope_rotate(khat, pos0 + np.arange(khat.shape[0]), inv_freq)
     return float(out_scale) * (np.asarray(q, dtype=np.float64) @ rot.T)
 
@@ -505,15 +507,14 @@ class CacheOracle:
     def scores_rope(self, q, inv_freq, pos0: int = 0, out_scale: float = 1.0):
         """The same for a cache that holds keys as they are before the rotary embedding (SQuat-pre,
         Section 4): cached token t is rotated to position pos0 + t after dequantization (quantized
-        keys) or as it is (residual keys), then meets q.  Per-token key groups only."""
-        if self.key_axis != "token":
-            raise ValueError("rotation after dequantization is defined here for per-token key groups")
+        keys) or as it is (residual keys), then meets q."""
         q = np.asarray(q, dtype=np.float64)
         parts = []
         nq = len(self.k_codes)
         if nq:
             parts.append(key_scores_rope(q, np.stack(self.k_codes), np.stack(self.k_scale), np.stack(self.k_zero),
-                                         self.G, inv_freq, pos0, out_scale))
+                                         32 if self.key_axis == "channel" else self.G, inv_freq, pos0, out_scale,
+                                         axis=self.key_axis))
         if self.k_full:
             rot = rope_rotate(np.stack(self.k_full), pos0 + nq + np.arange(len(self.k_full)), inv_freq)
             parts.append(float(out_scale) * (q @ rot.T))

@@ -469,7 +469,6 @@ extern "C" int squat_cache_key_scores_rope(const squat_cache* c, const void* q, 
                                            int64_t s_stride_head, squat_stream stream) {
     if (!c) return SQUAT_E_NULLPTR;
     const squat_cache_config& f = c->cfg;
-    if (f.key_per_channel) return SQUAT_E_BADSHAPE;         // the rotating kernel reads the per-token store only
     if (!q || !scores || !inv_freq) return SQUAT_E_NULLPTR;
     if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
     if (pos0 < 0 || pos0 >= (int64_t(1) << 40)) return SQUAT_E_BADSHAPE;
@@ -477,10 +476,15 @@ extern "C" int squat_cache_key_scores_rope(const squat_cache* c, const void* q, 
         return SQUAT_E_BADSHAPE;
     if ((q_stride_head % 8) || (q_stride_batch % 8) || !aligned(q, 16) || !aligned(scores, 4) || !aligned(inv_freq, 4))
         return SQUAT_E_ALIGN;
-    int rc = key_scores_rope_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch, f.n_kv_heads,
-                                  c->n_kq, f.max_tokens, f.d, f.bits, f.group, inv_freq, pos0, q, q_dt, f.q_per_kv,
-                                  q_stride_batch, q_stride_head, out_scale, scores, s_stride_batch, s_stride_head,
-                                  stream);
+    int rc = f.key_per_channel
+                 ? key_scores_pc_rope_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch,
+                                           f.n_kv_heads, c->n_kq, f.max_tokens, f.d, f.bits, kTileTokens, inv_freq,
+                                           pos0, q, q_dt, f.q_per_kv, q_stride_batch, q_stride_head, out_scale,
+                                           scores, s_stride_batch, s_stride_head, stream)
+                 : key_scores_rope_from(c->buf.key_codes, c->buf.key_scale, c->buf.key_zero, f.n_batch, f.n_kv_heads,
+                                        c->n_kq, f.max_tokens, f.d, f.bits, f.group, inv_freq, pos0, q, q_dt,
+                                        f.q_per_kv, q_stride_batch, q_stride_head, out_scale, scores,
+                                        s_stride_batch, s_stride_head, stream);
     if (rc) return rc;
     if (c->n_kres == 0) return SQUAT_OK;
     const int64_t n_bh = f.n_batch * f.n_kv_heads;

@@ -122,6 +122,12 @@ int key_scores_rope_from(const uint32_t* codes, const uint16_t* scale, const uin
                          int64_t q_stride_batch, int64_t q_stride_head, float out_scale, float* scores,
                          int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
 
+int key_scores_pc_rope_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                            int n_kv_heads, int64_t n_tokens, int64_t store_tokens, int d, int bits, int group,
+                            const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt, int q_per_kv,
+                            int64_t q_stride_batch, int64_t q_stride_head, float out_scale, float* scores,
+                            int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream);
+
 #if defined(__HIPCC__)
 // cos and sin of position * freq: the product is reduced to a fraction of a turn in fp64 first
 __device__ __forceinline__ void turn_sincos(double position, float freq, float& c, float& s) {

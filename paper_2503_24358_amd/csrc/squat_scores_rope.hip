@@ -268,6 +268,209 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
     }
 }
 
+// The same against the PER-CHANNEL store (statistics per channel over 32 tokens: codes
+// [tile][channel][BITS words], token j of the tile at bit BITS * (j mod 32 / BITS) of word j / (32 / BITS);
+// scale / zero [tile][channel]).  A wavefront goes over tiles of 32 tokens: the tile's words and metadata come
+// in with contiguous 16-byte loads, pass through a wavefront-private LDS tile, and are consumed as two units of
+// 16 tokens (lane = token of the unit x K block, as above; the lane's 32 channels each give one word per unit).
+// p.n_tokens and p.store_stride are multiples of 32; p.units_per_wave counts TILES here.
+template <int BITS, int QDT>
+__global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(const RopeParams p) {
+    constexpr int TW = kD * BITS;                         // packed words per tile
+    constexpr int NCL = TW / 256;                         // 16-byte code loads per lane and tile
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int kb = lane >> 4;
+    const int col = lane & 15;
+    const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
+    const int64_t b = bh / p.n_kv_heads;
+    const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
+
+    constexpr int QLD = kD + 1;
+    __shared__ float qlds[8 * QLD];
+    __shared__ float step_cs[2 * 64];
+    {
+        const int e0 = 4 * static_cast<int>(threadIdx.x);
+        const int qrow = e0 / kD, qch = e0 % kD;
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (qrow < p.qpk) {
+            const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
+            if constexpr (QDT == SQUAT_F32) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
+                v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+            } else {
+                const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
+                    v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
+                                             : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qlds[qrow * QLD + qch + i] = v[i];
+        if (threadIdx.x < 64) {
+            float c, s;
+            turn_sincos(static_cast<double>(kRopeUnit), p.inv_freq[threadIdx.x], c, s);
+            step_cs[2 * threadIdx.x] = c;
+            step_cs[2 * threadIdx.x + 1] = s;
+        }
+    }
+    __syncthreads();
+
+    const int qh = col >> 1, part = col & 1;
+    u32x4 aop[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            _Float16 h[2];
+#pragma unroll
+            for (int pp = 0; pp < 2; ++pp) {
+                const float v = qlds[qh * QLD + 32 * g + 8 * kb + 2 * r + pp];
+                const _Float16 hi = static_cast<_Float16>(v);
+                h[pp] = part == 0 ? hi : static_cast<_Float16>(v - static_cast<float>(hi));
+            }
+            aop[g][r] = pack_h2(h[0], h[1]);
+        }
+
+    // ---- this wavefront's tiles
+    const int n_tiles = static_cast<int>(p.n_tokens / 32);
+    const int t0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
+    const int t1 = min(t0 + p.units_per_wave, n_tiles);
+    if (t0 >= t1) return;                                 // after the last workgroup barrier
+
+    float cs[16], sn[16], dc[16], ds[16];
+    {
+        const double position = static_cast<double>(p.pos0 + static_cast<int64_t>(t0) * 32 + col);
+#pragma unroll
+        for (int f = 0; f < 16; ++f) {
+            const int ch = 32 * (f >> 3) + 8 * kb + (f & 7);
+            turn_sincos(position, p.inv_freq[ch], cs[f], sn[f]);
+            dc[f] = step_cs[2 * ch];
+            ds[f] = step_cs[2 * ch + 1];
+        }
+    }
+
+    const int64_t tile0 = bh * (p.store_stride / 32);
+    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
+    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    const float fin = p.out_scale;
+
+    constexpr int TILE_BYTES = TW * 4 + 512;              // words, then 128 scales and 128 zero-points (fp16)
+    __shared__ __attribute__((aligned(16))) unsigned char lds_all[kRopeWaves * TILE_BYTES];
+    unsigned char* lds = lds_all + wave * TILE_BYTES;
+    const uint32_t* ldsw = reinterpret_cast<const uint32_t*>(lds);
+    struct Raw {
+        u32x4 c[NCL];
+        u32x4 m;
+    };
+    const bool is_m = lane < 32;                          // lanes 0..15: scales, 16..31: zero-points (8 channels each)
+    auto fetch = [&](int t, Raw& r) {
+        const int64_t tile = tile0 + t;
+        const uint32_t* cw = p.codes + tile * TW;
+#pragma unroll
+        for (int i = 0; i < NCL; ++i) r.c[i] = RP_LOAD(reinterpret_cast<const u32x4*>(cw + (i * 64 + lane) * 4));
+        r.m = u32x4{0u, 0u, 0u, 0u};
+        if (is_m) {
+            const uint16_t* mb = ((lane & 16) ? p.zero : p.scale) + tile * kD + 8 * (lane & 15);
+            r.m = RP_LOAD(reinterpret_cast<const u32x4*>(mb));
+        }
+    };
+
+    auto compute = [&](int t, const Raw& raw) {
+#pragma unroll
+        for (int i = 0; i < NCL; ++i) *reinterpret_cast<u32x4*>(lds + (i * 64 + lane) * 16) = raw.c[i];
+        if (is_m) *reinterpret_cast<u32x4*>(lds + TW * 4 + lane * 16) = raw.m;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // scales and zero-points of this lane's channels 32 g + 8 kb .. + 7 (fp16 pairs)
+        u32x4 sraw[4], zraw[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            sraw[g] = *reinterpret_cast<const u32x4*>(lds + TW * 4 + (32 * g + 8 * kb) * 2);
+            zraw[g] = *reinterpret_cast<const u32x4*>(lds + TW * 4 + 256 + (32 * g + 8 * kb) * 2);
+        }
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            // token 16 hf + col of the tile: word and bit of its code inside a channel's words
+            const int widx = BITS == 2 ? hf : 2 * hf + (col >> 3);
+            const uint32_t bit = BITS == 2 ? 2u * col : 4u * (col & 7);
+            uint32_t w[4][8];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) w[g][i] = ldsw[(32 * g + 8 * kb + i) * BITS + widx];
+            float k[4][8];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t sw = sraw[g][i >> 1], zw = zraw[g][i >> 1];
+                    const float sc = static_cast<float>(
+                        __builtin_bit_cast(_Float16, static_cast<uint16_t>((i & 1) ? (sw >> 16) : (sw & 0xFFFFu))));
+                    const float zp = static_cast<float>(
+                        __builtin_bit_cast(_Float16, static_cast<uint16_t>((i & 1) ? (zw >> 16) : (zw & 0xFFFFu))));
+                    const uint32_t code = (w[g][i] >> bit) & ((1u << BITS) - 1u);
+                    k[g][i] = fmaf(static_cast<float>(code), sc, zp);
+                }
+#pragma unroll
+            for (int f = 0; f < 16; ++f) {
+                const int g = f >> 3, i = f & 7;
+                const float a = k[g][i], bb = k[g + 2][i];
+                k[g][i] = fmaf(a, cs[f], -(bb * sn[f]));
+                k[g + 2][i] = fmaf(bb, cs[f], a * sn[f]);
+                const float c2 = fmaf(cs[f], dc[f], -(sn[f] * ds[f]));
+                sn[f] = fmaf(sn[f], dc[f], cs[f] * ds[f]);
+                cs[f] = c2;
+            }
+            f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x4 bop;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    bop[r] = pack_h2(static_cast<_Float16>(k[g][2 * r]), static_cast<_Float16>(k[g][2 * r + 1]));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]),
+                                                             __builtin_bit_cast(half8, bop), acc, 0, 0, 0);
+            }
+            const int64_t tok = static_cast<int64_t>(t) * 32 + 16 * hf + col;
+            if (st0) __builtin_nontemporal_store(fin * (acc[0] + acc[1]), out0 + tok);
+            if (st1) __builtin_nontemporal_store(fin * (acc[2] + acc[3]), out0 + p.ssh + tok);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    Raw ring[kRopeDepth];
+#pragma unroll
+    for (int i = 0; i < kRopeDepth; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
+    for (int t = t0; t < t1; t += kRopeDepth) {
+#pragma unroll
+        for (int i = 0; i < kRopeDepth; ++i) {
+            const Raw cur = ring[i];
+            fetch(min(t + i + kRopeDepth, t1 - 1), ring[i]);
+            if (t + i < t1) compute(t + i, cur);
+        }
+    }
+}
+
+template <int BITS>
+int launch_pc_dt(const RopeParams& p, dim3 grid, hipStream_t s) {
+    const dim3 block(kRopeWaves * kWave);
+    switch (p.q_dt) {
+        case SQUAT_F32: hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, SQUAT_F32>), grid, block, 0, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, SQUAT_F16>), grid, block, 0, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, SQUAT_BF16>), grid, block, 0, s, p); break;
+        default: return SQUAT_E_BADDTYPE;
+    }
+    return check_launch();
+}
+
 template <int BITS, int NG>
 int launch_dt(const RopeParams& p, dim3 grid, hipStream_t s) {
     const dim3 block(kRopeWaves * kWave);
@@ -367,4 +570,81 @@ extern "C" int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scal
     return squat::key_scores_rope_from(codes, scale, zero, n_batch, n_kv_heads, n_tokens, n_tokens, d, bits, group,
                                        inv_freq, pos0, q, q_dt, q_per_kv, q_stride_batch, q_stride_head, out_scale,
                                        scores, s_stride_batch, s_stride_head, stream);
+}
+
+// Per-channel store: the first n_tokens tokens (a multiple of 32) of a store that holds store_tokens per (batch, KV head).
+int squat::key_scores_pc_rope_from(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero, int64_t n_batch,
+                                   int n_kv_heads, int64_t n_tokens, int64_t store_tokens, int d, int bits, int group,
+                                   const float* inv_freq, int64_t pos0, const void* q, squat_dtype q_dt, int q_per_kv,
+                                   int64_t q_stride_batch, int64_t q_stride_head, float out_scale, float* scores,
+                                   int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (bits != 2 && bits != 4) return SQUAT_E_BADSHAPE;
+    if (group != kTileTokens) return SQUAT_E_BADSHAPE;
+    if (q_per_kv < 1 || q_per_kv > 8) return SQUAT_E_BADSHAPE;
+    if (n_batch < 0 || n_kv_heads < 0 || n_tokens < 0 || n_tokens >= (int64_t(1) << 25) || n_tokens % group)
+        return SQUAT_E_BADSHAPE;
+    if (store_tokens < n_tokens || store_tokens % group) return SQUAT_E_BADSHAPE;
+    if (pos0 < 0 || pos0 >= (int64_t(1) << 40)) return SQUAT_E_BADSHAPE;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (!(out_scale == out_scale)) return SQUAT_E_BADVALUE;
+    if (n_batch == 0 || n_kv_heads == 0 || n_tokens == 0) return SQUAT_OK;
+    if (!codes || !scale || !zero || !q || !scores || !inv_freq) return SQUAT_E_NULLPTR;
+    if (q_stride_head < d || q_stride_batch < 0 || s_stride_head < n_tokens || s_stride_batch < 0) return SQUAT_E_BADSHAPE;
+    if ((q_stride_head % 8) || (q_stride_batch % 8)) return SQUAT_E_ALIGN;
+    if (!aligned(codes, 16) || !aligned(scale, 16) || !aligned(zero, 16) || !aligned(scores, 4) || !aligned(q, 16) ||
+        !aligned(inv_freq, 4))
+        return SQUAT_E_ALIGN;
+
+    RopeParams p;
+    p.codes = codes;
+    p.scale = scale;
+    p.zero = zero;
+    p.q = static_cast<const unsigned char*>(q);
+    p.inv_freq = inv_freq;
+    p.pos0 = pos0;
+    p.q_dt = static_cast<int>(q_dt);
+    p.qsb = q_stride_batch;
+    p.qsh = q_stride_head;
+    p.scores = scores;
+    p.ssb = s_stride_batch;
+    p.ssh = s_stride_head;
+    p.n_tokens = n_tokens;
+    p.store_stride = store_tokens;
+    p.n_kv_heads = n_kv_heads;
+    p.qpk = q_per_kv;
+    p.out_scale = out_scale;
+
+    // workgroups along the sequence: about kRopeWaves * kRopeMaxUnitsPerWave / 2 tiles each, spread evenly
+    const int64_t n_tiles = n_tokens / group;
+    const int64_t slab = static_cast<int64_t>(kRopeWaves) * (kRopeMaxUnitsPerWave / 2);
+    int64_t gx = (n_tiles + slab / 2) / slab;
+    if (gx < 1) gx = 1;
+    int64_t tpw = (n_tiles + kRopeWaves * gx - 1) / (kRopeWaves * gx);
+    if (tpw < kRopeMinUnitsPerWave / 2) tpw = kRopeMinUnitsPerWave / 2;
+    p.units_per_wave = static_cast<int>(tpw);
+    gx = (n_tiles + kRopeWaves * tpw - 1) / (kRopeWaves * tpw);
+    const int64_t bh = n_batch * n_kv_heads;
+    int64_t gy = bh, gz = 1;
+    if (gy > 65535) {
+        gy = 0;
+        for (int64_t cand = 65535; cand >= 1; --cand)
+            if (bh % cand == 0) { gy = cand; break; }
+        gz = bh / gy;
+    }
+    if (gx > 0x7FFFFFFF || gz > 65535) return SQUAT_E_BADSHAPE;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(gz));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bits == 2 ? launch_pc_dt<2>(p, grid, s) : launch_pc_dt<4>(p, grid, s);
+}
+
+extern "C" int squat_key_scores_rope_per_channel(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
+                                                 int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits,
+                                                 int group, const float* inv_freq, int64_t pos0, const void* q,
+                                                 squat_dtype q_dt, int q_per_kv, int64_t q_stride_batch,
+                                                 int64_t q_stride_head, float out_scale, float* scores,
+                                                 int64_t s_stride_batch, int64_t s_stride_head, squat_stream stream) {
+    return squat::key_scores_pc_rope_from(codes, scale, zero, n_batch, n_kv_heads, n_tokens, n_tokens, d, bits, group,
+                                          inv_freq, pos0, q, q_dt, q_per_kv, q_stride_batch, q_stride_head, out_scale,
+                                          scores, s_stride_batch, s_stride_head, stream);
 }

@@ -21,6 +21,7 @@ SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
            "squat_quantize_keys", "squat_dequantize_keys",
            "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel", "squat_key_scores_rope",
+           "squat_key_scores_rope_per_channel",
            "squat_cache_arena_bytes", "squat_cache_create", "squat_cache_destroy", "squat_cache_reset",
            "squat_cache_state", "squat_cache_get_buffers", "squat_cache_prefill", "squat_cache_append",
            "squat_cache_key_scores", "squat_cache_key_scores_rope")
@@ -105,6 +106,9 @@ def lib() -> ctypes.CDLL:
     L.squat_cache_append.argtypes = [vp, vp, vp, i64, i64, vp]
     L.squat_key_scores_rope.restype = i32
     L.squat_key_scores_rope.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i64, vp, i32, i32, i64, i64, f32, vp,
+                                        i64, i64, vp]
+    L.squat_key_scores_rope_per_channel.restype = i32
+    L.squat_key_scores_rope_per_channel.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i64, vp, i32, i32, i64, i64, f32, vp,
                                         i64, i64, vp]
     L.squat_key_scores_per_channel.restype = i32
     L.squat_key_scores_per_channel.argtypes = list(L.squat_key_scores.argtypes)
@@ -342,6 +346,36 @@ def key_scores_rope(q: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, z
                                      float(out_scale), _ptr(out), out.stride(0), out.stride(1), _stream(stream))
     if rc:
         raise SquatError(rc, "squat_key_scores_rope")
+    return out
+
+
+def key_scores_rope_per_channel(q: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor,
+                                bits: int, q_per_kv: int, inv_freq: torch.Tensor, pos0: int = 0,
+                                out_scale: float = 1.0, out=None, stream=None) -> torch.Tensor:
+    """squat_key_scores_rope_per_channel: logits against keys stored before the rotary embedding in the
+    per-channel layout (codes [B, H, n/32, d, bits] int32, scale/zero [B, H, n/32, d] float16).  inv_freq:
+    float32 [64] on the device; pos0: position of token 0."""
+    b, h, tiles, d, nw = codes.shape
+    n = tiles * 32
+    if nw != bits or scale.shape != (b, h, tiles, d) or zero.shape != scale.shape:
+        raise ValueError("codes [B,H,n/32,d,bits], scale/zero [B,H,n/32,d] expected")
+    if inv_freq.dtype != torch.float32 or inv_freq.numel() != 64 or not inv_freq.is_contiguous():
+        raise ValueError("inv_freq must be 64 dense float32 values")
+    _need_cuda(q, codes, inv_freq)
+    if q.dim() != 3 or q.shape[0] != b or q.shape[1] != h * q_per_kv or q.shape[2] != d or q.stride(2) != 1:
+        raise ValueError("q must be [B, n_kv_heads*q_per_kv, d] with unit channel stride")
+    if not (codes.is_contiguous() and scale.is_contiguous() and zero.is_contiguous()):
+        raise ValueError("codes/scale/zero must be dense")
+    if out is None:
+        out = torch.empty((b, h * q_per_kv, n), dtype=torch.float32, device=codes.device)
+    if out.dtype != torch.float32 or out.stride(2) != 1 or out.shape[0] != b or out.shape[1] != h * q_per_kv:
+        raise ValueError("out must be float32 [B, n_q_heads, >= n] with unit token stride")
+    rc = lib().squat_key_scores_rope_per_channel(_ptr(codes), _ptr(scale), _ptr(zero), b, h, n, d, bits, 32,
+                                                 _ptr(inv_freq), int(pos0), _ptr(q), _DT[q.dtype], q_per_kv,
+                                                 q.stride(0), q.stride(1), float(out_scale), _ptr(out),
+                                                 out.stride(0), out.stride(1), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_key_scores_rope_per_channel")
     return out
 
 

@@ -188,6 +188,24 @@ def test_key_scores_argument_validation_happens_before_any_launch():
     assert kr(ssh=32) == -2
     assert kr(codes=odd) == -4
     assert kr(n=0) == 0
+    krp = lambda **kw: L.squat_key_scores_rope_per_channel(  # noqa: E731
+        kw.get("codes", fake), kw.get("scale", fake), fake, 1, 2, kw.get("n", 64), kw.get("d", 128),
+        kw.get("bits", 2), kw.get("G", 32), kw.get("freq", fake), kw.get("pos0", 0), kw.get("q", fake),
+        kw.get("dt", 2), kw.get("qpk", 4), 1024, kw.get("qsh", 128), kw.get("os", 1.0), kw.get("out", fake), 8 * 64,
+        kw.get("ssh", 64), None)
+    assert krp(d=64) == -2
+    assert krp(bits=3) == -2
+    assert krp(G=64) == -2
+    assert krp(n=48) == -2
+    assert krp(qpk=9) == -2
+    assert krp(pos0=1 << 40) == -2
+    assert krp(dt=4) == -3
+    assert krp(os=float("nan")) == -7
+    assert krp(freq=None) == -1
+    assert krp(ssh=32) == -2
+    assert krp(codes=odd) == -4
+    assert krp(scale=odd) == -4
+    assert krp(n=0) == 0
 
 
 def test_cache_configuration_and_creation_are_validated_on_the_host():
@@ -237,7 +255,7 @@ def test_cache_configuration_and_creation_are_validated_on_the_host():
     assert rope() == 0                                                                 # empty cache: nothing launched
     hp = ctypes.c_void_p()
     assert L.squat_cache_create(ctypes.byref(pc), ctypes.c_void_p(0x100000), need, None, ctypes.byref(hp)) == 0
-    assert rope(c=hp) == -2                                                            # per-channel key store
+    assert rope(c=hp) == 0 and rope(c=hp, f=None) == -1                                # per-channel key store
     L.squat_cache_destroy(hp)
     assert L.squat_cache_reset(h) == 0
     L.squat_cache_destroy(h)

@@ -82,29 +82,29 @@ def _run(B, H, qpk, bits, G, g, R, n_prompt, n_decode, dtype, values, seed, per_
                             qmax = np.abs(qval[b, h * qpk:(h + 1) * qpk]).max()
                             floor = 0.25 * 128 * (2 ** bits - 1) * 2.0 ** -24 * qmax * np.repeat(sc[b, h].astype(np.float64).max(axis=1), 32)
                         assert np.all(np.abs(g64[b, hq, :nq] - want) <= 4e-5 * bound + floor + 1e-30)
-            if not per_channel:
-                # the same cache read as a store of pre-RoPE keys: token t rotated to position pos0 + t
-                pos0 = 1000003 if t == n_all - 1 else 0
-                inv32 = (10000.0 ** (-np.arange(64) / 64.0)).astype(np.float32)
-                gr = cache.key_scores_rope(qt, torch.from_numpy(inv32).cuda(), pos0, 0.25)
-                torch.cuda.synchronize()
-                r64 = gr.cpu().numpy().astype(np.float64)
-                inv64 = inv32.astype(np.float64)
-                for b in range(B):
-                    for hq in range(H * qpk):
-                        h = hq // qpk
-                        aq = np.abs(qval[b, hq])
-                        if nr:
-                            kres = kval[b, h, t + 1 - nr:t + 1]
-                            want_res = 0.25 * qval[b, hq] @ O.rope_rotate(kres, pos0 + nq + np.arange(nr), inv64).T
-                            mag = np.abs(kres) + np.abs(np.concatenate([kres[:, 64:], kres[:, :64]], axis=1))
-                            assert np.all(np.abs(r64[b, hq, nq:] - want_res) <= 2e-5 * 0.25 * (aq @ mag.T) + 1e-30)
-                        if nq:
-                            want = O.key_scores_rope(qval[b, hq][None], codes[b, h], sc[b, h], ze[b, h], KG, inv64, pos0, 0.25)[0]
-                            krot = np.abs(O.rope_rotate(O.dequantize_keys(codes[b, h], sc[b, h], ze[b, h], KG),
-                                                        pos0 + np.arange(nq), inv64))
-                            # the rotated key is rounded to fp16 before the matrix product (2^-11 per channel)
-                            assert np.all(np.abs(r64[b, hq, :nq] - want) <= 6e-4 * 0.25 * (krot @ aq) + 1e-30)
+            # the same cache read as a store of pre-RoPE keys: token t rotated to position pos0 + t
+            pos0 = 1000003 if t == n_all - 1 else 0
+            inv32 = (10000.0 ** (-np.arange(64) / 64.0)).astype(np.float32)
+            gr = cache.key_scores_rope(qt, torch.from_numpy(inv32).cuda(), pos0, 0.25)
+            torch.cuda.synchronize()
+            r64 = gr.cpu().numpy().astype(np.float64)
+            inv64 = inv32.astype(np.float64)
+            for b in range(B):
+                for hq in range(H * qpk):
+                    h = hq // qpk
+                    aq = np.abs(qval[b, hq])
+                    if nr:
+                        kres = kval[b, h, t + 1 - nr:t + 1]
+                        want_res = 0.25 * qval[b, hq] @ O.rope_rotate(kres, pos0 + nq + np.arange(nr), inv64).T
+                        mag = np.abs(kres) + np.abs(np.concatenate([kres[:, 64:], kres[:, :64]], axis=1))
+                        assert np.all(np.abs(r64[b, hq, nq:] - want_res) <= 2e-5 * 0.25 * (aq @ mag.T) + 1e-30)
+                    if nq:
+                        want = O.key_scores_rope(qval[b, hq][None], codes[b, h], sc[b, h], ze[b, h], KG, inv64, pos0, 0.25,
+                                                 axis=axis)[0]
+                        krot = np.abs(O.rope_rotate(O.dequantize_keys(codes[b, h], sc[b, h], ze[b, h], KG, axis=axis),
+                                                    pos0 + np.arange(nq), inv64))
+                        # the rotated key is rounded to fp16 before the matrix product (2^-11 per channel)
+                        assert np.all(np.abs(r64[b, hq, :nq] - want) <= 6e-4 * 0.25 * (krot @ aq) + 1e-30)
     torch.cuda.synchronize()
     cnt = cache.counts()
     st = cache.stores()

@@ -1,4 +1,4 @@
-"""GPU parity of squat_key_scores_rope (logits against keys stored BEFORE the rotary embedding: the
+"""GPU parity of squat_key_scores_rope and squat_key_scores_rope_per_channel (logits against keys stored BEFORE the rotary embedding: the
 key is dequantized, rotated to its position, and only then contracted with the query) against the
 float64 oracle.  The rotated key reaches the matrix cores rounded to fp16 (relative 2^-11 per channel),
 the queries as exact fp16 high/low pairs, the angles are good to ~1e-5 rad: worst case 2^-11 * sum_c
@@ -117,3 +117,89 @@ def test_rope_scores_query_heads_strides_and_tiny_inputs():
         torch.cuda.synchronize()
         _check(qval, codes, scale, zero, 64, qpk, INV_FREQ, 5, 0.3, big[..., :n])
         assert torch.all(big[..., n:] == -7.0)
+
+
+# ---------------------------------------------------------------- per-channel store
+
+def _store_pc(seed, B, H, n, bits):
+    gen = synth.rng(seed)
+    x = synth.keys(seed + 1, H, n, batch=B)
+    codes = np.empty((B, H, n, 128), dtype=np.uint8)
+    scale = np.empty((B, H, n // 32, 128), dtype=np.float16)
+    zero = np.empty_like(scale)
+    for b in range(B):
+        for h in range(H):
+            out = O.quantize_keys(x[b, h].astype(np.float64), None, bits, 32, 128, axis="channel")
+            codes[b, h], scale[b, h], zero[b, h] = out["codes"], out["scale"], out["zero"]
+    return gen, codes, scale, zero
+
+
+def _dev_pc(codes, scale, zero, bits):
+    words = O.pack_codes_tokens(codes, bits)
+    return (torch.from_numpy(words.view(np.int32)).cuda(), torch.from_numpy(scale).cuda(), torch.from_numpy(zero).cuda())
+
+
+def _check_pc(qval, codes, scale, zero, qpk, inv_freq, pos0, out_scale, got):
+    B, Hq = qval.shape[:2]
+    got = got.cpu().numpy().astype(np.float64)
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // qpk
+            want = O.key_scores_rope(qval[b, hq][None], codes[b, h], scale[b, h], zero[b, h], 32, inv_freq, pos0,
+                                     out_scale, axis="channel")[0]
+            khat = O.dequantize_keys(codes[b, h], scale[b, h], zero[b, h], 32, axis="channel")
+            rot = np.abs(O.rope_rotate(khat, pos0 + np.arange(khat.shape[0]), inv_freq))
+            bound = abs(out_scale) * (np.abs(qval[b, hq])[None] * rot).sum(axis=1)
+            err = np.abs(got[b, hq] - want)
+            assert np.all(err <= 6e-4 * bound + 1e-30), (b, hq, float((err / (bound + 1e-30)).max()))
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("qdt", [synth.BF16, synth.F16, synth.F32])
+def test_rope_scores_per_channel_match_definition(bits, qdt):
+    B, H, n, qpk = 2, 3, 32 * 101, 4      # 101 token groups: two workgroups, 13 groups per wavefront, the last 10
+    gen, codes, scale, zero = _store_pc(5500 + bits, B, H, n, bits)
+    q32 = (gen.standard_normal((B, H * qpk, 128)) * 3).astype(np.float32)
+    qraw, qval = synth.store(q32, qdt)
+    ct, st, zt = _dev_pc(codes, scale, zero, bits)
+    got = squat.key_scores_rope_per_channel(util.to_device(qraw, qdt), ct, st, zt, bits, qpk,
+                                            torch.from_numpy(INV_FREQ).cuda(), pos0=0, out_scale=128 ** -0.5)
+    torch.cuda.synchronize()
+    assert got.shape == (B, H * qpk, n)
+    _check_pc(qval, codes, scale, zero, qpk, INV_FREQ, 0, 128 ** -0.5, got)
+
+
+@pytest.mark.parametrize("pos0,bits", [(1, 2), (131000, 4), (2 ** 33 + 5, 2)])
+def test_rope_scores_per_channel_at_large_positions_and_long_ranges(pos0, bits):
+    B, H, n, qpk = 1, 2, 32 * 90, 2       # 90 groups: up to 23 per wavefront (46 steps of the recurrence)
+    gen, codes, scale, zero = _store_pc(5600 + bits, B, H, n, bits)
+    q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.BF16)
+    ct, st, zt = _dev_pc(codes, scale, zero, bits)
+    got = squat.key_scores_rope_per_channel(util.to_device(qraw, synth.BF16), ct, st, zt, bits, qpk,
+                                            torch.from_numpy(INV_FREQ).cuda(), pos0=pos0)
+    torch.cuda.synchronize()
+    _check_pc(qval, codes, scale, zero, qpk, INV_FREQ, pos0, 1.0, got)
+
+
+def test_rope_scores_per_channel_reduce_to_plain_scores_heads_and_strides():
+    for qpk, n in ((1, 32), (3, 64), (8, 160)):
+        B, H = 2, 2
+        gen, codes, scale, zero = _store_pc(5700 + n, B, H, n, 4)
+        q32 = gen.standard_normal((B, H * qpk, 128)).astype(np.float32)
+        qraw, qval = synth.store(q32, synth.F16)
+        ct, st, zt = _dev_pc(codes, scale, zero, 4)
+        qt = util.to_device(qraw, synth.F16)
+        big = torch.full((B, H * qpk, n + 24), -7.0, dtype=torch.float32, device="cuda")
+        squat.key_scores_rope_per_channel(qt, ct, st, zt, 4, qpk, torch.from_numpy(INV_FREQ).cuda(), pos0=5,
+                                          out_scale=0.3, out=big)
+        torch.cuda.synchronize()
+        _check_pc(qval, codes, scale, zero, qpk, INV_FREQ, 5, 0.3, big[..., :n])
+        assert torch.all(big[..., n:] == -7.0)
+        # zero frequencies: the unrotated per-channel logits
+        plain = squat.key_scores_per_channel(qt, ct, st, zt, 4, qpk).cpu().numpy().astype(np.float64)
+        flat = squat.key_scores_rope_per_channel(qt, ct, st, zt, 4, qpk, torch.zeros(64, device="cuda"), pos0=77)
+        assert np.abs(flat.cpu().numpy() - plain).max() <= 6e-4 * np.abs(plain).max() + 1e-6
+    empty = squat.key_scores_rope_per_channel(qt, ct[:, :, :0], st[:, :, :0], zt[:, :, :0], 4, qpk,
+                                              torch.from_numpy(INV_FREQ).cuda())
+    assert empty.shape == (B, H * qpk, 0)

@@ -380,6 +380,22 @@ def test_rope_logits_are_rotations_applied_after_dequantization():
     for t in range(n):
         want = 0.5 * q @ O.rope_rotate(back[t:t + 1], np.array([3 + t]), inv_freq)[0]
         assert np.allclose(got[:, t], want, rtol=1e-12, atol=1e-12)
+    # per-channel statistics (one scale / zero-point per channel and 32 tokens): element loops
+    cc = gen.integers(0, 16, size=(64, d)).astype(np.uint8)
+    sc = gen.uniform(0.1, 2.0, size=(2, d)).astype(np.float16)
+    zc = gen.standard_normal((2, d)).astype(np.float16)
+    assert np.array_equal(O.key_scores_rope(q, cc, sc, zc, 32, np.zeros(64), 9, 0.5, axis="channel"),
+                          O.key_scores(q, cc, sc, zc, 32, 0.5, axis="channel"))
+    got = O.key_scores_rope(q, cc, sc, zc, 32, inv_freq, pos0=11, out_scale=2.0, axis="channel")
+    for t in (0, 31, 32, 63):
+        key = [float(cc[t, c]) * float(sc[t // 32, c]) + float(zc[t // 32, c]) for c in range(d)]
+        for i in range(2):
+            acc = 0.0
+            for c in range(64):
+                ang = (11 + t) * inv_freq[c]
+                acc += q[i, c] * (key[c] * np.cos(ang) - key[c + 64] * np.sin(ang))
+                acc += q[i, c + 64] * (key[c + 64] * np.cos(ang) + key[c] * np.sin(ang))
+            assert abs(got[i, t] - 2.0 * acc) <= 1e-11 * max(1.0, abs(acc))
 
 
 def test_cache_rope_logits_are_the_plain_ones_of_rotated_keys():
@@ -407,6 +423,22 @@ def test_cache_rope_logits_are_the_plain_ones_of_rotated_keys():
         assert np.allclose(got[:, t], 0.25 * q @ rot, rtol=1e-12, atol=1e-12)
     qm = O.rope_rotate(q, np.full(3, 40), inv_freq)
     assert np.allclose(c.scores_rope(qm, inv_freq, pos0=40), c.scores_rope(q, inv_freq, pos0=0), rtol=1e-9, atol=1e-9)
+    # keys grouped per channel: the same statement with the per-channel dequantization
+    K = gen.standard_normal((75, d))
+    c = O.CacheOracle(None, 4, G, 128, 32, key_axis="channel")
+    c.prefill(K[:40])                                  # 32 quantized, 8 buffered
+    for t in range(40, 75):
+        c.append(K[t])                                 # ends with 64 quantized, 11 buffered
+    assert len(c.k_codes) == 64 and len(c.k_scale) == 2 and len(c.k_full) == 11
+    assert np.array_equal(c.scores_rope(q, np.zeros(64), 7, 0.25), c.scores(q, 0.25))
+    got = c.scores_rope(q, inv_freq, pos0=5, out_scale=0.25)
+    deq = O.dequantize_keys(np.stack(c.k_codes), np.stack(c.k_scale), np.stack(c.k_zero), 32, axis="channel")
+    cached = np.concatenate([deq, np.stack(c.k_full)])
+    for t in range(75):
+        ang = (5 + t) * inv_freq
+        a, b = cached[t, :64], cached[t, 64:]
+        rot = np.concatenate([a * np.cos(ang) - b * np.sin(ang), b * np.cos(ang) + a * np.sin(ang)])
+        assert np.allclose(got[:, t], 0.25 * q @ rot, rtol=1e-12, atol=1e-12)
 
 
 def test_cache_bookkeeping_follows_algorithm_1():
