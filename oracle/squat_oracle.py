@@ -23,9 +23,11 @@ Parity status of each function:
                                 soft and hard invariants), both grouping axes
   CacheOracle                   pinned (counts against l mod R by hand, stores
                                 against one-shot quantization of the prefix; scores_rope:
-                                zero frequencies = scores, hand-rotated cached keys)
+                                zero frequencies = scores, hand-rotated cached keys,
+                                both key groupings)
   key_scores_rope, rope_rotate  pinned (norm preservation, relative-position identity, explicit
-                                2x2 rotations, zero angle = key_scores)
+                                2x2 rotations, zero angle = key_scores; per-channel grouping:
+                                element loops)
   key_scores                    pinned (element loops, one-hot queries, closed
                                 form for constant codes)
   dequantize_keys, pack/unpack  pinned (definition of deq; pack o unpack = id,
