@@ -181,3 +181,44 @@ def test_fullsize_logits_from_both_stores_on_sampled_tokens(run):
     chan2 = squat.key_scores_per_channel(qdec, pc, ps, pz, wl.bits, qpk, out_scale)
     torch.cuda.synchronize()
     assert torch.equal(tok, tok2) and torch.equal(chan, chan2)
+
+
+def test_fullsize_pre_rope_logits_from_both_stores_on_sampled_tokens(run):
+    """squat_key_scores_rope and squat_key_scores_rope_per_channel at the same launch shape: the stores read
+    as pre-RoPE keys, token t rotated to position pos0 + t; sampled logits against the oracle applied to the
+    GPU's own stores (the rotated key is rounded to fp16: bound 6e-4 sum |q| |k_rot|), every logit finite,
+    second run bit-identical."""
+    wl = run["wl"]
+    n, d, qpk = wl.n_tokens, wl.d, wl.q_per_kv
+    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()
+    out_scale, pos0 = d ** -0.5, 98304
+    inv32 = (10000.0 ** (-np.arange(64) / 64.0)).astype(np.float32)
+    inv = torch.from_numpy(inv32).cuda()
+    inv64 = inv32.astype(np.float64)
+    tok = squat.key_scores_rope(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, inv, pos0, out_scale)
+    pc, ps, pz = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
+    chan = squat.key_scores_rope_per_channel(qdec, pc, ps, pz, wl.bits, qpk, inv, pos0, out_scale)
+    torch.cuda.synchronize()
+    assert tok.shape == chan.shape == (1, wl.heads * qpk, n)
+    assert torch.isfinite(tok).all() and torch.isfinite(chan).all()
+    gen = np.random.default_rng(29)
+    for hq in np.concatenate([[0, wl.heads * qpk - 1], gen.integers(0, wl.heads * qpk, size=10)]):
+        h = int(hq) // qpk
+        q = _bf16_to_f64(qdec[0, hq])
+        ts = np.unique(np.concatenate([[0, 15, 16, n - 1], gen.integers(0, n, size=40)]))
+        codes = O.unpack_codes(run["codes"][0, h, ts].cpu().numpy().view(np.uint32), wl.bits)
+        sc, ze = run["scale"][0, h, ts].cpu().numpy(), run["zero"][0, h, ts].cpu().numpy()
+        rot = O.rope_rotate(O.dequantize_keys(codes, sc, ze, wl.group), pos0 + ts, inv64)
+        got = tok[0, hq, ts].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - out_scale * rot @ q) <= 6e-4 * out_scale * (np.abs(rot) @ np.abs(q)))
+        for gi in np.unique(np.concatenate([[0, n // 32 - 1], gen.integers(0, n // 32, size=6)])):
+            codes = O.unpack_codes_tokens(pc[0, h, gi:gi + 1].cpu().numpy().view(np.uint32), wl.bits)
+            sc, ze = ps[0, h, gi:gi + 1].cpu().numpy(), pz[0, h, gi:gi + 1].cpu().numpy()
+            want = O.key_scores_rope(q[None], codes, sc, ze, 32, inv64, pos0 + 32 * int(gi), out_scale, axis="channel")[0]
+            rot = O.rope_rotate(O.dequantize_keys(codes, sc, ze, 32, axis="channel"), pos0 + 32 * int(gi) + np.arange(32), inv64)
+            got = chan[0, hq, gi * 32:(gi + 1) * 32].cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(got - want) <= 6e-4 * out_scale * (np.abs(rot) @ np.abs(q)))
+    tok2 = squat.key_scores_rope(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, inv, pos0, out_scale)
+    chan2 = squat.key_scores_rope_per_channel(qdec, pc, ps, pz, wl.bits, qpk, inv, pos0, out_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(tok, tok2) and torch.equal(chan, chan2)
