@@ -246,6 +246,7 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
+    float held0 = 0.0f, held1 = 0.0f;
     auto compute = [&](int u, const Raw& raw) {
         const int tok = u * kUnitTokens + col;
         Words wd;
@@ -297,9 +298,23 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
         const float s0 = fin * (fmaf(DESCALE, r[0] + r[1], zacc[0] + zacc[1]));
         const float s1 = fin * (fmaf(DESCALE, r[2] + r[3], zacc[2] + zacc[3]));
-        if (tok < n_tok) {
-            if (st0) __builtin_nontemporal_store(s0, out0 + tok);
-            if (st1) __builtin_nontemporal_store(s1, out0 + p.ssh + tok);
+        // Two consecutive units fill one 128-byte line of a score row: the first unit of an (even, odd) pair
+        // keeps its results until the second one is done, and both halves are stored back to back (stored
+        // a unit apart, the halves reach memory as two partial line writes).
+        if ((u & 1) == 0 && u + 1 < u1) {
+            held0 = s0;
+            held1 = s1;
+        } else {
+            const bool pair = (u & 1) && u > u0;          // the held unit is complete: u exists
+            const bool mine = tok < n_tok;
+            if (st0) {                                    // the two halves of a line in consecutive instructions
+                if (pair) __builtin_nontemporal_store(held0, out0 + tok - kUnitTokens);
+                if (mine) __builtin_nontemporal_store(s0, out0 + tok);
+            }
+            if (st1) {
+                if (pair) __builtin_nontemporal_store(held1, out0 + p.ssh + tok - kUnitTokens);
+                if (mine) __builtin_nontemporal_store(s1, out0 + p.ssh + tok);
+            }
         }
     };
 
@@ -390,6 +405,7 @@ int squat::key_scores_from(const uint32_t* codes, const uint16_t* scale, const u
     if (gx < 1) gx = 1;
     int64_t upw = (n_units + kScoreWaves * gx - 1) / (kScoreWaves * gx);
     if (upw < kMinUnitsPerWave) upw = kMinUnitsPerWave;
+    upw += upw & 1;                                       // even: every wavefront's range starts on a 32-token line
     p.units_per_wave = static_cast<int>(upw);
     gx = (n_units + kScoreWaves * upw - 1) / (kScoreWaves * upw);
     const int64_t bh = n_batch * n_kv_heads;

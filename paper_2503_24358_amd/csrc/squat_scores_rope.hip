@@ -192,6 +192,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
         }
     };
 
+    float held0 = 0.0f, held1 = 0.0f;
     auto compute = [&](int u, const Raw& raw) {
         // registers -> LDS tile -> the words of this lane's K block, the metadata of its token
         if (is_c) *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) = raw.c;
@@ -247,10 +248,24 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
                                                          acc, 0, 0, 0);
         }
         // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
+        // two consecutive units fill one 128-byte line of a score row: the first of an (even, odd) pair is
+        // kept and stored together with the second (a unit apart they reach memory as partial line writes)
         const int tok = u * kRopeUnit + col;
-        if (tok < n_tok) {
-            if (st0) __builtin_nontemporal_store(fin * (acc[0] + acc[1]), out0 + tok);
-            if (st1) __builtin_nontemporal_store(fin * (acc[2] + acc[3]), out0 + p.ssh + tok);
+        const float s0 = fin * (acc[0] + acc[1]), s1 = fin * (acc[2] + acc[3]);
+        if ((u & 1) == 0 && u + 1 < u1) {
+            held0 = s0;
+            held1 = s1;
+        } else {
+            const bool pair = (u & 1) && u > u0;          // the held unit is complete: u exists
+            const bool mine = tok < n_tok;
+            if (st0) {                                    // the two halves of a line in consecutive instructions
+                if (pair) __builtin_nontemporal_store(held0, out0 + tok - kRopeUnit);
+                if (mine) __builtin_nontemporal_store(s0, out0 + tok);
+            }
+            if (st1) {
+                if (pair) __builtin_nontemporal_store(held1, out0 + p.ssh + tok - kRopeUnit);
+                if (mine) __builtin_nontemporal_store(s1, out0 + p.ssh + tok);
+            }
         }
     };
 
@@ -278,6 +293,7 @@ template <int BITS, int QDT>
 __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(const RopeParams p) {
     constexpr int TW = kD * BITS;                         // packed words per tile
     constexpr int NCL = TW / 256;                         // 16-byte code loads per lane and tile
+    constexpr int DEPTH = BITS == 4 ? 2 : kRopeDepth;     // tiles in flight (4-bit tiles take twice the registers)
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -394,6 +410,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
             sraw[g] = *reinterpret_cast<const u32x4*>(lds + TW * 4 + (32 * g + 8 * kb) * 2);
             zraw[g] = *reinterpret_cast<const u32x4*>(lds + TW * 4 + 256 + (32 * g + 8 * kb) * 2);
         }
+        float res[2][2];
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
             // token 16 hf + col of the tile: word and bit of its code inside a channel's words
@@ -437,23 +454,33 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]),
                                                              __builtin_bit_cast(half8, bop), acc, 0, 0, 0);
             }
-            const int64_t tok = static_cast<int64_t>(t) * 32 + 16 * hf + col;
-            if (st0) __builtin_nontemporal_store(fin * (acc[0] + acc[1]), out0 + tok);
-            if (st1) __builtin_nontemporal_store(fin * (acc[2] + acc[3]), out0 + p.ssh + tok);
+            res[hf][0] = fin * (acc[0] + acc[1]);
+            res[hf][1] = fin * (acc[2] + acc[3]);
+            __builtin_amdgcn_sched_barrier(0);            // keep the halves apart: interleaved they need > 256 registers
+        }
+        // both halves of the group's 128-byte line of a score row, back to back
+        const int64_t tok = static_cast<int64_t>(t) * 32 + col;
+        if (st0) {
+            __builtin_nontemporal_store(res[0][0], out0 + tok);
+            __builtin_nontemporal_store(res[1][0], out0 + tok + 16);
+        }
+        if (st1) {
+            __builtin_nontemporal_store(res[0][1], out0 + p.ssh + tok);
+            __builtin_nontemporal_store(res[1][1], out0 + p.ssh + tok + 16);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
-    Raw ring[kRopeDepth];
+    Raw ring[DEPTH];
 #pragma unroll
-    for (int i = 0; i < kRopeDepth; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
-    for (int t = t0; t < t1; t += kRopeDepth) {
+    for (int i = 0; i < DEPTH; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
+    for (int t = t0; t < t1; t += DEPTH) {
 #pragma unroll
-        for (int i = 0; i < kRopeDepth; ++i) {
+        for (int i = 0; i < DEPTH; ++i) {
             const Raw cur = ring[i];
-            fetch(min(t + i + kRopeDepth, t1 - 1), ring[i]);
+            fetch(min(t + i + DEPTH, t1 - 1), ring[i]);
             if (t + i < t1) compute(t + i, cur);
         }
     }
@@ -545,6 +572,7 @@ int squat::key_scores_rope_from(const uint32_t* codes, const uint16_t* scale, co
     if (gx < 1) gx = 1;
     int64_t upw = (n_units + kRopeWaves * gx - 1) / (kRopeWaves * gx);
     if (upw < kRopeMinUnitsPerWave) upw = kRopeMinUnitsPerWave;
+    upw += upw & 1;                                       // even: every wavefront's range starts on a 32-token line
     p.units_per_wave = static_cast<int>(upw);
     gx = (n_units + kRopeWaves * upw - 1) / (kRopeWaves * upw);
     const int64_t bh = n_batch * n_kv_heads;
