@@ -263,12 +263,40 @@ def main():
                                                               out=logits), reps=10)
         nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // 32))
         sb = n_keys * (d * bits // 8 + 4 * (d // 32) + 4 * wl.q_per_kv)
+        # the whole path with this grouping in place of the per-token one (subspace and update as in `step`): the
+        # kernel's time between the other stages, not back to back with itself
+        in_step = None
+        if use_update and g == wl.g and not only:
+            def step_pc(ev=None):
+                squat.build_subspace(wl.q, wl.q_per_kv, wl.r, qhat=qhat, eig=eig, ws=ws_sub)
+                squat.prepare(qhat, wl.lam, wl.g, update=update, ws=ws_prep)
+                if ev: ev[0].record()
+                squat.quantize_keys_per_channel(wl.k, update, bits, 32, g, codes=c, scale=sc, zero=ze)
+                if ev: ev[1].record()
+                squat.dequantize_keys_per_channel(c, sc, ze, bits, 32, out=back)
+                if ev: ev[2].record()
+            for _ in range(max(1, args.warmup)):
+                step_pc()
+            torch.cuda.synchronize()
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                step_pc(evs[i])
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            tq_in = sorted(e[0].elapsed_time(e[1]) for e in evs)
+            td_in = sorted(e[1].elapsed_time(e[2]) for e in evs)
+            in_step = {"ms_per_step": ms, "keys_per_s": n_keys / (ms * 1e-3),
+                       "quantize_us_mean": sum(tq_in) / len(tq_in) * 1e3, "quantize_us_median": tq_in[len(tq_in) // 2] * 1e3,
+                       "quantize_frac_of_hbm_peak": nbytes / (sum(tq_in) / len(tq_in) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "dequantize_us_mean": sum(td_in) / len(td_in) * 1e3}
         out["per_channel"].append({"bits": bits, "token_group": 32, "g": g, "update": use_update,
                                    "bytes_per_key": nbytes // n_keys,
                                    "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                    "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                    "key_scores_us": tsc * 1e3, "key_scores_bytes_per_key": sb // n_keys,
                                    "key_scores_frac_of_hbm_peak": sb / (tsc * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "whole_path": in_step,
                                    "key_scores_rope_us": tsr * 1e3,
                                    "key_scores_rope_frac_of_hbm_peak": sb / (tsr * 1e-3) / 1e9 / HBM_PEAK_GBS})
     # Decode-side consumer: attention logits of one query token per query head straight from the packed
