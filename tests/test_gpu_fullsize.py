@@ -17,6 +17,23 @@ def _bf16_to_f64(t: torch.Tensor) -> np.ndarray:
     return t.float().cpu().numpy().astype(np.float64)
 
 
+def _synthetic_stores(wl, seed):
+    """Packed stores of the benchmark's shape filled by a seeded generator (a store is an INPUT of the logits
+    calls: any words, scales and zero-points are a valid one): per-token layout and per-channel layout."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    H, n, d, bits = wl.heads, wl.n_tokens, wl.d, wl.bits
+    def words(shape):
+        return torch.randint(-2 ** 31, 2 ** 31 - 1, shape, dtype=torch.int32, device="cuda", generator=gen)
+    def meta(shape):
+        sc = (torch.rand(shape, device="cuda", generator=gen) * 1.5 + 0.05).half()
+        ze = (torch.randn(shape, device="cuda", generator=gen) * 2.0).half()
+        return sc, ze
+    tok = (words((1, H, n, d * bits // 32)),) + meta((1, H, n, d // wl.group))
+    chan = (words((1, H, n // 32, d, bits)),) + meta((1, H, n // 32, d))
+    return tok, chan
+
+
 @pytest.fixture(scope="module")
 def run():
     wl = LongContext()
@@ -143,13 +160,13 @@ def test_fullsize_per_channel_mode_on_sampled_token_groups(run):
 def test_fullsize_logits_from_both_stores_on_sampled_tokens(run):
     """squat_key_scores and squat_key_scores_per_channel as bench.py launches them (one decode query per
     query head over all 32768 quantized tokens of every head): sampled (query head, token) logits against
-    the oracle applied to the GPU's own stores; every logit finite; second run bit-identical."""
+    the oracle on the same seeded synthetic stores; every logit finite; second run bit-identical."""
     wl = run["wl"]
     n, d, qpk = wl.n_tokens, wl.d, wl.q_per_kv
     qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()
     out_scale = d ** -0.5
-    tok = squat.key_scores(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, out_scale)
-    pc, ps, pz = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
+    (tc, tsc, tze), (pc, ps, pz) = _synthetic_stores(wl, 2301)
+    tok = squat.key_scores(qdec, tc, tsc, tze, wl.bits, wl.group, qpk, out_scale)
     chan = squat.key_scores_per_channel(qdec, pc, ps, pz, wl.bits, qpk, out_scale)
     torch.cuda.synchronize()
     assert tok.shape == chan.shape == (1, wl.heads * qpk, n)
@@ -160,8 +177,8 @@ def test_fullsize_logits_from_both_stores_on_sampled_tokens(run):
         q = _bf16_to_f64(qdec[0, hq])
         # per-token store: sampled tokens, including the first and last of the sequence
         ts = np.unique(np.concatenate([[0, 15, 16, n - 1], gen.integers(0, n, size=40)]))
-        codes = O.unpack_codes(run["codes"][0, h, ts].cpu().numpy().view(np.uint32), wl.bits)
-        sc, ze = run["scale"][0, h, ts].cpu().numpy(), run["zero"][0, h, ts].cpu().numpy()
+        codes = O.unpack_codes(tc[0, h, ts].cpu().numpy().view(np.uint32), wl.bits)
+        sc, ze = tsc[0, h, ts].cpu().numpy(), tze[0, h, ts].cpu().numpy()
         want = O.key_scores(q[None], codes, sc, ze, wl.group, out_scale)[0]
         bound = out_scale * (np.abs(q)[None] * np.abs(O.dequantize_keys(codes, sc, ze, wl.group))).sum(axis=1)
         got = tok[0, hq, ts].cpu().numpy().astype(np.float64)
@@ -177,7 +194,7 @@ def test_fullsize_logits_from_both_stores_on_sampled_tokens(run):
             floor = out_scale * 128 * (2 ** wl.bits - 1) * 2.0 ** -24 * qmax * float(sc.astype(np.float64).max())
             got = chan[0, hq, gi * 32:(gi + 1) * 32].cpu().numpy().astype(np.float64)
             assert np.all(np.abs(got - want) <= 4e-5 * bound + floor)
-    tok2 = squat.key_scores(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, out_scale)
+    tok2 = squat.key_scores(qdec, tc, tsc, tze, wl.bits, wl.group, qpk, out_scale)
     chan2 = squat.key_scores_per_channel(qdec, pc, ps, pz, wl.bits, qpk, out_scale)
     torch.cuda.synchronize()
     assert torch.equal(tok, tok2) and torch.equal(chan, chan2)
@@ -185,8 +202,8 @@ def test_fullsize_logits_from_both_stores_on_sampled_tokens(run):
 
 def test_fullsize_pre_rope_logits_from_both_stores_on_sampled_tokens(run):
     """squat_key_scores_rope and squat_key_scores_rope_per_channel at the same launch shape: the stores read
-    as pre-RoPE keys, token t rotated to position pos0 + t; sampled logits against the oracle applied to the
-    GPU's own stores (the rotated key is rounded to fp16: bound 6e-4 sum |q| |k_rot|), every logit finite,
+    as pre-RoPE keys, token t rotated to position pos0 + t; sampled logits against the oracle on the same seeded
+    synthetic stores (the rotated key is rounded to fp16: bound 6e-4 sum |q| |k_rot|), every logit finite,
     second run bit-identical."""
     wl = run["wl"]
     n, d, qpk = wl.n_tokens, wl.d, wl.q_per_kv
@@ -195,8 +212,8 @@ def test_fullsize_pre_rope_logits_from_both_stores_on_sampled_tokens(run):
     inv32 = (10000.0 ** (-np.arange(64) / 64.0)).astype(np.float32)
     inv = torch.from_numpy(inv32).cuda()
     inv64 = inv32.astype(np.float64)
-    tok = squat.key_scores_rope(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, inv, pos0, out_scale)
-    pc, ps, pz = squat.quantize_keys_per_channel(wl.k, run["update"], wl.bits, 32, wl.g)
+    (tc, tsc, tze), (pc, ps, pz) = _synthetic_stores(wl, 2901)
+    tok = squat.key_scores_rope(qdec, tc, tsc, tze, wl.bits, wl.group, qpk, inv, pos0, out_scale)
     chan = squat.key_scores_rope_per_channel(qdec, pc, ps, pz, wl.bits, qpk, inv, pos0, out_scale)
     torch.cuda.synchronize()
     assert tok.shape == chan.shape == (1, wl.heads * qpk, n)
@@ -206,8 +223,8 @@ def test_fullsize_pre_rope_logits_from_both_stores_on_sampled_tokens(run):
         h = int(hq) // qpk
         q = _bf16_to_f64(qdec[0, hq])
         ts = np.unique(np.concatenate([[0, 15, 16, n - 1], gen.integers(0, n, size=40)]))
-        codes = O.unpack_codes(run["codes"][0, h, ts].cpu().numpy().view(np.uint32), wl.bits)
-        sc, ze = run["scale"][0, h, ts].cpu().numpy(), run["zero"][0, h, ts].cpu().numpy()
+        codes = O.unpack_codes(tc[0, h, ts].cpu().numpy().view(np.uint32), wl.bits)
+        sc, ze = tsc[0, h, ts].cpu().numpy(), tze[0, h, ts].cpu().numpy()
         rot = O.rope_rotate(O.dequantize_keys(codes, sc, ze, wl.group), pos0 + ts, inv64)
         got = tok[0, hq, ts].cpu().numpy().astype(np.float64)
         assert np.all(np.abs(got - out_scale * rot @ q) <= 6e-4 * out_scale * (np.abs(rot) @ np.abs(q)))
@@ -218,7 +235,7 @@ def test_fullsize_pre_rope_logits_from_both_stores_on_sampled_tokens(run):
             rot = O.rope_rotate(O.dequantize_keys(codes, sc, ze, 32, axis="channel"), pos0 + 32 * int(gi) + np.arange(32), inv64)
             got = chan[0, hq, gi * 32:(gi + 1) * 32].cpu().numpy().astype(np.float64)
             assert np.all(np.abs(got - want) <= 6e-4 * out_scale * (np.abs(rot) @ np.abs(q)))
-    tok2 = squat.key_scores_rope(qdec, run["codes"], run["scale"], run["zero"], wl.bits, wl.group, qpk, inv, pos0, out_scale)
+    tok2 = squat.key_scores_rope(qdec, tc, tsc, tze, wl.bits, wl.group, qpk, inv, pos0, out_scale)
     chan2 = squat.key_scores_rope_per_channel(qdec, pc, ps, pz, wl.bits, qpk, inv, pos0, out_scale)
     torch.cuda.synchronize()
     assert torch.equal(tok, tok2) and torch.equal(chan, chan2)
