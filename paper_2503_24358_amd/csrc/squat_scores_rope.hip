@@ -21,6 +21,16 @@
 // a fraction of a turn before the fp32 sincospi), so the recurrence runs for at
 // most ~48 steps (error ~ 1e-5 of a radian, far below the fp16 rounding of the
 // rotated key, 2^-11 relative, which sets the accuracy of this call).
+//
+// squat_key_scores_rope_per_channel is the same computation over the per-channel
+// store (statistics per channel over 32 tokens, the grouping Algorithm 1 prints):
+// a wavefront takes whole token groups, the lane roles and the arithmetic after
+// the dequantize step are unchanged.
+//
+// Score stores: a 128-byte line of a score row is written by two 16-lane stores;
+// they are issued in consecutive instructions (the per-token kernel keeps the
+// even unit of a pair in registers until the odd one is done), because halves
+// stored a unit of work apart reach memory as two partial line writes.
 #include "squat_internal.h"
 
 using namespace squat;
