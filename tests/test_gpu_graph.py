@@ -34,7 +34,15 @@ def test_whole_path_and_logits_replay_from_a_graph():
     back = torch.empty((1, H, n, d), dtype=torch.bfloat16, device=dev)
     qdec = qt[:, n - 1, :].unsqueeze(0).contiguous()
     logits = torch.empty((1, hq, n), dtype=torch.float32, device=dev)
-    outs = (qhat, eig, upd, codes, scale, zero, back, logits)
+    # the per-channel grouping and the pre-RoPE logits of both stores ride along (n is a multiple of 32)
+    pcodes = torch.empty((1, H, n // 32, d, 2), dtype=torch.int32, device=dev)
+    pscale = torch.empty((1, H, n // 32, d), dtype=torch.float16, device=dev)
+    pzero = torch.empty_like(pscale)
+    inv_freq = (10000.0 ** (-torch.arange(64, dtype=torch.float64, device=dev) / 64.0)).float()
+    rope = torch.empty_like(logits)
+    plogits = torch.empty_like(logits)
+    prope = torch.empty_like(logits)
+    outs = (qhat, eig, upd, codes, scale, zero, back, logits, pcodes, pscale, pzero, rope, plogits, prope)
 
     def path():
         squat.build_subspace(qt, qpk, r, qhat=qhat, eig=eig, ws=ws)
@@ -42,6 +50,10 @@ def test_whole_path_and_logits_replay_from_a_graph():
         squat.quantize_keys(kt, upd, 2, 32, 32, codes=codes, scale=scale, zero=zero)
         squat.dequantize_keys(codes, scale, zero, 2, 32, out=back)
         squat.key_scores(qdec, codes, scale, zero, 2, 32, qpk, d ** -0.5, out=logits)
+        squat.key_scores_rope(qdec, codes, scale, zero, 2, 32, qpk, inv_freq, 7, d ** -0.5, out=rope)
+        squat.quantize_keys_per_channel(kt, upd, 2, 32, 32, codes=pcodes, scale=pscale, zero=pzero)
+        squat.key_scores_per_channel(qdec, pcodes, pscale, pzero, 2, qpk, d ** -0.5, out=plogits)
+        squat.key_scores_rope_per_channel(qdec, pcodes, pscale, pzero, 2, qpk, inv_freq, 7, d ** -0.5, out=prope)
 
     path()                                   # eager: also sets the kernels' attributes before any capture
     torch.cuda.synchronize()
