@@ -312,12 +312,12 @@ def main():
                                              d ** -0.5, out=logits), reps=10)
     out["key_scores_rope"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bound": "alu", "us": tr * 1e3,
                               "keys_per_s": n_keys / (tr * 1e-3), "frac_of_hbm_peak": sbytes / (tr * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                              "valu_instructions_per_16_keys": 270,
-                              # 270 wave64 instructions per 16 keys = 1080 lane-operations per key; peak: 256 CUs x 4 SIMDs
+                              "valu_instructions_per_16_keys": 300,
+                              # 300 wave64 instructions per 16 keys (main loop of the built kernel) = 1200 lane-operations per key; peak: 256 CUs x 4 SIMDs
                               # x 16 lanes x 2.4 GHz (packed fp32 is switched off in this build)
-                              "alu_lane_ops_per_s": n_keys / (tr * 1e-3) * 1080,
+                              "alu_lane_ops_per_s": n_keys / (tr * 1e-3) * 1200,
                               "alu_peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
-                              "alu_frac": n_keys / (tr * 1e-3) * 1080 / (256 * 4 * 16 * 2.4e9)}
+                              "alu_frac": n_keys / (tr * 1e-3) * 1200 / (256 * 4 * 16 * 2.4e9)}
     if args.variants:
         out["variants"] = []
         for bits, G, g, use_update in [(2, 32, 32, True), (2, 32, 64, True), (4, 32, 32, True), (4, 32, 64, True),

@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     constexpr float DESCALE = static_cast<float>(1 << (24 - TOP));
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // uniform: scalar loop control
     const int kb = lane >> 4;                             // K block of an operand / row block of the result
     const int col = lane & 15;                            // operand row (A) or token (B, result)
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
@@ -323,13 +323,24 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     Raw ring[kDepth];
 #pragma unroll
     for (int i = 0; i < kDepth; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
-    for (int u = u0; u < u1; u += kDepth) {
+    // whole groups of kDepth units run without a test (a skipped unit inside the loop costs a register copy
+    // per value the loop carries); the last, shorter group is handled after it
+    int u = u0;
+    for (; u + kDepth <= u1; u += kDepth) {
 #pragma unroll
         for (int i = 0; i < kDepth; ++i) {
             const Raw cur = ring[i];
             fetch(min(u + i + kDepth, u1 - 1), ring[i]);
-            if (u + i < u1) compute(u + i, cur);
+            compute(u + i, cur);
         }
+    }
+    static_assert(kDepth <= 4, "the tail picks its unit from ring[0] .. ring[2]");
+#pragma nounroll
+    for (int i = 0; u + i < u1; ++i) {                    // at most kDepth - 1 units; one copy of the code
+        Raw cur = ring[0];
+        if (i == 1) cur = ring[1];
+        if (i == 2) cur = ring[2];
+        compute(u + i, cur);
     }
 }
 

@@ -84,7 +84,7 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     constexpr int ML = 2 * NT;                            // metadata dwords a lane loads
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // uniform: scalar loop control
     const int kb = lane >> 4;                             // K block of an operand / row block of the result
     const int col = lane & 15;                            // operand row (A) or column (B, result)
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
@@ -343,13 +343,23 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     Raw ring[kPcDepth];
 #pragma unroll
     for (int i = 0; i < kPcDepth; ++i) fetch(t0 + NT * i, ring[i]);
-    for (int t = t0; t < t1; t += NT * kPcDepth) {
+    // whole groups of kPcDepth steps run without a test (a skipped step inside the loop costs a register copy
+    // per value the loop carries); the last, shorter group is handled after it
+    int t = t0;
+    for (; t + NT * (kPcDepth - 1) < t1; t += NT * kPcDepth) {
 #pragma unroll
         for (int i = 0; i < kPcDepth; ++i) {
             const Raw cur = ring[i];
             fetch(t + NT * (i + kPcDepth), ring[i]);
-            if (t + NT * i < t1) compute(t + NT * i, cur);
+            compute(t + NT * i, cur);
         }
+    }
+    static_assert(kPcDepth <= 3, "the tail picks its step from ring[0] / ring[1]");
+#pragma nounroll
+    for (int i = 0; t + NT * i < t1; ++i) {               // at most kPcDepth - 1 steps; one copy of the code
+        Raw cur = ring[0];
+        if (i == 1) cur = ring[1];
+        compute(t + NT * i, cur);
     }
 }
 

@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
     constexpr int CPG = 4 / NG;                           // 32-channel chunks per group
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // uniform: scalar loop control
     const int kb = lane >> 4;                             // K block of an operand / row block of the result
     const int col = lane & 15;                            // operand row (A) or token (B, result)
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
@@ -283,13 +283,23 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
     Raw ring[kRopeDepth];
 #pragma unroll
     for (int i = 0; i < kRopeDepth; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
-    for (int u = u0; u < u1; u += kRopeDepth) {
+    // whole groups of kRopeDepth units run without a test (a skipped unit inside the loop costs a register
+    // copy per value the loop carries: the 32 angles); the last, shorter group is handled after it
+    int u = u0;
+    for (; u + kRopeDepth <= u1; u += kRopeDepth) {
 #pragma unroll
         for (int i = 0; i < kRopeDepth; ++i) {
             const Raw cur = ring[i];
             fetch(min(u + i + kRopeDepth, u1 - 1), ring[i]);
-            if (u + i < u1) compute(u + i, cur);
+            compute(u + i, cur);
         }
+    }
+    static_assert(kRopeDepth <= 3, "the tail picks its unit from ring[0] / ring[1]");
+#pragma nounroll
+    for (int i = 0; u + i < u1; ++i) {                    // at most kRopeDepth - 1 units; one copy of the code
+        Raw cur = ring[0];
+        if (i == 1) cur = ring[1];
+        compute(u + i, cur);
     }
 }
 
@@ -306,7 +316,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
     constexpr int DEPTH = BITS == 4 ? 2 : kRopeDepth;     // tiles in flight (4-bit tiles take twice the registers)
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // uniform: scalar loop control
     const int kb = lane >> 4;
     const int col = lane & 15;
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
@@ -486,13 +496,21 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
     Raw ring[DEPTH];
 #pragma unroll
     for (int i = 0; i < DEPTH; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
-    for (int t = t0; t < t1; t += DEPTH) {
+    int t = t0;                                           // whole groups of DEPTH tiles, then the shorter last one
+    for (; t + DEPTH <= t1; t += DEPTH) {
 #pragma unroll
         for (int i = 0; i < DEPTH; ++i) {
             const Raw cur = ring[i];
             fetch(min(t + i + DEPTH, t1 - 1), ring[i]);
-            if (t + i < t1) compute(t + i, cur);
+            compute(t + i, cur);
         }
+    }
+    static_assert(DEPTH <= 3, "the tail picks its tile from ring[0] / ring[1]");
+#pragma nounroll
+    for (int i = 0; t + i < t1; ++i) {                    // at most DEPTH - 1 tiles; one copy of the code
+        Raw cur = ring[0];
+        if (i == 1) cur = ring[1];
+        compute(t + i, cur);
     }
 }
 
