@@ -267,14 +267,29 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
             held1 = s1;
         } else {
             const bool pair = (u & 1) && u > u0;          // the held unit is complete: u exists
-            const bool mine = tok < n_tok;
-            if (st0) {                                    // the two halves of a line in consecutive instructions
-                if (pair) __builtin_nontemporal_store(held0, out0 + tok - kRopeUnit);
-                if (mine) __builtin_nontemporal_store(s0, out0 + tok);
-            }
-            if (st1) {
-                if (pair) __builtin_nontemporal_store(held1, out0 + p.ssh + tok - kRopeUnit);
-                if (mine) __builtin_nontemporal_store(s1, out0 + p.ssh + tok);
+            float* const d0 = out0 + tok;
+            float* const d1 = d0 + p.ssh;
+            if (pair && (u + 1) * kRopeUnit <= n_tok) {
+                // the usual case, all tests wave-uniform but the lane's rows: four stores, the two halves
+                // of a line in consecutive instructions
+                if (st0) {
+                    __builtin_nontemporal_store(held0, d0 - kRopeUnit);
+                    __builtin_nontemporal_store(s0, d0);
+                }
+                if (st1) {
+                    __builtin_nontemporal_store(held1, d1 - kRopeUnit);
+                    __builtin_nontemporal_store(s1, d1);
+                }
+            } else {
+                const bool mine = tok < n_tok;
+                if (st0) {
+                    if (pair) __builtin_nontemporal_store(held0, d0 - kRopeUnit);
+                    if (mine) __builtin_nontemporal_store(s0, d0);
+                }
+                if (st1) {
+                    if (pair) __builtin_nontemporal_store(held1, d1 - kRopeUnit);
+                    if (mine) __builtin_nontemporal_store(s1, d1);
+                }
             }
         }
     };
