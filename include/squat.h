@@ -178,6 +178,36 @@ int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_batch, int n_
                         uint16_t* zero, squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
+ * squat_quantize_keys_plan  (Algorithm 1, prefill phase: the token groups of a
+ * prompt are quantized in parallel -- this says how a call spreads them).
+ *
+ * Host-only query, nothing is launched: the launch shape squat_quantize_keys
+ * (per_channel = 0) or squat_quantize_keys_per_channel (per_channel = 1) uses
+ * for a problem of this size on the current device.  Keys are processed in
+ * tiles of 32 consecutive tokens of one (batch entry, head).  The tiles that
+ * share an update matrix (a head's, over the whole batch, or one batch
+ * entry's when update_stride_batch != 0) form a "problem"; each problem gets
+ * workgroups_per_problem persistent workgroups whose wavefronts take tiles
+ *     w, w + S, w + 2 S, ...     (w = wavefront index within the problem,
+ *     S = workgroups_per_problem * wavefronts_per_workgroup)
+ * until tiles_per_problem is reached.  A wavefront therefore runs
+ * floor(tiles_per_problem / S) or one more tile.
+ *
+ *   has_update   0 for update == NULL.   out   host memory.
+ *   Same argument checks (and status codes) as the quantize call itself.
+ * ------------------------------------------------------------------------- */
+typedef struct squat_quantize_plan {
+    int64_t problems;
+    int workgroups_per_problem;
+    int wavefronts_per_workgroup;
+    int64_t tiles_per_problem;
+} squat_quantize_plan;
+
+int squat_quantize_keys_plan(squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens,
+                             int has_update, int64_t update_stride_batch, int bits, int group, int g,
+                             int per_channel, squat_quantize_plan* out);
+
+/* ------------------------------------------------------------------------- *
  * squat_dequantize_keys  (Section 2: deq(c) = c * Delta + m).
  *
  * Inverse of the storage format above: k_out[b,h,t,c] = code * scale + zero

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "squat.h"
 
 namespace squat {
@@ -136,6 +138,36 @@ __device__ __forceinline__ void turn_sincos(double position, float freq, float& 
     sincospif(static_cast<float>(2.0 * frac), &s, &c);
 }
 #endif
+
+// Raises a kernel's dynamic-LDS limit once per device and process.  `done` holds one bit per device
+// ordinal; threads that race only repeat the (idempotent) runtime call.
+inline int set_max_lds_once(std::atomic<uint64_t>& done, const void* kernel, int bytes) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SQUAT_E_HIP;
+    const uint64_t bit = uint64_t(1) << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return SQUAT_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return SQUAT_E_HIP;
+    }
+    done.fetch_or(bit, std::memory_order_release);
+    return SQUAT_OK;
+}
+
+// How a quantize launch spreads its 32-token tiles: `problems` update matrices, each served by
+// `wgs_per_prob` persistent workgroups of `waves` wavefronts that stride over `units_per_prob` tiles.
+struct QuantPlan {
+    int64_t n_prob;
+    int64_t n_inner;         // batch entries that share one update matrix
+    int64_t tiles_per_seq;
+    int64_t units_per_prob;
+    int wgs_per_prob;
+    int waves;
+};
+int plan_quantize(squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens, bool has_update,
+                  int64_t update_stride_batch, int group, int g, QuantPlan& out);
+int plan_quantize_pc(squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens, bool has_update,
+                     int64_t update_stride_batch, int g, QuantPlan& out);
 
 // Number of compute units of the current device (256 if the query fails).
 inline int device_cu_count() {

@@ -368,22 +368,29 @@ extern "C" size_t squat_prepare_workspace(int n_heads, int d, int r, int g) {
     return total < 256 ? 256 : total;
 }
 
-extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, int g, float* update,
-                             void* ws, size_t ws_bytes, squat_stream stream) {
-    if (d != kD) return SQUAT_E_BADSHAPE;
-    if (n_heads < 0 || r < 0 || r > d) return SQUAT_E_BADSHAPE;
-    if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
-    if (!(lambda >= 0.0f)) return SQUAT_E_BADVALUE;       // also rejects NaN
-    if (n_heads == 0) return SQUAT_OK;
-    if (!update || (r > 0 && !qhat)) return SQUAT_E_NULLPTR;
-    if (!aligned(update, 16)) return SQUAT_E_ALIGN;
-    const int nsteps = d / g - 1;
+namespace {
+
+// Bytes of the two scratch pieces a call uses: `yz` (intermediate products of the r > 32 kernel) and
+// `flags` (one int per head, written by the Cholesky kernel and read by the eigen-route kernel that follows
+// it).  Both are fully written before they are read, so neither needs clearing.
+struct PrepScratch {
+    size_t yz_bytes, flag_bytes;
+};
+PrepScratch prep_scratch(int n_heads, int r, int g, bool hard) {
+    const int nsteps = kD / g - 1;
+    const int rp = (r + 1) & ~1;
+    PrepScratch out{0, 0};
+    if (rp > 32)
+        out.yz_bytes = (static_cast<size_t>(n_heads) * nsteps * rp * (g + kD) * sizeof(double) + 255) & ~size_t(255);
+    else if (!hard)
+        out.flag_bytes = (static_cast<size_t>(n_heads) * sizeof(int) + 255) & ~size_t(255);
+    return out;
+}
+
+int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, float* update, double* yz, int* flags,
+                 hipStream_t s) {
+    const int nsteps = kD / g - 1;
     const bool trivial = (r == 0 || lambda == 0.0f || nsteps == 0);
-    if (!trivial) {
-        if (!ws || ws_bytes < squat_prepare_workspace(n_heads, d, r, g)) return SQUAT_E_WORKSPACE;
-        if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
-    }
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t n4 = static_cast<int64_t>(n_heads) * kD * kD / 4;
     hipLaunchKernelGGL(zero_fill, dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, s, update, n4);
     int rc = check_launch();
@@ -392,7 +399,7 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
     PrepParams p;
     p.qhat = qhat;
     p.update = update;
-    p.ws = static_cast<double*>(ws);
+    p.ws = yz;
     p.r = r;
     p.rp = (r + 1) & ~1;
     p.g = g;
@@ -404,26 +411,13 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
         // one workgroup per head, one wavefront per panel
         const size_t lds = ((static_cast<size_t>(p.rp) * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
                            nsteps * (static_cast<size_t>(p.rp) * (p.rp + 2) + p.rp + 2 + 2 * static_cast<size_t>(p.rp) * g) * sizeof(double);
-        static bool done = false;
-        if (!done) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(prepare_wave_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
-                return SQUAT_E_HIP;
-            done = true;
-        }
+        static std::atomic<uint64_t> wave_done{0}, chol_done{0};
+        if ((rc = set_max_lds_once(wave_done, reinterpret_cast<const void*>(prepare_wave_kernel), 140 * 1024))) return rc;
         const int* need = nullptr;
         if (!p.hard) {
-            int* flags = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) +
-                                                ((static_cast<size_t>(n_heads) * nsteps * p.rp * (g + kD) * sizeof(double) + 255) & ~size_t(255)));
             const size_t clds = ((32 * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
                                 static_cast<size_t>(nsteps) * 32 * (kCholLd + g) * sizeof(double) + 16;
-            static bool cdone = false;
-            if (!cdone) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void*>(prepare_chol_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
-                    return SQUAT_E_HIP;
-                cdone = true;
-            }
+            if ((rc = set_max_lds_once(chol_done, reinterpret_cast<const void*>(prepare_chol_kernel), 140 * 1024))) return rc;
             hipLaunchKernelGGL(prepare_chol_kernel, dim3(n_heads), dim3(kCholThreads), clds, s, p, flags);
             rc = check_launch();
             if (rc) return rc;
@@ -437,13 +431,9 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
     const int ts = team_size(p.rp);
 #define SQUAT_PREP_LAUNCH(TS)                                                                              \
     do {                                                                                                   \
-        static bool done = false;                                                                          \
-        if (!done) {                                                                                       \
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(prepare_kernel<TS>),                     \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess) \
-                return SQUAT_E_HIP;                                                                        \
-            done = true;                                                                                   \
-        }                                                                                                  \
+        static std::atomic<uint64_t> done{0};                                                              \
+        if ((rc = set_max_lds_once(done, reinterpret_cast<const void*>(prepare_kernel<TS>), 140 * 1024)))  \
+            return rc;                                                                                     \
         hipLaunchKernelGGL(prepare_kernel<TS>, grid, dim3(kPrepThreads), lds, s, p);                       \
     } while (0)
     if (ts == 64) SQUAT_PREP_LAUNCH(64);
@@ -451,4 +441,36 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
     else SQUAT_PREP_LAUNCH(16);
 #undef SQUAT_PREP_LAUNCH
     return check_launch();
+}
+
+int prepare_check(const float* qhat, int n_heads, int d, int r, float lambda, int g, const float* update) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (n_heads < 0 || r < 0 || r > d) return SQUAT_E_BADSHAPE;
+    if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
+    if (!(lambda >= 0.0f)) return SQUAT_E_BADVALUE;       // also rejects NaN
+    if (n_heads == 0) return SQUAT_OK;
+    if (!update || (r > 0 && !qhat)) return SQUAT_E_NULLPTR;
+    if (!aligned(update, 16)) return SQUAT_E_ALIGN;
+    return SQUAT_OK;
+}
+
+}  // namespace
+
+extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, int g, float* update,
+                             void* ws, size_t ws_bytes, squat_stream stream) {
+    if (int rc = prepare_check(qhat, n_heads, d, r, lambda, g, update)) return rc;
+    if (n_heads == 0) return SQUAT_OK;
+    const int nsteps = d / g - 1;
+    const bool trivial = (r == 0 || lambda == 0.0f || nsteps == 0);
+    int* flags = nullptr;
+    if (!trivial) {
+        if (!ws || ws_bytes < squat_prepare_workspace(n_heads, d, r, g)) return SQUAT_E_WORKSPACE;
+        if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
+        // the flags follow the (r-independent) room for the intermediate products
+        const int rp = (r + 1) & ~1;
+        flags = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) +
+                                       ((static_cast<size_t>(n_heads) * nsteps * rp * (g + kD) * sizeof(double) + 255) & ~size_t(255)));
+    }
+    return prepare_impl(qhat, n_heads, r, lambda, g, update, static_cast<double*>(ws), flags,
+                        static_cast<hipStream_t>(stream));
 }

@@ -433,13 +433,8 @@ int launch(const QuantParams& p, int64_t n_prob, hipStream_t stream) {
     constexpr int kWaves = waves_for(DT, GT, BT);
     constexpr size_t lds = n_pairs(BT) * 4096 + kWaves * 32 * (kD * ES + 16) + 16;
     auto kern = quantize_kernel<BITS, GT, BT, DT>;
-    static bool attr_done = false;      // idempotent; a race only repeats the call
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
-            return SQUAT_E_HIP;
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> attr_done{0};
+    if (int rc = set_max_lds_once(attr_done, reinterpret_cast<const void*>(kern), static_cast<int>(lds))) return rc;
     const dim3 grid(static_cast<unsigned>(n_prob * p.wgs_per_prob));
     hipLaunchKernelGGL(kern, grid, dim3(kWaves * kWave), lds, stream, p);
     return check_launch();
@@ -474,6 +469,41 @@ int dispatch_gt(int gt, int bt, squat_dtype dt, const QuantParams& p, int64_t n_
 }
 
 }  // namespace
+
+// The launch shape of squat_quantize_keys for a problem size: shared by the launcher and by
+// squat_quantize_keys_plan, so that what a caller is told is what runs.
+int squat::plan_quantize(squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens, bool has_update,
+                         int64_t update_stride_batch, int group, int g, QuantPlan& out) {
+    if (group != 32 && group != 64 && group != 128) return SQUAT_E_BADSHAPE;
+    if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
+    if (k_dt != SQUAT_F32 && k_dt != SQUAT_F16 && k_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_batch < 1 || n_heads < 1 || n_tokens < 1 || update_stride_batch < 0) return SQUAT_E_BADSHAPE;
+    if (n_batch * n_heads > (int64_t(1) << 30)) return SQUAT_E_BADSHAPE;
+    out.tiles_per_seq = (n_tokens + kTileTokens - 1) / kTileTokens;
+    // Workgroups are bound to one update matrix: per head when it is shared across the
+    // batch, per (batch, head) otherwise.
+    if (has_update && update_stride_batch != 0) {
+        out.n_prob = n_batch * n_heads;
+        out.n_inner = 1;
+    } else {
+        out.n_prob = n_heads;
+        out.n_inner = n_batch;
+    }
+    out.units_per_prob = out.n_inner * out.tiles_per_seq;
+    if (out.units_per_prob >= (int64_t(1) << 31) || out.tiles_per_seq >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    const int gt = group / 32;
+    const int bt = has_update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
+    if (!(gt % bt == 0 || bt % gt == 0)) return SQUAT_E_BADSHAPE;
+    out.waves = waves_for(k_dt, gt, bt);
+    const int64_t target = kWgsPerCU * static_cast<int64_t>(device_cu_count());   // fill every CU once
+    int64_t per = (target + out.n_prob - 1) / out.n_prob;
+    const int64_t need = (out.units_per_prob + out.waves - 1) / out.waves;
+    if (per > need) per = need;
+    if (per < 1) per = 1;
+    if (out.n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
+    out.wgs_per_prob = static_cast<int>(per);
+    return SQUAT_OK;
+}
 
 // squat_quantize_keys with the outputs placed at tokens out_offset .. of a store that holds out_stride
 // tokens per (batch, head): what a cache appends with.
@@ -517,19 +547,14 @@ int squat::quantize_keys_into(const void* k, squat_dtype k_dt, int64_t n_batch, 
     p.n_heads = n_heads;
     p.tiles_per_seq = (n_tokens + kTileTokens - 1) / kTileTokens;
 
-    // Workgroups are bound to one update matrix: per head when it is shared across the
-    // batch, per (batch, head) otherwise.
-    int64_t n_prob;
-    if (update && update_stride_batch != 0) {
-        n_prob = n_batch * n_heads;
-        p.n_inner = 1;
-    } else {
-        n_prob = n_heads;
-        p.n_inner = n_batch;
-    }
-    p.units_per_prob = p.n_inner * p.tiles_per_seq;
-    if (p.units_per_prob >= (int64_t(1) << 31) || p.tiles_per_seq >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    QuantPlan plan;
+    if (int rc = plan_quantize(k_dt, n_batch, n_heads, n_tokens, update != nullptr, update_stride_batch, group, g, plan))
+        return rc;
     if (k_stride_token * es >= (int64_t(1) << 26)) return SQUAT_E_BADSHAPE;
+    const int64_t n_prob = plan.n_prob;
+    p.n_inner = plan.n_inner;
+    p.units_per_prob = plan.units_per_prob;
+    p.wgs_per_prob = plan.wgs_per_prob;
     {
         // floor(u / d) for u < 2^31: shift = 31 + ceil(log2 d), mul = floor(2^shift / d) + 1
         const uint64_t dv = static_cast<uint64_t>(p.tiles_per_seq);
@@ -538,18 +563,8 @@ int squat::quantize_keys_into(const void* k, squat_dtype k_dt, int64_t n_batch, 
         p.div_shift = 31 + l;
         p.div_mul = static_cast<uint32_t>(((uint64_t(1) << p.div_shift) / dv) + 1);
     }
-
-    const int cus = device_cu_count();
-    const int64_t target = kWgsPerCU * static_cast<int64_t>(cus);   // fill every CU once
-    int64_t per = (target + n_prob - 1) / n_prob;
     const int gt = group / 32;
     const int bt = update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
-    const int kw = waves_for(k_dt, gt, bt);
-    const int64_t need = (p.units_per_prob + kw - 1) / kw;
-    if (per > need) per = need;
-    if (per < 1) per = 1;
-    p.wgs_per_prob = static_cast<int>(per);
-    if (n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
 
     if (!(gt % bt == 0 || bt % gt == 0)) return SQUAT_E_BADSHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -457,13 +457,8 @@ int launch(const PcParams& p, int64_t n_prob, hipStream_t stream) {
     constexpr int kWaves = pc_waves_for(DT, BT);
     constexpr size_t lds = n_pairs(BT) * 8192 + kWaves * 32 * (kD * ES + 16) + 16 + 2 * 64 * 16;
     auto kern = quantize_pc_kernel<BITS, BT, DT>;
-    static bool attr_done = false;      // idempotent; a race only repeats the call
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
-            return SQUAT_E_HIP;
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> attr_done{0};
+    if (int rc = set_max_lds_once(attr_done, reinterpret_cast<const void*>(kern), static_cast<int>(lds))) return rc;
     const dim3 grid(static_cast<unsigned>(n_prob * p.wgs_per_prob));
     hipLaunchKernelGGL(kern, grid, dim3(kWaves * kWave), lds, stream, p);
     return check_launch();
@@ -489,6 +484,37 @@ int dispatch_bt(int bt, squat_dtype dt, const PcParams& p, int64_t n_prob, hipSt
 }
 
 }  // namespace
+
+// The launch shape of squat_quantize_keys_per_channel for a problem size (shared with squat_quantize_keys_plan).
+int squat::plan_quantize_pc(squat_dtype k_dt, int64_t n_batch, int n_heads, int64_t n_tokens, bool has_update,
+                            int64_t update_stride_batch, int g, QuantPlan& out) {
+    if (g != 32 && g != 64 && g != 128) return SQUAT_E_BADSHAPE;
+    if (k_dt != SQUAT_F32 && k_dt != SQUAT_F16 && k_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_batch < 1 || n_heads < 1 || n_tokens < 1 || n_tokens % kTileTokens || update_stride_batch < 0)
+        return SQUAT_E_BADSHAPE;
+    if (n_batch * n_heads > (int64_t(1) << 30)) return SQUAT_E_BADSHAPE;
+    out.tiles_per_seq = n_tokens / kTileTokens;
+    // Workgroups are bound to one update matrix: per head when it is shared across the
+    // batch, per (batch, head) otherwise.
+    if (has_update && update_stride_batch != 0) {
+        out.n_prob = n_batch * n_heads;
+        out.n_inner = 1;
+    } else {
+        out.n_prob = n_heads;
+        out.n_inner = n_batch;
+    }
+    out.units_per_prob = out.n_inner * out.tiles_per_seq;
+    if (out.units_per_prob >= (int64_t(1) << 31) || out.tiles_per_seq >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    const int bt = has_update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
+    out.waves = pc_waves_for(k_dt, bt);
+    int64_t per = (static_cast<int64_t>(device_cu_count()) + out.n_prob - 1) / out.n_prob;     // fill every CU once
+    const int64_t need = (out.units_per_prob + out.waves - 1) / out.waves;
+    if (per > need) per = need;
+    if (per < 1) per = 1;
+    if (out.n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
+    out.wgs_per_prob = static_cast<int>(per);
+    return SQUAT_OK;
+}
 
 // squat_quantize_keys_per_channel into a store that holds out_stride tokens per (batch, head), starting at
 // token out_offset (both multiples of 32).
@@ -531,19 +557,14 @@ int squat::quantize_keys_pc_into(const void* k, squat_dtype k_dt, int64_t n_batc
     p.out_tiles = out_stride / kTileTokens;
     p.out_tile0 = out_offset / kTileTokens;
 
-    // Workgroups are bound to one update matrix: per head when it is shared across the
-    // batch, per (batch, head) otherwise.
-    int64_t n_prob;
-    if (update && update_stride_batch != 0) {
-        n_prob = n_batch * n_heads;
-        p.n_inner = 1;
-    } else {
-        n_prob = n_heads;
-        p.n_inner = n_batch;
-    }
-    p.units_per_prob = p.n_inner * p.tiles_per_seq;
-    if (p.units_per_prob >= (int64_t(1) << 31) || p.tiles_per_seq >= (int64_t(1) << 31)) return SQUAT_E_BADSHAPE;
+    QuantPlan plan;
+    if (int rc = plan_quantize_pc(k_dt, n_batch, n_heads, n_tokens, update != nullptr, update_stride_batch, g, plan))
+        return rc;
     if (k_stride_token * es >= (int64_t(1) << 26)) return SQUAT_E_BADSHAPE;
+    const int64_t n_prob = plan.n_prob;
+    p.n_inner = plan.n_inner;
+    p.units_per_prob = plan.units_per_prob;
+    p.wgs_per_prob = plan.wgs_per_prob;
     {
         // floor(u / dv) for u < 2^31: shift = 31 + ceil(log2 dv), mul = floor(2^shift / dv) + 1
         const uint64_t dv = static_cast<uint64_t>(p.tiles_per_seq);
@@ -552,15 +573,7 @@ int squat::quantize_keys_pc_into(const void* k, squat_dtype k_dt, int64_t n_batc
         p.div_shift = 31 + l;
         p.div_mul = static_cast<uint32_t>(((uint64_t(1) << p.div_shift) / dv) + 1);
     }
-
     const int bt = update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
-    const int kw = pc_waves_for(k_dt, bt);
-    int64_t per = (static_cast<int64_t>(device_cu_count()) + n_prob - 1) / n_prob;     // fill every CU once
-    const int64_t need = (p.units_per_prob + kw - 1) / kw;
-    if (per > need) per = need;
-    if (per < 1) per = 1;
-    p.wgs_per_prob = static_cast<int>(per);
-    if (n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bits == 2 ? dispatch_bt<2>(bt, k_dt, p, n_prob, s) : dispatch_bt<4>(bt, k_dt, p, n_prob, s);

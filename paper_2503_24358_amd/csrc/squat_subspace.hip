@@ -473,28 +473,19 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
 
     const size_t red_lds = 2 * kPartialFloats * sizeof(float);      // 80 KB
     const dim3 grid(static_cast<unsigned>(n_kv_heads) * pl.wgs_per_head);
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gram_partial_16<SQUAT_BF16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(red_lds)) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(gram_partial_16<SQUAT_F16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(red_lds)) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(gram_partial_f32),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(red_lds)) != hipSuccess)
-            return SQUAT_E_HIP;
-    }
     const size_t eig_lds = kD * kEigLd * sizeof(double) + kD * sizeof(double) + kD * sizeof(int) + 16;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(eig_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(eig_lds)) != hipSuccess)
-            return SQUAT_E_HIP;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(eig_tridiag_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kTriLdsBytes)) != hipSuccess)
-            return SQUAT_E_HIP;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gram_reduce),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kRedLdsBytes)) != hipSuccess)
-            return SQUAT_E_HIP;
-        attr_done = true;
+    {
+        // one flag per kernel: a failed call is retried by the next launch, a raced one only repeated
+        static std::atomic<uint64_t> done[6];
+        const struct { const void* kernel; size_t bytes; } limits[6] = {
+            {reinterpret_cast<const void*>(gram_partial_16<SQUAT_BF16>), red_lds},
+            {reinterpret_cast<const void*>(gram_partial_16<SQUAT_F16>), red_lds},
+            {reinterpret_cast<const void*>(gram_partial_f32), red_lds},
+            {reinterpret_cast<const void*>(eig_kernel), eig_lds},
+            {reinterpret_cast<const void*>(eig_tridiag_kernel), static_cast<size_t>(kTriLdsBytes)},
+            {reinterpret_cast<const void*>(gram_reduce), static_cast<size_t>(kRedLdsBytes)}};
+        for (int i = 0; i < 6; ++i)
+            if (int rc = set_max_lds_once(done[i], limits[i].kernel, static_cast<int>(limits[i].bytes))) return rc;
     }
     switch (q_dt) {
         case SQUAT_BF16: hipLaunchKernelGGL(gram_partial_16<SQUAT_BF16>, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;

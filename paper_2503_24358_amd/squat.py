@@ -19,7 +19,7 @@ _lib = None
 
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
            "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
-           "squat_quantize_keys", "squat_dequantize_keys",
+           "squat_quantize_keys", "squat_quantize_keys_plan", "squat_dequantize_keys",
            "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel", "squat_key_scores_rope",
            "squat_key_scores_rope_per_channel",
            "squat_cache_arena_bytes", "squat_cache_create", "squat_cache_destroy", "squat_cache_reset",
@@ -45,6 +45,11 @@ class CacheCounts(ctypes.Structure):
     _fields_ = [("n_tokens", ctypes.c_int64), ("keys_quantized", ctypes.c_int64), ("keys_residual", ctypes.c_int),
                 ("values_quantized", ctypes.c_int64), ("values_residual", ctypes.c_int),
                 ("value_ring_head", ctypes.c_int)]
+
+
+class QuantizePlan(ctypes.Structure):
+    _fields_ = [("problems", ctypes.c_int64), ("workgroups_per_problem", ctypes.c_int),
+                ("wavefronts_per_workgroup", ctypes.c_int), ("tiles_per_problem", ctypes.c_int64)]
 
 
 class SquatError(RuntimeError):
@@ -78,6 +83,9 @@ def lib() -> ctypes.CDLL:
     L.squat_quantize_keys.restype = i32
     L.squat_quantize_keys.argtypes = [vp, i32, i64, i32, i64, i32, i64, i64, i64, vp, i64, i32, i32, i32,
                                       vp, vp, vp, vp]
+    L.squat_quantize_keys_plan.restype = i32
+    L.squat_quantize_keys_plan.argtypes = [i32, i64, i32, i64, i32, i64, i32, i32, i32, i32,
+                                           ctypes.POINTER(QuantizePlan)]
     L.squat_dequantize_keys.restype = i32
     L.squat_dequantize_keys.argtypes = [vp, vp, vp, i64, i32, i64, i32, i32, i32, vp, i32, i64, i64, i64, vp]
     L.squat_quantize_keys_per_channel.restype = i32
@@ -227,6 +235,17 @@ def quantize_keys(k: torch.Tensor, update: Optional[torch.Tensor], bits: int, gr
     if rc:
         raise SquatError(rc, "squat_quantize_keys")
     return codes, scale, zero
+
+
+def quantize_keys_plan(k_dtype, n_batch: int, n_heads: int, n_tokens: int, has_update: bool, update_stride_batch: int,
+                       bits: int, group: int, g: int, per_channel: bool = False) -> QuantizePlan:
+    """squat_quantize_keys_plan: the launch shape the quantize call would use (host-only query)."""
+    out = QuantizePlan()
+    rc = lib().squat_quantize_keys_plan(_DT[k_dtype], n_batch, n_heads, n_tokens, int(bool(has_update)),
+                                        update_stride_batch, bits, group, g, int(bool(per_channel)), ctypes.byref(out))
+    if rc:
+        raise SquatError(rc, "squat_quantize_keys_plan")
+    return out
 
 
 def dequantize_keys(codes: torch.Tensor, scale: torch.Tensor, zero: torch.Tensor, bits: int, group: int,

@@ -260,3 +260,38 @@ def test_cache_configuration_and_creation_are_validated_on_the_host():
     assert L.squat_cache_reset(h) == 0
     L.squat_cache_destroy(h)
     assert L.squat_cache_state(None, ctypes.byref(cnt)) == -1
+
+
+def test_quantize_plan_follows_the_documented_rule():
+    """squat_quantize_keys_plan is a host-only query (without a GPU the library plans for 256 compute units):
+    tiles of 32 tokens, problems = update matrices, persistent workgroups striding over a problem's tiles."""
+    import torch
+    bf16, f32 = torch.bfloat16, torch.float32
+    # the benchmark's launch: 256 stacked heads, one workgroup each, 1024 tiles over 12 wavefronts
+    p = squat.quantize_keys_plan(bf16, 1, 256, 32768, True, 0, 2, 32, 32)
+    assert (p.problems, p.workgroups_per_problem, p.wavefronts_per_workgroup, p.tiles_per_problem) == (256, 1, 12, 1024)
+    # one layer: 8 heads share the 256 compute units
+    p = squat.quantize_keys_plan(bf16, 1, 8, 32768, True, 0, 2, 32, 32)
+    assert (p.problems, p.workgroups_per_problem, p.tiles_per_problem) == (8, 32, 1024)
+    # the decode flush: one tile per (sequence, head), the update matrix shared by the 64 sequences
+    p = squat.quantize_keys_plan(bf16, 64, 256, 32, True, 0, 2, 32, 32)
+    assert (p.problems, p.workgroups_per_problem, p.tiles_per_problem) == (256, 1, 64)
+    # per-batch matrices: a problem per (sequence, head)
+    p = squat.quantize_keys_plan(bf16, 4, 8, 100, True, 128 * 128 * 8, 2, 32, 32)
+    assert (p.problems, p.tiles_per_problem) == (32, 4) and p.workgroups_per_problem == 1
+    # fp32 keys run 6 wavefronts per workgroup, the two-tile-per-block and four-tile-statistics variants 8
+    assert squat.quantize_keys_plan(f32, 1, 256, 1191, True, 0, 2, 32, 32).wavefronts_per_workgroup == 6
+    assert squat.quantize_keys_plan(bf16, 1, 256, 1191, True, 0, 2, 32, 64).wavefronts_per_workgroup == 8
+    assert squat.quantize_keys_plan(bf16, 1, 256, 1191, True, 0, 4, 128, 32).wavefronts_per_workgroup == 8
+    # per-channel grouping: whole token groups only
+    p = squat.quantize_keys_plan(bf16, 1, 256, 1216, True, 0, 2, 32, 32, per_channel=True)
+    assert (p.problems, p.workgroups_per_problem, p.wavefronts_per_workgroup, p.tiles_per_problem) == (256, 1, 12, 38)
+    L = squat.lib()
+    out = squat.QuantizePlan()
+    ref = ctypes.byref(out)
+    assert L.squat_quantize_keys_plan(2, 1, 8, 1000, 1, 0, 2, 32, 32, 1, ref) == -2      # not a multiple of 32
+    assert L.squat_quantize_keys_plan(2, 1, 8, 1024, 1, 0, 3, 32, 32, 0, ref) == -2
+    assert L.squat_quantize_keys_plan(2, 1, 8, 1024, 1, 0, 2, 48, 32, 0, ref) == -2
+    assert L.squat_quantize_keys_plan(2, 1, 8, 1024, 1, 0, 2, 64, 32, 1, ref) == -2      # per-channel groups are 32 tokens
+    assert L.squat_quantize_keys_plan(9, 1, 8, 1024, 1, 0, 2, 32, 32, 0, ref) == -3
+    assert L.squat_quantize_keys_plan(2, 1, 8, 1024, 1, 0, 2, 32, 32, 0, None) == -1

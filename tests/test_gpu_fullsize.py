@@ -108,6 +108,47 @@ def test_fullsize_codes_and_dequantized_keys_on_sampled_rows(run):
     assert tot["worst_code_dist"] <= 1e-5
 
 
+@pytest.mark.parametrize("bits,group", [(4, 32), (2, 128), (4, 128)])
+def test_fullsize_other_long_context_variants_on_sampled_rows(run, bits, group):
+    """The long-context configuration names 2- and 4-bit codes with statistics groups of 32 and 128 channels:
+    the three variants next to the headline one, at the benchmark's size and launch configuration (86
+    tiles per wavefront), sampled rows replayed by the oracle; dequantize read-back of the same rows."""
+    wl = run["wl"]
+    codes_t, scale_t, zero_t = squat.quantize_keys(wl.k, run["update"], bits, group, wl.g)
+    back_t = squat.dequantize_keys(codes_t, scale_t, zero_t, bits, group, torch.bfloat16)
+    torch.cuda.synchronize()
+    plan = squat.quantize_keys_plan(wl.k.dtype, 1, wl.heads, wl.n_tokens, True, 0, bits, group, wl.g)
+    assert plan.tiles_per_problem // (plan.workgroups_per_problem * plan.wavefronts_per_workgroup) >= 80
+    assert torch.isfinite(scale_t).all() and torch.isfinite(zero_t).all() and (scale_t >= 0).all()
+    gen = np.random.default_rng(100 * bits + group)
+    heads = np.concatenate([[0, 255], gen.integers(0, wl.heads, size=10)])
+    tot = dict(code_diff=0, code_unexplained=0, meta_diff=0, meta_unexplained=0, n_codes=0, worst_code_dist=0.0)
+    free = 0
+    for h in heads:
+        toks = np.unique(np.concatenate([[0, 31, 32, wl.n_tokens - 1], gen.integers(0, wl.n_tokens, size=252)]))
+        idx = torch.from_numpy(toks).cuda()
+        k = _bf16_to_f64(wl.k[0, h].index_select(0, idx))
+        U = run["update"][h].cpu().numpy().astype(np.float64)
+        codes = O.unpack_codes(codes_t[0, h].index_select(0, idx).cpu().numpy().view(np.uint32), bits)
+        scale = scale_t[0, h].index_select(0, idx).cpu().numpy()
+        zero = zero_t[0, h].index_select(0, idx).cpu().numpy()
+        rep = O.replay_classify(k, U, bits, group, wl.g, codes, scale, zero)
+        for key in tot:
+            tot[key] = max(tot[key], rep[key]) if key.startswith("worst") else tot[key] + rep[key]
+        free += int((O.quantize_keys(k, U, bits, group, wl.g)["codes"] != codes).sum())
+        want = O.dequantize_keys(codes, scale, zero, group)
+        got = _bf16_to_f64(back_t[0, h].index_select(0, idx))
+        m, e = np.frexp(want)
+        assert (got != np.ldexp(np.rint(m * 256.0) / 256.0, e)).mean() <= 1e-4
+    assert tot["code_unexplained"] == 0 and tot["meta_unexplained"] == 0, tot
+    assert tot["code_diff"] + tot["meta_diff"] <= max(1, 1e-4 * tot["n_codes"]), tot
+    assert free <= 1e-3 * tot["n_codes"], (tot, free)
+    assert tot["worst_code_dist"] <= 1e-5
+    c2, s2, z2 = squat.quantize_keys(wl.k, run["update"], bits, group, wl.g)
+    torch.cuda.synchronize()
+    assert torch.equal(c2, codes_t) and torch.equal(s2, scale_t) and torch.equal(z2, zero_t)
+
+
 def test_fullsize_outputs_are_valid_everywhere(run):
     """Properties that hold at any size, over ALL outputs: no NaN/Inf metadata, scales non-negative,
     a bit-identical second run (deterministic), and the hot path leaves its input untouched."""

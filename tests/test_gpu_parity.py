@@ -155,7 +155,7 @@ def _check_against_oracle(kt, kval, U_np, bits, G, g, *, per_batch_U=False, budg
 
 
 @pytest.mark.parametrize("bits,G,g", [(2, 32, 32), (4, 32, 32), (2, 32, 64), (4, 64, 64), (2, 128, 32), (2, 64, 32),
-                                      (4, 128, 64), (2, 32, 128)])
+                                      (4, 128, 64), (2, 32, 128), (4, 128, 32), (4, 32, 128), (4, 64, 32)])
 def test_quantize_with_update_matches_oracle(bits, G, g):
     B, H, n = 2, 4, 1031          # 32 full tiles and a ragged tail of 7
     kt, kval = _keys(200 + bits + G + g, H, n, synth.BF16, batch=B)

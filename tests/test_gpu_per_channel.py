@@ -140,7 +140,7 @@ def test_per_channel_rtn(bits, dtype):
 @pytest.mark.parametrize("bits,g", [(2, 32), (4, 32), (2, 64), (4, 64), (2, 128)])
 @pytest.mark.parametrize("fp16_grid", [False, True])
 def test_per_channel_with_update_matches_oracle(bits, g, fp16_grid):
-    B, H, n = 2, 4, 1056          # 33 tiles: more units than one workgroup's wavefronts
+    B, H, n = 2, 4, 1056          # 33 tiles per (batch entry, head); one tile per wavefront (loop depth: test_gpu_loop_depth.py)
     kt, kval = _keys(2300 + bits + g, H, n, synth.BF16, batch=B)
     _, U = _oracle_U(2400 + g, H, 16, 1e-3, g, fp16_grid=fp16_grid)
     _check(kt, kval, U, bits, g)
