@@ -139,6 +139,26 @@ int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, in
                   float* update, void* ws, size_t ws_bytes, squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
+ * squat_prepare_noalloc  -- squat_prepare for callers that cannot allocate or
+ * carry a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.
+ *
+ * Same arguments, checks, kernels and results as squat_prepare, without `ws`:
+ * the scratch is a 4 MiB array inside the library's code object (one copy per
+ * device, held until the process ends).  The call allocates and frees nothing.
+ * Limits: r <= 32 with a finite lambda needs 4 bytes per head (n_heads <=
+ * 2^20); r <= 32 with lambda = +INFINITY needs none; r > 32 needs
+ * n_heads * (d/g - 1) * (r rounded up to even) * (g + d) * 8 bytes, rounded up
+ * to 256.  A problem beyond 4 MiB returns SQUAT_E_WORKSPACE (nothing launched).
+ * Every call on a device shares that device's array: calls that may overlap
+ * on one device (different streams, or threads) race; order them.  The first
+ * call on a device looks the array's address up (no allocation); make that
+ * call outside a graph capture.
+ * ------------------------------------------------------------------------- */
+int squat_prepare_noalloc(const float* qhat, int n_heads, int d, int r, float lambda, int g,
+                          float* update, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
  * squat_quantize_keys  (Section 2 "Quantization": qtz/deq; Algorithm 1,
  * function Quant; Lemma 2, the update of the not-yet-quantized elements).
  *

@@ -16,6 +16,12 @@
 
 using namespace squat;
 
+// Scratch of squat_prepare_noalloc: lives in the code object, one copy per device that loads the library,
+// for the life of the process.  In host code this name only stands for the symbol; the device address is
+// looked up once per device (scratch_address below) and the kernels get that pointer.
+constexpr size_t kStaticScratchBytes = size_t(4) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 constexpr int kPrepThreads = 1024;
@@ -473,4 +479,46 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
     }
     return prepare_impl(qhat, n_heads, r, lambda, g, update, static_cast<double*>(ws), flags,
                         static_cast<hipStream_t>(stream));
+}
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (each device holds its own copy at its own address).
+int scratch_address(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SQUAT_E_HIP;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return SQUAT_E_HIP;
+        }
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // threads that race store the same address
+    }
+    *out = ptr;
+    return SQUAT_OK;
+}
+
+}  // namespace
+
+extern "C" int squat_prepare_noalloc(const float* qhat, int n_heads, int d, int r, float lambda, int g,
+                                     float* update, squat_stream stream) {
+    if (int rc = prepare_check(qhat, n_heads, d, r, lambda, g, update)) return rc;
+    if (n_heads == 0) return SQUAT_OK;
+    const bool trivial = (r == 0 || lambda == 0.0f || d / g - 1 == 0);
+    double* yz = nullptr;
+    int* flags = nullptr;
+    if (!trivial) {
+        const PrepScratch need = prep_scratch(n_heads, r, g, isinf(lambda));
+        if (need.yz_bytes + need.flag_bytes > kStaticScratchBytes) return SQUAT_E_WORKSPACE;
+        void* base = nullptr;
+        if (int rc = scratch_address(&base)) return rc;
+        // a call uses one of the two pieces, from the start of the array
+        yz = static_cast<double*>(base);
+        flags = static_cast<int*>(base);
+    }
+    return prepare_impl(qhat, n_heads, r, lambda, g, update, yz, flags, static_cast<hipStream_t>(stream));
 }

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsquat.s
 _lib = None
 
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
-           "squat_build_subspace", "squat_prepare_workspace", "squat_prepare",
+           "squat_build_subspace", "squat_prepare_workspace", "squat_prepare", "squat_prepare_noalloc",
            "squat_quantize_keys", "squat_quantize_keys_plan", "squat_dequantize_keys",
            "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel", "squat_key_scores_rope",
            "squat_key_scores_rope_per_channel",
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
     L.squat_prepare_workspace.argtypes = [i32, i32, i32, i32]
     L.squat_prepare.restype = i32
     L.squat_prepare.argtypes = [vp, i32, i32, i32, f32, i32, vp, vp, sz, vp]
+    L.squat_prepare_noalloc.restype = i32
+    L.squat_prepare_noalloc.argtypes = [vp, i32, i32, i32, f32, i32, vp, vp]
     L.squat_quantize_keys.restype = i32
     L.squat_quantize_keys.argtypes = [vp, i32, i64, i32, i64, i32, i64, i64, i64, vp, i64, i32, i32, i32,
                                       vp, vp, vp, vp]
@@ -204,6 +206,22 @@ def prepare(qhat: torch.Tensor, lam: float, g: int, *, update=None, ws=None, str
                              ws.numel(), _stream(stream))
     if rc:
         raise SquatError(rc, "squat_prepare")
+    return update
+
+
+def prepare_noalloc(qhat: torch.Tensor, lam: float, g: int, update: torch.Tensor, stream=None) -> torch.Tensor:
+    """squat_prepare_noalloc: squat_prepare on the library's static scratch; `update` [n_heads, d, d] f32 is
+    the caller's (this binding allocates nothing either)."""
+    _need_cuda(qhat, update)
+    if qhat.dtype != torch.float32 or not qhat.is_contiguous():
+        raise ValueError("qhat must be dense float32")
+    h, r, d = qhat.shape
+    if update.dtype != torch.float32 or not update.is_contiguous() or tuple(update.shape) != (h, d, d):
+        raise ValueError("update must be dense float32 [n_heads, d, d]")
+    rc = lib().squat_prepare_noalloc(_ptr(qhat) if r > 0 else None, h, d, r, float(lam), g, _ptr(update),
+                                     _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_prepare_noalloc")
     return update
 
 
