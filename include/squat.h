@@ -139,6 +139,24 @@ int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, in
                   float* update, void* ws, size_t ws_bytes, squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
+ * squat_prepare_ex  (Lemma 2, Lemma 3: as squat_prepare) -- squat_prepare with
+ * a choice of how the entries of U are stored.
+ *
+ *   flags   0: as squat_prepare, entries on the fp16 grid (an approximation of
+ *           this implementation, relative 2^-12 per entry, in exchange for a
+ *           two-pass contraction in the quantize kernels);
+ *           SQUAT_PREPARE_FULL_PRECISION: the fp64 result rounded once to fp32
+ *           (Lemma 2's matrix to fp32 accuracy; the quantize kernels then run
+ *           their three-pass contraction, a few per cent slower).
+ *           Any other bit set: SQUAT_E_BADVALUE.
+ *   Everything else as for squat_prepare (same workspace size).
+ * ------------------------------------------------------------------------- */
+#define SQUAT_PREPARE_FULL_PRECISION 1u
+
+int squat_prepare_ex(const float* qhat, int n_heads, int d, int r, float lambda, int g, unsigned flags,
+                     float* update, void* ws, size_t ws_bytes, squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
  * squat_prepare_noalloc  -- squat_prepare for callers that cannot allocate or
  * carry a workspace: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.

@@ -7,8 +7,8 @@
 // One workgroup per (head, t) works in fp64: it forms S = I/lambda + Qr Qr^T in LDS,
 // diagonalises it with the one-sided Jacobi routine (rows a_i = mu_i v_i), and applies
 // S^+ = sum_i a_i a_i^T / mu_i^3.  lambda = +inf drops the I/lambda term and discards the
-// (numerically) zero mu_i, which yields -pinv(Qr) Qb.  The result is stored as fp32 numbers that are
-// exactly representable in fp16.
+// (numerically) zero mu_i, which yields -pinv(Qr) Qb.  By default the result is stored as fp32 numbers that
+// are exactly representable in fp16; squat_prepare_ex can store the plain fp32 rounding instead.
 #include <math.h>
 
 #include "squat_internal.h"
@@ -34,7 +34,15 @@ struct PrepParams {
     int nprob;            // heads * nsteps
     double inv_lambda;    // 0 for lambda = +inf
     int hard;
+    int full;             // 1: store the fp32 rounding of the fp64 result; 0: round it to the fp16 grid first
 };
+
+// The stored form of an entry of U.  On the fp16 grid (relative 2^-12) the quantize kernels contract with two
+// fp16 matrix passes instead of three.
+__device__ __forceinline__ float stored_entry(double v, int full) {
+    const float f = static_cast<float>(v);
+    return full ? f : static_cast<float>(static_cast<_Float16>(f));
+}
 
 __global__ void __launch_bounds__(256) zero_fill(float* p, int64_t n4) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -111,9 +119,7 @@ __global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams 
         const int c = idx / g, j = idx % g;
         double s = 0.0;
         for (int i = 0; i < rp; ++i) s += z[i * kD + c] * y[i * g + j];
-        // Entries are rounded to the fp16 grid (relative 2^-12): the quantize kernel then needs two
-        // matrix passes instead of three, and both sides of any comparison use this same matrix.
-        U[(c0 + c) * kD + (c0 - g) + j] = static_cast<float>(static_cast<_Float16>(static_cast<float>(-s)));
+        U[(c0 + c) * kD + (c0 - g) + j] = stored_entry(-s, p.full);
     }
 }
 
@@ -184,8 +190,7 @@ __global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p, c
         const int c = idx / g, j = idx % g;
         double s = 0.0;
         for (int k = 0; k < rp; ++k) s = fma(static_cast<double>(Qf[k * QLD + c0 + c]), X[k * g + j], s);
-        // rounded to the fp16 grid, as in the large-r kernel
-        U[(c0 + c) * kD + (c0 - g) + j] = static_cast<float>(static_cast<_Float16>(static_cast<float>(-s)));
+        U[(c0 + c) * kD + (c0 - g) + j] = stored_entry(-s, p.full);
     }
 }
 
@@ -339,7 +344,7 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     }
     __syncthreads();
 
-    // W_t[c][j] = -sum_k Q[k][(t+1) g + c] X_t[k][j], rounded to the fp16 grid as in the other kernels
+    // W_t[c][j] = -sum_k Q[k][(t+1) g + c] X_t[k][j]
     float* U = p.update + static_cast<int64_t>(head) * kD * kD;
     for (int t = 0; t < nsteps; ++t) {
         const int c0 = (t + 1) * g, nrest = kD - c0;
@@ -351,7 +356,7 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
             for (int k = 0; k < 32; ++k)
                 s4[k & 3] = fma(static_cast<double>(Qf[k * QLD + c0 + c]), X[k * g + j], s4[k & 3]);
             const double sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-            U[(c0 + c) * kD + (c0 - g) + j] = static_cast<float>(static_cast<_Float16>(static_cast<float>(-sum)));
+            U[(c0 + c) * kD + (c0 - g) + j] = stored_entry(-sum, p.full);
         }
     }
 }
@@ -393,8 +398,8 @@ PrepScratch prep_scratch(int n_heads, int r, int g, bool hard) {
     return out;
 }
 
-int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, float* update, double* yz, int* flags,
-                 hipStream_t s) {
+int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, unsigned flags_arg, float* update,
+                 double* yz, int* flags, hipStream_t s) {
     const int nsteps = kD / g - 1;
     const bool trivial = (r == 0 || lambda == 0.0f || nsteps == 0);
     const int64_t n4 = static_cast<int64_t>(n_heads) * kD * kD / 4;
@@ -411,6 +416,7 @@ int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, flo
     p.g = g;
     p.nsteps = nsteps;
     p.hard = isinf(lambda) ? 1 : 0;
+    p.full = (flags_arg & SQUAT_PREPARE_FULL_PRECISION) ? 1 : 0;
     p.inv_lambda = p.hard ? 0.0 : 1.0 / static_cast<double>(lambda);
     p.nprob = n_heads * nsteps;
     if (p.rp <= 32) {
@@ -464,6 +470,12 @@ int prepare_check(const float* qhat, int n_heads, int d, int r, float lambda, in
 
 extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float lambda, int g, float* update,
                              void* ws, size_t ws_bytes, squat_stream stream) {
+    return squat_prepare_ex(qhat, n_heads, d, r, lambda, g, 0u, update, ws, ws_bytes, stream);
+}
+
+extern "C" int squat_prepare_ex(const float* qhat, int n_heads, int d, int r, float lambda, int g, unsigned flags_arg,
+                                float* update, void* ws, size_t ws_bytes, squat_stream stream) {
+    if (flags_arg & ~unsigned(SQUAT_PREPARE_FULL_PRECISION)) return SQUAT_E_BADVALUE;
     if (int rc = prepare_check(qhat, n_heads, d, r, lambda, g, update)) return rc;
     if (n_heads == 0) return SQUAT_OK;
     const int nsteps = d / g - 1;
@@ -477,7 +489,7 @@ extern "C" int squat_prepare(const float* qhat, int n_heads, int d, int r, float
         flags = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) +
                                        ((static_cast<size_t>(n_heads) * nsteps * rp * (g + kD) * sizeof(double) + 255) & ~size_t(255)));
     }
-    return prepare_impl(qhat, n_heads, r, lambda, g, update, static_cast<double*>(ws), flags,
+    return prepare_impl(qhat, n_heads, r, lambda, g, flags_arg, update, static_cast<double*>(ws), flags,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -520,5 +532,5 @@ extern "C" int squat_prepare_noalloc(const float* qhat, int n_heads, int d, int 
         yz = static_cast<double*>(base);
         flags = static_cast<int*>(base);
     }
-    return prepare_impl(qhat, n_heads, r, lambda, g, update, yz, flags, static_cast<hipStream_t>(stream));
+    return prepare_impl(qhat, n_heads, r, lambda, g, 0u, update, yz, flags, static_cast<hipStream_t>(stream));
 }

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsquat.s
 _lib = None
 
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
-           "squat_build_subspace", "squat_prepare_workspace", "squat_prepare", "squat_prepare_noalloc",
+           "squat_build_subspace", "squat_prepare_workspace", "squat_prepare", "squat_prepare_ex", "squat_prepare_noalloc",
            "squat_quantize_keys", "squat_quantize_keys_plan", "squat_dequantize_keys",
            "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel", "squat_key_scores_rope",
            "squat_key_scores_rope_per_channel",
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
     L.squat_prepare_workspace.argtypes = [i32, i32, i32, i32]
     L.squat_prepare.restype = i32
     L.squat_prepare.argtypes = [vp, i32, i32, i32, f32, i32, vp, vp, sz, vp]
+    L.squat_prepare_ex.restype = i32
+    L.squat_prepare_ex.argtypes = [vp, i32, i32, i32, f32, i32, ctypes.c_uint, vp, vp, sz, vp]
     L.squat_prepare_noalloc.restype = i32
     L.squat_prepare_noalloc.argtypes = [vp, i32, i32, i32, f32, i32, vp, vp]
     L.squat_quantize_keys.restype = i32
@@ -192,8 +194,13 @@ def prepare_workspace(n_heads: int, d: int, r: int, g: int) -> int:
     return int(lib().squat_prepare_workspace(n_heads, d, r, g))
 
 
-def prepare(qhat: torch.Tensor, lam: float, g: int, *, update=None, ws=None, stream=None) -> torch.Tensor:
-    """squat_prepare.  qhat: [n_heads, r, d] f32 dense -> update [n_heads, d, d] f32."""
+PREPARE_FULL_PRECISION = 1
+
+
+def prepare(qhat: torch.Tensor, lam: float, g: int, *, update=None, ws=None, stream=None,
+            full_precision: bool = False) -> torch.Tensor:
+    """squat_prepare (squat_prepare_ex with SQUAT_PREPARE_FULL_PRECISION when full_precision is set).
+    qhat: [n_heads, r, d] f32 dense -> update [n_heads, d, d] f32."""
     _need_cuda(qhat)
     if qhat.dtype != torch.float32 or not qhat.is_contiguous():
         raise ValueError("qhat must be dense float32")
@@ -202,8 +209,12 @@ def prepare(qhat: torch.Tensor, lam: float, g: int, *, update=None, ws=None, str
         update = torch.empty((h, d, d), dtype=torch.float32, device=qhat.device)
     if ws is None:
         ws = _ws(prepare_workspace(h, d, r, g), qhat.device)
-    rc = lib().squat_prepare(_ptr(qhat) if r > 0 else None, h, d, r, float(lam), g, _ptr(update), _ptr(ws),
-                             ws.numel(), _stream(stream))
+    if full_precision:
+        rc = lib().squat_prepare_ex(_ptr(qhat) if r > 0 else None, h, d, r, float(lam), g, PREPARE_FULL_PRECISION,
+                                    _ptr(update), _ptr(ws), ws.numel(), _stream(stream))
+    else:
+        rc = lib().squat_prepare(_ptr(qhat) if r > 0 else None, h, d, r, float(lam), g, _ptr(update), _ptr(ws),
+                                 ws.numel(), _stream(stream))
     if rc:
         raise SquatError(rc, "squat_prepare")
     return update

@@ -406,6 +406,27 @@ def test_prepare_matches_oracle(r, lam, g):
             assert not U[h][t * g:(t + 1) * g, t * g:].any()
 
 
+@pytest.mark.parametrize("r,lam,g", [(16, 1e-3, 32), (5, 1e-3, 64), (40, 5e-4, 64), (32, 1e-3, 32), (7, 0.5, 32),
+                                     (16, np.inf, 32), (60, 5e-4, 32), (128, 1e-3, 32)])
+def test_prepare_full_precision_matches_oracle(r, lam, g):
+    """squat_prepare_ex with SQUAT_PREPARE_FULL_PRECISION: Lemma 2's matrix computed in fp64 and rounded once to
+    fp32, against the oracle's float64 matrix at the accuracy that arithmetic delivers."""
+    H = 3
+    gen = synth.rng(1300 + r)
+    Qh = (gen.standard_normal((H, r, 128)) * np.linspace(60, 5, r)[None, :, None]).astype(np.float32)
+    U = squat.prepare(torch.from_numpy(Qh).cuda(), lam, g, full_precision=True).cpu().numpy().astype(np.float64)
+    grid = squat.prepare(torch.from_numpy(Qh).cuda(), lam, g).cpu().numpy().astype(np.float64)
+    for h in range(H):
+        ref = O.update_matrix_lowrank(Qh[h].astype(np.float64), lam, g)
+        assert np.linalg.norm(U[h] - ref) <= 1e-5 * np.linalg.norm(ref)
+        assert np.abs(U[h] - ref).max() <= 1e-5 * np.abs(ref).max()
+        # the default form is this matrix rounded to the fp16 grid (a midpoint may fall either way)
+        assert (grid[h] != U[h].astype(np.float16).astype(np.float64)).mean() <= 1e-3
+        assert (U[h] != grid[h]).mean() > 0.1
+        for t in range(128 // g):
+            assert not U[h][t * g:(t + 1) * g, t * g:].any()
+
+
 def test_prepare_mixed_conditioning_picks_the_route_per_head():
     """r <= 32, finite lambda: heads whose S = I / lambda + Qr Qr^T is well conditioned take the Cholesky
     route (large rows of full rank, or zero rows at ordinary scale); a head with zero rows AND lambda *
@@ -466,3 +487,55 @@ def test_chained_path_end_to_end():
     want = util.round_to(O.dequantize_keys(codes, scale, zero, 32), torch.bfloat16)
     got = util.out_to_f64(back_t)
     assert (got != want).mean() <= 1e-4
+
+
+@pytest.mark.parametrize("planted,r", [(12, 8), (0, 16)])
+@pytest.mark.parametrize("full_precision", [True, False])
+def test_gpu_chain_against_the_oracles_own_chain(planted, r, full_precision, record_property):
+    """The distance between the two CHAINS, nothing handed over: the GPU goes queries, keys -> Qhat -> U -> codes
+    with its own intermediates, the oracle does the same in float64 with its own.  Codes are then compared
+    free-running.  This measures what the stage-by-stage tests cannot: how much the GPU's own Qhat (fp32 Gram
+    sums) and its stored U (on the fp16 grid by default, fp32 with SQUAT_PREPARE_FULL_PRECISION) move the
+    result.  What must hold either way: the method's objective (the energy of the error's projection on the
+    query subspace) matches the oracle chain's to 1 %, far below round-to-nearest's; keys whose discrete
+    decisions all agree dequantize identically."""
+    # planted = 12, r = 8: the r-th singular value is well separated, the subspace well defined;
+    # planted = 0, r = 16: near-isotropic queries, where the subspace itself moves with the Gram sums' rounding
+    hq, qpk, n, lam, g, bits, G = 8, 4, 4096, 1e-3, 32, 2, 32
+    H = hq // qpk
+    qt, qval = _queries(1600 + planted, hq, n, synth.BF16, planted=planted)
+    kt, kval = _keys(1601, H, n, synth.BF16, batch=1)
+    qhat_t, _, _ = squat.build_subspace(qt, qpk, r)
+    U_t = squat.prepare(qhat_t, lam, g, full_precision=full_precision)
+    codes_t, scale_t, zero_t = squat.quantize_keys(kt, U_t, bits, G, g)
+    back_t = squat.dequantize_keys(codes_t, scale_t, zero_t, bits, G, torch.float32)
+    torch.cuda.synchronize()
+    codes, scale, zero = _unpack(codes_t, scale_t, zero_t, bits)
+    back = util.out_to_f64(back_t)
+    diff = n_codes = keys_diff = 0
+    e_gpu = e_or = e_rtn = 0.0
+    for h in range(H):
+        Qh, _ = O.subspace(qval[h * qpk:(h + 1) * qpk], r)
+        U = O.update_matrix_lemma(Qh, lam, g)
+        ref = O.quantize_keys(kval[0, h], U, bits, G, g)
+        rtn = O.quantize_keys(kval[0, h], None, bits, G, g)
+        d = ref["codes"] != codes[0, h]
+        diff += int(d.sum())
+        keys_diff += int(d.any(axis=1).sum())
+        n_codes += d.size
+        same = ~d.any(axis=1) & (ref["scale"] == scale[0, h]).all(axis=1) & (ref["zero"] == zero[0, h]).all(axis=1)
+        assert np.abs(back[0, h][same] - ref["xhat"][same]).max() <= 1e-6 * np.abs(ref["xhat"]).max()
+        proj = lambda x: float(np.sum(((x - kval[0, h]) @ Qh.T) ** 2))      # noqa: E731
+        e_gpu += proj(back[0, h])
+        e_or += proj(ref["xhat"])
+        e_rtn += proj(rtn["xhat"])
+    frac = diff / n_codes
+    record_property("codes_differing", frac)
+    record_property("projected_error_energy_gpu_over_oracle", e_gpu / e_or)
+    print("chain vs chain: planted=%d r=%d full_precision=%s codes differing %.3e (keys %.3e), projected error energy "
+          "gpu/oracle %.5f, oracle/rtn %.4f" % (planted, r, full_precision, frac, keys_diff / (H * n), e_gpu / e_or, e_or / e_rtn))
+    assert abs(e_gpu / e_or - 1.0) <= 1e-2
+    assert e_gpu < 0.5 * e_rtn
+    # free-running distance: with U in full precision on well-separated spectra the chains agree to the budget
+    # of the stage-by-stage tests (roots and their cascades); the fp16 grid costs a few 1e-4 of the codes
+    assert frac <= (1e-3 if not (full_precision and planted) else 3e-4), frac

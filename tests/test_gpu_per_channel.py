@@ -261,3 +261,30 @@ def test_per_channel_decode_flush_shape():
     kt, kval = _keys(3000, H, n, synth.BF16, batch=B)
     _, U = _oracle_U(3001, H, 16, 1e-3, 32, fp16_grid=True)
     _check(kt, kval, U, 2, 32)
+
+
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F32])
+@pytest.mark.parametrize("bad", [float("inf"), float("nan")])
+def test_per_channel_non_finite_key_stays_inside_its_token_group(dtype, bad):
+    """The header asks for finite keys: a NaN or Inf spoils the group of 32 tokens it belongs to (in the
+    definition it spoils its own channel and, through the update, every later block of the group; the kernel's
+    exact conversion of 16-bit keys on the matrix cores additionally spoils the other channels of its block).
+    What is pinned here: the damage stays inside that token group -- every other group of the head, and every
+    other head, is bit-identical to a run without the bad value -- and the call completes."""
+    B, H, n = 1, 3, 5 * 32
+    x32 = synth.keys(2950, H, n, batch=B)
+    clean_raw, _ = synth.store(x32, dtype)
+    x32[0, 1, 2 * 32 + 5, 40] = bad                      # head 1, token group 2
+    raw, _ = synth.store(x32, dtype)
+    _, U = _oracle_U(2951, H, 16, 1e-3, 32)
+    Ut = torch.from_numpy(U).cuda()
+    c0, s0, z0 = squat.quantize_keys_per_channel(util.to_device(clean_raw, dtype), Ut, 2, 32, 32)
+    c1, s1, z1 = squat.quantize_keys_per_channel(util.to_device(raw, dtype), Ut, 2, 32, 32)
+    torch.cuda.synchronize()
+    keep = torch.ones((H, n // 32), dtype=torch.bool, device="cuda")
+    keep[1, 2] = False
+    for a, b in ((c0, c1), (s0, s1), (z0, z1)):
+        assert torch.equal(a[0][keep], b[0][keep])
+    # in the spoiled group the channels of EARLIER blocks (0..31) never see the bad value in the definition;
+    # the kernel keeps those too
+    assert torch.equal(c0[0, 1, 2, :32], c1[0, 1, 2, :32]) and torch.equal(s0[0, 1, 2, :32], s1[0, 1, 2, :32])
