@@ -16,6 +16,11 @@ T = d / g iterations, G the quantization group size, b the bit width.
 
 Parity status of each function:
   gram, subspace                pinned (library SVD, planted spectrum, Eckart-Young)
+  gram_update, iteration_start,
+  subspace_iteration            pinned (Gram of the concatenated queries; fixed point at the exact
+                                eigenvectors; converged limit = library eigh; residual and Ritz
+                                values against their definitions; monotone Ritz values; the
+                                convergence rate (lambda_{p+1} / lambda_r)^k on a planted spectrum)
   update_matrix_*               pinned (three routes + brute-force constrained LS,
                                 g=1 against the one-coordinate rule of Prop. 1)
   rtn_group, quantize_keys      pinned (hand-worked fixture, r=0 fixed point,
@@ -42,6 +47,7 @@ import numpy as np
 
 __all__ = [
     "gram", "subspace", "subspace_svd", "deviation_from_subspace",
+    "gram_update", "iteration_start", "subspace_iteration",
     "update_matrix_lemma", "update_matrix_kkt", "update_matrix_lowrank",
     "rtn_group", "quantize_keys", "dequantize_keys",
     "pack_codes", "unpack_codes", "pack_codes_tokens", "unpack_codes_tokens",
@@ -142,6 +148,83 @@ def deviation_from_subspace(q: np.ndarray, basis: np.ndarray) -> np.ndarray:
     Qo, _ = np.linalg.qr(B.T)
     proj = (q @ Qo) @ Qo.T
     return np.linalg.norm(q - proj, axis=-1)
+
+
+# --------------------------------------------------------------------------- #
+# Step 1, cheaper: block power iteration on the Gram matrix, and its refresh
+# (Algorithm 1, the remark on the SVD line: the decomposition "can be
+# accelerated using block power method")
+# --------------------------------------------------------------------------- #
+
+def gram_update(G: np.ndarray, Q_new) -> np.ndarray:
+    """Gram matrix after more queries have arrived: Q^T Q of the old and new rows together is the sum of
+    the two Gram matrices (the same identity that pools the query heads of one KV head)."""
+    return np.asarray(G, dtype=np.float64) + gram(Q_new)
+
+
+def iteration_start(Qhat_prev, d: int = 128, p: int = 32) -> np.ndarray:
+    """Start block X0 (d x p) of the iteration.
+
+    Warm start: the directions of a previous Qhat (its non-zero rows, normalised) come first; the block is
+    completed to p columns with coordinate vectors e_c, c = 0, s, 2 s, ... with s = d // (p - k) for the
+    p - k missing columns (after one multiplication by the Gram matrix these are columns of it, i.e.
+    a range-finder start).  Cold start (Qhat_prev None or empty): all p columns are coordinate vectors,
+    s = d // p.  This is this build's choice (the paper does not spell an initialisation out); both sides
+    of the parity tests use it.
+    """
+    cols = []
+    if Qhat_prev is not None:
+        for row in np.asarray(Qhat_prev, dtype=np.float64):
+            nrm = np.linalg.norm(row)
+            if nrm > 0.0 and len(cols) < p:
+                cols.append(row / nrm)
+    k = len(cols)
+    if k < p:
+        step = d // (p - k)
+        for j in range(p - k):
+            e = np.zeros(d)
+            e[j * step] = 1.0
+            cols.append(e)
+    return np.stack(cols, axis=1)
+
+
+def subspace_iteration(G: np.ndarray, X0: np.ndarray, iterations: int, r: int):
+    """Block power (orthogonal / subspace) iteration on the Gram matrix followed by a Rayleigh-Ritz step.
+
+    X <- orth(X0); `iterations` times X <- orth(G X); then T = X^T G X is diagonalised, T = W diag(theta) W^T,
+    and the Ritz pairs (theta_i, x_i = X w_i) with the r largest theta stand in for the eigenpairs:
+    Qhat[i] = sqrt(theta_i) x_i^T with the sign convention of `subspace`.  The block may be wider than r
+    (oversampling): the iteration then converges like (lambda_{p+1} / lambda_r)^iterations.
+
+    Returns (Qhat (r, d), theta (r,), resid (r,)) with resid_i = ||G x_i - theta_i x_i||_2 / theta_1, the
+    relative residual of each Ritz pair (zero at an exact eigenpair).
+    """
+    G = np.asarray(G, dtype=np.float64)
+    d = G.shape[0]
+    X, _ = np.linalg.qr(np.asarray(X0, dtype=np.float64))
+    for _ in range(iterations):
+        X, _ = np.linalg.qr(G @ X)
+    Y = G @ X
+    T = X.T @ Y
+    T = 0.5 * (T + T.T)
+    theta, W = np.linalg.eigh(T)
+    order = np.argsort(theta)[::-1]
+    theta = theta[order]
+    Xr = X @ W[:, order]
+    Yr = Y @ W[:, order]
+    top = max(theta[0], 0.0)
+    Qhat = np.zeros((r, d))
+    th = np.zeros(r)
+    resid = np.zeros(r)
+    for i in range(min(r, Xr.shape[1])):
+        v = Xr[:, i]
+        resid[i] = np.linalg.norm(Yr[:, i] - theta[i] * v) / top if top > 0 else 0.0
+        j = int(np.argmax(np.abs(v)))
+        if v[j] < 0:
+            v = -v
+        th[i] = max(theta[i], 0.0)
+        Qhat[i] = np.sqrt(th[i]) * v
+    return Qhat, th, resid
 
 
 # --------------------------------------------------------------------------- #

@@ -8,6 +8,7 @@ import pytest
 import scipy.optimize
 
 from oracle import squat_oracle as O
+from paper_2503_24358_amd import synth   # seeded input generators only (no method arithmetic)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -636,3 +637,99 @@ def test_rank_deficient_queries_give_zero_rows():
     Q = gen.standard_normal((3, 16))
     Qh, eig = O.subspace(Q, 6)
     assert np.allclose(Qh[3:], 0, atol=1e-6) and np.all(eig[:3] > 0)
+
+
+# ---------------------------------------------------------------------------
+# Block power iteration on the Gram matrix and its refresh (Algorithm 1, remark on the SVD line)
+# ---------------------------------------------------------------------------
+def _planted_gram(seed, eigs):
+    gen = synth.rng(seed)
+    B, _ = np.linalg.qr(gen.standard_normal((128, 128)))
+    return (B * np.asarray(eigs)) @ B.T, B
+
+
+def test_gram_update_is_the_gram_of_all_queries_seen():
+    gen = synth.rng(5200)
+    old, new = gen.standard_normal((2, 300, 128)), gen.standard_normal((2, 17, 128))
+    G = O.gram_update(O.gram(old), new)
+    both = np.concatenate([old.reshape(-1, 128), new.reshape(-1, 128)])
+    assert np.allclose(G, both.T @ both, rtol=1e-12, atol=1e-9)
+
+
+def test_iteration_start_layout():
+    X0 = O.iteration_start(None)
+    assert X0.shape == (128, 32)
+    assert all(X0[4 * j, j] == 1.0 and np.count_nonzero(X0[:, j]) == 1 for j in range(32))
+    gen = synth.rng(5201)
+    prev = gen.standard_normal((12, 128)) * 7
+    prev[5] = 0.0                                                 # a zero row (r > rank) is dropped
+    X0 = O.iteration_start(prev)
+    assert np.allclose(X0[:, 0], prev[0] / np.linalg.norm(prev[0])) and np.allclose(X0[:, 5], prev[6] / np.linalg.norm(prev[6]))
+    step = 128 // (32 - 11)
+    assert all(X0[j * step, 11 + j] == 1.0 and np.count_nonzero(X0[:, 11 + j]) == 1 for j in range(21))
+
+
+def test_subspace_iteration_fixed_point_and_residual_definition():
+    eigs = np.concatenate([np.linspace(900, 300, 32), np.linspace(40, 1, 96)])
+    G, B = _planted_gram(5202, eigs)
+    Qh, th, resid = O.subspace_iteration(G, B[:, :32], 0, 16)     # exact invariant subspace: Ritz pairs are eigenpairs
+    assert np.allclose(th, eigs[:16], rtol=1e-12) and resid.max() <= 1e-13
+    for i in range(16):
+        v = Qh[i] / np.sqrt(th[i])
+        assert abs(abs(v @ B[:, i]) - 1.0) <= 1e-10 and v[np.argmax(np.abs(v))] > 0
+    # a rotated basis of the same subspace gives the same result (Rayleigh-Ritz undoes the rotation)
+    R, _ = np.linalg.qr(synth.rng(5203).standard_normal((32, 32)))
+    Qh2, th2, _ = O.subspace_iteration(G, B[:, :32] @ R, 0, 16)
+    assert np.allclose(th2, th, rtol=1e-10) and np.allclose(Qh2.T @ Qh2, Qh.T @ Qh, atol=1e-8 * th[0])
+    # the residual is what it says, on a block that is NOT invariant
+    X0 = O.iteration_start(None)
+    Qh3, th3, resid3 = O.subspace_iteration(G, X0, 1, 8)
+    for i in range(8):
+        v = Qh3[i] / np.sqrt(th3[i])
+        assert np.isclose(np.linalg.norm(G @ v - th3[i] * v) / th3[0], resid3[i], rtol=1e-9)
+        assert np.isclose(v @ G @ v, th3[i], rtol=1e-12)          # Ritz value = Rayleigh quotient
+
+
+def test_subspace_iteration_converges_to_the_library_decomposition_at_the_textbook_rate():
+    # lambda_33 / lambda_16 = 0.1: the error of the 16 leading Ritz values shrinks like 0.1^(2 k)
+    eigs = np.concatenate([np.linspace(1000, 500, 16), np.linspace(400, 100, 16), np.linspace(50, 1, 96)])
+    G, B = _planted_gram(5204, eigs)
+    X0 = O.iteration_start(None)
+    errs = []
+    prev = np.zeros(16)
+    for k in range(0, 7):
+        Qh, th, resid = O.subspace_iteration(G, X0, k, 16)
+        assert np.all(th >= prev - 1e-9 * eigs[0])                # Ritz values grow monotonically towards the eigenvalues
+        prev = th
+        errs.append(np.abs(th - eigs[:16]).max() / eigs[0])
+    assert errs[6] <= 1e-9 and errs[3] <= 1e-3
+    assert all(errs[k + 1] <= 0.05 * errs[k] + 1e-13 for k in range(1, 5))
+    Qh, th, resid = O.subspace_iteration(G, X0, 12, 16)
+    w, V = np.linalg.eigh(G)
+    Vr = V[:, ::-1][:, :16]
+    assert np.linalg.norm(Qh.T @ Qh - (Vr * w[::-1][:16]) @ Vr.T) <= 1e-9 * w[-1] and resid.max() <= 1e-9
+    # and equals `subspace` on actual queries once converged (well-separated planted directions)
+    q = synth.queries(5205, 2, 600, planted_rank=12).astype(np.float64)
+    ref, ev = O.subspace(q, 8)
+    Qh, th, resid = O.subspace_iteration(O.gram(q), O.iteration_start(None), 40, 8)
+    assert np.allclose(th, ev, rtol=1e-8) and np.linalg.norm(Qh.T @ Qh - ref.T @ ref) <= 1e-6 * ev[0]
+
+
+def test_warm_started_refresh_is_worth_several_iterations():
+    """The use the refresh is for: the Gram matrix grows by a few new queries and the previous Qhat starts the
+    iteration.  Both starts contract at the same rate (lambda_33 / lambda_r per multiplication, squared in
+    the Ritz values); the warm start begins more than an order of magnitude closer."""
+    q_old = synth.queries(5206, 4, 2048, planted_rank=12).astype(np.float64)
+    gen = synth.rng(5207)
+    q_new = q_old[:, gen.integers(0, 2048, size=64)] + 0.3 * gen.standard_normal((4, 64, 128))
+    r = 8
+    prev, _ = O.subspace(q_old, r)
+    G = O.gram_update(O.gram(q_old), q_new)
+    exact, ev = O.subspace(np.concatenate([q_old, q_new], axis=1), r)
+    err = lambda Qh: np.linalg.norm(Qh.T @ Qh - exact.T @ exact) / np.linalg.norm(exact.T @ exact)      # noqa: E731
+    ks = (0, 1, 2, 3, 5, 8)
+    warm = [err(O.subspace_iteration(G, O.iteration_start(prev), k, r)[0]) for k in ks]
+    cold = [err(O.subspace_iteration(G, O.iteration_start(None), k, r)[0]) for k in ks]
+    assert all(w <= c / 10 for w, c in zip(warm, cold))
+    assert all(b < a for a, b in zip(warm, warm[1:])) and all(b < a for a, b in zip(cold, cold[1:]))
+    assert warm[-1] <= 1e-5 and warm[3] <= 3e-3 and cold[3] >= 1e-2
