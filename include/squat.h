@@ -109,6 +109,50 @@ int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int 
                          void* ws, size_t ws_bytes, squat_stream stream);
 
 /* ------------------------------------------------------------------------- *
+ * squat_refresh_subspace  (Algorithm 1, prefill phase, the remark on the SVD
+ * line: the decomposition "can be accelerated using block power method";
+ * Section 3.2 for what Qhat is; GQA pooling as for squat_build_subspace).
+ *
+ * The cheaper, approximate route to Qhat, and the way to keep Qhat current
+ * while queries keep arriving.  The caller owns a running Gram matrix per KV
+ * head (`gram_state`, fp64); the call
+ *   1. adds the pooled Gram matrix of `q_new` to it (accumulate != 0) or
+ *      overwrites it with that matrix (accumulate == 0); n_new == 0 with
+ *      accumulate != 0 leaves it as it is;
+ *   2. iterations >= 0: runs that many steps X <- orth(G X) of block power
+ *      iteration on a block of 32 vectors, started from the non-zero rows of
+ *      `qhat_prev` (normalised) completed with coordinate vectors e_c,
+ *      c = 0, s, 2 s, ... (s = d / number of missing columns), and takes the
+ *      Ritz pairs (theta_i, x_i) of the final block (Rayleigh-Ritz):
+ *          qhat[j, i, :] = sqrt(theta_i) x_i,  i = 0..r-1, descending theta,
+ *      sign convention as squat_build_subspace.  The iteration converges like
+ *      (eig_33 / eig_r)^iterations: fast for queries that concentrate in a
+ *      low-dimensional subspace and for warm starts, not at all for a flat
+ *      spectrum; `residual` reports how far it got.  A head whose block turns
+ *      out rank-deficient is redone by the exact solver (residual 0).
+ *      iterations < 0: the exact solver of squat_build_subspace on the state.
+ *
+ *   q_new    [n_kv_heads*q_per_kv, n_new, d] as `q` of squat_build_subspace
+ *            (same alignment rules); may be NULL if n_new == 0.
+ *   gram_state  in/out [n_kv_heads, d, d] double, dense, 16-byte aligned.
+ *   r        0 <= r <= 32 for iterations >= 0 (r <= d otherwise).
+ *   qhat_prev   [n_kv_heads, r_prev, d] float or NULL (cold start); r_prev <= 32;
+ *            may be the same buffer as qhat when r_prev == r.
+ *   qhat, eig   as for squat_build_subspace (eig = Ritz values).
+ *   residual out [n_kv_heads] float or NULL: max over the r pairs of
+ *            ||G x_i - theta_i x_i||_2 / theta_1.
+ *   ws       scratch of at least squat_refresh_subspace_workspace(...) bytes,
+ *            256-byte aligned.
+ * ------------------------------------------------------------------------- */
+size_t squat_refresh_subspace_workspace(int64_t n_new, int n_kv_heads, int q_per_kv, int d, int r);
+
+int squat_refresh_subspace(const void* q_new, squat_dtype q_dt, int64_t n_new, int n_kv_heads, int q_per_kv,
+                           int d, int64_t q_stride_head, int64_t q_stride_token, int accumulate,
+                           double* gram_state, int r, int iterations, const float* qhat_prev, int r_prev,
+                           float* qhat, float* eig, float* residual, void* ws, size_t ws_bytes,
+                           squat_stream stream);
+
+/* ------------------------------------------------------------------------- *
  * squat_prepare  (Lemma 2: the block update B_t H_t; Lemma 3 and its Remark:
  * the A_t^{-1} chain; Prop. 1 is the g = 1 case).
  *

@@ -22,6 +22,7 @@
 #include "squat_internal.h"
 #include "squat_jacobi.h"
 #include "squat_tridiag.h"
+#include "squat_subiter.h"
 
 using namespace squat;
 
@@ -291,8 +292,9 @@ constexpr size_t kRedLdsBytes = static_cast<size_t>(kD) * kRedLd * sizeof(double
 
 // The tile layout is scattered over the matrix, so the sums are placed (both triangles) in an LDS copy of the
 // matrix first and written out row by row.
+// accumulate != 0: the sums are added to what g64 holds (more queries of the same heads have arrived).
 __global__ void __launch_bounds__(kRedThreads) gram_reduce(const float* partial, int wgs_per_head,
-                                                           double* g64, float* gram_out) {
+                                                           double* g64, float* gram_out, int accumulate) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     double* L = reinterpret_cast<double*>(smem);
     const int kvh = blockIdx.x;
@@ -323,7 +325,8 @@ __global__ void __launch_bounds__(kRedThreads) gram_reduce(const float* partial,
     }
     __syncthreads();
     for (int idx = threadIdx.x; idx < kD * kD; idx += kRedThreads) {
-        const double v = L[(idx >> 7) * kRedLd + (idx & (kD - 1))];
+        double v = L[(idx >> 7) * kRedLd + (idx & (kD - 1))];
+        if (accumulate) v += g[idx];
         g[idx] = v;
         if (go) go[idx] = static_cast<float>(v);
     }
@@ -340,6 +343,27 @@ __global__ void __launch_bounds__(kTriThreads) eig_tridiag_kernel(const double* 
     const bool ok = tridiag_top_eigs(g64 + kvh * kD * kD, vws + kvh * kD * kD, r, qhat + kvh * r * kD,
                                      eig ? eig + kvh * r : nullptr, reinterpret_cast<double*>(smem));
     if (threadIdx.x == 0) need[kvh] = ok ? 0 : 1;
+}
+
+// Block power iteration + Rayleigh-Ritz (squat_subiter.h), one workgroup per KV head; need[head] = 1 asks the
+// exact solver to redo a head whose block broke down.
+__global__ void __launch_bounds__(kItThreads) subspace_iter_kernel(const double* g64, const float* prev, int r_prev,
+                                                                   int r, int iterations, float* qhat, float* eig,
+                                                                   float* resid, int* need) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int64_t kvh = blockIdx.x;
+    const bool ok = subspace_iterate(g64 + kvh * kD * kD, prev ? prev + kvh * r_prev * kD : nullptr, r_prev, r,
+                                     iterations, qhat + kvh * r * kD, eig ? eig + kvh * r : nullptr,
+                                     resid ? resid + kvh : nullptr, reinterpret_cast<double*>(smem));
+    if (threadIdx.x == 0) {
+        need[kvh] = ok ? 0 : 1;
+        if (!ok && resid) resid[kvh] = 0.0f;        // the exact solver takes this head
+    }
+}
+
+__global__ void __launch_bounds__(256) fill_float(float* p, int n, float v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
 }
 
 // need: NULL = every head; else only the heads with need[head] != 0
@@ -439,25 +463,44 @@ extern "C" size_t squat_build_subspace_workspace(int64_t n_tokens, int n_kv_head
     return plan(n_tokens, n_kv_heads, q_per_kv, kPlanCUs).total;
 }
 
-extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads,
-                                    int q_per_kv, int d, int64_t q_stride_head, int64_t q_stride_token,
-                                    int r, float* qhat, float* eig, float* gram, void* ws, size_t ws_bytes,
-                                    squat_stream stream) {
-    if (d != kD) return SQUAT_E_BADSHAPE;
-    if (n_tokens < 1 || n_kv_heads < 0 || q_per_kv < 1 || r < 0 || r > d) return SQUAT_E_BADSHAPE;
+namespace {
+
+constexpr size_t kEigLdsBytes = kD * kEigLd * sizeof(double) + kD * sizeof(double) + kD * sizeof(int) + 16;
+constexpr size_t kGramLdsBytes = 2 * kPartialFloats * sizeof(float);      // 80 KB
+
+int raise_lds_limits() {
+    // one flag per kernel: a failed call is retried by the next launch, a raced one only repeated
+    static std::atomic<uint64_t> done[7];
+    const struct { const void* kernel; size_t bytes; } limits[7] = {
+        {reinterpret_cast<const void*>(gram_partial_16<SQUAT_BF16>), kGramLdsBytes},
+        {reinterpret_cast<const void*>(gram_partial_16<SQUAT_F16>), kGramLdsBytes},
+        {reinterpret_cast<const void*>(gram_partial_f32), kGramLdsBytes},
+        {reinterpret_cast<const void*>(eig_kernel), kEigLdsBytes},
+        {reinterpret_cast<const void*>(eig_tridiag_kernel), static_cast<size_t>(kTriLdsBytes)},
+        {reinterpret_cast<const void*>(gram_reduce), static_cast<size_t>(kRedLdsBytes)},
+        {reinterpret_cast<const void*>(subspace_iter_kernel), static_cast<size_t>(kItLdsBytes)}};
+    for (int i = 0; i < 7; ++i)
+        if (int rc = set_max_lds_once(done[i], limits[i].kernel, static_cast<int>(limits[i].bytes))) return rc;
+    return SQUAT_OK;
+}
+
+int check_queries(const void* q, squat_dtype q_dt, int n_kv_heads, int q_per_kv, int d, int64_t q_stride_head,
+                  int64_t q_stride_token) {
     if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
-    if (n_kv_heads == 0) return SQUAT_OK;
-    if (!q || (r > 0 && !qhat)) return SQUAT_E_NULLPTR;
+    if (!q) return SQUAT_E_NULLPTR;
     if (q_stride_token < d || q_stride_head < 0) return SQUAT_E_BADSHAPE;
     if ((q_stride_token % 8) || (q_stride_head % 8) || !aligned(q, 16)) return SQUAT_E_ALIGN;
     if (static_cast<int64_t>(n_kv_heads) * q_per_kv > (int64_t(1) << 24)) return SQUAT_E_BADSHAPE;
     // a chunk's 16 rows are addressed by 32-bit byte offsets from its first row
     if (q_stride_token * elem_size(q_dt) >= (int64_t(1) << 27)) return SQUAT_E_BADSHAPE;
-    const SubspacePlan pl = plan(n_tokens, n_kv_heads, q_per_kv, kPlanCUs);
-    if (!ws || ws_bytes < pl.total) return SQUAT_E_WORKSPACE;
-    if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
+    return SQUAT_OK;
+}
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
+// Pooled Gram matrices of the queries into g64 (fp64 [n_kv_heads, d, d]; added to it if accumulate), optionally
+// also as fp32 into gram_out.
+int run_gram(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads, int q_per_kv, int64_t q_stride_head,
+             int64_t q_stride_token, const SubspacePlan& pl, void* ws, double* g64, float* gram_out, int accumulate,
+             hipStream_t s) {
     const int es = elem_size(q_dt);
     GramParams p;
     p.q = static_cast<const unsigned char*>(q);
@@ -469,47 +512,114 @@ extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_t
     p.chunks_per_qhead = (n_tokens + 15) / 16;
     p.units_per_head = p.chunks_per_qhead * q_per_kv;
     p.partial = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + pl.off_partial);
-    double* g64 = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_g64);
-
-    const size_t red_lds = 2 * kPartialFloats * sizeof(float);      // 80 KB
     const dim3 grid(static_cast<unsigned>(n_kv_heads) * pl.wgs_per_head);
-    const size_t eig_lds = kD * kEigLd * sizeof(double) + kD * sizeof(double) + kD * sizeof(int) + 16;
-    {
-        // one flag per kernel: a failed call is retried by the next launch, a raced one only repeated
-        static std::atomic<uint64_t> done[6];
-        const struct { const void* kernel; size_t bytes; } limits[6] = {
-            {reinterpret_cast<const void*>(gram_partial_16<SQUAT_BF16>), red_lds},
-            {reinterpret_cast<const void*>(gram_partial_16<SQUAT_F16>), red_lds},
-            {reinterpret_cast<const void*>(gram_partial_f32), red_lds},
-            {reinterpret_cast<const void*>(eig_kernel), eig_lds},
-            {reinterpret_cast<const void*>(eig_tridiag_kernel), static_cast<size_t>(kTriLdsBytes)},
-            {reinterpret_cast<const void*>(gram_reduce), static_cast<size_t>(kRedLdsBytes)}};
-        for (int i = 0; i < 6; ++i)
-            if (int rc = set_max_lds_once(done[i], limits[i].kernel, static_cast<int>(limits[i].bytes))) return rc;
-    }
     switch (q_dt) {
-        case SQUAT_BF16: hipLaunchKernelGGL(gram_partial_16<SQUAT_BF16>, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;
-        case SQUAT_F16: hipLaunchKernelGGL(gram_partial_16<SQUAT_F16>, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;
-        default: hipLaunchKernelGGL(gram_partial_f32, grid, dim3(kGramWaves * kWave), red_lds, s, p); break;
+        case SQUAT_BF16: hipLaunchKernelGGL(gram_partial_16<SQUAT_BF16>, grid, dim3(kGramWaves * kWave), kGramLdsBytes, s, p); break;
+        case SQUAT_F16: hipLaunchKernelGGL(gram_partial_16<SQUAT_F16>, grid, dim3(kGramWaves * kWave), kGramLdsBytes, s, p); break;
+        default: hipLaunchKernelGGL(gram_partial_f32, grid, dim3(kGramWaves * kWave), kGramLdsBytes, s, p); break;
     }
     int rc = check_launch();
     if (rc) return rc;
-    hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(kRedThreads), kRedLdsBytes, s, p.partial, pl.wgs_per_head, g64, gram);
-    rc = check_launch();
-    if (rc) return rc;
-    if (r > 0) {
-        int* need = nullptr;
-        if (r <= kTriMaxR) {
-            need = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) + pl.off_need);
-            double* vws = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_v);
-            hipLaunchKernelGGL(eig_tridiag_kernel, dim3(n_kv_heads), dim3(kTriThreads), kTriLdsBytes, s, g64, vws, r, qhat,
-                               eig, need);
+    hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(kRedThreads), kRedLdsBytes, s, p.partial, pl.wgs_per_head, g64,
+                       gram_out, accumulate);
+    return check_launch();
+}
+
+// Exact top-r eigenpairs of the Gram matrices in g64: tridiagonal route (r <= 32), Jacobi for larger r and for
+// the heads that route flags.
+int run_exact_solver(const double* g64, int n_kv_heads, int r, float* qhat, float* eig, const SubspacePlan& pl, void* ws,
+                     hipStream_t s) {
+    int rc = SQUAT_OK;
+    int* need = nullptr;
+    if (r <= kTriMaxR) {
+        need = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) + pl.off_need);
+        double* vws = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_v);
+        hipLaunchKernelGGL(eig_tridiag_kernel, dim3(n_kv_heads), dim3(kTriThreads), kTriLdsBytes, s, g64, vws, r, qhat,
+                           eig, need);
+        rc = check_launch();
+        if (rc) return rc;
+    }
+    hipLaunchKernelGGL(eig_kernel, dim3(n_kv_heads), dim3(kEigThreads), kEigLdsBytes, s, g64, r, qhat, eig,
+                       static_cast<int*>(nullptr), static_cast<const int*>(need));
+    return check_launch();
+}
+
+}  // namespace
+
+extern "C" int squat_build_subspace(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads,
+                                    int q_per_kv, int d, int64_t q_stride_head, int64_t q_stride_token,
+                                    int r, float* qhat, float* eig, float* gram, void* ws, size_t ws_bytes,
+                                    squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (n_tokens < 1 || n_kv_heads < 0 || q_per_kv < 1 || r < 0 || r > d) return SQUAT_E_BADSHAPE;
+    if (q_dt != SQUAT_F32 && q_dt != SQUAT_F16 && q_dt != SQUAT_BF16) return SQUAT_E_BADDTYPE;
+    if (n_kv_heads == 0) return SQUAT_OK;
+    if (!q || (r > 0 && !qhat)) return SQUAT_E_NULLPTR;
+    if (int rc = check_queries(q, q_dt, n_kv_heads, q_per_kv, d, q_stride_head, q_stride_token)) return rc;
+    const SubspacePlan pl = plan(n_tokens, n_kv_heads, q_per_kv, kPlanCUs);
+    if (!ws || ws_bytes < pl.total) return SQUAT_E_WORKSPACE;
+    if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
+    if (int rc = raise_lds_limits()) return rc;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double* g64 = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_g64);
+    int rc = run_gram(q, q_dt, n_tokens, n_kv_heads, q_per_kv, q_stride_head, q_stride_token, pl, ws, g64, gram, 0, s);
+    if (rc || r == 0) return rc;
+    return run_exact_solver(g64, n_kv_heads, r, qhat, eig, pl, ws, s);
+}
+
+extern "C" size_t squat_refresh_subspace_workspace(int64_t n_new, int n_kv_heads, int q_per_kv, int d, int r) {
+    (void)r;
+    if (d != kD || n_new < 0 || n_kv_heads < 1 || q_per_kv < 1) return 0;
+    // as squat_build_subspace (the slot of its own fp64 Gram matrix stays unused: the state is the caller's)
+    return plan(n_new < 1 ? 1 : n_new, n_kv_heads, q_per_kv, kPlanCUs).total;
+}
+
+extern "C" int squat_refresh_subspace(const void* q_new, squat_dtype q_dt, int64_t n_new, int n_kv_heads, int q_per_kv,
+                                      int d, int64_t q_stride_head, int64_t q_stride_token, int accumulate,
+                                      double* gram_state, int r, int iterations, const float* qhat_prev, int r_prev,
+                                      float* qhat, float* eig, float* residual, void* ws, size_t ws_bytes,
+                                      squat_stream stream) {
+    if (d != kD) return SQUAT_E_BADSHAPE;
+    if (n_new < 0 || n_kv_heads < 0 || q_per_kv < 1 || r < 0 || r > d || r_prev < 0 || r_prev > kItP)
+        return SQUAT_E_BADSHAPE;
+    if (iterations >= 0 && r > kItP) return SQUAT_E_BADSHAPE;         // the iteration's block is 32 wide
+    if (iterations > 1000) return SQUAT_E_BADSHAPE;
+    if (n_new == 0 && !accumulate) return SQUAT_E_BADSHAPE;            // nothing to build the state from
+    if (n_kv_heads == 0) return SQUAT_OK;
+    if (!gram_state || (r > 0 && !qhat)) return SQUAT_E_NULLPTR;
+    if (!aligned(gram_state, 16)) return SQUAT_E_ALIGN;
+    if (n_new > 0)
+        if (int rc = check_queries(q_new, q_dt, n_kv_heads, q_per_kv, d, q_stride_head, q_stride_token)) return rc;
+    const SubspacePlan pl = plan(n_new < 1 ? 1 : n_new, n_kv_heads, q_per_kv, kPlanCUs);
+    if (!ws || ws_bytes < pl.total) return SQUAT_E_WORKSPACE;
+    if (!aligned(ws, 256)) return SQUAT_E_ALIGN;
+    if (int rc = raise_lds_limits()) return rc;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = SQUAT_OK;
+    if (n_new > 0) {
+        rc = run_gram(q_new, q_dt, n_new, n_kv_heads, q_per_kv, q_stride_head, q_stride_token, pl, ws, gram_state,
+                      nullptr, accumulate ? 1 : 0, s);
+        if (rc) return rc;
+    }
+    if (r == 0) return rc;
+    if (iterations < 0) {
+        if (residual) {
+            hipLaunchKernelGGL(fill_float, dim3((n_kv_heads + 255) / 256), dim3(256), 0, s, residual, n_kv_heads, 0.0f);
             rc = check_launch();
             if (rc) return rc;
         }
-        hipLaunchKernelGGL(eig_kernel, dim3(n_kv_heads), dim3(kEigThreads), eig_lds, s, g64, r, qhat, eig,
-                           static_cast<int*>(nullptr), static_cast<const int*>(need));
-        rc = check_launch();
+        return run_exact_solver(gram_state, n_kv_heads, r, qhat, eig, pl, ws, s);
     }
-    return rc;
+    int* need = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) + pl.off_need);
+    hipLaunchKernelGGL(subspace_iter_kernel, dim3(n_kv_heads), dim3(kItThreads), kItLdsBytes, s, gram_state,
+                       (qhat_prev && r_prev > 0) ? qhat_prev : static_cast<const float*>(nullptr), r_prev, r, iterations,
+                       qhat, eig, residual, need);
+    rc = check_launch();
+    if (rc) return rc;
+    // heads whose block broke down (rank-deficient Gram matrix or start block): exact solver, exits at once otherwise
+    hipLaunchKernelGGL(eig_kernel, dim3(n_kv_heads), dim3(kEigThreads), kEigLdsBytes, s, gram_state, r, qhat, eig,
+                       static_cast<int*>(nullptr), static_cast<const int*>(need));
+    return check_launch();
 }

@@ -18,7 +18,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsquat.s
 _lib = None
 
 SYMBOLS = ("squat_version", "squat_strerror", "squat_build_subspace_workspace",
-           "squat_build_subspace", "squat_prepare_workspace", "squat_prepare", "squat_prepare_ex", "squat_prepare_noalloc",
+           "squat_build_subspace", "squat_refresh_subspace_workspace", "squat_refresh_subspace",
+           "squat_prepare_workspace", "squat_prepare", "squat_prepare_ex", "squat_prepare_noalloc",
            "squat_quantize_keys", "squat_quantize_keys_plan", "squat_dequantize_keys",
            "squat_quantize_keys_per_channel", "squat_dequantize_keys_per_channel", "squat_key_scores", "squat_key_scores_per_channel", "squat_key_scores_rope",
            "squat_key_scores_rope_per_channel",
@@ -76,6 +77,11 @@ def lib() -> ctypes.CDLL:
     L.squat_build_subspace_workspace.argtypes = [i64, i32, i32, i32, i32]
     L.squat_build_subspace.restype = i32
     L.squat_build_subspace.argtypes = [vp, i32, i64, i32, i32, i32, i64, i64, i32, vp, vp, vp, vp, sz, vp]
+    L.squat_refresh_subspace_workspace.restype = sz
+    L.squat_refresh_subspace_workspace.argtypes = [i64, i32, i32, i32, i32]
+    L.squat_refresh_subspace.restype = i32
+    L.squat_refresh_subspace.argtypes = [vp, i32, i64, i32, i32, i32, i64, i64, i32, vp, i32, i32, vp, i32, vp, vp, vp,
+                                         vp, sz, vp]
     L.squat_prepare_workspace.restype = sz
     L.squat_prepare_workspace.argtypes = [i32, i32, i32, i32]
     L.squat_prepare.restype = i32
@@ -188,6 +194,44 @@ def build_subspace(q: torch.Tensor, q_per_kv: int, r: int, *, want_eig: bool = T
     if rc:
         raise SquatError(rc, "squat_build_subspace")
     return qhat, eig, gram
+
+
+def refresh_subspace(gram_state: torch.Tensor, q_per_kv: int, r: int, iterations: int, *, q_new=None,
+                     accumulate: bool = True, qhat_prev=None, qhat=None, eig=None, residual=None, ws=None, stream=None):
+    """squat_refresh_subspace.  gram_state: float64 [n_kv_heads, d, d] (updated in place); q_new:
+    [n_kv_heads*q_per_kv, n_new, d] or None; qhat_prev: float32 [n_kv_heads, r_prev, d] or None (cold start).
+    Returns (qhat [n_kv, r, d] f32, eig [n_kv, r] f32, residual [n_kv] f32)."""
+    _need_cuda(gram_state, q_new, qhat_prev)
+    n_kv, d, _ = gram_state.shape
+    if gram_state.dtype != torch.float64 or not gram_state.is_contiguous():
+        raise ValueError("gram_state must be dense float64 [n_kv_heads, d, d]")
+    dev = gram_state.device
+    n_new, sh, st, dt = 0, 0, 0, BF16
+    if q_new is not None:
+        hq, n_new, _ = q_new.shape
+        if q_new.stride(2) != 1 or hq != n_kv * q_per_kv:
+            raise ValueError("q_new must be [n_kv_heads*q_per_kv, tokens, d] with unit channel stride")
+        sh, st, dt = q_new.stride(0), q_new.stride(1), _DT[q_new.dtype]
+    r_prev = 0
+    if qhat_prev is not None:
+        if qhat_prev.dtype != torch.float32 or not qhat_prev.is_contiguous() or qhat_prev.shape[0] != n_kv:
+            raise ValueError("qhat_prev must be dense float32 [n_kv_heads, r_prev, d]")
+        r_prev = qhat_prev.shape[1]
+    if qhat is None:
+        qhat = torch.empty((n_kv, r, d), dtype=torch.float32, device=dev)
+    if eig is None:
+        eig = torch.empty((n_kv, r), dtype=torch.float32, device=dev)
+    if residual is None:
+        residual = torch.empty((n_kv,), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = _ws(lib().squat_refresh_subspace_workspace(n_new, n_kv, q_per_kv, d, r), dev)
+    rc = lib().squat_refresh_subspace(_ptr(q_new) if n_new else None, dt, n_new, n_kv, q_per_kv, d, sh, st,
+                                      int(bool(accumulate)), _ptr(gram_state), r, int(iterations),
+                                      _ptr(qhat_prev) if r_prev else None, r_prev, _ptr(qhat) if r > 0 else None,
+                                      _ptr(eig), _ptr(residual), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise SquatError(rc, "squat_refresh_subspace")
+    return qhat, eig, residual
 
 
 def prepare_workspace(n_heads: int, d: int, r: int, g: int) -> int:

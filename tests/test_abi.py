@@ -295,3 +295,29 @@ def test_quantize_plan_follows_the_documented_rule():
     assert L.squat_quantize_keys_plan(2, 1, 8, 1024, 1, 0, 2, 64, 32, 1, ref) == -2      # per-channel groups are 32 tokens
     assert L.squat_quantize_keys_plan(9, 1, 8, 1024, 1, 0, 2, 32, 32, 0, ref) == -3
     assert L.squat_quantize_keys_plan(2, 1, 8, 1024, 1, 0, 2, 32, 32, 0, None) == -1
+
+
+def test_refresh_subspace_argument_validation_happens_before_any_launch():
+    L = squat.lib()
+    fake = ctypes.c_void_p(0x1000)
+    rf = lambda **kw: L.squat_refresh_subspace(  # noqa: E731
+        kw.get("q", fake), kw.get("dt", 2), kw.get("n", 64), kw.get("h", 2), kw.get("qpk", 1), kw.get("d", 128),
+        8192, kw.get("st", 128), kw.get("acc", 1), kw.get("state", fake), kw.get("r", 8), kw.get("it", 2),
+        kw.get("prev", None), kw.get("rp", 0), kw.get("qhat", fake), None, None, kw.get("ws", fake),
+        kw.get("wsb", 1 << 30), None)
+    assert rf(d=64) == -2
+    assert rf(r=33) == -2              # the iteration's block is 32 wide ...
+    assert rf(r=33, it=-1, ws=None) == -5   # ... the exact mode takes any r (and fails later, on the missing workspace)
+    assert rf(rp=33) == -2
+    assert rf(n=-1) == -2
+    assert rf(n=0, acc=0) == -2        # no queries and nothing to accumulate onto
+    assert rf(state=None) == -1
+    assert rf(qhat=None) == -1
+    assert rf(q=None) == -1
+    assert rf(dt=9) == -3
+    assert rf(st=130) == -4
+    assert rf(ws=None) == -5
+    assert rf(wsb=16) == -5
+    assert rf(h=0) == 0
+    assert squat.lib().squat_refresh_subspace_workspace(64, 8, 4, 128, 16) >= 2 * 8 * 128 * 128 * 8
+    assert squat.lib().squat_refresh_subspace_workspace(64, 8, 4, 96, 16) == 0
