@@ -5,12 +5,20 @@ One step = one pass of the whole path over the long-context workload (32 layers 
 stacked along the head axis, 32768 tokens per layer, d = 128, bf16, r = 32, 2-bit, group 32):
   squat_build_subspace -> squat_prepare -> squat_quantize_keys -> squat_dequantize_keys.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Beside the headline step the default run also times, each in a bounded number of launches: the four
+(bits, group) variants of the long-context configuration, the two storage forms of the update matrix, the
+kernels under sustained back-to-back load, the per-channel grouping, the logits kernels, the decode-time
+flush, the layer-by-layer schedule with its per-stage split, and the routes to the query subspace.
+`--brief` keeps only the headline step (for profiler runs).
 """
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -19,13 +27,29 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
-MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_16BIT_PEAK_TFLOPS = 2500.0
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9      # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (packed fp32 is off in this build)
+
+
+def profile_facts() -> dict:
+    """Figures that only a profiler run can give (HBM traffic, instruction counts) are read from the tracked
+    summaries under profiles/: lines of the form `@bench <name> <number>`.  Nothing is hard-coded here, so a
+    summary that is missing or was made for another workload simply leaves the figure out."""
+    facts = {}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        try:
+            for line in open(path):
+                m = re.match(r"@bench\s+(\S+)\s+([-+0-9.eE]+)\s*$", line)
+                if m:
+                    facts[m.group(1)] = (float(m.group(2)), os.path.basename(path))
+        except OSError:
+            pass
+    return facts
 
 
 def cpu_baseline(wl_args: dict, heads: int = 4, repeats: int = 8):
     """The float64 oracle, as it stands, on a bounded sample of the same workload: `heads` KV heads
     (pooled queries of 4 query heads each, all their tokens)."""
-    import numpy as np
     from oracle import squat_oracle as O
     from paper_2503_24358_amd import synth
     try:
@@ -37,14 +61,6 @@ def cpu_baseline(wl_args: dict, heads: int = 4, repeats: int = 8):
     qpk = wl_args["q_per_kv"]
     _, qval = synth.store(synth.queries(77, heads * qpk, n), synth.BF16)
     _, kval = synth.store(synth.keys(78, heads, n), synth.BF16)
-    t0 = time.perf_counter()
-    for _ in range(repeats):
-        for h in range(heads):
-            Qh, _ = O.subspace(qval[h * qpk:(h + 1) * qpk], r)
-            U = O.update_matrix_lemma(Qh, lam, g)
-            out = O.quantize_keys(kval[h], U, bits, G, g)
-            O.dequantize_keys(out["codes"], out["scale"], out["zero"], G)
-    dt = time.perf_counter() - t0
 
     def one_pass():
         for h in range(heads):
@@ -53,6 +69,10 @@ def cpu_baseline(wl_args: dict, heads: int = 4, repeats: int = 8):
             out = O.quantize_keys(kval[h], U, bits, G, g)
             O.dequantize_keys(out["codes"], out["scale"], out["zero"], G)
 
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        one_pass()
+    dt = time.perf_counter() - t0
     single = None
     try:                                            # the same oracle with the BLAS / OpenMP pools held to one thread
         from threadpoolctl import threadpool_limits
@@ -82,20 +102,17 @@ def main():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--variants", action="store_true",
-                    help="also time the quantize and dequantize kernels for the other bit widths / group sizes "
-                         "of the long-context configuration (adds a \"variants\" list to the JSON line)")
+    ap.add_argument("--brief", action="store_true", help="headline step only (profiler runs)")
     ap.add_argument("--decode", action="store_true",
-                    help="also time the decode-time flush shape (64 sequences, 32 buffered tokens per head): one "
-                         "layer (8 heads) per launch and all 32 layers (256 heads) per launch (adds \"decode_flush\")")
-    ap.add_argument("--per-layer", action="store_true",
-                    help="also run the whole path with one launch per stage and LAYER (8 KV heads per launch instead of "
-                         "all 256 stacked), launched eagerly and replayed from a HIP graph (adds \"per_layer\")")
+                    help="also run the cache object's append + logits loop at the decode shape (64 sequences x 256 "
+                         "heads x 2048 tokens) and the logits kernel alone at that shape")
     ap.add_argument("--with-copy", action="store_true",
                     help="profiling aid: also run one plain device copy of the key tensor (known size) per step, "
                          "to calibrate the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--only", default="", help="profiling aid: time only this stage (e.g. quantize_keys); "
                                                "the other stages run once, untimed, to prepare its inputs")
+    ap.add_argument("--extra-kernels", action="store_true",
+                    help="profiling aid: with --brief, also launch the per-channel and logits kernels once per step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads/layers would shard without communication); "
@@ -113,6 +130,11 @@ def main():
     wl = LongContext(layers=args.layers, n_tokens=args.tokens)
     H, n, d = wl.heads, wl.n_tokens, wl.d
     dev = wl.device
+    default_workload = args.layers == 32 and args.tokens == 32768
+    facts = profile_facts() if default_workload else {}
+
+    def fact(name):
+        return facts[name][0] if name in facts else None
 
     # every buffer is allocated once, outside the timed region
     qhat = torch.empty((H, wl.r, d), dtype=torch.float32, device=dev)
@@ -124,9 +146,14 @@ def main():
     scale = torch.empty((1, H, n, d // wl.group), dtype=torch.float16, device=dev)
     zero = torch.empty((1, H, n, d // wl.group), dtype=torch.float16, device=dev)
     back = torch.empty((1, H, n, d), dtype=torch.bfloat16, device=dev)
+    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()                      # [1, q_heads, d]: the last prompt token's queries
+    logits = torch.empty((1, H * wl.q_per_kv, n), dtype=torch.float32, device=dev)
+    inv_freq = (10000.0 ** (-torch.arange(64, dtype=torch.float64, device=dev) / 64.0)).float()
+    pc_codes = torch.empty((1, H, n // 32, d, wl.bits), dtype=torch.int32, device=dev)
+    pc_scale = torch.empty((1, H, n // 32, d), dtype=torch.float16, device=dev)
+    pc_zero = torch.empty_like(pc_scale)
 
     stages = ("build_subspace", "prepare", "quantize_keys", "dequantize_keys")
-
     only = args.only
 
     def step(ev=None, everything=False):
@@ -146,6 +173,14 @@ def main():
         if ev: ev[4].record()
         if args.with_copy:
             back.copy_(wl.k)          # 2 x keys x 256 B through a plain elementwise copy kernel
+        if args.extra_kernels:
+            squat.quantize_keys_per_channel(wl.k, update, wl.bits, 32, wl.g, codes=pc_codes, scale=pc_scale, zero=pc_zero)
+            squat.dequantize_keys_per_channel(pc_codes, pc_scale, pc_zero, wl.bits, 32, out=back)
+            squat.key_scores(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=logits)
+            squat.key_scores_per_channel(qdec, pc_codes, pc_scale, pc_zero, wl.bits, wl.q_per_kv, d ** -0.5, out=logits)
+            squat.key_scores_rope(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, inv_freq, 0, d ** -0.5, out=logits)
+            squat.key_scores_rope_per_channel(qdec, pc_codes, pc_scale, pc_zero, wl.bits, wl.q_per_kv, inv_freq, 0,
+                                              d ** -0.5, out=logits)
 
     step(everything=True)
 
@@ -159,8 +194,7 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    stage_ms = {}
-    stage_ms_median, stage_ms_min = {}, {}
+    stage_ms, stage_ms_median, stage_ms_min = {}, {}, {}
     for s, name in enumerate(stages):
         ts = sorted(ev[s].elapsed_time(ev[s + 1]) for ev in events)
         stage_ms[name] = sum(ts) / args.steps
@@ -173,15 +207,21 @@ def main():
     q_ms = stage_ms["quantize_keys"]
     q_bytes = n_keys * wl.key_bytes()
     achieved = q_bytes / (q_ms * 1e-3) / 1e9
+    # the embedded contraction (Lemma 2's update): 12288 flop per key at g = 32 by the definition; the kernel
+    # executes it as two fp16 matrix passes (update matrix on the fp16 grid), i.e. twice that
+    alg_tflops = n_keys * 12288 / (q_ms * 1e-3) / 1e12
+    traffic_gb = fact("quantize_kernel.traffic_GB_per_launch")
     roofline = {"kernel": "quantize_kernel<2-bit,G32,g32,bf16>", "bound": "hbm", "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                # FETCH_SIZE + WRITE_SIZE of this kernel from rocprofv3 --pmc, scaled by a plain copy of known
-                # size (profiles/quantize_kernel_long_context_hbm_traffic.txt); measured at the default workload
-                "traffic": 2.5629e9 if (args.layers == 32 and args.tokens == 32768) else None,
+                # FETCH_SIZE + WRITE_SIZE of this kernel from rocprofv3 --pmc, scaled by a plain copy of known size:
+                # read from the tracked summary, None when there is none for this workload
+                "traffic": None if traffic_gb is None else traffic_gb * 1e9,
+                "traffic_source": facts["quantize_kernel.traffic_GB_per_launch"][1] if traffic_gb is not None else None,
                 "bytes_per_launch": q_bytes, "ms_per_launch": q_ms,
-                # embedded contraction: 12288 flop per key at g = 32, two fp16 passes (update matrix on the fp16 grid)
-                "mfma_tflops": n_keys * 12288 * 2 / (q_ms * 1e-3) / 1e12,
-                "mfma_frac_of_fp16_peak": n_keys * 12288 * 2 / (q_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+                "contraction": {"algorithmic_flop_per_key": 12288, "algorithmic_tflops": alg_tflops,
+                                "algorithmic_frac_of_fp16_mfma_peak": alg_tflops / MFMA_16BIT_PEAK_TFLOPS,
+                                "executed_fp16_passes": 2, "executed_tflops": 2 * alg_tflops,
+                                "executed_frac_of_fp16_mfma_peak": 2 * alg_tflops / MFMA_16BIT_PEAK_TFLOPS}}
     d_ms = stage_ms["dequantize_keys"]
     gram_bytes = wl.q.numel() * 2
     other = {
@@ -208,17 +248,57 @@ def main():
         "roofline": roofline,
         "other_kernels": other,
     }
-    def timed(fn, reps=5):
-        fn()
-        fn()
-        torch.cuda.synchronize()
+
+    def finish():
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(dict(n_tokens=n, r=wl.r, lam=wl.lam, bits=wl.bits, group=wl.group,
+                                                    g=wl.g, q_per_kv=wl.q_per_kv))
+        print(json.dumps(out))
+
+    if args.brief or only:
+        finish()
+        return
+
+    def series(fn, reps):
+        """reps back-to-back launches of fn, each timed by its own pair of events (us)."""
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
         evs[0].record()
         for i in range(reps):
             fn()
             evs[i + 1].record()
         torch.cuda.synchronize()
-        return sum(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) / reps
+        return [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(reps)]
+
+    def timed(fn, reps=5):
+        """mean ms of `reps` launches after two untimed ones"""
+        fn()
+        fn()
+        torch.cuda.synchronize()
+        return sum(series(fn, reps)) / reps * 1e-3
+
+    def in_path(qfn, dfn, reps=12):
+        """A quantize launch timed as it runs in the path: between other kernels (its own dequantize), not back
+        to back with itself.  Returns (quantize us, dequantize us), medians over reps after three untimed rounds
+        (the first launches after a change of kernel fall into the power controller's transient, see
+        `sustained_back_to_back`)."""
+        tq, td = [], []
+        for i in range(reps + 3):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record()
+            qfn()
+            e[1].record()
+            dfn()
+            e[2].record()
+            torch.cuda.synchronize()
+            if i >= 3:
+                tq.append(e[0].elapsed_time(e[1]) * 1e3)
+                td.append(e[1].elapsed_time(e[2]) * 1e3)
+        tq.sort()
+        td.sort()
+        return tq[len(tq) // 2], td[len(td) // 2]
+
+    def hbm_frac(nbytes, us):
+        return nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
 
     # The machine, and a practical ceiling measured beside the vendor peak: a plain elementwise device copy
     # of the key tensor (reads and writes keys x 256 B each).
@@ -241,120 +321,242 @@ def main():
                      "device_copy_GBps": 2 * n_keys * d * 2 / (t_copy * 1e-3) / 1e9}
     roofline["frac_of_device_copy"] = achieved / out["device"]["device_copy_GBps"]
 
-    # The paper's own grouping (statistics per channel over 32 tokens): same keys, same update matrix, the
-    # per-channel entry points; the headline variant always, the others with --variants.
-    pc_list = [(2, 32, True)]
-    if args.variants:
-        pc_list += [(2, 64, True), (4, 32, True), (4, 64, True), (2, 128, False)]
-    out["per_channel"] = []
-    qdec = wl.q[:, n - 1, :].unsqueeze(0).contiguous()                      # [1, q_heads, d]: the last prompt token's queries
-    logits = torch.empty((1, H * wl.q_per_kv, n), dtype=torch.float32, device=dev)
-    inv_freq = (10000.0 ** (-torch.arange(64, dtype=torch.float64, device=dev) / 64.0)).float()
-    for bits, g, use_update in pc_list:
+    # ---- the long-context configuration's variants: 2 and 4 bits x groups of 32 and 128 channels (g = 32), each
+    # quantize launch timed between other kernels as in the path, plus the single-block ceiling (g = G = 128, no
+    # update: plain round-to-nearest)
+    out["variants"] = []
+    for bits, G, g, use_update in [(2, 32, 32, True), (4, 32, 32, True), (2, 128, 32, True), (4, 128, 32, True),
+                                   (2, 32, 64, True), (2, 128, 128, False)]:
         upd = (update if g == wl.g else squat.prepare(qhat, wl.lam, g)) if use_update else None
-        c = torch.empty((1, H, n // 32, d, bits), dtype=torch.int32, device=dev)
-        sc = torch.empty((1, H, n // 32, d), dtype=torch.float16, device=dev)
+        c = torch.empty((1, H, n, d * bits // 32), dtype=torch.int32, device=dev)
+        sc = torch.empty((1, H, n, d // G), dtype=torch.float16, device=dev)
         ze = torch.empty_like(sc)
-        tq = timed(lambda: squat.quantize_keys_per_channel(wl.k, upd, bits, 32, g, codes=c, scale=sc, zero=ze))
-        td = timed(lambda: squat.dequantize_keys_per_channel(c, sc, ze, bits, 32, out=back))
-        tsc = timed(lambda: squat.key_scores_per_channel(qdec, c, sc, ze, bits, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
+        tq, td = in_path(lambda: squat.quantize_keys(wl.k, upd, bits, G, g, codes=c, scale=sc, zero=ze),
+                         lambda: squat.dequantize_keys(c, sc, ze, bits, G, out=back))
+        nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // G))
+        out["variants"].append({"bits": bits, "group": G, "g": g, "update": use_update, "bytes_per_key": nbytes // n_keys,
+                                "quantize_us": tq, "quantize_frac_of_hbm_peak": hbm_frac(nbytes, tq),
+                                "quantize_keys_per_s": n_keys / (tq * 1e-6),
+                                "dequantize_us": td, "dequantize_frac_of_hbm_peak": hbm_frac(nbytes, td)})
+        del c, sc, ze
+
+    # ---- the update matrix's two storage forms (squat_prepare: fp16 grid, two matrix passes in the quantize
+    # kernels; squat_prepare_ex full precision: three passes), same keys, same launches
+    update_full = squat.prepare(qhat, wl.lam, wl.g, full_precision=True)
+    forms = {}
+    for name, upd in (("fp16_grid", update), ("full_precision", update_full)):
+        tq, _ = in_path(lambda: squat.quantize_keys(wl.k, upd, wl.bits, wl.group, wl.g, codes=codes, scale=scale, zero=zero),
+                        lambda: squat.dequantize_keys(codes, scale, zero, wl.bits, wl.group, out=back))
+        tp, _ = in_path(lambda: squat.quantize_keys_per_channel(wl.k, upd, wl.bits, 32, wl.g, codes=pc_codes, scale=pc_scale, zero=pc_zero),
+                        lambda: squat.dequantize_keys_per_channel(pc_codes, pc_scale, pc_zero, wl.bits, 32, out=back))
+        forms[name] = {"quantize_us": tq, "quantize_frac_of_hbm_peak": hbm_frac(q_bytes, tq),
+                       "quantize_per_channel_us": tp, "quantize_per_channel_frac_of_hbm_peak": hbm_frac(q_bytes, tp)}
+    out["update_matrix_storage"] = forms
+    del update_full
+    squat.quantize_keys(wl.k, update, wl.bits, wl.group, wl.g, codes=codes, scale=scale, zero=zero)
+
+    # ---- sustained load: 60 launches of one kernel back to back.  The first launch after a pause runs at the
+    # boost clock, launches 4-8 are the slowest (the power controller's reaction), then the time settles.
+    def sustained(fn):
+        torch.cuda.synchronize()
+        time.sleep(0.05)
+        us = series(fn, 60)
+        tail = sorted(us[40:])
+        return {"first_us": us[0], "slowest_us": max(us), "slowest_at_launch": us.index(max(us)) + 1,
+                "settled_us_median_of_last_20": tail[len(tail) // 2], "first_12_us": [round(x, 1) for x in us[:12]]}
+    sus = {"quantize_keys": sustained(lambda: squat.quantize_keys(wl.k, update, wl.bits, wl.group, wl.g, codes=codes, scale=scale, zero=zero)),
+           "dequantize_keys": sustained(lambda: squat.dequantize_keys(codes, scale, zero, wl.bits, wl.group, out=back)),
+           "quantize_keys_per_channel": sustained(lambda: squat.quantize_keys_per_channel(wl.k, update, wl.bits, 32, wl.g, codes=pc_codes, scale=pc_scale, zero=pc_zero))}
+    for v in sus.values():
+        v["settled_frac_of_hbm_peak"] = hbm_frac(q_bytes, v["settled_us_median_of_last_20"])
+    out["sustained_back_to_back"] = sus
+
+    # ---- the paper's own grouping (statistics per channel over 32 tokens): same keys, same update matrix
+    out["per_channel"] = []
+    for bits, g, use_update in [(2, 32, True), (4, 32, True), (2, 64, True)]:
+        upd = (update if g == wl.g else squat.prepare(qhat, wl.lam, g)) if use_update else None
+        c = pc_codes if bits == wl.bits else torch.empty((1, H, n // 32, d, bits), dtype=torch.int32, device=dev)
+        tq, td = in_path(lambda: squat.quantize_keys_per_channel(wl.k, upd, bits, 32, g, codes=c, scale=pc_scale, zero=pc_zero),
+                         lambda: squat.dequantize_keys_per_channel(c, pc_scale, pc_zero, bits, 32, out=back))
+        tsc = timed(lambda: squat.key_scores_per_channel(qdec, c, pc_scale, pc_zero, bits, wl.q_per_kv, d ** -0.5, out=logits), reps=10) * 1e3
         # the same store read as pre-RoPE keys (rotation after dequantization: the paper's SQuat-pre on its own grouping)
-        tsr = timed(lambda: squat.key_scores_rope_per_channel(qdec, c, sc, ze, bits, wl.q_per_kv, inv_freq, 0, d ** -0.5,
-                                                              out=logits), reps=10)
+        tsr = timed(lambda: squat.key_scores_rope_per_channel(qdec, c, pc_scale, pc_zero, bits, wl.q_per_kv, inv_freq, 0, d ** -0.5,
+                                                              out=logits), reps=10) * 1e3
         nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // 32))
         sb = n_keys * (d * bits // 8 + 4 * (d // 32) + 4 * wl.q_per_kv)
-        # the whole path with this grouping in place of the per-token one (subspace and update as in `step`): the
-        # kernel's time between the other stages, not back to back with itself
-        in_step = None
-        if use_update and g == wl.g and not only:
-            def step_pc(ev=None):
-                squat.build_subspace(wl.q, wl.q_per_kv, wl.r, qhat=qhat, eig=eig, ws=ws_sub)
-                squat.prepare(qhat, wl.lam, wl.g, update=update, ws=ws_prep)
-                if ev: ev[0].record()
-                squat.quantize_keys_per_channel(wl.k, update, bits, 32, g, codes=c, scale=sc, zero=ze)
-                if ev: ev[1].record()
-                squat.dequantize_keys_per_channel(c, sc, ze, bits, 32, out=back)
-                if ev: ev[2].record()
-            for _ in range(max(1, args.warmup)):
-                step_pc()
-            torch.cuda.synchronize()
-            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-            t0 = time.perf_counter()
-            for i in range(args.steps):
-                step_pc(evs[i])
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3 / args.steps
-            tq_in = sorted(e[0].elapsed_time(e[1]) for e in evs)
-            td_in = sorted(e[1].elapsed_time(e[2]) for e in evs)
-            in_step = {"ms_per_step": ms, "keys_per_s": n_keys / (ms * 1e-3),
-                       "quantize_us_mean": sum(tq_in) / len(tq_in) * 1e3, "quantize_us_median": tq_in[len(tq_in) // 2] * 1e3,
-                       "quantize_frac_of_hbm_peak": nbytes / (sum(tq_in) / len(tq_in) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                       "dequantize_us_mean": sum(td_in) / len(td_in) * 1e3}
         out["per_channel"].append({"bits": bits, "token_group": 32, "g": g, "update": use_update,
                                    "bytes_per_key": nbytes // n_keys,
-                                   "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                   "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                   "key_scores_us": tsc * 1e3, "key_scores_bytes_per_key": sb // n_keys,
-                                   "key_scores_frac_of_hbm_peak": sb / (tsc * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                   "whole_path": in_step,
-                                   "key_scores_rope_us": tsr * 1e3,
-                                   "key_scores_rope_frac_of_hbm_peak": sb / (tsr * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                                   "quantize_us": tq, "quantize_frac_of_hbm_peak": hbm_frac(nbytes, tq),
+                                   "dequantize_us": td, "dequantize_frac_of_hbm_peak": hbm_frac(nbytes, td),
+                                   "key_scores_us": tsc, "key_scores_bytes_per_key": sb // n_keys,
+                                   "key_scores_frac_of_hbm_peak": hbm_frac(sb, tsc),
+                                   "key_scores_rope_us": tsr, "key_scores_rope_frac_of_hbm_peak": hbm_frac(sb, tsr)})
     # Decode-side consumer: attention logits of one query token per query head straight from the packed
     # store just written (48 B of codes and metadata in, 4 B per query head out, per key).
-    ts = timed(lambda: squat.key_scores(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=logits), reps=10)
+    ts = timed(lambda: squat.key_scores(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, d ** -0.5, out=logits), reps=10) * 1e3
     sbytes = n_keys * (d * wl.bits // 8 + 4 * (d // wl.group) + 4 * wl.q_per_kv)
     out["key_scores"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bytes_per_key": sbytes // n_keys,
-                         "us": ts * 1e3, "keys_per_s": n_keys / (ts * 1e-3),
-                         "frac_of_hbm_peak": sbytes / (ts * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                         "us": ts, "keys_per_s": n_keys / (ts * 1e-6), "frac_of_hbm_peak": hbm_frac(sbytes, ts)}
     # the pre-RoPE variant of the same consumer: keys dequantized, rotated to their positions and rounded to
     # fp16 in registers before the contraction (bound by vector arithmetic, not by HBM)
     tr = timed(lambda: squat.key_scores_rope(qdec, codes, scale, zero, wl.bits, wl.group, wl.q_per_kv, inv_freq, 0,
-                                             d ** -0.5, out=logits), reps=10)
-    out["key_scores_rope"] = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bound": "alu", "us": tr * 1e3,
-                              "keys_per_s": n_keys / (tr * 1e-3), "frac_of_hbm_peak": sbytes / (tr * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                              "valu_instructions_per_16_keys": 300,
-                              # 300 wave64 instructions per 16 keys (main loop of the built kernel) = 1200 lane-operations per key; peak: 256 CUs x 4 SIMDs
-                              # x 16 lanes x 2.4 GHz (packed fp32 is switched off in this build)
-                              "alu_lane_ops_per_s": n_keys / (tr * 1e-3) * 1200,
-                              "alu_peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
-                              "alu_frac": n_keys / (tr * 1e-3) * 1200 / (256 * 4 * 16 * 2.4e9)}
-    if args.variants:
-        out["variants"] = []
-        for bits, G, g, use_update in [(2, 32, 32, True), (2, 32, 64, True), (4, 32, 32, True), (4, 32, 64, True),
-                                       (2, 128, 32, True), (4, 128, 32, True), (2, 128, 64, True),
-                                       (2, 32, 128, False), (2, 128, 128, False), (4, 128, 128, False)]:
-            upd = squat.prepare(qhat, wl.lam, g) if use_update else None
-            c = torch.empty((1, H, n, d * bits // 32), dtype=torch.int32, device=dev)
-            sc = torch.empty((1, H, n, d // G), dtype=torch.float16, device=dev)
-            ze = torch.empty_like(sc)
-            tq = timed(lambda: squat.quantize_keys(wl.k, upd, bits, G, g, codes=c, scale=sc, zero=ze))
-            td = timed(lambda: squat.dequantize_keys(c, sc, ze, bits, G, out=back))
-            nbytes = n_keys * (d * 2 + d * bits // 8 + 4 * (d // G))
-            out["variants"].append({"bits": bits, "group": G, "g": g, "update": use_update,
-                                    "bytes_per_key": nbytes // n_keys,
-                                    "quantize_us": tq * 1e3, "quantize_frac_of_hbm_peak": nbytes / (tq * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                    "dequantize_us": td * 1e3, "dequantize_frac_of_hbm_peak": nbytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                                             d ** -0.5, out=logits), reps=10) * 1e3
+    rope = {"bits": wl.bits, "group": wl.group, "q_per_kv": wl.q_per_kv, "bound": "alu", "us": tr,
+            "keys_per_s": n_keys / (tr * 1e-6), "frac_of_hbm_peak": hbm_frac(sbytes, tr)}
+    valu = fact("key_scores_rope_kernel.valu_per_16_keys")       # SQ_INSTS_VALU per unit of 16 keys, from the tracked counters
+    if valu is not None:
+        lane_ops = n_keys / (tr * 1e-6) * valu * 64 / 16
+        rope.update({"valu_instructions_per_16_keys": valu, "valu_source": facts["key_scores_rope_kernel.valu_per_16_keys"][1],
+                     "alu_lane_ops_per_s": lane_ops, "alu_peak_lane_ops_per_s": ALU_PEAK_LANE_OPS,
+                     "alu_frac": lane_ops / ALU_PEAK_LANE_OPS})
+    out["key_scores_rope"] = rope
+
+    # ---- decode-time flush (Algorithm 1, decoding phase): 64 sequences x 32 buffered tokens per head, the update
+    # matrix shared by the batch; one layer (8 heads) per launch and all 32 layers (256 heads) per launch.  Latency
+    # of an isolated flush (host-synchronised) and the rate of flushes issued back to back.
+    out["decode_flush"] = []
+    for heads in (wl.kv_heads, H):
+        kb = torch.randn((64, heads, 32, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        c = torch.empty((64, heads, 32, d * wl.bits // 32), dtype=torch.int32, device=dev)
+        sc = torch.empty((64, heads, 32, d // wl.group), dtype=torch.float16, device=dev)
+        ze = torch.empty_like(sc)
+        fn = lambda: squat.quantize_keys(kb, update[:heads], wl.bits, wl.group, wl.g, codes=c, scale=sc, zero=ze)  # noqa: E731
+        fn()
+        torch.cuda.synchronize()
+        lat = []
+        for _ in range(20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1) * 1e3)
+        lat.sort()
+        us = series(fn, 50)
+        nk = 64 * heads * 32
+        out["decode_flush"].append({"sequences": 64, "heads_per_launch": heads, "keys_per_flush": nk,
+                                    "us_per_flush_isolated_median": lat[len(lat) // 2],
+                                    "us_per_flush_back_to_back": sum(us) / len(us),
+                                    "keys_per_s_back_to_back": nk / (sum(us) / len(us) * 1e-6)})
+
+    # ---- the same work issued layer by layer (8 KV heads per launch, as a prefill produces them): one stream,
+    # with the per-stage split; then layer l on stream l mod S for S = 2 and 8 (equal priorities), which lets the
+    # per-head solvers of one layer (8 of 256 CUs busy) overlap the streaming kernels of others
+    kvh, qhs = wl.kv_heads, wl.kv_heads * wl.q_per_kv
+    ws_l = torch.empty(squat.build_subspace_workspace(n, kvh, wl.q_per_kv, d, wl.r), dtype=torch.uint8, device=dev)
+    wp_l = torch.empty(max(256, squat.prepare_workspace(kvh, d, wl.r, wl.g)), dtype=torch.uint8, device=dev)
+
+    def one_layer(l, ws, wp, ev=None):
+        hs = slice(l * kvh, (l + 1) * kvh)
+        if ev: ev[0].record()
+        squat.build_subspace(wl.q[l * qhs:(l + 1) * qhs], wl.q_per_kv, wl.r, qhat=qhat[hs], eig=eig[hs], ws=ws)
+        if ev: ev[1].record()
+        squat.prepare(qhat[hs], wl.lam, wl.g, update=update[hs], ws=wp)
+        if ev: ev[2].record()
+        squat.quantize_keys(wl.k[:, hs], update[hs], wl.bits, wl.group, wl.g, codes=codes[:, hs],
+                            scale=scale[:, hs], zero=zero[:, hs])
+        if ev: ev[3].record()
+        squat.dequantize_keys(codes[:, hs], scale[:, hs], zero[:, hs], wl.bits, wl.group, out=back[:, hs])
+        if ev: ev[4].record()
+
+    def layer_step(ev=None):
+        for l in range(wl.layers):
+            one_layer(l, ws_l, wp_l, ev[l] if ev else None)
+
+    layer_step()
+    layer_step()
+    torch.cuda.synchronize()
+    reps = 4
+    evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(wl.layers)] for _ in range(reps)]
+    t0 = time.perf_counter()
+    for i in range(reps):
+        layer_step(evs[i])
+    torch.cuda.synchronize()
+    t_serial = (time.perf_counter() - t0) * 1e3 / reps
+    split = {name: sum(evs[i][l][s].elapsed_time(evs[i][l][s + 1]) for i in range(reps) for l in range(wl.layers)) / reps
+             for s, name in enumerate(stages)}
+    per_layer = {"launch_groups": wl.layers, "heads_per_launch": kvh, "one_stream": {"ms_per_step": t_serial,
+                 "keys_per_s": n_keys / (t_serial * 1e-3), "stage_ms_sum_over_layers": split}}
+    codes_serial = codes.clone()
+    for NS in (2, 8):
+        streams = [torch.cuda.Stream() for _ in range(NS)]
+        ws_s = [torch.empty_like(ws_l) for _ in range(NS)]
+        wp_s = [torch.empty_like(wp_l) for _ in range(NS)]
+
+        def streams_step():
+            main = torch.cuda.current_stream()
+            start = torch.cuda.Event()
+            start.record(main)
+            for st in streams:
+                st.wait_event(start)
+            for l in range(wl.layers):
+                with torch.cuda.stream(streams[l % NS]):
+                    one_layer(l, ws_s[l % NS], wp_s[l % NS])
+            for st in streams:
+                done = torch.cuda.Event()
+                done.record(st)
+                main.wait_event(done)
+
+        codes.zero_()
+        streams_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            streams_step()
+        torch.cuda.synchronize()
+        t_s = (time.perf_counter() - t0) * 1e3 / reps
+        per_layer["%d_streams" % NS] = {"ms_per_step": t_s, "keys_per_s": n_keys / (t_s * 1e-3),
+                                        "codes_equal_one_stream": bool(torch.equal(codes, codes_serial))}
+        del streams, ws_s, wp_s
+    out["per_layer"] = per_layer
+    del codes_serial
+
+    # ---- routes to the query subspace on 256 heads: the exact solver against block power iteration on the Gram
+    # matrix (cold start, and warm start after 64 new queries), on near-isotropic queries and on queries that
+    # concentrate in a few directions; error = || Qhat^T Qhat - exact || / || exact ||, worst head
+    def subspace_routes(q, n_tok, r, label):
+        qpk = wl.q_per_kv
+        heads = q.shape[0] // qpk
+        n_old = n_tok - 64
+        state = torch.zeros((heads, d, d), dtype=torch.float64, device=dev)
+        ws = torch.empty(int(squat.lib().squat_refresh_subspace_workspace(n_old, heads, qpk, d, r)), dtype=torch.uint8, device=dev)
+        prev, _, _ = squat.refresh_subspace(state, qpk, r, -1, q_new=q[:, :n_old], accumulate=False, ws=ws)
+        squat.refresh_subspace(state, qpk, 0, 0, q_new=q[:, n_old:n_tok], accumulate=True, ws=ws)
+        exact, ev, _ = squat.refresh_subspace(state, qpk, r, -1, ws=ws)
+        ref = torch.bmm(exact.double().transpose(1, 2), exact.double())
+        refn = ref.flatten(1).norm(dim=1)
+        qh, ei, re = torch.empty_like(exact), torch.empty_like(ev), torch.empty((heads,), dtype=torch.float32, device=dev)
+
+        def err(x):
+            m = torch.bmm(x.double().transpose(1, 2), x.double())
+            return float(((m - ref).flatten(1).norm(dim=1) / refn).max())
+        t_exact = timed(lambda: squat.refresh_subspace(state, qpk, r, -1, qhat=qh, eig=ei, residual=re, ws=ws), reps=5) * 1e3
+        rows = {"exact_solver_us": t_exact, "cold": [], "warm_after_64_new_queries": []}
+        for k in (0, 1, 2, 4, 8, 16, 32, 64):
+            t = timed(lambda: squat.refresh_subspace(state, qpk, r, k, qhat=qh, eig=ei, residual=re, ws=ws), reps=3) * 1e3
+            rows["cold"].append({"iterations": k, "us": t, "error": err(qh), "residual": float(re.max()),
+                                 "eig_rel_error": float(((ei - ev).abs().max(dim=1).values / ev[:, 0]).max())})
+        for k in (0, 1, 2, 3, 5, 8):
+            t = timed(lambda: squat.refresh_subspace(state, qpk, r, k, qhat_prev=prev, qhat=qh, eig=ei, residual=re, ws=ws), reps=3) * 1e3
+            rows["warm_after_64_new_queries"].append({"iterations": k, "us": t, "error": err(qh), "residual": float(re.max())})
+        rows["previous_qhat_error"] = err(prev)
+        rows["workload"] = label
+        return rows
+    routes = []
+    n_r = min(n, 4096)
+    routes.append(subspace_routes(wl.q, n_r, 32, "near-isotropic N(0,1) queries, %d tokens x 4 query heads per KV head, r = 32" % n_r))
+    routes.append(subspace_routes(wl.q, n_r, 8, "near-isotropic N(0,1) queries, %d tokens x 4 query heads per KV head, r = 8" % n_r))
+    wlp = LongContext(layers=args.layers, n_tokens=n_r, planted_rank=12, seed=5100)
+    routes.append(subspace_routes(wlp.q, n_r, 8, "queries with 12 planted decaying directions, %d tokens, r = 8" % n_r))
+    routes.append(subspace_routes(wlp.q, n_r, 16, "queries with 12 planted decaying directions, %d tokens, r = 16" % n_r))
+    del wlp
+    out["subspace_routes"] = routes
+
     if args.decode:
         def timed_us(fn, reps=50):
             fn()
             torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) * 1e3 / reps
-        out["decode_flush"] = []
-        for heads in (wl.kv_heads, H):
-            kb = torch.randn((64, heads, 32, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
-            c = torch.empty((64, heads, 32, d * wl.bits // 32), dtype=torch.int32, device=dev)
-            sc = torch.empty((64, heads, 32, d // wl.group), dtype=torch.float16, device=dev)
-            ze = torch.empty_like(sc)
-            us = timed_us(lambda: squat.quantize_keys(kb, update[:heads], wl.bits, wl.group, wl.g, codes=c, scale=sc, zero=ze))
-            nk = 64 * heads * 32
-            out["decode_flush"].append({"sequences": 64, "heads_per_launch": heads, "keys_per_flush": nk,
-                                        "us_per_flush_back_to_back": us, "keys_per_s": nk / (us * 1e-6)})
+            return sum(series(fn, reps)) / reps
         # logits of 64 sequences x all (layer, KV head) slots over 2048 quantized tokens each
         nd = 2048
         cd = torch.randint(-2 ** 31, 2 ** 31 - 1, (64, H, nd, d * wl.bits // 32), dtype=torch.int32, device=dev)
@@ -399,75 +601,7 @@ def main():
         del kp
         out["decode_scores"] = {"sequences": 64, "heads": H, "quantized_tokens": nd, "q_per_kv": wl.q_per_kv, "us": us,
                                 "keys_per_s": nk / (us * 1e-6), "frac_of_hbm_peak": nb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
-    if args.per_layer:
-        # The same work as `step`, issued layer by layer: 4 launches-groups x 32 layers.  Eager launches are
-        # bound by the host (ctypes marshalling per call); the graph replays the identical launches back to back.
-        kvh, qhs = wl.kv_heads, wl.kv_heads * wl.q_per_kv
-        ws_l = torch.empty(squat.build_subspace_workspace(n, kvh, wl.q_per_kv, d, wl.r), dtype=torch.uint8, device=dev)
-        wp_l = torch.empty(max(256, squat.prepare_workspace(kvh, d, wl.r, wl.g)), dtype=torch.uint8, device=dev)
-        codes_b = codes.clone()
-
-        def layer_step():
-            for l in range(wl.layers):
-                hs = slice(l * kvh, (l + 1) * kvh)
-                squat.build_subspace(wl.q[l * qhs:(l + 1) * qhs], wl.q_per_kv, wl.r, qhat=qhat[hs], eig=eig[hs], ws=ws_l)
-                squat.prepare(qhat[hs], wl.lam, wl.g, update=update[hs], ws=wp_l)
-                squat.quantize_keys(wl.k[:, hs], update[hs], wl.bits, wl.group, wl.g, codes=codes[:, hs],
-                                    scale=scale[:, hs], zero=zero[:, hs])
-                squat.dequantize_keys(codes[:, hs], scale[:, hs], zero[:, hs], wl.bits, wl.group, out=back[:, hs])
-
-        t_eager = timed(layer_step, reps=5)
-        codes_e = codes.clone()
-
-        # the same launches spread over 8 streams (layer l on stream l mod 8, each stream with its own workspaces)
-        NS = 8
-        streams = [torch.cuda.Stream() for _ in range(NS)]
-        ws_s = [torch.empty_like(ws_l) for _ in range(NS)]
-        wp_s = [torch.empty_like(wp_l) for _ in range(NS)]
-
-        def streams_step():
-            main = torch.cuda.current_stream()
-            start = torch.cuda.Event()
-            start.record(main)
-            for i, st in enumerate(streams):
-                st.wait_event(start)
-            for l in range(wl.layers):
-                i = l % NS
-                hs = slice(l * kvh, (l + 1) * kvh)
-                with torch.cuda.stream(streams[i]):
-                    squat.build_subspace(wl.q[l * qhs:(l + 1) * qhs], wl.q_per_kv, wl.r, qhat=qhat[hs], eig=eig[hs], ws=ws_s[i])
-                    squat.prepare(qhat[hs], wl.lam, wl.g, update=update[hs], ws=wp_s[i])
-                    squat.quantize_keys(wl.k[:, hs], update[hs], wl.bits, wl.group, wl.g, codes=codes[:, hs],
-                                        scale=scale[:, hs], zero=zero[:, hs])
-                    squat.dequantize_keys(codes[:, hs], scale[:, hs], zero[:, hs], wl.bits, wl.group, out=back[:, hs])
-            for st in streams:
-                done = torch.cuda.Event()
-                done.record(st)
-                main.wait_event(done)
-
-        codes.zero_()
-        t_streams = timed(streams_step, reps=5)
-        streams_equal = bool(torch.equal(codes, codes_e))
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            layer_step()
-        codes.zero_()
-        t_graph = timed(graph.replay, reps=10)
-        out["per_layer"] = {"launch_groups": wl.layers, "heads_per_launch": kvh, "ms_per_step_eager": t_eager,
-                            "ms_per_step_graph": t_graph, "keys_per_s_graph": n_keys / (t_graph * 1e-3),
-                            "ms_per_step_8_streams": t_streams, "keys_per_s_8_streams": n_keys / (t_streams * 1e-3),
-                            "streams_codes_equal_eager": streams_equal,
-                            "graph_codes_equal_eager": bool(torch.equal(codes, codes_e)),
-                            # the Gram sums are grouped differently (32 workgroups per head instead of 1)
-                            "packed_words_differing_from_stacked": float((codes_e != codes_b).float().mean()),
-                            "note": "the per-head solvers (eigen-solver 0.37 ms, prepare 0.07 ms per launch whatever the "
-                                    "number of heads) run on 8 of 256 CUs here and are serial over the layers: stack the "
-                                    "layers, as the headline step does, or give each layer its own stream"}
-        del graph
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(dict(n_tokens=n, r=wl.r, lam=wl.lam, bits=wl.bits, group=wl.group,
-                                                g=wl.g, q_per_kv=wl.q_per_kv))
-    print(json.dumps(out))
+    finish()
 
 
 if __name__ == "__main__":
