@@ -407,8 +407,14 @@ int squat_key_scores(const uint32_t* codes, const uint16_t* scale, const uint16_
  *   inv_freq [64] float, device memory: the rotary frequencies (theta^(-c/64),
  *            or any scaled variant).
  *   pos0     position of token 0 of the store, 0 <= pos0 < 2^40.
- *   Accuracy: the rotated key is rounded to fp16 before the contraction
- *   (relative 2^-11 per channel); angles are exact to ~1e-5 rad.
+ *   Accuracy: the queries enter as exact fp16 high/low pairs (rotated in fp32
+ *   by the part of the angle that a block of 64 tokens shares, angles good to
+ *   ~1e-5 rad); the key is dequantized and rotated in packed fp16, where the
+ *   dequantized value, the cos/sin entry, one product and the result are each
+ *   rounded to fp16: a rotated channel is off by at most 4 * 2^-11 times the
+ *   norm of its rotary pair (typically a quarter of that), a logit by at most
+ *   4 * 2^-11 * out_scale * sum_{c<64} (|q_c| + |q_{c+64}|) |(k_c, k_{c+64})|.
+ *   Dequantized keys and their rotations must stay below 65504.
  * ------------------------------------------------------------------------- */
 int squat_key_scores_rope(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
                           int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits, int group,
@@ -459,7 +465,7 @@ int squat_key_scores_per_channel(const uint32_t* codes, const uint16_t* scale, c
  *   inv_freq, pos0   as for squat_key_scores_rope.
  *   q, q_per_kv, out_scale, scores and their strides   as for squat_key_scores
  *            (|q| below the fp16 range, 65504).
- *   Accuracy: as squat_key_scores_rope (rotated key rounded to fp16).
+ *   Accuracy: as squat_key_scores_rope.
  * ------------------------------------------------------------------------- */
 int squat_key_scores_rope_per_channel(const uint32_t* codes, const uint16_t* scale, const uint16_t* zero,
                                       int64_t n_batch, int n_kv_heads, int64_t n_tokens, int d, int bits,

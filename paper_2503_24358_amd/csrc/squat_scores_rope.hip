@@ -5,22 +5,14 @@
 // channel pairs (c, c + 64) rotated by (pos0 + t) * inv_freq[c]; per-token store.
 //
 // The rotation sits between the codes and the contraction, so the codes cannot
-// go to the matrix cores raw as in squat_key_scores: every key is dequantized in
-// registers (code * Delta + m, fp32), rotated, rounded to fp16 and only then
-// multiplied with the fp16 high/low rows of the queries
-// (v_mfma_f32_16x16x32_f16, token = column, (query head, part) = row).  This
-// kernel is bound by vector arithmetic (270 instructions per 16 tokens against
-// about 60 in the unrotated kernel), which is the price of that variant; it
-// still never writes a key to memory.
-//
-// A lane owns, for its token, channels 32 g + 8 kb + i (g < 4, i < 8): both
-// members of every rotary pair (chunks g and g + 2), so the rotation needs no
-// lane exchange.  cos / sin of the lane's 16 angles are carried in registers
-// and advanced by 16 positions per unit with the addition theorems; they are
-// seeded per wavefront from fp64 range reduction (position * inv_freq reduced to
-// a fraction of a turn before the fp32 sincospi), so the recurrence runs for at
-// most ~48 steps (error ~ 1e-5 of a radian, far below the fp16 rounding of the
-// rotated key, 2^-11 relative, which sets the accuracy of this call).
+// go to the matrix cores raw as in squat_key_scores: every key is dequantized
+// and rotated in registers and only then multiplied with the fp16 high/low rows
+// of the queries (v_mfma_f32_16x16x32_f16, token = column, (query head, part) =
+// row).  The kernels are bound by vector arithmetic (about 160 instructions per 16
+// tokens against about 90 in the unrotated kernel), which is the price of that
+// variant; they still never write a key to memory.  How the arithmetic is kept
+// that small (angle split into a per-epoch and a per-token part, packed fp16 on
+// rotary pairs) is described at the shared pieces below.
 //
 // squat_key_scores_rope_per_channel is the same computation over the per-channel
 // store (statistics per channel over 32 tokens, the grouping Algorithm 1 prints):
@@ -31,6 +23,8 @@
 // they are issued in consecutive instructions (the per-token kernel keeps the
 // even unit of a pair in registers until the odd one is done), because halves
 // stored a unit of work apart reach memory as two partial line writes.
+#include <type_traits>
+
 #include "squat_internal.h"
 
 using namespace squat;
@@ -43,7 +37,7 @@ constexpr int kRopeDepth = 3;          // units whose loads are in flight per wa
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int kRopeUnit = 16;          // tokens per matrix product (MFMA N)
-constexpr int kRopeMaxUnitsPerWave = 32;
+constexpr int kRopeMaxUnitsPerWave = 64;
 constexpr int kRopeMinUnitsPerWave = 4;
 constexpr int kRopeWaves = 4;
 
@@ -71,94 +65,212 @@ __device__ __forceinline__ uint32_t pack_h2(_Float16 lo, _Float16 hi) {
            (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
 }
 
+// ---- shared pieces of the two kernels -----------------------------------------------------------------------
+//
+// Angle of token t and frequency f:  (pos0 + t) f = theta_E + theta_l  with E the first token of t's EPOCH of 64
+// tokens and l = t - E.  R(theta) = R(theta_E) R(theta_l), and  q . R(theta) k = (R(-theta_E) q) . (R(theta_l) k):
+//   - key side: theta_l runs over 64 x 64 fixed values, the same for every epoch, wavefront and position offset:
+//     their (cos, sin) sit in an LDS table as packed fp16 pairs, filled once per workgroup;
+//   - query side: R(-theta_E) q is rebuilt once per epoch and wavefront in fp32 (cos / sin of theta_E advance by the
+//     addition theorems, seeded from an fp64 range reduction), split into exact fp16 high / low parts, and becomes
+//     the A operand of the epoch's matrix products.
+// The key itself is dequantized and rotated in PACKED fp16: a register holds a rotary pair (k_c, k_{c+64}) of the
+// lane's token, so x' = (a cos - b sin, b cos + a sin) is one packed multiply and one packed multiply-add on the
+// pair and its swapped copy, and the result is the B operand as it stands (the contraction index is ordered
+// pair by pair on both sides).  Rounding: the dequantized value, the table entries, the product and the result are
+// each rounded to fp16: |error of x'| <= 4 * 2^-11 * sqrt(a^2 + b^2) in the worst case (typically a quarter of it).
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+constexpr int kEpochUnits = 4;                 // units of 16 tokens that share one query-side operand
+constexpr int kEpochTokens = kEpochUnits * kRopeUnit;
+constexpr int kTrigLd = 68;                    // words per table row (64 + 4: 16-byte lane reads fall on distinct banks)
+constexpr int kATileLd = 68;                   // words per row of the A-operand exchange tile
+constexpr float kCodeScale = 512.0f;           // codes enter the multiply-add as code * 2^-9, the scales times 2^9
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t h2_bits(h2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ uint32_t pack_rne(float lo, float hi) {
+    return pack_h2(static_cast<_Float16>(lo), static_cast<_Float16>(hi));
+}
+
+// (a cos - b sin, b cos + a sin) for the pair x = (a, b) and cs = (cos, sin)
+__device__ __forceinline__ h2 rotate_pair(h2 x, h2 cs) {
+    const h2 cc = __builtin_shufflevector(cs, cs, 0, 0);
+    const h2 sw = __builtin_shufflevector(x, x, 1, 0);
+    const h2 ss = {-cs[1], cs[1]};
+    return __builtin_elementwise_fma(sw, ss, x * cc);
+}
+
+// Word index of frequency f inside a row of the LDS tables: lane K-block kb = (f >> 3) & 3 first, then the
+// 32-channel chunk g = f >> 5, then i = f & 7, so that the 16 entries of one lane are 64 contiguous bytes.
+__device__ __forceinline__ int freq_slot(int f) { return ((f >> 3) & 3) * 16 + (f >> 5) * 8 + (f & 7); }
+
+// Fills the key-side table trig[l][slot(f)] = (cos, sin)(l * inv_freq[f]) and step64[f] = (cos, sin)(64 inv_freq[f]).
+// 256 threads; thread (f, quarter) covers l = 16 quarter .. + 15 by the addition theorems from an fp64-reduced start.
+__device__ __forceinline__ void fill_trig_tables(const float* inv_freq, uint32_t* trig, float* step64) {
+    const int f = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+    const float fr = inv_freq[f];
+    float c, s, c1, s1;
+    turn_sincos(static_cast<double>(16 * quarter), fr, c, s);
+    turn_sincos(1.0, fr, c1, s1);
+    const int slot = freq_slot(f);
+#pragma unroll 4
+    for (int l = 0; l < 16; ++l) {
+        trig[(16 * quarter + l) * kTrigLd + slot] = pack_rne(c, s);
+        const float c2 = fmaf(c, c1, -(s * s1));
+        s = fmaf(s, c1, c * s1);
+        c = c2;
+    }
+    if (quarter == 0) {
+        float ce, se;
+        turn_sincos(static_cast<double>(kEpochTokens), fr, ce, se);
+        step64[2 * f] = ce;
+        step64[2 * f + 1] = se;
+    }
+}
+
+// Query side of one wavefront.  With more than four query heads per KV head lane (h = lane >> 3, fb = lane & 7)
+// owns the NF = 8 pairs (q_h[f], q_h[f + 64]), f = 8 fb + i; with at most four (the usual grouped-query case) lane
+// (h = lane >> 4, fb = lane & 15) owns NF = 4 pairs, f = 4 fb + i, and rows 8 .. 15 of the operand stay zero.  `build`
+// writes R(-theta_E) q as fp16 high (row 2 h) and low (row 2 h + 1) parts into the wavefront's exchange tile, from
+// which every lane reads the 16 registers of its A operands.
+struct QuerySide {
+    float ce[8], se[8];          // cos / sin of theta_E (the only state that lives across epochs)
+    const float* qrow;           // this lane's query head in LDS (fp32)
+    const float* step;           // (cos, sin) of one epoch's rotation (64 positions) per frequency, LDS
+    int f0;                      // first frequency of this lane
+    bool wide;                   // NF = 8
+
+    __device__ __forceinline__ void init(const float* qlds, int qld, const float* step64, const float* inv_freq,
+                                         double position, int lane, int qpk, uint32_t* atile) {
+        wide = qpk > 4;
+        const int h = wide ? lane >> 3 : lane >> 4;
+        f0 = wide ? 8 * (lane & 7) : 4 * (lane & 15);
+        qrow = qlds + h * qld;
+        step = step64;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (i < 4 || wide)
+                turn_sincos(position, inv_freq[f0 + i], ce[i], se[i]);
+            else
+                ce[i] = se[i] = 0.0f;
+        }
+        // rows that `build` never writes (query heads past 4 in the narrow form) must read as zero
+        for (int idx = lane; idx < 16 * kATileLd; idx += kWave) atile[idx] = 0u;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    template <int NF>
+    __device__ __forceinline__ void rotate_and_store(uint32_t* dst) {
+        uint32_t hi[NF], lo[NF];
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+            const float qa = qrow[f0 + i], qb = qrow[64 + f0 + i];
+            const float dc = step[2 * (f0 + i)], ds = step[2 * (f0 + i) + 1];
+            // R(-theta): (a cos + b sin, b cos - a sin)
+            const float ra = fmaf(qa, ce[i], qb * se[i]);
+            const float rb = fmaf(qb, ce[i], -(qa * se[i]));
+            const auto hv = __builtin_amdgcn_cvt_pkrtz(ra, rb);
+            hi[i] = __builtin_bit_cast(uint32_t, hv);
+            lo[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ra - static_cast<float>(hv[0]),
+                                                                            rb - static_cast<float>(hv[1])));
+            const float c2 = fmaf(ce[i], dc, -(se[i] * ds));
+            se[i] = fmaf(se[i], dc, ce[i] * ds);
+            ce[i] = c2;
+        }
+#pragma unroll
+        for (int i = 0; i < NF; i += 4) {
+            *reinterpret_cast<u32x4*>(dst + i) = u32x4{hi[i], hi[i + 1], hi[i + 2], hi[i + 3]};
+            *reinterpret_cast<u32x4*>(dst + kATileLd + i) = u32x4{lo[i], lo[i + 1], lo[i + 2], lo[i + 3]};
+        }
+    }
+    // A operands of the epoch whose angles are current, then the angles move on by one epoch
+    __device__ __forceinline__ void build(uint32_t* atile, int lane, u32x4 (&aop)[4]) {
+        if (wide) {
+            // frequencies 8 fb .. 8 fb + 7 are K-block fb & 3, chunk fb >> 2: 8 consecutive words of a row
+            const int h = lane >> 3, fb = lane & 7;
+            rotate_and_store<8>(atile + (2 * h) * kATileLd + (fb & 3) * 16 + (fb >> 2) * 8);
+        } else {
+            // frequencies 4 fb .. 4 fb + 3: K-block (fb >> 1) & 3, chunk fb >> 3, pairs 4 (fb & 1) .. + 3
+            const int h = lane >> 4, fb = lane & 15;
+            rotate_and_store<4>(atile + (2 * h) * kATileLd + ((fb >> 1) & 3) * 16 + (fb >> 3) * 8 + (fb & 1) * 4);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint32_t* src = atile + (lane & 15) * kATileLd + (lane >> 4) * 16;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) aop[m] = *reinterpret_cast<const u32x4*>(src + 4 * m);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+};
+
+// Loads the KV head's queries into LDS as fp32 (rows past q_per_kv zero).  256 threads, 8 x 128 values.
+template <int QDT>
+__device__ __forceinline__ void stage_queries(const RopeParams& p, int64_t b, int kvh, float* qlds, int qld) {
+    const int e0 = 4 * static_cast<int>(threadIdx.x);
+    const int qrow = e0 / kD, qch = e0 % kD;
+    float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (qrow < p.qpk) {
+        const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
+        if constexpr (QDT == SQUAT_F32) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
+            v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+        } else {
+            const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
+                v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
+                                         : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qlds[qrow * qld + qch + i] = v[i];
+}
+
+// Per-token store.  Lane (kb = lane >> 4, col = lane & 15): token col of the unit, rotary pairs
+// (32 g + 8 kb + i, + 64), g < 2, i < 8.  Matrix product m = 2 g + (i >> 2) takes the pairs i & 3 = 0..3 of chunk g
+// as its K slots 8 kb .. 8 kb + 7 (both operands), rows = (query head, fp16 high / low part).
 template <int BITS, int NG, int QDT>
 __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(const RopeParams p) {
     constexpr int WPK = kD * BITS / 32;                   // packed words per key
-    constexpr int CPG = 4 / NG;                           // 32-channel chunks per group
+    constexpr int CPR = 8 / BITS;                         // codes of a pair register whose bits stay below bit 8 of a half
+    constexpr int NSRC = 8 / CPR;                         // such source registers per chunk pair: 2 (2-bit), 4 (4-bit)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // uniform: scalar loop control
-    const int kb = lane >> 4;                             // K block of an operand / row block of the result
-    const int col = lane & 15;                            // operand row (A) or token (B, result)
+    const int kb = lane >> 4;
+    const int col = lane & 15;
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
     const int64_t b = bh / p.n_kv_heads;
     const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
 
-    // ---- the KV head's queries -> LDS as fp32 (rows past q_per_kv zero); rotation of 16 positions per
-    // frequency -> LDS
     constexpr int QLD = kD + 1;
     __shared__ float qlds[8 * QLD];
-    __shared__ float step_cs[2 * 64];
-    {
-        const int e0 = 4 * static_cast<int>(threadIdx.x);
-        const int qrow = e0 / kD, qch = e0 % kD;
-        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (qrow < p.qpk) {
-            const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
-            if constexpr (QDT == SQUAT_F32) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
-                v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
-            } else {
-                const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
-                    v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
-                                             : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qlds[qrow * QLD + qch + i] = v[i];
-        if (threadIdx.x < 64) {
-            float c, s;
-            turn_sincos(static_cast<double>(kRopeUnit), p.inv_freq[threadIdx.x], c, s);
-            step_cs[2 * threadIdx.x] = c;
-            step_cs[2 * threadIdx.x + 1] = s;
-        }
-    }
+    __shared__ float step64[2 * 64];
+    __shared__ __attribute__((aligned(16))) uint32_t trig[kEpochTokens * kTrigLd];
+    __shared__ __attribute__((aligned(16))) uint32_t atiles[kRopeWaves * 16 * kATileLd];
+    stage_queries<QDT>(p, b, kvh, qlds, QLD);
+    fill_trig_tables(p.inv_freq, trig, step64);
     __syncthreads();
 
-    // ---- A operands: row `col` = (query head col / 2, fp16 high / low part col % 2);
-    // register r of chunk g holds K = 8 kb + 2 r + {0, 1}  <->  channels 32 g + 8 kb + 2 r + {0, 1}
-    const int qh = col >> 1, part = col & 1;
-    u32x4 aop[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            _Float16 h[2];
-#pragma unroll
-            for (int pp = 0; pp < 2; ++pp) {
-                const float v = qlds[qh * QLD + 32 * g + 8 * kb + 2 * r + pp];
-                const _Float16 hi = static_cast<_Float16>(v);
-                h[pp] = part == 0 ? hi : static_cast<_Float16>(v - static_cast<float>(hi));
-            }
-            aop[g][r] = pack_h2(h[0], h[1]);
-        }
-
-    // ---- this wavefront's 16-token units
+    // ---- this wavefront's 16-token units (whole epochs; the range starts on an epoch boundary)
     const int n_units = static_cast<int>((p.n_tokens + kRopeUnit - 1) / kRopeUnit);
     const int u0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
     const int u1 = min(u0 + p.units_per_wave, n_units);
     if (u0 >= u1) return;                                 // after the last workgroup barrier
 
-    // rotary state of this lane: frequency index 8 g' + i  <->  channel pair (32 g' + 8 kb + i, + 64)
-    float cs[16], sn[16], dc[16], ds[16];
-    {
-        const double position = static_cast<double>(p.pos0 + static_cast<int64_t>(u0) * kRopeUnit + col);
-#pragma unroll
-        for (int f = 0; f < 16; ++f) {
-            const int ch = 32 * (f >> 3) + 8 * kb + (f & 7);
-            turn_sincos(position, p.inv_freq[ch], cs[f], sn[f]);
-            dc[f] = step_cs[2 * ch];
-            ds[f] = step_cs[2 * ch + 1];
-        }
-    }
+    uint32_t* atile = atiles + wave * 16 * kATileLd;
+    QuerySide qs;
+    qs.init(qlds, QLD, step64, p.inv_freq, static_cast<double>(p.pos0 + static_cast<int64_t>(u0) * kRopeUnit), lane,
+            p.qpk, atile);
 
     const int64_t row0 = bh * p.store_stride;
-    const int widx0 = BITS == 2 ? (kb >> 1) : kb;         // word of chunk 0 this lane unpacks
-    const uint32_t wshift = BITS == 2 ? 16u * (kb & 1) : 0u;
     float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
     const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
     const float fin = p.out_scale;
@@ -202,8 +314,13 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
         }
     };
 
+    // where this lane's codes sit: 2-bit: 16 bits (one half of a word) per chunk; 4-bit: one word per chunk
+    const int widx0 = BITS == 2 ? (kb >> 1) : kb;
+    const uint32_t half_sel = (kb & 1) ? 0x07060302u : 0x05040100u;       // v_perm: (hi : lo) <- the same half of both words
+
+    u32x4 aop[4];
     float held0 = 0.0f, held1 = 0.0f;
-    auto compute = [&](int u, const Raw& raw) {
+    auto compute = [&](int u, int v, const Raw& raw) {
         // registers -> LDS tile -> the words of this lane's K block, the metadata of its token
         if (is_c) *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) = raw.c;
         if (is_m) *reinterpret_cast<u32x2*>(lds + META0 + (ml & 16) * 8 + m_tok * 8) = raw.m;
@@ -213,50 +330,85 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
         uint32_t w[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-            w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4) >> wshift;
+            w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4);
         const u32x2 sv = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
         const u32x2 zv = *reinterpret_cast<const u32x2*>(lds + META0 + 128 + col * 8);
+        // key-side angles of token 16 v + col of the epoch, this lane's 16 frequencies
+        u32x4 tr[4];
+        {
+            const uint32_t* trow = trig + (kRopeUnit * v + col) * kTrigLd + kb * 16;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) tr[m] = *reinterpret_cast<const u32x4*>(trow + 4 * m);
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        float sc[NG], zp[NG];
+        // scale and zero-point of the two members of a pair of chunk g: groups (g, g + 2) * NG / 4
+        h2 dsc[2], dzp[2];
+        bool big = false;
 #pragma unroll
-        for (int gi = 0; gi < NG; ++gi) {
-            const uint32_t sw = gi < 2 ? sv[0] : sv[1], zw = gi < 2 ? zv[0] : zv[1];
-            sc[gi] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>((gi & 1) ? (sw >> 16) : (sw & 0xFFFFu))));
-            zp[gi] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>((gi & 1) ? (zw >> 16) : (zw & 0xFFFFu))));
+        for (int g = 0; g < 2; ++g) {
+            const int ga = g * NG / 4, gb = (g + 2) * NG / 4;
+            auto half_of = [](const u32x2& x, int gi) -> uint32_t { return (gi & 1) ? (x[gi >> 1] >> 16) : (x[gi >> 1] & 0xFFFFu); };
+            const uint32_t sw = half_of(sv, ga) | (half_of(sv, gb) << 16);
+            const uint32_t zw = half_of(zv, ga) | (half_of(zv, gb) << 16);
+            // scales are non-negative fp16 numbers: their bit patterns order like their values (127.0 = 0x57F0;
+            // Inf and NaN land on the careful side as well)
+            big = big || (sw & 0xFFFFu) > 0x57F0u || (sw >> 16) > 0x57F0u;
+            dsc[g] = as_h2(sw);
+            dzp[g] = as_h2(zw);
         }
-        // dequantize this lane's 32 channels (Section 2: code * Delta + m)
-        float k[4][8];
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t code = (w[g] >> (BITS * i)) & ((1u << BITS) - 1u);
-                k[g][i] = fmaf(static_cast<float>(code), sc[g / CPG], zp[g / CPG]);
-            }
-        // rotate the pairs (chunk g', chunk g' + 2), then move the angles on by 16 positions
-#pragma unroll
-        for (int f = 0; f < 16; ++f) {
-            const int g = f >> 3, i = f & 7;
-            const float a = k[g][i], bb = k[g + 2][i];
-            k[g][i] = fmaf(a, cs[f], -(bb * sn[f]));
-            k[g + 2][i] = fmaf(bb, cs[f], a * sn[f]);
-            const float c2 = fmaf(cs[f], dc[f], -(sn[f] * ds[f]));
-            sn[f] = fmaf(sn[f], dc[f], cs[f] * ds[f]);
-            cs[f] = c2;
-        }
+        // dequantize into rotary pairs (Section 2: code * Delta + m), rotate, and contract
         f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        auto body = [&](auto fast_tag) {
+            constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            u32x4 bop;
+            for (int g = 0; g < 2; ++g) {
+                // source registers: (codes of chunk g + 2 : codes of chunk g), each code below bit 8 of its half
+                uint32_t src[NSRC];
+                if constexpr (BITS == 2) {
+                    src[0] = __builtin_amdgcn_perm(w[g + 2], w[g], half_sel);
+                    src[1] = src[0] >> 8;
+                } else {
+                    src[0] = __builtin_amdgcn_perm(w[g + 2], w[g], 0x05040100u);
+                    src[1] = src[0] >> 8;
+                    src[2] = __builtin_amdgcn_perm(w[g + 2], w[g], 0x07060302u);
+                    src[3] = src[2] >> 8;
+                }
+                const h2 sc9 = FAST ? dsc[g] * h2{static_cast<_Float16>(kCodeScale), static_cast<_Float16>(kCodeScale)} : dsc[g];
+                u32x4 bop[2];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                bop[r] = pack_h2(static_cast<_Float16>(k[g][2 * r]), static_cast<_Float16>(k[g][2 * r + 1]));
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]), __builtin_bit_cast(half8, bop),
-                                                         acc, 0, 0, 0);
-        }
+                for (int i = 0; i < 8; ++i) {
+                    const int sr = i / CPR, pos = i % CPR;
+                    constexpr uint32_t CM = (1u << BITS) - 1u;
+                    const uint32_t bitsv = src[sr] & ((CM | (CM << 16)) << (BITS * pos));
+                    h2 kv;
+                    if constexpr (FAST) {
+                        // the masked bits ARE the fp16 subnormals code * 2^(BITS pos - 24): times 2^(15 - BITS pos)
+                        // gives code * 2^-9 exactly
+                        const _Float16 kf = static_cast<_Float16>(static_cast<float>(1u << (15 - BITS * pos)));
+                        const h2 t = as_h2(bitsv) * h2{kf, kf};
+                        kv = __builtin_elementwise_fma(t, sc9, dzp[g]);
+                    } else {
+                        const float ca = static_cast<float>((bitsv & 0xFFFFu) >> (BITS * pos));
+                        const float cb = static_cast<float>(bitsv >> (16 + BITS * pos));
+                        kv = h2{static_cast<_Float16>(fmaf(ca, static_cast<float>(sc9[0]), static_cast<float>(dzp[g][0]))),
+                                static_cast<_Float16>(fmaf(cb, static_cast<float>(sc9[1]), static_cast<float>(dzp[g][1])))};
+                    }
+                    const h2 xr = rotate_pair(kv, as_h2(tr[2 * g + (i >> 2)][i & 3]));
+                    bop[i >> 2][i & 3] = h2_bits(xr);
+                }
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[2 * g + mm]),
+                                                                 __builtin_bit_cast(half8, bop[mm]), acc, 0, 0, 0);
+            }
+        };
+        if (__builtin_amdgcn_ballot_w64(big) == 0ull)
+            body(std::true_type{});
+        else
+            body(std::false_type{});
         // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
         // two consecutive units fill one 128-byte line of a score row: the first of an (even, odd) pair is
         // kept and stored together with the second (a unit apart they reach memory as partial line writes)
@@ -270,8 +422,6 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
             float* const d0 = out0 + tok;
             float* const d1 = d0 + p.ssh;
             if (pair && (u + 1) * kRopeUnit <= n_tok) {
-                // the usual case, all tests wave-uniform but the lane's rows: four stores, the two halves
-                // of a line in consecutive instructions
                 if (st0) {
                     __builtin_nontemporal_store(held0, d0 - kRopeUnit);
                     __builtin_nontemporal_store(s0, d0);
@@ -294,41 +444,37 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
         }
     };
 
-    // software pipeline; every unit of the range is computed in order (the angles advance with it)
-    Raw ring[kRopeDepth];
+    // software pipeline: the loads of the next epoch's units are in flight while this epoch is computed
+    Raw ring[kEpochUnits];
 #pragma unroll
-    for (int i = 0; i < kRopeDepth; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
-    // whole groups of kRopeDepth units run without a test (a skipped unit inside the loop costs a register
-    // copy per value the loop carries: the 32 angles); the last, shorter group is handled after it
-    int u = u0;
-    for (; u + kRopeDepth <= u1; u += kRopeDepth) {
+    for (int i = 0; i < kEpochUnits; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
+    for (int e = u0; e < u1; e += kEpochUnits) {
+        qs.build(atile, lane, aop);
 #pragma unroll
-        for (int i = 0; i < kRopeDepth; ++i) {
-            const Raw cur = ring[i];
-            fetch(min(u + i + kRopeDepth, u1 - 1), ring[i]);
-            compute(u + i, cur);
+        for (int v = 0; v < kEpochUnits; ++v) {
+            if (e + v < u1) {                             // wave-uniform
+                const Raw cur = ring[v];
+                fetch(min(e + v + kEpochUnits, u1 - 1), ring[v]);
+                compute(e + v, v, cur);
+            }
         }
-    }
-    static_assert(kRopeDepth <= 3, "the tail picks its unit from ring[0] / ring[1]");
-#pragma nounroll
-    for (int i = 0; u + i < u1; ++i) {                    // at most kRopeDepth - 1 units; one copy of the code
-        Raw cur = ring[0];
-        if (i == 1) cur = ring[1];
-        compute(u + i, cur);
     }
 }
 
 // The same against the PER-CHANNEL store (statistics per channel over 32 tokens: codes
 // [tile][channel][BITS words], token j of the tile at bit BITS * (j mod 32 / BITS) of word j / (32 / BITS);
-// scale / zero [tile][channel]).  A wavefront goes over tiles of 32 tokens: the tile's words and metadata come
-// in with contiguous 16-byte loads, pass through a wavefront-private LDS tile, and are consumed as two units of
-// 16 tokens (lane = token of the unit x K block, as above; the lane's 32 channels each give one word per unit).
-// p.n_tokens and p.store_stride are multiples of 32; p.units_per_wave counts TILES here.
+// scale / zero [tile][channel]).  A wavefront goes over tiles of 32 tokens, two per epoch: the tile's words and
+// metadata come in with contiguous 16-byte loads, pass through a wavefront-private LDS tile, and are consumed as two
+// units of 16 tokens (lane = token of the unit x K block, as above).  A rotary pair's two codes come from two
+// channels' words: one v_perm picks the byte that holds the lane's token from both, one v_and leaves the two codes
+// as fp16 subnormals at a lane-constant bit, one packed multiply by a lane-constant power of two normalises them.
+// p.n_tokens and p.store_stride are multiples of 32; p.units_per_wave counts TILES here (a multiple of 2).
 template <int BITS, int QDT>
 __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(const RopeParams p) {
     constexpr int TW = kD * BITS;                         // packed words per tile
     constexpr int NCL = TW / 256;                         // 16-byte code loads per lane and tile
-    constexpr int DEPTH = BITS == 4 ? 2 : kRopeDepth;     // tiles in flight (4-bit tiles take twice the registers)
+    constexpr int DEPTH = 2;                              // tiles in flight = one epoch
+    constexpr uint32_t CM = (1u << BITS) - 1u;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));   // uniform: scalar loop control
@@ -340,70 +486,22 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
 
     constexpr int QLD = kD + 1;
     __shared__ float qlds[8 * QLD];
-    __shared__ float step_cs[2 * 64];
-    {
-        const int e0 = 4 * static_cast<int>(threadIdx.x);
-        const int qrow = e0 / kD, qch = e0 % kD;
-        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (qrow < p.qpk) {
-            const int64_t qoff = b * p.qsb + (static_cast<int64_t>(kvh) * p.qpk + qrow) * p.qsh + qch;
-            if constexpr (QDT == SQUAT_F32) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(p.q + qoff * 4);
-                v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
-            } else {
-                const u32x2 t = *reinterpret_cast<const u32x2*>(p.q + qoff * 2);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t raw = (i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu);
-                    v[i] = QDT == SQUAT_BF16 ? as_f32(raw << 16)
-                                             : static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(raw)));
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qlds[qrow * QLD + qch + i] = v[i];
-        if (threadIdx.x < 64) {
-            float c, s;
-            turn_sincos(static_cast<double>(kRopeUnit), p.inv_freq[threadIdx.x], c, s);
-            step_cs[2 * threadIdx.x] = c;
-            step_cs[2 * threadIdx.x + 1] = s;
-        }
-    }
+    __shared__ float step64[2 * 64];
+    __shared__ __attribute__((aligned(16))) uint32_t trig[kEpochTokens * kTrigLd];
+    __shared__ __attribute__((aligned(16))) uint32_t atiles[kRopeWaves * 16 * kATileLd];
+    stage_queries<QDT>(p, b, kvh, qlds, QLD);
+    fill_trig_tables(p.inv_freq, trig, step64);
     __syncthreads();
 
-    const int qh = col >> 1, part = col & 1;
-    u32x4 aop[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            _Float16 h[2];
-#pragma unroll
-            for (int pp = 0; pp < 2; ++pp) {
-                const float v = qlds[qh * QLD + 32 * g + 8 * kb + 2 * r + pp];
-                const _Float16 hi = static_cast<_Float16>(v);
-                h[pp] = part == 0 ? hi : static_cast<_Float16>(v - static_cast<float>(hi));
-            }
-            aop[g][r] = pack_h2(h[0], h[1]);
-        }
-
-    // ---- this wavefront's tiles
+    // ---- this wavefront's tiles (whole epochs of two)
     const int n_tiles = static_cast<int>(p.n_tokens / 32);
     const int t0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
     const int t1 = min(t0 + p.units_per_wave, n_tiles);
     if (t0 >= t1) return;                                 // after the last workgroup barrier
 
-    float cs[16], sn[16], dc[16], ds[16];
-    {
-        const double position = static_cast<double>(p.pos0 + static_cast<int64_t>(t0) * 32 + col);
-#pragma unroll
-        for (int f = 0; f < 16; ++f) {
-            const int ch = 32 * (f >> 3) + 8 * kb + (f & 7);
-            turn_sincos(position, p.inv_freq[ch], cs[f], sn[f]);
-            dc[f] = step_cs[2 * ch];
-            ds[f] = step_cs[2 * ch + 1];
-        }
-    }
+    uint32_t* atile = atiles + wave * 16 * kATileLd;
+    QuerySide qs;
+    qs.init(qlds, QLD, step64, p.inv_freq, static_cast<double>(p.pos0 + static_cast<int64_t>(t0) * 32), lane, p.qpk, atile);
 
     const int64_t tile0 = bh * (p.store_stride / 32);
     float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
@@ -431,77 +529,98 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
         }
     };
 
-    auto compute = [&](int t, const Raw& raw) {
+    // where the code of this lane's token (16 hf + col of the tile) sits inside a channel's words
+    //   2-bit: word hf, bit 2 col;  4-bit: word 2 hf + (col >> 3), bit 4 (col & 7)
+    const int tbit = BITS == 2 ? 2 * col : 4 * (col & 7);
+    const int wsub = BITS == 2 ? 0 : (col >> 3);
+    const uint32_t bsel = 0x0C000C00u | (static_cast<uint32_t>(4 + (tbit >> 3)) << 16) | static_cast<uint32_t>(tbit >> 3);
+    const int sh = tbit & 7;
+    const uint32_t cmask = (CM | (CM << 16)) << sh;
+    const _Float16 kf = static_cast<_Float16>(static_cast<float>(1u << (15 - sh)));      // code * 2^(sh - 24) -> code * 2^-9
+    const h2 knorm = {kf, kf};
+    const h2 k512 = {static_cast<_Float16>(kCodeScale), static_cast<_Float16>(kCodeScale)};
+
+    u32x4 aop[4];
+    auto compute = [&](int t, int v, const Raw& raw) {
 #pragma unroll
         for (int i = 0; i < NCL; ++i) *reinterpret_cast<u32x4*>(lds + (i * 64 + lane) * 16) = raw.c[i];
         if (is_m) *reinterpret_cast<u32x4*>(lds + TW * 4 + lane * 16) = raw.m;
+        // the lanes that loaded the scales look for one beyond the packed range (scales are non-negative fp16
+        // numbers: bit patterns order like values, 127.0 = 0x57F0)
+        bool big = false;
+        if (lane < 16) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) big = big || (raw.m[w] & 0xFFFFu) > 0x57F0u || (raw.m[w] >> 16) > 0x57F0u;
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // scales and zero-points of this lane's channels 32 g + 8 kb .. + 7 (fp16 pairs)
-        u32x4 sraw[4], zraw[4];
+        const bool fast = __builtin_amdgcn_ballot_w64(big) == 0ull;
+
+        f32x4v acc[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+        auto body = [&](auto fast_tag) {
+            constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            sraw[g] = *reinterpret_cast<const u32x4*>(lds + TW * 4 + (32 * g + 8 * kb) * 2);
-            zraw[g] = *reinterpret_cast<const u32x4*>(lds + TW * 4 + 256 + (32 * g + 8 * kb) * 2);
-        }
-        float res[2][2];
+            for (int g = 0; g < 2; ++g) {
+                // (scale, zero-point) of the two members of pair i: channels 32 g + 8 kb + i and + 64
+                h2 dsc[8], dzp[8];
+                {
+                    const u32x4 sa = *reinterpret_cast<const u32x4*>(lds + TW * 4 + (32 * g + 8 * kb) * 2);
+                    const u32x4 sb = *reinterpret_cast<const u32x4*>(lds + TW * 4 + (32 * g + 64 + 8 * kb) * 2);
+                    const u32x4 za = *reinterpret_cast<const u32x4*>(lds + TW * 4 + 256 + (32 * g + 8 * kb) * 2);
+                    const u32x4 zb = *reinterpret_cast<const u32x4*>(lds + TW * 4 + 256 + (32 * g + 64 + 8 * kb) * 2);
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-            // token 16 hf + col of the tile: word and bit of its code inside a channel's words
-            const int widx = BITS == 2 ? hf : 2 * hf + (col >> 3);
-            const uint32_t bit = BITS == 2 ? 2u * col : 4u * (col & 7);
-            uint32_t w[4][8];
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) w[g][i] = ldsw[(32 * g + 8 * kb + i) * BITS + widx];
-            float k[4][8];
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t sw = sraw[g][i >> 1], zw = zraw[g][i >> 1];
-                    const float sc = static_cast<float>(
-                        __builtin_bit_cast(_Float16, static_cast<uint16_t>((i & 1) ? (sw >> 16) : (sw & 0xFFFFu))));
-                    const float zp = static_cast<float>(
-                        __builtin_bit_cast(_Float16, static_cast<uint16_t>((i & 1) ? (zw >> 16) : (zw & 0xFFFFu))));
-                    const uint32_t code = (w[g][i] >> bit) & ((1u << BITS) - 1u);
-                    k[g][i] = fmaf(static_cast<float>(code), sc, zp);
+                    for (int i = 0; i < 8; ++i) {
+                        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                        const h2 sc = as_h2(__builtin_amdgcn_perm(sb[i >> 1], sa[i >> 1], sel));
+                        dsc[i] = FAST ? sc * k512 : sc;
+                        dzp[i] = as_h2(__builtin_amdgcn_perm(zb[i >> 1], za[i >> 1], sel));
+                    }
                 }
 #pragma unroll
-            for (int f = 0; f < 16; ++f) {
-                const int g = f >> 3, i = f & 7;
-                const float a = k[g][i], bb = k[g + 2][i];
-                k[g][i] = fmaf(a, cs[f], -(bb * sn[f]));
-                k[g + 2][i] = fmaf(bb, cs[f], a * sn[f]);
-                const float c2 = fmaf(cs[f], dc[f], -(sn[f] * ds[f]));
-                sn[f] = fmaf(sn[f], dc[f], cs[f] * ds[f]);
-                cs[f] = c2;
-            }
-            f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                for (int hf = 0; hf < 2; ++hf) {
+                    const uint32_t* trow = trig + (2 * kRopeUnit * v + kRopeUnit * hf + col) * kTrigLd + kb * 16 + 8 * g;
+                    const u32x4 tr0 = *reinterpret_cast<const u32x4*>(trow);
+                    const u32x4 tr1 = *reinterpret_cast<const u32x4*>(trow + 4);
+                    u32x4 bop[2];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                u32x4 bop;
+                    for (int i = 0; i < 8; ++i) {
+                        const int ca = 32 * g + 8 * kb + i;
+                        const uint32_t wa = ldsw[ca * BITS + (BITS / 2) * hf + wsub];
+                        const uint32_t wb = ldsw[(ca + 64) * BITS + (BITS / 2) * hf + wsub];
+                        const uint32_t pr = __builtin_amdgcn_perm(wb, wa, bsel) & cmask;
+                        h2 kv;
+                        if constexpr (FAST) {
+                            kv = __builtin_elementwise_fma(as_h2(pr) * knorm, dsc[i], dzp[i]);
+                        } else {
+                            const float fa = static_cast<float>((pr & 0xFFFFu) >> sh);
+                            const float fb = static_cast<float>(pr >> (16 + sh));
+                            kv = h2{static_cast<_Float16>(fmaf(fa, static_cast<float>(dsc[i][0]), static_cast<float>(dzp[i][0]))),
+                                    static_cast<_Float16>(fmaf(fb, static_cast<float>(dsc[i][1]), static_cast<float>(dzp[i][1])))};
+                        }
+                        const uint32_t cs = i < 4 ? tr0[i & 3] : tr1[i & 3];
+                        bop[i >> 2][i & 3] = h2_bits(rotate_pair(kv, as_h2(cs)));
+                    }
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    bop[r] = pack_h2(static_cast<_Float16>(k[g][2 * r]), static_cast<_Float16>(k[g][2 * r + 1]));
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]),
-                                                             __builtin_bit_cast(half8, bop), acc, 0, 0, 0);
+                    for (int mm = 0; mm < 2; ++mm)
+                        acc[hf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[2 * g + mm]),
+                                                                         __builtin_bit_cast(half8, bop[mm]), acc[hf], 0, 0, 0);
+                }
             }
-            res[hf][0] = fin * (acc[0] + acc[1]);
-            res[hf][1] = fin * (acc[2] + acc[3]);
-            __builtin_amdgcn_sched_barrier(0);            // keep the halves apart: interleaved they need > 256 registers
-        }
+        };
+        if (fast)
+            body(std::true_type{});
+        else
+            body(std::false_type{});
         // both halves of the group's 128-byte line of a score row, back to back
         const int64_t tok = static_cast<int64_t>(t) * 32 + col;
         if (st0) {
-            __builtin_nontemporal_store(res[0][0], out0 + tok);
-            __builtin_nontemporal_store(res[1][0], out0 + tok + 16);
+            __builtin_nontemporal_store(fin * (acc[0][0] + acc[0][1]), out0 + tok);
+            __builtin_nontemporal_store(fin * (acc[1][0] + acc[1][1]), out0 + tok + 16);
         }
         if (st1) {
-            __builtin_nontemporal_store(res[0][1], out0 + p.ssh + tok);
-            __builtin_nontemporal_store(res[1][1], out0 + p.ssh + tok + 16);
+            __builtin_nontemporal_store(fin * (acc[0][2] + acc[0][3]), out0 + p.ssh + tok);
+            __builtin_nontemporal_store(fin * (acc[1][2] + acc[1][3]), out0 + p.ssh + tok + 16);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -511,21 +630,16 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
     Raw ring[DEPTH];
 #pragma unroll
     for (int i = 0; i < DEPTH; ++i) fetch(min(t0 + i, t1 - 1), ring[i]);
-    int t = t0;                                           // whole groups of DEPTH tiles, then the shorter last one
-    for (; t + DEPTH <= t1; t += DEPTH) {
+    for (int e = t0; e < t1; e += DEPTH) {
+        qs.build(atile, lane, aop);
 #pragma unroll
-        for (int i = 0; i < DEPTH; ++i) {
-            const Raw cur = ring[i];
-            fetch(min(t + i + DEPTH, t1 - 1), ring[i]);
-            compute(t + i, cur);
+        for (int v = 0; v < DEPTH; ++v) {
+            if (e + v < t1) {                             // wave-uniform
+                const Raw cur = ring[v];
+                fetch(min(e + v + DEPTH, t1 - 1), ring[v]);
+                compute(e + v, v, cur);
+            }
         }
-    }
-    static_assert(DEPTH <= 3, "the tail picks its tile from ring[0] / ring[1]");
-#pragma nounroll
-    for (int i = 0; t + i < t1; ++i) {                    // at most DEPTH - 1 tiles; one copy of the code
-        Raw cur = ring[0];
-        if (i == 1) cur = ring[1];
-        compute(t + i, cur);
     }
 }
 
@@ -615,7 +729,7 @@ int squat::key_scores_rope_from(const uint32_t* codes, const uint16_t* scale, co
     if (gx < 1) gx = 1;
     int64_t upw = (n_units + kRopeWaves * gx - 1) / (kRopeWaves * gx);
     if (upw < kRopeMinUnitsPerWave) upw = kRopeMinUnitsPerWave;
-    upw += upw & 1;                                       // even: every wavefront's range starts on a 32-token line
+    upw = (upw + kEpochUnits - 1) / kEpochUnits * kEpochUnits;       // whole epochs: a range starts where the query-side operand changes
     p.units_per_wave = static_cast<int>(upw);
     gx = (n_units + kRopeWaves * upw - 1) / (kRopeWaves * upw);
     const int64_t bh = n_batch * n_kv_heads;
@@ -693,6 +807,7 @@ int squat::key_scores_pc_rope_from(const uint32_t* codes, const uint16_t* scale,
     if (gx < 1) gx = 1;
     int64_t tpw = (n_tiles + kRopeWaves * gx - 1) / (kRopeWaves * gx);
     if (tpw < kRopeMinUnitsPerWave / 2) tpw = kRopeMinUnitsPerWave / 2;
+    tpw += tpw & 1;                                       // whole epochs of two tiles
     p.units_per_wave = static_cast<int>(tpw);
     gx = (n_tiles + kRopeWaves * tpw - 1) / (kRopeWaves * tpw);
     const int64_t bh = n_batch * n_kv_heads;
