@@ -55,6 +55,7 @@ struct ScoreParams {
     int qpk;
     float out_scale;
     int units_per_wave;
+    int wide_loads;                  // rows of the store are 16-byte aligned: whole units are fetched with 16-byte loads
 };
 
 __device__ __forceinline__ uint32_t pack_halves(_Float16 lo, _Float16 hi) {
@@ -109,8 +110,10 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     }
     __syncthreads();
 
-    // ---- A operands: row `col` = (query head col / 2, part col % 2); K = 8 kb + 2 j + pp
-    const int qh = col >> 1, part = col & 1;
+    // ---- A operands.  Result row 4 kb + i belongs to query head kb + 4 (i >> 1), part i & 1 (high or low
+    // half of the fp16 split), so that with up to four query heads every lane of the result holds exactly
+    // one of them; K = 8 kb + 2 j + pp.
+    const int qh = (col >> 2) + 4 * ((col >> 1) & 1), part = col & 1;
     const bool row_live = qh < p.qpk;
     // Wavefront w builds the operand of chunk w (and that chunk's sum of q per row); the four share them
     // through LDS.
@@ -155,105 +158,86 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         aop[g] = aop_lds[g * kWave + lane];
         csum[g] = csum_lds[g * kWave + lane];
     }
-    // group sums of q as an fp16 high/low pair in K = 2 g + {0, 1} of the rows of part 0; every other
-    // entry of this operand is zero
+    // Zero-points: one more matrix product per unit, K = g.  The B operand is the token's stored zero-points
+    // as they lie in memory (K = g in K block 0; the other K blocks hold the same numbers and meet zero rows
+    // here); the A operand carries the group sums of q, their fp16 high part in the rows of part 0 and the
+    // low part in the rows of part 1, which are added after the product anyway.
     u32x4 azp = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        float s = 0.0f;
+    for (int i = 0; i < (NG + 1) / 2; ++i) {
+        _Float16 h[2] = {static_cast<_Float16>(0.0f), static_cast<_Float16>(0.0f)};
 #pragma unroll
-        for (int c = 0; c < CPG; ++c) s += csum[g * CPG + c];
-        const _Float16 hi = static_cast<_Float16>(s);
-        const _Float16 lo = static_cast<_Float16>(s - static_cast<float>(hi));
-        azp[g] = (kb == 0 && part == 0) ? pack_halves(hi, lo) : 0u;
+        for (int e = 0; e < 2; ++e) {
+            const int g = 2 * i + e;
+            if (g < NG) {
+                float s = 0.0f;
+#pragma unroll
+                for (int c = 0; c < CPG; ++c) s += csum[g * CPG + c];
+                const _Float16 hi = static_cast<_Float16>(s);
+                h[e] = part == 0 ? hi : static_cast<_Float16>(s - static_cast<float>(hi));
+            }
+        }
+        azp[i] = kb == 0 ? pack_halves(h[0], h[1]) : 0u;
     }
 
     // ---- stream the 16-token units of this wavefront
-    const int n_units = static_cast<int>((p.n_tokens + kUnitTokens - 1) / kUnitTokens);
+    // 32-bit token indices inside this (batch, KV head): the host rejects sequences of 2^25 tokens or more
+    const int n_tok = static_cast<int>(p.n_tokens);
+    const int n_units = (n_tok + kUnitTokens - 1) / kUnitTokens;
     const int u0 = (static_cast<int>(blockIdx.x) * kScoreWaves + wave) * p.units_per_wave;
     const int u1 = min(u0 + p.units_per_wave, n_units);
+    if (u0 >= u1) return;
     const int64_t row0 = bh * p.store_stride;
     const int widx0 = BITS == 2 ? (kb >> 1) : kb;          // word of chunk 0 this lane unpacks
     // right-rotations that bring this lane's codes to bits 6..9 of both halves: 2-bit, codes c0, c0 + 1
     // (c0 = 4 (kb & 1), at bits 2 c0) then c0 + 2, c0 + 3; a rotation by 32 - k is a left shift by k
     const uint32_t rot_a = (kb & 1) ? 2u : 26u, rot_b = (kb & 1) ? 6u : 30u;
-    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
-    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    const bool two = p.qpk > 4;                           // a lane holds a second query head (kb + 4)
+    const bool st0 = kb < p.qpk, st1 = kb + 4 < p.qpk;
+    float* const out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + kb) * p.ssh;
+    const int64_t out1 = 4 * p.ssh;
     const float fin = p.out_scale;
 
-    // Loads: as few vector-memory instructions as possible (they, not bytes or arithmetic, bound this
-    // kernel when every lane fetches its own 4-byte words): per unit ONE 16-byte load by the lanes that
-    // cover the unit's codes (contiguous in memory) and ONE load of the scales and zero-points, landed
-    // in a small per-wavefront LDS tile from which every lane then picks the words of its K block.
+    // A unit's packed words (16 tokens x WPK words, contiguous in memory) and its scales and zero-points (two
+    // contiguous runs of 32 NG bytes) pass through a small per-wavefront LDS tile, from which every lane picks
+    // the words of its K block and the metadata of its token.
     constexpr int PPT = WPK / 4;                          // 16-byte pieces of codes per token
     constexpr int CL = kUnitTokens * PPT;                 // lanes that load codes (32 or 64)
+    constexpr int MP = 2 * NG;                            // 16-byte pieces of scales (and of zero-points) per unit
     constexpr int CS = WPK * 4 + 16;                      // LDS bytes per token of codes (padded)
-    constexpr int META0 = kUnitTokens * CS;               // scales at META0 + 8 t, zero-points 128 bytes later
-    constexpr int TILE = META0 + 256;
+    constexpr int META0 = kUnitTokens * CS;               // scales: 2 NG bytes per token from META0, zero-points from ZOFF
+    constexpr int ZOFF = META0 + MP * 16;
+    constexpr int SPARE = META0 + 256;                    // 16 bytes per lane for the lanes with nothing to deliver
+    constexpr int TILE = SPARE + kWave * 16;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[kScoreWaves * TILE];
     unsigned char* lds = lds_all + wave * TILE;
-    struct Raw {
-        u32x4 c;
-        u32x2 m;
-    };
-    // 32-bit token indices inside this (batch, KV head): the host rejects sequences of 2^25 tokens or more
-    const int n_tok = static_cast<int>(p.n_tokens);
-    const int ml = BITS == 2 ? lane - 32 : lane;          // index among the lanes that load metadata
-    const bool is_c = lane < CL, is_m = ml >= 0 && ml < 32;
-    const int c_tok = lane / PPT, c_piece = lane % PPT;
-    const int m_tok = ml & 15;
-    const uint32_t* c_base = p.codes + row0 * WPK + c_piece * 4;
-    const uint16_t* m_base = ((ml & 16) ? p.zero : p.scale) + row0 * NG;
-    // units past the end of this wavefront's range re-read its last unit (never used); rows past the end
-    // of the keys re-read the last key
-    auto fetch = [&](int u, Raw& r) {
-        r.c = u32x4{0u, 0u, 0u, 0u};
-        r.m = u32x2{0u, 0u};
-        if (is_c) {
-            const int t = min(u * kUnitTokens + c_tok, n_tok - 1);
-            r.c = SC_LOAD(reinterpret_cast<const u32x4*>(c_base + static_cast<uint32_t>(t) * WPK));
-        }
-        if (is_m) {
-            const int t = min(u * kUnitTokens + m_tok, n_tok - 1);
-            if constexpr (NG == 4) {
-                r.m = SC_LOAD(reinterpret_cast<const u32x2*>(m_base + static_cast<uint32_t>(t) * 4));
-            } else if constexpr (NG == 2) {
-                r.m[0] = SC_LOAD(reinterpret_cast<const uint32_t*>(m_base + static_cast<uint32_t>(t) * 2));
-            } else {
-                r.m[0] = SC_LOAD(m_base + static_cast<uint32_t>(t));
-            }
-        }
-    };
-    struct Words {
-        uint32_t w[4];
-        uint32_t sraw[2], zraw[2];
-    };
-    // registers -> LDS tile -> the words of this lane's K block, the scales and zero-points of its token
-    auto redistribute = [&](const Raw& r, Words& o) {
-        if (is_c) *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) = r.c;
-        if (is_m) *reinterpret_cast<u32x2*>(lds + META0 + (ml & 16) * 8 + m_tok * 8) = r.m;
+
+    // tile -> logits of the lane's token for the lane's query head(s)
+    auto unit_scores = [&](float& s0, float& s1) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t w[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-            o.w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4);
-        const u32x2 sv = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
-        const u32x2 zv = *reinterpret_cast<const u32x2*>(lds + META0 + 128 + col * 8);
-        o.sraw[0] = sv[0]; o.sraw[1] = sv[1];
-        o.zraw[0] = zv[0]; o.zraw[1] = zv[1];
+            w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4);
+        uint32_t sraw[2] = {0u, 0u}, zraw[2] = {0u, 0u};
+        if constexpr (NG == 4) {
+            const u32x2 sv = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
+            const u32x2 zv = *reinterpret_cast<const u32x2*>(lds + ZOFF + col * 8);
+            sraw[0] = sv[0]; sraw[1] = sv[1];
+            zraw[0] = zv[0]; zraw[1] = zv[1];
+        } else if constexpr (NG == 2) {
+            sraw[0] = *reinterpret_cast<const uint32_t*>(lds + META0 + col * 4);
+            zraw[0] = *reinterpret_cast<const uint32_t*>(lds + ZOFF + col * 4);
+        } else {
+            sraw[0] = *reinterpret_cast<const uint16_t*>(lds + META0 + col * 2);
+            zraw[0] = *reinterpret_cast<const uint16_t*>(lds + ZOFF + col * 2);
+        }
+        // the next unit's tile must not overtake these reads
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-    float held0 = 0.0f, held1 = 0.0f;
-    auto compute = [&](int u, const Raw& raw) {
-        const int tok = u * kUnitTokens + col;
-        Words wd;
-        redistribute(raw, wd);
-        const uint32_t* w = wd.w;
-        const uint32_t* sraw = wd.sraw;
-        const uint32_t* zraw = wd.zraw;
         f32x4v acc[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) acc[g] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
@@ -274,88 +258,165 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
             acc[g / CPG] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[g]),
                                                                   __builtin_bit_cast(half8, bop), acc[g / CPG], 0, 0, 0);
         }
-        // zero-points: K = 2 g + {0, 1} both hold m_g (the other K blocks meet zero rows of the A operand)
-        u32x4 zop = {0u, 0u, 0u, 0u};
-        zop[0] = __builtin_amdgcn_perm(zraw[0], zraw[0], 0x01000100u);
-        if constexpr (NG >= 2) zop[1] = __builtin_amdgcn_perm(zraw[0], zraw[0], 0x03020302u);
-        if constexpr (NG == 4) {
-            zop[2] = __builtin_amdgcn_perm(zraw[1], zraw[1], 0x01000100u);
-            zop[3] = __builtin_amdgcn_perm(zraw[1], zraw[1], 0x03020302u);
-        }
+        const u32x4 zop = {zraw[0], zraw[1], 0u, 0u};
         f32x4v zacc = {0.0f, 0.0f, 0.0f, 0.0f};
         zacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, azp), __builtin_bit_cast(half8, zop),
                                                       zacc, 0, 0, 0);
-        // Delta of this lane's token scales each group's result
-        f32x4v r = {0.0f, 0.0f, 0.0f, 0.0f};
+        // Delta of this lane's token scales each group's result.  The conversions are kept apart from the
+        // multiply-adds on purpose: the mixed-precision multiply-add the compiler would fuse them into issues
+        // at half the rate of a plain one.
+        float sc[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             const uint32_t word = sraw[g >> 1];
-            const float sc = static_cast<float>(
+            sc[g] = static_cast<float>(
                 __builtin_bit_cast(_Float16, static_cast<uint16_t>((g & 1) ? (word >> 16) : (word & 0xFFFFu))));
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = fmaf(sc, acc[g][i], r[i]);
+            asm volatile("" : "+v"(sc[g]));
         }
-        // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
-        const float s0 = fin * (fmaf(DESCALE, r[0] + r[1], zacc[0] + zacc[1]));
-        const float s1 = fin * (fmaf(DESCALE, r[2] + r[3], zacc[2] + zacc[3]));
-        // Two consecutive units fill one 128-byte line of a score row: the first unit of an (even, odd) pair
-        // keeps its results until the second one is done, and both halves are stored back to back (stored
-        // a unit apart, the halves reach memory as two partial line writes).
-        if ((u & 1) == 0 && u + 1 < u1) {
-            held0 = s0;
-            held1 = s1;
-        } else {
-            const bool pair = (u & 1) && u > u0;          // the held unit is complete: u exists
-            float* const d0 = out0 + tok;
-            float* const d1 = d0 + p.ssh;
-            if (pair && (u + 1) * kUnitTokens <= n_tok) {
-                // the usual case, all tests wave-uniform but the lane's rows: four stores, the two halves
-                // of a line in consecutive instructions
-                if (st0) {
-                    __builtin_nontemporal_store(held0, d0 - kUnitTokens);
-                    __builtin_nontemporal_store(s0, d0);
-                }
-                if (st1) {
-                    __builtin_nontemporal_store(held1, d1 - kUnitTokens);
-                    __builtin_nontemporal_store(s1, d1);
-                }
-            } else {
-                const bool mine = tok < n_tok;
-                if (st0) {
-                    if (pair) __builtin_nontemporal_store(held0, d0 - kUnitTokens);
-                    if (mine) __builtin_nontemporal_store(s0, d0);
-                }
-                if (st1) {
-                    if (pair) __builtin_nontemporal_store(held1, d1 - kUnitTokens);
-                    if (mine) __builtin_nontemporal_store(s1, d1);
-                }
+        // rows 4 kb + {0, 1}: high and low part of query head kb; rows + {2, 3}: query head kb + 4
+        {
+            float r0 = sc[0] * acc[0][0], r1 = sc[0] * acc[0][1];
+#pragma unroll
+            for (int g = 1; g < NG; ++g) {
+                r0 = fmaf(sc[g], acc[g][0], r0);
+                r1 = fmaf(sc[g], acc[g][1], r1);
             }
+            s0 = fin * (fmaf(DESCALE, r0 + r1, zacc[0] + zacc[1]));
+        }
+        if (two) {
+            float r2 = sc[0] * acc[0][2], r3 = sc[0] * acc[0][3];
+#pragma unroll
+            for (int g = 1; g < NG; ++g) {
+                r2 = fmaf(sc[g], acc[g][2], r2);
+                r3 = fmaf(sc[g], acc[g][3], r3);
+            }
+            s1 = fin * (fmaf(DESCALE, r2 + r3, zacc[2] + zacc[3]));
         }
     };
 
-    // software pipeline: the loads of kDepth units are in flight while one is being computed
-    if (u0 >= u1) return;
-    Raw ring[kDepth];
-#pragma unroll
-    for (int i = 0; i < kDepth; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
-    // whole groups of kDepth units run without a test (a skipped unit inside the loop costs a register copy
-    // per value the loop carries); the last, shorter group is handled after it
-    int u = u0;
-    for (; u + kDepth <= u1; u += kDepth) {
+    // ---- whole units, in pairs: one 16-byte load per lane and unit (a second one for the metadata of 4-bit
+    // stores), contiguous over the wavefront, kDepth units in flight.  Lanes left over after the codes and the
+    // metadata repeat a neighbour's load and drop it into a spare LDS slot: no lane tests in the loop.
+    const int n_full = n_tok / kUnitTokens;
+    int nf = 0;
+    if (p.wide_loads) nf = max(min(u1, n_full) - u0, 0) & ~1;
+    const int uf = u0 + nf;
+    if (nf > 0) {
+        const int64_t trow = row0 + static_cast<int64_t>(u0) * kUnitTokens;
+        const int ml = BITS == 2 ? (lane - 32) & 31 : lane;              // index among the lanes that may load metadata
+        const int mm = ml & (2 * MP - 1);
+        const unsigned char* mptr = reinterpret_cast<const unsigned char*>(mm >= MP ? p.zero : p.scale) +
+                                    trow * (2 * NG) + (mm & (MP - 1)) * 16;
+        const int m_lds = ml < 2 * MP ? META0 + mm * 16 : SPARE + lane * 16;
+        const unsigned char* cptr = reinterpret_cast<const unsigned char*>(p.codes) + trow * (WPK * 4) + lane * 16;
+        const int c_lds = (lane / PPT) * CS + (lane % PPT) * 16;
+        // 2-bit: lanes 0..31 deliver codes, lanes 32.. metadata, with one instruction
+        const bool code_lane = BITS == 4 || lane < CL;
+        const unsigned char* gp = code_lane ? cptr : mptr;
+        const uint32_t gstep = code_lane ? kUnitTokens * WPK * 4 : kUnitTokens * 2 * NG;
+        const int g_lds = code_lane ? c_lds : m_lds;
+        struct Raw {
+            u32x4 c;
+            u32x4 m;
+        };
+        Raw ring[kDepth];
+        auto fetch = [&](Raw& r) {
+            r.c = SC_LOAD(reinterpret_cast<const u32x4*>(gp));
+            gp += gstep;
+            if constexpr (BITS == 4) {
+                r.m = SC_LOAD(reinterpret_cast<const u32x4*>(mptr));
+                mptr += kUnitTokens * 2 * NG;
+            }
+        };
+        auto deliver = [&](const Raw& r) {
+            *reinterpret_cast<u32x4*>(lds + g_lds) = r.c;
+            if constexpr (BITS == 4) *reinterpret_cast<u32x4*>(lds + m_lds) = r.m;
+        };
 #pragma unroll
         for (int i = 0; i < kDepth; ++i) {
-            const Raw cur = ring[i];
-            fetch(min(u + i + kDepth, u1 - 1), ring[i]);
-            compute(u + i, cur);
+            ring[i].c = u32x4{0u, 0u, 0u, 0u};
+            ring[i].m = u32x4{0u, 0u, 0u, 0u};
+            if (i < nf) fetch(ring[i]);
+        }
+        float* optr = out0 + static_cast<int64_t>(u0) * kUnitTokens + col;
+        float held0 = 0.0f, held1 = 0.0f;
+        // Two consecutive units fill one 128-byte line of a score row: the first unit of a pair keeps its results
+        // until the second one is done, and both halves are stored back to back (stored a unit apart, the halves
+        // reach memory as two partial line writes).
+        auto pair_step = [&](int i, bool more) {
+            float s0 = 0.0f, s1 = 0.0f;
+            deliver(ring[i]);
+            if (more) fetch(ring[i]);
+            unit_scores(s0, s1);
+            if ((i & 1) == 0) {
+                held0 = s0;
+                held1 = s1;
+            } else {
+                if (st0) {
+                    __builtin_nontemporal_store(held0, optr);
+                    __builtin_nontemporal_store(s0, optr + kUnitTokens);
+                }
+                if (st1) {
+                    __builtin_nontemporal_store(held1, optr + out1);
+                    __builtin_nontemporal_store(s1, optr + out1 + kUnitTokens);
+                }
+                optr += 2 * kUnitTokens;
+            }
+        };
+        static_assert(kDepth % 2 == 0, "pairs of units");
+        int u = u0;
+        for (; u + kDepth <= uf; u += kDepth) {
+#pragma unroll
+            for (int i = 0; i < kDepth; ++i) pair_step(i, u + i + kDepth < uf);
+        }
+        // nf is even: an even number of units below kDepth is left, all of them in flight
+#pragma unroll
+        for (int i = 0; i < kDepth - 2; i += 2) {
+            if (u + i < uf) {
+                pair_step(i, false);
+                pair_step(i + 1, false);
+            }
         }
     }
-    static_assert(kDepth <= 4, "the tail picks its unit from ring[0] .. ring[2]");
+
+    // ---- what is left: a single unit after the pairs, the ragged end of the sequence, or everything when the
+    // store's rows are not aligned for the wide loads.  Every lane fetches for itself; rows past the end of the
+    // keys re-read the last key and are not stored.
+    {
+        const int sl = BITS == 2 ? lane - 32 : lane;          // index among the lanes that load metadata
+        const bool is_c = lane < CL, is_m = sl >= 0 && sl < 32;
+        const int c_tok = lane / PPT, c_piece = lane % PPT;
+        const int m_tok = sl & 15;
+        const uint32_t* c_base = p.codes + row0 * WPK + c_piece * 4;
+        const uint16_t* m_base = ((sl & 16) ? p.zero : p.scale) + row0 * NG;
+        unsigned char* m_dst = lds + ((sl & 16) ? ZOFF : META0) + m_tok * (2 * NG);
 #pragma nounroll
-    for (int i = 0; u + i < u1; ++i) {                    // at most kDepth - 1 units; one copy of the code
-        Raw cur = ring[0];
-        if (i == 1) cur = ring[1];
-        if (i == 2) cur = ring[2];
-        compute(u + i, cur);
+        for (int u = uf; u < u1; ++u) {
+            if (is_c) {
+                const int t = min(u * kUnitTokens + c_tok, n_tok - 1);
+                *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) =
+                    SC_LOAD(reinterpret_cast<const u32x4*>(c_base + static_cast<uint32_t>(t) * WPK));
+            }
+            if (is_m) {
+                const int t = min(u * kUnitTokens + m_tok, n_tok - 1);
+                if constexpr (NG == 4) {
+                    *reinterpret_cast<u32x2*>(m_dst) =
+                        SC_LOAD(reinterpret_cast<const u32x2*>(m_base + static_cast<uint32_t>(t) * 4));
+                } else if constexpr (NG == 2) {
+                    *reinterpret_cast<uint32_t*>(m_dst) =
+                        SC_LOAD(reinterpret_cast<const uint32_t*>(m_base + static_cast<uint32_t>(t) * 2));
+                } else {
+                    *reinterpret_cast<uint16_t*>(m_dst) = SC_LOAD(m_base + static_cast<uint32_t>(t));
+                }
+            }
+            float s0 = 0.0f, s1 = 0.0f;
+            unit_scores(s0, s1);
+            const int tok = u * kUnitTokens + col;
+            if (tok < n_tok) {
+                if (st0) __builtin_nontemporal_store(s0, out0 + tok);
+                if (st1) __builtin_nontemporal_store(s1, out0 + out1 + tok);
+            }
+        }
     }
 }
 
@@ -421,6 +482,10 @@ int squat::key_scores_from(const uint32_t* codes, const uint16_t* scale, const u
     p.n_kv_heads = n_kv_heads;
     p.qpk = q_per_kv;
     p.out_scale = out_scale;
+    {
+        const int64_t meta_row = 2 * (128 / group);       // bytes of scales (or zero-points) per key
+        p.wide_loads = (store_stride * meta_row) % 16 == 0 && aligned(scale, 16) && aligned(zero, 16);
+    }
 
     const int64_t n_units = (n_tokens + kUnitTokens - 1) / kUnitTokens;
     // Workgroups along the sequence: about kScoreWaves * kMaxUnitsPerWave units each, the count rounded to
