@@ -82,6 +82,68 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     const int64_t b = bh / p.n_kv_heads;
     const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
 
+    // ---- this wavefront's 16-token units; the loads of its first units are issued before anything else, so
+    // that their latency overlaps the set-up of the query-side operands
+    // 32-bit token indices inside this (batch, KV head): the host rejects sequences of 2^25 tokens or more
+    const int n_tok = static_cast<int>(p.n_tokens);
+    const int n_units = (n_tok + kUnitTokens - 1) / kUnitTokens;
+    const int u0 = (static_cast<int>(blockIdx.x) * kScoreWaves + wave) * p.units_per_wave;
+    const int u1 = min(u0 + p.units_per_wave, n_units);
+    const int64_t row0 = bh * p.store_stride;
+    // A unit's packed words (16 tokens x WPK words, contiguous in memory) and its scales and zero-points (two
+    // contiguous runs of 32 NG bytes) pass through a small per-wavefront LDS tile, from which every lane picks
+    // the words of its K block and the metadata of its token.
+    constexpr int PPT = WPK / 4;                          // 16-byte pieces of codes per token
+    constexpr int CL = kUnitTokens * PPT;                 // lanes that load codes (32 or 64)
+    constexpr int MP = 2 * NG;                            // 16-byte pieces of scales (and of zero-points) per unit
+    constexpr int CS = WPK * 4 + 16;                      // LDS bytes per token of codes (padded)
+    constexpr int META0 = kUnitTokens * CS;               // scales: 2 NG bytes per token from META0, zero-points from ZOFF
+    constexpr int ZOFF = META0 + MP * 16;
+    constexpr int SPARE = META0 + 256;                    // 16 bytes per lane for the lanes with nothing to deliver
+    constexpr int TILE = SPARE + kWave * 16;
+    // Whole units, in pairs: one 16-byte load per lane and unit (a second one for the metadata of 4-bit stores),
+    // contiguous over the wavefront, kDepth units in flight.  Lanes left over after the codes and the metadata
+    // repeat a neighbour's load and drop it into a spare LDS slot: no lane tests in the loop.
+    const int n_full = n_tok / kUnitTokens;
+    int nf = 0;
+    if (p.wide_loads) nf = max(min(u1, n_full) - u0, 0) & ~1;
+    const int uf = u0 + nf;
+    const int ml = BITS == 2 ? (lane - 32) & 31 : lane;   // index among the lanes that may load metadata
+    const int mm = ml & (2 * MP - 1);
+    const int m_lds = ml < 2 * MP ? META0 + mm * 16 : SPARE + lane * 16;
+    const int c_lds = (lane / PPT) * CS + (lane % PPT) * 16;
+    // 2-bit: lanes 0..31 deliver codes, lanes 32.. metadata, with one instruction
+    const bool code_lane = BITS == 4 || lane < CL;
+    const int g_lds = code_lane ? c_lds : m_lds;
+    const uint32_t gstep = code_lane ? kUnitTokens * WPK * 4 : kUnitTokens * 2 * NG;
+    const unsigned char* mptr;
+    const unsigned char* gp;
+    {
+        const int64_t trow = row0 + static_cast<int64_t>(u0) * kUnitTokens;
+        mptr = reinterpret_cast<const unsigned char*>(mm >= MP ? p.zero : p.scale) + trow * (2 * NG) + (mm & (MP - 1)) * 16;
+        const unsigned char* cptr = reinterpret_cast<const unsigned char*>(p.codes) + trow * (WPK * 4) + lane * 16;
+        gp = code_lane ? cptr : mptr;
+    }
+    struct Raw {
+        u32x4 c;
+        u32x4 m;
+    };
+    Raw ring[kDepth];
+    auto fetch = [&](Raw& r) {
+        r.c = SC_LOAD(reinterpret_cast<const u32x4*>(gp));
+        gp += gstep;
+        if constexpr (BITS == 4) {
+            r.m = SC_LOAD(reinterpret_cast<const u32x4*>(mptr));
+            mptr += kUnitTokens * 2 * NG;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kDepth; ++i) {
+        ring[i].c = u32x4{0u, 0u, 0u, 0u};
+        ring[i].m = u32x4{0u, 0u, 0u, 0u};
+        if (i < nf) fetch(ring[i]);
+    }
+
     // ---- the KV head's queries -> LDS as fp32 (one wide load per thread instead of 32 two-byte loads per
     // lane: vector-memory instructions are what this kernel runs out of first)
     constexpr int QLD = kD + 1;                           // row stride in floats (odd: spreads the banks)
@@ -180,14 +242,8 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         azp[i] = kb == 0 ? pack_halves(h[0], h[1]) : 0u;
     }
 
-    // ---- stream the 16-token units of this wavefront
-    // 32-bit token indices inside this (batch, KV head): the host rejects sequences of 2^25 tokens or more
-    const int n_tok = static_cast<int>(p.n_tokens);
-    const int n_units = (n_tok + kUnitTokens - 1) / kUnitTokens;
-    const int u0 = (static_cast<int>(blockIdx.x) * kScoreWaves + wave) * p.units_per_wave;
-    const int u1 = min(u0 + p.units_per_wave, n_units);
+    // ---- stream the units
     if (u0 >= u1) return;
-    const int64_t row0 = bh * p.store_stride;
     const int widx0 = BITS == 2 ? (kb >> 1) : kb;          // word of chunk 0 this lane unpacks
     // right-rotations that bring this lane's codes to bits 6..9 of both halves: 2-bit, codes c0, c0 + 1
     // (c0 = 4 (kb & 1), at bits 2 c0) then c0 + 2, c0 + 3; a rotation by 32 - k is a left shift by k
@@ -198,17 +254,6 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
     const int64_t out1 = 4 * p.ssh;
     const float fin = p.out_scale;
 
-    // A unit's packed words (16 tokens x WPK words, contiguous in memory) and its scales and zero-points (two
-    // contiguous runs of 32 NG bytes) pass through a small per-wavefront LDS tile, from which every lane picks
-    // the words of its K block and the metadata of its token.
-    constexpr int PPT = WPK / 4;                          // 16-byte pieces of codes per token
-    constexpr int CL = kUnitTokens * PPT;                 // lanes that load codes (32 or 64)
-    constexpr int MP = 2 * NG;                            // 16-byte pieces of scales (and of zero-points) per unit
-    constexpr int CS = WPK * 4 + 16;                      // LDS bytes per token of codes (padded)
-    constexpr int META0 = kUnitTokens * CS;               // scales: 2 NG bytes per token from META0, zero-points from ZOFF
-    constexpr int ZOFF = META0 + MP * 16;
-    constexpr int SPARE = META0 + 256;                    // 16 bytes per lane for the lanes with nothing to deliver
-    constexpr int TILE = SPARE + kWave * 16;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[kScoreWaves * TILE];
     unsigned char* lds = lds_all + wave * TILE;
 
@@ -294,50 +339,12 @@ __global__ void __launch_bounds__(kScoreWaves* kWave) key_scores_kernel(const Sc
         }
     };
 
-    // ---- whole units, in pairs: one 16-byte load per lane and unit (a second one for the metadata of 4-bit
-    // stores), contiguous over the wavefront, kDepth units in flight.  Lanes left over after the codes and the
-    // metadata repeat a neighbour's load and drop it into a spare LDS slot: no lane tests in the loop.
-    const int n_full = n_tok / kUnitTokens;
-    int nf = 0;
-    if (p.wide_loads) nf = max(min(u1, n_full) - u0, 0) & ~1;
-    const int uf = u0 + nf;
+    // ---- whole units, in pairs
     if (nf > 0) {
-        const int64_t trow = row0 + static_cast<int64_t>(u0) * kUnitTokens;
-        const int ml = BITS == 2 ? (lane - 32) & 31 : lane;              // index among the lanes that may load metadata
-        const int mm = ml & (2 * MP - 1);
-        const unsigned char* mptr = reinterpret_cast<const unsigned char*>(mm >= MP ? p.zero : p.scale) +
-                                    trow * (2 * NG) + (mm & (MP - 1)) * 16;
-        const int m_lds = ml < 2 * MP ? META0 + mm * 16 : SPARE + lane * 16;
-        const unsigned char* cptr = reinterpret_cast<const unsigned char*>(p.codes) + trow * (WPK * 4) + lane * 16;
-        const int c_lds = (lane / PPT) * CS + (lane % PPT) * 16;
-        // 2-bit: lanes 0..31 deliver codes, lanes 32.. metadata, with one instruction
-        const bool code_lane = BITS == 4 || lane < CL;
-        const unsigned char* gp = code_lane ? cptr : mptr;
-        const uint32_t gstep = code_lane ? kUnitTokens * WPK * 4 : kUnitTokens * 2 * NG;
-        const int g_lds = code_lane ? c_lds : m_lds;
-        struct Raw {
-            u32x4 c;
-            u32x4 m;
-        };
-        Raw ring[kDepth];
-        auto fetch = [&](Raw& r) {
-            r.c = SC_LOAD(reinterpret_cast<const u32x4*>(gp));
-            gp += gstep;
-            if constexpr (BITS == 4) {
-                r.m = SC_LOAD(reinterpret_cast<const u32x4*>(mptr));
-                mptr += kUnitTokens * 2 * NG;
-            }
-        };
         auto deliver = [&](const Raw& r) {
             *reinterpret_cast<u32x4*>(lds + g_lds) = r.c;
             if constexpr (BITS == 4) *reinterpret_cast<u32x4*>(lds + m_lds) = r.m;
         };
-#pragma unroll
-        for (int i = 0; i < kDepth; ++i) {
-            ring[i].c = u32x4{0u, 0u, 0u, 0u};
-            ring[i].m = u32x4{0u, 0u, 0u, 0u};
-            if (i < nf) fetch(ring[i]);
-        }
         float* optr = out0 + static_cast<int64_t>(u0) * kUnitTokens + col;
         float held0 = 0.0f, held1 = 0.0f;
         // Two consecutive units fill one 128-byte line of a score row: the first unit of a pair keeps its results

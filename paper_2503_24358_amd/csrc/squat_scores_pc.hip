@@ -18,10 +18,10 @@
 // bits 6..9 (the matrix cores align products by exponent fields; lower positions
 // lose bits).  A packed word holds 16 (2-bit) or 8 (4-bit) TOKENS of one channel
 // while a matrix operand wants consecutive CHANNELS of one token in a lane, so
-// the group's words go through a small per-wavefront LDS tile; a lane then takes
-// the low (high) 16-bit halves of two channels' words with one v_perm, and one
-// rotate + mask puts its token's two codes into an operand register: 1.5
-// instructions per code.  The zero-point term is one more matrix product per
+// the group's words go through a small per-wavefront LDS tile, regrouped on the
+// way in as (low halves, high halves) of the words of two neighbouring channels
+// (one v_perm each); a lane then reads such a pair and one rotate + mask puts
+// its token's two codes into an operand register: one instruction per code.  The zero-point term is one more matrix product per
 // chunk with the zero-points as stored as the other operand (every column gets
 // the same sum, so each lane finds it next to its own token's result).
 #include "squat_internal.h"
@@ -77,8 +77,9 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     constexpr int W = BITS;                               // packed words per channel and token group
     constexpr int TH = 16 / BITS;                         // tokens per 16-bit half of a word: 8 or 4
     constexpr uint32_t MASK = BITS == 2 ? 0x00C000C0u : 0x03C003C0u;   // a code at bits 6.. of both halves
-    // LDS tile of one wavefront: region (i, k) = word k of every channel of group i (128 words; 32 spare
-    // bytes shift the banks of consecutive regions), then scales of group 0 (, 1), zero-points of group 0 (, 1)
+    // LDS tile of one wavefront: region (i, k) = word k of every channel of group i, per pair of channels the
+    // low halves of both words, then the high halves (128 words; 32 spare bytes shift the banks of consecutive
+    // regions), then scales of group 0 (, 1), zero-points of group 0 (, 1)
     constexpr int RSTRIDE = 512 + 32;
     constexpr int META = NT * W * RSTRIDE, ZOFF = NT * 256, TILE = META + 2 * NT * 256;
     constexpr int ML = 2 * NT;                            // metadata dwords a lane loads
@@ -90,6 +91,43 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     const int64_t bh = static_cast<int64_t>(blockIdx.z) * gridDim.y + blockIdx.y;
     const int64_t b = bh / p.n_kv_heads;
     const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
+
+    // ---- this wavefront's token groups (tiles_per_wave is a multiple of NT); the loads of its first steps are
+    // issued before anything else, so that their latency overlaps the set-up of the query-side registers
+    const int t0 = (static_cast<int>(blockIdx.x) * kPcWaves + wave) * p.tiles_per_wave;
+    const int t1 = min(t0 + p.tiles_per_wave, p.n_tiles);
+    const int64_t tile0 = bh * p.store_tiles;
+    // loads per token group: lane L fetches the words of channels 2 L and 2 L + 1 (16 or 32 contiguous
+    // bytes); metadata per step: 2 NT arrays of 128 halves (scales of group 0 (, 1), zero-points of group
+    // 0 (, 1)), 4 NT halves per lane
+    const uint32_t* c_base = p.codes + tile0 * (kD * W) + lane * (2 * W);
+    constexpr int LPA = 32 / NT;                          // lanes per metadata array
+    const int m_arr = lane / LPA;                         // which array this lane loads from
+    const int m_tile = m_arr % NT;
+    const uint16_t* m_base = (m_arr < NT ? p.scale : p.zero) + tile0 * kD + (lane % LPA) * (4 * NT);
+    typedef uint32_t mvec __attribute__((ext_vector_type(ML)));
+    struct Raw {
+        u32x4 c[NT][BITS / 2];
+        mvec m;
+    };
+    // a group past the end of this wavefront's range re-reads its last group (never used)
+    auto fetch = [&](int t, Raw& r) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const uint32_t tt = static_cast<uint32_t>(min(t + i, t1 - 1));
+#pragma unroll
+            for (int k = 0; k < BITS / 2; ++k)
+                r.c[i][k] = PC_LOAD(reinterpret_cast<const u32x4*>(c_base + tt * (kD * W) + 4 * k));
+        }
+        const uint32_t tm = static_cast<uint32_t>(min(t + m_tile, t1 - 1));
+        r.m = PC_LOAD(reinterpret_cast<const mvec*>(m_base + tm * kD));
+    };
+
+    Raw ring[kPcDepth];
+    if (t0 < t1) {
+#pragma unroll
+        for (int i = 0; i < kPcDepth; ++i) fetch(t0 + NT * i, ring[i]);
+    }
 
     // ---- the KV head's queries -> LDS as fp32, rows past q_per_kv zero
     constexpr int QLD = kD + 1;
@@ -132,7 +170,7 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     const float inv_q = as_f32((254u - eb) << 23);        // 2^-(eb - 127)
     const float fin = p.out_scale * as_f32(eb << 23);     // out_scale * 2^(eb - 127)
 
-    // ---- constant query-side registers: row `col` = (token group col / 8 if NT = 2, query head, part);
+    // ---- constant query-side operands: row `col` = (token group col / 8 if NT = 2, query head, part);
     // register r of chunk g holds K = 8 kb + 2 r + {0, 1}  <->  channels 32 g + 8 kb + 2 r + {0, 1}.
     // The operand register of a row is  fma(q_hi, Delta, -sub)  with sub = rn(q_sub Delta): high rows keep
     // q_sub = 0 (the result is rn(q_hi Delta)), low rows q_sub = q_hi (the result is the exact remainder),
@@ -140,11 +178,14 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     const int arow = NT == 2 ? (col & 7) : col;
     const int ahalf = NT == 2 ? (col >> 3) : 0;           // token group whose scales this lane's row uses
     const int qh = arow >> 1, part = arow & 1;
-    half2v qhi[4][4];
-    half2v qsub[4][4];
-    half2v qlo[4][4];                                     // fp32 queries only: low part (low rows), else 0
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
+    // They live in LDS, not in registers (32 to 48 of them would cost a wavefront per SIMD): wavefront g builds
+    // chunk g for every lane position, and a step reads a chunk back with one 16-byte read per kind.
+    __shared__ __attribute__((aligned(16))) u32x4 qhi_lds[4 * kWave];
+    __shared__ __attribute__((aligned(16))) u32x4 qsub_lds[4 * kWave];
+    __shared__ __attribute__((aligned(16))) u32x4 qlo_lds[QDT == SQUAT_F32 ? 4 * kWave : 1];   // fp32 queries only: low part (low rows), else 0
+    {
+        const int g = wave;
+        u32x4 vh, vs, vl;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int c = 32 * g + 8 * kb + 2 * r;
@@ -152,71 +193,61 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
             const _Float16 h0 = static_cast<_Float16>(v0), h1 = static_cast<_Float16>(v1);
             const _Float16 l0 = static_cast<_Float16>(v0 - static_cast<float>(h0));
             const _Float16 l1 = static_cast<_Float16>(v1 - static_cast<float>(h1));
-            const _Float16 zh = static_cast<_Float16>(0.0f);
-            qhi[g][r] = half2v{h0, h1};
-            qsub[g][r] = part == 0 ? half2v{zh, zh} : half2v{h0, h1};
-            qlo[g][r] = part == 0 ? half2v{zh, zh} : half2v{l0, l1};
+            vh[r] = pack2(h0, h1);
+            vs[r] = part == 0 ? 0u : pack2(h0, h1);
+            vl[r] = part == 0 ? 0u : pack2(l0, l1);
         }
+        qhi_lds[g * kWave + lane] = vh;
+        qsub_lds[g * kWave + lane] = vs;
+        if constexpr (QDT == SQUAT_F32) qlo_lds[g * kWave + lane] = vl;
+    }
+    __syncthreads();
 
-    // ---- this wavefront's token groups (tiles_per_wave is a multiple of NT)
-    const int t0 = (static_cast<int>(blockIdx.x) * kPcWaves + wave) * p.tiles_per_wave;
-    const int t1 = min(t0 + p.tiles_per_wave, p.n_tiles);
     if (t0 >= t1) return;                                 // after the last workgroup barrier
 
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[kPcWaves * TILE];
     unsigned char* lds = lds_all + wave * TILE;
-    const int64_t tile0 = bh * p.store_tiles;
-    // loads per token group: lane L fetches the words of channels 2 L and 2 L + 1 (16 or 32 contiguous
-    // bytes); metadata per step: 2 NT arrays of 128 halves (scales of group 0 (, 1), zero-points of group
-    // 0 (, 1)), 4 NT halves per lane
-    const uint32_t* c_base = p.codes + tile0 * (kD * W) + lane * (2 * W);
-    constexpr int LPA = 32 / NT;                          // lanes per metadata array
-    const int m_arr = lane / LPA;                         // which array this lane loads from
-    const int m_tile = m_arr % NT;
-    const uint16_t* m_base = (m_arr < NT ? p.scale : p.zero) + tile0 * kD + (lane % LPA) * (4 * NT);
-    typedef uint32_t mvec __attribute__((ext_vector_type(ML)));
-    struct Raw {
-        u32x4 c[NT][BITS / 2];
-        mvec m;
-    };
-    // a group past the end of this wavefront's range re-reads its last group (never used)
-    auto fetch = [&](int t, Raw& r) {
-#pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            const uint32_t tt = static_cast<uint32_t>(min(t + i, t1 - 1));
-#pragma unroll
-            for (int k = 0; k < BITS / 2; ++k)
-                r.c[i][k] = PC_LOAD(reinterpret_cast<const u32x4*>(c_base + tt * (kD * W) + 4 * k));
-        }
-        const uint32_t tm = static_cast<uint32_t>(min(t + m_tile, t1 - 1));
-        r.m = PC_LOAD(reinterpret_cast<const mvec*>(m_base + tm * kD));
-    };
-
-    const int wsel = col / TH, j = col % TH;              // this lane's word and token position in a half
+    // This lane's tokens.  4-bit: word wsel of a channel, position j in both of its 16-bit halves, i.e. tokens
+    // tokA and tokA + 4.  2-bit: a half holds 8 tokens, and two NEIGHBOURING tokens can be taken from one rotated
+    // register (bits 6..7 and 8..9; the second comes out times 4, undone in the final scale): word wsel, half
+    // hsel, tokens tokA = 2 jp and tokA + 1.
+    constexpr int TOKB = BITS == 2 ? 1 : TH;              // distance of the second product's token
+    const int wsel = BITS == 2 ? col >> 3 : col / TH;
+    const int hsel = BITS == 2 ? (col >> 2) & 1 : 0;
+    const int j = BITS == 2 ? 2 * (col & 3) : col % TH;
     const uint32_t rot = static_cast<uint32_t>(BITS * j - 6) & 31u;      // right-rotation: code -> bits 6..
-    const int tokA = (32 / W) * wsel + j;                 // token of the first product's column, second: + TH
+    const int tokA = (32 / W) * wsel + 8 * hsel + j;
     const int kbh = NT == 2 ? (kb & 1) : kb;              // pair of query heads in this lane's result rows
     const int rhalf = NT == 2 ? (kb >> 1) : 0;            // token group of this lane's result rows
     float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kbh) * p.ssh;
     const bool st0 = 2 * kbh < p.qpk, st1 = 2 * kbh + 1 < p.qpk;
-    const unsigned char* rd_codes = lds + wsel * RSTRIDE + 32 * kb;
+    const unsigned char* rd_codes = lds + wsel * RSTRIDE + 32 * kb + 16 * hsel;
     const unsigned char* rd_scale = lds + META + ahalf * 256 + 16 * kb;
     // zero-points: the group of the COLUMN (every K block of a column must see the same group)
     const unsigned char* rd_zero = lds + META + ZOFF + (NT == 2 ? (col >> 3) * 256 : 0) + 16 * kb;
     const bool z_mine = NT == 1 || (col >> 3) == rhalf;
 
-    auto compute = [&](int t, const Raw& raw) {
-        // registers -> LDS tile
+    // registers -> LDS tile; returns the lane's largest scale pattern (the registers are free afterwards)
+    auto deliver = [&](const Raw& raw) -> uint32_t {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            unsigned char* reg = lds + i * W * RSTRIDE + 8 * lane;
-            if constexpr (BITS == 2) {
-                *reinterpret_cast<u32x2*>(reg) = u32x2{raw.c[i][0][0], raw.c[i][0][2]};
-                *reinterpret_cast<u32x2*>(reg + RSTRIDE) = u32x2{raw.c[i][0][1], raw.c[i][0][3]};
-            } else {
+            // word k of the lane's two channels, regrouped as (low halves, high halves): a half-word pair is
+            // what an operand register of the reader holds, so the regrouping is done once here, not per reader
+            // (4-bit: the two kinds alternate, a reader takes both; 2-bit: per block of 8 channels the four low
+            // pairs, then the four high pairs, a reader takes one kind with one 16-byte read)
+            unsigned char* reg = lds + i * W * RSTRIDE + (BITS == 2 ? (lane >> 2) * 32 + (lane & 3) * 4 : 8 * lane);
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    *reinterpret_cast<u32x2*>(reg + k * RSTRIDE) = u32x2{raw.c[i][0][k], raw.c[i][BITS / 2 - 1][k]};
+            for (int k = 0; k < W; ++k) {
+                const uint32_t we = raw.c[i][0][k];
+                const uint32_t wo = BITS == 2 ? raw.c[i][0][2 + k] : raw.c[i][BITS / 2 - 1][k];
+                const uint32_t pl = __builtin_amdgcn_perm(wo, we, 0x05040100u);
+                const uint32_t ph = __builtin_amdgcn_perm(wo, we, 0x07060302u);
+                if constexpr (BITS == 2) {
+                    *reinterpret_cast<uint32_t*>(reg + k * RSTRIDE) = pl;
+                    *reinterpret_cast<uint32_t*>(reg + k * RSTRIDE + 16) = ph;
+                } else {
+                    *reinterpret_cast<u32x2*>(reg + k * RSTRIDE) = u32x2{pl, ph};
+                }
             }
         }
         *reinterpret_cast<mvec*>(lds + META + 4 * ML * lane) = raw.m;
@@ -229,6 +260,9 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
             const uint32_t v = raw.m[i];
             mx = max(mx, max(v & 0xFFFFu, v >> 16));
         }
+        return mx;
+    };
+    auto compute = [&](int t, uint32_t mx) {
         mx = dpp_max<0xB1>(mx);                           // quad_perm [1,0,3,2]
         mx = dpp_max<0x4E>(mx);                           // quad_perm [2,3,0,1]
         mx = dpp_max<0x141>(mx);                          // row_half_mirror
@@ -260,31 +294,44 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
         for (int g = 0; g < 4; ++g) {
             const u32x4 sc = *reinterpret_cast<const u32x4*>(rd_scale + 64 * g);
             const u32x4 zm = *reinterpret_cast<const u32x4*>(rd_zero + 64 * g);
+            const u32x4 qh4 = qhi_lds[g * kWave + lane];
+            const u32x4 qs4 = qsub_lds[g * kWave + lane];
+            u32x4 ql4 = {0u, 0u, 0u, 0u};
+            if constexpr (QDT == SQUAT_F32) ql4 = qlo_lds[g * kWave + lane];
             u32x4 aop;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // (bit-casting the vector ELEMENT expression directly makes this compiler read element 0)
-                const uint32_t sraw = sc[r];
+                const uint32_t sraw = sc[r], qhr = qh4[r], qsr = qs4[r], qlr = ql4[r];
                 const half2v dl = __builtin_bit_cast(half2v, sraw) * spack;
-                const half2v sub = qsub[g][r] * dl;
-                half2v a = __builtin_elementwise_fma(qhi[g][r], dl, -sub);
-                if constexpr (QDT == SQUAT_F32) a = __builtin_elementwise_fma(qlo[g][r], dl, a);
+                const half2v sub = __builtin_bit_cast(half2v, qsr) * dl;
+                half2v a = __builtin_elementwise_fma(__builtin_bit_cast(half2v, qhr), dl, -sub);
+                if constexpr (QDT == SQUAT_F32) a = __builtin_elementwise_fma(__builtin_bit_cast(half2v, qlr), dl, a);
                 aop[r] = __builtin_bit_cast(uint32_t, a);
             }
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
                 const unsigned char* src = rd_codes + i * W * RSTRIDE + 128 * g;
-                const u32x4 wlo = *reinterpret_cast<const u32x4*>(src);
-                const u32x4 whi = *reinterpret_cast<const u32x4*>(src + 16);
-                const uint32_t w[8] = {wlo[0], wlo[1], wlo[2], wlo[3], whi[0], whi[1], whi[2], whi[3]};
                 u32x4 bopA, bopB;
+                if constexpr (BITS == 2) {
+                    const u32x4 wq = *reinterpret_cast<const u32x4*>(src);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    // low / high halves of the words of channels 2 r, 2 r + 1: tokens j / TH + j of the word
-                    const uint32_t pl = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x05040100u);
-                    const uint32_t ph = __builtin_amdgcn_perm(w[2 * r + 1], w[2 * r], 0x07060302u);
-                    bopA[r] = __builtin_amdgcn_alignbit(pl, pl, rot) & MASK;
-                    bopB[r] = __builtin_amdgcn_alignbit(ph, ph, rot) & MASK;
+                    for (int r = 0; r < 4; ++r) {
+                        const uint32_t wr = wq[r];
+                        const uint32_t x = __builtin_amdgcn_alignbit(wr, wr, rot);
+                        bopA[r] = x & MASK;                   // token tokA of channels 2 r, 2 r + 1
+                        bopB[r] = x & (MASK << 2);            // token tokA + 1, times 4
+                    }
+                } else {
+                    const u32x4 wlo = *reinterpret_cast<const u32x4*>(src);
+                    const u32x4 whi = *reinterpret_cast<const u32x4*>(src + 16);
+                    const uint32_t w[8] = {wlo[0], wlo[1], wlo[2], wlo[3], whi[0], whi[1], whi[2], whi[3]};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        // low / high halves of the words of channels 2 r, 2 r + 1: tokens j / TH + j of the word
+                        bopA[r] = __builtin_amdgcn_alignbit(w[2 * r], w[2 * r], rot) & MASK;
+                        bopB[r] = __builtin_amdgcn_alignbit(w[2 * r + 1], w[2 * r + 1], rot) & MASK;
+                    }
                 }
                 acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop),
                                                                    __builtin_bit_cast(half8, bopA), acc[i][0], 0, 0, 0);
@@ -294,9 +341,9 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
             u32x4 az;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                // high rows: q_hi (q_sub = 0), low rows: q_lo (q_sub = q_hi); rebuilt to save 16 registers
-                az[r] = __builtin_bit_cast(uint32_t, qhi[g][r]) ^ __builtin_bit_cast(uint32_t, qsub[g][r]);
-                if constexpr (QDT == SQUAT_F32) az[r] |= __builtin_bit_cast(uint32_t, qlo[g][r]);
+                // high rows: q_hi (q_sub = 0), low rows: q_lo (q_sub = q_hi)
+                az[r] = qh4[r] ^ qs4[r];
+                if constexpr (QDT == SQUAT_F32) az[r] |= ql4[r];
             }
             zacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, az), __builtin_bit_cast(half8, zm),
                                                           zacc, 0, 0, 0);
@@ -322,36 +369,33 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = rhalf ? acc[NT - 1][sgn][e] : v[e];
             }
-            r0[sgn] = fin * fmaf(descale, v[0] + v[1], z0);
-            r1[sgn] = fin * fmaf(descale, v[2] + v[3], z1);
+            const float ds = (BITS == 2 && sgn == 1) ? 0.25f * descale : descale;
+            r0[sgn] = fin * fmaf(ds, v[0] + v[1], z0);
+            r1[sgn] = fin * fmaf(ds, v[2] + v[3], z1);
         }
         const int tr = t + rhalf;
         if (tr < t1) {
             const int64_t tok = static_cast<int64_t>(tr) * 32 + tokA;
             if (st0) {
                 __builtin_nontemporal_store(r0[0], out0 + tok);
-                __builtin_nontemporal_store(r0[1], out0 + tok + TH);
+                __builtin_nontemporal_store(r0[1], out0 + tok + TOKB);
             }
             if (st1) {
                 __builtin_nontemporal_store(r1[0], out0 + p.ssh + tok);
-                __builtin_nontemporal_store(r1[1], out0 + p.ssh + tok + TH);
+                __builtin_nontemporal_store(r1[1], out0 + p.ssh + tok + TOKB);
             }
         }
     };
 
-    // software pipeline: the loads of kPcDepth steps are in flight while one is being computed
-    Raw ring[kPcDepth];
-#pragma unroll
-    for (int i = 0; i < kPcDepth; ++i) fetch(t0 + NT * i, ring[i]);
     // whole groups of kPcDepth steps run without a test (a skipped step inside the loop costs a register copy
     // per value the loop carries); the last, shorter group is handled after it
     int t = t0;
     for (; t + NT * (kPcDepth - 1) < t1; t += NT * kPcDepth) {
 #pragma unroll
         for (int i = 0; i < kPcDepth; ++i) {
-            const Raw cur = ring[i];
+            const uint32_t mx = deliver(ring[i]);
             fetch(t + NT * (i + kPcDepth), ring[i]);
-            compute(t + NT * i, cur);
+            compute(t + NT * i, mx);
         }
     }
     static_assert(kPcDepth <= 3, "the tail picks its step from ring[0] / ring[1]");
@@ -359,7 +403,8 @@ __global__ void __launch_bounds__(kPcWaves* kWave) key_scores_pc_kernel(const Sc
     for (int i = 0; t + NT * i < t1; ++i) {               // at most kPcDepth - 1 steps; one copy of the code
         Raw cur = ring[0];
         if (i == 1) cur = ring[1];
-        compute(t + NT * i, cur);
+        const uint32_t mx = deliver(cur);
+        compute(t + NT * i, mx);
     }
 }
 
