@@ -58,6 +58,7 @@ struct RopeParams {
     int qpk;
     float out_scale;
     int units_per_wave;
+    int wide_loads;                  // per-token store: rows 16-byte aligned, whole units fetched with 16-byte loads
 };
 
 __device__ __forceinline__ uint32_t pack_h2(_Float16 lo, _Float16 hi) {
@@ -132,7 +133,8 @@ __device__ __forceinline__ void fill_trig_tables(const float* inv_freq, uint32_t
 // Query side of one wavefront.  With more than four query heads per KV head lane (h = lane >> 3, fb = lane & 7)
 // owns the NF = 8 pairs (q_h[f], q_h[f + 64]), f = 8 fb + i; with at most four (the usual grouped-query case) lane
 // (h = lane >> 4, fb = lane & 15) owns NF = 4 pairs, f = 4 fb + i, and rows 8 .. 15 of the operand stay zero.  `build`
-// writes R(-theta_E) q as fp16 high (row 2 h) and low (row 2 h + 1) parts into the wavefront's exchange tile, from
+// writes R(-theta_E) q as fp16 high (row 4 (h & 3) + 2 (h >> 2)) and low (the row after it) parts into the
+// wavefront's exchange tile (so that result lane block kb holds query heads kb and kb + 4), from
 // which every lane reads the 16 registers of its A operands.
 struct QuerySide {
     float ce[8], se[8];          // cos / sin of theta_E (the only state that lives across epochs)
@@ -190,11 +192,11 @@ struct QuerySide {
         if (wide) {
             // frequencies 8 fb .. 8 fb + 7 are K-block fb & 3, chunk fb >> 2: 8 consecutive words of a row
             const int h = lane >> 3, fb = lane & 7;
-            rotate_and_store<8>(atile + (2 * h) * kATileLd + (fb & 3) * 16 + (fb >> 2) * 8);
+            rotate_and_store<8>(atile + (4 * (h & 3) + 2 * (h >> 2)) * kATileLd + (fb & 3) * 16 + (fb >> 2) * 8);
         } else {
             // frequencies 4 fb .. 4 fb + 3: K-block (fb >> 1) & 3, chunk fb >> 3, pairs 4 (fb & 1) .. + 3
             const int h = lane >> 4, fb = lane & 15;
-            rotate_and_store<4>(atile + (2 * h) * kATileLd + ((fb >> 1) & 3) * 16 + (fb >> 3) * 8 + (fb & 1) * 4);
+            rotate_and_store<4>(atile + (4 * h) * kATileLd + ((fb >> 1) & 3) * 16 + (fb >> 3) * 8 + (fb & 1) * 4);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -236,8 +238,10 @@ __device__ __forceinline__ void stage_queries(const RopeParams& p, int64_t b, in
 // Per-token store.  Lane (kb = lane >> 4, col = lane & 15): token col of the unit, rotary pairs
 // (32 g + 8 kb + i, + 64), g < 2, i < 8.  Matrix product m = 2 g + (i >> 2) takes the pairs i & 3 = 0..3 of chunk g
 // as its K slots 8 kb .. 8 kb + 7 (both operands), rows = (query head, fp16 high / low part).
+// (Registers are capped at three wavefronts per SIMD: the 4-bit forms would otherwise take a few more and run two.)
 template <int BITS, int NG, int QDT>
-__global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(const RopeParams p) {
+__global__ void __launch_bounds__(kRopeWaves* kWave) __attribute__((amdgpu_waves_per_eu(3)))
+key_scores_rope_kernel(const RopeParams p) {
     constexpr int WPK = kD * BITS / 32;                   // packed words per key
     constexpr int CPR = 8 / BITS;                         // codes of a pair register whose bits stay below bit 8 of a half
     constexpr int NSRC = 8 / CPR;                         // such source registers per chunk pair: 2 (2-bit), 4 (4-bit)
@@ -250,6 +254,64 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
     const int64_t b = bh / p.n_kv_heads;
     const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
 
+    // ---- this wavefront's 16-token units (whole epochs; the range starts on an epoch boundary).  The loads of its
+    // first units are issued before anything else: their latency overlaps the set-up of queries and tables.
+    const int n_tok = static_cast<int>(p.n_tokens);
+    const int n_units = (n_tok + kRopeUnit - 1) / kRopeUnit;
+    const int u0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
+    const int u1 = min(u0 + p.units_per_wave, n_units);
+    const int64_t row0 = bh * p.store_stride;
+    // A unit's packed words (contiguous in memory) and its scales and zero-points (two contiguous runs of 32 NG
+    // bytes) pass through a small per-wavefront LDS tile, as in the unrotated kernel: whole units with one 16-byte
+    // load per lane (a second one for the metadata of 4-bit stores) and no lane tests; lanes left over repeat a
+    // neighbour's load and drop it into a spare LDS slot.
+    constexpr int PPT = WPK / 4;                          // 16-byte pieces of codes per token
+    constexpr int CL = kRopeUnit * PPT;                   // lanes that load codes (32 or 64)
+    constexpr int MP = 2 * NG;                            // 16-byte pieces of scales (and of zero-points) per unit
+    constexpr int CS = WPK * 4 + 16;                      // LDS bytes per token of codes (padded)
+    constexpr int META0 = kRopeUnit * CS;                 // scales: 2 NG bytes per token from META0, zero-points from ZOFF
+    constexpr int ZOFF = META0 + MP * 16;
+    constexpr int SPARE = META0 + 256;
+    constexpr int TILE = SPARE + kWave * 16;
+    const int n_full = n_tok / kRopeUnit;
+    int nf = 0;
+    if (p.wide_loads) nf = max(min(u1, n_full) - u0, 0) & ~1;
+    const int uf = u0 + nf;
+    const int ml = BITS == 2 ? (lane - 32) & 31 : lane;   // index among the lanes that may load metadata
+    const int mm = ml & (2 * MP - 1);
+    const int m_lds = ml < 2 * MP ? META0 + mm * 16 : SPARE + lane * 16;
+    const int c_lds = (lane / PPT) * CS + (lane % PPT) * 16;
+    const bool code_lane = BITS == 4 || lane < CL;        // 2-bit: lanes 0..31 deliver codes, lanes 32.. metadata
+    const int g_lds = code_lane ? c_lds : m_lds;
+    const uint32_t gstep = code_lane ? kRopeUnit * WPK * 4 : kRopeUnit * 2 * NG;
+    const unsigned char* mptr;
+    const unsigned char* gp;
+    {
+        const int64_t trow = row0 + static_cast<int64_t>(u0) * kRopeUnit;
+        mptr = reinterpret_cast<const unsigned char*>(mm >= MP ? p.zero : p.scale) + trow * (2 * NG) + (mm & (MP - 1)) * 16;
+        const unsigned char* cptr = reinterpret_cast<const unsigned char*>(p.codes) + trow * (WPK * 4) + lane * 16;
+        gp = code_lane ? cptr : mptr;
+    }
+    struct Raw {
+        u32x4 c;
+        u32x4 m;
+    };
+    Raw ring[kEpochUnits];
+    auto fetch = [&](Raw& r) {
+        r.c = RP_LOAD(reinterpret_cast<const u32x4*>(gp));
+        gp += gstep;
+        if constexpr (BITS == 4) {
+            r.m = RP_LOAD(reinterpret_cast<const u32x4*>(mptr));
+            mptr += kRopeUnit * 2 * NG;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kEpochUnits; ++i) {
+        ring[i].c = u32x4{0u, 0u, 0u, 0u};
+        ring[i].m = u32x4{0u, 0u, 0u, 0u};
+        if (i < nf) fetch(ring[i]);
+    }
+
     constexpr int QLD = kD + 1;
     __shared__ float qlds[8 * QLD];
     __shared__ float step64[2 * 64];
@@ -258,11 +320,6 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
     stage_queries<QDT>(p, b, kvh, qlds, QLD);
     fill_trig_tables(p.inv_freq, trig, step64);
     __syncthreads();
-
-    // ---- this wavefront's 16-token units (whole epochs; the range starts on an epoch boundary)
-    const int n_units = static_cast<int>((p.n_tokens + kRopeUnit - 1) / kRopeUnit);
-    const int u0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
-    const int u1 = min(u0 + p.units_per_wave, n_units);
     if (u0 >= u1) return;                                 // after the last workgroup barrier
 
     uint32_t* atile = atiles + wave * 16 * kATileLd;
@@ -270,60 +327,23 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
     qs.init(qlds, QLD, step64, p.inv_freq, static_cast<double>(p.pos0 + static_cast<int64_t>(u0) * kRopeUnit), lane,
             p.qpk, atile);
 
-    const int64_t row0 = bh * p.store_stride;
-    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
-    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    // result rows 4 kb + {0, 1}: high and low part of query head kb; rows + {2, 3}: query head kb + 4
+    const bool two = p.qpk > 4;
+    const bool st0 = kb < p.qpk, st1 = kb + 4 < p.qpk;
+    float* const out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + kb) * p.ssh;
+    const int64_t out1 = 4 * p.ssh;
     const float fin = p.out_scale;
 
-    // loads: per unit ONE 16-byte load by the lanes that cover the unit's codes and ONE load of the
-    // scales and zero-points, through a small per-wavefront LDS tile (as in the unrotated kernel)
-    constexpr int PPT = WPK / 4;
-    constexpr int CL = kRopeUnit * PPT;
-    constexpr int CS = WPK * 4 + 16;
-    constexpr int META0 = kRopeUnit * CS;
-    constexpr int TILE = META0 + 256;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[kRopeWaves * TILE];
     unsigned char* lds = lds_all + wave * TILE;
-    struct Raw {
-        u32x4 c;
-        u32x2 m;
-    };
-    const int n_tok = static_cast<int>(p.n_tokens);
-    const int ml = BITS == 2 ? lane - 32 : lane;
-    const bool is_c = lane < CL, is_m = ml >= 0 && ml < 32;
-    const int c_tok = lane / PPT, c_piece = lane % PPT;
-    const int m_tok = ml & 15;
-    const uint32_t* c_base = p.codes + row0 * WPK + c_piece * 4;
-    const uint16_t* m_base = ((ml & 16) ? p.zero : p.scale) + row0 * NG;
-    auto fetch = [&](int u, Raw& r) {
-        r.c = u32x4{0u, 0u, 0u, 0u};
-        r.m = u32x2{0u, 0u};
-        if (is_c) {
-            const int t = min(u * kRopeUnit + c_tok, n_tok - 1);
-            r.c = RP_LOAD(reinterpret_cast<const u32x4*>(c_base + static_cast<uint32_t>(t) * WPK));
-        }
-        if (is_m) {
-            const int t = min(u * kRopeUnit + m_tok, n_tok - 1);
-            if constexpr (NG == 4) {
-                r.m = RP_LOAD(reinterpret_cast<const u32x2*>(m_base + static_cast<uint32_t>(t) * 4));
-            } else if constexpr (NG == 2) {
-                r.m[0] = RP_LOAD(reinterpret_cast<const uint32_t*>(m_base + static_cast<uint32_t>(t) * 2));
-            } else {
-                r.m[0] = RP_LOAD(m_base + static_cast<uint32_t>(t));
-            }
-        }
-    };
 
     // where this lane's codes sit: 2-bit: 16 bits (one half of a word) per chunk; 4-bit: one word per chunk
     const int widx0 = BITS == 2 ? (kb >> 1) : kb;
     const uint32_t half_sel = (kb & 1) ? 0x07060302u : 0x05040100u;       // v_perm: (hi : lo) <- the same half of both words
 
     u32x4 aop[4];
-    float held0 = 0.0f, held1 = 0.0f;
-    auto compute = [&](int u, int v, const Raw& raw) {
-        // registers -> LDS tile -> the words of this lane's K block, the metadata of its token
-        if (is_c) *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) = raw.c;
-        if (is_m) *reinterpret_cast<u32x2*>(lds + META0 + (ml & 16) * 8 + m_tok * 8) = raw.m;
+    // LDS tile -> logits of the lane's token (unit v of the epoch) for the lane's query head(s)
+    auto unit_scores = [&](int v, float& s0, float& s1) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -331,8 +351,20 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             w[g] = *reinterpret_cast<const uint32_t*>(lds + col * CS + (g * (WPK / 4) + widx0) * 4);
-        const u32x2 sv = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
-        const u32x2 zv = *reinterpret_cast<const u32x2*>(lds + META0 + 128 + col * 8);
+        // scales and zero-points of the token: NG fp16 numbers each
+        uint32_t sv[2] = {0u, 0u}, zv[2] = {0u, 0u};
+        if constexpr (NG == 4) {
+            const u32x2 s2 = *reinterpret_cast<const u32x2*>(lds + META0 + col * 8);
+            const u32x2 z2 = *reinterpret_cast<const u32x2*>(lds + ZOFF + col * 8);
+            sv[0] = s2[0]; sv[1] = s2[1];
+            zv[0] = z2[0]; zv[1] = z2[1];
+        } else if constexpr (NG == 2) {
+            sv[0] = *reinterpret_cast<const uint32_t*>(lds + META0 + col * 4);
+            zv[0] = *reinterpret_cast<const uint32_t*>(lds + ZOFF + col * 4);
+        } else {
+            sv[0] = *reinterpret_cast<const uint16_t*>(lds + META0 + col * 2);
+            zv[0] = *reinterpret_cast<const uint16_t*>(lds + ZOFF + col * 2);
+        }
         // key-side angles of token 16 v + col of the epoch, this lane's 16 frequencies
         u32x4 tr[4];
         {
@@ -340,6 +372,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
 #pragma unroll
             for (int m = 0; m < 4; ++m) tr[m] = *reinterpret_cast<const u32x4*>(trow + 4 * m);
         }
+        // the next unit's tile must not overtake these reads
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -350,7 +383,7 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             const int ga = g * NG / 4, gb = (g + 2) * NG / 4;
-            auto half_of = [](const u32x2& x, int gi) -> uint32_t { return (gi & 1) ? (x[gi >> 1] >> 16) : (x[gi >> 1] & 0xFFFFu); };
+            auto half_of = [](const uint32_t (&x)[2], int gi) -> uint32_t { return (gi & 1) ? (x[gi >> 1] >> 16) : (x[gi >> 1] & 0xFFFFu); };
             const uint32_t sw = half_of(sv, ga) | (half_of(sv, gb) << 16);
             const uint32_t zw = half_of(zv, ga) | (half_of(zv, gb) << 16);
             // scales are non-negative fp16 numbers: their bit patterns order like their values (127.0 = 0x57F0;
@@ -400,62 +433,99 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
                     bop[i >> 2][i & 3] = h2_bits(xr);
                 }
 #pragma unroll
-                for (int mm = 0; mm < 2; ++mm)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[2 * g + mm]),
-                                                                 __builtin_bit_cast(half8, bop[mm]), acc, 0, 0, 0);
+                for (int mm2 = 0; mm2 < 2; ++mm2)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop[2 * g + mm2]),
+                                                                 __builtin_bit_cast(half8, bop[mm2]), acc, 0, 0, 0);
             }
         };
         if (__builtin_amdgcn_ballot_w64(big) == 0ull)
             body(std::true_type{});
         else
             body(std::false_type{});
-        // rows 4 kb + {0, 1}: high and low part of query head 2 kb; rows + {2, 3}: query head 2 kb + 1
-        // two consecutive units fill one 128-byte line of a score row: the first of an (even, odd) pair is
-        // kept and stored together with the second (a unit apart they reach memory as partial line writes)
-        const int tok = u * kRopeUnit + col;
-        const float s0 = fin * (acc[0] + acc[1]), s1 = fin * (acc[2] + acc[3]);
-        if ((u & 1) == 0 && u + 1 < u1) {
-            held0 = s0;
-            held1 = s1;
-        } else {
-            const bool pair = (u & 1) && u > u0;          // the held unit is complete: u exists
-            float* const d0 = out0 + tok;
-            float* const d1 = d0 + p.ssh;
-            if (pair && (u + 1) * kRopeUnit <= n_tok) {
-                if (st0) {
-                    __builtin_nontemporal_store(held0, d0 - kRopeUnit);
-                    __builtin_nontemporal_store(s0, d0);
-                }
-                if (st1) {
-                    __builtin_nontemporal_store(held1, d1 - kRopeUnit);
-                    __builtin_nontemporal_store(s1, d1);
-                }
-            } else {
-                const bool mine = tok < n_tok;
-                if (st0) {
-                    if (pair) __builtin_nontemporal_store(held0, d0 - kRopeUnit);
-                    if (mine) __builtin_nontemporal_store(s0, d0);
-                }
-                if (st1) {
-                    if (pair) __builtin_nontemporal_store(held1, d1 - kRopeUnit);
-                    if (mine) __builtin_nontemporal_store(s1, d1);
-                }
-            }
-        }
+        s0 = fin * (acc[0] + acc[1]);
+        if (two) s1 = fin * (acc[2] + acc[3]);
     };
 
-    // software pipeline: the loads of the next epoch's units are in flight while this epoch is computed
-    Raw ring[kEpochUnits];
-#pragma unroll
-    for (int i = 0; i < kEpochUnits; ++i) fetch(min(u0 + i, u1 - 1), ring[i]);
-    for (int e = u0; e < u1; e += kEpochUnits) {
-        qs.build(atile, lane, aop);
-#pragma unroll
-        for (int v = 0; v < kEpochUnits; ++v) {
-            if (e + v < u1) {                             // wave-uniform
-                const Raw cur = ring[v];
-                fetch(min(e + v + kEpochUnits, u1 - 1), ring[v]);
-                compute(e + v, v, cur);
+    // ---- whole units, in pairs, an epoch at a time; the loads of the next epoch's units are in flight while this
+    // epoch is computed.  Two consecutive units fill one 128-byte line of a score row: the first of a pair is kept
+    // and stored together with the second (a unit apart they reach memory as partial line writes).
+    if (nf > 0) {
+        auto deliver = [&](const Raw& r) {
+            *reinterpret_cast<u32x4*>(lds + g_lds) = r.c;
+            if constexpr (BITS == 4) *reinterpret_cast<u32x4*>(lds + m_lds) = r.m;
+        };
+        float* optr = out0 + static_cast<int64_t>(u0) * kRopeUnit + col;
+        float held0 = 0.0f, held1 = 0.0f;
+        auto pair_step = [&](int v, bool more) {
+            float s0 = 0.0f, s1 = 0.0f;
+            deliver(ring[v]);
+            if (more) fetch(ring[v]);
+            unit_scores(v, s0, s1);
+            if ((v & 1) == 0) {
+                held0 = s0;
+                held1 = s1;
+            } else {
+                if (st0) {
+                    __builtin_nontemporal_store(held0, optr);
+                    __builtin_nontemporal_store(s0, optr + kRopeUnit);
+                }
+                if (st1) {
+                    __builtin_nontemporal_store(held1, optr + out1);
+                    __builtin_nontemporal_store(s1, optr + out1 + kRopeUnit);
+                }
+                optr += 2 * kRopeUnit;
+            }
+        };
+        static_assert(kEpochUnits == 4, "an epoch is two pairs of units");
+        for (int e = u0; e < uf; e += kEpochUnits) {
+            qs.build(atile, lane, aop);
+            pair_step(0, e + kEpochUnits < uf);
+            pair_step(1, e + 1 + kEpochUnits < uf);
+            if (e + 2 < uf) {                             // wave-uniform; nf is even
+                pair_step(2, e + 2 + kEpochUnits < uf);
+                pair_step(3, e + 3 + kEpochUnits < uf);
+            }
+        }
+    }
+
+    // ---- what is left: a single unit after the pairs, the ragged end of the sequence, or everything when the
+    // store's rows are not aligned for the wide loads.  Every lane fetches for itself; rows past the end of the
+    // keys re-read the last key and are not stored.
+    {
+        const int sl = BITS == 2 ? lane - 32 : lane;          // index among the lanes that load metadata
+        const bool is_c = lane < CL, is_m = sl >= 0 && sl < 32;
+        const int c_tok = lane / PPT, c_piece = lane % PPT;
+        const int m_tok = sl & 15;
+        const uint32_t* c_base = p.codes + row0 * WPK + c_piece * 4;
+        const uint16_t* m_base = ((sl & 16) ? p.zero : p.scale) + row0 * NG;
+        unsigned char* m_dst = lds + ((sl & 16) ? ZOFF : META0) + m_tok * (2 * NG);
+#pragma nounroll
+        for (int u = uf; u < u1; ++u) {
+            const int v = (u - u0) & (kEpochUnits - 1);
+            if (v == 0) qs.build(atile, lane, aop);           // a new epoch starts here
+            if (is_c) {
+                const int t = min(u * kRopeUnit + c_tok, n_tok - 1);
+                *reinterpret_cast<u32x4*>(lds + c_tok * CS + c_piece * 16) =
+                    RP_LOAD(reinterpret_cast<const u32x4*>(c_base + static_cast<uint32_t>(t) * WPK));
+            }
+            if (is_m) {
+                const int t = min(u * kRopeUnit + m_tok, n_tok - 1);
+                if constexpr (NG == 4) {
+                    *reinterpret_cast<u32x2*>(m_dst) =
+                        RP_LOAD(reinterpret_cast<const u32x2*>(m_base + static_cast<uint32_t>(t) * 4));
+                } else if constexpr (NG == 2) {
+                    *reinterpret_cast<uint32_t*>(m_dst) =
+                        RP_LOAD(reinterpret_cast<const uint32_t*>(m_base + static_cast<uint32_t>(t) * 2));
+                } else {
+                    *reinterpret_cast<uint16_t*>(m_dst) = RP_LOAD(m_base + static_cast<uint32_t>(t));
+                }
+            }
+            float s0 = 0.0f, s1 = 0.0f;
+            unit_scores(v, s0, s1);
+            const int tok = u * kRopeUnit + col;
+            if (tok < n_tok) {
+                if (st0) __builtin_nontemporal_store(s0, out0 + tok);
+                if (st1) __builtin_nontemporal_store(s1, out0 + out1 + tok);
             }
         }
     }
@@ -469,8 +539,11 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_rope_kernel(cons
 // channels' words: one v_perm picks the byte that holds the lane's token from both, one v_and leaves the two codes
 // as fp16 subnormals at a lane-constant bit, one packed multiply by a lane-constant power of two normalises them.
 // p.n_tokens and p.store_stride are multiples of 32; p.units_per_wave counts TILES here (a multiple of 2).
+// (The 2-bit form is capped at the registers of three wavefronts per SIMD: it sits four registers above that line,
+// and the two values that move to scratch are reloaded once per epoch.)
 template <int BITS, int QDT>
-__global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(const RopeParams p) {
+__global__ void __launch_bounds__(kRopeWaves* kWave) __attribute__((amdgpu_waves_per_eu(BITS == 2 ? 3 : 2)))
+key_scores_pc_rope_kernel(const RopeParams p) {
     constexpr int TW = kD * BITS;                         // packed words per tile
     constexpr int NCL = TW / 256;                         // 16-byte code loads per lane and tile
     constexpr int DEPTH = 2;                              // tiles in flight = one epoch
@@ -484,6 +557,25 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
     const int64_t b = bh / p.n_kv_heads;
     const int kvh = static_cast<int>(bh - b * p.n_kv_heads);
 
+    // ---- this wavefront's tiles (whole epochs of two)
+    const int n_tiles = static_cast<int>(p.n_tokens / 32);
+    const int t0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
+    const int t1 = min(t0 + p.units_per_wave, n_tiles);
+    const int64_t tile0 = bh * (p.store_stride / 32);
+    struct Raw {
+        u32x4 c[NCL];
+        u32x4 m;
+    };
+    // metadata: lanes 0..15 scales, 16..31 zero-points (8 channels each); lanes 32..63 repeat those loads and
+    // drop them into a spare LDS slot (no lane tests)
+    auto fetch = [&](int t, Raw& r) {
+        const int64_t tile = tile0 + t;
+        const uint32_t* cw = p.codes + tile * TW;
+#pragma unroll
+        for (int i = 0; i < NCL; ++i) r.c[i] = RP_LOAD(reinterpret_cast<const u32x4*>(cw + (i * 64 + lane) * 4));
+        r.m = RP_LOAD(reinterpret_cast<const u32x4*>(((lane & 16) ? p.zero : p.scale) + tile * kD + 8 * (lane & 15)));
+    };
+
     constexpr int QLD = kD + 1;
     __shared__ float qlds[8 * QLD];
     __shared__ float step64[2 * 64];
@@ -492,42 +584,22 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
     stage_queries<QDT>(p, b, kvh, qlds, QLD);
     fill_trig_tables(p.inv_freq, trig, step64);
     __syncthreads();
-
-    // ---- this wavefront's tiles (whole epochs of two)
-    const int n_tiles = static_cast<int>(p.n_tokens / 32);
-    const int t0 = (static_cast<int>(blockIdx.x) * kRopeWaves + wave) * p.units_per_wave;
-    const int t1 = min(t0 + p.units_per_wave, n_tiles);
     if (t0 >= t1) return;                                 // after the last workgroup barrier
 
     uint32_t* atile = atiles + wave * 16 * kATileLd;
     QuerySide qs;
     qs.init(qlds, QLD, step64, p.inv_freq, static_cast<double>(p.pos0 + static_cast<int64_t>(t0) * 32), lane, p.qpk, atile);
 
-    const int64_t tile0 = bh * (p.store_stride / 32);
-    float* out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + 2 * kb) * p.ssh;
-    const bool st0 = 2 * kb < p.qpk, st1 = 2 * kb + 1 < p.qpk;
+    // result rows 4 kb + {0, 1}: high and low part of query head kb; rows + {2, 3}: query head kb + 4
+    const bool two = p.qpk > 4;
+    float* const out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + kb) * p.ssh;
+    const bool st0 = kb < p.qpk, st1 = kb + 4 < p.qpk;
     const float fin = p.out_scale;
 
-    constexpr int TILE_BYTES = TW * 4 + 512;              // words, then 128 scales and 128 zero-points (fp16)
+    constexpr int TILE_BYTES = TW * 4 + 512 + 512;        // words, 128 scales and 128 zero-points (fp16), spare slots
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[kRopeWaves * TILE_BYTES];
     unsigned char* lds = lds_all + wave * TILE_BYTES;
     const uint32_t* ldsw = reinterpret_cast<const uint32_t*>(lds);
-    struct Raw {
-        u32x4 c[NCL];
-        u32x4 m;
-    };
-    const bool is_m = lane < 32;                          // lanes 0..15: scales, 16..31: zero-points (8 channels each)
-    auto fetch = [&](int t, Raw& r) {
-        const int64_t tile = tile0 + t;
-        const uint32_t* cw = p.codes + tile * TW;
-#pragma unroll
-        for (int i = 0; i < NCL; ++i) r.c[i] = RP_LOAD(reinterpret_cast<const u32x4*>(cw + (i * 64 + lane) * 4));
-        r.m = u32x4{0u, 0u, 0u, 0u};
-        if (is_m) {
-            const uint16_t* mb = ((lane & 16) ? p.zero : p.scale) + tile * kD + 8 * (lane & 15);
-            r.m = RP_LOAD(reinterpret_cast<const u32x4*>(mb));
-        }
-    };
 
     // where the code of this lane's token (16 hf + col of the tile) sits inside a channel's words
     //   2-bit: word hf, bit 2 col;  4-bit: word 2 hf + (col >> 3), bit 4 (col & 7)
@@ -541,10 +613,12 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
     const h2 k512 = {static_cast<_Float16>(kCodeScale), static_cast<_Float16>(kCodeScale)};
 
     u32x4 aop[4];
-    auto compute = [&](int t, int v, const Raw& raw) {
+    // registers -> LDS tile (the registers are free afterwards); returns whether this lane saw a scale beyond the
+    // packed range
+    auto deliver = [&](const Raw& raw) -> bool {
 #pragma unroll
         for (int i = 0; i < NCL; ++i) *reinterpret_cast<u32x4*>(lds + (i * 64 + lane) * 16) = raw.c[i];
-        if (is_m) *reinterpret_cast<u32x4*>(lds + TW * 4 + lane * 16) = raw.m;
+        *reinterpret_cast<u32x4*>(lds + TW * 4 + lane * 16) = raw.m;      // lanes 32..63: the spare slots
         // the lanes that loaded the scales look for one beyond the packed range (scales are non-negative fp16
         // numbers: bit patterns order like values, 127.0 = 0x57F0)
         bool big = false;
@@ -552,6 +626,9 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
 #pragma unroll
             for (int w = 0; w < 4; ++w) big = big || (raw.m[w] & 0xFFFFu) > 0x57F0u || (raw.m[w] >> 16) > 0x57F0u;
         }
+        return big;
+    };
+    auto compute = [&](int t, int v, bool big) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -618,9 +695,11 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
             __builtin_nontemporal_store(fin * (acc[0][0] + acc[0][1]), out0 + tok);
             __builtin_nontemporal_store(fin * (acc[1][0] + acc[1][1]), out0 + tok + 16);
         }
-        if (st1) {
-            __builtin_nontemporal_store(fin * (acc[0][2] + acc[0][3]), out0 + p.ssh + tok);
-            __builtin_nontemporal_store(fin * (acc[1][2] + acc[1][3]), out0 + p.ssh + tok + 16);
+        if (two) {
+            if (st1) {
+                __builtin_nontemporal_store(fin * (acc[0][2] + acc[0][3]), out0 + 4 * p.ssh + tok);
+                __builtin_nontemporal_store(fin * (acc[1][2] + acc[1][3]), out0 + 4 * p.ssh + tok + 16);
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -635,9 +714,9 @@ __global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(c
 #pragma unroll
         for (int v = 0; v < DEPTH; ++v) {
             if (e + v < t1) {                             // wave-uniform
-                const Raw cur = ring[v];
+                const bool big = deliver(ring[v]);
                 fetch(min(e + v + DEPTH, t1 - 1), ring[v]);
-                compute(e + v, v, cur);
+                compute(e + v, v, big);
             }
         }
     }
@@ -721,6 +800,10 @@ int squat::key_scores_rope_from(const uint32_t* codes, const uint16_t* scale, co
     p.n_kv_heads = n_kv_heads;
     p.qpk = q_per_kv;
     p.out_scale = out_scale;
+    {
+        const int64_t meta_row = 2 * (128 / group);       // bytes of scales (or zero-points) per key
+        p.wide_loads = (store_stride * meta_row) % 16 == 0 && aligned(scale, 16) && aligned(zero, 16);
+    }
 
     // workgroups along the sequence: about kRopeWaves * kRopeMaxUnitsPerWave units each, spread evenly
     const int64_t n_units = (n_tokens + kRopeUnit - 1) / kRopeUnit;
@@ -808,6 +891,7 @@ int squat::key_scores_pc_rope_from(const uint32_t* codes, const uint16_t* scale,
     int64_t tpw = (n_tiles + kRopeWaves * gx - 1) / (kRopeWaves * gx);
     if (tpw < kRopeMinUnitsPerWave / 2) tpw = kRopeMinUnitsPerWave / 2;
     tpw += tpw & 1;                                       // whole epochs of two tiles
+    p.wide_loads = 0;
     p.units_per_wave = static_cast<int>(tpw);
     gx = (n_tiles + kRopeWaves * tpw - 1) / (kRopeWaves * tpw);
     const int64_t bh = n_batch * n_kv_heads;
