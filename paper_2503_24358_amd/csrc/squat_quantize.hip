@@ -138,6 +138,39 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
     const int head = static_cast<int>(prob % p.n_heads);
     const int64_t bo = prob / p.n_heads;
 
+    // The first tile's loads are issued before the panels are converted: their latency overlaps that work.
+    const uint32_t st32 = static_cast<uint32_t>(p.st);
+    u32x4 pre[NLOAD];
+    // unit -> (batch entry, first token): exact multiply-shift division by tiles_per_seq (units < 2^31)
+    auto locate = [&](uint32_t u, uint32_t& bi, int64_t& tok0) {
+        bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
+        tok0 = static_cast<int64_t>(u - bi * static_cast<uint32_t>(p.tiles_per_seq)) * kTileTokens;
+    };
+    auto issue_loads = [&](uint32_t u) {
+        uint32_t bi;
+        int64_t tok0;
+        locate(u, bi, tok0);
+        const unsigned char* base = p.k + (bo + bi) * p.sb + head * p.sh + tok0 * p.st;
+        const int64_t left = p.n_tokens - tok0;                 // >= 1 valid rows in this tile
+        const int last = left >= kTileTokens ? kTileTokens - 1 : static_cast<int>(left) - 1;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int flat = i * kWave + lane;
+            int row = flat / CPR;
+            const int ch = flat % CPR;
+            row = row < last ? row : last;      // rows past the end re-read the last valid key; their outputs are not stored
+            // streamed once: non-temporal, so the tile does not displace the update panels in L2
+            pre[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16)));
+        }
+    };
+
+    const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
+    const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
+    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
+    if (unit < nunits) issue_loads(unit);
+
+
     // Panels whose entries are all fp16 numbers (as squat_prepare writes them) have a zero low part:
     // the third matrix product is skipped for the whole head.
     bool need_lo = false;
@@ -177,37 +210,6 @@ __global__ void __launch_bounds__(waves_for(DT, GT, BT) * kWave, kWgsPerCU) quan
         __syncthreads();
         need_lo = *lo_flag != 0;
     }
-
-    const uint32_t st32 = static_cast<uint32_t>(p.st);
-    u32x4 pre[NLOAD];
-    // unit -> (batch entry, first token): exact multiply-shift division by tiles_per_seq (units < 2^31)
-    auto locate = [&](uint32_t u, uint32_t& bi, int64_t& tok0) {
-        bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
-        tok0 = static_cast<int64_t>(u - bi * static_cast<uint32_t>(p.tiles_per_seq)) * kTileTokens;
-    };
-    auto issue_loads = [&](uint32_t u) {
-        uint32_t bi;
-        int64_t tok0;
-        locate(u, bi, tok0);
-        const unsigned char* base = p.k + (bo + bi) * p.sb + head * p.sh + tok0 * p.st;
-        const int64_t left = p.n_tokens - tok0;                 // >= 1 valid rows in this tile
-        const int last = left >= kTileTokens ? kTileTokens - 1 : static_cast<int>(left) - 1;
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
-            const int flat = i * kWave + lane;
-            int row = flat / CPR;
-            const int ch = flat % CPR;
-            row = row < last ? row : last;      // rows past the end re-read the last valid key; their outputs are not stored
-            // streamed once: non-temporal, so the tile does not displace the update panels in L2
-            pre[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4*>(base + (static_cast<uint32_t>(row) * st32 + ch * 16)));
-        }
-    };
-
-    const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
-    const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
-    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
-    if (unit < nunits) issue_loads(unit);
 
     while (unit < nunits) {
         // ---- registers -> LDS (token-major rows), then read back channel-major per lane

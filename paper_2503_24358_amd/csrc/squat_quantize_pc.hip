@@ -109,6 +109,40 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
     const int head = static_cast<int>(prob % p.n_heads);
     const int64_t bo = prob / p.n_heads;
 
+    // The first tile's loads are issued before the panels are converted: their latency overlaps that work.
+    const uint32_t st32 = static_cast<uint32_t>(p.st);
+    u32x4 pre[NLOAD];
+    // unit -> (batch entry, tile): exact multiply-shift division by tiles_per_seq (units < 2^31)
+    auto locate = [&](uint32_t u, uint32_t& bi, uint32_t& tile) {
+        bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
+        tile = u - bi * static_cast<uint32_t>(p.tiles_per_seq);
+    };
+    // lane part of a load address: 16-byte chunk (lane % CPR) of row (lane / CPR); load i adds 64 / CPR rows
+    const uint32_t lane_off = static_cast<uint32_t>(lane / CPR) * st32 + static_cast<uint32_t>(lane % CPR) * 16;
+    auto issue_loads = [&](uint32_t u) {
+        uint32_t bi, tile;
+        locate(u, bi, tile);
+        // wave-uniform by construction; say so, so that the loads take a scalar base and one lane offset
+        // (the builtin returns a signed int: widen both halves as unsigned)
+        const uint64_t voff = static_cast<uint64_t>((bo + bi) * p.sb + head * p.sh +
+                                                    static_cast<int64_t>(tile) * kTileTokens * p.st);
+        const uint32_t off_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(voff >> 32)));
+        const uint32_t off_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(voff & 0xFFFFFFFFull)));
+        const unsigned char* base = p.k + ((static_cast<uint64_t>(off_hi) << 32) | static_cast<uint64_t>(off_lo));
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            // streamed once: non-temporal, so the tile does not displace the update panels in L2
+            pre[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(base + static_cast<int64_t>(i * (kWave / CPR)) * p.st + lane_off));
+        }
+    };
+
+    const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
+    const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
+    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
+    if (unit < nunits) issue_loads(unit);
+
+
     // Panels whose entries are all fp16 numbers (as squat_prepare writes them) have a zero low part:
     // the product with it is skipped for the whole head.
     bool need_lo = false;
@@ -167,38 +201,6 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
         __syncthreads();
         need_lo = *lo_flag != 0;
     }
-
-    const uint32_t st32 = static_cast<uint32_t>(p.st);
-    u32x4 pre[NLOAD];
-    // unit -> (batch entry, tile): exact multiply-shift division by tiles_per_seq (units < 2^31)
-    auto locate = [&](uint32_t u, uint32_t& bi, uint32_t& tile) {
-        bi = static_cast<uint32_t>((static_cast<uint64_t>(u) * p.div_mul) >> p.div_shift);
-        tile = u - bi * static_cast<uint32_t>(p.tiles_per_seq);
-    };
-    // lane part of a load address: 16-byte chunk (lane % CPR) of row (lane / CPR); load i adds 64 / CPR rows
-    const uint32_t lane_off = static_cast<uint32_t>(lane / CPR) * st32 + static_cast<uint32_t>(lane % CPR) * 16;
-    auto issue_loads = [&](uint32_t u) {
-        uint32_t bi, tile;
-        locate(u, bi, tile);
-        // wave-uniform by construction; say so, so that the loads take a scalar base and one lane offset
-        // (the builtin returns a signed int: widen both halves as unsigned)
-        const uint64_t voff = static_cast<uint64_t>((bo + bi) * p.sb + head * p.sh +
-                                                    static_cast<int64_t>(tile) * kTileTokens * p.st);
-        const uint32_t off_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(voff >> 32)));
-        const uint32_t off_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(voff & 0xFFFFFFFFull)));
-        const unsigned char* base = p.k + ((static_cast<uint64_t>(off_hi) << 32) | static_cast<uint64_t>(off_lo));
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
-            // streamed once: non-temporal, so the tile does not displace the update panels in L2
-            pre[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4*>(base + static_cast<int64_t>(i * (kWave / CPR)) * p.st + lane_off));
-        }
-    };
-
-    const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
-    const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
-    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
-    if (unit < nunits) issue_loads(unit);
 
     while (unit < nunits) {
         // ---- registers -> LDS (token-major rows), then read back one channel per lane
