@@ -288,6 +288,7 @@ __global__ void __launch_bounds__(kGramWaves * kWave, 1) gram_partial_f32(const 
 // nn = lane & 31, mm = 8*(e>>2) + 4*(lane>>5) + (e&3), i.e. G[4*mm + a][4*nn + b].
 constexpr int kRedLd = kD + 1;          // padded row of the LDS copy: the mirrored writes spread over the banks
 constexpr int kRedThreads = 512;
+static_assert(kPartialFloats % kRedThreads == 0, "whole entries per thread");
 constexpr size_t kRedLdsBytes = static_cast<size_t>(kD) * kRedLd * sizeof(double);
 
 // The tile layout is scattered over the matrix, so the sums are placed (both triangles) in an LDS copy of the
@@ -301,9 +302,26 @@ __global__ void __launch_bounds__(kRedThreads) gram_reduce(const float* partial,
     const float* src = partial + static_cast<int64_t>(kvh) * wgs_per_head * kPartialFloats;
     double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
     float* go = gram_out ? gram_out + static_cast<int64_t>(kvh) * kD * kD : nullptr;
-    for (int idx = threadIdx.x; idx < kPartialFloats; idx += kRedThreads) {
-        double s = 0.0;
-        for (int w = 0; w < wgs_per_head; ++w) s += static_cast<double>(src[static_cast<int64_t>(w) * kPartialFloats + idx]);
+    // Partials outermost, the thread's kRedPer entries inside: the loads of one partial (and, unrolled, of the next)
+    // are all in flight together, while every entry is still summed in the order of the partials.  (With the
+    // partials innermost a thread's loads followed one another: 165 us for 32 partials per head.)
+    constexpr int kRedPer = kPartialFloats / kRedThreads;
+    double sums[kRedPer];
+#pragma unroll
+    for (int k = 0; k < kRedPer; ++k) sums[k] = 0.0;
+#pragma unroll 2
+    for (int w = 0; w < wgs_per_head; ++w) {
+        const float* pw = src + static_cast<int64_t>(w) * kPartialFloats + threadIdx.x;
+        float v[kRedPer];
+#pragma unroll
+        for (int k = 0; k < kRedPer; ++k) v[k] = __builtin_nontemporal_load(pw + k * kRedThreads);
+#pragma unroll
+        for (int k = 0; k < kRedPer; ++k) sums[k] += static_cast<double>(v[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < kRedPer; ++k) {
+        const int idx = threadIdx.x + k * kRedThreads;
+        const double s = sums[k];
         const int t = idx >> 10, e = (idx >> 6) & 15, lane = idx & 63;
         int a = 0, b = 0;
         {
