@@ -78,6 +78,23 @@ def test_scores_query_heads_per_kv_head(qpk):
     _check(None, qval, codes, scale, zero, 2, 32, qpk, 1.0, got)
 
 
+@pytest.mark.parametrize("bits,G", [(2, 32), (4, 32), (2, 64), (4, 128), (2, 128), (4, 64)])
+@pytest.mark.parametrize("n", [333, 120])
+def test_scores_unaligned_rows_and_odd_ends(bits, G, n):
+    """The two ways out of the kernel's loop over pairs of whole units.  n = 333: an odd number of tokens per
+    (batch, head) puts the metadata rows of every second head off a 16-byte boundary, so every unit of the launch
+    (six per wavefront) is fetched lane by lane.  n = 120: rows are aligned, and the second wavefront is left with
+    one pair, one single whole unit and a ragged unit of 8 tokens."""
+    B, H, qpk = 2, 3, 4
+    gen, codes, scale, zero = _store(3250 + bits + G + n, B, H, n, bits, G)
+    q32 = (gen.standard_normal((B, H * qpk, 128)) * 2).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.BF16)
+    ct, st, zt = _dev(codes, scale, zero, bits)
+    got = squat.key_scores(util.to_device(qraw, synth.BF16), ct, st, zt, bits, G, qpk, out_scale=0.5)
+    torch.cuda.synchronize()
+    _check(None, qval, codes, scale, zero, bits, G, qpk, 0.5, got)
+
+
 def test_scores_strided_output_tiny_and_empty_inputs():
     B, H, qpk = 2, 2, 4
     for n in (1, 15, 16, 17):

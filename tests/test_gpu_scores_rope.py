@@ -119,6 +119,24 @@ def test_rope_scores_reduce_to_plain_scores_and_respect_relative_positions():
     assert np.abs(moved - base).max() <= 2e-3 * scale_ref
 
 
+@pytest.mark.parametrize("bits,G", [(2, 32), (4, 32), (2, 64), (4, 128), (2, 128)])
+@pytest.mark.parametrize("n", [333, 120])
+def test_rope_scores_unaligned_rows_and_odd_ends(bits, G, n):
+    """The two ways out of the kernel's loop over pairs of whole units.  n = 333: an odd number of tokens per
+    (batch, head) puts the metadata rows of every second head off a 16-byte boundary, so every unit of the launch
+    is fetched lane by lane (eight units per wavefront: the query-side operand changes inside that loop).
+    n = 120: rows are aligned; the second wavefront is left with one pair, a single whole unit and a ragged unit."""
+    B, H, qpk = 2, 3, 4
+    gen, codes, scale, zero = _store(5250 + bits + G + n, B, H, n, bits, G)
+    q32 = (gen.standard_normal((B, H * qpk, 128)) * 2).astype(np.float32)
+    qraw, qval = synth.store(q32, synth.BF16)
+    ct, st, zt = _dev(codes, scale, zero, bits)
+    got = squat.key_scores_rope(util.to_device(qraw, synth.BF16), ct, st, zt, bits, G, qpk,
+                                torch.from_numpy(INV_FREQ).cuda(), pos0=77, out_scale=0.5)
+    torch.cuda.synchronize()
+    _check(qval, codes, scale, zero, G, qpk, INV_FREQ, 77, 0.5, got)
+
+
 def test_rope_scores_with_scales_beyond_the_packed_range():
     """The packed dequantization multiplies the fp16 scale by 2^9, which must stay an fp16 number: units in which
     some token has a scale above 127 take the fp32 dequantization instead (wave-uniform choice).  Stores with huge
