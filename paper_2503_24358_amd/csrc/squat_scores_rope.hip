@@ -136,34 +136,29 @@ __device__ __forceinline__ void fill_trig_tables(const float* inv_freq, uint32_t
 // writes R(-theta_E) q as fp16 high (row 4 (h & 3) + 2 (h >> 2)) and low (the row after it) parts into the
 // wavefront's exchange tile (so that result lane block kb holds query heads kb and kb + 4), from
 // which every lane reads the 16 registers of its A operands.
+template <bool WIDE>
 struct QuerySide {
-    float ce[8], se[8];          // cos / sin of theta_E (the only state that lives across epochs)
+    static constexpr int NF = WIDE ? 8 : 4;
+    float ce[NF], se[NF];        // cos / sin of theta_E (the only state that lives across epochs)
     const float* qrow;           // this lane's query head in LDS (fp32)
     const float* step;           // (cos, sin) of one epoch's rotation (64 positions) per frequency, LDS
     int f0;                      // first frequency of this lane
-    bool wide;                   // NF = 8
 
     __device__ __forceinline__ void init(const float* qlds, int qld, const float* step64, const float* inv_freq,
                                          double position, int lane, int qpk, uint32_t* atile) {
-        wide = qpk > 4;
-        const int h = wide ? lane >> 3 : lane >> 4;
-        f0 = wide ? 8 * (lane & 7) : 4 * (lane & 15);
+        (void)qpk;
+        const int h = WIDE ? lane >> 3 : lane >> 4;
+        f0 = WIDE ? 8 * (lane & 7) : 4 * (lane & 15);
         qrow = qlds + h * qld;
         step = step64;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (i < 4 || wide)
-                turn_sincos(position, inv_freq[f0 + i], ce[i], se[i]);
-            else
-                ce[i] = se[i] = 0.0f;
-        }
+        for (int i = 0; i < NF; ++i) turn_sincos(position, inv_freq[f0 + i], ce[i], se[i]);
         // rows that `build` never writes (query heads past 4 in the narrow form) must read as zero
         for (int idx = lane; idx < 16 * kATileLd; idx += kWave) atile[idx] = 0u;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    template <int NF>
     __device__ __forceinline__ void rotate_and_store(uint32_t* dst) {
         uint32_t hi[NF], lo[NF];
 #pragma unroll
@@ -189,14 +184,14 @@ struct QuerySide {
     }
     // A operands of the epoch whose angles are current, then the angles move on by one epoch
     __device__ __forceinline__ void build(uint32_t* atile, int lane, u32x4 (&aop)[4]) {
-        if (wide) {
+        if constexpr (WIDE) {
             // frequencies 8 fb .. 8 fb + 7 are K-block fb & 3, chunk fb >> 2: 8 consecutive words of a row
             const int h = lane >> 3, fb = lane & 7;
-            rotate_and_store<8>(atile + (4 * (h & 3) + 2 * (h >> 2)) * kATileLd + (fb & 3) * 16 + (fb >> 2) * 8);
+            rotate_and_store(atile + (4 * (h & 3) + 2 * (h >> 2)) * kATileLd + (fb & 3) * 16 + (fb >> 2) * 8);
         } else {
             // frequencies 4 fb .. 4 fb + 3: K-block (fb >> 1) & 3, chunk fb >> 3, pairs 4 (fb & 1) .. + 3
             const int h = lane >> 4, fb = lane & 15;
-            rotate_and_store<4>(atile + (4 * h) * kATileLd + ((fb >> 1) & 3) * 16 + (fb >> 3) * 8 + (fb & 1) * 4);
+            rotate_and_store(atile + (4 * h) * kATileLd + ((fb >> 1) & 3) * 16 + (fb >> 3) * 8 + (fb & 1) * 4);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -238,8 +233,9 @@ __device__ __forceinline__ void stage_queries(const RopeParams& p, int64_t b, in
 // Per-token store.  Lane (kb = lane >> 4, col = lane & 15): token col of the unit, rotary pairs
 // (32 g + 8 kb + i, + 64), g < 2, i < 8.  Matrix product m = 2 g + (i >> 2) takes the pairs i & 3 = 0..3 of chunk g
 // as its K slots 8 kb .. 8 kb + 7 (both operands), rows = (query head, fp16 high / low part).
-// (Registers are capped at three wavefronts per SIMD: the 4-bit forms would otherwise take a few more and run two.)
-template <int BITS, int NG, int QDT>
+// (Registers are capped at three wavefronts per SIMD: the 4-bit forms for more than four query heads per KV head
+// would otherwise take a few more and run two, 6 % slower.)
+template <int BITS, int NG, int QDT, bool WIDE>
 __global__ void __launch_bounds__(kRopeWaves* kWave) __attribute__((amdgpu_waves_per_eu(3)))
 key_scores_rope_kernel(const RopeParams p) {
     constexpr int WPK = kD * BITS / 32;                   // packed words per key
@@ -323,12 +319,12 @@ key_scores_rope_kernel(const RopeParams p) {
     if (u0 >= u1) return;                                 // after the last workgroup barrier
 
     uint32_t* atile = atiles + wave * 16 * kATileLd;
-    QuerySide qs;
+    QuerySide<WIDE> qs;
     qs.init(qlds, QLD, step64, p.inv_freq, static_cast<double>(p.pos0 + static_cast<int64_t>(u0) * kRopeUnit), lane,
             p.qpk, atile);
 
     // result rows 4 kb + {0, 1}: high and low part of query head kb; rows + {2, 3}: query head kb + 4
-    const bool two = p.qpk > 4;
+    constexpr bool two = WIDE;
     const bool st0 = kb < p.qpk, st1 = kb + 4 < p.qpk;
     float* const out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + kb) * p.ssh;
     const int64_t out1 = 4 * p.ssh;
@@ -539,11 +535,8 @@ key_scores_rope_kernel(const RopeParams p) {
 // channels' words: one v_perm picks the byte that holds the lane's token from both, one v_and leaves the two codes
 // as fp16 subnormals at a lane-constant bit, one packed multiply by a lane-constant power of two normalises them.
 // p.n_tokens and p.store_stride are multiples of 32; p.units_per_wave counts TILES here (a multiple of 2).
-// (The 2-bit form is capped at the registers of three wavefronts per SIMD: it sits four registers above that line,
-// and the two values that move to scratch are reloaded once per epoch.)
-template <int BITS, int QDT>
-__global__ void __launch_bounds__(kRopeWaves* kWave) __attribute__((amdgpu_waves_per_eu(BITS == 2 ? 3 : 2)))
-key_scores_pc_rope_kernel(const RopeParams p) {
+template <int BITS, int QDT, bool WIDE>
+__global__ void __launch_bounds__(kRopeWaves* kWave) key_scores_pc_rope_kernel(const RopeParams p) {
     constexpr int TW = kD * BITS;                         // packed words per tile
     constexpr int NCL = TW / 256;                         // 16-byte code loads per lane and tile
     constexpr int DEPTH = 2;                              // tiles in flight = one epoch
@@ -587,11 +580,11 @@ key_scores_pc_rope_kernel(const RopeParams p) {
     if (t0 >= t1) return;                                 // after the last workgroup barrier
 
     uint32_t* atile = atiles + wave * 16 * kATileLd;
-    QuerySide qs;
+    QuerySide<WIDE> qs;
     qs.init(qlds, QLD, step64, p.inv_freq, static_cast<double>(p.pos0 + static_cast<int64_t>(t0) * 32), lane, p.qpk, atile);
 
     // result rows 4 kb + {0, 1}: high and low part of query head kb; rows + {2, 3}: query head kb + 4
-    const bool two = p.qpk > 4;
+    constexpr bool two = WIDE;
     float* const out0 = p.scores + b * p.ssb + (static_cast<int64_t>(kvh) * p.qpk + kb) * p.ssh;
     const bool st0 = kb < p.qpk, st1 = kb + 4 < p.qpk;
     const float fin = p.out_scale;
@@ -722,25 +715,42 @@ key_scores_pc_rope_kernel(const RopeParams p) {
     }
 }
 
+// (WIDE: more than four query heads per KV head)
+template <int BITS, int QDT>
+void launch_pc_wide(const RopeParams& p, dim3 grid, dim3 block, hipStream_t s) {
+    if (p.qpk > 4)
+        hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, QDT, true>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, QDT, false>), grid, block, 0, s, p);
+}
+
 template <int BITS>
 int launch_pc_dt(const RopeParams& p, dim3 grid, hipStream_t s) {
     const dim3 block(kRopeWaves * kWave);
     switch (p.q_dt) {
-        case SQUAT_F32: hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, SQUAT_F32>), grid, block, 0, s, p); break;
-        case SQUAT_F16: hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, SQUAT_F16>), grid, block, 0, s, p); break;
-        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_pc_rope_kernel<BITS, SQUAT_BF16>), grid, block, 0, s, p); break;
+        case SQUAT_F32: launch_pc_wide<BITS, SQUAT_F32>(p, grid, block, s); break;
+        case SQUAT_F16: launch_pc_wide<BITS, SQUAT_F16>(p, grid, block, s); break;
+        case SQUAT_BF16: launch_pc_wide<BITS, SQUAT_BF16>(p, grid, block, s); break;
         default: return SQUAT_E_BADDTYPE;
     }
     return check_launch();
+}
+
+template <int BITS, int NG, int QDT>
+void launch_wide(const RopeParams& p, dim3 grid, dim3 block, hipStream_t s) {
+    if (p.qpk > 4)
+        hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, QDT, true>), grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, QDT, false>), grid, block, 0, s, p);
 }
 
 template <int BITS, int NG>
 int launch_dt(const RopeParams& p, dim3 grid, hipStream_t s) {
     const dim3 block(kRopeWaves * kWave);
     switch (p.q_dt) {
-        case SQUAT_F32: hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, SQUAT_F32>), grid, block, 0, s, p); break;
-        case SQUAT_F16: hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, SQUAT_F16>), grid, block, 0, s, p); break;
-        case SQUAT_BF16: hipLaunchKernelGGL((key_scores_rope_kernel<BITS, NG, SQUAT_BF16>), grid, block, 0, s, p); break;
+        case SQUAT_F32: launch_wide<BITS, NG, SQUAT_F32>(p, grid, block, s); break;
+        case SQUAT_F16: launch_wide<BITS, NG, SQUAT_F16>(p, grid, block, s); break;
+        case SQUAT_BF16: launch_wide<BITS, NG, SQUAT_BF16>(p, grid, block, s); break;
         default: return SQUAT_E_BADDTYPE;
     }
     return check_launch();
