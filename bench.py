@@ -47,7 +47,7 @@ def profile_facts() -> dict:
     return facts
 
 
-def cpu_baseline(wl_args: dict, heads: int = 4, repeats: int = 8):
+def cpu_baseline(wl_args: dict, heads: int = 4, repeats: int = 16):
     """The float64 oracle, as it stands, on a bounded sample of the same workload: `heads` KV heads
     (pooled queries of 4 query heads each, all their tokens)."""
     from oracle import squat_oracle as O
