@@ -374,7 +374,12 @@ int squat_dequantize_keys_per_channel(const uint32_t* codes, const uint16_t* sca
  *
  *   codes, scale, zero   as written by squat_quantize_keys: [n_batch,
  *            n_kv_heads, n_tokens, ...], dense; codes 16-byte, scale/zero
- *            8-byte aligned.  n_tokens < 2^25.
+ *            8-byte aligned.  n_tokens < 2^25.  (Fastest when every (batch,
+ *            head) row block of scale and zero starts on a 16-byte boundary,
+ *            i.e. both bases 16-byte aligned and n_tokens * 2 * d / group a
+ *            multiple of 16: whole 16-token units are then fetched with
+ *            16-byte loads; otherwise every lane fetches its own pieces.  The
+ *            results are the same.)
  *   q        [n_batch, n_kv_heads*q_per_kv, d] dtype q_dt, element (b,hq,c) at
  *            q[b*q_stride_batch + hq*q_stride_head + c]; base 16-byte aligned,
  *            strides multiples of 8 elements; |q| < 16000.
