@@ -87,13 +87,6 @@ __device__ __forceinline__ double tri_readlane(double v, int src) {
     return __hiloint2double(hi, lo);
 }
 
-// Sum over the wavefront, the same value (bit for bit) in every lane and in every wavefront that
-// sums the same numbers: four 16-lane sums by lane permutes, combined as scalars.
-__device__ __forceinline__ double tri_wave_sum(double v) {
-    v = team_sum<16>(v);
-    return (tri_readlane(v, 0) + tri_readlane(v, 16)) + (tri_readlane(v, 32) + tri_readlane(v, 48));
-}
-
 // Sum over an aligned team of 32 lanes (two rows of 16): row sums by lane permutes, then the two rows
 // trade their sums with the row-swap instruction (no trip through the LDS crossbar).
 __device__ __forceinline__ double tri_sum32(double v) {
@@ -101,6 +94,18 @@ __device__ __forceinline__ double tri_sum32(double v) {
     const uint32_t lo = static_cast<uint32_t>(__double2loint(v)), hi = static_cast<uint32_t>(__double2hiint(v));
     const auto sl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
     const auto sh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __hiloint2double(static_cast<int>(sh[0]), static_cast<int>(sl[0])) +
+           __hiloint2double(static_cast<int>(sh[1]), static_cast<int>(sl[1]));
+}
+
+// Sum over the wavefront, the same value (bit for bit) in every lane and in every wavefront that sums the same
+// numbers: row sums, rows 0 + 1 and 2 + 3, then the two halves (all by lane permutes and swaps: the route through
+// scalar registers, four v_readlane pairs and scalar-operand adds, cost about 100 cycles more per sum).
+__device__ __forceinline__ double tri_wave_sum(double v) {
+    v = tri_sum32(v);
+    const uint32_t lo = static_cast<uint32_t>(__double2loint(v)), hi = static_cast<uint32_t>(__double2hiint(v));
+    const auto sl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto sh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
     return __hiloint2double(static_cast<int>(sh[0]), static_cast<int>(sl[0])) +
            __hiloint2double(static_cast<int>(sh[1]), static_cast<int>(sl[1]));
 }
@@ -156,8 +161,10 @@ __device__ __forceinline__ void tri_step(double (&a)[kTriRows][16], int kk, int 
     for (int r = 0; r < kTriRows; ++r) p_i[r] = v_i[r] = 0.0;
     double vj[16];
     bool live = false;
+    double xa = 0.0, xb = 0.0;                            // column entries lane and lane + 64 (used again for K)
     if (rows_live || wave == 0) {
-        const double xa = xs[lane], xb = xs[lane + 64];
+        xa = xs[lane];
+        xb = xs[lane + 64];
         const double x0 = xs[k + 1];
         // sigma = |x|^2 without its first element
         double r2 = fma(xb, xb, xa * xa);
@@ -205,7 +212,7 @@ __device__ __forceinline__ void tri_step(double (&a)[kTriRows][16], int kk, int 
         // K = beta/2 p'v ; w = p - K v ; A -= v w' + w v'
         double s;
         {
-            double va = xs[lane], vb = xs[lane + 64];
+            double va = xa, vb = xb;
             if (lane == k + 1) va -= alpha;
             if (lane + 64 == k + 1) vb -= alpha;
             s = fma(ps[lane], va, ps[lane + 64] * vb);
