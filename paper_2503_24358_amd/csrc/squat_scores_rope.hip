@@ -132,7 +132,8 @@ __device__ __forceinline__ void fill_trig_tables(const float* inv_freq, uint32_t
 
 // Query side of one wavefront.  With more than four query heads per KV head lane (h = lane >> 3, fb = lane & 7)
 // owns the NF = 8 pairs (q_h[f], q_h[f + 64]), f = 8 fb + i; with at most four (the usual grouped-query case) lane
-// (h = lane >> 4, fb = lane & 15) owns NF = 4 pairs, f = 4 fb + i, and rows 8 .. 15 of the operand stay zero.  `build`
+// (h = lane >> 4, fb = lane & 15) owns NF = 4 pairs, f = 4 fb + i, and the rows of query heads 4 .. 7 stay zero (WIDE,
+// a template parameter: the narrow form keeps half the state in registers).  `build`
 // writes R(-theta_E) q as fp16 high (row 4 (h & 3) + 2 (h >> 2)) and low (the row after it) parts into the
 // wavefront's exchange tile (so that result lane block kb holds query heads kb and kb + 4), from
 // which every lane reads the 16 registers of its A operands.
