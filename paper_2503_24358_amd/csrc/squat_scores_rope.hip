@@ -374,21 +374,29 @@ key_scores_rope_kernel(const RopeParams p) {
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // scale and zero-point of the two members of a pair of chunk g: groups (g, g + 2) * NG / 4
-        h2 dsc[2], dzp[2];
-        bool big = false;
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            const int ga = g * NG / 4, gb = (g + 2) * NG / 4;
-            auto half_of = [](const uint32_t (&x)[2], int gi) -> uint32_t { return (gi & 1) ? (x[gi >> 1] >> 16) : (x[gi >> 1] & 0xFFFFu); };
-            const uint32_t sw = half_of(sv, ga) | (half_of(sv, gb) << 16);
-            const uint32_t zw = half_of(zv, ga) | (half_of(zv, gb) << 16);
-            // scales are non-negative fp16 numbers: their bit patterns order like their values (127.0 = 0x57F0;
-            // Inf and NaN land on the careful side as well)
-            big = big || (sw & 0xFFFFu) > 0x57F0u || (sw >> 16) > 0x57F0u;
-            dsc[g] = as_h2(sw);
-            dzp[g] = as_h2(zw);
+        // scale and zero-point of the two members of a pair of chunk g: groups (g, g + 2) * NG / 4, as one packed
+        // pair per chunk (one byte permute each at most)
+        uint32_t sw[2], zw[2];
+        if constexpr (NG == 4) {
+            sw[0] = __builtin_amdgcn_perm(sv[1], sv[0], 0x05040100u);        // (s0, s2)
+            sw[1] = __builtin_amdgcn_perm(sv[1], sv[0], 0x07060302u);        // (s1, s3)
+            zw[0] = __builtin_amdgcn_perm(zv[1], zv[0], 0x05040100u);
+            zw[1] = __builtin_amdgcn_perm(zv[1], zv[0], 0x07060302u);
+        } else if constexpr (NG == 2) {
+            sw[0] = sw[1] = sv[0];                                           // (s0, s1) for both chunks
+            zw[0] = zw[1] = zv[0];
+        } else {
+            sw[0] = sw[1] = __builtin_amdgcn_perm(sv[0], sv[0], 0x01000100u);   // (s0, s0)
+            zw[0] = zw[1] = __builtin_amdgcn_perm(zv[0], zv[0], 0x01000100u);
         }
+        // scales are non-negative fp16 numbers: their bit patterns order like their values (127.0 = 0x57F0; Inf
+        // and NaN land on the careful side as well): the largest of the four, compared as packed 16-bit integers
+        typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+        const u16x2 smax = __builtin_elementwise_max(__builtin_bit_cast(u16x2, sw[0]), __builtin_bit_cast(u16x2, sw[1]));
+        const u16x2 scap = __builtin_elementwise_min(smax, u16x2{0x57F0, 0x57F0});
+        const bool big = __builtin_bit_cast(uint32_t, smax) != __builtin_bit_cast(uint32_t, scap);
+        const h2 dsc[2] = {as_h2(sw[0]), as_h2(sw[1])};
+        const h2 dzp[2] = {as_h2(zw[0]), as_h2(zw[1])};
         // dequantize into rotary pairs (Section 2: code * Delta + m), rotate, and contract
         f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
         auto body = [&](auto fast_tag) {
