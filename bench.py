@@ -454,10 +454,30 @@ def main():
         lat.sort()
         us = series(fn, 50)
         nk = 64 * heads * 32
+        # the same launch 32 times in a captured graph (a decode step flushes layer after layer): the rate the
+        # device sustains when the host's per-call cost is out of the way
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(32):
+                fn()
+        graph.replay()
+        torch.cuda.synchronize()
+        rep = []
+        for _ in range(10):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            rep.append(e0.elapsed_time(e1) * 1e3 / 32)
+        rep.sort()
+        del graph
         out["decode_flush"].append({"sequences": 64, "heads_per_launch": heads, "keys_per_flush": nk,
                                     "us_per_flush_isolated_median": lat[len(lat) // 2],
                                     "us_per_flush_back_to_back": sum(us) / len(us),
-                                    "keys_per_s_back_to_back": nk / (sum(us) / len(us) * 1e-6)})
+                                    "keys_per_s_back_to_back": nk / (sum(us) / len(us) * 1e-6),
+                                    "us_per_flush_in_a_graph_of_32": rep[len(rep) // 2],
+                                    "keys_per_s_in_a_graph": nk / (rep[len(rep) // 2] * 1e-6)})
 
     # ---- the same work issued layer by layer (8 KV heads per launch, as a prefill produces them): one stream,
     # with the per-stage split; then layer l on stream l mod S for S = 2 and 8 (equal priorities), which lets the

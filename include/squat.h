@@ -269,11 +269,15 @@ int squat_quantize_keys(const void* k, squat_dtype k_dt, int64_t n_batch, int n_
  * tiles of 32 consecutive tokens of one (batch entry, head).  The tiles that
  * share an update matrix (a head's, over the whole batch, or one batch
  * entry's when update_stride_batch != 0) form a "problem"; each problem gets
- * workgroups_per_problem persistent workgroups whose wavefronts take tiles
- *     w, w + S, w + 2 S, ...     (w = wavefront index within the problem,
+ * workgroups_per_problem persistent workgroups (as many as fill the device
+ * once, at most one per tile) whose wavefronts take tiles
+ *     w, w + S, w + 2 S, ...     (w = wavefront_in_workgroup *
+ *     workgroups_per_problem + workgroup_in_problem,
  *     S = workgroups_per_problem * wavefronts_per_workgroup)
  * until tiles_per_problem is reached.  A wavefront therefore runs
- * floor(tiles_per_problem / S) or one more tile.
+ * floor(tiles_per_problem / S) or one more tile, and a problem with fewer
+ * tiles than S leaves the higher-numbered wavefronts of every workgroup idle
+ * rather than whole workgroups.
  *
  *   has_update   0 for update == NULL.   out   host memory.
  *   Same argument checks (and status codes) as the quantize call itself.

@@ -139,7 +139,9 @@ __global__ void __launch_bounds__(pc_waves_for(DT, BT) * kWave, 1) quantize_pc_k
 
     const uint32_t nunits = static_cast<uint32_t>(p.units_per_prob);
     const uint32_t ustride = static_cast<uint32_t>(p.wgs_per_prob) * kWaves;
-    uint32_t unit = static_cast<uint32_t>(wg) * kWaves + wave;
+    // Wavefront v of workgroup w starts at tile v * workgroups + w: a problem with few tiles (a decode-time flush)
+    // is spread over the workgroups first, so its wavefronts do not share a SIMD.
+    uint32_t unit = static_cast<uint32_t>(wave) * static_cast<uint32_t>(p.wgs_per_prob) + wg;
     if (unit < nunits) issue_loads(unit);
 
 
@@ -510,7 +512,7 @@ int squat::plan_quantize_pc(squat_dtype k_dt, int64_t n_batch, int n_heads, int6
     const int bt = has_update ? g / 32 : 4;      // no update matrix: one block, plain round-to-nearest
     out.waves = pc_waves_for(k_dt, bt);
     int64_t per = (static_cast<int64_t>(device_cu_count()) + out.n_prob - 1) / out.n_prob;     // fill every CU once
-    const int64_t need = (out.units_per_prob + out.waves - 1) / out.waves;
+    const int64_t need = out.units_per_prob;     // at least one tile per workgroup
     if (per > need) per = need;
     if (per < 1) per = 1;
     if (out.n_prob * per > 0x7FFFFFFF) return SQUAT_E_BADSHAPE;

@@ -278,7 +278,13 @@ def test_quantize_plan_follows_the_documented_rule():
     assert (p.problems, p.workgroups_per_problem, p.tiles_per_problem) == (256, 1, 64)
     # per-batch matrices: a problem per (sequence, head)
     p = squat.quantize_keys_plan(bf16, 4, 8, 100, True, 128 * 128 * 8, 2, 32, 32)
-    assert (p.problems, p.tiles_per_problem) == (32, 4) and p.workgroups_per_problem == 1
+    assert (p.problems, p.tiles_per_problem) == (32, 4) and p.workgroups_per_problem == 4
+    # a one-layer flush: 64 tiles per head spread over 32 workgroups each (two wavefronts busy per workgroup)
+    p = squat.quantize_keys_plan(bf16, 64, 8, 32, True, 0, 2, 32, 32)
+    assert (p.problems, p.workgroups_per_problem, p.tiles_per_problem) == (8, 32, 64)
+    # never more workgroups than tiles
+    p = squat.quantize_keys_plan(bf16, 1, 1, 100, True, 0, 2, 32, 32)
+    assert (p.problems, p.workgroups_per_problem, p.tiles_per_problem) == (1, 4, 4)
     # fp32 keys run 6 wavefronts per workgroup, the two-tile-per-block and four-tile-statistics variants 8
     assert squat.quantize_keys_plan(f32, 1, 256, 1191, True, 0, 2, 32, 32).wavefronts_per_workgroup == 6
     assert squat.quantize_keys_plan(bf16, 1, 256, 1191, True, 0, 2, 32, 64).wavefronts_per_workgroup == 8
