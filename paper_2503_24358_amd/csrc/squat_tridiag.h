@@ -4,9 +4,11 @@
 // eigenpairs of its Gram matrix):
 //
 //   1. Householder reduction to tridiagonal form T.  The matrix lives in
-//      REGISTERS: thread (row pair, lane l of the pair's team of 8) holds columns
-//      16 l .. 16 l + 15 of two rows; per step only the column being eliminated, the
-//      product A v and two scalars travel through LDS (two barriers per step).
+//      REGISTERS, dealt out cyclically: thread (team, lane l of the team of 8)
+//      holds rows team and 64 + team at columns l, 8 + l, .., 120 + l, so the
+//      trailing block shrinks in every thread at once; per step only the column
+//      being eliminated, the product A v and two scalars travel through LDS
+//      (two barriers per step).
 //   2. The r largest eigenvalues of T by 17-section on Sturm counts (16 trial
 //      shifts per eigenvalue and round, 14 rounds from [-3, 3] ||T||): the count
 //      is the number of sign changes of the three-term recurrence of the leading
@@ -131,104 +133,129 @@ __device__ __forceinline__ double tri_rcp(double x) {
     return y;
 }
 
-// One Householder step, column k = 16 KK + CC (CC is a compile-time register index).  The kernel is
-// bound by instruction issue: per step every wavefront recomputes sigma, alpha, beta and K and re-reads v
-// and p from LDS, so fewer, fatter wavefronts do less in total.  A thread therefore holds kTriRows rows
-// (x 16 columns): v and p are read once for both rows.  The eliminated column goes to LDS with zeros
-// above the diagonal (no masks afterwards), and the rank-two update v w' + w v' is applied as two
-// multiply-adds per element.
+// Eight Householder steps, columns k = 8 CC .. 8 CC + 7 (CC is a compile-time register index).  Rows and columns
+// are dealt out cyclically: thread (team, l) holds rows team and 64 + team at columns 8 c + l, c = 0 .. 15.  The
+// trailing block of step k then shrinks in every thread at once: registers c < CC hold finished columns for every
+// lane (skipped at compile time), the rows below 64 are finished from CC = 8 on, and the wavefronts stay equally
+// loaded until k passes 71.  Per step every wavefront recomputes sigma, alpha, beta and K and re-reads its part of v
+// and p from LDS.  The eliminated column goes to LDS with zeros down to the diagonal (no masks afterwards: finished
+// rows and columns meet zeros of v and p), and the rank-two update v w' + w v' is applied as two multiply-adds per
+// element.
 template <int CC>
-__device__ __forceinline__ void tri_step(double (&a)[kTriRows][16], int kk, int i0, int l, int tid, double* L) {
-    const int k = 16 * kk + CC;
-    if (k > kTriN - 3) return;                            // uniform
-    constexpr int CN = (CC + 1) & 15;                     // register of column k + 1 ...
-    const int own = CC == 15 ? kk + 1 : kk;               // ... in this lane of the row team
+__device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, int l, int tid, double* L) {
+    static_assert(kTriRows == 2 && kTriN == 128, "rows team and 64 + team, columns 8 c + l");
+    constexpr bool kLow = CC < 8;                         // rows 0 .. 63 still reach into the trailing block
+    constexpr int R0 = kLow ? 0 : 1;                      // first row register that can be live
     const int lane = tid & 63, wave = tid >> 6;
-    double* xs = L + kTriXs + (k & 1) * kTriN;
-    double* ps = L + kTriPs + (k & 1) * kTriN;
-    if (l == kk) {
+#pragma nounroll
+    for (int ll = 0; ll < 8; ++ll) {
+        const int k = 8 * CC + ll;
+        if (k > kTriN - 3) return;                        // uniform
+        double* xs = L + kTriXs + (k & 1) * kTriN;
+        double* ps = L + kTriPs + (k & 1) * kTriN;
+        if (l == ll) {
 #pragma unroll
-        for (int r = 0; r < kTriRows; ++r) {
-            xs[i0 + r] = i0 + r > k ? a[r][CC] : 0.0;
-            if (i0 + r == k) L[kTriDd + k] = a[r][CC];
+            for (int r = 0; r < kTriRows; ++r) {
+                const int row = 64 * r + team;
+                xs[row] = row > k ? a[r][CC] : 0.0;
+                if (row == k) L[kTriDd + k] = a[r][CC];
+            }
         }
-    }
-    tri_lds_barrier();
-    const bool rows_live = 8 * kTriRows * (wave + 1) - 1 > k;   // this wavefront still owns rows of the trailing block
-    double alpha = 0.0, beta = 0.0;
-    double p_i[kTriRows], v_i[kTriRows];
+        tri_lds_barrier();
+        const bool rows_live = 64 + 8 * wave + 7 > k;     // this wavefront still owns rows of the trailing block
+        const bool low_live = kLow && 8 * wave + 7 > k;   // ... among them rows below 64
+        double alpha = 0.0, beta = 0.0;
+        double p_i[kTriRows], v_i[kTriRows];
 #pragma unroll
-    for (int r = 0; r < kTriRows; ++r) p_i[r] = v_i[r] = 0.0;
-    double vj[16];
-    bool live = false;
-    double xa = 0.0, xb = 0.0;                            // column entries lane and lane + 64 (used again for K)
-    if (rows_live || wave == 0) {
-        xa = xs[lane];
-        xb = xs[lane + 64];
-        const double x0 = xs[k + 1];
-        // sigma = |x|^2 without its first element
-        double r2 = fma(xb, xb, xa * xa);
-        r2 = tri_wave_sum(r2) - x0 * x0;
-        // (cancellation in the line above only matters when the rest is ~1e-16 |x0|^2: then the reflector is
-        // the identity to working precision either way; a tiny negative result takes the identity branch)
-        live = r2 > 0.0;
-        alpha = x0;
-        if (live) {
-            const double sigma = fma(x0, x0, r2);
-            const double sq = sigma * tri_rsqrt(sigma);
-            alpha = x0 >= 0.0 ? -sq : sq;
-            beta = tri_rcp(fma(fabs(x0), sq, sigma));     // 2 / v'v with v = x - alpha e_1
-            if (rows_live) {
+        for (int r = 0; r < kTriRows; ++r) p_i[r] = v_i[r] = 0.0;
+        double vj[16];
+        bool live = false;
+        double xa = 0.0, xb = 0.0;                        // column entries lane and lane + 64 (used again for K)
+        if (rows_live || wave == 0) {
+            xa = xs[lane];
+            xb = xs[lane + 64];
+            const double x0 = xs[k + 1];
+            // sigma = |x|^2 without its first element
+            double r2 = fma(xb, xb, xa * xa);
+            r2 = tri_wave_sum(r2) - x0 * x0;
+            // (cancellation in the line above only matters when the rest is ~1e-16 |x0|^2: then the reflector is
+            // the identity to working precision either way; a tiny negative result takes the identity branch)
+            live = r2 > 0.0;
+            alpha = x0;
+            if (live) {
+                const double sigma = fma(x0, x0, r2);
+                const double sq = sigma * tri_rsqrt(sigma);
+                alpha = x0 >= 0.0 ? -sq : sq;
+                beta = tri_rcp(fma(fabs(x0), sq, sigma)); // 2 / v'v with v = x - alpha e_1
+                if (rows_live) {
 #pragma unroll
-                for (int c = 0; c < 16; ++c) vj[c] = xs[16 * l + c];
-                if (l == own) vj[CN] -= alpha;
+                    for (int c = CC; c < 16; ++c) vj[c] = xs[8 * c + l];
+                    // column k + 1 sits in lane (ll + 1) mod 8, one register further when the lane wraps
+                    if (l == ((ll + 1) & 7)) {
+                        if (ll < 7) vj[CC] -= alpha;
+                        if constexpr (CC < 15) {
+                            if (ll == 7) vj[CC + 1] -= alpha;
+                        }
+                    }
 #pragma unroll
-                for (int r = 0; r < kTriRows; ++r) {
-                    double q4[4] = {0.0, 0.0, 0.0, 0.0};
+                    for (int r = R0; r < kTriRows; ++r) {
+                        if (r == 0 && !low_live) continue;            // uniform
+                        const int row = 64 * r + team;
+                        double q4[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                    for (int c = 0; c < 16; ++c) q4[c & 3] = fma(a[r][c], vj[c], q4[c & 3]);
-                    const double q = team_sum<8>((q4[0] + q4[1]) + (q4[2] + q4[3]));
-                    v_i[r] = xs[i0 + r];
-                    if (i0 + r == k + 1) v_i[r] -= alpha;
-                    p_i[r] = i0 + r > k ? beta * q : 0.0;
+                        for (int c = CC; c < 16; ++c) q4[c & 3] = fma(a[r][c], vj[c], q4[c & 3]);
+                        const double q = team_sum<8>((q4[0] + q4[1]) + (q4[2] + q4[3]));
+                        v_i[r] = xs[row];
+                        if (row == k + 1) v_i[r] -= alpha;
+                        p_i[r] = row > k ? beta * q : 0.0;
+                    }
                 }
             }
         }
-    }
-    // rows that are done contribute zeros; every row writes so that nothing stale is read
-    if (l == 0) {
+        // rows that are done contribute zeros; every row writes so that nothing stale is read
+        if (l == 0) {
 #pragma unroll
-        for (int r = 0; r < kTriRows; ++r) {
-            ps[i0 + r] = p_i[r];
-            L[kTriX + k * kTriN + i0 + r] = v_i[r];        // reflector k (the block of the later phases is free now)
+            for (int r = 0; r < kTriRows; ++r) {
+                const int row = 64 * r + team;
+                ps[row] = p_i[r];
+                L[kTriX + k * kTriN + row] = v_i[r];      // reflector k (the block of the later phases is free now)
+            }
         }
-    }
-    if (tid == 0) {
-        L[kTriEe + k] = alpha;
-        L[kTriBet + k] = beta;
-    }
-    tri_lds_barrier();
-    if (live && rows_live) {
-        // K = beta/2 p'v ; w = p - K v ; A -= v w' + w v'
-        double s;
-        {
-            double va = xa, vb = xb;
-            if (lane == k + 1) va -= alpha;
-            if (lane + 64 == k + 1) vb -= alpha;
-            s = fma(ps[lane], va, ps[lane + 64] * vb);
+        if (tid == 0) {
+            L[kTriEe + k] = alpha;
+            L[kTriBet + k] = beta;
         }
-        const double K = 0.5 * beta * tri_wave_sum(s);
-        double nw_i[kTriRows], nv_i[kTriRows];
+        tri_lds_barrier();
+        if (live && rows_live) {
+            // K = beta/2 p'v ; w = p - K v ; A -= v w' + w v'
+            double s;
+            {
+                double va = xa, vb = xb;
+                if (lane == k + 1) va -= alpha;
+                if (lane + 64 == k + 1) vb -= alpha;
+                s = fma(ps[lane], va, ps[lane + 64] * vb);
+            }
+            const double K = 0.5 * beta * tri_wave_sum(s);
+            double nw_i[kTriRows], nv_i[kTriRows];
 #pragma unroll
-        for (int r = 0; r < kTriRows; ++r) {
-            nw_i[r] = fma(K, v_i[r], -p_i[r]);
-            nv_i[r] = -v_i[r];
-        }
+            for (int r = 0; r < kTriRows; ++r) {
+                nw_i[r] = fma(K, v_i[r], -p_i[r]);
+                nv_i[r] = -v_i[r];
+            }
+            if (low_live) {
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            const double w = fma(-K, vj[c], ps[16 * l + c]);
+                for (int c = CC; c < 16; ++c) {
+                    const double w = fma(-K, vj[c], ps[8 * c + l]);
 #pragma unroll
-            for (int r = 0; r < kTriRows; ++r) a[r][c] = fma(nv_i[r], w, fma(nw_i[r], vj[c], a[r][c]));
+                    for (int r = 0; r < kTriRows; ++r) a[r][c] = fma(nv_i[r], w, fma(nw_i[r], vj[c], a[r][c]));
+                }
+            } else {
+#pragma unroll
+                for (int c = CC; c < 16; ++c) {
+                    const double w = fma(-K, vj[c], ps[8 * c + l]);
+                    a[1][c] = fma(nv_i[1], w, fma(nw_i[1], vj[c], a[1][c]));
+                }
+            }
         }
     }
 }
@@ -240,20 +267,16 @@ __device__ __forceinline__ void tri_step(double (&a)[kTriRows][16], int kk, int 
 __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, int r, float* qhat, float* eig,
                                                  double* L) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i0 = kTriRows * (tid >> 3), l = tid & 7;    // this thread's rows i0 .. and columns 16 l ..
+    const int team = tid >> 3, l = tid & 7;               // this thread's rows team, 64 + team and columns 8 c + l
     double* misc = L + kTriMisc;
 
     // ---- load, scale by a power of two so that the largest entry is in [1, 2)
     double a[kTriRows][16];
 #pragma unroll
     for (int r = 0; r < kTriRows; ++r) {
-        const double* src = g + (i0 + r) * kTriN + 16 * l;
+        const double* src = g + (64 * r + team) * kTriN + l;
 #pragma unroll
-        for (int c = 0; c < 16; c += 2) {
-            const double2 t = *reinterpret_cast<const double2*>(src + c);
-            a[r][c] = t.x;
-            a[r][c + 1] = t.y;
-        }
+        for (int c = 0; c < 16; ++c) a[r][c] = src[8 * c];
     }
     double amax = 0.0;
 #pragma unroll
@@ -279,35 +302,31 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     // ---- 1. Householder reduction
     for (int e = tid; e < 4 * kTriN; e += kTriThreads) L[e] = 0.0;      // column and product buffers: never read uninitialised
     __syncthreads();
-    for (int kk = 0; kk < 8; ++kk) {
-        tri_step<0>(a, kk, i0, l, tid, L);
-        tri_step<1>(a, kk, i0, l, tid, L);
-        tri_step<2>(a, kk, i0, l, tid, L);
-        tri_step<3>(a, kk, i0, l, tid, L);
-        tri_step<4>(a, kk, i0, l, tid, L);
-        tri_step<5>(a, kk, i0, l, tid, L);
-        tri_step<6>(a, kk, i0, l, tid, L);
-        tri_step<7>(a, kk, i0, l, tid, L);
-        tri_step<8>(a, kk, i0, l, tid, L);
-        tri_step<9>(a, kk, i0, l, tid, L);
-        tri_step<10>(a, kk, i0, l, tid, L);
-        tri_step<11>(a, kk, i0, l, tid, L);
-        tri_step<12>(a, kk, i0, l, tid, L);
-        tri_step<13>(a, kk, i0, l, tid, L);
-        tri_step<14>(a, kk, i0, l, tid, L);
-        tri_step<15>(a, kk, i0, l, tid, L);
+    tri_steps<0>(a, team, l, tid, L);
+    tri_steps<1>(a, team, l, tid, L);
+    tri_steps<2>(a, team, l, tid, L);
+    tri_steps<3>(a, team, l, tid, L);
+    tri_steps<4>(a, team, l, tid, L);
+    tri_steps<5>(a, team, l, tid, L);
+    tri_steps<6>(a, team, l, tid, L);
+    tri_steps<7>(a, team, l, tid, L);
+    tri_steps<8>(a, team, l, tid, L);
+    tri_steps<9>(a, team, l, tid, L);
+    tri_steps<10>(a, team, l, tid, L);
+    tri_steps<11>(a, team, l, tid, L);
+    tri_steps<12>(a, team, l, tid, L);
+    tri_steps<13>(a, team, l, tid, L);
+    tri_steps<14>(a, team, l, tid, L);
+    tri_steps<15>(a, team, l, tid, L);
+    // the last 2 x 2 block: rows and columns 126 = (team 62, lane 6) and 127 = (team 63, lane 7), register 15
+    if (team == 62 && l == 6) L[kTriDd + kTriN - 2] = a[1][15];
+    if (team == 63 && l == 7) {
+        L[kTriDd + kTriN - 1] = a[1][15];
+        L[kTriEe + kTriN - 1] = 0.0;
+        L[kTriBet + kTriN - 2] = 0.0;
+        L[kTriBet + kTriN - 1] = 0.0;
     }
-    static_assert(kTriRows >= 2, "the last two rows are taken from one thread");
-    if (l == 7 && i0 == kTriN - kTriRows) {
-        L[kTriDd + kTriN - 2] = a[kTriRows - 2][14];
-        {
-            L[kTriDd + kTriN - 1] = a[kTriRows - 1][15];
-            L[kTriEe + kTriN - 2] = a[kTriRows - 1][14];
-            L[kTriEe + kTriN - 1] = 0.0;
-            L[kTriBet + kTriN - 2] = 0.0;
-            L[kTriBet + kTriN - 1] = 0.0;
-        }
-    }
+    if (team == 63 && l == 6) L[kTriEe + kTriN - 2] = a[1][15];
     __syncthreads();
     // the reflectors leave LDS (their block is needed for the vectors and factors) and come back for step 5
     for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
