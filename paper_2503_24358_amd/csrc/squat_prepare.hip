@@ -201,20 +201,16 @@ __global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p, c
 //   - S: thread (i, k) accumulates the three 32-channel pieces of Q_i . Q_k side by side and sums them
 //     from the back (S_t needs the channels from t g on);
 //   - Cholesky: one wavefront per panel, lane = row, the row in REGISTERS, right-looking (the column
-//     being eliminated is broadcast with v_readlane);
-//   - triangular solves: every wavefront takes a few pairs of columns of Qb, lane = row of one column of the
-//     pair: the unknown just found is broadcast and every later row subtracts its multiple at once;
+//     being eliminated goes through a 32-double LDS buffer of the wavefront, which every lane reads back at
+//     uniform addresses; 1 / sqrt(pivot) from the hardware approximation and two Newton steps, branch-free);
+//   - triangular solves: one wavefront per panel, lane = COLUMN of Qb with its 32 unknowns in registers, so a
+//     step needs no exchange between lanes: the factor's entries are read at uniform LDS addresses and the
+//     whole substitution is one straight-line block;
 //   - W = -Qr^T X with four accumulators per entry.
 // A panel whose pivots span more than 1e9 (lambda times the largest eigenvalue of Qr Qr^T that large)
 // sets the head's flag: the eigen-route kernel, launched afterwards, redoes exactly the flagged heads.
 constexpr int kCholThreads = 512;           // 256 registers per thread: the Cholesky keeps a 32-double row in them
 constexpr int kCholLd = 33;
-
-__device__ __forceinline__ double chol_readlane(double v, int src) {
-    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
-    return __hiloint2double(hi, lo);
-}
 
 __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepParams p, int* need) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -225,11 +221,21 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     float* Qf = reinterpret_cast<float*>(smem);                                   // [32][129]
     double* Sall = reinterpret_cast<double*>(smem + ((32 * QLD * sizeof(float) + 15) & ~size_t(15)));   // [nsteps][32][33]
     double* Xall = Sall + nsteps * 32 * kCholLd;                                  // [nsteps][32][g]
-    int* bad = reinterpret_cast<int*>(Xall + nsteps * 32 * g);
+    double* colbuf = Xall + nsteps * 32 * g;                                      // [nsteps][32] column in flight
+    int* bad = reinterpret_cast<int*>(colbuf + nsteps * 32);
     const float* Q = p.qhat + static_cast<int64_t>(head) * r * kD;
     for (int idx = tid; idx < 32 * kD; idx += kCholThreads)
         Qf[(idx >> 7) * QLD + (idx & 127)] = idx < r * kD ? Q[idx] : 0.0f;
     if (tid == 0) bad[0] = 0;
+    // Everything of this head's matrix outside the panels is zero: row i from the start of its own block of g
+    // columns on (the panels, written at the end or by the eigen route, are the columns before it).
+    {
+        float* Uz = p.update + static_cast<int64_t>(head) * kD * kD;
+        for (int idx = tid; idx < kD * (kD / 4); idx += kCholThreads) {
+            const int row = idx / (kD / 4), col = 4 * (idx % (kD / 4));
+            if (col >= row / g * g) *reinterpret_cast<f32x4*>(Uz + row * kD + col) = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
     __syncthreads();
 
     // S_t[i][k] = [i == k] / lambda + sum_{c >= (t+1) g} Q[i][c] Q[k][c]   (rows / columns >= r: identity)
@@ -256,25 +262,37 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     // Cholesky S = C C^T, one wavefront per panel; C goes back to LDS with 1 / C_jj on the diagonal
     if (wave < nsteps) {
         double* S = Sall + wave * 32 * kCholLd;
-        const int row = lane & 31;                        // lanes 32..63 mirror lanes 0..31 (and do not store)
+        double* col = colbuf + wave * 32;
+        const int row = lane & 31;                        // lanes 32..63 mirror lanes 0..31 (same values, same addresses)
         double a[32];
 #pragma unroll
         for (int c = 0; c < 32; ++c) a[c] = S[row * kCholLd + c];
         double pmin = 1e300, pmax = 0.0;
 #pragma unroll
         for (int j = 0; j < 32; ++j) {
-            const double piv = chol_readlane(a[j], j);
+            // column j of the trailing matrix: through the wavefront's own buffer (a wavefront's LDS accesses
+            // complete in order, so the reads see this write), read back at addresses that are the same in every lane
+            col[row] = a[j];
+            const double piv = col[j];
             if (j < r) {
                 pmin = fmin(pmin, piv);
                 pmax = fmax(pmax, piv);
             }
-            const double rs = piv > 0.0 ? 1.0 / sqrt(piv) : 0.0;
+            // 1 / sqrt(pivot) without the library routines' branches (with them the compiler keeps the column's
+            // loads live across the branch and spills); two Newton steps reach the last bit
+            double y = __builtin_amdgcn_rsq(piv);
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const double e = fma(-piv * y, y, 1.0);
+                y = fma(0.5 * y, e, y);
+            }
+            const double rs = piv > 0.0 ? y : 0.0;
             const double lj = a[j] * rs;                  // column j of C (rows > j), garbage above the diagonal
             a[j] = row == j ? rs : lj;
 #pragma unroll
-            for (int k2 = j + 1; k2 < 32; ++k2) a[k2] = fma(-lj, chol_readlane(lj, k2), a[k2]);
+            for (int k2 = j + 1; k2 < 32; ++k2) a[k2] = fma(-lj, col[k2] * rs, a[k2]);
+            asm volatile("" ::: "memory");                // the next step's write stays behind these reads
         }
-        // stored with zeros above the diagonal: the solves below then need no row tests for them
         if (lane < 32) {
 #pragma unroll
             for (int c = 0; c < 32; ++c) S[row * kCholLd + c] = c > row ? 0.0 : a[c];
@@ -288,75 +306,89 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     }
     if (tid == 0) need[head] = 0;
 
-    // X = S^-1 Qb.  A wavefront holds TWO columns of Qb per register (lanes 0..31 the rows of one, lanes 32..63
-    // the rows of the other, both of the same panel) and nsteps g / 16 such pairs (6 at g = 32, 4 at g = 64).  The
-    // unknown of a step is broadcast inside each half by a lane permutation through the LDS crossbar (two
-    // v_readlane per column, which is what a broadcast to all 64 lanes costs, made this phase 44 of the
-    // kernel's 70 us).
-    {
-        const int pairs_per_panel = g / 2;
-        const int ppw = nsteps * pairs_per_panel / 8;     // pairs per wavefront: 6 or 4
-        const int row = lane & 31, half = lane >> 5;
-        double bcol[6];
-        int so[6];                                        // offset of the pair's panel in Sall (an index, so that the reads stay LDS reads)
-        int tq[6], jq[6];
+    // X = S^-1 Qb, one wavefront per panel, lane j = column j of Qb (g = 32: half a wavefront): the column's 32
+    // entries live in registers and both substitutions are straight-line code whose only memory traffic is the
+    // factor, read at addresses that are the same in every lane.  (With a lane per ROW and the unknown of every
+    // step broadcast between the lanes, the LDS crossbar bounded this phase: 26 of the kernel's 50 us.)
+    if (wave < nsteps && lane < g) {
+        const double* C = Sall + wave * 32 * kCholLd;
+        double b[32];
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
-            const int pr = min(wave + 8 * q, nsteps * pairs_per_panel - 1);
-            tq[q] = pr / pairs_per_panel;
-            jq[q] = 2 * (pr % pairs_per_panel) + half;
-            so[q] = tq[q] * 32 * kCholLd;
-            bcol[q] = static_cast<double>(Qf[row * QLD + tq[q] * g + jq[q]]);
-        }
-        const int src_base = 4 * (lane & 32);             // byte address of lane 0 of this half
-        auto half_bcast = [&](double v, int k) {
-            const int lo = __builtin_amdgcn_ds_bpermute(src_base + 4 * k, __double2loint(v));
-            const int hi = __builtin_amdgcn_ds_bpermute(src_base + 4 * k, __double2hiint(v));
-            return __hiloint2double(hi, lo);
-        };
-        // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k (C_ik = 0 for i < k as stored)
+        for (int k = 0; k < 32; ++k) b[k] = static_cast<double>(Qf[k * QLD + wave * g + lane]);
+        // The factor's column (row) of step k + 1 is fetched while step k computes; the fences keep the compiler
+        // from hoisting every load of the block to its top (which spills the registers).
+        double cur[32], nxt[32];
+        // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
+#pragma unroll
+        for (int i = 0; i < 32; ++i) cur[i] = C[i * kCholLd];
+#pragma unroll
         for (int k = 0; k < 32; ++k) {
-            const bool own = row == k;
+            if (k + 1 < 32) {
 #pragma unroll
-            for (int q = 0; q < 6; ++q) {
-                // (no test on q here: pairs past ppw repeat the last one, so that the six chains stay one
-                // straight-line block and overlap their LDS round trips)
-                const double cik = Sall[so[q] + row * kCholLd + k];              // row == k: 1 / C_kk
-                const double tk = bcol[q] * cik;
-                const double yk = half_bcast(tk, k);
-                bcol[q] = own ? tk : fma(-cik, yk, bcol[q]);
+                for (int i = k + 1; i < 32; ++i) nxt[i] = C[i * kCholLd + k + 1];
             }
+            b[k] *= cur[k];                               // the diagonal holds 1 / C_kk
+#pragma unroll
+            for (int i = k + 1; i < 32; ++i) b[i] = fma(-cur[i], b[k], b[i]);
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int i = k + 1; i < 32; ++i) cur[i] = nxt[i];
         }
-        // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k (C_ki = 0 for i > k as stored)
+        // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k
+#pragma unroll
+        for (int i = 0; i < 32; ++i) cur[i] = C[31 * kCholLd + i];
+#pragma unroll
         for (int k = 31; k >= 0; --k) {
-            const bool own = row == k;
+            if (k > 0) {
 #pragma unroll
-            for (int q = 0; q < 6; ++q) {
-                const double cki = Sall[so[q] + k * kCholLd + row];
-                const double tk = bcol[q] * cki;
-                const double xk = half_bcast(tk, k);
-                bcol[q] = own ? tk : fma(-cki, xk, bcol[q]);
+                for (int i = 0; i < k; ++i) nxt[i] = C[(k - 1) * kCholLd + i];
             }
+            b[k] *= cur[k];
+#pragma unroll
+            for (int i = 0; i < k; ++i) b[i] = fma(-cur[i], b[k], b[i]);
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < k; ++i) cur[i] = nxt[i];
         }
 #pragma unroll
-        for (int q = 0; q < 6; ++q)
-            if (q < ppw) Xall[(tq[q] * 32 + row) * g + jq[q]] = bcol[q];
+        for (int k = 0; k < 32; ++k) Xall[(wave * 32 + k) * g + lane] = b[k];
     }
     __syncthreads();
 
-    // W_t[c][j] = -sum_k Q[k][(t+1) g + c] X_t[k][j]
+    // W_t[c][j] = -sum_k Q[k][(t+1) g + c] X_t[k][j], a thread per 2 x 2 block of outputs (two LDS reads feed
+    // four multiply-adds), the blocks of all panels dealt out in one run (1536 at g = 32: three per thread)
     float* U = p.update + static_cast<int64_t>(head) * kD * kD;
-    for (int t = 0; t < nsteps; ++t) {
-        const int c0 = (t + 1) * g, nrest = kD - c0;
-        const double* X = Xall + t * 32 * g;
-        for (int idx = tid; idx < nrest * g; idx += kCholThreads) {
-            const int c = idx / g, j = idx % g;
-            double s4[4] = {0.0, 0.0, 0.0, 0.0};
+    const int hg = g / 2;
+    int total = 0;
+    for (int t = 0; t < nsteps; ++t) total += (kD - (t + 1) * g) * g / 4;
+    for (int q0 = tid; q0 < total; q0 += kCholThreads) {
+        int t = 0, q = q0;
+        while (q >= (kD - (t + 1) * g) * g / 4) {
+            q -= (kD - (t + 1) * g) * g / 4;
+            ++t;
+        }
+        const int c0 = (t + 1) * g;
+        const int c = 2 * (q / hg), j = 2 * (q % hg);
+        const double* X = Xall + t * 32 * g + j;
+        const float* Qc = Qf + c0 + c;
+        double s4[2][2][4];
 #pragma unroll
-            for (int k = 0; k < 32; ++k)
-                s4[k & 3] = fma(static_cast<double>(Qf[k * QLD + c0 + c]), X[k * g + j], s4[k & 3]);
-            const double sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-            U[(c0 + c) * kD + (c0 - g) + j] = stored_entry(-sum, p.full);
+        for (int e = 0; e < 16; ++e) (&s4[0][0][0])[e] = 0.0;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const double qa = static_cast<double>(Qc[k * QLD]), qb = static_cast<double>(Qc[k * QLD + 1]);
+            const double2 x = *reinterpret_cast<const double2*>(X + k * g);
+            s4[0][0][k & 3] = fma(qa, x.x, s4[0][0][k & 3]);
+            s4[0][1][k & 3] = fma(qa, x.y, s4[0][1][k & 3]);
+            s4[1][0][k & 3] = fma(qb, x.x, s4[1][0][k & 3]);
+            s4[1][1][k & 3] = fma(qb, x.y, s4[1][1][k & 3]);
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            float2 o;
+            o.x = stored_entry(-((s4[a][0][0] + s4[a][0][1]) + (s4[a][0][2] + s4[a][0][3])), p.full);
+            o.y = stored_entry(-((s4[a][1][0] + s4[a][1][1]) + (s4[a][1][2] + s4[a][1][3])), p.full);
+            *reinterpret_cast<float2*>(U + (c0 + c + a) * kD + (c0 - g) + j) = o;
         }
     }
 }
@@ -402,9 +434,14 @@ int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, uns
                  double* yz, int* flags, hipStream_t s) {
     const int nsteps = kD / g - 1;
     const bool trivial = (r == 0 || lambda == 0.0f || nsteps == 0);
-    const int64_t n4 = static_cast<int64_t>(n_heads) * kD * kD / 4;
-    hipLaunchKernelGGL(zero_fill, dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, s, update, n4);
-    int rc = check_launch();
+    // The Cholesky route's kernel clears its heads' matrices itself; every other route starts from a cleared tensor.
+    const bool chol_route = !trivial && r <= 32 && !isinf(lambda);
+    int rc = SQUAT_OK;
+    if (!chol_route) {
+        const int64_t n4 = static_cast<int64_t>(n_heads) * kD * kD / 4;
+        hipLaunchKernelGGL(zero_fill, dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, s, update, n4);
+        rc = check_launch();
+    }
     if (rc || trivial) return rc;
 
     PrepParams p;
@@ -428,7 +465,7 @@ int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, uns
         const int* need = nullptr;
         if (!p.hard) {
             const size_t clds = ((32 * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
-                                static_cast<size_t>(nsteps) * 32 * (kCholLd + g) * sizeof(double) + 16;
+                                static_cast<size_t>(nsteps) * 32 * (kCholLd + g + 1) * sizeof(double) + 16;
             if ((rc = set_max_lds_once(chol_done, reinterpret_cast<const void*>(prepare_chol_kernel), 140 * 1024))) return rc;
             hipLaunchKernelGGL(prepare_chol_kernel, dim3(n_heads), dim3(kCholThreads), clds, s, p, flags);
             rc = check_launch();
