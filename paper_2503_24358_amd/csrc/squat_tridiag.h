@@ -629,8 +629,16 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     }
     if (!ok) return false;                                // uniform: every thread saw the same flags
 
-    // ---- 5. back-transformation; the reflectors come back from global memory into the vectors' and
-    // factors' LDS block (the vectors are in registers now)
+    // ---- 5. back-transformation: team of 16 lanes per vector (every thread of the block: 32 vectors), lane s holds
+    // elements s, s + 16, ..., s + 112.  Per reflector and lane: one dot product over 8 elements, a sum over the 16
+    // lanes (four lane-permute stages; with 32 lanes and two vectors per thread the sums were most of the
+    // instructions), 8 multiply-adds; the next reflector's entries are fetched meanwhile.  The vectors are read
+    // from LDS in this layout before the reflectors come back from global memory into their block.
+    static_assert(kTriThreads == 16 * kTriMaxR, "one team of 16 lanes per vector");
+    const int bvj = tid >> 4, bs = tid & 15;
+    double xb[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) xb[m] = L[kTriX + 32 * (bs + 16 * m) + bvj];
     __syncthreads();
     __threadfence_block();
     {
@@ -641,48 +649,48 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
             *reinterpret_cast<double2*>(V + e) = *reinterpret_cast<const double2*>(vws + e);
         __syncthreads();
+        double vn[8];
+#pragma unroll
+        for (int m = 0; m < 8; ++m) vn[m] = V[(kTriN - 3) * kTriN + bs + 16 * m];
         for (int k = kTriN - 3; k >= 0; --k) {
             const double beta = L[kTriBet + k];
-            if (beta == 0.0) continue;                    // uniform
-            double v[4];
+            double v[8];
 #pragma unroll
-            for (int m = 0; m < 4; ++m) v[m] = V[k * kTriN + sub + 32 * m];
-            double s[NV];
+            for (int m = 0; m < 8; ++m) v[m] = vn[m];
+            if (k > 0) {
 #pragma unroll
-            for (int q = 0; q < NV; ++q) {
-                s[q] = 0.0;
-#pragma unroll
-                for (int m = 0; m < 4; ++m) s[q] = fma(v[m], xv[q][m], s[q]);
+                for (int m = 0; m < 8; ++m) vn[m] = V[(k - 1) * kTriN + bs + 16 * m];
             }
+            if (beta == 0.0) continue;                    // uniform
+            double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-            for (int q = 0; q < NV; ++q) s[q] = tri_sum32(s[q]) * beta;
+            for (int m = 0; m < 8; m += 2) {
+                s0 = fma(v[m], xb[m], s0);
+                s1 = fma(v[m + 1], xb[m + 1], s1);
+            }
+            const double sc = team_sum<16>(s0 + s1) * beta;
 #pragma unroll
-            for (int q = 0; q < NV; ++q)
-#pragma unroll
-                for (int m = 0; m < 4; ++m) xv[q][m] = fma(-s[q], v[m], xv[q][m]);
+            for (int m = 0; m < 8; ++m) xb[m] = fma(-sc, v[m], xb[m]);
         }
     }
 
     // ---- output: rank by eigenvalue, sign so that the largest component is positive, rows sqrt(lambda) v
-#pragma unroll
-    for (int q = 0; q < NV; ++q) {
-        const int vj = (tid >> 5) + q * (kTriThreads / 32);
-        if (vj >= r) continue;                            // uniform per team of 32 lanes
-        const double lam = L[kTriLam + 64 + vj];
+    if (bvj < r) {                                        // uniform per team of 16 lanes
+        const double lam = L[kTriLam + 64 + bvj];
         int rank = 0;
         for (int o = 0; o < r; ++o) {
             const double lo = L[kTriLam + 64 + o];
-            rank += (lo > lam) || (lo == lam && o < vj);
+            rank += (lo > lam) || (lo == lam && o < bvj);
         }
         double best = -1.0, bestv = 0.0;
         int besti = kTriN;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const double av = fabs(xv[q][m]);
-            if (av > best) { best = av; bestv = xv[q][m]; besti = sub + 32 * m; }
+        for (int m = 0; m < 8; ++m) {
+            const double av = fabs(xb[m]);
+            if (av > best) { best = av; bestv = xb[m]; besti = bs + 16 * m; }
         }
 #pragma unroll
-        for (int off = 16; off > 0; off >>= 1) {
+        for (int off = 8; off > 0; off >>= 1) {
             const double ob = __shfl_xor(best, off, 64);
             const double ov = __shfl_xor(bestv, off, 64);
             const int oi = __shfl_xor(besti, off, 64);
@@ -692,8 +700,8 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         const double sc = (bestv < 0.0 ? -1.0 : 1.0) * sqrt(lam_true);
         float* dst = qhat + rank * kTriN;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) dst[sub + 32 * m] = static_cast<float>(xv[q][m] * sc);
-        if (eig && sub == 0) eig[rank] = static_cast<float>(lam_true);
+        for (int m = 0; m < 8; ++m) dst[bs + 16 * m] = static_cast<float>(xb[m] * sc);
+        if (eig && bs == 0) eig[rank] = static_cast<float>(lam_true);
     }
     return true;
 }
