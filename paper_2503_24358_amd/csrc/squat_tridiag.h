@@ -3,12 +3,13 @@
 // right singular vectors and singular values of the query matrix are the
 // eigenpairs of its Gram matrix):
 //
-//   1. Householder reduction to tridiagonal form T.  The matrix lives in
-//      REGISTERS, dealt out cyclically: thread (team, lane l of the team of 8)
-//      holds rows team and 64 + team at columns l, 8 + l, .., 120 + l, so the
-//      trailing block shrinks in every thread at once; per step only the column
-//      being eliminated, the product A v and two scalars travel through LDS
-//      (two barriers per step).
+//   1. Householder reduction to tridiagonal form T.  The matrix lives in the
+//      REGISTERS of the first four wavefronts, dealt out cyclically: thread
+//      (team, lane l of the team of 8) holds rows team, 32 + team, 64 + team,
+//      96 + team at columns l, 8 + l, .., 120 + l, so the trailing block
+//      shrinks in every thread at once; per step only the column being
+//      eliminated, the product A v and two scalars travel through LDS (two
+//      barriers per step).
 //   2. The r largest eigenvalues of T by 17-section on Sturm counts (16 trial
 //      shifts per eigenvalue and round, 14 rounds from [-3, 3] ||T||): the count
 //      is the number of sign changes of the three-term recurrence of the leading
@@ -34,8 +35,12 @@
 namespace squat {
 
 constexpr int kTriN = 128;
-constexpr int kTriRows = 2;              // matrix rows per thread
-constexpr int kTriThreads = kTriN / kTriRows * 8;   // 512: a row's 128 columns are spread over 8 lanes
+constexpr int kTriRows = 4;              // matrix rows per thread in the reduction (one wavefront per SIMD holds the matrix:
+                                         // the step's scalar chain and its two wavefront sums are then done once per
+                                         // SIMD, not twice; 6 us of 325 against two rows per thread on all eight)
+constexpr int kTriRedThreads = kTriN / kTriRows * 8;   // threads that hold the matrix: a row's 128 columns are spread over 8 lanes
+constexpr int kTriThreads = 512;
+static_assert(kTriRedThreads <= kTriThreads && (kTriN / kTriRows) % 8 == 0, "whole wavefronts of 8 teams hold the matrix");
 constexpr int kTriMaxR = 32;            // vectors the LDS plan holds
 constexpr int kTriPts = 16;             // trial shifts per eigenvalue and round (32 eigenvalues x 16 = every thread of the block)
 constexpr int kTriRounds = 14;          // 17^14 > 6 * 2^53
@@ -134,36 +139,37 @@ __device__ __forceinline__ double tri_rcp(double x) {
 }
 
 // Eight Householder steps, columns k = 8 CC .. 8 CC + 7 (CC is a compile-time register index).  Rows and columns
-// are dealt out cyclically: thread (team, l) holds rows team and 64 + team at columns 8 c + l, c = 0 .. 15.  The
-// trailing block of step k then shrinks in every thread at once: registers c < CC hold finished columns for every
-// lane (skipped at compile time), the rows below 64 are finished from CC = 8 on, and the wavefronts stay equally
-// loaded until k passes 71.  Per step every wavefront recomputes sigma, alpha, beta and K and re-reads its part of v
-// and p from LDS.  The eliminated column goes to LDS with zeros down to the diagonal (no masks afterwards: finished
-// rows and columns meet zeros of v and p), and the rank-two update v w' + w v' is applied as two multiply-adds per
-// element.
+// are dealt out cyclically: thread (team, l) holds rows team, RG + team, ... (RG = 128 / kTriRows rows per group) at
+// columns 8 c + l, c = 0 .. 15.  The trailing block of step k then shrinks in every thread at once: registers c < CC
+// hold finished columns for every lane (skipped at compile time), a group of rows is finished once k passes its
+// last row, and the wavefronts stay equally loaded until the last group thins out.  Per step every wavefront
+// recomputes sigma, alpha, beta and K and re-reads its part of v and p from LDS.  The eliminated column goes to LDS
+// with zeros down to the diagonal (no masks afterwards: finished rows and columns meet zeros of v and p), and the
+// rank-two update v w' + w v' is applied as two multiply-adds per element.  Threads beyond kTriRedThreads hold no
+// part of the matrix and only keep the barriers.
 template <int CC>
 __device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, int l, int tid, double* L) {
-    static_assert(kTriRows == 2 && kTriN == 128, "rows team and 64 + team, columns 8 c + l");
-    constexpr bool kLow = CC < 8;                         // rows 0 .. 63 still reach into the trailing block
-    constexpr int R0 = kLow ? 0 : 1;                      // first row register that can be live
+    constexpr int RG = kTriN / kTriRows;                  // rows per group = teams
+    constexpr int R0 = 8 * CC / RG;                       // first row register that can be live
     const int lane = tid & 63, wave = tid >> 6;
+    const bool active = tid < kTriRedThreads;
 #pragma nounroll
     for (int ll = 0; ll < 8; ++ll) {
         const int k = 8 * CC + ll;
         if (k > kTriN - 3) return;                        // uniform
         double* xs = L + kTriXs + (k & 1) * kTriN;
         double* ps = L + kTriPs + (k & 1) * kTriN;
-        if (l == ll) {
+        if (active && l == ll) {
 #pragma unroll
             for (int r = 0; r < kTriRows; ++r) {
-                const int row = 64 * r + team;
+                const int row = RG * r + team;
                 xs[row] = row > k ? a[r][CC] : 0.0;
                 if (row == k) L[kTriDd + k] = a[r][CC];
             }
         }
         tri_lds_barrier();
-        const bool rows_live = 64 + 8 * wave + 7 > k;     // this wavefront still owns rows of the trailing block
-        const bool low_live = kLow && 8 * wave + 7 > k;   // ... among them rows below 64
+        // this wavefront still owns rows of the trailing block (its last group's last row is beyond k)
+        const bool rows_live = active && RG * (kTriRows - 1) + 8 * wave + 7 > k;
         double alpha = 0.0, beta = 0.0;
         double p_i[kTriRows], v_i[kTriRows];
 #pragma unroll
@@ -199,8 +205,8 @@ __device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, i
                     }
 #pragma unroll
                     for (int r = R0; r < kTriRows; ++r) {
-                        if (r == 0 && !low_live) continue;            // uniform
-                        const int row = 64 * r + team;
+                        if (!(RG * r + 8 * wave + 7 > k)) continue;   // uniform: this group's rows are done here
+                        const int row = RG * r + team;
                         double q4[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
                         for (int c = CC; c < 16; ++c) q4[c & 3] = fma(a[r][c], vj[c], q4[c & 3]);
@@ -213,10 +219,10 @@ __device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, i
             }
         }
         // rows that are done contribute zeros; every row writes so that nothing stale is read
-        if (l == 0) {
+        if (active && l == 0) {
 #pragma unroll
             for (int r = 0; r < kTriRows; ++r) {
-                const int row = 64 * r + team;
+                const int row = RG * r + team;
                 ps[row] = p_i[r];
                 L[kTriX + k * kTriN + row] = v_i[r];      // reflector k (the block of the later phases is free now)
             }
@@ -236,25 +242,15 @@ __device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, i
                 s = fma(ps[lane], va, ps[lane + 64] * vb);
             }
             const double K = 0.5 * beta * tri_wave_sum(s);
-            double nw_i[kTriRows], nv_i[kTriRows];
+            double w[16];
 #pragma unroll
-            for (int r = 0; r < kTriRows; ++r) {
-                nw_i[r] = fma(K, v_i[r], -p_i[r]);
-                nv_i[r] = -v_i[r];
-            }
-            if (low_live) {
+            for (int c = CC; c < 16; ++c) w[c] = fma(-K, vj[c], ps[8 * c + l]);
 #pragma unroll
-                for (int c = CC; c < 16; ++c) {
-                    const double w = fma(-K, vj[c], ps[8 * c + l]);
+            for (int r = R0; r < kTriRows; ++r) {
+                if (!(RG * r + 8 * wave + 7 > k)) continue;           // uniform
+                const double nw = fma(K, v_i[r], -p_i[r]), nv = -v_i[r];
 #pragma unroll
-                    for (int r = 0; r < kTriRows; ++r) a[r][c] = fma(nv_i[r], w, fma(nw_i[r], vj[c], a[r][c]));
-                }
-            } else {
-#pragma unroll
-                for (int c = CC; c < 16; ++c) {
-                    const double w = fma(-K, vj[c], ps[8 * c + l]);
-                    a[1][c] = fma(nv_i[1], w, fma(nw_i[1], vj[c], a[1][c]));
-                }
+                for (int c = CC; c < 16; ++c) a[r][c] = fma(nv, w[c], fma(nw, vj[c], a[r][c]));
             }
         }
     }
@@ -267,16 +263,16 @@ __device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, i
 __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, int r, float* qhat, float* eig,
                                                  double* L) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int team = tid >> 3, l = tid & 7;               // this thread's rows team, 64 + team and columns 8 c + l
+    const int team = tid >> 3, l = tid & 7;               // this thread's rows team, 32 + team, ... and columns 8 c + l
     double* misc = L + kTriMisc;
 
     // ---- load, scale by a power of two so that the largest entry is in [1, 2)
     double a[kTriRows][16];
 #pragma unroll
     for (int r = 0; r < kTriRows; ++r) {
-        const double* src = g + (64 * r + team) * kTriN + l;
+        const double* src = g + (kTriN / kTriRows * r + team) * kTriN + l;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) a[r][c] = src[8 * c];
+        for (int c = 0; c < 16; ++c) a[r][c] = tid < kTriRedThreads ? src[8 * c] : 0.0;
     }
     double amax = 0.0;
 #pragma unroll
@@ -318,15 +314,17 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     tri_steps<13>(a, team, l, tid, L);
     tri_steps<14>(a, team, l, tid, L);
     tri_steps<15>(a, team, l, tid, L);
-    // the last 2 x 2 block: rows and columns 126 = (team 62, lane 6) and 127 = (team 63, lane 7), register 15
-    if (team == 62 && l == 6) L[kTriDd + kTriN - 2] = a[1][15];
-    if (team == 63 && l == 7) {
-        L[kTriDd + kTriN - 1] = a[1][15];
+    // the last 2 x 2 block: rows 126 and 127 are the last two teams' last rows, columns 126 and 127 lanes 6 and 7
+    // at register 15
+    constexpr int kLastTeam = kTriN / kTriRows - 1;
+    if (team == kLastTeam - 1 && l == 6) L[kTriDd + kTriN - 2] = a[kTriRows - 1][15];
+    if (team == kLastTeam && l == 7) {
+        L[kTriDd + kTriN - 1] = a[kTriRows - 1][15];
         L[kTriEe + kTriN - 1] = 0.0;
         L[kTriBet + kTriN - 2] = 0.0;
         L[kTriBet + kTriN - 1] = 0.0;
     }
-    if (team == 63 && l == 6) L[kTriEe + kTriN - 2] = a[1][15];
+    if (team == kLastTeam && l == 6) L[kTriEe + kTriN - 2] = a[kTriRows - 1][15];
     __syncthreads();
     // the reflectors leave LDS (their block is needed for the vectors and factors) and come back for step 5
     for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
