@@ -249,11 +249,16 @@ def test_quantize_is_deterministic():
         assert torch.equal(x, y)
 
 
-def test_decode_flush_shape():
-    """Config 4 in miniature: many sequences x (layers*heads), one 32-token tile each, U shared across batch."""
-    B, H, n = 16, 24, 32
-    kt, kval = _keys(1000, H, n, synth.BF16, batch=B)
+@pytest.mark.parametrize("B,H,n", [(16, 24, 32),      # config 4 in miniature: one tile per (sequence, head)
+                                   (40, 1, 32),       # one head: its 40 tiles over 40 workgroups, one busy wavefront each
+                                   (3, 2, 150)])      # 15 tiles per head (the last of a sequence ragged) over 15 workgroups
+def test_decode_flush_shape(B, H, n):
+    """Few tiles per update matrix, shared across the batch: the launch spreads them over the workgroups first, so most
+    wavefronts of a workgroup have no tile at all."""
+    kt, kval = _keys(1000 + B, H, n, synth.BF16, batch=B)
     _, U = _oracle_U(1001, H, 16, 1e-3, 32)
+    plan = squat.quantize_keys_plan(torch.bfloat16, B, H, n, True, 0, 2, 32, 32)
+    assert plan.workgroups_per_problem == min(-(-256 // H), plan.tiles_per_problem)
     _check_against_oracle(kt, kval, U, 2, 32, 32)
 
 
