@@ -255,10 +255,12 @@ def test_per_channel_rejects_bad_shapes():
         squat.quantize_keys_per_channel(k64, None, 3, 32, 32)
 
 
-def test_per_channel_decode_flush_shape():
-    """Many sequences x (layers * heads), one 32-token group each, update shared across the batch."""
-    B, H, n = 16, 24, 32
-    kt, kval = _keys(3000, H, n, synth.BF16, batch=B)
+@pytest.mark.parametrize("B,H,n", [(16, 24, 32),      # many sequences x (layers * heads), one 32-token group each
+                                   (40, 1, 32),       # one head: 40 groups over 40 workgroups, one busy wavefront each
+                                   (3, 2, 160)])      # 15 groups per head over 15 workgroups
+def test_per_channel_decode_flush_shape(B, H, n):
+    """Few token groups per update matrix, shared across the batch: the launch spreads them over the workgroups first."""
+    kt, kval = _keys(3000 + B, H, n, synth.BF16, batch=B)
     _, U = _oracle_U(3001, H, 16, 1e-3, 32, fp16_grid=True)
     _check(kt, kval, U, 2, 32)
 
