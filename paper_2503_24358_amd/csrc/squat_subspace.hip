@@ -11,7 +11,9 @@
 //                 a <= b are formed (symmetry).  fp32 accumulation per
 //                 workgroup, partial tiles go to the workspace.
 //   gram_reduce   sums the workgroups' partials in fp64 in a fixed order
-//                 (deterministic), un-permutes channels and mirrors.
+//                 (deterministic), un-permutes channels and mirrors;
+//   gram_reduce_tiles  the same with a workgroup per (tile, head), for
+//                 heads with many partials.
 //   eig_tridiag_kernel  r <= 32: Householder tridiagonalisation, Sturm-count search
 //                 for the r largest eigenvalues, inverse iteration, back-transformation
 //                 (squat_tridiag.h), one workgroup per KV head; flags a head whose result
@@ -350,6 +352,58 @@ __global__ void __launch_bounds__(kRedThreads) gram_reduce(const float* partial,
     }
 }
 
+// The same sums when a head has several partials (a launch with few heads: every head's Gram kernel workgroups
+// left one each): one workgroup per (tile, head) instead of one per head, which then is bound by what one compute
+// unit can read (1.3 MB for the 32 partials of a head of a single layer: 28 us); the sums go straight to their two
+// places in the matrix (the scattered 8-byte writes are 128 KB per head).  Same order of additions, same bits.
+__global__ void __launch_bounds__(kRedThreads) gram_reduce_tiles(const float* partial, int wgs_per_head,
+                                                                 double* g64, float* gram_out, int accumulate) {
+    const int kvh = blockIdx.y, t = blockIdx.x;
+    const float* src = partial + static_cast<int64_t>(kvh) * wgs_per_head * kPartialFloats + t * 1024 + threadIdx.x;
+    double* g = g64 + static_cast<int64_t>(kvh) * kD * kD;
+    float* go = gram_out ? gram_out + static_cast<int64_t>(kvh) * kD * kD : nullptr;
+    constexpr int kPer = 1024 / kRedThreads;
+    double sums[kPer];
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) sums[k] = 0.0;
+#pragma unroll 8
+    for (int w = 0; w < wgs_per_head; ++w) {
+        float v[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k)
+            v[k] = __builtin_nontemporal_load(src + static_cast<int64_t>(w) * kPartialFloats + k * kRedThreads);
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) sums[k] += static_cast<double>(v[k]);
+    }
+    int a = 0, b = 0;
+    {
+        int c = 0;
+        for (int i = 0; i < 4; ++i)
+            for (int j = i; j < 4; ++j) {
+                if (c == t) { a = i; b = j; }
+                ++c;
+            }
+    }
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const int idx = threadIdx.x + k * kRedThreads;
+        const int e = (idx >> 6) & 15, lane = idx & 63;
+        const int nn = lane & 31;
+        const int mm = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const int row = 4 * mm + a, col = 4 * nn + b;
+        if (a != b || row <= col) {
+            double v = sums[k];
+            if (accumulate) v += g[row * kD + col];
+            g[row * kD + col] = v;
+            g[col * kD + row] = v;
+            if (go) {
+                go[row * kD + col] = static_cast<float>(v);
+                go[col * kD + row] = static_cast<float>(v);
+            }
+        }
+    }
+}
+
 constexpr int kEigTeam = 16;                    // lanes per row pair
 constexpr int kEigThreads = 64 * kEigTeam;
 constexpr int kEigLd = kD;       // rows are read with unit stride by consecutive lanes
@@ -538,8 +592,12 @@ int run_gram(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads, 
     }
     int rc = check_launch();
     if (rc) return rc;
-    hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(kRedThreads), kRedLdsBytes, s, p.partial, pl.wgs_per_head, g64,
-                       gram_out, accumulate);
+    if (pl.wgs_per_head >= 4 && n_kv_heads <= 65535)
+        hipLaunchKernelGGL(gram_reduce_tiles, dim3(kTiles, static_cast<unsigned>(n_kv_heads)), dim3(kRedThreads), 0, s, p.partial,
+                           pl.wgs_per_head, g64, gram_out, accumulate);
+    else
+        hipLaunchKernelGGL(gram_reduce, dim3(n_kv_heads), dim3(kRedThreads), kRedLdsBytes, s, p.partial, pl.wgs_per_head,
+                           g64, gram_out, accumulate);
     return check_launch();
 }
 
