@@ -32,10 +32,13 @@ def _hipcc() -> str:
 
 # Per-file extras.  The scores kernels read every matrix-product result right away with ordinary vector
 # instructions: keep those results in the ordinary register file instead of the accumulation registers
-# (saves one copy per result register).
+# (saves one copy per result register).  The update-matrix kernel for up to 64 subspace directions keeps 64
+# unknowns per lane in registers through two triangular substitutions written as fully unrolled loops: past the
+# compiler's default size limit for such loops it leaves them rolled and the unknowns in scratch memory.
 EXTRA = {"squat_scores.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "squat_scores_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-         "squat_scores_rope.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+         "squat_scores_rope.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "squat_prepare.hip": ["-mllvm", "-pragma-unroll-threshold=200000"]}
 
 
 def _compile(src: str) -> str:

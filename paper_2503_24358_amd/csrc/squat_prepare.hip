@@ -49,11 +49,12 @@ __global__ void __launch_bounds__(256) zero_fill(float* p, int64_t n4) {
     if (i < n4) reinterpret_cast<f32x4*>(p)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
-// Large r (> 32): one 1024-thread workgroup per (head, t) panel; intermediate products go through the
-// global workspace.
+// Large r (> 32; up to 64 with a finite lambda only for the heads the Cholesky kernel flags): one 1024-thread
+// workgroup per (head, t) panel; intermediate products go through the global workspace.
 template <int TS>
-__global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams p) {
+__global__ void __launch_bounds__(kPrepThreads) prepare_kernel(const PrepParams p, const int* need) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    if (need && need[blockIdx.x / p.nsteps] == 0) return;  // done by the Cholesky kernel
     constexpr int THREADS = kPrepThreads;
     const int r = p.r, rp = p.rp, g = p.g;
     double* S = reinterpret_cast<double*>(smem);     // rp x rp
@@ -194,37 +195,49 @@ __global__ void __launch_bounds__(192) prepare_wave_kernel(const PrepParams p, c
     }
 }
 
-// r <= 32 and finite lambda: S = I/lambda + Qr Qr^T is positive definite with smallest eigenvalue
+// r <= 64 and finite lambda: S = I/lambda + Qr Qr^T is positive definite with smallest eigenvalue
 // >= 1/lambda, so X = S^-1 Qb comes from a Cholesky factorisation instead of an eigen-decomposition.
 // One 512-thread workgroup per head does all panels, arranged so that no thread runs a long chain of
-// dependent LDS reads:
-//   - S: thread (i, k) accumulates the three 32-channel pieces of Q_i . Q_k side by side and sums them
-//     from the back (S_t needs the channels from t g on);
+// dependent LDS reads (RP = 32 or 64 rows: r rounded up; rows and columns >= r are the identity and cost nothing):
+//   - S: RP = 32: thread (i, k) accumulates the three 32-channel pieces of Q_i . Q_k side by side and sums them
+//     from the back (S_t needs the channels from t g on); RP = 64: a thread per 2 x 2 block of the upper triangle,
+//     mirrored;
 //   - Cholesky: one wavefront per panel, lane = row, the row in REGISTERS, right-looking (the column
-//     being eliminated goes through a 32-double LDS buffer of the wavefront, which every lane reads back at
+//     being eliminated goes through an LDS buffer of the wavefront, which every lane reads back at
 //     uniform addresses; 1 / sqrt(pivot) from the hardware approximation and two Newton steps, branch-free);
-//   - triangular solves: one wavefront per panel, lane = COLUMN of Qb with its 32 unknowns in registers, so a
-//     step needs no exchange between lanes: the factor's entries are read at uniform LDS addresses and the
-//     whole substitution is one straight-line block;
-//   - W = -Qr^T X with four accumulators per entry.
+//   - triangular solves: one wavefront per panel, lane = COLUMN of Qb with its RP unknowns in registers, so a
+//     step needs no exchange between lanes: the factor's entries are read at uniform LDS addresses, fetched ahead
+//     of their use, and the whole substitution is straight-line code;
+//   - W = -Qr^T X with a thread per 2 x 2 block of outputs and four accumulators per entry.
 // A panel whose pivots span more than 1e9 (lambda times the largest eigenvalue of Qr Qr^T that large)
 // sets the head's flag: the eigen-route kernel, launched afterwards, redoes exactly the flagged heads.
-constexpr int kCholThreads = 512;           // 256 registers per thread: the Cholesky keeps a 32-double row in them
-constexpr int kCholLd = 33;
+constexpr int kCholThreads = 512;           // 256 registers per thread: the Cholesky keeps a row of RP doubles in them
 
+constexpr size_t chol_lds_bytes(int rp, int nsteps, int g) {
+    // Qhat as fp32, the panels' matrices / factors, (RP = 32: the solutions,) the columns in flight, one flag;
+    // RP = 64 writes a panel's solutions over its factor, which is not needed any more by then
+    return ((static_cast<size_t>(rp) * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
+           static_cast<size_t>(nsteps) * rp * ((rp + 1) + (rp == 32 ? g : 0) + 1) * sizeof(double) + 16;
+}
+
+template <int RP>
 __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepParams p, int* need) {
+    static_assert(RP == 32 || RP == 64, "rows of a panel's matrix: one or two per lane pair of a wavefront");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int r = p.r, g = p.g, nsteps = p.nsteps;
     constexpr int QLD = kD + 1;
+    constexpr int LD = RP + 1;
+    constexpr bool kAlias = RP == 64;                     // the solutions X_t overwrite the factor of panel t
     const int head = blockIdx.x, tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    float* Qf = reinterpret_cast<float*>(smem);                                   // [32][129]
-    double* Sall = reinterpret_cast<double*>(smem + ((32 * QLD * sizeof(float) + 15) & ~size_t(15)));   // [nsteps][32][33]
-    double* Xall = Sall + nsteps * 32 * kCholLd;                                  // [nsteps][32][g]
-    double* colbuf = Xall + nsteps * 32 * g;                                      // [nsteps][32] column in flight
-    int* bad = reinterpret_cast<int*>(colbuf + nsteps * 32);
+    float* Qf = reinterpret_cast<float*>(smem);                                   // [RP][129]
+    double* Sall = reinterpret_cast<double*>(smem + ((RP * QLD * sizeof(float) + 15) & ~size_t(15)));   // [nsteps][RP][LD]
+    double* Xall = kAlias ? Sall : Sall + nsteps * RP * LD;                       // [nsteps][RP][g] (aliased: at the panel's factor)
+    const int xstride = kAlias ? RP * LD : RP * g;                                // doubles between the panels' solutions
+    double* colbuf = Sall + nsteps * RP * LD + (kAlias ? 0 : nsteps * RP * g);    // [nsteps][RP] column in flight
+    int* bad = reinterpret_cast<int*>(colbuf + nsteps * RP);
     const float* Q = p.qhat + static_cast<int64_t>(head) * r * kD;
-    for (int idx = tid; idx < 32 * kD; idx += kCholThreads)
+    for (int idx = tid; idx < RP * kD; idx += kCholThreads)
         Qf[(idx >> 7) * QLD + (idx & 127)] = idx < r * kD ? Q[idx] : 0.0f;
     if (tid == 0) bad[0] = 0;
     // Everything of this head's matrix outside the panels is zero: row i from the start of its own block of g
@@ -239,63 +252,113 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     __syncthreads();
 
     // S_t[i][k] = [i == k] / lambda + sum_{c >= (t+1) g} Q[i][c] Q[k][c]   (rows / columns >= r: identity)
-    for (int e = tid; e < 1024; e += kCholThreads) {
-        const int i = e >> 5, k = e & 31;
-        const float* qi = Qf + i * QLD;
-        const float* qk = Qf + k * QLD;
-        double piece[3] = {0.0, 0.0, 0.0};                // channels 32..63, 64..95, 96..127
+    if constexpr (RP == 32) {
+        for (int e = tid; e < 1024; e += kCholThreads) {
+            const int i = e >> 5, k = e & 31;
+            const float* qi = Qf + i * QLD;
+            const float* qk = Qf + k * QLD;
+            double piece[3] = {0.0, 0.0, 0.0};                // channels 32..63, 64..95, 96..127
 #pragma unroll 8
-        for (int c = 0; c < 32; ++c) {
+            for (int c = 0; c < 32; ++c) {
 #pragma unroll
-            for (int b = 0; b < 3; ++b)
-                piece[b] = fma(static_cast<double>(qi[32 * (b + 1) + c]), static_cast<double>(qk[32 * (b + 1) + c]), piece[b]);
+                for (int b = 0; b < 3; ++b)
+                    piece[b] = fma(static_cast<double>(qi[32 * (b + 1) + c]), static_cast<double>(qk[32 * (b + 1) + c]), piece[b]);
+            }
+            const double diag = i == k ? (i < r ? p.inv_lambda : 1.0) : 0.0;
+            for (int t = 0; t < nsteps; ++t) {
+                double s = diag;
+                for (int b = (t + 1) * (g / 32) - 1; b < 3; ++b) s += piece[b];
+                Sall[(t * RP + i) * LD + k] = s;
+            }
         }
-        const double diag = i == k ? (i < r ? p.inv_lambda : 1.0) : 0.0;
-        for (int t = 0; t < nsteps; ++t) {
-            double s = diag;
-            for (int b = (t + 1) * (g / 32) - 1; b < 3; ++b) s += piece[b];
-            Sall[(t * 32 + i) * kCholLd + k] = s;
+    } else {
+        // 2 x 2 blocks (rows 2 ti.., columns 2 tk.., ti <= tk) of the upper triangle: 528 of them, folded into a
+        // 16 x 33 rectangle of indices
+        for (int e = tid; e < 528; e += kCholThreads) {
+            const int fa = e / 33, fb = e % 33;
+            const int ti = fb > fa ? fa : 31 - fa;
+            const int tk = fb > fa ? fb - 1 : 31 - fa + fb;
+            const int i0 = 2 * ti, k0 = 2 * tk;
+            double piece[2][2][3];
+#pragma unroll
+            for (int q = 0; q < 12; ++q) (&piece[0][0][0])[q] = 0.0;
+            if (k0 < r) {                                 // (i0 <= k0; beyond r the rows of Qhat are zero)
+                const float* qi = Qf + i0 * QLD;
+                const float* qk = Qf + k0 * QLD;
+#pragma unroll 4
+                for (int c = 0; c < 32; ++c) {
+#pragma unroll
+                    for (int b = 0; b < 3; ++b) {
+                        const double i_0 = static_cast<double>(qi[32 * (b + 1) + c]), i_1 = static_cast<double>(qi[QLD + 32 * (b + 1) + c]);
+                        const double k_0 = static_cast<double>(qk[32 * (b + 1) + c]), k_1 = static_cast<double>(qk[QLD + 32 * (b + 1) + c]);
+                        piece[0][0][b] = fma(i_0, k_0, piece[0][0][b]);
+                        piece[0][1][b] = fma(i_0, k_1, piece[0][1][b]);
+                        piece[1][0][b] = fma(i_1, k_0, piece[1][0][b]);
+                        piece[1][1][b] = fma(i_1, k_1, piece[1][1][b]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int ia = 0; ia < 2; ++ia)
+#pragma unroll
+                for (int ka = 0; ka < 2; ++ka) {
+                    const int i = i0 + ia, k = k0 + ka;
+                    const double diag = i == k ? (i < r ? p.inv_lambda : 1.0) : 0.0;
+                    for (int t = 0; t < nsteps; ++t) {
+                        double s = diag;
+                        for (int b = (t + 1) * (g / 32) - 1; b < 3; ++b) s += piece[ia][ka][b];
+                        Sall[(t * RP + i) * LD + k] = s;
+                        Sall[(t * RP + k) * LD + i] = s;
+                    }
+                }
         }
     }
     __syncthreads();
 
     // Cholesky S = C C^T, one wavefront per panel; C goes back to LDS with 1 / C_jj on the diagonal
     if (wave < nsteps) {
-        double* S = Sall + wave * 32 * kCholLd;
-        double* col = colbuf + wave * 32;
-        const int row = lane & 31;                        // lanes 32..63 mirror lanes 0..31 (same values, same addresses)
-        double a[32];
+        double* S = Sall + wave * RP * LD;
+        double* col = colbuf + wave * RP;
+        const int row = lane & (RP - 1);                  // RP = 32: lanes 32..63 mirror lanes 0..31 (same values, same addresses)
+        double a[RP];
 #pragma unroll
-        for (int c = 0; c < 32; ++c) a[c] = S[row * kCholLd + c];
+        for (int c = 0; c < RP; ++c) a[c] = S[row * LD + c];
         double pmin = 1e300, pmax = 0.0;
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            // column j of the trailing matrix: through the wavefront's own buffer (a wavefront's LDS accesses
-            // complete in order, so the reads see this write), read back at addresses that are the same in every lane
-            col[row] = a[j];
-            const double piv = col[j];
-            if (j < r) {
-                pmin = fmin(pmin, piv);
-                pmax = fmax(pmax, piv);
-            }
-            // 1 / sqrt(pivot) without the library routines' branches (with them the compiler keeps the column's
-            // loads live across the branch and spills); two Newton steps reach the last bit
-            double y = __builtin_amdgcn_rsq(piv);
+        for (int j = 0; j < RP; ++j) {
+            if (RP == 64 || j < r) {                      // uniform; the rows and columns from r on are the identity already
+                                                          // (64 guarded steps make the compiler keep the row in scratch memory)
+                // column j of the trailing matrix: through the wavefront's own buffer (a wavefront's LDS accesses
+                // complete in order, so the reads see this write), read back at addresses that are the same in every lane
+                col[row] = a[j];
+                const double piv = col[j];
+                if (j < r) {
+                    pmin = fmin(pmin, piv);
+                    pmax = fmax(pmax, piv);
+                }
+                // 1 / sqrt(pivot) without the library routines' branches (with them the compiler keeps the column's
+                // loads live across the branch and spills); two Newton steps reach the last bit
+                double y = __builtin_amdgcn_rsq(piv);
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const double e = fma(-piv * y, y, 1.0);
-                y = fma(0.5 * y, e, y);
-            }
-            const double rs = piv > 0.0 ? y : 0.0;
-            const double lj = a[j] * rs;                  // column j of C (rows > j), garbage above the diagonal
-            a[j] = row == j ? rs : lj;
+                for (int it = 0; it < 2; ++it) {
+                    const double e = fma(-piv * y, y, 1.0);
+                    y = fma(0.5 * y, e, y);
+                }
+                const double rs = piv > 0.0 ? y : 0.0;
+                const double lj = a[j] * rs;              // column j of C (rows > j), garbage above the diagonal
+                a[j] = row == j ? rs : lj;
 #pragma unroll
-            for (int k2 = j + 1; k2 < 32; ++k2) a[k2] = fma(-lj, col[k2] * rs, a[k2]);
-            asm volatile("" ::: "memory");                // the next step's write stays behind these reads
+                for (int k2 = j + 1; k2 < RP; ++k2) {
+                    a[k2] = fma(-lj, col[k2] * rs, a[k2]);
+                    // (half a long column at a time, so that its loads and the row fit the registers)
+                    if (RP == 64 && k2 == j + 32) asm volatile("" ::: "memory");
+                }
+                asm volatile("" ::: "memory");            // the next step's write stays behind these reads
+            }
         }
-        if (lane < 32) {
+        if (lane < RP) {
 #pragma unroll
-            for (int c = 0; c < 32; ++c) S[row * kCholLd + c] = c > row ? 0.0 : a[c];
+            for (int c = 0; c < RP; ++c) S[row * LD + c] = c > row ? 0.0 : a[c];
         }
         if (lane == 0 && !(pmin > 1e-9 * pmax)) atomicOr(bad, 1);       // also catches NaN
     }
@@ -306,52 +369,123 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
     }
     if (tid == 0) need[head] = 0;
 
-    // X = S^-1 Qb, one wavefront per panel, lane j = column j of Qb (g = 32: half a wavefront): the column's 32
+    // X = S^-1 Qb, one wavefront per panel, lane j = column j of Qb (g = 32: half a wavefront): the column's
     // entries live in registers and both substitutions are straight-line code whose only memory traffic is the
     // factor, read at addresses that are the same in every lane.  (With a lane per ROW and the unknown of every
     // step broadcast between the lanes, the LDS crossbar bounded this phase: 26 of the kernel's 50 us.)
     if (wave < nsteps && lane < g) {
-        const double* C = Sall + wave * 32 * kCholLd;
-        double b[32];
+        const double* C = Sall + wave * RP * LD;
+        double b[RP];
 #pragma unroll
-        for (int k = 0; k < 32; ++k) b[k] = static_cast<double>(Qf[k * QLD + wave * g + lane]);
-        // The factor's column (row) of step k + 1 is fetched while step k computes; the fences keep the compiler
-        // from hoisting every load of the block to its top (which spills the registers).
-        double cur[32], nxt[32];
-        // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
+        for (int k = 0; k < RP; ++k) b[k] = static_cast<double>(Qf[k * QLD + wave * g + lane]);
+        if constexpr (RP == 32) {
+            // The factor's column (row) of step k + 1 is fetched while step k computes; the fences keep the compiler
+            // from hoisting every load of the block to its top (which spills the registers).
+            double cur[32], nxt[32];
+            // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
 #pragma unroll
-        for (int i = 0; i < 32; ++i) cur[i] = C[i * kCholLd];
+            for (int i = 0; i < 32; ++i) cur[i] = C[i * LD];
 #pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            if (k + 1 < 32) {
+            for (int k = 0; k < 32; ++k) {
+                if (k + 1 < 32) {
 #pragma unroll
-                for (int i = k + 1; i < 32; ++i) nxt[i] = C[i * kCholLd + k + 1];
+                    for (int i = k + 1; i < 32; ++i) nxt[i] = C[i * LD + k + 1];
+                }
+                b[k] *= cur[k];                           // the diagonal holds 1 / C_kk
+#pragma unroll
+                for (int i = k + 1; i < 32; ++i) b[i] = fma(-cur[i], b[k], b[i]);
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int i = k + 1; i < 32; ++i) cur[i] = nxt[i];
             }
-            b[k] *= cur[k];                               // the diagonal holds 1 / C_kk
+            // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k
 #pragma unroll
-            for (int i = k + 1; i < 32; ++i) b[i] = fma(-cur[i], b[k], b[i]);
-            asm volatile("" ::: "memory");
+            for (int i = 0; i < 32; ++i) cur[i] = C[31 * LD + i];
 #pragma unroll
-            for (int i = k + 1; i < 32; ++i) cur[i] = nxt[i];
-        }
-        // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k
+            for (int k = 31; k >= 0; --k) {
+                if (k > 0) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) cur[i] = C[31 * kCholLd + i];
+                    for (int i = 0; i < k; ++i) nxt[i] = C[(k - 1) * LD + i];
+                }
+                b[k] *= cur[k];
 #pragma unroll
-        for (int k = 31; k >= 0; --k) {
-            if (k > 0) {
+                for (int i = 0; i < k; ++i) b[i] = fma(-cur[i], b[k], b[i]);
+                asm volatile("" ::: "memory");
 #pragma unroll
-                for (int i = 0; i < k; ++i) nxt[i] = C[(k - 1) * kCholLd + i];
+                for (int i = 0; i < k; ++i) cur[i] = nxt[i];
             }
-            b[k] *= cur[k];
+        } else {
+            // 64 unknowns leave room for 16 entries of the factor at a time and 16 more on their way: a step's column
+            // (row) is taken in pieces of 16, the next piece (of this step or the next) fetched while one is used.
+            // (The steps from r on meet zeros and the identity; guarding them makes the compiler keep the unknowns in
+            // scratch memory.)
+            constexpr int PC = 16;
+            double cur[PC], nxt[PC], dcur, dnxt = 0.0;
+            // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
+            dcur = C[0];
 #pragma unroll
-            for (int i = 0; i < k; ++i) b[i] = fma(-cur[i], b[k], b[i]);
-            asm volatile("" ::: "memory");
+            for (int e = 0; e < PC; ++e) cur[e] = C[(1 + e) * LD];
 #pragma unroll
-            for (int i = 0; i < k; ++i) cur[i] = nxt[i];
+            for (int k = 0; k < RP; ++k) {
+                b[k] *= dcur;                             // the diagonal holds 1 / C_kk
+                if (k + 1 < RP) dnxt = C[(k + 1) * LD + k + 1];
+#pragma unroll
+                for (int pc = 0; pc < RP / PC; ++pc) {    // (a constant number of trips, so that the loop unrolls)
+                    const int i0 = k + 1 + pc * PC;
+                    if (i0 >= RP) continue;
+                    // the piece after this one: further down this column, or the head of the next
+                    if (i0 + PC < RP) {
+#pragma unroll
+                        for (int e = 0; e < PC; ++e)
+                            if (i0 + PC + e < RP) nxt[e] = C[(i0 + PC + e) * LD + k];
+                    } else if (k + 2 < RP) {
+#pragma unroll
+                        for (int e = 0; e < PC; ++e)
+                            if (k + 2 + e < RP) nxt[e] = C[(k + 2 + e) * LD + k + 1];
+                    }
+#pragma unroll
+                    for (int e = 0; e < PC; ++e)
+                        if (i0 + e < RP) b[i0 + e] = fma(-cur[e], b[k], b[i0 + e]);
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int e = 0; e < PC; ++e) cur[e] = nxt[e];
+                }
+                dcur = dnxt;
+            }
+            // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k (row k of the factor, from its start)
+            dcur = C[(RP - 1) * LD + RP - 1];
+#pragma unroll
+            for (int e = 0; e < PC; ++e) cur[e] = C[(RP - 1) * LD + e];
+#pragma unroll
+            for (int k = RP - 1; k >= 0; --k) {
+                b[k] *= dcur;
+                if (k > 0) dnxt = C[(k - 1) * LD + k - 1];
+#pragma unroll
+                for (int pc = 0; pc < RP / PC; ++pc) {
+                    const int i0 = pc * PC;
+                    if (i0 >= k) continue;
+                    if (i0 + PC < k) {
+#pragma unroll
+                        for (int e = 0; e < PC; ++e)
+                            if (i0 + PC + e < k) nxt[e] = C[k * LD + i0 + PC + e];
+                    } else if (k > 1) {
+#pragma unroll
+                        for (int e = 0; e < PC; ++e)
+                            if (e < k - 1) nxt[e] = C[(k - 1) * LD + e];
+                    }
+#pragma unroll
+                    for (int e = 0; e < PC; ++e)
+                        if (i0 + e < k) b[i0 + e] = fma(-cur[e], b[k], b[i0 + e]);
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int e = 0; e < PC; ++e) cur[e] = nxt[e];
+                }
+                dcur = dnxt;
+            }
         }
+        // (aliased: every lane of the wavefront is past its last read of the factor here)
 #pragma unroll
-        for (int k = 0; k < 32; ++k) Xall[(wave * 32 + k) * g + lane] = b[k];
+        for (int k = 0; k < RP; ++k) Xall[wave * xstride + k * g + lane] = b[k];
     }
     __syncthreads();
 
@@ -369,19 +503,29 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
         }
         const int c0 = (t + 1) * g;
         const int c = 2 * (q / hg), j = 2 * (q % hg);
-        const double* X = Xall + t * 32 * g + j;
+        const double* X = Xall + t * xstride + j;
         const float* Qc = Qf + c0 + c;
         double s4[2][2][4];
 #pragma unroll
         for (int e = 0; e < 16; ++e) (&s4[0][0][0])[e] = 0.0;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
+        auto term = [&](int k, int slot) {
             const double qa = static_cast<double>(Qc[k * QLD]), qb = static_cast<double>(Qc[k * QLD + 1]);
             const double2 x = *reinterpret_cast<const double2*>(X + k * g);
-            s4[0][0][k & 3] = fma(qa, x.x, s4[0][0][k & 3]);
-            s4[0][1][k & 3] = fma(qa, x.y, s4[0][1][k & 3]);
-            s4[1][0][k & 3] = fma(qb, x.x, s4[1][0][k & 3]);
-            s4[1][1][k & 3] = fma(qb, x.y, s4[1][1][k & 3]);
+            s4[0][0][slot] = fma(qa, x.x, s4[0][0][slot]);
+            s4[0][1][slot] = fma(qa, x.y, s4[0][1][slot]);
+            s4[1][0][slot] = fma(qb, x.x, s4[1][0][slot]);
+            s4[1][1][slot] = fma(qb, x.y, s4[1][1][slot]);
+        };
+        if constexpr (RP == 32) {
+#pragma unroll
+            for (int k = 0; k < 32; ++k) term(k, k & 3);
+        } else {
+            const int kmax = (r + 3) & ~3;                // rows from r on are zero on both sides
+#pragma unroll 2
+            for (int k4 = 0; k4 < kmax; k4 += 4) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) term(k4 + kk, kk);
+            }
         }
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
@@ -425,7 +569,7 @@ PrepScratch prep_scratch(int n_heads, int r, int g, bool hard) {
     PrepScratch out{0, 0};
     if (rp > 32)
         out.yz_bytes = (static_cast<size_t>(n_heads) * nsteps * rp * (g + kD) * sizeof(double) + 255) & ~size_t(255);
-    else if (!hard)
+    if (!hard && rp <= 64)
         out.flag_bytes = (static_cast<size_t>(n_heads) * sizeof(int) + 255) & ~size_t(255);
     return out;
 }
@@ -435,7 +579,7 @@ int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, uns
     const int nsteps = kD / g - 1;
     const bool trivial = (r == 0 || lambda == 0.0f || nsteps == 0);
     // The Cholesky route's kernel clears its heads' matrices itself; every other route starts from a cleared tensor.
-    const bool chol_route = !trivial && r <= 32 && !isinf(lambda);
+    const bool chol_route = !trivial && r <= 64 && !isinf(lambda);
     int rc = SQUAT_OK;
     if (!chol_route) {
         const int64_t n4 = static_cast<int64_t>(n_heads) * kD * kD / 4;
@@ -456,22 +600,26 @@ int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, uns
     p.full = (flags_arg & SQUAT_PREPARE_FULL_PRECISION) ? 1 : 0;
     p.inv_lambda = p.hard ? 0.0 : 1.0 / static_cast<double>(lambda);
     p.nprob = n_heads * nsteps;
+    const int* need = nullptr;
+    if (chol_route) {
+        static std::atomic<uint64_t> chol32_done{0}, chol64_done{0};
+        if (p.rp <= 32) {
+            if ((rc = set_max_lds_once(chol32_done, reinterpret_cast<const void*>(prepare_chol_kernel<32>), 140 * 1024))) return rc;
+            hipLaunchKernelGGL(prepare_chol_kernel<32>, dim3(n_heads), dim3(kCholThreads), chol_lds_bytes(32, nsteps, g), s, p, flags);
+        } else {
+            if ((rc = set_max_lds_once(chol64_done, reinterpret_cast<const void*>(prepare_chol_kernel<64>), 140 * 1024))) return rc;
+            hipLaunchKernelGGL(prepare_chol_kernel<64>, dim3(n_heads), dim3(kCholThreads), chol_lds_bytes(64, nsteps, g), s, p, flags);
+        }
+        rc = check_launch();
+        if (rc) return rc;
+        need = flags;                                     // the eigen route below redoes the flagged heads only
+    }
     if (p.rp <= 32) {
         // one workgroup per head, one wavefront per panel
         const size_t lds = ((static_cast<size_t>(p.rp) * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
                            nsteps * (static_cast<size_t>(p.rp) * (p.rp + 2) + p.rp + 2 + 2 * static_cast<size_t>(p.rp) * g) * sizeof(double);
-        static std::atomic<uint64_t> wave_done{0}, chol_done{0};
+        static std::atomic<uint64_t> wave_done{0};
         if ((rc = set_max_lds_once(wave_done, reinterpret_cast<const void*>(prepare_wave_kernel), 140 * 1024))) return rc;
-        const int* need = nullptr;
-        if (!p.hard) {
-            const size_t clds = ((32 * (kD + 1) * sizeof(float) + 15) & ~size_t(15)) +
-                                static_cast<size_t>(nsteps) * 32 * (kCholLd + g + 1) * sizeof(double) + 16;
-            if ((rc = set_max_lds_once(chol_done, reinterpret_cast<const void*>(prepare_chol_kernel), 140 * 1024))) return rc;
-            hipLaunchKernelGGL(prepare_chol_kernel, dim3(n_heads), dim3(kCholThreads), clds, s, p, flags);
-            rc = check_launch();
-            if (rc) return rc;
-            need = flags;
-        }
         hipLaunchKernelGGL(prepare_wave_kernel, dim3(n_heads), dim3(64 * nsteps), lds, s, p, need);
         return check_launch();
     }
@@ -483,7 +631,7 @@ int prepare_impl(const float* qhat, int n_heads, int r, float lambda, int g, uns
         static std::atomic<uint64_t> done{0};                                                              \
         if ((rc = set_max_lds_once(done, reinterpret_cast<const void*>(prepare_kernel<TS>), 140 * 1024)))  \
             return rc;                                                                                     \
-        hipLaunchKernelGGL(prepare_kernel<TS>, grid, dim3(kPrepThreads), lds, s, p);                       \
+        hipLaunchKernelGGL(prepare_kernel<TS>, grid, dim3(kPrepThreads), lds, s, p, need);                 \
     } while (0)
     if (ts == 64) SQUAT_PREP_LAUNCH(64);
     else if (ts == 32) SQUAT_PREP_LAUNCH(32);
@@ -565,9 +713,9 @@ extern "C" int squat_prepare_noalloc(const float* qhat, int n_heads, int d, int 
         if (need.yz_bytes + need.flag_bytes > kStaticScratchBytes) return SQUAT_E_WORKSPACE;
         void* base = nullptr;
         if (int rc = scratch_address(&base)) return rc;
-        // a call uses one of the two pieces, from the start of the array
+        // the intermediate products first (if any), the flags behind them
         yz = static_cast<double*>(base);
-        flags = static_cast<int*>(base);
+        flags = reinterpret_cast<int*>(static_cast<unsigned char*>(base) + need.yz_bytes);
     }
     return prepare_impl(qhat, n_heads, r, lambda, g, 0u, update, yz, flags, static_cast<hipStream_t>(stream));
 }
