@@ -97,9 +97,10 @@ const char* squat_strerror(int status);
  *           256-byte aligned.
  *   0 <= r <= d.  n_tokens >= 1.  The Gram products are exact for bf16/f16
  *   inputs and accumulate in fp32 within a slab of tokens, fp64 across slabs;
- *   the eigen-solver works in fp64 (r <= 32: Householder tridiagonalisation,
- *   Sturm-count search, inverse iteration; otherwise, or if that route's own
- *   residual checks fail for a head, cyclic one-sided Jacobi).
+ *   the eigen-solver works in fp64 (r <= 64: Householder tridiagonalisation,
+ *   Sturm-count search, inverse iteration, the vectors in batches of 32;
+ *   otherwise, or if that route's own checks fail for a head, cyclic
+ *   one-sided Jacobi).
  * ------------------------------------------------------------------------- */
 size_t squat_build_subspace_workspace(int64_t n_tokens, int n_kv_heads, int q_per_kv, int d, int r);
 
@@ -162,7 +163,7 @@ int squat_refresh_subspace(const void* q_new, squat_dtype q_dt, int64_t n_new, i
  * A_t is its leading (t g x t g) block, B_t the block below it and H_t the
  * last g columns of A_t^{-1}.  The kernel evaluates the equivalent rank-r
  * form  -Qr^T (I/lambda + Qr Qr^T)^{-1} Qb  (Qb, Qr: the columns of Qhat in
- * and after block t) in fp64 (r <= 32 and finite lambda: by a Cholesky
+ * and after block t) in fp64 (r <= 64 and finite lambda: by a Cholesky
  * factorisation, heads that turn out ill-conditioned and all other cases by an
  * eigen-decomposition).  lambda = +INFINITY selects the limit
  * -pinv(Qr) Qb (the equality constraint of Eq. (1)); lambda = 0 or r = 0
@@ -211,6 +212,7 @@ int squat_prepare_ex(const float* qhat, int n_heads, int d, int r, float lambda,
  * Limits: r <= 32 with a finite lambda needs 4 bytes per head (n_heads <=
  * 2^20); r <= 32 with lambda = +INFINITY needs none; r > 32 needs
  * n_heads * (d/g - 1) * (r rounded up to even) * (g + d) * 8 bytes, rounded up
+ * to 256, plus, for r <= 64 with a finite lambda, 4 bytes per head rounded up
  * to 256.  A problem beyond 4 MiB returns SQUAT_E_WORKSPACE (nothing launched).
  * Every call on a device shares that device's array: calls that may overlap
  * on one device (different streams, or threads) race; order them.  The first

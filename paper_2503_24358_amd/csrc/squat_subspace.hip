@@ -14,12 +14,12 @@
 //                 (deterministic), un-permutes channels and mirrors;
 //   gram_reduce_tiles  the same with a workgroup per (tile, head), for
 //                 heads with many partials.
-//   eig_tridiag_kernel  r <= 32: Householder tridiagonalisation, Sturm-count search
+//   eig_tridiag_kernel  r <= 64: Householder tridiagonalisation, Sturm-count search
 //                 for the r largest eigenvalues, inverse iteration, back-transformation
 //                 (squat_tridiag.h), one workgroup per KV head; flags a head whose result
 //                 fails its own residual checks.
 //   eig_kernel    cyclic one-sided Jacobi in fp64 on the 128 x 128 Gram matrix in
-//                 LDS, one workgroup per KV head, then picks the r largest: r > 32, and
+//                 LDS, one workgroup per KV head, then picks the r largest: r > 64, and
 //                 the heads the kernel above flagged.
 #include "squat_internal.h"
 #include "squat_jacobi.h"
@@ -601,13 +601,13 @@ int run_gram(const void* q, squat_dtype q_dt, int64_t n_tokens, int n_kv_heads, 
     return check_launch();
 }
 
-// Exact top-r eigenpairs of the Gram matrices in g64: tridiagonal route (r <= 32), Jacobi for larger r and for
-// the heads that route flags.
+// Exact top-r eigenpairs of the Gram matrices in g64: tridiagonal route (r <= 64, in batches of 32 vectors), Jacobi
+// for larger r and for the heads that route flags.
 int run_exact_solver(const double* g64, int n_kv_heads, int r, float* qhat, float* eig, const SubspacePlan& pl, void* ws,
                      hipStream_t s) {
     int rc = SQUAT_OK;
     int* need = nullptr;
-    if (r <= kTriMaxR) {
+    if (r <= 2 * kTriMaxR) {
         need = reinterpret_cast<int*>(static_cast<unsigned char*>(ws) + pl.off_need);
         double* vws = reinterpret_cast<double*>(static_cast<unsigned char*>(ws) + pl.off_v);
         hipLaunchKernelGGL(eig_tridiag_kernel, dim3(n_kv_heads), dim3(kTriThreads), kTriLdsBytes, s, g64, vws, r, qhat,

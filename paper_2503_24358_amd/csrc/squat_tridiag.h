@@ -1,4 +1,4 @@
-// Top-r eigenpairs of a symmetric positive semi-definite 128 x 128 matrix by the
+// Top-r eigenpairs (r <= 64) of a symmetric positive semi-definite 128 x 128 matrix by the
 // classical dense route, one 512-thread workgroup per matrix (Section 3.2: the
 // right singular vectors and singular values of the query matrix are the
 // eigenpairs of its Gram matrix):
@@ -258,8 +258,9 @@ __device__ __forceinline__ void tri_steps(double (&a)[kTriRows][16], int team, i
 
 // g: the matrix (row-major doubles, symmetric positive semi-definite); vws: 128 x 128 doubles of
 // scratch in global memory; qhat: r rows of 128 floats = sqrt(lambda_j) v_j, eigenvalues descending;
-// eig: r floats or NULL.  Returns (to every thread) whether the result was accepted; if not, nothing
-// was written.  All kTriThreads threads of the block must call it; L: kTriLdsBytes of LDS, 16-byte aligned.
+// eig: r floats or NULL; r <= 2 kTriMaxR.  Returns (to every thread) whether the result was accepted; if not, the
+// outputs are to be redone as a whole (a first batch of rows may have been written).  All kTriThreads threads of
+// the block must call it; L: kTriLdsBytes of LDS, 16-byte aligned.
 __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, int r, float* qhat, float* eig,
                                                  double* L) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -346,360 +347,376 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
     }
     __syncthreads();
 
-    // ---- 2. the r largest eigenvalues by 17-section on Sturm counts
-    if (tid < kTriPts * r) {
-        const int j = tid / kTriPts, pt = tid % kTriPts;
-        const int below_target = kTriN - 1 - j;           // eigenvalue j (descending) has this many below it
-        double lo = -3.0001, hi = 3.0001;
-        const double* de = L + kTriDe;
-        for (int round = 0; round < kTriRounds; ++round) {
-            asm volatile("" ::: "memory");                // keep the 128 LDS reads inside the round (not hoisted into registers)
-            const double step = (hi - lo) * (1.0 / (kTriPts + 1));
-            const double x = fma(step, static_cast<double>(pt + 1), lo);
-            double p0 = 1.0, p1 = de[0] - x;
-            // The signs of the minors are shifted into a register, newest at bit 0 (one instruction per term);
-            // a block's sign changes are then the ones of (signs ^ signs >> 1) over its terms.  The sign of
-            // p_0 = 1 is 0, so the first minor's own sign is a change.
-            uint32_t signs = static_cast<uint32_t>(__double2hiint(p1)) >> 31;
-            int cnt = static_cast<int>(signs);
-            auto block = [&](int b, auto nt_tag) {
-                constexpr int NTERMS = decltype(nt_tag)::value;
-#pragma unroll
-                for (int u = 0; u < NTERMS; ++u) {
-                    const double2 t = *reinterpret_cast<const double2*>(de + 2 * (b + u));
-                    const double p2 = fma(t.x - x, p1, -(t.y * p0));
-                    signs = __builtin_amdgcn_alignbit(signs, static_cast<uint32_t>(__double2hiint(p2)), 31);
-                    p0 = p1;
-                    p1 = p2;
-                }
-                cnt += __popc((signs ^ (signs >> 1)) & ((1u << NTERMS) - 1u));
-                // rescale the pair by a power of two (the larger one to [1, 2))
-                const double m = fmax(fabs(p0), fabs(p1));
-                const int ex = ((__double2hiint(m) >> 20) & 0x7FF) - 1023;
-                if (ex > -1000 && ex < 1000) {
-                    const double f = tri_pow2(-ex);
-                    p0 *= f;
-                    p1 *= f;
-                }
-            };
-            static_assert((kTriN - 1) % 8 == 7, "15 blocks of 8 terms and one of 7");
-            for (int b = 1; b + 8 <= kTriN; b += 8) block(b, std::integral_constant<int, 8>{});
-            block(kTriN - 7, std::integral_constant<int, 7>{});
-            // the team's points are ascending: those with count <= target are a prefix
-            const unsigned long long mask = __ballot(cnt <= below_target);
-            const int nb = __popc(static_cast<unsigned>((mask >> (lane & ~(kTriPts - 1))) & ((1u << kTriPts) - 1u)));
-            const double nlo = nb == 0 ? lo : fma(step, static_cast<double>(nb), lo);
-            const double nhi = nb == kTriPts ? hi : fma(step, static_cast<double>(nb + 1), lo);
-            lo = nlo;
-            hi = nhi;
-        }
-        if (pt == 0) L[kTriLam + j] = 0.5 * (lo + hi);
-    }
-    __syncthreads();
-
-    // ---- 3. inverse iteration, one lane per vector
-    if (tid == 0) {
-        const double sep = 10.0 * 2.220446049250313e-16;  // coincident eigenvalues get shifts a few ulps apart
-        double prev = L[kTriLam];
-        L[kTriLam + 32] = prev;
-        for (int j = 1; j < r; ++j) {
-            double s = L[kTriLam + j];
-            s = s > prev - sep ? prev - sep : s;
-            L[kTriLam + 32 + j] = s;
-            prev = s;
-        }
-    }
-    // columns r .. 31 are padding (unit vectors, never used)
-    for (int e = tid; e < kTriN * 32; e += kTriThreads) {
-        const int row = e >> 5, colj = e & 31;
-        // start vectors: a fixed pseudo-random pattern in (-1, 1)
-        uint32_t h = static_cast<uint32_t>(row) * 2654435761u + static_cast<uint32_t>(colj) * 40503u + 12345u;
-        h ^= h >> 15;
-        h *= 2246822519u;
-        h ^= h >> 13;
-        const double rnd = (static_cast<double>(h >> 8) + 0.5) * (2.0 / 16777216.0) - 1.0;
-        L[kTriX + e] = colj < r ? rnd : (row == colj ? 1.0 : 0.0);
-    }
-    __syncthreads();
-    if (tid < r) {
-        const int j = tid;
-        const double shift = L[kTriLam + 32 + j];
-        const double pivmin = 2.0e-19;
-        const double* dn = L + kTriDd;
-        const double* en = L + kTriEe;
-        double* X = L + kTriX + j;
-        double* U0 = L + kTriU0 + j;
-        double* U1 = L + kTriU1 + j;
-        double* U2 = L + kTriU2 + j;
-        double scale = 1.0;
-        for (int it = 0; it < 2; ++it) {
-            // forward elimination with row interchanges, applied to the right-hand side on the fly
-            double ca = dn[0] - shift, cc = en[0], cf = 0.0, cb = X[0] * scale;
-            for (int row = 0; row < kTriN - 1; ++row) {
-                const double na = en[row], nc = dn[row + 1] - shift, nf = row + 1 < kTriN - 1 ? en[row + 1] : 0.0;
-                const double nb = X[32 * (row + 1)] * scale;
-                const bool keep = fabs(ca) >= fabs(na);
-                double pa = keep ? ca : na, pc = keep ? cc : nc, pf = keep ? cf : nf, pb = keep ? cb : nb;
-                const double oa = keep ? na : ca, oc = keep ? nc : cc, of = keep ? nf : cf, ob = keep ? nb : cb;
-                if (fabs(pa) < pivmin) pa = pa < 0.0 ? -pivmin : pivmin;
-                const double inv = tri_rcp(pa);
-                const double mlt = oa * inv;
-                U0[32 * row] = inv;
-                U1[32 * row] = pc;
-                U2[32 * row] = pf;
-                X[32 * row] = pb;
-                ca = fma(-mlt, pc, oc);
-                cc = fma(-mlt, pf, of);
-                cf = 0.0;
-                cb = fma(-mlt, pb, ob);
+    // Steps 2-5 take the eigenpairs in batches of kTriMaxR, largest first (the LDS plan holds that many vectors): r <= 32
+    // is one batch; for more, T and the reflectors serve every batch.  (Two inlined copies of the batch rather than
+    // a loop around one: inside a loop the compiler spills a hundred registers.)
+    double lam_edge = 0.0;                                // smallest eigenvalue of the batch before
+    auto batch = [&](const int joff, const int rb) -> bool {
+        // ---- 2. the rb largest eigenvalues by 17-section on Sturm counts
+        if (tid < kTriPts * rb) {
+            const int j = tid / kTriPts, pt = tid % kTriPts;
+            const int below_target = kTriN - 1 - (joff + j);  // eigenvalue joff + j (descending) has this many below it
+            double lo = -3.0001, hi = 3.0001;
+            const double* de = L + kTriDe;
+            for (int round = 0; round < kTriRounds; ++round) {
+                asm volatile("" ::: "memory");                // keep the 128 LDS reads inside the round (not hoisted into registers)
+                const double step = (hi - lo) * (1.0 / (kTriPts + 1));
+                const double x = fma(step, static_cast<double>(pt + 1), lo);
+                double p0 = 1.0, p1 = de[0] - x;
+                // The signs of the minors are shifted into a register, newest at bit 0 (one instruction per term);
+                // a block's sign changes are then the ones of (signs ^ signs >> 1) over its terms.  The sign of
+                // p_0 = 1 is 0, so the first minor's own sign is a change.
+                uint32_t signs = static_cast<uint32_t>(__double2hiint(p1)) >> 31;
+                int cnt = static_cast<int>(signs);
+                auto block = [&](int b, auto nt_tag) {
+                    constexpr int NTERMS = decltype(nt_tag)::value;
+    #pragma unroll
+                    for (int u = 0; u < NTERMS; ++u) {
+                        const double2 t = *reinterpret_cast<const double2*>(de + 2 * (b + u));
+                        const double p2 = fma(t.x - x, p1, -(t.y * p0));
+                        signs = __builtin_amdgcn_alignbit(signs, static_cast<uint32_t>(__double2hiint(p2)), 31);
+                        p0 = p1;
+                        p1 = p2;
+                    }
+                    cnt += __popc((signs ^ (signs >> 1)) & ((1u << NTERMS) - 1u));
+                    // rescale the pair by a power of two (the larger one to [1, 2))
+                    const double m = fmax(fabs(p0), fabs(p1));
+                    const int ex = ((__double2hiint(m) >> 20) & 0x7FF) - 1023;
+                    if (ex > -1000 && ex < 1000) {
+                        const double f = tri_pow2(-ex);
+                        p0 *= f;
+                        p1 *= f;
+                    }
+                };
+                static_assert((kTriN - 1) % 8 == 7, "15 blocks of 8 terms and one of 7");
+                for (int b = 1; b + 8 <= kTriN; b += 8) block(b, std::integral_constant<int, 8>{});
+                block(kTriN - 7, std::integral_constant<int, 7>{});
+                // the team's points are ascending: those with count <= target are a prefix
+                const unsigned long long mask = __ballot(cnt <= below_target);
+                const int nb = __popc(static_cast<unsigned>((mask >> (lane & ~(kTriPts - 1))) & ((1u << kTriPts) - 1u)));
+                const double nlo = nb == 0 ? lo : fma(step, static_cast<double>(nb), lo);
+                const double nhi = nb == kTriPts ? hi : fma(step, static_cast<double>(nb + 1), lo);
+                lo = nlo;
+                hi = nhi;
             }
-            if (fabs(ca) < pivmin) ca = ca < 0.0 ? -pivmin : pivmin;
-            // back substitution
-            double x2 = 0.0, x1 = cb * tri_rcp(ca), big = fabs(x1);
-            X[32 * (kTriN - 1)] = x1;
-            for (int row = kTriN - 2; row >= 0; --row) {
-                const double x = (X[32 * row] - U1[32 * row] * x1 - U2[32 * row] * x2) * U0[32 * row];
-                X[32 * row] = x;
-                big = fmax(big, fabs(x));
-                x2 = x1;
-                x1 = x;
-            }
-            scale = big > 0.0 && big < 1e300 ? 1.0 / big : 1.0;
+            if (pt == 0) L[kTriLam + j] = 0.5 * (lo + hi);
         }
-        // unit 2-norm
-        double s2 = 0.0;
-        for (int row = 0; row < kTriN; ++row) {
-            const double x = X[32 * row] * scale;
-            s2 = fma(x, x, s2);
-        }
-        const double nrm = scale * (s2 > 0.0 ? 1.0 / sqrt(s2) : 0.0);
-        for (int row = 0; row < kTriN; ++row) X[32 * row] *= nrm;
-    }
-    __syncthreads();
+        __syncthreads();
+        // A later batch stands on its own only if its eigenvalues are clear of the batch before (vectors of eigenvalues
+        // closer than this could share a subspace, which only a joint orthonormalisation would see)
+        if (joff > 0 && !(lam_edge - L[kTriLam] >= 1e-7)) return false;      // uniform
+        lam_edge = L[kTriLam + rb - 1];
 
-    // ---- orthonormality: Gram matrix of the 32 columns; Cholesky-QR (twice) only if it is not the identity
-    double* S = L + kTriS;
-    bool ok = true;
-    for (int pass = 0; pass < 3; ++pass) {
-        double dev = 0.0;
-        if (tid < 256) {
-            const int a2 = tid >> 4, b2 = tid & 15;
-            double s00 = 0.0, s01 = 0.0, s10 = 0.0, s11 = 0.0;
+        // ---- 3. inverse iteration, one lane per vector
+        if (tid == 0) {
+            const double sep = 10.0 * 2.220446049250313e-16;  // coincident eigenvalues get shifts a few ulps apart
+            double prev = L[kTriLam];
+            L[kTriLam + 32] = prev;
+            for (int j = 1; j < rb; ++j) {
+                double s = L[kTriLam + j];
+                s = s > prev - sep ? prev - sep : s;
+                L[kTriLam + 32 + j] = s;
+                prev = s;
+            }
+        }
+        // columns rb .. 31 are padding (unit vectors, never used)
+        for (int e = tid; e < kTriN * 32; e += kTriThreads) {
+            const int row = e >> 5, colj = e & 31;
+            // start vectors: a fixed pseudo-random pattern in (-1, 1)
+            uint32_t h = static_cast<uint32_t>(row) * 2654435761u + static_cast<uint32_t>(colj) * 40503u + 12345u;
+            h ^= h >> 15;
+            h *= 2246822519u;
+            h ^= h >> 13;
+            const double rnd = (static_cast<double>(h >> 8) + 0.5) * (2.0 / 16777216.0) - 1.0;
+            L[kTriX + e] = colj < rb ? rnd : (row == colj ? 1.0 : 0.0);
+        }
+        __syncthreads();
+        if (tid < rb) {
+            const int j = tid;
+            const double shift = L[kTriLam + 32 + j];
+            const double pivmin = 2.0e-19;
+            const double* dn = L + kTriDd;
+            const double* en = L + kTriEe;
+            double* X = L + kTriX + j;
+            double* U0 = L + kTriU0 + j;
+            double* U1 = L + kTriU1 + j;
+            double* U2 = L + kTriU2 + j;
+            double scale = 1.0;
+            for (int it = 0; it < 2; ++it) {
+                // forward elimination with row interchanges, applied to the right-hand side on the fly
+                double ca = dn[0] - shift, cc = en[0], cf = 0.0, cb = X[0] * scale;
+                for (int row = 0; row < kTriN - 1; ++row) {
+                    const double na = en[row], nc = dn[row + 1] - shift, nf = row + 1 < kTriN - 1 ? en[row + 1] : 0.0;
+                    const double nb = X[32 * (row + 1)] * scale;
+                    const bool keep = fabs(ca) >= fabs(na);
+                    double pa = keep ? ca : na, pc = keep ? cc : nc, pf = keep ? cf : nf, pb = keep ? cb : nb;
+                    const double oa = keep ? na : ca, oc = keep ? nc : cc, of = keep ? nf : cf, ob = keep ? nb : cb;
+                    if (fabs(pa) < pivmin) pa = pa < 0.0 ? -pivmin : pivmin;
+                    const double inv = tri_rcp(pa);
+                    const double mlt = oa * inv;
+                    U0[32 * row] = inv;
+                    U1[32 * row] = pc;
+                    U2[32 * row] = pf;
+                    X[32 * row] = pb;
+                    ca = fma(-mlt, pc, oc);
+                    cc = fma(-mlt, pf, of);
+                    cf = 0.0;
+                    cb = fma(-mlt, pb, ob);
+                }
+                if (fabs(ca) < pivmin) ca = ca < 0.0 ? -pivmin : pivmin;
+                // back substitution
+                double x2 = 0.0, x1 = cb * tri_rcp(ca), big = fabs(x1);
+                X[32 * (kTriN - 1)] = x1;
+                for (int row = kTriN - 2; row >= 0; --row) {
+                    const double x = (X[32 * row] - U1[32 * row] * x1 - U2[32 * row] * x2) * U0[32 * row];
+                    X[32 * row] = x;
+                    big = fmax(big, fabs(x));
+                    x2 = x1;
+                    x1 = x;
+                }
+                scale = big > 0.0 && big < 1e300 ? 1.0 / big : 1.0;
+            }
+            // unit 2-norm
+            double s2 = 0.0;
             for (int row = 0; row < kTriN; ++row) {
-                const double2 xa = *reinterpret_cast<const double2*>(L + kTriX + 32 * row + 2 * a2);
-                const double2 xb = *reinterpret_cast<const double2*>(L + kTriX + 32 * row + 2 * b2);
-                s00 = fma(xa.x, xb.x, s00);
-                s01 = fma(xa.x, xb.y, s01);
-                s10 = fma(xa.y, xb.x, s10);
-                s11 = fma(xa.y, xb.y, s11);
+                const double x = X[32 * row] * scale;
+                s2 = fma(x, x, s2);
             }
-            S[(2 * a2) * 33 + 2 * b2] = s00;
-            S[(2 * a2) * 33 + 2 * b2 + 1] = s01;
-            S[(2 * a2 + 1) * 33 + 2 * b2] = s10;
-            S[(2 * a2 + 1) * 33 + 2 * b2 + 1] = s11;
-            // only the r real columns count (the padding columns are never used)
-            const double i00 = a2 == b2 ? 1.0 : 0.0;
-            const bool ra0 = 2 * a2 < r, ra1 = 2 * a2 + 1 < r, rb0 = 2 * b2 < r, rb1 = 2 * b2 + 1 < r;
-            dev = fmax(fmax(ra0 && rb0 ? fabs(s00 - i00) : 0.0, ra1 && rb1 ? fabs(s11 - i00) : 0.0),
-                       fmax(ra0 && rb1 ? fabs(s01) : 0.0, ra1 && rb0 ? fabs(s10) : 0.0));
+            const double nrm = scale * (s2 > 0.0 ? 1.0 / sqrt(s2) : 0.0);
+            for (int row = 0; row < kTriN; ++row) X[32 * row] *= nrm;
         }
-        dev = tri_block_max(dev, misc, tid);
-        if (!(dev == dev)) ok = false;
-        if (dev <= 1e-10 || !ok) break;
-        if (pass == 2) {
-            ok = dev <= kTriAccept;
-            break;
-        }
-        if (dev <= 1e-5) {
-            // nearly orthonormal (close eigenvalues, not coincident ones): one symmetric step
-            // X <- X (3/2 I - 1/2 S) squares the deviation
-            constexpr int NP = kTriN * 8 / kTriThreads;    // row passes per thread
-            const int j0 = 4 * (tid & 7);
-            double out[NP][4];
-#pragma unroll
-            for (int ps2 = 0; ps2 < NP; ++ps2) {
-                const double* xr = L + kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8));
-#pragma unroll
-                for (int c = 0; c < 4; ++c) out[ps2][c] = 0.0;
-                for (int k2 = 0; k2 < r; ++k2) {
-                    const double xk = xr[k2];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) out[ps2][c] = fma(xk, S[k2 * 33 + j0 + c], out[ps2][c]);
+        __syncthreads();
+
+        // ---- orthonormality: Gram matrix of the 32 columns; Cholesky-QR (twice) only if it is not the identity
+        double* S = L + kTriS;
+        bool ok = true;
+        for (int pass = 0; pass < 3; ++pass) {
+            double dev = 0.0;
+            if (tid < 256) {
+                const int a2 = tid >> 4, b2 = tid & 15;
+                double s00 = 0.0, s01 = 0.0, s10 = 0.0, s11 = 0.0;
+                for (int row = 0; row < kTriN; ++row) {
+                    const double2 xa = *reinterpret_cast<const double2*>(L + kTriX + 32 * row + 2 * a2);
+                    const double2 xb = *reinterpret_cast<const double2*>(L + kTriX + 32 * row + 2 * b2);
+                    s00 = fma(xa.x, xb.x, s00);
+                    s01 = fma(xa.x, xb.y, s01);
+                    s10 = fma(xa.y, xb.x, s10);
+                    s11 = fma(xa.y, xb.y, s11);
                 }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) out[ps2][c] = fma(-0.5, out[ps2][c], 1.5 * xr[j0 + c]);
+                S[(2 * a2) * 33 + 2 * b2] = s00;
+                S[(2 * a2) * 33 + 2 * b2 + 1] = s01;
+                S[(2 * a2 + 1) * 33 + 2 * b2] = s10;
+                S[(2 * a2 + 1) * 33 + 2 * b2 + 1] = s11;
+                // only the rb real columns count (the padding columns are never used)
+                const double i00 = a2 == b2 ? 1.0 : 0.0;
+                const bool ra0 = 2 * a2 < rb, ra1 = 2 * a2 + 1 < rb, rb0 = 2 * b2 < rb, rb1 = 2 * b2 + 1 < rb;
+                dev = fmax(fmax(ra0 && rb0 ? fabs(s00 - i00) : 0.0, ra1 && rb1 ? fabs(s11 - i00) : 0.0),
+                           fmax(ra0 && rb1 ? fabs(s01) : 0.0, ra1 && rb0 ? fabs(s10) : 0.0));
+            }
+            dev = tri_block_max(dev, misc, tid);
+            if (!(dev == dev)) ok = false;
+            if (dev <= 1e-10 || !ok) break;
+            if (pass == 2) {
+                ok = dev <= kTriAccept;
+                break;
+            }
+            if (dev <= 1e-5) {
+                // nearly orthonormal (close eigenvalues, not coincident ones): one symmetric step
+                // X <- X (3/2 I - 1/2 S) squares the deviation
+                constexpr int NP = kTriN * 8 / kTriThreads;    // row passes per thread
+                const int j0 = 4 * (tid & 7);
+                double out[NP][4];
+    #pragma unroll
+                for (int ps2 = 0; ps2 < NP; ++ps2) {
+                    const double* xr = L + kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8));
+    #pragma unroll
+                    for (int c = 0; c < 4; ++c) out[ps2][c] = 0.0;
+                    for (int k2 = 0; k2 < rb; ++k2) {
+                        const double xk = xr[k2];
+    #pragma unroll
+                        for (int c = 0; c < 4; ++c) out[ps2][c] = fma(xk, S[k2 * 33 + j0 + c], out[ps2][c]);
+                    }
+    #pragma unroll
+                    for (int c = 0; c < 4; ++c) out[ps2][c] = fma(-0.5, out[ps2][c], 1.5 * xr[j0 + c]);
+                }
+                __syncthreads();
+    #pragma unroll
+                for (int ps2 = 0; ps2 < NP; ++ps2)
+    #pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (j0 + c < rb) L[kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8)) + j0 + c] = out[ps2][c];
+                __syncthreads();
+                continue;
+            }
+            // Cholesky S = C C' in place (lower triangle), one wavefront, lane = row
+            if (wave == 0) {
+                int bad = 0;
+                for (int j = 0; j < rb; ++j) {
+                    double acc = 0.0;
+                    if (lane < rb && lane >= j) {
+                        acc = S[lane * 33 + j];
+                        for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[lane * 33 + k2], S[j * 33 + k2], acc);
+                    }
+                    const double piv = __shfl(acc, j, 64);
+                    if (!(piv > 1e-280)) bad = 1;
+                    const double rs = bad ? 0.0 : 1.0 / sqrt(piv);
+                    if (lane < rb && lane >= j) S[lane * 33 + j] = lane == j ? rs : acc * rs;      // diagonal: 1 / C_jj
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                }
+                if (lane == 0) misc[32] = bad ? 1.0 : 0.0;
             }
             __syncthreads();
-#pragma unroll
-            for (int ps2 = 0; ps2 < NP; ++ps2)
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (j0 + c < r) L[kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8)) + j0 + c] = out[ps2][c];
+            if (misc[32] != 0.0) {
+                ok = false;
+                break;
+            }
+            // X <- X C^-T : row by row, y_j = (x_j - sum_{k<j} C_jk y_k) / C_jj
+            if (tid < kTriN) {
+                double* xr = L + kTriX + 32 * tid;
+                double y[32];
+    #pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    if (j < rb) {                              // uniform
+                        double acc = xr[j];
+    #pragma unroll
+                        for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[j * 33 + k2], y[k2], acc);
+                        y[j] = acc * S[j * 33 + j];
+                    }
+                }
+    #pragma unroll
+                for (int j = 0; j < 32; ++j)
+                    if (j < rb) xr[j] = y[j];
+            }
             __syncthreads();
-            continue;
         }
-        // Cholesky S = C C' in place (lower triangle), one wavefront, lane = row
-        if (wave == 0) {
-            int bad = 0;
-            for (int j = 0; j < r; ++j) {
-                double acc = 0.0;
-                if (lane < r && lane >= j) {
-                    acc = S[lane * 33 + j];
-                    for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[lane * 33 + k2], S[j * 33 + k2], acc);
+
+        // ---- 4. Rayleigh quotients and residuals: team of 32 lanes per vector, 4 elements per lane, NV
+        // vectors per thread
+        constexpr int NV = 32 * 32 / kTriThreads;
+        const int sub = tid & 31;
+        double xv[NV][4];
+        {
+            double worst = 0.0;
+    #pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const int vj = (tid >> 5) + q * (kTriThreads / 32);
+                double num = 0.0, den = 0.0;
+                double yv[4];
+    #pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int row = sub + 32 * m;
+                    const double x = L[kTriX + 32 * row + vj];
+                    const double xm = row > 0 ? L[kTriX + 32 * (row - 1) + vj] : 0.0;
+                    const double xp = row < kTriN - 1 ? L[kTriX + 32 * (row + 1) + vj] : 0.0;
+                    const double em = row > 0 ? L[kTriEe + row - 1] : 0.0;
+                    const double y = fma(L[kTriDd + row], x, fma(em, xm, L[kTriEe + row] * xp));
+                    xv[q][m] = x;
+                    yv[m] = y;
+                    num = fma(x, y, num);
+                    den = fma(x, x, den);
                 }
-                const double piv = __shfl(acc, j, 64);
-                if (!(piv > 1e-280)) bad = 1;
-                const double rs = bad ? 0.0 : 1.0 / sqrt(piv);
-                if (lane < r && lane >= j) S[lane * 33 + j] = lane == j ? rs : acc * rs;      // diagonal: 1 / C_jj
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            }
-            if (lane == 0) misc[32] = bad ? 1.0 : 0.0;
-        }
-        __syncthreads();
-        if (misc[32] != 0.0) {
-            ok = false;
-            break;
-        }
-        // X <- X C^-T : row by row, y_j = (x_j - sum_{k<j} C_jk y_k) / C_jj
-        if (tid < kTriN) {
-            double* xr = L + kTriX + 32 * tid;
-            double y[32];
-#pragma unroll
-            for (int j = 0; j < 32; ++j) {
-                if (j < r) {                              // uniform
-                    double acc = xr[j];
-#pragma unroll
-                    for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[j * 33 + k2], y[k2], acc);
-                    y[j] = acc * S[j * 33 + j];
+                num = tri_sum32(num);
+                den = tri_sum32(den);
+                const double rq = den > 0.0 ? num / den : 0.0;
+                double res = 0.0;
+    #pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const double t = yv[m] - rq * xv[q][m];
+                    res = fma(t, t, res);
                 }
+                res = tri_sum32(res);
+                if (sub == 0) L[kTriLam + 64 + vj] = rq;
+                double w = vj < rb ? sqrt(res) : 0.0;
+                if (!(w == w)) w = 1e300;
+                worst = fmax(worst, w);
             }
-#pragma unroll
-            for (int j = 0; j < 32; ++j)
-                if (j < r) xr[j] = y[j];
+            worst = tri_block_max(worst, misc, tid);
+            if (!(worst <= kTriAccept)) ok = false;
         }
+        if (!ok) return false;                                // uniform: every thread saw the same flags
+
+        // ---- 5. back-transformation: team of 16 lanes per vector (every thread of the block: 32 vectors), lane s holds
+        // elements s, s + 16, ..., s + 112.  Per reflector and lane: one dot product over 8 elements, a sum over the 16
+        // lanes (four lane-permute stages; with 32 lanes and two vectors per thread the sums were most of the
+        // instructions), 8 multiply-adds; the next reflector's entries are fetched meanwhile.  The vectors are read
+        // from LDS in this layout before the reflectors come back from global memory into their block.
+        static_assert(kTriThreads == 16 * kTriMaxR, "one team of 16 lanes per vector");
+        const int bvj = tid >> 4, bs = tid & 15;
+        double xb[8];
+    #pragma unroll
+        for (int m = 0; m < 8; ++m) xb[m] = L[kTriX + 32 * (bs + 16 * m) + bvj];
         __syncthreads();
-    }
+        __threadfence_block();
+        {
+            double* V = L + kTriX;
+            // (unrolled, so that the loads of several trips are in flight together: one trip at a time, each of the 16
+            // trips waits out a whole global-memory round trip)
+    #pragma unroll 8
+            for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
+                *reinterpret_cast<double2*>(V + e) = *reinterpret_cast<const double2*>(vws + e);
+            __syncthreads();
+            double vn[8];
+    #pragma unroll
+            for (int m = 0; m < 8; ++m) vn[m] = V[(kTriN - 3) * kTriN + bs + 16 * m];
+            for (int k = kTriN - 3; k >= 0; --k) {
+                const double beta = L[kTriBet + k];
+                double v[8];
+    #pragma unroll
+                for (int m = 0; m < 8; ++m) v[m] = vn[m];
+                if (k > 0) {
+    #pragma unroll
+                    for (int m = 0; m < 8; ++m) vn[m] = V[(k - 1) * kTriN + bs + 16 * m];
+                }
+                if (beta == 0.0) continue;                    // uniform
+                double s0 = 0.0, s1 = 0.0;
+    #pragma unroll
+                for (int m = 0; m < 8; m += 2) {
+                    s0 = fma(v[m], xb[m], s0);
+                    s1 = fma(v[m + 1], xb[m + 1], s1);
+                }
+                const double sc = team_sum<16>(s0 + s1) * beta;
+    #pragma unroll
+                for (int m = 0; m < 8; ++m) xb[m] = fma(-sc, v[m], xb[m]);
+            }
+        }
 
-    // ---- 4. Rayleigh quotients and residuals: team of 32 lanes per vector, 4 elements per lane, NV
-    // vectors per thread
-    constexpr int NV = 32 * 32 / kTriThreads;
-    const int sub = tid & 31;
-    double xv[NV][4];
-    {
-        double worst = 0.0;
-#pragma unroll
-        for (int q = 0; q < NV; ++q) {
-            const int vj = (tid >> 5) + q * (kTriThreads / 32);
-            double num = 0.0, den = 0.0;
-            double yv[4];
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const int row = sub + 32 * m;
-                const double x = L[kTriX + 32 * row + vj];
-                const double xm = row > 0 ? L[kTriX + 32 * (row - 1) + vj] : 0.0;
-                const double xp = row < kTriN - 1 ? L[kTriX + 32 * (row + 1) + vj] : 0.0;
-                const double em = row > 0 ? L[kTriEe + row - 1] : 0.0;
-                const double y = fma(L[kTriDd + row], x, fma(em, xm, L[kTriEe + row] * xp));
-                xv[q][m] = x;
-                yv[m] = y;
-                num = fma(x, y, num);
-                den = fma(x, x, den);
+        // ---- output: rank by eigenvalue, sign so that the largest component is positive, rows sqrt(lambda) v
+        if (bvj < rb) {                                        // uniform per team of 16 lanes
+            const double lam = L[kTriLam + 64 + bvj];
+            int rank = 0;
+            for (int o = 0; o < rb; ++o) {
+                const double lo = L[kTriLam + 64 + o];
+                rank += (lo > lam) || (lo == lam && o < bvj);
             }
-            num = tri_sum32(num);
-            den = tri_sum32(den);
-            const double rq = den > 0.0 ? num / den : 0.0;
-            double res = 0.0;
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const double t = yv[m] - rq * xv[q][m];
-                res = fma(t, t, res);
+            double best = -1.0, bestv = 0.0;
+            int besti = kTriN;
+    #pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const double av = fabs(xb[m]);
+                if (av > best) { best = av; bestv = xb[m]; besti = bs + 16 * m; }
             }
-            res = tri_sum32(res);
-            if (sub == 0) L[kTriLam + 64 + vj] = rq;
-            double w = vj < r ? sqrt(res) : 0.0;
-            if (!(w == w)) w = 1e300;
-            worst = fmax(worst, w);
-        }
-        worst = tri_block_max(worst, misc, tid);
-        if (!(worst <= kTriAccept)) ok = false;
-    }
-    if (!ok) return false;                                // uniform: every thread saw the same flags
-
-    // ---- 5. back-transformation: team of 16 lanes per vector (every thread of the block: 32 vectors), lane s holds
-    // elements s, s + 16, ..., s + 112.  Per reflector and lane: one dot product over 8 elements, a sum over the 16
-    // lanes (four lane-permute stages; with 32 lanes and two vectors per thread the sums were most of the
-    // instructions), 8 multiply-adds; the next reflector's entries are fetched meanwhile.  The vectors are read
-    // from LDS in this layout before the reflectors come back from global memory into their block.
-    static_assert(kTriThreads == 16 * kTriMaxR, "one team of 16 lanes per vector");
-    const int bvj = tid >> 4, bs = tid & 15;
-    double xb[8];
-#pragma unroll
-    for (int m = 0; m < 8; ++m) xb[m] = L[kTriX + 32 * (bs + 16 * m) + bvj];
-    __syncthreads();
-    __threadfence_block();
-    {
-        double* V = L + kTriX;
-        // (unrolled, so that the loads of several trips are in flight together: one trip at a time, each of the 16
-        // trips waits out a whole global-memory round trip)
-#pragma unroll 8
-        for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
-            *reinterpret_cast<double2*>(V + e) = *reinterpret_cast<const double2*>(vws + e);
-        __syncthreads();
-        double vn[8];
-#pragma unroll
-        for (int m = 0; m < 8; ++m) vn[m] = V[(kTriN - 3) * kTriN + bs + 16 * m];
-        for (int k = kTriN - 3; k >= 0; --k) {
-            const double beta = L[kTriBet + k];
-            double v[8];
-#pragma unroll
-            for (int m = 0; m < 8; ++m) v[m] = vn[m];
-            if (k > 0) {
-#pragma unroll
-                for (int m = 0; m < 8; ++m) vn[m] = V[(k - 1) * kTriN + bs + 16 * m];
+    #pragma unroll
+            for (int off = 8; off > 0; off >>= 1) {
+                const double ob = __shfl_xor(best, off, 64);
+                const double ov = __shfl_xor(bestv, off, 64);
+                const int oi = __shfl_xor(besti, off, 64);
+                if (ob > best || (ob == best && oi < besti)) { best = ob; bestv = ov; besti = oi; }
             }
-            if (beta == 0.0) continue;                    // uniform
-            double s0 = 0.0, s1 = 0.0;
-#pragma unroll
-            for (int m = 0; m < 8; m += 2) {
-                s0 = fma(v[m], xb[m], s0);
-                s1 = fma(v[m + 1], xb[m + 1], s1);
-            }
-            const double sc = team_sum<16>(s0 + s1) * beta;
-#pragma unroll
-            for (int m = 0; m < 8; ++m) xb[m] = fma(-sc, v[m], xb[m]);
+            const double lam_true = fmax(lam, 0.0) * tmax * up;
+            const double sc = (bestv < 0.0 ? -1.0 : 1.0) * sqrt(lam_true);
+            float* dst = qhat + (joff + rank) * kTriN;
+    #pragma unroll
+            for (int m = 0; m < 8; ++m) dst[bs + 16 * m] = static_cast<float>(xb[m] * sc);
+            if (eig && bs == 0) eig[joff + rank] = static_cast<float>(lam_true);
         }
-    }
-
-    // ---- output: rank by eigenvalue, sign so that the largest component is positive, rows sqrt(lambda) v
-    if (bvj < r) {                                        // uniform per team of 16 lanes
-        const double lam = L[kTriLam + 64 + bvj];
-        int rank = 0;
-        for (int o = 0; o < r; ++o) {
-            const double lo = L[kTriLam + 64 + o];
-            rank += (lo > lam) || (lo == lam && o < bvj);
-        }
-        double best = -1.0, bestv = 0.0;
-        int besti = kTriN;
-#pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            const double av = fabs(xb[m]);
-            if (av > best) { best = av; bestv = xb[m]; besti = bs + 16 * m; }
-        }
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) {
-            const double ob = __shfl_xor(best, off, 64);
-            const double ov = __shfl_xor(bestv, off, 64);
-            const int oi = __shfl_xor(besti, off, 64);
-            if (ob > best || (ob == best && oi < besti)) { best = ob; bestv = ov; besti = oi; }
-        }
-        const double lam_true = fmax(lam, 0.0) * tmax * up;
-        const double sc = (bestv < 0.0 ? -1.0 : 1.0) * sqrt(lam_true);
-        float* dst = qhat + rank * kTriN;
-#pragma unroll
-        for (int m = 0; m < 8; ++m) dst[bs + 16 * m] = static_cast<float>(xb[m] * sc);
-        if (eig && bs == 0) eig[rank] = static_cast<float>(lam_true);
+        __syncthreads();                                  // the next batch reuses every LDS block
+        return true;
+    };
+    if (!batch(0, r < kTriMaxR ? r : kTriMaxR)) return false;
+    if (r > kTriMaxR) {
+        if (!batch(kTriMaxR, r - kTriMaxR)) return false;
     }
     return true;
 }

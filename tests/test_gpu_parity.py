@@ -336,7 +336,7 @@ def _subspace_checks(q_np, r, qpk=1, scale_tol=1.0):
 
 
 def test_subspace_special_spectra():
-    """Spectra that stress the eigen-solver for r <= 32 (tridiagonal reduction, Sturm-count search,
+    """Spectra that stress the eigen-solver (tridiagonal reduction, Sturm-count search,
     inverse iteration): decaying, flat, rank-deficient, coincident eigenvalues, a single direction,
     zero, and wildly different magnitudes across heads."""
     gen = synth.rng(1250)
@@ -359,8 +359,14 @@ def test_subspace_special_spectra():
     heads.append(dg)
     q = np.stack(heads)
     for r in (32, 16, 1):
-        assert _subspace_checks(q, r) == 0       # even these are accepted by the fast route (33 forces Jacobi)
-    _subspace_checks(q, 33)
+        assert _subspace_checks(q, r) == 0       # even these are accepted by the fast route
+    # More than 32 directions come in two batches of vectors; a head whose eigenvalues 32 and 33 (nearly) coincide is
+    # handed to the Jacobi kernel: rank 20, 5 I, the ten-and-the-rest spectrum, the single direction and zero... the
+    # others (distinct eigenvalues at the batch boundary) stay on the fast route.
+    for r in (33, 40, 60, 64):
+        redone = _subspace_checks(q, r)
+        assert 1 <= redone <= 5, redone
+    _subspace_checks(q, 65)                      # beyond 64: the Jacobi kernel for every head
 
 
 def test_subspace_many_random_heads_r32():
@@ -369,6 +375,16 @@ def test_subspace_many_random_heads_r32():
     assert _subspace_checks(q, 32) == 0          # the fast route's own residual checks accepted every head
     q = synth.queries(1261, 16, 300, planted_rank=0)
     assert _subspace_checks(q, 32, qpk=4) == 0
+
+
+@pytest.mark.parametrize("r", [40, 60, 64])
+def test_subspace_many_random_heads_two_batches(r):
+    """The paper's larger settings (r = 40 and 60 in its long-context experiments): two batches of vectors on the
+    fast route, near-isotropic and planted spectra, none handed to the Jacobi kernel."""
+    q = synth.queries(1262 + r, 32, 700, planted_rank=0)
+    assert _subspace_checks(q, r) == 0
+    q = synth.queries(1263 + r, 8, 500, planted_rank=12)
+    assert _subspace_checks(q, r, qpk=2) == 0
 
 
 def test_subspace_rank_edge_cases():
