@@ -592,6 +592,42 @@ def main():
     del wlp
     out["subspace_routes"] = routes
 
+    # ---- the (r, lambda, g) settings the paper reports (Section 4 "Hyper-parameters"): the default of its short-task
+    # runs and the ones of its long-context runs, whole path on the same workload, stage by stage
+    out["paper_settings"] = []
+    for r_s, lam_s, g_s in ((5, 1e-3, 64), (10, 5e-4, 64), (20, 5e-4, 64), (40, 1e-3, 64), (60, 5e-4, 32)):
+        qh_s = torch.empty((H, r_s, d), dtype=torch.float32, device=dev)
+        eg_s = torch.empty((H, r_s), dtype=torch.float32, device=dev)
+        wp_s = torch.empty(max(256, squat.prepare_workspace(H, d, r_s, g_s)), dtype=torch.uint8, device=dev)
+
+        def setting(ev=None):
+            if ev: ev[0].record()
+            squat.build_subspace(wl.q, wl.q_per_kv, r_s, qhat=qh_s, eig=eg_s, ws=ws_sub)
+            if ev: ev[1].record()
+            squat.prepare(qh_s, lam_s, g_s, update=update, ws=wp_s)
+            if ev: ev[2].record()
+            squat.quantize_keys(wl.k, update, wl.bits, wl.group, g_s, codes=codes, scale=scale, zero=zero)
+            if ev: ev[3].record()
+            squat.dequantize_keys(codes, scale, zero, wl.bits, wl.group, out=back)
+            if ev: ev[4].record()
+
+        setting()
+        setting()
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(4)]
+        for e5 in evs:
+            setting(e5)
+        torch.cuda.synchronize()
+        med = lambda k: sorted(e5[k].elapsed_time(e5[k + 1]) for e5 in evs)[2]  # noqa: E731
+        tot = sorted(e5[0].elapsed_time(e5[4]) for e5 in evs)[2]
+        out["paper_settings"].append({"r": r_s, "lambda": lam_s, "g": g_s, "ms_per_step": tot, "keys_per_s": n_keys / (tot * 1e-3),
+                                      "stage_ms": {"build_subspace": med(0), "prepare": med(1), "quantize_keys": med(2),
+                                                   "dequantize_keys": med(3)}})
+        del qh_s, eg_s, wp_s
+    # the headline matrices back in place for what follows
+    squat.prepare(qhat, wl.lam, wl.g, update=update, ws=ws_prep)
+    squat.quantize_keys(wl.k, update, wl.bits, wl.group, wl.g, codes=codes, scale=scale, zero=zero)
+
     if args.decode:
         def timed_us(fn, reps=50):
             fn()

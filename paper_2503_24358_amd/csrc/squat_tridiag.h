@@ -370,7 +370,7 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
                 int cnt = static_cast<int>(signs);
                 auto block = [&](int b, auto nt_tag) {
                     constexpr int NTERMS = decltype(nt_tag)::value;
-    #pragma unroll
+#pragma unroll
                     for (int u = 0; u < NTERMS; ++u) {
                         const double2 t = *reinterpret_cast<const double2*>(de + 2 * (b + u));
                         const double p2 = fma(t.x - x, p1, -(t.y * p0));
@@ -526,23 +526,23 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
                 constexpr int NP = kTriN * 8 / kTriThreads;    // row passes per thread
                 const int j0 = 4 * (tid & 7);
                 double out[NP][4];
-    #pragma unroll
+#pragma unroll
                 for (int ps2 = 0; ps2 < NP; ++ps2) {
                     const double* xr = L + kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8));
-    #pragma unroll
+#pragma unroll
                     for (int c = 0; c < 4; ++c) out[ps2][c] = 0.0;
                     for (int k2 = 0; k2 < rb; ++k2) {
                         const double xk = xr[k2];
-    #pragma unroll
+#pragma unroll
                         for (int c = 0; c < 4; ++c) out[ps2][c] = fma(xk, S[k2 * 33 + j0 + c], out[ps2][c]);
                     }
-    #pragma unroll
+#pragma unroll
                     for (int c = 0; c < 4; ++c) out[ps2][c] = fma(-0.5, out[ps2][c], 1.5 * xr[j0 + c]);
                 }
                 __syncthreads();
-    #pragma unroll
+#pragma unroll
                 for (int ps2 = 0; ps2 < NP; ++ps2)
-    #pragma unroll
+#pragma unroll
                     for (int c = 0; c < 4; ++c)
                         if (j0 + c < rb) L[kTriX + 32 * ((tid >> 3) + ps2 * (kTriThreads / 8)) + j0 + c] = out[ps2][c];
                 __syncthreads();
@@ -576,16 +576,16 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
             if (tid < kTriN) {
                 double* xr = L + kTriX + 32 * tid;
                 double y[32];
-    #pragma unroll
+#pragma unroll
                 for (int j = 0; j < 32; ++j) {
                     if (j < rb) {                              // uniform
                         double acc = xr[j];
-    #pragma unroll
+#pragma unroll
                         for (int k2 = 0; k2 < j; ++k2) acc = fma(-S[j * 33 + k2], y[k2], acc);
                         y[j] = acc * S[j * 33 + j];
                     }
                 }
-    #pragma unroll
+#pragma unroll
                 for (int j = 0; j < 32; ++j)
                     if (j < rb) xr[j] = y[j];
             }
@@ -599,12 +599,12 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         double xv[NV][4];
         {
             double worst = 0.0;
-    #pragma unroll
+#pragma unroll
             for (int q = 0; q < NV; ++q) {
                 const int vj = (tid >> 5) + q * (kTriThreads / 32);
                 double num = 0.0, den = 0.0;
                 double yv[4];
-    #pragma unroll
+#pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const int row = sub + 32 * m;
                     const double x = L[kTriX + 32 * row + vj];
@@ -621,7 +621,7 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
                 den = tri_sum32(den);
                 const double rq = den > 0.0 ? num / den : 0.0;
                 double res = 0.0;
-    #pragma unroll
+#pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const double t = yv[m] - rq * xv[q][m];
                     res = fma(t, t, res);
@@ -645,7 +645,7 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
         static_assert(kTriThreads == 16 * kTriMaxR, "one team of 16 lanes per vector");
         const int bvj = tid >> 4, bs = tid & 15;
         double xb[8];
-    #pragma unroll
+#pragma unroll
         for (int m = 0; m < 8; ++m) xb[m] = L[kTriX + 32 * (bs + 16 * m) + bvj];
         __syncthreads();
         __threadfence_block();
@@ -653,31 +653,32 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
             double* V = L + kTriX;
             // (unrolled, so that the loads of several trips are in flight together: one trip at a time, each of the 16
             // trips waits out a whole global-memory round trip)
-    #pragma unroll 8
+#pragma unroll 8
             for (int e = tid * 2; e < (kTriN - 2) * kTriN; e += 2 * kTriThreads)
                 *reinterpret_cast<double2*>(V + e) = *reinterpret_cast<const double2*>(vws + e);
             __syncthreads();
             double vn[8];
-    #pragma unroll
+#pragma unroll
             for (int m = 0; m < 8; ++m) vn[m] = V[(kTriN - 3) * kTriN + bs + 16 * m];
-            for (int k = kTriN - 3; k >= 0; --k) {
+            // (a wavefront holds four vectors: one whose vectors are all padding skips the loop)
+            for (int k = 4 * wave < rb ? kTriN - 3 : -1; k >= 0; --k) {
                 const double beta = L[kTriBet + k];
                 double v[8];
-    #pragma unroll
+#pragma unroll
                 for (int m = 0; m < 8; ++m) v[m] = vn[m];
                 if (k > 0) {
-    #pragma unroll
+#pragma unroll
                     for (int m = 0; m < 8; ++m) vn[m] = V[(k - 1) * kTriN + bs + 16 * m];
                 }
                 if (beta == 0.0) continue;                    // uniform
                 double s0 = 0.0, s1 = 0.0;
-    #pragma unroll
+#pragma unroll
                 for (int m = 0; m < 8; m += 2) {
                     s0 = fma(v[m], xb[m], s0);
                     s1 = fma(v[m + 1], xb[m + 1], s1);
                 }
                 const double sc = team_sum<16>(s0 + s1) * beta;
-    #pragma unroll
+#pragma unroll
                 for (int m = 0; m < 8; ++m) xb[m] = fma(-sc, v[m], xb[m]);
             }
         }
@@ -692,12 +693,12 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
             }
             double best = -1.0, bestv = 0.0;
             int besti = kTriN;
-    #pragma unroll
+#pragma unroll
             for (int m = 0; m < 8; ++m) {
                 const double av = fabs(xb[m]);
                 if (av > best) { best = av; bestv = xb[m]; besti = bs + 16 * m; }
             }
-    #pragma unroll
+#pragma unroll
             for (int off = 8; off > 0; off >>= 1) {
                 const double ob = __shfl_xor(best, off, 64);
                 const double ov = __shfl_xor(bestv, off, 64);
@@ -707,7 +708,7 @@ __device__ __forceinline__ bool tridiag_top_eigs(const double* g, double* vws, i
             const double lam_true = fmax(lam, 0.0) * tmax * up;
             const double sc = (bestv < 0.0 ? -1.0 : 1.0) * sqrt(lam_true);
             float* dst = qhat + (joff + rank) * kTriN;
-    #pragma unroll
+#pragma unroll
             for (int m = 0; m < 8; ++m) dst[bs + 16 * m] = static_cast<float>(xb[m] * sc);
             if (eig && bs == 0) eig[joff + rank] = static_cast<float>(lam_true);
         }
