@@ -412,7 +412,8 @@ def _assert_update_matches(U, ref):
 
 @pytest.mark.parametrize("r,lam,g", [(16, 1e-3, 32), (5, 1e-3, 64), (40, 5e-4, 64), (32, 1e-3, 32), (7, 0.5, 32),
                                      (16, np.inf, 32), (60, 5e-4, 32), (128, 1e-3, 32), (16, 1e-3, 128), (16, 0.0, 32),
-                                     (0, 1e-3, 32)])
+                                     (0, 1e-3, 32), (33, 1e-3, 32), (64, 1e-2, 64), (47, 1e-3, 32), (40, np.inf, 64),
+                                     (65, 1e-3, 32)])
 def test_prepare_matches_oracle(r, lam, g):
     H = 3
     gen = synth.rng(1300 + r)
@@ -428,7 +429,7 @@ def test_prepare_matches_oracle(r, lam, g):
 
 
 @pytest.mark.parametrize("r,lam,g", [(16, 1e-3, 32), (5, 1e-3, 64), (40, 5e-4, 64), (32, 1e-3, 32), (7, 0.5, 32),
-                                     (16, np.inf, 32), (60, 5e-4, 32), (128, 1e-3, 32)])
+                                     (16, np.inf, 32), (60, 5e-4, 32), (128, 1e-3, 32), (33, 1e-3, 32), (64, 1e-2, 64)])
 def test_prepare_full_precision_matches_oracle(r, lam, g):
     """squat_prepare_ex with SQUAT_PREPARE_FULL_PRECISION: Lemma 2's matrix computed in fp64 and rounded once to
     fp32, against the oracle's float64 matrix at the accuracy that arithmetic delivers."""
