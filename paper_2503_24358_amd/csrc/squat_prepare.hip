@@ -326,16 +326,13 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
         double pmin = 1e300, pmax = 0.0;
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
-            if (RP == 64 || j < r) {                      // uniform; the rows and columns from r on are the identity already
-                                                          // (64 guarded steps make the compiler keep the row in scratch memory)
+            if (j < r) {                                  // uniform; the rows and columns from r on are the identity already
                 // column j of the trailing matrix: through the wavefront's own buffer (a wavefront's LDS accesses
                 // complete in order, so the reads see this write), read back at addresses that are the same in every lane
                 col[row] = a[j];
                 const double piv = col[j];
-                if (j < r) {
-                    pmin = fmin(pmin, piv);
-                    pmax = fmax(pmax, piv);
-                }
+                pmin = fmin(pmin, piv);
+                pmax = fmax(pmax, piv);
                 // 1 / sqrt(pivot) without the library routines' branches (with them the compiler keeps the column's
                 // loads live across the branch and spills); two Newton steps reach the last bit
                 double y = __builtin_amdgcn_rsq(piv);
@@ -417,8 +414,7 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
         } else {
             // 64 unknowns leave room for 16 entries of the factor at a time and 16 more on their way: a step's column
             // (row) is taken in pieces of 16, the next piece (of this step or the next) fetched while one is used.
-            // (The steps from r on meet zeros and the identity; guarding them makes the compiler keep the unknowns in
-            // scratch memory.)
+            // Steps from r on meet zeros and the identity and are skipped (uniform).
             constexpr int PC = 16;
             double cur[PC], nxt[PC], dcur, dnxt = 0.0;
             // forward: y_k = b_k / C_kk, then b_i -= C_ik y_k for i > k
@@ -427,6 +423,7 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
             for (int e = 0; e < PC; ++e) cur[e] = C[(1 + e) * LD];
 #pragma unroll
             for (int k = 0; k < RP; ++k) {
+                if (k >= r) continue;                     // uniform: the unknowns from r on are zero
                 b[k] *= dcur;                             // the diagonal holds 1 / C_kk
                 if (k + 1 < RP) dnxt = C[(k + 1) * LD + k + 1];
 #pragma unroll
@@ -452,14 +449,16 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
                 }
                 dcur = dnxt;
             }
-            // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k (row k of the factor, from its start)
-            dcur = C[(RP - 1) * LD + RP - 1];
-#pragma unroll
-            for (int e = 0; e < PC; ++e) cur[e] = C[(RP - 1) * LD + e];
+            // backward: x_k = y_k / C_kk, then y_i -= C_ki x_k for i < k (row k of the factor, from its start); the
+            // first step that counts is r - 1, so every step fetches its own first piece and the later ones ahead
 #pragma unroll
             for (int k = RP - 1; k >= 0; --k) {
+                if (k >= r) continue;                     // uniform
+                dcur = C[k * LD + k];
+#pragma unroll
+                for (int e = 0; e < PC; ++e)
+                    if (e < k) cur[e] = C[k * LD + e];
                 b[k] *= dcur;
-                if (k > 0) dnxt = C[(k - 1) * LD + k - 1];
 #pragma unroll
                 for (int pc = 0; pc < RP / PC; ++pc) {
                     const int i0 = pc * PC;
@@ -468,10 +467,6 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
 #pragma unroll
                         for (int e = 0; e < PC; ++e)
                             if (i0 + PC + e < k) nxt[e] = C[k * LD + i0 + PC + e];
-                    } else if (k > 1) {
-#pragma unroll
-                        for (int e = 0; e < PC; ++e)
-                            if (e < k - 1) nxt[e] = C[(k - 1) * LD + e];
                     }
 #pragma unroll
                     for (int e = 0; e < PC; ++e)
@@ -480,7 +475,6 @@ __global__ void __launch_bounds__(kCholThreads) prepare_chol_kernel(const PrepPa
 #pragma unroll
                     for (int e = 0; e < PC; ++e) cur[e] = nxt[e];
                 }
-                dcur = dnxt;
             }
         }
         // (aliased: every lane of the wavefront is past its last read of the factor here)
