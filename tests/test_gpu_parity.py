@@ -449,15 +449,19 @@ def test_prepare_full_precision_matches_oracle(r, lam, g):
             assert not U[h][t * g:(t + 1) * g, t * g:].any()
 
 
-def test_prepare_mixed_conditioning_picks_the_route_per_head():
-    """r <= 32, finite lambda: heads whose S = I / lambda + Qr Qr^T is well conditioned take the Cholesky
+@pytest.mark.parametrize("r,g", [(20, 32), (44, 32), (64, 64)])
+def test_prepare_mixed_conditioning_picks_the_route_per_head(r, g):
+    """r <= 64, finite lambda: heads whose S = I / lambda + Qr Qr^T is well conditioned take the Cholesky
     route (large rows of full rank, or zero rows at ordinary scale); a head with zero rows AND lambda *
-    sigma^2 ~ 1e12 (eigenvalues 1 / lambda next to sigma^2) is flagged and redone by the eigen route.  All
-    must match the oracle; the flags live in the last 256-byte-aligned block of the workspace."""
-    H, r, g, lam = 4, 20, 32, 50.0
+    sigma^2 ~ 1e12 (eigenvalues 1 / lambda next to sigma^2) is flagged and redone by the eigen route (the
+    one-wavefront kernel up to r = 32, the workgroup-per-panel kernel beyond).  All must match the oracle;
+    the flags live in the last 256-byte-aligned block of the workspace."""
+    H, lam = 4, 50.0
     gen = synth.rng(1450)
     Qh = gen.standard_normal((H, r, 128)).astype(np.float32)
-    Qh[0] *= 3e4                              # large but of full row rank
+    # large but of full row rank in every panel (with more directions than the last panel has channels left the
+    # problem itself is singular to 1 / (lambda sigma^2): a scale at which float64 still resolves it)
+    Qh[0] *= 3e4 if r <= 128 - (128 // g - 1) * g else 300.0
     Qh[1] *= 3e4                              # lambda sigma^2 ~ 50 * 9e8 * 100 ...
     Qh[1, 8:] = 0.0                           # ... next to 1 / lambda
     Qh[2, 8:] = 0.0                           # rank 8
