@@ -515,7 +515,7 @@ def test_chained_path_end_to_end():
     assert (got != want).mean() <= 1e-4
 
 
-@pytest.mark.parametrize("planted,r", [(12, 8), (0, 16)])
+@pytest.mark.parametrize("planted,r", [(12, 8), (0, 16), (0, 40), (12, 60)])
 @pytest.mark.parametrize("full_precision", [True, False])
 def test_gpu_chain_against_the_oracles_own_chain(planted, r, full_precision, record_property):
     """The distance between the two CHAINS, nothing handed over: the GPU goes queries, keys -> Qhat -> U -> codes
@@ -561,7 +561,10 @@ def test_gpu_chain_against_the_oracles_own_chain(planted, r, full_precision, rec
     print("chain vs chain: planted=%d r=%d full_precision=%s codes differing %.3e (keys %.3e), projected error energy "
           "gpu/oracle %.5f, oracle/rtn %.4f" % (planted, r, full_precision, frac, keys_diff / (H * n), e_gpu / e_or, e_or / e_rtn))
     assert abs(e_gpu / e_or - 1.0) <= 1e-2
-    assert e_gpu < 0.5 * e_rtn
+    # (the gain over round-to-nearest shrinks as r takes in more of a flat spectrum: 0.35-0.39 of its energy at r = 8
+    # and 16, 0.55 at r = 40 on near-isotropic queries; the oracle's chain says the same)
+    assert e_gpu < (0.5 if r <= 16 else 0.75) * e_rtn
     # free-running distance: with U in full precision on well-separated spectra the chains agree to the budget
     # of the stage-by-stage tests (roots and their cascades); the fp16 grid costs a few 1e-4 of the codes
-    assert frac <= (1e-3 if not (full_precision and planted) else 3e-4), frac
+    # (well separated: r inside the planted directions)
+    assert frac <= (3e-4 if full_precision and 0 < r <= planted else 1e-3), frac
